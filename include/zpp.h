@@ -1,0 +1,182 @@
+/*
+ * zpp.h — C ABI of the ZeroPP stage hot path on one MI355X (gfx950).
+ *
+ * What one GPU does under the ZeroPP schedule (paper Section 3.1 "ZeRO-compatible pipeline
+ * parallelism" and Section 3.2 "ZeRO-3 + PP + DP"): the micro-batches of a pipeline stage run
+ * back to back inside a scheduling unit of U micro-batches, so that the stage's parameters are
+ * gathered once per unit (not once per micro-batch), its gradients are reduced once per unit, and
+ * the optimizer step runs on the local partition of the model state.  With one GPU the gather is
+ * a local cast/copy out of the flat fp32 master shard and the reduce-scatter is a local
+ * accumulation into the flat fp32 gradient shard.
+ *
+ * Conventions
+ *   - Every pointer named P, G, M, V, workspace, x, y, dy, dx is DEVICE memory owned by the caller.
+ *     The library allocates no device memory, creates no streams and never synchronises; all work
+ *     is enqueued on the `hip_stream` argument (a hipStream_t passed as void*, NULL = default
+ *     stream).  Handles hold host metadata only.
+ *   - Tensors are row-major.  Activations are [T, h] with T = micro_batch * seq tokens and the
+ *     hidden axis contiguous; samples of a micro-batch are consecutive blocks of `seq` rows.
+ *   - Activation element type: float when compute_dtype = ZPP_DTYPE_FP32, bf16 (upper half of an
+ *     IEEE float, 2 bytes) when compute_dtype = ZPP_DTYPE_BF16.  P, G, M, V are always float.
+ *   - Device pointers must be 256-byte aligned.
+ *   - Every call returns a zpp_status; 0 is success.  Argument, state and alignment errors are
+ *     found on the host before anything is launched.  zpp_last_error() returns a thread-local
+ *     message for the last failing call.  No C++ exception crosses this boundary.
+ *
+ * Flat parameter layout (shared by P, G, M, V, the working copy and the staging gradients): blocks
+ * concatenated without padding; inside a block, in this order, each matrix [out_features,
+ * in_features] row-major so that y = x W^T + b:
+ *   GPT   (arch 0): ln1.gamma[h] ln1.beta[h] attn.wqkv[3h,h] attn.bqkv[3h] attn.wo[h,h] attn.bo[h]
+ *                   ln2.gamma[h] ln2.beta[h] mlp.w1[f,h] mlp.b1[f] mlp.w2[h,f] mlp.b2[h]
+ *   LLaMA (arch 1): norm1.gamma[h] attn.wqkv[3h,h] attn.wo[h,h] norm2.gamma[h]
+ *                   mlp.wgate[f,h] mlp.wup[f,h] mlp.wdown[h,f]
+ * Rows of wqkv: all of Q (head n = rows n*d .. (n+1)*d-1), then K, then V.  A GPT block holds
+ * 4h^2 + 2hf + 9h + f parameters, i.e. the "around 12 h^2" of Section 4.1 when f = 4h.
+ */
+#ifndef ZPP_H
+#define ZPP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct zpp_stage zpp_stage; /* opaque; host-side metadata only */
+
+typedef enum {
+    ZPP_OK = 0,
+    ZPP_ERR_ARG = -1,         /* null pointer, out-of-range index, inconsistent configuration */
+    ZPP_ERR_STATE = -2,       /* call out of order (see the state machine below) */
+    ZPP_ERR_ALIGN = -3,       /* device pointer not 256-byte aligned */
+    ZPP_ERR_WORKSPACE = -4,   /* workspace smaller than zpp_stage_workspace_bytes() */
+    ZPP_ERR_DEVICE = -5,      /* a kernel launch or HIP call failed */
+    ZPP_ERR_UNSUPPORTED = -6  /* shape outside what the kernels support */
+} zpp_status;
+
+enum { ZPP_ARCH_GPT = 0, ZPP_ARCH_LLAMA = 1 };
+enum { ZPP_DTYPE_FP32 = 0, ZPP_DTYPE_BF16 = 1 };
+enum { ZPP_GELU_TANH = 0, ZPP_GELU_ERF = 1 };
+
+typedef struct {
+    int32_t arch;          /* ZPP_ARCH_GPT: pre-LN LayerNorm, biases, GeLU MLP.
+                              ZPP_ARCH_LLAMA: RMSNorm, rotary embedding on Q and K, SwiGLU MLP, no biases */
+    int32_t n_blocks;      /* transformer blocks in the stage ("contiguous network layers", Section 2.1) */
+    int32_t hidden;        /* h */
+    int32_t n_heads;       /* head dim d = h / n_heads */
+    int32_t ffn;           /* f, MLP width */
+    int32_t seq;           /* s */
+    int32_t micro_batch;   /* b, samples per micro-batch */
+    int32_t unit_mbs;      /* U, micro-batches per scheduling unit (Section 3.1.2) */
+    int32_t compute_dtype; /* ZPP_DTYPE_FP32: everything float.  ZPP_DTYPE_BF16: bf16 working copy and
+                              activations, fp32 master / gradients / moments, fp32 accumulation */
+    int32_t gelu_mode;     /* ZPP_GELU_TANH (default) or ZPP_GELU_ERF */
+    float norm_eps;        /* epsilon inside the norm's square root */
+    float rope_base;       /* rotary base (LLaMA only); angle = position * base^(-2i/d), adjacent pairs */
+} zpp_stage_config;
+
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    float grad_scale;      /* ghat = grad_scale * G */
+    int32_t step;          /* t >= 1, used for bias correction */
+    int32_t decoupled_wd;  /* 1: p -= lr*wd*p_old (AdamW form).  0: ghat += wd*p (L2 form) */
+    int32_t zero_grad;     /* 1: G is zeroed in the same pass */
+} zpp_adam;
+
+/* ---- handle, sizes, layout (host only; no device is touched) -------------------------------- */
+
+/* Validates the configuration (positive sizes, hidden divisible by n_heads, shapes the kernels
+ * support) and creates a handle.  Errors: ZPP_ERR_ARG, ZPP_ERR_UNSUPPORTED. */
+zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out);
+void zpp_stage_destroy(zpp_stage *stage);
+
+/* N, the number of parameters of the stage = elements of each of P, G, M, V. */
+uint64_t zpp_stage_param_count(const zpp_stage *stage);
+
+/* Bytes of caller-owned device workspace the stage needs: the materialised working copy of the
+ * stage (one gathered stage, the L*M_w/(P*V) term of the memory formula in Section 4.2), the
+ * fp32 staging buffer for one micro-batch's weight gradients, the activation stash of one
+ * scheduling unit (the min(B,U)*L*M_a/P term; linear in unit_mbs) and per-call temporaries. */
+uint64_t zpp_stage_workspace_bytes(const zpp_stage *stage);
+
+/* Number of tensors in the flat layout, and the idx-th entry.  `name` points into the handle and
+ * stays valid until zpp_stage_destroy.  offset is in elements. */
+int32_t zpp_stage_layout_size(const zpp_stage *stage);
+zpp_status zpp_stage_param_layout(const zpp_stage *stage, int32_t idx, const char **name,
+                                  uint64_t *offset, uint64_t *rows, uint64_t *cols);
+
+/* Binds caller-owned device memory.  P: fp32 master parameters [N]; G: fp32 gradient accumulator
+ * [N] (the caller zeroes it before a training step, or uses zpp_adam.zero_grad); M, V: fp32 Adam
+ * moments [N]; workspace: at least zpp_stage_workspace_bytes() bytes.  All 256-byte aligned.
+ * May be called again to re-bind; resets the state machine. */
+zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float *V, void *workspace,
+                          uint64_t workspace_bytes);
+
+/* ---- the hot path ----------------------------------------------------------------------------
+ *
+ * State machine (from the task order of Section 3.1.1: forward pass, input/weight gradient
+ * computation, optimizer step; and Section 3.2: gather -> U micro-batches -> reduce):
+ *   bind -> stage_materialize_params -> stage_forward(mb) once per mb in [0,U), any order
+ *        -> stage_backward(mb) only after stage_forward(mb), once
+ *        -> stage_accumulate_grads(mb) only after stage_backward(mb), once; because the staging
+ *           buffer is reused, stage_backward of another micro-batch before that is ZPP_ERR_STATE
+ *        -> shard_adam_step only when no micro-batch is backward-done but not accumulated
+ *        -> zpp_stage_end_unit, after which the next unit starts with forward (the working copy
+ *           stays valid until P changes; after shard_adam_step without write-back a new
+ *           stage_materialize_params is required).
+ */
+
+/* Stand-in for the per-unit parameter all-gather of Section 3.2: produces the working copy of the
+ * whole stage from the flat fp32 master shard P (bf16 round-to-nearest-even cast, or a float
+ * copy).  Idempotent; may be called again before the backward phase, mirroring the paper's second
+ * gather, without changing results. */
+zpp_status stage_materialize_params(zpp_stage *stage, void *hip_stream);
+
+/* One micro-batch through all blocks of the stage (the forward task of Section 3.1.1).  Per block:
+ * x1 = x + Attn(Norm1(x)); y = x1 + MLP(Norm2(x1)), causal attention, no dropout.  x, y: [T, h]
+ * in the activation element type; x is only read during the call's enqueued work, y is written.
+ * What backward needs is kept in the unit's activation stash, slot `micro_batch`. */
+zpp_status stage_forward(zpp_stage *stage, int32_t micro_batch, const void *x, void *y, void *hip_stream);
+
+/* Input-gradient and weight-gradient tasks of one micro-batch, fused (Sections 2.3 and 3.1.1): for
+ * every linear layer dX = dY.W and dW = dY^T.X.  dy: gradient w.r.t. the stage output [T, h];
+ * dx: gradient w.r.t. the stage input [T, h] (written).  The micro-batch's weight gradients g_mb
+ * are written to the fp32 staging buffer (parameter layout) inside the workspace. */
+zpp_status stage_backward(zpp_stage *stage, int32_t micro_batch, const void *dy, void *dx, void *hip_stream);
+
+/* Stand-in for the per-unit gradient reduce-scatter of Section 3.2: G <- G + scale * g_mb over the
+ * whole flat shard. */
+zpp_status stage_accumulate_grads(zpp_stage *stage, int32_t micro_batch, float scale, void *hip_stream);
+
+/* The optimizer-step task (Section 3.1.1; Section 3.2.2 "update the parameters corresponding to the
+ * partitioned optimizer states"): Adam on elements [offset, offset+count) of P, M, V using G.
+ *   ghat = grad_scale*G (+ wd*p in L2 form); m <- b1 m + (1-b1) ghat; v <- b2 v + (1-b2) ghat^2;
+ *   p <- p - lr*( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd*p_old [decoupled form] ).
+ * offset and count must be multiples of 4 elements except that offset+count may equal N.
+ * Marks the working copy stale. */
+zpp_status shard_adam_step(zpp_stage *stage, uint64_t offset, uint64_t count, const zpp_adam *hp,
+                           void *hip_stream);
+
+/* Releases the unit's activation stash slots ("memory allocated by each scheduling unit is released
+ * before the next scheduling unit begins", Section 3.1.2) and resets the per-micro-batch states. */
+zpp_status zpp_stage_end_unit(zpp_stage *stage);
+
+/* ---- introspection (tests, benchmarks) ------------------------------------------------------- */
+
+/* Number of times stage_materialize_params ran and bytes it read+wrote, since create. */
+void zpp_stage_counters(const zpp_stage *stage, uint64_t *materialize_calls, uint64_t *materialize_bytes);
+
+/* Device address and size of a named region inside the bound workspace:
+ *   "W" working copy, "S" staging gradients; stash tensors of (micro_batch, block) by name, e.g.
+ *   "x", "n1", "qkv", "attn", "lse", "x1", "n2", "u", "g".  elem_bytes is 2 or 4.
+ * Errors: ZPP_ERR_STATE before bind, ZPP_ERR_ARG for an unknown name or index. */
+zpp_status zpp_stage_region(const zpp_stage *stage, const char *name, int32_t micro_batch, int32_t block,
+                            void **ptr, uint64_t *elems, int32_t *elem_bytes);
+
+const char *zpp_last_error(void);
+const char *zpp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZPP_H */

@@ -1,0 +1,47 @@
+/*
+ * zpp_ops.h — operator-level entry points of the same library, for per-kernel parity tests and
+ * micro-benchmarks.  They launch exactly the kernels the stage calls in zpp.h use.  All pointers
+ * are DEVICE pointers owned by the caller; work is enqueued on `hip_stream`; nothing allocates or
+ * synchronises.  Errors are reported as in zpp.h.
+ */
+#ifndef ZPP_OPS_H
+#define ZPP_OPS_H
+
+#include "zpp.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* bf16 MFMA GEMM with fp32 accumulation: C[M,N] = A[M,K] . B[N,K]^T (+ bias[n]) (+ resid[m,n]).
+ * This is the shape of every linear layer of the transformer block (Section 4.1) and, with
+ * transposed operands, of the input- and weight-gradient products of Section 2.3.
+ * A, B: bf16, K-contiguous, leading dimensions lda, ldb (elements, multiples of 8); K % 64 == 0.
+ * C: bf16, or float when out_f32 != 0; leading dimension ldc.  bias, resid: bf16 or NULL.
+ * variant: -1 automatic, 0..3 force a tile shape (256x256/8 waves, 128x256, 128x128, 256x256/4 waves). */
+zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
+                               int32_t out_f32, int32_t variant, void *hip_stream);
+
+/* Causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each; T = b*seq, h = nh*d):
+ * attn[T, h] = softmax(Q K^T / sqrt(d) + causal mask) V per (sample, head); lse[b, nh, seq] is the
+ * log-sum-exp of the scaled, masked scores.  dtype: ZPP_DTYPE_*; impl 0 = generic kernel,
+ * 1 = MFMA kernel (bf16, d = 128, seq % 128 == 0). */
+zpp_status zpp_op_attention_fwd(int32_t dtype, int32_t impl, const void *qkv, void *attn, float *lse, int64_t b,
+                                int64_t seq, int64_t nh, int64_t d, void *hip_stream);
+
+/* Backward of the above: dqkv[T, 3h] = (dQ | dK | dV) from dattn[T, h]; delta[b, nh, seq] is scratch. */
+zpp_status zpp_op_attention_bwd(int32_t dtype, int32_t impl, const void *qkv, const void *attn, const void *dattn,
+                                const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh,
+                                int64_t d, void *hip_stream);
+
+/* The flat-buffer passes on raw arrays of n elements (16-byte aligned): the optimizer step, the
+ * gradient accumulation G += scale*S, and the fp32 -> working-copy cast. */
+zpp_status zpp_op_flat_adam(float *P, float *M, float *V, float *G, uint64_t n, const zpp_adam *hp, void *hip_stream);
+zpp_status zpp_op_flat_accumulate(float *G, const float *S, uint64_t n, float scale, void *hip_stream);
+zpp_status zpp_op_flat_materialize(const float *P, void *W, uint64_t n, int32_t dtype, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZPP_OPS_H */

@@ -670,35 +670,53 @@ struct Stage {
         for (int64_t i = 0; i < (int64_t)N; ++i) G[i] = G[i] + scale * S[i];
     }
 
-    // Adam on elements [offset, offset+count) of the flat shard, t = step >= 1, ghat = grad_scale*G:
-    //   m <- b1 m + (1-b1) ghat ; v <- b2 v + (1-b2) ghat^2 ; mhat = m/(1-b1^t) ; vhat = v/(1-b2^t)
-    //   decoupled: p <- p - lr (mhat/(sqrt(vhat)+eps) + wd p_old) ; L2 form: ghat += wd p first.
+    // Adam on elements [offset, offset+count) of the flat shard; see adam_range below.
     void adam(uint64_t offset, uint64_t count, double lr, double beta1, double beta2, double eps,
-              double wd, double grad_scale, int step, int decoupled, int zero_grad)
-    {
-        const R b1 = (R)beta1, b2 = (R)beta2;
-        // 1-beta is formed in double from the given hyper-parameters, then rounded once
-        const R omb1 = (R)(1.0 - beta1), omb2 = (R)(1.0 - beta2);
-        const R c1 = (R)(1.0 - std::pow(beta1, (double)step));
-        const R c2 = (R)(1.0 - std::pow(beta2, (double)step));
-#pragma omp parallel for schedule(static)
-        for (int64_t i = (int64_t)offset; i < (int64_t)(offset + count); ++i) {
-            R g = (R)grad_scale * G[i];
-            const R p = P[i];
-            if (!decoupled) g += (R)wd * p;
-            const R m = b1 * M[i] + omb1 * g;
-            const R v = b2 * V[i] + omb2 * g * g;
-            const R mhat = m / c1;
-            const R vhat = v / c2;
-            R upd = mhat / (std::sqrt(vhat) + (R)eps);
-            if (decoupled) upd += (R)wd * p;
-            P[i] = p - (R)lr * upd;
-            M[i] = m;
-            V[i] = v;
-            if (zero_grad) G[i] = 0;
-        }
-    }
+              double wd, double grad_scale, int step, int decoupled, int zero_grad);
 };
+
+// Adam, t = step >= 1, ghat = grad_scale*G:
+//   m <- b1 m + (1-b1) ghat ; v <- b2 v + (1-b2) ghat^2 ; mhat = m/(1-b1^t) ; vhat = v/(1-b2^t)
+//   decoupled: p <- p - lr (mhat/(sqrt(vhat)+eps) + wd p_old) ; L2 form: ghat += wd p first.
+// Every operation is rounded on its own (no fused multiply-add), so the result is the plain
+// left-to-right evaluation of the formulas above in the working precision.
+template <class R>
+__attribute__((optimize("fp-contract=off"))) void adam_range(R *P, R *M, R *V, R *G, int64_t begin,
+                                                             int64_t end, double lr, double beta1,
+                                                             double beta2, double eps, double wd,
+                                                             double grad_scale, int step, int decoupled,
+                                                             int zero_grad)
+{
+    const R b1 = (R)beta1, b2 = (R)beta2;
+    // 1-beta is formed in double from the given hyper-parameters, then rounded once
+    const R omb1 = (R)(1.0 - beta1), omb2 = (R)(1.0 - beta2);
+    const R c1 = (R)(1.0 - std::pow(beta1, (double)step));
+    const R c2 = (R)(1.0 - std::pow(beta2, (double)step));
+#pragma omp parallel for schedule(static)
+    for (int64_t i = begin; i < end; ++i) {
+        R g = (R)grad_scale * G[i];
+        const R p = P[i];
+        if (!decoupled) g = g + (R)wd * p;
+        const R m = b1 * M[i] + omb1 * g;
+        const R v = b2 * V[i] + (omb2 * g) * g;
+        const R mhat = m / c1;
+        const R vhat = v / c2;
+        R upd = mhat / (std::sqrt(vhat) + (R)eps);
+        if (decoupled) upd = upd + (R)wd * p;
+        P[i] = p - (R)lr * upd;
+        M[i] = m;
+        V[i] = v;
+        if (zero_grad) G[i] = 0;
+    }
+}
+
+template <class R>
+void Stage<R>::adam(uint64_t offset, uint64_t count, double lr, double beta1, double beta2, double eps,
+                    double wd, double grad_scale, int step, int decoupled, int zero_grad)
+{
+    adam_range<R>(P.data(), M.data(), V.data(), G.data(), (int64_t)offset, (int64_t)(offset + count), lr,
+                  beta1, beta2, eps, wd, grad_scale, step, decoupled, zero_grad);
+}
 
 template <class R>
 R *buffer_ptr(Stage<R> *s, int which)

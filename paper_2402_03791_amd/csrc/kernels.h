@@ -1,0 +1,95 @@
+// Internal host-side launch API of the gfx950 kernels.  Everything is enqueued on the given
+// stream; nothing allocates or synchronises.  Pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zpp {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { NORM_LAYER = 0, NORM_RMS = 1 };
+enum { COLRED_SUM = 0, COLRED_LAYERNORM = 1, COLRED_RMSNORM = 2 };
+enum { ACT_NONE = 0, ACT_GELU_DUAL = 1, ACT_DGELU_MUL = 2 };
+
+inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+struct AdamArgs {
+    float lr, beta1, beta2, eps, wd, grad_scale;
+    float omb1, omb2;  // 1-beta1, 1-beta2, formed in double on the host and rounded once
+    float c1, c2;      // bias corrections 1-beta1^t, 1-beta2^t
+    int decoupled, zero_grad;
+};
+
+// Epilogue of a GEMM: out = act(acc + bias[n] + resid[m,n]).
+struct GemmEpi {
+    const void *bias = nullptr;   // [N], element type of the compute dtype, or null
+    const void *resid = nullptr;  // [M, ldc], element type of the compute dtype, or null
+    void *out2 = nullptr;         // ACT_GELU_DUAL: receives gelu(out) while C receives out
+    const void *aux = nullptr;    // ACT_DGELU_MUL: pre-activation u[m,n]; out = acc * gelu'(u)
+    int act = ACT_NONE;
+    int gelu_mode = 0;
+    int out_f32 = 0;              // 1: C is float regardless of the compute dtype (weight gradients)
+};
+
+// ---- flat-buffer passes (HBM bound) ----
+hipError_t launch_materialize(const float *P, void *W, uint64_t n, int dt, hipStream_t s);
+// Wt[c, r] = bf16(P[r, c]) for a [rows, cols] matrix
+hipError_t launch_transpose_cast(const float *P, void *Wt, uint64_t rows, uint64_t cols, hipStream_t s);
+hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s);
+hipError_t launch_adam(float *P, float *M, float *V, float *G, uint64_t n, const AdamArgs &a, hipStream_t s);
+
+// ---- norms ----
+// n = gamma * xhat (+ beta); mean (LayerNorm only) and rstd are saved; xcopy (nullable) receives x.
+hipError_t launch_norm_fwd(int dt, int kind, const void *x, const void *gamma, const void *beta, int64_t T,
+                           int64_t h, float eps, void *n, float *mean, float *rstd, void *xcopy,
+                           hipStream_t s);
+// dx = resid + d(norm)/dx
+hipError_t launch_norm_bwd(int dt, int kind, const void *dn, const void *x, const float *mean,
+                           const float *rstd, const void *gamma, const void *resid, void *dx, int64_t T,
+                           int64_t h, hipStream_t s);
+// Column reductions over T rows of a [T, C] matrix with row stride ld:
+//   COLRED_SUM: out0[c] = sum_t a[t,c]
+//   COLRED_LAYERNORM: out0[c] = sum_t a[t,c]*(x[t,c]-mean[t])*rstd[t], out1[c] = sum_t a[t,c]
+//   COLRED_RMSNORM:   out0[c] = sum_t a[t,c]*x[t,c]*rstd[t]
+// partial: scratch of colreduce_scratch_floats(T, C) floats.
+uint64_t colreduce_scratch_floats(int64_t T, int64_t C);
+hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
+                            const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
+                            float *partial, hipStream_t s);
+
+// ---- elementwise ----
+// out[c, r] = in[r, c]; in has row stride ld_in, out row stride ld_out (elements)
+hipError_t launch_transpose(int dt, const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
+                            int64_t ld_out, hipStream_t s);
+// table[p, i] = (cos, sin)(p * base^(-2i/d)), p < seq, i < d/2
+hipError_t launch_rope_table(float *table, int64_t seq, int64_t d, double base, hipStream_t s);
+// rotates the Q and K parts of qkv[T, 3h] in place; sign = +1 forward, -1 inverse
+hipError_t launch_rope(int dt, void *qkv, const float *table, int64_t T, int64_t seq, int64_t nh, int64_t d,
+                       int sign, hipStream_t s);
+// gu = [gate | up] of shape [T, 2f]; act[T, f] = silu(gate) * up
+hipError_t launch_swiglu_fwd(int dt, const void *gu, void *act, int64_t T, int64_t f, hipStream_t s);
+hipError_t launch_swiglu_bwd(int dt, const void *gu, const void *dact, void *dgu, int64_t T, int64_t f,
+                             hipStream_t s);
+
+// ---- GEMMs ----
+// Generic strided fp32 GEMM: C[m,n] = sum_k A[m*sam + k*sak] * B[n*sbn + k*sbk], then the epilogue.
+hipError_t launch_gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int64_t sam, int64_t sak,
+                           const float *B, int64_t sbn, int64_t sbk, float *C, int64_t ldc,
+                           const GemmEpi &epi, hipStream_t s);
+// bf16 MFMA GEMM, both operands K-contiguous: C[M,N] = A[M,K] . B[N,K]^T with fp32 accumulation.
+// Requires K % 64 == 0, lda/ldb % 8 == 0, 16-byte aligned bases.
+hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
+bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
+
+// ---- causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each) ----
+// attn[T, h] (heads merged), lse[b, nh, s] = log-sum-exp of the scaled masked scores.
+hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int64_t b, int64_t seq,
+                           int64_t nh, int64_t d, hipStream_t s);
+// delta[b, nh, s] = sum_e dattn*attn is scratch; dqkv[T, 3h] receives dQ | dK | dV.
+hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void *dattn, const float *lse,
+                           float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh, int64_t d,
+                           hipStream_t s);
+bool attn_mfma_supported(int64_t seq, int64_t d);
+
+}  // namespace zpp

@@ -1,0 +1,244 @@
+// LayerNorm / RMSNorm forward and backward, and the column reductions that give the gradients of
+// gains, offsets and biases.  One wavefront per row with wave-level reductions; statistics and all
+// arithmetic in fp32, storage in the compute dtype.  HBM bound.
+#include "device_utils.h"
+#include "kernels.h"
+
+namespace zpp {
+
+constexpr int kRowsPerBlock = 4;  // 4 waves of 64 lanes
+
+// ------------------------------------------------------------------ forward
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
+                                                       const T *__restrict__ beta, int64_t rows, int64_t h,
+                                                       float eps, T *__restrict__ n, float *__restrict__ mean,
+                                                       float *__restrict__ rstd, T *__restrict__ xcopy)
+{
+    constexpr int VN = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const T *xr = x + row * h;
+    const int64_t nv = h / VN;
+    float mu = 0.0f;
+    if (KIND == NORM_LAYER) {
+        float s = 0.0f;
+        for (int64_t c = lane; c < nv; c += 64) {
+            const Vec16<T> v = load16(xr + c * VN);
+#pragma unroll
+            for (int k = 0; k < VN; ++k) s += v.get(k);
+        }
+        mu = wave_sum(s) / (float)h;
+    }
+    float q = 0.0f;
+    for (int64_t c = lane; c < nv; c += 64) {
+        const Vec16<T> v = load16(xr + c * VN);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+            const float dlt = v.get(k) - mu;
+            q += dlt * dlt;
+        }
+    }
+    const float var = wave_sum(q) / (float)h;
+    const float rs = 1.0f / sqrtf(var + eps);
+    if (lane == 0) {
+        if (mean) mean[row] = mu;
+        rstd[row] = rs;
+    }
+    for (int64_t c = lane; c < nv; c += 64) {
+        const Vec16<T> v = load16(xr + c * VN);
+        const Vec16<T> g = load16(gamma + c * VN);
+        Vec16<T> o;
+        if (KIND == NORM_LAYER) {
+            const Vec16<T> b = load16(beta + c * VN);
+#pragma unroll
+            for (int k = 0; k < VN; ++k) o.set(k, g.get(k) * ((v.get(k) - mu) * rs) + b.get(k));
+        } else {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) o.set(k, g.get(k) * (v.get(k) * rs));
+        }
+        store16(n + row * h + c * VN, o);
+        if (xcopy) store16(xcopy + row * h + c * VN, v);
+    }
+}
+
+hipError_t launch_norm_fwd(int dt, int kind, const void *x, const void *gamma, const void *beta, int64_t T,
+                           int64_t h, float eps, void *n, float *mean, float *rstd, void *xcopy,
+                           hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    const dim3 grid((unsigned)((T + kRowsPerBlock - 1) / kRowsPerBlock));
+#define ZPP_LAUNCH(TT, KK)                                                                               \
+    norm_fwd_kernel<TT, KK><<<grid, 256, 0, s>>>((const TT *)x, (const TT *)gamma, (const TT *)beta, T, h, \
+                                                 eps, (TT *)n, mean, rstd, (TT *)xcopy)
+    if (dt == DT_BF16) {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(bf16, NORM_LAYER); else ZPP_LAUNCH(bf16, NORM_RMS);
+    } else {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(float, NORM_LAYER); else ZPP_LAUNCH(float, NORM_RMS);
+    }
+#undef ZPP_LAUNCH
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ backward (row part)
+// ghat = dn*gamma; LayerNorm: dx = (ghat - mean(ghat) - xhat*mean(ghat*xhat))*rstd
+//                  RMSNorm:   dx = (ghat - xhat*mean(ghat*xhat))*rstd          (+ resid)
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dn, const T *__restrict__ x,
+                                                       const float *__restrict__ mean,
+                                                       const float *__restrict__ rstd,
+                                                       const T *__restrict__ gamma, const T *__restrict__ resid,
+                                                       T *__restrict__ dx, int64_t rows, int64_t h)
+{
+    constexpr int VN = Vec16<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int64_t nv = h / VN;
+    const float mu = (KIND == NORM_LAYER) ? mean[row] : 0.0f;
+    const float rs = rstd[row];
+    float s1 = 0.0f, s2 = 0.0f;
+    for (int64_t c = lane; c < nv; c += 64) {
+        const Vec16<T> d = load16(dn + row * h + c * VN);
+        const Vec16<T> v = load16(x + row * h + c * VN);
+        const Vec16<T> g = load16(gamma + c * VN);
+#pragma unroll
+        for (int k = 0; k < VN; ++k) {
+            const float gh = d.get(k) * g.get(k);
+            s1 += gh;
+            s2 += gh * ((v.get(k) - mu) * rs);
+        }
+    }
+    const float m1 = (KIND == NORM_LAYER) ? wave_sum(s1) / (float)h : 0.0f;
+    const float m2 = wave_sum(s2) / (float)h;
+    for (int64_t c = lane; c < nv; c += 64) {
+        const Vec16<T> d = load16(dn + row * h + c * VN);
+        const Vec16<T> v = load16(x + row * h + c * VN);
+        const Vec16<T> g = load16(gamma + c * VN);
+        Vec16<T> o;
+        if (resid) {
+            const Vec16<T> r = load16(resid + row * h + c * VN);
+#pragma unroll
+            for (int k = 0; k < VN; ++k) {
+                const float xh = (v.get(k) - mu) * rs;
+                o.set(k, r.get(k) + (d.get(k) * g.get(k) - m1 - xh * m2) * rs);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < VN; ++k) {
+                const float xh = (v.get(k) - mu) * rs;
+                o.set(k, (d.get(k) * g.get(k) - m1 - xh * m2) * rs);
+            }
+        }
+        store16(dx + row * h + c * VN, o);
+    }
+}
+
+hipError_t launch_norm_bwd(int dt, int kind, const void *dn, const void *x, const float *mean,
+                           const float *rstd, const void *gamma, const void *resid, void *dx, int64_t T,
+                           int64_t h, hipStream_t s)
+{
+    if (T == 0) return hipSuccess;
+    const dim3 grid((unsigned)((T + kRowsPerBlock - 1) / kRowsPerBlock));
+#define ZPP_LAUNCH(TT, KK)                                                                              \
+    norm_bwd_kernel<TT, KK><<<grid, 256, 0, s>>>((const TT *)dn, (const TT *)x, mean, rstd,             \
+                                                 (const TT *)gamma, (const TT *)resid, (TT *)dx, T, h)
+    if (dt == DT_BF16) {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(bf16, NORM_LAYER); else ZPP_LAUNCH(bf16, NORM_RMS);
+    } else {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(float, NORM_LAYER); else ZPP_LAUNCH(float, NORM_RMS);
+    }
+#undef ZPP_LAUNCH
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ column reductions
+// Stage 1: grid (ceil(C/64), RC); a block reduces kColRows rows x 64 columns to one partial row.
+// Stage 2: sums the RC partial rows in a fixed order, so results are run-to-run identical.
+constexpr int kColRows = 128;
+
+uint64_t colreduce_scratch_floats(int64_t T, int64_t C)
+{
+    const int64_t rc = (T + kColRows - 1) / kColRows;
+    return (uint64_t)(2 * rc * C);
+}
+
+template <class T, int MODE>
+__global__ __launch_bounds__(256) void colreduce_stage1(const T *__restrict__ a, const T *__restrict__ x,
+                                                        const float *__restrict__ mean,
+                                                        const float *__restrict__ rstd, int64_t rows, int64_t C,
+                                                        int64_t ld, float *__restrict__ partial)
+{
+    __shared__ float red0[4][64];
+    __shared__ float red1[4][64];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + tx;
+    const int64_t r0 = (int64_t)blockIdx.y * kColRows;
+    const int64_t r1 = (r0 + kColRows < rows) ? r0 + kColRows : rows;
+    float s0 = 0.0f, s1 = 0.0f;
+    if (c < C) {
+        for (int64_t r = r0 + ty; r < r1; r += 4) {
+            const float av = to_f32(a[r * ld + c]);
+            if (MODE == COLRED_SUM) {
+                s0 += av;
+            } else if (MODE == COLRED_LAYERNORM) {
+                s0 += av * ((to_f32(x[r * ld + c]) - mean[r]) * rstd[r]);
+                s1 += av;
+            } else {
+                s0 += av * (to_f32(x[r * ld + c]) * rstd[r]);
+            }
+        }
+    }
+    red0[ty][tx] = s0;
+    red1[ty][tx] = s1;
+    __syncthreads();
+    if (ty == 0 && c < C) {
+        const int64_t rc = gridDim.y;
+        partial[(int64_t)blockIdx.y * C + c] = (red0[0][tx] + red0[1][tx]) + (red0[2][tx] + red0[3][tx]);
+        if (MODE == COLRED_LAYERNORM)
+            partial[(rc + blockIdx.y) * C + c] = (red1[0][tx] + red1[1][tx]) + (red1[2][tx] + red1[3][tx]);
+    }
+}
+
+__global__ __launch_bounds__(256) void colreduce_stage2(const float *__restrict__ partial, int64_t rc, int64_t C,
+                                                        float *__restrict__ out0, float *__restrict__ out1)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s0 = 0.0f, s1 = 0.0f;
+    for (int64_t r = 0; r < rc; ++r) {
+        s0 += partial[r * C + c];
+        if (out1) s1 += partial[(rc + r) * C + c];
+    }
+    out0[c] = s0;
+    if (out1) out1[c] = s1;
+}
+
+hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
+                            const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
+                            float *partial, hipStream_t s)
+{
+    if (T == 0 || C == 0) return hipSuccess;
+    const int64_t rc = (T + kColRows - 1) / kColRows;
+    const dim3 grid((unsigned)((C + 63) / 64), (unsigned)rc);
+#define ZPP_LAUNCH(TT, MM)                                                                                 \
+    colreduce_stage1<TT, MM><<<grid, 256, 0, s>>>((const TT *)a, (const TT *)x, mean, rstd, T, C, ld, partial)
+    if (dt == DT_BF16) {
+        if (mode == COLRED_SUM) ZPP_LAUNCH(bf16, COLRED_SUM);
+        else if (mode == COLRED_LAYERNORM) ZPP_LAUNCH(bf16, COLRED_LAYERNORM);
+        else ZPP_LAUNCH(bf16, COLRED_RMSNORM);
+    } else {
+        if (mode == COLRED_SUM) ZPP_LAUNCH(float, COLRED_SUM);
+        else if (mode == COLRED_LAYERNORM) ZPP_LAUNCH(float, COLRED_LAYERNORM);
+        else ZPP_LAUNCH(float, COLRED_RMSNORM);
+    }
+#undef ZPP_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    colreduce_stage2<<<(unsigned)((C + 255) / 256), 256, 0, s>>>(partial, rc, C, out0,
+                                                                 mode == COLRED_LAYERNORM ? out1 : nullptr);
+    return hipGetLastError();
+}
+
+}  // namespace zpp

@@ -1,0 +1,728 @@
+// Host side of the C ABI declared in include/zpp.h: configuration checks, the flat parameter
+// layout, the carve-up of the caller's workspace, the per-unit state machine, and the sequence of
+// kernel launches that make up materialise / forward / backward / accumulate / Adam for one
+// pipeline stage (paper Sections 3.1 and 3.2).  No device memory is allocated here.
+#include "../../include/zpp.h"
+#include "../../include/zpp_ops.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+namespace zpp {
+hipError_t launch_attn_simple_fwd(int dt, const void *qkv, void *attn, float *lse, int64_t b, int64_t seq,
+                                  int64_t nh, int64_t d, hipStream_t s);
+hipError_t launch_attn_simple_bwd(int dt, const void *qkv, const void *attn, const void *dattn,
+                                  const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq,
+                                  int64_t nh, int64_t d, hipStream_t s);
+void gemm_bf16_force_variant(int v);
+}  // namespace zpp
+
+using namespace zpp;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+zpp_status fail(zpp_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned(const void *p) { return ((uintptr_t)p % kAlign) == 0; }
+
+struct Tensor {
+    std::string name;
+    uint64_t offset, rows, cols;
+};
+
+struct Region {
+    uint64_t off = 0, elems = 0;
+    int esz = 0;
+};
+
+enum MbState { MB_IDLE = 0, MB_FWD = 1, MB_BWD = 2, MB_ACC = 3 };
+
+}  // namespace
+
+struct zpp_stage {
+    zpp_stage_config c;
+    int64_t T, h, f, f1, d, nh, L, U;
+    int dt;
+    size_t esz;
+    std::vector<Tensor> layout;
+    std::map<std::string, size_t> index;      // name -> layout idx
+    struct WtEntry { uint64_t src_off, rows, cols, dst_off; };
+    std::map<std::string, WtEntry> wt;        // matrix name -> its slot in the transposed working copy
+    uint64_t N = 0, Nmat = 0;
+
+    // workspace plan (byte offsets)
+    Region rW, rWt, rS, rRope;
+    uint64_t stash_base = 0, stash_block_bytes = 0;
+    std::map<std::string, Region> stash_t;    // per (mb, block) tensors, offsets relative to the slot
+    std::map<std::string, Region> tmp;        // shared temporaries
+    uint64_t ws_bytes = 0;
+
+    // bound memory
+    float *P = nullptr, *G = nullptr, *M = nullptr, *V = nullptr;
+    unsigned char *ws = nullptr;
+    bool bound = false, materialized = false, rope_ready = false;
+    std::vector<int> mb_state;
+    int pending_acc = -1;
+    uint64_t n_materialize = 0, materialize_bytes = 0;
+
+    uint64_t off(int blk, const char *nm) const
+    {
+        return layout[index.at("blk" + std::to_string(blk) + "." + nm)].offset;
+    }
+    void *Wp(int blk, const char *nm) const { return ws + rW.off + off(blk, nm) * esz; }
+    void *Wtp(int blk, const char *nm) const
+    {
+        return ws + rWt.off + wt.at("blk" + std::to_string(blk) + "." + nm).dst_off * 2;
+    }
+    float *Sp(int blk, const char *nm) const { return (float *)(ws + rS.off) + off(blk, nm); }
+    void *stash(int mb, int blk, const char *nm) const
+    {
+        return ws + stash_base + ((uint64_t)mb * L + blk) * stash_block_bytes + stash_t.at(nm).off;
+    }
+    void *tp(const char *nm) const { return ws + tmp.at(nm).off; }
+};
+
+namespace {
+
+void build_layout(zpp_stage *s)
+{
+    uint64_t off = 0;
+    const uint64_t h = s->h, f = s->f;
+    auto add = [&](int blk, const char *nm, uint64_t r, uint64_t c) {
+        Tensor t{"blk" + std::to_string(blk) + "." + nm, off, r, c};
+        s->index[t.name] = s->layout.size();
+        s->layout.push_back(t);
+        off += r * c;
+    };
+    for (int b = 0; b < s->L; ++b) {
+        if (s->c.arch == ZPP_ARCH_GPT) {
+            add(b, "ln1.gamma", 1, h);
+            add(b, "ln1.beta", 1, h);
+            add(b, "attn.wqkv", 3 * h, h);
+            add(b, "attn.bqkv", 1, 3 * h);
+            add(b, "attn.wo", h, h);
+            add(b, "attn.bo", 1, h);
+            add(b, "ln2.gamma", 1, h);
+            add(b, "ln2.beta", 1, h);
+            add(b, "mlp.w1", f, h);
+            add(b, "mlp.b1", 1, f);
+            add(b, "mlp.w2", h, f);
+            add(b, "mlp.b2", 1, h);
+        } else {
+            add(b, "norm1.gamma", 1, h);
+            add(b, "attn.wqkv", 3 * h, h);
+            add(b, "attn.wo", h, h);
+            add(b, "norm2.gamma", 1, h);
+            add(b, "mlp.wgate", f, h);
+            add(b, "mlp.wup", f, h);
+            add(b, "mlp.wdown", h, f);
+        }
+    }
+    s->N = off;
+    // Transposed working copy (bf16 mode): one [cols, rows] slot per matrix.  wgate and wup are
+    // adjacent and are used as one [2f, h] matrix, so they share one [h, 2f] slot.
+    uint64_t woff = 0;
+    for (auto &t : s->layout) {
+        if (t.rows <= 1) continue;
+        const std::string leaf = t.name.substr(t.name.find('.') + 1);
+        if (leaf == "mlp.wup") continue;
+        const uint64_t rows = leaf == "mlp.wgate" ? 2 * t.rows : t.rows;
+        s->wt[t.name] = {t.offset, rows, t.cols, woff};
+        woff += rows * t.cols;
+    }
+    s->Nmat = woff;
+}
+
+void plan_workspace(zpp_stage *s)
+{
+    uint64_t cur = 0;
+    auto carve = [&](uint64_t elems, int esz) {
+        Region r;
+        r.off = cur;
+        r.elems = elems;
+        r.esz = esz;
+        cur = align_up(cur + elems * esz);
+        return r;
+    };
+    const int e = (int)s->esz;
+    const uint64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    s->rW = carve(s->N, e);
+    if (s->dt == DT_BF16) s->rWt = carve(s->Nmat, 2);
+    s->rS = carve(s->N, 4);
+    if (s->c.arch == ZPP_ARCH_LLAMA) s->rRope = carve((uint64_t)s->c.seq * (s->d / 2) * 2, 4);
+    // activation stash: one slot per (micro-batch, block)
+    {
+        uint64_t rel = 0;
+        auto sc = [&](const char *nm, uint64_t elems, int esz) {
+            Region r;
+            r.off = rel;
+            r.elems = elems;
+            r.esz = esz;
+            rel = align_up(rel + elems * esz);
+            s->stash_t[nm] = r;
+        };
+        sc("x", T * h, e);
+        sc("mean1", T, 4);
+        sc("rstd1", T, 4);
+        sc("n1", T * h, e);
+        sc("qkv", T * 3 * h, e);
+        sc("attn", T * h, e);
+        sc("lse", (uint64_t)s->c.micro_batch * s->nh * s->c.seq, 4);
+        sc("x1", T * h, e);
+        sc("mean2", T, 4);
+        sc("rstd2", T, 4);
+        sc("n2", T * h, e);
+        sc("u", T * f1, e);
+        sc("g", T * f, e);
+        s->stash_block_bytes = rel;
+        s->stash_base = cur;
+        cur = align_up(cur + (uint64_t)s->U * s->L * rel);
+    }
+    auto tmp = [&](const char *nm, uint64_t elems, int esz) { s->tmp[nm] = carve(elems, esz); };
+    tmp("gA", T * h, e);
+    tmp("gB", T * h, e);
+    tmp("dn", T * h, e);
+    tmp("dx1", T * h, e);
+    tmp("dattn", T * h, e);
+    tmp("dqkv", T * 3 * h, e);
+    tmp("du", T * f1, e);
+    if (s->c.arch == ZPP_ARCH_LLAMA) tmp("dact", T * f, e);
+    tmp("delta", (uint64_t)s->c.micro_batch * s->nh * s->c.seq, 4);
+    const uint64_t widest = std::max<uint64_t>(3 * h, f1);
+    if (s->dt == DT_BF16) {
+        tmp("tA", widest * T, 2);
+        tmp("tB", std::max<uint64_t>(h, f) * T, 2);
+    }
+    tmp("colred", colreduce_scratch_floats((int64_t)T, (int64_t)widest), 4);
+    s->ws_bytes = cur;
+}
+
+#define ZPP_TRY(expr)                                                                                    \
+    do {                                                                                                 \
+        hipError_t _e = (expr);                                                                          \
+        if (_e != hipSuccess)                                                                            \
+            return fail(ZPP_ERR_DEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, \
+                        __LINE__);                                                                       \
+    } while (0)
+
+// y[T,out] = epilogue(x[T,in] . W[out,in]^T)
+hipError_t linear_fwd(zpp_stage *s, const void *x, int blk, const char *w, int64_t in, int64_t out, void *y,
+                      GemmEpi epi, hipStream_t st)
+{
+    if (s->dt == DT_BF16)
+        return launch_gemm_bf16_nt(s->T, out, in, x, in, s->Wp(blk, w), in, y, out, epi, st);
+    return launch_gemm_f32(s->T, out, in, (const float *)x, in, 1, (const float *)s->Wp(blk, w), in, 1,
+                           (float *)y, out, epi, st);
+}
+
+// Input gradient (Section 2.3): dx[T,in] = epilogue(dy[T,out] . W[out,in])
+hipError_t linear_dx(zpp_stage *s, const void *dy, int blk, const char *w, int64_t in, int64_t out, void *dx,
+                     GemmEpi epi, hipStream_t st)
+{
+    if (s->dt == DT_BF16)  // uses the transposed working copy W^T[in,out] so both operands are K-contiguous
+        return launch_gemm_bf16_nt(s->T, in, out, dy, out, s->Wtp(blk, w), out, dx, in, epi, st);
+    return launch_gemm_f32(s->T, in, out, (const float *)dy, out, 1, (const float *)s->Wp(blk, w), 1, in,
+                           (float *)dx, in, epi, st);
+}
+
+// Weight gradient (Section 2.3): dW[out,in] = dy[T,out]^T . x[T,in]  (fp32, into the staging buffer),
+// and optionally db[out] = column sums of dy.
+hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const char *w, const char *bias,
+                     int64_t in, int64_t out, hipStream_t st)
+{
+    GemmEpi epi;
+    epi.out_f32 = 1;
+    hipError_t e;
+    if (s->dt == DT_BF16) {
+        void *tA = s->tp("tA"), *tB = s->tp("tB");
+        if ((e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st)) != hipSuccess) return e;
+        if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
+        e = launch_gemm_bf16_nt(out, in, s->T, tA, s->T, tB, s->T, s->Sp(blk, w), in, epi, st);
+    } else {
+        e = launch_gemm_f32(out, in, s->T, (const float *)dy, 1, out, (const float *)x, 1, in, s->Sp(blk, w),
+                            in, epi, st);
+    }
+    if (e != hipSuccess) return e;
+    if (bias)
+        e = launch_colreduce(s->dt, COLRED_SUM, dy, nullptr, nullptr, nullptr, s->T, out, out, s->Sp(blk, bias),
+                             nullptr, (float *)s->tp("colred"), st);
+    return e;
+}
+
+hipError_t attention_fwd(zpp_stage *s, const void *qkv, void *attn, float *lse, hipStream_t st)
+{
+    if (s->dt == DT_BF16 && attn_mfma_supported(s->c.seq, s->d))
+        return launch_attn_fwd(s->dt, qkv, attn, lse, s->c.micro_batch, s->c.seq, s->nh, s->d, st);
+    return launch_attn_simple_fwd(s->dt, qkv, attn, lse, s->c.micro_batch, s->c.seq, s->nh, s->d, st);
+}
+
+hipError_t attention_bwd(zpp_stage *s, const void *qkv, const void *attn, const void *dattn, const float *lse,
+                         void *dqkv, hipStream_t st)
+{
+    float *delta = (float *)s->tp("delta");
+    if (s->dt == DT_BF16 && attn_mfma_supported(s->c.seq, s->d))
+        return launch_attn_bwd(s->dt, qkv, attn, dattn, lse, delta, dqkv, s->c.micro_batch, s->c.seq, s->nh,
+                               s->d, st);
+    return launch_attn_simple_bwd(s->dt, qkv, attn, dattn, lse, delta, dqkv, s->c.micro_batch, s->c.seq, s->nh,
+                                  s->d, st);
+}
+
+zpp_status check_stage(const zpp_stage *s, bool need_bound)
+{
+    if (!s) return fail(ZPP_ERR_ARG, "stage is NULL");
+    if (need_bound && !s->bound) return fail(ZPP_ERR_STATE, "stage has no bound memory (call zpp_stage_bind)");
+    return ZPP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *zpp_last_error(void) { return g_err; }
+const char *zpp_version(void) { return "zpp-stage 0.1 (gfx950)"; }
+
+zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out)
+{
+    if (!cfg || !out) return fail(ZPP_ERR_ARG, "cfg/out is NULL");
+    *out = nullptr;
+    const zpp_stage_config &c = *cfg;
+    if (c.arch != ZPP_ARCH_GPT && c.arch != ZPP_ARCH_LLAMA) return fail(ZPP_ERR_ARG, "arch must be 0 or 1");
+    if (c.compute_dtype != ZPP_DTYPE_FP32 && c.compute_dtype != ZPP_DTYPE_BF16)
+        return fail(ZPP_ERR_ARG, "compute_dtype must be 0 or 1");
+    if (c.gelu_mode != ZPP_GELU_TANH && c.gelu_mode != ZPP_GELU_ERF)
+        return fail(ZPP_ERR_ARG, "gelu_mode must be 0 or 1");
+    if (c.n_blocks <= 0 || c.hidden <= 0 || c.n_heads <= 0 || c.ffn <= 0 || c.seq <= 0 || c.micro_batch <= 0 ||
+        c.unit_mbs <= 0)
+        return fail(ZPP_ERR_ARG, "all sizes must be positive");
+    if (c.hidden % c.n_heads) return fail(ZPP_ERR_ARG, "hidden (%d) not divisible by n_heads (%d)", c.hidden, c.n_heads);
+    if (!(c.norm_eps > 0.0f)) return fail(ZPP_ERR_ARG, "norm_eps must be > 0");
+    const int64_t d = c.hidden / c.n_heads;
+    if (c.arch == ZPP_ARCH_LLAMA && (d % 2)) return fail(ZPP_ERR_ARG, "rotary embedding needs an even head dim");
+    if (c.arch == ZPP_ARCH_LLAMA && !(c.rope_base > 0.0f)) return fail(ZPP_ERR_ARG, "rope_base must be > 0");
+    const int vec = c.compute_dtype == ZPP_DTYPE_BF16 ? 8 : 4;
+    if (c.hidden % vec || c.ffn % vec)
+        return fail(ZPP_ERR_UNSUPPORTED, "hidden and ffn must be multiples of %d elements (16-byte vectors)", vec);
+    const int64_t T = (int64_t)c.micro_batch * c.seq;
+    if (c.compute_dtype == ZPP_DTYPE_BF16) {
+        if (c.hidden % 64 || c.ffn % 64 || T % 64)
+            return fail(ZPP_ERR_UNSUPPORTED,
+                        "bf16 MFMA GEMMs need hidden, ffn and micro_batch*seq to be multiples of 64");
+    }
+    if ((2 * d + 2 * (int64_t)c.seq) * 4 > 64 * 1024 &&
+        !(c.compute_dtype == ZPP_DTYPE_BF16 && attn_mfma_supported(c.seq, d)))
+        return fail(ZPP_ERR_UNSUPPORTED, "sequence too long for the generic attention kernel");
+    if (c.micro_batch > 65535 || c.n_heads > 65535) return fail(ZPP_ERR_UNSUPPORTED, "micro_batch/n_heads too large");
+
+    zpp_stage *s = new (std::nothrow) zpp_stage();
+    if (!s) return fail(ZPP_ERR_ARG, "out of host memory");
+    s->c = c;
+    s->T = T;
+    s->h = c.hidden;
+    s->f = c.ffn;
+    s->f1 = c.arch == ZPP_ARCH_LLAMA ? 2 * (int64_t)c.ffn : c.ffn;
+    s->d = d;
+    s->nh = c.n_heads;
+    s->L = c.n_blocks;
+    s->U = c.unit_mbs;
+    s->dt = c.compute_dtype == ZPP_DTYPE_BF16 ? DT_BF16 : DT_F32;
+    s->esz = dt_size(s->dt);
+    build_layout(s);
+    plan_workspace(s);
+    s->mb_state.assign(s->U, MB_IDLE);
+    *out = s;
+    return ZPP_OK;
+}
+
+void zpp_stage_destroy(zpp_stage *s) { delete s; }
+
+uint64_t zpp_stage_param_count(const zpp_stage *s) { return s ? s->N : 0; }
+uint64_t zpp_stage_workspace_bytes(const zpp_stage *s) { return s ? s->ws_bytes : 0; }
+int32_t zpp_stage_layout_size(const zpp_stage *s) { return s ? (int32_t)s->layout.size() : 0; }
+
+zpp_status zpp_stage_param_layout(const zpp_stage *s, int32_t idx, const char **name, uint64_t *offset,
+                                  uint64_t *rows, uint64_t *cols)
+{
+    if (check_stage(s, false)) return ZPP_ERR_ARG;
+    if (idx < 0 || idx >= (int32_t)s->layout.size()) return fail(ZPP_ERR_ARG, "layout index %d out of range", idx);
+    const Tensor &t = s->layout[idx];
+    if (name) *name = t.name.c_str();
+    if (offset) *offset = t.offset;
+    if (rows) *rows = t.rows;
+    if (cols) *cols = t.cols;
+    return ZPP_OK;
+}
+
+zpp_status zpp_stage_bind(zpp_stage *s, float *P, float *G, float *M, float *V, void *workspace,
+                          uint64_t workspace_bytes)
+{
+    if (check_stage(s, false)) return ZPP_ERR_ARG;
+    if (!P || !G || !M || !V || !workspace) return fail(ZPP_ERR_ARG, "P, G, M, V and workspace must be non-NULL");
+    if (!aligned(P) || !aligned(G) || !aligned(M) || !aligned(V) || !aligned(workspace))
+        return fail(ZPP_ERR_ALIGN, "P, G, M, V and workspace must be 256-byte aligned");
+    if (workspace_bytes < s->ws_bytes)
+        return fail(ZPP_ERR_WORKSPACE, "workspace has %llu bytes, %llu needed", (unsigned long long)workspace_bytes,
+                    (unsigned long long)s->ws_bytes);
+    s->P = P;
+    s->G = G;
+    s->M = M;
+    s->V = V;
+    s->ws = (unsigned char *)workspace;
+    s->bound = true;
+    s->materialized = false;
+    s->rope_ready = false;
+    s->pending_acc = -1;
+    s->mb_state.assign(s->U, MB_IDLE);
+    return ZPP_OK;
+}
+
+zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    hipStream_t st = (hipStream_t)hip_stream;
+    ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
+    uint64_t bytes = s->N * (4 + s->esz);
+    if (s->dt == DT_BF16) {
+        for (auto &kv : s->wt) {
+            const auto &w = kv.second;
+            ZPP_TRY(launch_transpose_cast(s->P + w.src_off, s->ws + s->rWt.off + w.dst_off * 2, w.rows, w.cols, st));
+            bytes += w.rows * w.cols * 6;
+        }
+    }
+    if (s->c.arch == ZPP_ARCH_LLAMA && !s->rope_ready) {
+        ZPP_TRY(launch_rope_table((float *)(s->ws + s->rRope.off), s->c.seq, s->d, (double)s->c.rope_base, st));
+        s->rope_ready = true;
+    }
+    s->materialized = true;
+    s->n_materialize++;
+    s->materialize_bytes += bytes;
+    return ZPP_OK;
+}
+
+zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
+    if (!x || !y) return fail(ZPP_ERR_ARG, "x/y is NULL");
+    if (!aligned(x) || !aligned(y)) return fail(ZPP_ERR_ALIGN, "x and y must be 256-byte aligned");
+    if (!s->materialized) return fail(ZPP_ERR_STATE, "stage_forward before stage_materialize_params");
+    if (s->mb_state[mb] != MB_IDLE) return fail(ZPP_ERR_STATE, "stage_forward(%d) called twice in this unit", mb);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool gpt = s->c.arch == ZPP_ARCH_GPT;
+    const int kind = gpt ? NORM_LAYER : NORM_RMS;
+    const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    for (int blk = 0; blk < s->L; ++blk) {
+        void *xs = s->stash(mb, blk, "x");
+        const void *xin = blk == 0 ? x : xs;
+        void *out = blk == s->L - 1 ? y : s->stash(mb, blk + 1, "x");
+        float *mean1 = (float *)s->stash(mb, blk, "mean1"), *rstd1 = (float *)s->stash(mb, blk, "rstd1");
+        float *mean2 = (float *)s->stash(mb, blk, "mean2"), *rstd2 = (float *)s->stash(mb, blk, "rstd2");
+        void *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv"), *attn = s->stash(mb, blk, "attn");
+        void *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2"), *u = s->stash(mb, blk, "u");
+        void *g = s->stash(mb, blk, "g");
+        float *lse = (float *)s->stash(mb, blk, "lse");
+
+        ZPP_TRY(launch_norm_fwd(s->dt, kind, xin, s->Wp(blk, gpt ? "ln1.gamma" : "norm1.gamma"),
+                                gpt ? s->Wp(blk, "ln1.beta") : nullptr, T, h, s->c.norm_eps, n1, mean1, rstd1,
+                                blk == 0 ? xs : nullptr, st));
+        GemmEpi e_qkv;
+        if (gpt) e_qkv.bias = s->Wp(blk, "attn.bqkv");
+        ZPP_TRY(linear_fwd(s, n1, blk, "attn.wqkv", h, 3 * h, qkv, e_qkv, st));
+        if (!gpt)
+            ZPP_TRY(launch_rope(s->dt, qkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, +1, st));
+        ZPP_TRY(attention_fwd(s, qkv, attn, lse, st));
+        GemmEpi e_o;
+        if (gpt) e_o.bias = s->Wp(blk, "attn.bo");
+        e_o.resid = xs;
+        ZPP_TRY(linear_fwd(s, attn, blk, "attn.wo", h, h, x1, e_o, st));
+        ZPP_TRY(launch_norm_fwd(s->dt, kind, x1, s->Wp(blk, gpt ? "ln2.gamma" : "norm2.gamma"),
+                                gpt ? s->Wp(blk, "ln2.beta") : nullptr, T, h, s->c.norm_eps, n2, mean2, rstd2,
+                                nullptr, st));
+        GemmEpi e_2;
+        e_2.resid = x1;
+        if (gpt) {
+            GemmEpi e_1;
+            e_1.bias = s->Wp(blk, "mlp.b1");
+            e_1.act = ACT_GELU_DUAL;
+            e_1.out2 = g;
+            e_1.gelu_mode = s->c.gelu_mode;
+            ZPP_TRY(linear_fwd(s, n2, blk, "mlp.w1", h, f, u, e_1, st));
+            e_2.bias = s->Wp(blk, "mlp.b2");
+            ZPP_TRY(linear_fwd(s, g, blk, "mlp.w2", f, h, out, e_2, st));
+        } else {
+            // wgate and wup are adjacent in the layout: one GEMM against the [2f, h] matrix gives [gate | up]
+            ZPP_TRY(linear_fwd(s, n2, blk, "mlp.wgate", h, f1, u, GemmEpi(), st));
+            ZPP_TRY(launch_swiglu_fwd(s->dt, u, g, T, f, st));
+            ZPP_TRY(linear_fwd(s, g, blk, "mlp.wdown", f, h, out, e_2, st));
+        }
+    }
+    s->mb_state[mb] = MB_FWD;
+    return ZPP_OK;
+}
+
+zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
+    if (!dy || !dx) return fail(ZPP_ERR_ARG, "dy/dx is NULL");
+    if (!aligned(dy) || !aligned(dx)) return fail(ZPP_ERR_ALIGN, "dy and dx must be 256-byte aligned");
+    if (!s->materialized) return fail(ZPP_ERR_STATE, "working copy is stale: call stage_materialize_params");
+    if (s->mb_state[mb] != MB_FWD)
+        return fail(ZPP_ERR_STATE, "stage_backward(%d) needs exactly one stage_forward(%d) before it", mb, mb);
+    if (s->pending_acc >= 0)
+        return fail(ZPP_ERR_STATE, "staging buffer still holds micro-batch %d: call stage_accumulate_grads first",
+                    s->pending_acc);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool gpt = s->c.arch == ZPP_ARCH_GPT;
+    const int kind = gpt ? NORM_LAYER : NORM_RMS;
+    const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    void *gbuf[2] = {s->tp("gA"), s->tp("gB")};
+    void *dn = s->tp("dn"), *dx1 = s->tp("dx1"), *dattn = s->tp("dattn"), *dqkv = s->tp("dqkv"), *du = s->tp("du");
+    float *colred = (float *)s->tp("colred");
+    const void *dcur = dy;
+    for (int blk = (int)s->L - 1; blk >= 0; --blk) {
+        void *dout = blk == 0 ? dx : gbuf[blk & 1];
+        const void *xs = s->stash(mb, blk, "x"), *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv");
+        const void *attn = s->stash(mb, blk, "attn"), *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2");
+        const void *u = s->stash(mb, blk, "u"), *g = s->stash(mb, blk, "g");
+        const float *mean1 = (const float *)s->stash(mb, blk, "mean1"), *rstd1 = (const float *)s->stash(mb, blk, "rstd1");
+        const float *mean2 = (const float *)s->stash(mb, blk, "mean2"), *rstd2 = (const float *)s->stash(mb, blk, "rstd2");
+        const float *lse = (const float *)s->stash(mb, blk, "lse");
+        // ---- MLP branch
+        if (gpt) {
+            ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.w2", "mlp.b2", f, h, st));
+            GemmEpi e;
+            e.act = ACT_DGELU_MUL;
+            e.aux = u;
+            e.gelu_mode = s->c.gelu_mode;
+            ZPP_TRY(linear_dx(s, dcur, blk, "mlp.w2", f, h, du, e, st));
+            ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.w1", "mlp.b1", h, f, st));
+            ZPP_TRY(linear_dx(s, du, blk, "mlp.w1", h, f, dn, GemmEpi(), st));
+        } else {
+            void *dact = s->tp("dact");
+            ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.wdown", nullptr, f, h, st));
+            ZPP_TRY(linear_dx(s, dcur, blk, "mlp.wdown", f, h, dact, GemmEpi(), st));
+            ZPP_TRY(launch_swiglu_bwd(s->dt, u, dact, du, T, f, st));
+            ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.wgate", nullptr, h, f1, st));
+            ZPP_TRY(linear_dx(s, du, blk, "mlp.wgate", h, f1, dn, GemmEpi(), st));
+        }
+        const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
+        ZPP_TRY(launch_norm_bwd(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h, st));
+        ZPP_TRY(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
+                                 s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, colred, st));
+        // ---- attention branch
+        ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
+        ZPP_TRY(linear_dx(s, dx1, blk, "attn.wo", h, h, dattn, GemmEpi(), st));
+        ZPP_TRY(attention_bwd(s, qkv, attn, dattn, lse, dqkv, st));
+        if (!gpt)
+            ZPP_TRY(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
+        ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
+        ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
+        ZPP_TRY(launch_norm_bwd(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h, st));
+        ZPP_TRY(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
+                                 s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, colred, st));
+        dcur = dout;
+    }
+    s->mb_state[mb] = MB_BWD;
+    s->pending_acc = mb;
+    return ZPP_OK;
+}
+
+zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
+    if (s->mb_state[mb] != MB_BWD || s->pending_acc != mb)
+        return fail(ZPP_ERR_STATE, "stage_accumulate_grads(%d) needs stage_backward(%d) right before it", mb, mb);
+    ZPP_TRY(launch_accumulate(s->G, (const float *)(s->ws + s->rS.off), s->N, scale, (hipStream_t)hip_stream));
+    s->mb_state[mb] = MB_ACC;
+    s->pending_acc = -1;
+    return ZPP_OK;
+}
+
+zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const zpp_adam *hp, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (!hp) return fail(ZPP_ERR_ARG, "hyper-parameters are NULL");
+    if (offset > s->N || count > s->N - offset)
+        return fail(ZPP_ERR_ARG, "range [%llu, +%llu) outside the shard of %llu elements", (unsigned long long)offset,
+                    (unsigned long long)count, (unsigned long long)s->N);
+    if (offset % 4 || (count % 4 && offset + count != s->N))
+        return fail(ZPP_ERR_ALIGN, "offset and count must be multiples of 4 elements");
+    if (hp->step < 1) return fail(ZPP_ERR_ARG, "step must be >= 1");
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f && hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+        return fail(ZPP_ERR_ARG, "betas must lie in [0,1)");
+    if (s->pending_acc >= 0)
+        return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
+    AdamArgs a;
+    a.lr = hp->lr;
+    a.beta1 = hp->beta1;
+    a.beta2 = hp->beta2;
+    a.eps = hp->eps;
+    a.wd = hp->weight_decay;
+    a.grad_scale = hp->grad_scale;
+    a.omb1 = (float)(1.0 - (double)hp->beta1);
+    a.omb2 = (float)(1.0 - (double)hp->beta2);
+    a.c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
+    a.c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
+    a.decoupled = hp->decoupled_wd ? 1 : 0;
+    a.zero_grad = hp->zero_grad ? 1 : 0;
+    ZPP_TRY(launch_adam(s->P + offset, s->M + offset, s->V + offset, s->G + offset, count, a,
+                        (hipStream_t)hip_stream));
+    if (count) s->materialized = false;
+    return ZPP_OK;
+}
+
+zpp_status zpp_stage_end_unit(zpp_stage *s)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (s->pending_acc >= 0)
+        return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
+    s->mb_state.assign(s->U, MB_IDLE);
+    return ZPP_OK;
+}
+
+void zpp_stage_counters(const zpp_stage *s, uint64_t *calls, uint64_t *bytes)
+{
+    if (calls) *calls = s ? s->n_materialize : 0;
+    if (bytes) *bytes = s ? s->materialize_bytes : 0;
+}
+
+zpp_status zpp_stage_region(const zpp_stage *s, const char *name, int32_t mb, int32_t blk, void **ptr,
+                            uint64_t *elems, int32_t *elem_bytes)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (!name || !ptr) return fail(ZPP_ERR_ARG, "name/ptr is NULL");
+    Region r;
+    uint64_t base = 0;
+    std::string n(name);
+    if (n == "W") r = s->rW;
+    else if (n == "S") r = s->rS;
+    else if (n == "Wt" && s->dt == DT_BF16) r = s->rWt;
+    else if (s->stash_t.count(n)) {
+        if (mb < 0 || mb >= s->U || blk < 0 || blk >= s->L) return fail(ZPP_ERR_ARG, "(mb, block) out of range");
+        r = s->stash_t.at(n);
+        base = s->stash_base + ((uint64_t)mb * s->L + blk) * s->stash_block_bytes;
+    } else if (s->tmp.count(n)) r = s->tmp.at(n);
+    else return fail(ZPP_ERR_ARG, "unknown region '%s'", name);
+    *ptr = s->ws + base + r.off;
+    if (elems) *elems = r.elems;
+    if (elem_bytes) *elem_bytes = r.esz;
+    return ZPP_OK;
+}
+
+// ---- operator-level entry points (include/zpp_ops.h) ---------------------------------------------
+#define ZPP_OP_TRY(expr)                                                                     \
+    do {                                                                                     \
+        hipError_t _e = (expr);                                                              \
+        if (_e != hipSuccess) return fail(ZPP_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(_e)); \
+    } while (0)
+
+zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
+                               int32_t out_f32, int32_t variant, void *hip_stream)
+{
+    if (!A || !B || !C) return fail(ZPP_ERR_ARG, "A/B/C is NULL");
+    if (M < 0 || N < 0 || K <= 0) return fail(ZPP_ERR_ARG, "bad sizes");
+    if (K % 64 || lda % 8 || ldb % 8 || lda < K || ldb < K || ldc < N)
+        return fail(ZPP_ERR_UNSUPPORTED, "need K %% 64 == 0, lda/ldb multiples of 8 and >= K, ldc >= N");
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
+    if (variant < -1 || variant > 3) return fail(ZPP_ERR_ARG, "variant must be -1..3");
+    GemmEpi e;
+    e.bias = bias;
+    e.resid = resid;
+    e.out_f32 = out_f32;
+    gemm_bf16_force_variant(variant);
+    hipError_t err = launch_gemm_bf16_nt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
+    gemm_bf16_force_variant(-1);
+    if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_attention_fwd(int32_t dtype, int32_t impl, const void *qkv, void *attn, float *lse, int64_t b,
+                                int64_t seq, int64_t nh, int64_t d, void *hip_stream)
+{
+    if (!qkv || !attn || !lse) return fail(ZPP_ERR_ARG, "NULL pointer");
+    if (b <= 0 || seq <= 0 || nh <= 0 || d <= 0 || b > 65535 || nh > 65535) return fail(ZPP_ERR_ARG, "bad sizes");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (impl == 1) {
+        if (dtype != ZPP_DTYPE_BF16 || !attn_mfma_supported(seq, d))
+            return fail(ZPP_ERR_UNSUPPORTED, "MFMA attention needs bf16, d = 128 and seq %% 128 == 0");
+        ZPP_OP_TRY(launch_attn_fwd(DT_BF16, qkv, attn, lse, b, seq, nh, d, st));
+    } else {
+        if ((d + seq) * 4 > 64 * 1024) return fail(ZPP_ERR_UNSUPPORTED, "sequence too long");
+        ZPP_OP_TRY(launch_attn_simple_fwd(dtype == ZPP_DTYPE_BF16 ? DT_BF16 : DT_F32, qkv, attn, lse, b, seq, nh, d, st));
+    }
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_attention_bwd(int32_t dtype, int32_t impl, const void *qkv, const void *attn, const void *dattn,
+                                const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh,
+                                int64_t d, void *hip_stream)
+{
+    if (!qkv || !attn || !dattn || !lse || !delta || !dqkv) return fail(ZPP_ERR_ARG, "NULL pointer");
+    if (b <= 0 || seq <= 0 || nh <= 0 || d <= 0 || b > 65535 || nh > 65535) return fail(ZPP_ERR_ARG, "bad sizes");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (impl == 1) {
+        if (dtype != ZPP_DTYPE_BF16 || !attn_mfma_supported(seq, d))
+            return fail(ZPP_ERR_UNSUPPORTED, "MFMA attention needs bf16, d = 128 and seq %% 128 == 0");
+        ZPP_OP_TRY(launch_attn_bwd(DT_BF16, qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, d, st));
+    } else {
+        if ((2 * d + 2 * seq) * 4 > 64 * 1024) return fail(ZPP_ERR_UNSUPPORTED, "sequence too long");
+        ZPP_OP_TRY(launch_attn_simple_bwd(dtype == ZPP_DTYPE_BF16 ? DT_BF16 : DT_F32, qkv, attn, dattn, lse, delta,
+                                          dqkv, b, seq, nh, d, st));
+    }
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_flat_adam(float *P, float *M, float *V, float *G, uint64_t n, const zpp_adam *hp, void *hip_stream)
+{
+    if (!P || !M || !V || !G || !hp) return fail(ZPP_ERR_ARG, "NULL pointer");
+    if (((uintptr_t)P | (uintptr_t)M | (uintptr_t)V | (uintptr_t)G) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment");
+    if (hp->step < 1) return fail(ZPP_ERR_ARG, "step must be >= 1");
+    AdamArgs a;
+    a.lr = hp->lr; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps; a.wd = hp->weight_decay;
+    a.grad_scale = hp->grad_scale;
+    a.omb1 = (float)(1.0 - (double)hp->beta1);
+    a.omb2 = (float)(1.0 - (double)hp->beta2);
+    a.c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
+    a.c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
+    a.decoupled = hp->decoupled_wd ? 1 : 0;
+    a.zero_grad = hp->zero_grad ? 1 : 0;
+    ZPP_OP_TRY(launch_adam(P, M, V, G, n, a, (hipStream_t)hip_stream));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_flat_accumulate(float *G, const float *S, uint64_t n, float scale, void *hip_stream)
+{
+    if (!G || !S) return fail(ZPP_ERR_ARG, "NULL pointer");
+    if (((uintptr_t)G | (uintptr_t)S) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment");
+    ZPP_OP_TRY(launch_accumulate(G, S, n, scale, (hipStream_t)hip_stream));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_flat_materialize(const float *P, void *W, uint64_t n, int32_t dtype, void *hip_stream)
+{
+    if (!P || !W) return fail(ZPP_ERR_ARG, "NULL pointer");
+    if (((uintptr_t)P | (uintptr_t)W) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment");
+    ZPP_OP_TRY(launch_materialize(P, W, n, dtype == ZPP_DTYPE_BF16 ? DT_BF16 : DT_F32, (hipStream_t)hip_stream));
+    return ZPP_OK;
+}
+
+}  // extern "C"

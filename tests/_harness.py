@@ -1,0 +1,90 @@
+"""Shared helpers of the GPU parity tests: run the same seeded scheduling unit through the HIP
+library and through the CPU oracle, and compare tensor by tensor."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import synth
+
+
+def rel_err(a: np.ndarray, ref: np.ndarray) -> float:
+    """max|a - ref| / max|ref| : the per-tensor measure used for activations and gradients."""
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.abs(ref).max()
+    return float(np.abs(a - ref).max() / (den if den > 0 else 1.0))
+
+
+def to_dev(arr: np.ndarray, act_dtype, device="cuda:0"):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(device=device, dtype=act_dtype)
+
+
+def to_np(t) -> np.ndarray:
+    return t.detach().to("cpu").float().numpy()
+
+
+def make_inputs(shape, n_mbs):
+    xs = [synth.make_x(shape, m) for m in range(n_mbs)]
+    dys = [synth.make_dy(shape, m) for m in range(n_mbs)]
+    return xs, dys
+
+
+def run_oracle_unit(shape, P0: np.ndarray, xs, dys, dtype="f64", keep_stage=False):
+    st = oracle.OracleStage(shape, dtype)
+    st.P[:] = P0
+    st.G[:] = 0
+    st.materialize()
+    ys = [st.forward(m, x) for m, x in enumerate(xs)]
+    dxs, Ss = [], []
+    for m, dy in enumerate(dys):
+        dxs.append(st.backward(m, dy))
+        Ss.append(st.S.copy() if m == 0 else None)
+        st.accumulate(m, 1.0)
+    out = dict(ys=ys, dxs=dxs, G=st.G.copy(), S0=Ss[0], W=st.W.copy())
+    if keep_stage:
+        out["stage"] = st
+    else:
+        st.close()
+    return out
+
+
+def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False):
+    import torch
+    import paper_2402_03791_amd as zpp
+    st = zpp.Stage(shape)
+    st.P.copy_(torch.from_numpy(P0))
+    st.G.zero_()
+    st.materialize_params()
+    ys = [st.forward(m, to_dev(x, st.act_dtype)) for m, x in enumerate(xs)]
+    dxs = []
+    S0 = None
+    for m, dy in enumerate(dys):
+        dxs.append(st.backward(m, to_dev(dy, st.act_dtype)))
+        if m == 0:
+            S0 = to_np(st.region("S"))
+        st.accumulate_grads(m, 1.0)
+    torch.cuda.synchronize()
+    out = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs], G=to_np(st.G), S0=S0,
+               W=to_np(st.region("W")))
+    if keep_stage:
+        out["stage"] = st
+    else:
+        st.close()
+    return out
+
+
+def compare_units(shape, gpu, ref, layout, tol, tol_small=None):
+    """Asserts the per-tensor relative error bound on y, dx and every gradient tensor."""
+    worst = {}
+    for m, (a, b) in enumerate(zip(gpu["ys"], ref["ys"])):
+        worst[f"y[{m}]"] = rel_err(a, b)
+    for m, (a, b) in enumerate(zip(gpu["dxs"], ref["dxs"])):
+        worst[f"dx[{m}]"] = rel_err(a, b)
+    for name, off, r, c in layout:
+        worst[f"G.{name}"] = rel_err(gpu["G"][off:off + r * c], ref["G"][off:off + r * c])
+        worst[f"S0.{name}"] = rel_err(gpu["S0"][off:off + r * c], ref["S0"][off:off + r * c])
+    bad = {k: v for k, v in worst.items() if not (v <= tol)}
+    assert not bad, f"{shape.name}: tolerance {tol} exceeded: {bad}"
+    return worst

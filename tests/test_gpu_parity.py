@@ -1,0 +1,228 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances: per tensor max|gpu - ref| / max|ref| <= 2e-2 for bf16 MFMA paths with fp32 accumulation,
+<= 1e-4 for the all-fp32 configuration (summation order only), and element-wise <= 1e-6 relative for
+the Adam update when both sides start from bit-identical fp32 inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from synth import StageShape
+import paper_2402_03791_amd as zpp
+from _harness import (compare_units, make_inputs, rel_err, run_gpu_unit, run_oracle_unit, to_dev, to_np)
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+TOL_FP32 = 1e-4
+TOL_ADAM = 1e-6
+
+
+def f32hp():
+    """Adam hyper-parameters as the float32 values the C struct carries, widened for the oracle."""
+    return {k: float(np.float32(v)) for k, v in synth.ADAM.items()}
+
+
+# ------------------------------------------------------------------ flat-buffer passes
+@pytest.mark.parametrize("n", [4, 1000, 1579520, 8 * 1024 * 1024 + 4])
+def test_flat_adam_matches_oracle(n):
+    print(f"flat adam n={n}", flush=True)
+    sh = StageShape("flat", 0, 1, 8, 1, 8, 8, 1, 1, 0, 0)  # a dummy stage; only its flat buffers are used
+    rng = np.random.default_rng(n)
+    p0 = rng.normal(0, 0.02, n).astype(np.float32)
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    g[::11] = 0
+    m0 = rng.normal(0, 1e-4, n).astype(np.float32)
+    v0 = (rng.normal(0, 1e-4, n).astype(np.float32)) ** 2
+    hp = f32hp()
+    P, M, V, G = (torch.from_numpy(a.copy()).cuda() for a in (p0, m0, v0, g))
+    for step, kw in ((1, {}), (7, dict(decoupled_wd=0, grad_scale=0.5, zero_grad=1))):
+        zpp.op_flat_adam(P, M, V, G, step=step, **synth.ADAM, **kw)
+        torch.cuda.synchronize()
+        # oracle on the same inputs (its buffers are larger than n; only [0, n) is used)
+        big = oracle.OracleStage(sh.replace(hidden=64, ffn=64 * 1024, n_heads=1), "f32")
+        assert big.N >= n
+        big.P[:n], big.M[:n], big.V[:n], big.G[:n] = p0, m0, v0, g
+        big.adam(0, n, step=step, decoupled_wd=kw.get("decoupled_wd", 1), grad_scale=kw.get("grad_scale", 1.0),
+                 zero_grad=kw.get("zero_grad", 0), **hp)
+        for name, a, b in (("p", P, big.P[:n]), ("m", M, big.M[:n]), ("v", V, big.V[:n])):
+            a = a.cpu().numpy()
+            err = np.abs(a - b) / np.maximum(np.abs(b), 1e-30)
+            assert n == 0 or err.max() <= TOL_ADAM, (name, step, err.max())
+        if kw.get("zero_grad"):
+            assert torch.count_nonzero(G).item() == 0
+        p0, m0, v0 = big.P[:n].copy(), big.M[:n].copy(), big.V[:n].copy()
+        P.copy_(torch.from_numpy(p0)); M.copy_(torch.from_numpy(m0)); V.copy_(torch.from_numpy(v0))
+        big.close()
+
+
+def test_flat_materialize_is_bit_exact_rne():
+    # every bf16 high half with boundary low halves, plus a random bulk with a ragged tail
+    highs = np.arange(1 << 16, dtype=np.uint32)
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    pats = ((highs[:, None] << 16) | lows[None, :]).reshape(-1)
+    rnd = np.random.default_rng(0).integers(0, 1 << 32, 1000003, dtype=np.uint64).astype(np.uint32)
+    bits = np.concatenate([pats, rnd])
+    vals = bits.view(np.float32)
+    P = torch.from_numpy(vals.copy()).cuda()
+    W = torch.empty(P.numel(), dtype=torch.bfloat16, device="cuda")
+    zpp.op_flat_materialize(P, W)
+    got = W.view(torch.int16).cpu().numpy().view(np.uint16)
+    finite = ~np.isnan(vals)
+    sample = np.concatenate([np.arange(0, pats.size, 97), pats.size + np.arange(0, rnd.size, 1009)])
+    for i in sample:
+        if finite[i]:
+            assert got[i] == oracle.bf16_bits_rne(float(vals[i])), hex(int(bits[i]))
+    # vectorised check of everything finite: RNE by integer arithmetic
+    b = bits[finite].astype(np.uint64)
+    exp = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(got[finite], exp)
+    nan_out = got[~finite]
+    assert np.all((nan_out & 0x7F80) == 0x7F80) and np.all((nan_out & 0x7F) != 0)
+    # fp32 mode is a plain copy
+    Wf = torch.empty_like(P)
+    zpp.op_flat_materialize(P, Wf)
+    assert torch.equal(Wf.view(torch.int32), P.view(torch.int32))
+
+
+@pytest.mark.parametrize("n", [5, 4099, 3 * 1024 * 1024])
+def test_flat_accumulate(n):
+    rng = np.random.default_rng(n)
+    g, s = rng.normal(size=n).astype(np.float32), rng.normal(size=n).astype(np.float32)
+    G, S = torch.from_numpy(g.copy()).cuda(), torch.from_numpy(s).cuda()
+    zpp.op_flat_accumulate(G, S, 0.25)
+    ref = g.astype(np.float64) + 0.25 * s.astype(np.float64)
+    assert n == 0 or np.abs(G.cpu().numpy() - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max())
+
+
+# ------------------------------------------------------------------ whole unit, fp32 (configs[0])
+def test_cfg1_tiny_gpt_fp32_full_unit_and_adam():
+    sh = synth.CONFIGS["cfg1_tiny_gpt_fp32"]
+    print(f"unit {sh.name}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    gpu = run_gpu_unit(sh, P0, xs, dys, keep_stage=True)
+    assert np.array_equal(gpu["W"], P0)
+    worst = compare_units(sh, gpu, ref, layout, TOL_FP32)
+    print("worst rel err", max(worst.values()), flush=True)
+    # Adam on bit-identical inputs: feed the GPU's own fp32 G to the oracle
+    st = gpu["stage"]
+    o = oracle.OracleStage(sh, "f32")
+    o.P[:] = P0
+    o.G[:] = gpu["G"]
+    o.adam(step=1, **f32hp())
+    st.adam_step(step=1, **synth.ADAM)
+    torch.cuda.synchronize()
+    for name, a, b in (("p", st.P, o.P), ("m", st.M, o.M), ("v", st.V, o.V)):
+        a = a.cpu().numpy()
+        assert (np.abs(a - b) / np.maximum(np.abs(b), 1e-30)).max() <= TOL_ADAM, name
+    # the working copy is stale after the step
+    with pytest.raises(zpp.ZppError) as e:
+        st.end_unit()
+        st.forward(0, to_dev(xs[0], st.act_dtype))
+    assert e.value.status == -2
+    st.close()
+
+
+def small(arch, dtype, **kw):
+    base = dict(name=f"small_a{arch}_d{dtype}", arch=arch, n_blocks=2, hidden=256, n_heads=2, ffn=512, seq=192,
+                micro_batch=1, unit_mbs=2, compute_dtype=dtype, seed=11)
+    base.update(kw)
+    return StageShape(**base)
+
+
+@pytest.mark.parametrize("arch,dtype,kw", [
+    (0, 0, {}), (1, 0, {}), (0, 0, dict(gelu_mode=1, micro_batch=2, seq=96)),
+    (0, 1, {}), (1, 1, {}), (0, 1, dict(micro_batch=2, seq=160, ffn=768, n_heads=4)),
+    (1, 1, dict(micro_batch=2, seq=96, ffn=320)),
+])
+def test_small_stage_units(arch, dtype, kw):
+    sh = small(arch, dtype, **kw)
+    print(f"unit {sh.name} {kw}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    gpu = run_gpu_unit(sh, P0, xs, dys)
+    if dtype == 1:
+        assert np.array_equal(gpu["W"], ref["W"])  # same RNE cast on both sides
+    worst = compare_units(sh, gpu, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
+    print("worst rel err", max(worst.values()), flush=True)
+
+
+def test_materialize_counters_and_idempotence():
+    sh = small(0, 1)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout)
+    st = zpp.Stage(sh)
+    st.P.copy_(torch.from_numpy(P0))
+    st.materialize_params()
+    w1 = st.region("W").clone()
+    x = to_dev(synth.make_x(sh, 0), st.act_dtype)
+    y1 = st.forward(0, x).clone()
+    st.materialize_params()  # the paper's second gather before the backward phase: must not change anything
+    assert torch.equal(w1.view(torch.int16), st.region("W").view(torch.int16))
+    calls, nbytes = st.counters()
+    assert calls == 2 and nbytes > 0
+    st.end_unit()
+    y2 = st.forward(0, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))  # run-to-run identical
+    st.close()
+
+
+# ------------------------------------------------------------------ operators
+@pytest.mark.parametrize("M,N,K,variant", [
+    (256, 256, 64, 0), (300, 520, 192, 0), (300, 520, 192, 1), (300, 520, 192, 2), (300, 520, 192, 3),
+    (64, 96, 128, -1), (1, 1, 64, 2), (777, 129, 256, -1), (2048, 512, 1024, -1),
+])
+def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
+    print(f"gemm {M}x{N}x{K} variant {variant}", flush=True)
+    a = synth.normal_f32(1, 50, M * K, bf16_exact=True).reshape(M, K)
+    b = synth.normal_f32(1, 51, N * K, std=0.05, bf16_exact=True).reshape(N, K)
+    bias = synth.normal_f32(1, 52, N, bf16_exact=True)
+    res = synth.normal_f32(1, 53, M * N, bf16_exact=True).reshape(M, N)
+    ref = oracle.Ops("f64").linear_fwd(a, b, bias) + res
+    A, B, Bi, R = (to_dev(t, torch.bfloat16) for t in (a, b, bias, res))
+    C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    zpp.op_gemm_bf16_nt(A, B, C, bias=Bi, resid=R, variant=variant)
+    assert rel_err(to_np(C), ref) <= 8e-3  # bf16 output rounding only (2^-9 relative)
+    Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    zpp.op_gemm_bf16_nt(A, B, Cf, variant=variant)
+    ref2 = oracle.Ops("f64").linear_fwd(a, b)
+    assert rel_err(to_np(Cf), ref2) <= 1e-5      # fp32 accumulation of exact bf16 products
+
+
+@pytest.mark.parametrize("dtype,b,s,nh,d", [(torch.float32, 2, 70, 3, 32), (torch.bfloat16, 1, 130, 2, 128),
+                                            (torch.float32, 1, 1, 1, 64)])
+def test_generic_attention_against_oracle(dtype, b, s, nh, d):
+    print(f"attention generic {dtype} b{b} s{s} nh{nh} d{d}", flush=True)
+    h, T = nh * d, b * s
+    qkv = synth.normal_f32(2, 60, T * 3 * h, bf16_exact=(dtype == torch.bfloat16)).reshape(T, 3 * h)
+    da = synth.normal_f32(2, 61, T * h, bf16_exact=(dtype == torch.bfloat16)).reshape(T, h)
+    ops = oracle.Ops("f64")
+    split = lambda t: t.reshape(b, s, nh, d).transpose(0, 2, 1, 3)
+    q, k, v = (split(qkv[:, i * h:(i + 1) * h]) for i in range(3))
+    A, Pr = ops.attention_fwd(q, k, v)
+    dq, dk, dv = ops.attention_bwd(q, k, v, Pr, split(da))
+    merge = lambda t: t.transpose(0, 2, 1, 3).reshape(T, h)
+    QKV, DA = to_dev(qkv, dtype), to_dev(da, dtype)
+    AT = torch.empty(T, h, dtype=dtype, device="cuda")
+    lse = torch.empty(b * nh * s, dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(lse)
+    DQKV = torch.empty_like(QKV)
+    zpp.op_attention_fwd(QKV, AT, lse, b, s, nh, d, impl=0)
+    zpp.op_attention_bwd(QKV, AT, DA, lse, delta, DQKV, b, s, nh, d, impl=0)
+    tol = 1e-2 if dtype == torch.bfloat16 else 1e-5
+    assert rel_err(to_np(AT), merge(A)) <= tol
+    got = to_np(DQKV)
+    for i, r in enumerate((dq, dk, dv)):
+        assert rel_err(got[:, i * h:(i + 1) * h], merge(r)) <= tol
+    S = np.einsum("bnid,bnjd->bnij", q, k) / np.sqrt(d)
+    S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    ref_lse = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(lse.cpu().numpy().reshape(b, nh, s) - ref_lse).max() <= 1e-3

@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library that need no GPU: every symbol the headers declare is
+exported, the layout and size queries agree with the oracle's own layout code and with the paper's
+block-size estimate, the workspace is linear in the unit size, and argument / state / alignment
+errors are reported before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import synth
+import paper_2402_03791_amd as zpp
+from paper_2402_03791_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    for hdr in ("zpp.h", "zpp_ops.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    L = zpp.lib()
+    decl = declared_functions()
+    assert len(decl) >= 20
+    for n in decl:
+        assert hasattr(L, n), f"{n} declared in include/ but not exported"
+    assert set(decl) == set(zpp.EXPORTS)
+
+
+def test_param_count_and_layout_match_oracle():
+    for sh in synth.CONFIGS.values():
+        st = zpp.Stage(sh, allocate=False)
+        assert st.N == oracle.param_count(sh)
+        assert st.layout() == oracle.param_layout(sh)
+        st.close()
+
+
+def test_workspace_is_linear_in_unit_size():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    w = [zpp.Stage(sh.replace(unit_mbs=u), allocate=False).workspace_bytes for u in (1, 2, 3, 16)]
+    step = w[1] - w[0]
+    assert step > 0 and w[2] - w[1] == step and w[3] - w[0] == 15 * step
+    # one (micro-batch, block) slot holds the activations backward needs: 8 [T,h] + 2 [T,f] bf16 tensors
+    T, h, f = sh.tokens, sh.hidden, sh.ffn
+    assert abs(step / sh.n_blocks / ((8 * T * h + 2 * T * f) * 2) - 1) < 0.01
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("arch", 2, -1), ("n_blocks", 0, -1), ("hidden", 102, -1), ("compute_dtype", 3, -1), ("gelu_mode", 2, -1),
+    ("unit_mbs", 0, -1), ("norm_eps", 0.0, -1), ("seq", -5, -1), ("ffn", 1022, -6),
+])
+def test_create_rejects_bad_configs(field, value, status):
+    sh = synth.CONFIGS["cfg1_tiny_gpt_fp32"].replace(**{field: value})
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.Stage(sh, allocate=False)
+    assert e.value.status == status
+
+
+def test_bf16_shape_limits():
+    sh = synth.CONFIGS["cfg2_gpt_1p3b"].replace(seq=100, micro_batch=1)
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.Stage(sh, allocate=False)
+    assert e.value.status == -6
+
+
+def test_state_machine_and_argument_errors_without_launch():
+    sh = synth.CONFIGS["cfg1_tiny_gpt_fp32"]
+    st = zpp.Stage(sh, allocate=False)
+    L = zpp.lib()
+    fake = 0x10000  # never dereferenced: every call below must fail before any launch
+    with pytest.raises(zpp.ZppError) as e:
+        L_status = L.stage_materialize_params(st._h, None)
+        binding._check(L_status)
+    assert e.value.status == -2  # not bound
+    with pytest.raises(zpp.ZppError) as e:
+        st.bind_raw(fake, fake, fake, None, fake, st.workspace_bytes)
+    assert e.value.status == -1
+    with pytest.raises(zpp.ZppError) as e:
+        st.bind_raw(fake, fake + 64, fake, fake, fake, st.workspace_bytes)
+    assert e.value.status == -3
+    with pytest.raises(zpp.ZppError) as e:
+        st.bind_raw(fake, fake, fake, fake, fake, st.workspace_bytes - 1)
+    assert e.value.status == -4
+    st.bind_raw(fake, fake, fake, fake, fake, st.workspace_bytes)
+    for call, status in (
+        (lambda: L.stage_forward(st._h, 0, fake, fake, None), -2),      # before materialise
+        (lambda: L.stage_forward(st._h, sh.unit_mbs, fake, fake, None), -1),
+        (lambda: L.stage_forward(st._h, -1, fake, fake, None), -1),
+        (lambda: L.stage_forward(st._h, 0, None, fake, None), -1),
+        (lambda: L.stage_forward(st._h, 0, fake + 8, fake, None), -3),
+        (lambda: L.stage_backward(st._h, 0, fake, fake, None), -2),
+        (lambda: L.stage_accumulate_grads(st._h, 0, 1.0, None), -2),
+        (lambda: L.stage_accumulate_grads(st._h, 99, 1.0, None), -1),
+    ):
+        with pytest.raises(zpp.ZppError) as e:
+            binding._check(call())
+        assert e.value.status == status, zpp.lib().zpp_last_error()
+    a = binding._adam_struct(**synth.ADAM)
+    for off, cnt, hp, status in ((0, st.N + 4, a, -1), (2, 8, a, -3), (0, 6, a, -3),
+                                 (0, 8, binding._adam_struct(step=0, **synth.ADAM), -1), (0, 8, None, -1)):
+        with pytest.raises(zpp.ZppError) as e:
+            binding._check(L.shard_adam_step(st._h, off, cnt, ctypes.byref(hp) if hp else None, None))
+        assert e.value.status == status
+    assert b"" != L.zpp_last_error()
+    # an empty range is accepted and launches nothing
+    binding._check(L.shard_adam_step(st._h, 0, 0, ctypes.byref(a), None))
+    st.end_unit()
+    st.close()
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        zpp.load_library(str(tmp_path / "libzpp.so"))
