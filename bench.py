@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZeroPP stage hot path on one MI355X.
+
+A step is one pass of the whole hot path over one scheduling unit of synthetic input:
+stage_materialize_params, U x stage_forward, U x (stage_backward + stage_accumulate_grads),
+shard_adam_step (with zero_grad), zpp_stage_end_unit.  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3_gpt_6p2b] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
+PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
+
+
+def model_flops_per_unit(sh) -> float:
+    """Algorithmic work only: GEMMs 2*T*h*(3h+h+2f) forward (LLaMA 2*T*h*(4h+3f)), causal attention
+    2*b*s^2*h forward; backward = 2x forward; norms/activations not counted."""
+    T, h, f = sh.tokens, sh.hidden, sh.ffn
+    gemm = 2.0 * T * h * (4 * h + (2 * f if sh.arch == 0 else 3 * f))
+    attn = 2.0 * sh.micro_batch * sh.seq * sh.seq * h
+    return 3.0 * (gemm + attn) * sh.n_blocks * sh.unit_mbs
+
+
+def cpu_baseline(sh, seconds_hint: float = 20.0):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
+    one block of the stage, one micro-batch, full T/h/f (forward, backward, accumulate)."""
+    import numpy as np
+    import oracle
+    import synth
+    sample = sh.replace(n_blocks=1, unit_mbs=1)
+    st = oracle.OracleStage(sample, "f32")
+    synth.make_params(sample, st.layout(), out=st.P)
+    x, dy = synth.make_x(sample, 0), synth.make_dy(sample, 0)
+    t0 = time.perf_counter()
+    st.materialize()
+    st.forward(0, x)
+    st.backward(0, dy)
+    st.accumulate(0, 1.0)
+    dt = time.perf_counter() - t0
+    flops = model_flops_per_unit(sample)
+    threads = oracle.num_threads()
+    st.close()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"1 of {sh.n_blocks} blocks x 1 of {sh.unit_mbs} micro-batches at full T={sh.tokens}, "
+                      f"h={sh.hidden}, f={sh.ffn}: materialise + forward + backward + accumulate, fp32 oracle"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="cfg3_gpt_6p2b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the path; this build has no multi-GPU leg "
+              "(run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2402_03791_amd as zpp
+
+    sh = synth.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    st = zpp.Stage(sh, device="cuda:0")
+    act = st.act_dtype
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    P0 = synth.make_params(sh, st.layout())
+    st.P.copy_(torch.from_numpy(P0))
+    del P0
+    xs = [torch.from_numpy(synth.make_x(sh, m)).to(dev, act) for m in range(sh.unit_mbs)]
+    dys = [torch.from_numpy(synth.make_dy(sh, m)).to(dev, act) for m in range(sh.unit_mbs)]
+    y = torch.empty_like(xs[0])
+    dx = torch.empty_like(xs[0])
+    stream = torch.cuda.current_stream()
+    adam = dict(synth.ADAM)
+
+    def step(t: int):
+        st.materialize_params(stream)
+        for m in range(sh.unit_mbs):
+            st.forward(m, xs[m], y, stream)
+        for m in range(sh.unit_mbs):
+            st.backward(m, dys[m], dx, stream)
+            st.accumulate_grads(m, 1.0, stream)
+        st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
+        st.end_unit()
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        t += 1
+        step(t)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    flops = model_flops_per_unit(sh)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- one more step with HIP events around every kernel class (same stream), for the roofline
+    zpp.profile_reset()
+    zpp.profile_enable(True)
+    t += 1
+    step(t)
+    torch.cuda.synchronize()
+    prof = zpp.profile_read()
+    zpp.profile_enable(False)
+    zpp.profile_reset()
+
+    def rate(cls, scale):
+        n, ms, work = prof[cls]
+        return (work / (ms * 1e-3) / scale) if ms > 0 else 0.0
+
+    n_gemm, ms_gemm, fl_gemm = prof["gemm"]
+    gemm_tflops = rate("gemm", 1e12)
+    bf16 = sh.compute_dtype == 1
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    roofline = {
+        "kernel": "gemm_bf16_nt_kernel" if bf16 else "gemm_f32_kernel",
+        "bound": "mfma" if bf16 else "alu",
+        "achieved": round(gemm_tflops, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(gemm_tflops / peak, 4),
+        "launches": n_gemm, "avg_launch_ms": round(ms_gemm / max(n_gemm, 1), 4),
+        "flops_per_launch": fl_gemm / max(n_gemm, 1),
+        "traffic": None,
+    }
+    fb_ms = sum(prof[c][1] for c in ("gemm", "attn_fwd", "attn_bwd", "other"))
+    phases = {c: {"launches": prof[c][0], "ms": round(prof[c][1], 3)} for c in prof}
+    phases["gemm"]["TFLOP/s"] = round(gemm_tflops, 1)
+    phases["attn_fwd"]["TFLOP/s"] = round(rate("attn_fwd", 1e12), 1)
+    phases["attn_bwd"]["TFLOP/s"] = round(rate("attn_bwd", 1e12), 1)
+    for c in ("accumulate", "adam", "materialize"):
+        phases[c]["GB/s"] = round(rate(c, 1e9), 1)
+        phases[c]["frac_hbm_peak"] = round(rate(c, 1e9) / PEAK_HBM_GBS, 4)
+    hbm_pass = {
+        "adam_GBps": phases["adam"]["GB/s"], "accumulate_GBps": phases["accumulate"]["GB/s"],
+        "combined_GBps": round((prof["adam"][2] + prof["accumulate"][2]) /
+                               max((prof["adam"][1] + prof["accumulate"][1]) * 1e-3, 1e-12) / 1e9, 1),
+        "peak_GBps": PEAK_HBM_GBS,
+    }
+    hbm_pass["combined_frac"] = round(hbm_pass["combined_GBps"] / PEAK_HBM_GBS, 4)
+
+    out = {
+        "metric": "stage fwd+bwd TFLOP/s per GPU (% bf16 MFMA peak); Adam/accum HBM GB/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
+                   "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
+                   "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N},
+        "model_flops_per_step": flops,
+        "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),
+        "fwd_bwd_TFLOPs": round(flops / (fb_ms * 1e-3) / 1e12, 2) if fb_ms > 0 else None,
+        "wall_s_timed": round(wall, 3),
+        "roofline": roofline,
+        "hbm_pass": hbm_pass,
+        "phases": phases,
+    }
+    if not args.no_cpu_baseline:
+        st.close()
+        del st, xs, dys
+        out["cpu_baseline"] = cpu_baseline(sh)
+        out["gpu_over_cpu"] = round(value / out["cpu_baseline"]["value"], 1)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

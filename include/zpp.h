@@ -173,6 +173,21 @@ void zpp_stage_counters(const zpp_stage *stage, uint64_t *materialize_calls, uin
 zpp_status zpp_stage_region(const zpp_stage *stage, const char *name, int32_t micro_batch, int32_t block,
                             void **ptr, uint64_t *elems, int32_t *elem_bytes);
 
+/* Optional timing of the kernels the stage calls launch, by class, with HIP events recorded on the
+ * caller's stream around each launch (process-wide switch; off by default; adds two event records
+ * per launch).  zpp_profile_read waits for the recorded events and returns, for one class, the
+ * number of bracketed launches, their summed duration and their summed algorithmic work (flops for
+ * GEMM and attention with the causal convention 2*b*s^2*h forward and twice that backward; bytes
+ * for the flat passes: 12 per element accumulate, 28 (+4 with zero_grad) Adam, read+write bytes
+ * materialise; 0 for the rest). */
+enum {
+    ZPP_PROF_GEMM = 0, ZPP_PROF_ATTN_FWD = 1, ZPP_PROF_ATTN_BWD = 2, ZPP_PROF_ACCUMULATE = 3,
+    ZPP_PROF_ADAM = 4, ZPP_PROF_MATERIALIZE = 5, ZPP_PROF_OTHER = 6, ZPP_PROF_CLASSES = 7
+};
+zpp_status zpp_profile_enable(int32_t on);
+void zpp_profile_reset(void);
+zpp_status zpp_profile_read(int32_t cls, uint64_t *launches, double *total_ms, double *work);
+
 const char *zpp_last_error(void);
 const char *zpp_version(void);
 

@@ -15,6 +15,7 @@ EXPORTS = [
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
     "stage_forward", "stage_backward", "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
+    "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
     "zpp_op_flat_accumulate", "zpp_op_flat_materialize",
 ]
@@ -43,6 +44,10 @@ def load_library(path: str | None = None):
     if _lib is not None and path is None:
         return _lib
     path = path or _LIB_PATH
+    # PyTorch owns the device memory and streams this library works on, and its wheel bundles a HIP
+    # runtime with the same soname as the system one.  Import torch first so that one runtime serves
+    # both; the other order leaves the process with two runtimes and no usable device.
+    import torch  # noqa: F401
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is missing: run `python -m paper_2402_03791_amd.build` "
                                 "(there is no fallback path)")
@@ -69,6 +74,10 @@ def load_library(path: str | None = None):
     L.zpp_stage_counters.restype = None
     L.zpp_stage_region.argtypes = [vp, ctypes.c_char_p, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(u64),
                                    ctypes.POINTER(i32)]
+    L.zpp_profile_enable.argtypes = [i32]
+    L.zpp_profile_reset.restype = None
+    L.zpp_profile_read.argtypes = [i32, ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_double),
+                                   ctypes.POINTER(ctypes.c_double)]
     L.zpp_last_error.restype = ctypes.c_char_p
     L.zpp_version.restype = ctypes.c_char_p
     L.zpp_op_gemm_bf16_nt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i32, i32, vp]
@@ -230,6 +239,27 @@ class Stage:
         else:
             dt = torch.bfloat16
         return raw.view(dt)
+
+
+PROF_CLASSES = ["gemm", "attn_fwd", "attn_bwd", "accumulate", "adam", "materialize", "other"]
+
+
+def profile_enable(on: bool):
+    _check(lib().zpp_profile_enable(int(on)))
+
+
+def profile_reset():
+    lib().zpp_profile_reset()
+
+
+def profile_read():
+    """{class: (launches, total_ms, work)} for everything bracketed since the last reset."""
+    out = {}
+    n, ms, w = ctypes.c_uint64(), ctypes.c_double(), ctypes.c_double()
+    for i, name in enumerate(PROF_CLASSES):
+        _check(lib().zpp_profile_read(i, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(w)))
+        out[name] = (n.value, ms.value, w.value)
+    return out
 
 
 # ---- operator-level entry points (include/zpp_ops.h) ----------------------------------------------

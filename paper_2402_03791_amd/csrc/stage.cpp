@@ -54,6 +54,46 @@ struct Region {
 
 enum MbState { MB_IDLE = 0, MB_FWD = 1, MB_BWD = 2, MB_ACC = 3 };
 
+// ---- optional per-kernel-class timing with HIP events on the caller's stream -------------------
+struct ProfRec {
+    int cls;
+    double work;
+    hipEvent_t e0, e1;
+};
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+std::vector<hipEvent_t> g_event_pool;
+
+hipEvent_t prof_event()
+{
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+struct ProfScope {
+    bool on;
+    ProfRec r;
+    hipStream_t st;
+    ProfScope(int cls, double work, hipStream_t s) : on(g_prof_on), st(s)
+    {
+        if (!on) return;
+        r = {cls, work, prof_event(), prof_event()};
+        (void)hipEventRecord(r.e0, st);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(r.e1, st);
+        g_prof.push_back(r);
+    }
+};
+
 }  // namespace
 
 struct zpp_stage {
@@ -214,6 +254,12 @@ void plan_workspace(zpp_stage *s)
     s->ws_bytes = cur;
 }
 
+#define ZPP_OTHER(expr)                                   \
+    do {                                                  \
+        ProfScope _prof(ZPP_PROF_OTHER, 0.0, st);         \
+        ZPP_TRY(expr);                                    \
+    } while (0)
+
 #define ZPP_TRY(expr)                                                                                    \
     do {                                                                                                 \
         hipError_t _e = (expr);                                                                          \
@@ -226,6 +272,7 @@ void plan_workspace(zpp_stage *s)
 hipError_t linear_fwd(zpp_stage *s, const void *x, int blk, const char *w, int64_t in, int64_t out, void *y,
                       GemmEpi epi, hipStream_t st)
 {
+    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
     if (s->dt == DT_BF16)
         return launch_gemm_bf16_nt(s->T, out, in, x, in, s->Wp(blk, w), in, y, out, epi, st);
     return launch_gemm_f32(s->T, out, in, (const float *)x, in, 1, (const float *)s->Wp(blk, w), in, 1,
@@ -236,6 +283,7 @@ hipError_t linear_fwd(zpp_stage *s, const void *x, int blk, const char *w, int64
 hipError_t linear_dx(zpp_stage *s, const void *dy, int blk, const char *w, int64_t in, int64_t out, void *dx,
                      GemmEpi epi, hipStream_t st)
 {
+    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
     if (s->dt == DT_BF16)  // uses the transposed working copy W^T[in,out] so both operands are K-contiguous
         return launch_gemm_bf16_nt(s->T, in, out, dy, out, s->Wtp(blk, w), out, dx, in, epi, st);
     return launch_gemm_f32(s->T, in, out, (const float *)dy, out, 1, (const float *)s->Wp(blk, w), 1, in,
@@ -252,14 +300,20 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
     hipError_t e;
     if (s->dt == DT_BF16) {
         void *tA = s->tp("tA"), *tB = s->tp("tB");
-        if ((e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st)) != hipSuccess) return e;
-        if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
+        {
+            ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
+            if ((e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st)) != hipSuccess) return e;
+            if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
+        }
+        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
         e = launch_gemm_bf16_nt(out, in, s->T, tA, s->T, tB, s->T, s->Sp(blk, w), in, epi, st);
     } else {
+        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
         e = launch_gemm_f32(out, in, s->T, (const float *)dy, 1, out, (const float *)x, 1, in, s->Sp(blk, w),
                             in, epi, st);
     }
     if (e != hipSuccess) return e;
+    ProfScope prof2(ZPP_PROF_OTHER, 0.0, st);
     if (bias)
         e = launch_colreduce(s->dt, COLRED_SUM, dy, nullptr, nullptr, nullptr, s->T, out, out, s->Sp(blk, bias),
                              nullptr, (float *)s->tp("colred"), st);
@@ -268,6 +322,8 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
 
 hipError_t attention_fwd(zpp_stage *s, const void *qkv, void *attn, float *lse, hipStream_t st)
 {
+    // causal convention: two matmuls over the lower triangle, 2*b*s^2*h flops
+    ProfScope prof(ZPP_PROF_ATTN_FWD, 2.0 * s->c.micro_batch * (double)s->c.seq * s->c.seq * s->h, st);
     if (s->dt == DT_BF16 && attn_mfma_supported(s->c.seq, s->d))
         return launch_attn_fwd(s->dt, qkv, attn, lse, s->c.micro_batch, s->c.seq, s->nh, s->d, st);
     return launch_attn_simple_fwd(s->dt, qkv, attn, lse, s->c.micro_batch, s->c.seq, s->nh, s->d, st);
@@ -277,6 +333,7 @@ hipError_t attention_bwd(zpp_stage *s, const void *qkv, const void *attn, const 
                          void *dqkv, hipStream_t st)
 {
     float *delta = (float *)s->tp("delta");
+    ProfScope prof(ZPP_PROF_ATTN_BWD, 4.0 * s->c.micro_batch * (double)s->c.seq * s->c.seq * s->h, st);
     if (s->dt == DT_BF16 && attn_mfma_supported(s->c.seq, s->d))
         return launch_attn_bwd(s->dt, qkv, attn, dattn, lse, delta, dqkv, s->c.micro_batch, s->c.seq, s->nh,
                                s->d, st);
@@ -396,13 +453,14 @@ zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
     hipStream_t st = (hipStream_t)hip_stream;
-    ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
     uint64_t bytes = s->N * (4 + s->esz);
+    if (s->dt == DT_BF16) bytes += s->Nmat * 6;
+    ProfScope prof(ZPP_PROF_MATERIALIZE, (double)bytes, st);
+    ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
     if (s->dt == DT_BF16) {
         for (auto &kv : s->wt) {
             const auto &w = kv.second;
             ZPP_TRY(launch_transpose_cast(s->P + w.src_off, s->ws + s->rWt.off + w.dst_off * 2, w.rows, w.cols, st));
-            bytes += w.rows * w.cols * 6;
         }
     }
     if (s->c.arch == ZPP_ARCH_LLAMA && !s->rope_ready) {
@@ -438,20 +496,20 @@ zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void 
         void *g = s->stash(mb, blk, "g");
         float *lse = (float *)s->stash(mb, blk, "lse");
 
-        ZPP_TRY(launch_norm_fwd(s->dt, kind, xin, s->Wp(blk, gpt ? "ln1.gamma" : "norm1.gamma"),
+        ZPP_OTHER(launch_norm_fwd(s->dt, kind, xin, s->Wp(blk, gpt ? "ln1.gamma" : "norm1.gamma"),
                                 gpt ? s->Wp(blk, "ln1.beta") : nullptr, T, h, s->c.norm_eps, n1, mean1, rstd1,
                                 blk == 0 ? xs : nullptr, st));
         GemmEpi e_qkv;
         if (gpt) e_qkv.bias = s->Wp(blk, "attn.bqkv");
         ZPP_TRY(linear_fwd(s, n1, blk, "attn.wqkv", h, 3 * h, qkv, e_qkv, st));
         if (!gpt)
-            ZPP_TRY(launch_rope(s->dt, qkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, +1, st));
+            ZPP_OTHER(launch_rope(s->dt, qkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, +1, st));
         ZPP_TRY(attention_fwd(s, qkv, attn, lse, st));
         GemmEpi e_o;
         if (gpt) e_o.bias = s->Wp(blk, "attn.bo");
         e_o.resid = xs;
         ZPP_TRY(linear_fwd(s, attn, blk, "attn.wo", h, h, x1, e_o, st));
-        ZPP_TRY(launch_norm_fwd(s->dt, kind, x1, s->Wp(blk, gpt ? "ln2.gamma" : "norm2.gamma"),
+        ZPP_OTHER(launch_norm_fwd(s->dt, kind, x1, s->Wp(blk, gpt ? "ln2.gamma" : "norm2.gamma"),
                                 gpt ? s->Wp(blk, "ln2.beta") : nullptr, T, h, s->c.norm_eps, n2, mean2, rstd2,
                                 nullptr, st));
         GemmEpi e_2;
@@ -468,7 +526,7 @@ zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void 
         } else {
             // wgate and wup are adjacent in the layout: one GEMM against the [2f, h] matrix gives [gate | up]
             ZPP_TRY(linear_fwd(s, n2, blk, "mlp.wgate", h, f1, u, GemmEpi(), st));
-            ZPP_TRY(launch_swiglu_fwd(s->dt, u, g, T, f, st));
+            ZPP_OTHER(launch_swiglu_fwd(s->dt, u, g, T, f, st));
             ZPP_TRY(linear_fwd(s, g, blk, "mlp.wdown", f, h, out, e_2, st));
         }
     }
@@ -518,24 +576,24 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
             void *dact = s->tp("dact");
             ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.wdown", nullptr, f, h, st));
             ZPP_TRY(linear_dx(s, dcur, blk, "mlp.wdown", f, h, dact, GemmEpi(), st));
-            ZPP_TRY(launch_swiglu_bwd(s->dt, u, dact, du, T, f, st));
+            ZPP_OTHER(launch_swiglu_bwd(s->dt, u, dact, du, T, f, st));
             ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.wgate", nullptr, h, f1, st));
             ZPP_TRY(linear_dx(s, du, blk, "mlp.wgate", h, f1, dn, GemmEpi(), st));
         }
         const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
-        ZPP_TRY(launch_norm_bwd(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h, st));
-        ZPP_TRY(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
+        ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h, st));
+        ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
                                  s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, colred, st));
         // ---- attention branch
         ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
         ZPP_TRY(linear_dx(s, dx1, blk, "attn.wo", h, h, dattn, GemmEpi(), st));
         ZPP_TRY(attention_bwd(s, qkv, attn, dattn, lse, dqkv, st));
         if (!gpt)
-            ZPP_TRY(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
+            ZPP_OTHER(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
         ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
         ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
-        ZPP_TRY(launch_norm_bwd(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h, st));
-        ZPP_TRY(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
+        ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h, st));
+        ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
                                  s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, colred, st));
         dcur = dout;
     }
@@ -550,7 +608,10 @@ zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *h
     if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
     if (s->mb_state[mb] != MB_BWD || s->pending_acc != mb)
         return fail(ZPP_ERR_STATE, "stage_accumulate_grads(%d) needs stage_backward(%d) right before it", mb, mb);
-    ZPP_TRY(launch_accumulate(s->G, (const float *)(s->ws + s->rS.off), s->N, scale, (hipStream_t)hip_stream));
+    {
+        ProfScope prof(ZPP_PROF_ACCUMULATE, 12.0 * s->N, (hipStream_t)hip_stream);
+        ZPP_TRY(launch_accumulate(s->G, (const float *)(s->ws + s->rS.off), s->N, scale, (hipStream_t)hip_stream));
+    }
     s->mb_state[mb] = MB_ACC;
     s->pending_acc = -1;
     return ZPP_OK;
@@ -583,8 +644,11 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
     a.c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
     a.decoupled = hp->decoupled_wd ? 1 : 0;
     a.zero_grad = hp->zero_grad ? 1 : 0;
-    ZPP_TRY(launch_adam(s->P + offset, s->M + offset, s->V + offset, s->G + offset, count, a,
-                        (hipStream_t)hip_stream));
+    {
+        ProfScope prof(ZPP_PROF_ADAM, (a.zero_grad ? 32.0 : 28.0) * count, (hipStream_t)hip_stream);
+        ZPP_TRY(launch_adam(s->P + offset, s->M + offset, s->V + offset, s->G + offset, count, a,
+                            (hipStream_t)hip_stream));
+    }
     if (count) s->materialized = false;
     return ZPP_OK;
 }
@@ -624,6 +688,41 @@ zpp_status zpp_stage_region(const zpp_stage *s, const char *name, int32_t mb, in
     *ptr = s->ws + base + r.off;
     if (elems) *elems = r.elems;
     if (elem_bytes) *elem_bytes = r.esz;
+    return ZPP_OK;
+}
+
+zpp_status zpp_profile_enable(int32_t on)
+{
+    g_prof_on = on != 0;
+    return ZPP_OK;
+}
+
+void zpp_profile_reset(void)
+{
+    for (auto &r : g_prof) {
+        g_event_pool.push_back(r.e0);
+        g_event_pool.push_back(r.e1);
+    }
+    g_prof.clear();
+}
+
+zpp_status zpp_profile_read(int32_t cls, uint64_t *launches, double *total_ms, double *work)
+{
+    if (cls < 0 || cls >= ZPP_PROF_CLASSES) return fail(ZPP_ERR_ARG, "profile class %d out of range", cls);
+    uint64_t n = 0;
+    double ms = 0.0, w = 0.0;
+    for (auto &r : g_prof) {
+        if (r.cls != cls) continue;
+        if (hipEventSynchronize(r.e1) != hipSuccess) return fail(ZPP_ERR_DEVICE, "event synchronize failed");
+        float t = 0.0f;
+        if (hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) return fail(ZPP_ERR_DEVICE, "event elapsed failed");
+        ms += t;
+        w += r.work;
+        ++n;
+    }
+    if (launches) *launches = n;
+    if (total_ms) *total_ms = ms;
+    if (work) *work = w;
     return ZPP_OK;
 }
 

@@ -226,3 +226,35 @@ def test_generic_attention_against_oracle(dtype, b, s, nh, d):
     S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
     ref_lse = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
     assert np.abs(lse.cpu().numpy().reshape(b, nh, s) - ref_lse).max() <= 1e-3
+
+
+@pytest.mark.parametrize("b,s,nh", [(1, 128, 1), (1, 256, 2), (2, 384, 3)])
+def test_mfma_attention_against_oracle(b, s, nh):
+    print(f"attention mfma b{b} s{s} nh{nh}", flush=True)
+    d = 128
+    h, T = nh * d, b * s
+    qkv = synth.normal_f32(3, 70, T * 3 * h, bf16_exact=True).reshape(T, 3 * h)
+    da = synth.normal_f32(3, 71, T * h, std=0.1, bf16_exact=True).reshape(T, h)
+    ops = oracle.Ops("f64")
+    split = lambda t: t.reshape(b, s, nh, d).transpose(0, 2, 1, 3)
+    merge = lambda t: t.transpose(0, 2, 1, 3).reshape(T, h)
+    q, k, v = (split(qkv[:, i * h:(i + 1) * h]) for i in range(3))
+    A, Pr = ops.attention_fwd(q, k, v)
+    dq, dk, dv = ops.attention_bwd(q, k, v, Pr, split(da))
+    QKV, DA = to_dev(qkv, torch.bfloat16), to_dev(da, torch.bfloat16)
+    AT = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(b * nh * s, dtype=torch.float32, device="cuda")
+    delta = torch.empty_like(lse)
+    DQKV = torch.empty_like(QKV)
+    zpp.op_attention_fwd(QKV, AT, lse, b, s, nh, d, impl=1)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(AT), merge(A)) <= 1e-2
+    S = np.einsum("bnid,bnjd->bnij", q, k) / np.sqrt(d)
+    S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    ref_lse = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    assert np.abs(lse.cpu().numpy().reshape(b, nh, s) - ref_lse).max() <= 2e-3
+    zpp.op_attention_bwd(QKV, AT, DA, lse, delta, DQKV, b, s, nh, d, impl=1)
+    torch.cuda.synchronize()
+    got = to_np(DQKV)
+    for i, r in enumerate((dq, dk, dv)):
+        assert rel_err(got[:, i * h:(i + 1) * h], merge(r)) <= 1.5e-2, i
