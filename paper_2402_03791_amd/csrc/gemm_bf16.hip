@@ -11,6 +11,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <utility>
+
 namespace zpp {
 
 constexpr int kBK = 64;
@@ -19,6 +21,7 @@ struct EpiBf16 {
     const bf16 *bias, *resid, *aux;
     bf16 *out2;
     int act, gelu_mode, out_f32;
+    unsigned long long *dbg;  // optional [blocks][waves][4] cycle counters (development aid), else null
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -26,6 +29,122 @@ __device__ __forceinline__ int lds_off(int row, int chunk)
     // element offset of 16-byte chunk `chunk` (0..7) of tile row `row`
     const int sw = (row & 7) ^ ((row >> 3) & 1);
     return row * kBK + ((chunk ^ sw) << 3);
+}
+
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), so that register
+// arrays are only ever indexed with constants.
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
+
+// Element-wise tail of the epilogue for one output element.
+__device__ __forceinline__ void epi_store_one(float v, int64_t o_idx, void *__restrict__ Cv, const EpiBf16 &epi)
+{
+    if (epi.resid) v += (float)epi.resid[o_idx];
+    if (epi.act == ACT_DGELU_MUL) v *= gelu_bwd((float)epi.aux[o_idx], epi.gelu_mode);
+    if (epi.out_f32) {
+        reinterpret_cast<float *>(Cv)[o_idx] = v;
+    } else {
+        const bf16 o = (bf16)v;
+        reinterpret_cast<bf16 *>(Cv)[o_idx] = o;
+        // the activation is applied to the value that was stored (and that backward re-reads)
+        if (epi.act == ACT_GELU_DUAL) epi.out2[o_idx] = (bf16)gelu_fwd((float)o, epi.gelu_mode);
+    }
+}
+
+// Epilogue shared by the GEMM kernels.  The accumulator layout of the 32x32 MFMA gives a lane one
+// column and scattered rows, which would make every global store a 2-byte-per-lane scatter.  So each
+// wave transposes its tile through its own slice of LDS, 32 rows at a time (fp32, bias already
+// added), and then every lane owns 8 consecutive columns of a row: residual / GeLU inputs are read
+// and results written with 16-byte accesses, a full 128-byte line per 8 lanes.
+// acc[i][j][e] of lane l is C[m_wave + i*32 + (e/4)*8 + (l/32)*4 + e%4, n_wave + j*32 + l%32].
+// Must be entered after a work-group barrier that ends all use of the operand tiles in LDS.
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int wave, int lane,
+                                         void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
+                                         int64_t N, int64_t m_wave, int64_t n_wave)
+{
+    constexpr int WN = NT * 32;
+    constexpr int STRIDE = WN + 8;          // floats; 4 rows apart = half the banks apart
+    constexpr int CH = WN / 8;              // 8-column chunks per row
+    constexpr int ROWS_PER_PASS = 64 / CH;  // rows covered by the 64 lanes at once
+    constexpr int PASSES = 32 / ROWS_PER_PASS;
+    float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * STRIDE);
+    const int khalf = lane >> 5, c32 = lane & 31;
+    const bool vec_ok = (ldc % 8 == 0) && (reinterpret_cast<uintptr_t>(Cv) % 16 == 0) &&
+                        (!epi.resid || reinterpret_cast<uintptr_t>(epi.resid) % 16 == 0) &&
+                        (!epi.aux || reinterpret_cast<uintptr_t>(epi.aux) % 16 == 0) &&
+                        (!epi.out2 || reinterpret_cast<uintptr_t>(epi.out2) % 16 == 0);
+    float bias[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int64_t n = n_wave + j * 32 + c32;
+        bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
+    }
+    static_for<MT>([&](auto ii) {
+        constexpr int i = decltype(ii)::value;
+        static_for<NT>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                stage[((e >> 2) * 8 + khalf * 4 + (e & 3)) * STRIDE + j * 32 + c32] = acc[i][j][e] + bias[j];
+        });
+        // the slice is private to this wave; LDS operations of a wave complete in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = p * ROWS_PER_PASS + lane / CH;
+            const int c8 = lane % CH;
+            const int64_t m = m_wave + i * 32 + row;
+            const int64_t n = n_wave + c8 * 8;
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c8 * 8);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c8 * 8 + 4);
+            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            if (m >= M || n >= N) continue;
+            const int64_t o_idx = m * ldc + n;
+            if (vec_ok && n + 8 <= N) {
+                if (epi.resid) {
+                    const bf16x8 r = *reinterpret_cast<const bf16x8 *>(epi.resid + o_idx);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] += (float)r[k];
+                }
+                if (epi.act == ACT_DGELU_MUL) {
+                    const bf16x8 u = *reinterpret_cast<const bf16x8 *>(epi.aux + o_idx);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) v[k] *= gelu_bwd((float)u[k], epi.gelu_mode);
+                }
+                if (epi.out_f32) {
+                    float *cf = reinterpret_cast<float *>(Cv) + o_idx;
+                    *reinterpret_cast<f32x4 *>(cf) = f32x4{v[0], v[1], v[2], v[3]};
+                    *reinterpret_cast<f32x4 *>(cf + 4) = f32x4{v[4], v[5], v[6], v[7]};
+                } else {
+                    bf16x8 o;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) o[k] = (bf16)v[k];
+                    *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16 *>(Cv) + o_idx) = o;
+                    if (epi.act == ACT_GELU_DUAL) {
+                        bf16x8 g;
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) g[k] = (bf16)gelu_fwd((float)o[k], epi.gelu_mode);
+                        *reinterpret_cast<bf16x8 *>(epi.out2 + o_idx) = g;
+                    }
+                }
+            } else {
+                for (int k = 0; k < 8 && n + k < N; ++k) epi_store_one(v[k], o_idx + k, Cv, epi);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    });
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -144,36 +263,518 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
         __syncthreads();
     }
 
-    // ---- epilogue.  acc[i][j][e] of lane l is C[row, col] with
-    //   row = i*32 + (e/4)*8 + (l/32)*4 + e%4,  col = j*32 + l%32   (inside the wave's WM x WN tile)
-    float *Cf = reinterpret_cast<float *>(Cv);
-    bf16 *Cb = reinterpret_cast<bf16 *>(Cv);
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Second generation: operand tiles go from global memory straight into LDS (global_load_lds, 16
+// bytes per lane, no staging registers and no ds_write), and the MFMA operands of K sub-step ks+1
+// are fetched from LDS while sub-step ks is being multiplied.  Each load instruction of a wave
+// fills 8 consecutive tile rows (1 KB): lane i lands at byte 16*i, so lane i fetches the chunk the
+// swizzle assigns to that slot.
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void gbl_void_t;
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_dl_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;  // load instructions per wave per K-step
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);  // [2][BM*64]
+    bf16 *Bs = As + 2 * BM * kBK;                   // [2][BN*64]
+
+    int pid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (pid % per_group) % gsz;
+    const int tn = (pid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    const int lrow = lane >> 3, lch = lane & 7;
+    const bf16 *a_g[A_I];
+    const bf16 *b_g[B_I];
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int64_t n = n0 + wn * WN + j * 32 + (lane & 31);
-        if (n >= N) continue;
-        const float bias = epi.bias ? (float)epi.bias[n] : 0.0f;
+    for (int j = 0; j < A_I; ++j) {
+        const int row = (wave * A_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t gm = m0 + row;
+        if (gm > M - 1) gm = M - 1;
+        a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
+    }
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
+    for (int j = 0; j < B_I; ++j) {
+        const int row = (wave * B_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t gn = n0 + row;
+        if (gn > N - 1) gn = N - 1;
+        b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
+    }
+
+    f32x16 acc[MT][NT];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t m = m0 + wm * WM + i * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                if (m >= M) continue;
-                const int64_t idx = m * ldc + n;
-                float v = acc[i][j][e] + bias;
-                if (epi.resid) v += (float)epi.resid[idx];
-                if (epi.act == ACT_DGELU_MUL) v *= gelu_bwd((float)epi.aux[idx], epi.gelu_mode);
-                if (epi.out_f32) {
-                    Cf[idx] = v;
-                } else {
-                    const bf16 o = (bf16)v;
-                    Cb[idx] = o;
-                    // the activation is applied to the value that was stored (and that backward re-reads)
-                    if (epi.act == ACT_GELU_DUAL) epi.out2[idx] = (bf16)gelu_fwd((float)o, epi.gelu_mode);
-                }
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = (int)(K / kBK);
+
+    auto issue_loads = [&](int kt, int buf) {
+        const int64_t ko = (int64_t)kt * kBK;
+        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;
+        bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
+#pragma unroll
+        for (int j = 0; j < A_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 8 * kBK), 16, 0, 0);
+    };
+
+    const int a_row0 = wm * WM + (lane & 31);
+    const int b_row0 = wn * WN + (lane & 31);
+    const int khalf = lane >> 5;
+
+    auto compute = [&](int buf) {
+        const bf16 *as = As + buf * BM * kBK;
+        const bf16 *bs = Bs + buf * BN * kBK;
+        bf16x8 af[2][MT], bfr[2][NT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            af[0][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, khalf));
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            bfr[0][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, khalf));
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) {
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+                    af[nxt][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, (ks + 1) * 2 + khalf));
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, (ks + 1) * 2 + khalf));
             }
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    issue_loads(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + 1 < nk) issue_loads(kt + 1, (kt + 1) & 1);
+        compute(kt & 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Third generation: same data movement as above, but the K loop is rotated so that the MFMAs of
+// the last K sub-step of a tile overlap the first LDS operand reads of the next tile (right after
+// the barrier), and the instruction order inside each region is pinned with scheduling-group
+// barriers: one LDS read for every two MFMAs.  Meant for one wave per SIMD with a large
+// accumulator tile (lowest LDS traffic per flop), where nothing else hides LDS latency.
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);
+    bf16 *Bs = As + 2 * BM * kBK;
+
+    int pid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (pid % per_group) % gsz;
+    const int tn = (pid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    const int lrow = lane >> 3, lch = lane & 7;
+    const bf16 *a_g[A_I];
+    const bf16 *b_g[B_I];
+#pragma unroll
+    for (int j = 0; j < A_I; ++j) {
+        const int row = (wave * A_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t gm = m0 + row;
+        if (gm > M - 1) gm = M - 1;
+        a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
+    }
+#pragma unroll
+    for (int j = 0; j < B_I; ++j) {
+        const int row = (wave * B_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t gn = n0 + row;
+        if (gn > N - 1) gn = N - 1;
+        b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
+    }
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = (int)(K / kBK);
+
+    auto issue_loads = [&](int kt, int buf) {
+        const int64_t ko = (int64_t)kt * kBK;
+        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;
+        bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
+#pragma unroll
+        for (int j = 0; j < A_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 8 * kBK), 16, 0, 0);
+    };
+
+    const int a_row0 = wm * WM + (lane & 31);
+    const int b_row0 = wn * WN + (lane & 31);
+    const int khalf = lane >> 5;
+
+    bf16x8 af[2][MT], bfr[2][NT];
+    auto read_frags = [&](int buf, int ks, int slot) {
+        const bf16 *as = As + buf * BM * kBK;
+        const bf16 *bs = Bs + buf * BN * kBK;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, ks * 2 + khalf));
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, ks * 2 + khalf));
+    };
+    auto mfma_block = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int READS = MT + NT;         // LDS reads per sub-step
+    constexpr int MFMAS = MT * NT;         // MFMAs per sub-step
+    constexpr int MPR = MFMAS / READS;     // MFMAs per LDS read in the interleave
+
+    unsigned long long dbg_vm = 0, dbg_bar = 0, dbg_start = 0;
+    if (epi.dbg) dbg_start = __builtin_amdgcn_s_memtime();
+    issue_loads(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    issue_loads(nk > 1 ? 1 : 0, 1);
+    read_frags(0, 0, 0);
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        // sub-steps 0..2 of tile kt, each overlapping the operand reads of the next sub-step
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) {
+            read_frags(buf, ks + 1, (ks + 1) & 1);
+            mfma_block(ks & 1);
+        }
+#pragma unroll
+        for (int r = 0; r < 3 * READS; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 LDS read
+            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);  // MPR MFMAs
+        }
+        // tile kt+1 has landed and every wave is done reading tile kt
+        unsigned long long t0 = 0, t1 = 0, t2 = 0;
+        if (epi.dbg) t0 = __builtin_amdgcn_s_memtime();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (epi.dbg) t1 = __builtin_amdgcn_s_memtime();
+        __syncthreads();
+        if (epi.dbg) {
+            t2 = __builtin_amdgcn_s_memtime();
+            dbg_vm += t1 - t0;
+            dbg_bar += t2 - t1;
+        }
+        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
+        issue_loads(nxt2, buf);
+        read_frags(buf ^ 1, 0, 0);  // first operands of tile kt+1 (harmless garbage after the last tile)
+        mfma_block(1);              // sub-step 3 of tile kt
+#pragma unroll
+        for (int r = 0; r < READS; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, (A_I + B_I) / READS, 0);  // global->LDS loads
+            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
+    unsigned long long dbg_loop_end = 0;
+    if (epi.dbg) dbg_loop_end = __builtin_amdgcn_s_memtime();
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+    if (epi.dbg && lane == 0) {
+        unsigned long long *d = epi.dbg + ((size_t)blockIdx.x * NW + wave) * 4;
+        d[0] = dbg_loop_end - dbg_start;
+        d[1] = dbg_vm;
+        d[2] = dbg_bar;
+        d[3] = __builtin_amdgcn_s_memtime() - dbg_loop_end;
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t launch_variant_p(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_p_kernel<BM, BN, WGM, WGN>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
+                                                                 tiles_n);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fourth generation: a ring of four LDS stages of K = 32 each.  With two stages of K = 64 a tile
+// is requested only one K-step (about 2000 MFMA cycles) before it is needed, which is less than
+// the HBM/L2 round trip; with four half-size stages three are in flight (96 KB per CU) and a tile
+// has three steps (about 3000 cycles) to arrive, for the same LDS footprint.  One barrier per
+// stage; the MFMAs of each K sub-step overlap the LDS operand reads of the next one, across the
+// barrier as well.  LDS rows are 64 bytes (32 bf16); the 16-byte chunk index is XOR-swizzled with
+// bits 2..3 of the row so that 16 consecutive rows of one chunk column hit 16 different bank groups.
+constexpr int kRK = 32;      // K per ring stage
+constexpr int kRStages = 4;
+
+__device__ __forceinline__ int ring_off(int row, int chunk)
+{
+    // element offset of 16-byte chunk `chunk` (0..3) of tile row `row`
+    return row * kRK + ((chunk ^ ((row >> 2) & 3)) << 3);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;  // load instructions (16 rows each) per wave per stage
+    constexpr int LPS = A_I + B_I;                         // loads per stage per wave
+    constexpr int STAGE_ELEMS = (BM + BN) * kRK;
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile/waves mismatch");
+    static_assert(2 * LPS <= 63, "vmcnt range");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *ring = reinterpret_cast<bf16 *>(smem_raw);  // [4][A: BM*32 | B: BN*32]
+
+    int pid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (pid % per_group) % gsz;
+    const int tn = (pid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // lane i of a load instruction lands at LDS byte 16*i: row i/4 of the 16-row group, slot i%4
+    const int lrow = lane >> 2, lslot = lane & 3;
+    const bf16 *a_g[A_I];
+    const bf16 *b_g[B_I];
+#pragma unroll
+    for (int j = 0; j < A_I; ++j) {
+        const int row = (wave * A_I + j) * 16 + lrow;
+        int64_t gm = m0 + row;
+        if (gm > M - 1) gm = M - 1;
+        a_g[j] = A + gm * lda + ((lslot ^ ((row >> 2) & 3)) << 3);
+    }
+#pragma unroll
+    for (int j = 0; j < B_I; ++j) {
+        const int row = (wave * B_I + j) * 16 + lrow;
+        int64_t gn = n0 + row;
+        if (gn > N - 1) gn = N - 1;
+        b_g[j] = B + gn * ldb + ((lslot ^ ((row >> 2) & 3)) << 3);
+    }
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = (int)(K / kRK);
+
+    auto issue_loads = [&](int kt) {
+        const int st = kt < nk ? kt : nk - 1;  // past the end: reload the last stage into a free slot
+        const int64_t ko = (int64_t)st * kRK;
+        bf16 *as = ring + (kt & (kRStages - 1)) * STAGE_ELEMS + wave * A_I * 16 * kRK;
+        bf16 *bs = ring + (kt & (kRStages - 1)) * STAGE_ELEMS + BM * kRK + wave * B_I * 16 * kRK;
+#pragma unroll
+        for (int j = 0; j < A_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 16 * kRK), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_I; ++j)
+            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 16 * kRK), 16, 0, 0);
+    };
+
+    const int a_row0 = wm * WM + (lane & 31);
+    const int b_row0 = wn * WN + (lane & 31);
+    const int khalf = lane >> 5;
+
+    bf16x8 af[2][MT], bfr[2][NT];
+    auto read_frags = [&](int kt, int ks, int slot) {
+        const bf16 *as = ring + (kt & (kRStages - 1)) * STAGE_ELEMS;
+        const bf16 *bs = as + BM * kRK;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + ring_off(a_row0 + i * 32, ks * 2 + khalf));
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + ring_off(b_row0 + j * 32, ks * 2 + khalf));
+    };
+    auto mfma_block = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int READS = MT + NT;
+    constexpr int MFMAS = MT * NT;
+    constexpr int MPR = MFMAS / READS > 0 ? MFMAS / READS : 1;
+
+    issue_loads(0);
+    issue_loads(1);
+    issue_loads(2);
+    wait_vmcnt<2 * LPS>();
+    __syncthreads();
+    read_frags(0, 0, 0);
+
+    for (int kt = 0; kt < nk; ++kt) {
+        // after a barrier: slot (kt+3)%4 held stage kt-1, which every wave has finished reading
+        issue_loads(kt + 3);
+        read_frags(kt, 1, 1);
+        mfma_block(0);
+#pragma unroll
+        for (int r = 0; r < READS; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (r < LPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+        }
+        // stage kt+1 must have landed (only stages kt+2 and kt+3 may still be in flight)
+        wait_vmcnt<2 * LPS>();
+        __syncthreads();
+        read_frags(kt + 1, 0, 0);  // after the last stage this reads a stale slot; the values are unused
+        mfma_block(1);
+#pragma unroll
+        for (int r = 0; r < READS; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+        }
+    }
+    wait_vmcnt<0>();
+    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t launch_variant_r(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t lds = (size_t)kRStages * (BM + BN) * kRK * sizeof(bf16);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_r_kernel<BM, BN, WGM, WGN>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
+                                                                 tiles_n);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t launch_variant_dl(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_dl_kernel<BM, BN, WGM, WGN>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
+                                                                 tiles_n);
+    return hipGetLastError();
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -210,22 +811,33 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (M == 0 || N == 0) return hipSuccess;
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32};
+              epi.act, epi.gelu_mode, epi.out_f32, (unsigned long long *)epi.dbg};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     int variant = g_forced_variant;
     if (variant < 0) {
-        // Pick the largest tile that still gives every CU (256 of them) a work-group.
+        // 256x256 tiles (8 waves) have the lowest LDS and L2 traffic per flop but need whole rounds of
+        // the 256 CUs; otherwise 128x128 tiles (up to 3 work-groups per CU) quantise better.
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
-        if (t256 >= 256 * 2) variant = 0;
-        else if (t128x256 >= 256) variant = 1;
-        else variant = 2;
+        variant = (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024)) ? 11 : 12;
     }
     switch (variant) {
     case 0: return launch_variant<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 1: return launch_variant<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 2: return launch_variant<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 3: return launch_variant<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 4: return launch_variant_dl<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 5: return launch_variant_dl<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 6: return launch_variant_dl<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 7: return launch_variant_dl<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 8: return launch_variant_dl<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 9: return launch_variant_p<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 10: return launch_variant_p<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 11: return launch_variant_p<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 12: return launch_variant_p<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 13: return launch_variant_r<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 14: return launch_variant_r<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 15: return launch_variant_r<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 16: return launch_variant_r<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }

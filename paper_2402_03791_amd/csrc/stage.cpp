@@ -742,7 +742,7 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (K % 64 || lda % 8 || ldb % 8 || lda < K || ldb < K || ldc < N)
         return fail(ZPP_ERR_UNSUPPORTED, "need K %% 64 == 0, lda/ldb multiples of 8 and >= K, ldc >= N");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
-    if (variant < -1 || variant > 3) return fail(ZPP_ERR_ARG, "variant must be -1..3");
+    if (variant < -1 || variant > 16) return fail(ZPP_ERR_ARG, "variant must be -1..16");
     GemmEpi e;
     e.bias = bias;
     e.resid = resid;
@@ -752,6 +752,18 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     gemm_bf16_force_variant(-1);
     if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
     return ZPP_OK;
+}
+
+// development aid, not declared in the public headers
+zpp_status zpp_dev_gemm_dbg(int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C, int32_t variant,
+                            void *dbg, void *hip_stream)
+{
+    GemmEpi e;
+    e.dbg = dbg;
+    gemm_bf16_force_variant(variant);
+    hipError_t err = launch_gemm_bf16_nt(M, N, K, A, K, B, K, C, N, e, (hipStream_t)hip_stream);
+    gemm_bf16_force_variant(-1);
+    return err == hipSuccess ? ZPP_OK : ZPP_ERR_DEVICE;
 }
 
 zpp_status zpp_op_attention_fwd(int32_t dtype, int32_t impl, const void *qkv, void *attn, float *lse, int64_t b,
