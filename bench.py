@@ -132,10 +132,19 @@ def main():
     zpp.profile_reset()
 
     def rate(cls, scale):
-        n, ms, work = prof[cls]
+        n, ms, work, _ = prof[cls]
         return (work / (ms * 1e-3) / scale) if ms > 0 else 0.0
 
-    n_gemm, ms_gemm, fl_gemm = prof["gemm"]
+    def measured_traffic():
+        """HBM bytes per GEMM launch from the committed rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE,
+        scaled by what the counters read on the flat passes of known size), if they cover this workload."""
+        path = os.path.join(ROOT, "profiles", "cfg3_gemm_traffic.kv")
+        if not os.path.exists(path):
+            return None
+        kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
+        return float(kv["gemm_hbm_bytes_per_launch"]) if kv.get("workload") == sh.name else None
+
+    n_gemm, ms_gemm, fl_gemm, by_gemm = prof["gemm"]
     gemm_tflops = rate("gemm", 1e12)
     bf16 = sh.compute_dtype == 1
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
@@ -146,7 +155,8 @@ def main():
         "frac": round(gemm_tflops / peak, 4),
         "launches": n_gemm, "avg_launch_ms": round(ms_gemm / max(n_gemm, 1), 4),
         "flops_per_launch": fl_gemm / max(n_gemm, 1),
-        "traffic": None,
+        "algorithmic_bytes": by_gemm / max(n_gemm, 1),
+        "traffic": measured_traffic(),
     }
     fb_ms = sum(prof[c][1] for c in ("gemm", "attn_fwd", "attn_bwd", "other"))
     phases = {c: {"launches": prof[c][0], "ms": round(prof[c][1], 3)} for c in prof}

@@ -77,7 +77,7 @@ def load_library(path: str | None = None):
     L.zpp_profile_enable.argtypes = [i32]
     L.zpp_profile_reset.restype = None
     L.zpp_profile_read.argtypes = [i32, ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_double),
-                                   ctypes.POINTER(ctypes.c_double)]
+                                   ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     L.zpp_last_error.restype = ctypes.c_char_p
     L.zpp_version.restype = ctypes.c_char_p
     L.zpp_op_gemm_bf16_nt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i32, i32, vp]
@@ -253,12 +253,12 @@ def profile_reset():
 
 
 def profile_read():
-    """{class: (launches, total_ms, work)} for everything bracketed since the last reset."""
+    """{class: (launches, total_ms, work, min_bytes)} for everything bracketed since the last reset."""
     out = {}
-    n, ms, w = ctypes.c_uint64(), ctypes.c_double(), ctypes.c_double()
+    n, ms, w, b = ctypes.c_uint64(), ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
     for i, name in enumerate(PROF_CLASSES):
-        _check(lib().zpp_profile_read(i, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(w)))
-        out[name] = (n.value, ms.value, w.value)
+        _check(lib().zpp_profile_read(i, ctypes.byref(n), ctypes.byref(ms), ctypes.byref(w), ctypes.byref(b)))
+        out[name] = (n.value, ms.value, w.value, b.value)
     return out
 
 

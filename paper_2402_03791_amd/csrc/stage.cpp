@@ -57,7 +57,7 @@ enum MbState { MB_IDLE = 0, MB_FWD = 1, MB_BWD = 2, MB_ACC = 3 };
 // ---- optional per-kernel-class timing with HIP events on the caller's stream -------------------
 struct ProfRec {
     int cls;
-    double work;
+    double work, bytes;
     hipEvent_t e0, e1;
 };
 bool g_prof_on = false;
@@ -80,10 +80,10 @@ struct ProfScope {
     bool on;
     ProfRec r;
     hipStream_t st;
-    ProfScope(int cls, double work, hipStream_t s) : on(g_prof_on), st(s)
+    ProfScope(int cls, double work, hipStream_t s, double bytes = 0.0) : on(g_prof_on), st(s)
     {
         if (!on) return;
-        r = {cls, work, prof_event(), prof_event()};
+        r = {cls, work, bytes, prof_event(), prof_event()};
         (void)hipEventRecord(r.e0, st);
     }
     ~ProfScope()
@@ -272,7 +272,8 @@ void plan_workspace(zpp_stage *s)
 hipError_t linear_fwd(zpp_stage *s, const void *x, int blk, const char *w, int64_t in, int64_t out, void *y,
                       GemmEpi epi, hipStream_t st)
 {
-    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
+    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+                   (double)s->esz * ((double)s->T * in + (double)in * out + (double)s->T * out));
     if (s->dt == DT_BF16)
         return launch_gemm_bf16_nt(s->T, out, in, x, in, s->Wp(blk, w), in, y, out, epi, st);
     return launch_gemm_f32(s->T, out, in, (const float *)x, in, 1, (const float *)s->Wp(blk, w), in, 1,
@@ -283,7 +284,8 @@ hipError_t linear_fwd(zpp_stage *s, const void *x, int blk, const char *w, int64
 hipError_t linear_dx(zpp_stage *s, const void *dy, int blk, const char *w, int64_t in, int64_t out, void *dx,
                      GemmEpi epi, hipStream_t st)
 {
-    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
+    ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+                   (double)s->esz * ((double)s->T * in + (double)in * out + (double)s->T * out));
     if (s->dt == DT_BF16)  // uses the transposed working copy W^T[in,out] so both operands are K-contiguous
         return launch_gemm_bf16_nt(s->T, in, out, dy, out, s->Wtp(blk, w), out, dx, in, epi, st);
     return launch_gemm_f32(s->T, in, out, (const float *)dy, out, 1, (const float *)s->Wp(blk, w), 1, in,
@@ -305,10 +307,12 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
             if ((e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st)) != hipSuccess) return e;
             if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
         }
-        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
+        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+                       2.0 * ((double)s->T * in + (double)s->T * out) + 4.0 * in * out);
         e = launch_gemm_bf16_nt(out, in, s->T, tA, s->T, tB, s->T, s->Sp(blk, w), in, epi, st);
     } else {
-        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st);
+        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+                       4.0 * ((double)s->T * in + (double)s->T * out + (double)in * out));
         e = launch_gemm_f32(out, in, s->T, (const float *)dy, 1, out, (const float *)x, 1, in, s->Sp(blk, w),
                             in, epi, st);
     }
@@ -706,11 +710,11 @@ void zpp_profile_reset(void)
     g_prof.clear();
 }
 
-zpp_status zpp_profile_read(int32_t cls, uint64_t *launches, double *total_ms, double *work)
+zpp_status zpp_profile_read(int32_t cls, uint64_t *launches, double *total_ms, double *work, double *bytes)
 {
     if (cls < 0 || cls >= ZPP_PROF_CLASSES) return fail(ZPP_ERR_ARG, "profile class %d out of range", cls);
     uint64_t n = 0;
-    double ms = 0.0, w = 0.0;
+    double ms = 0.0, w = 0.0, b = 0.0;
     for (auto &r : g_prof) {
         if (r.cls != cls) continue;
         if (hipEventSynchronize(r.e1) != hipSuccess) return fail(ZPP_ERR_DEVICE, "event synchronize failed");
@@ -718,11 +722,13 @@ zpp_status zpp_profile_read(int32_t cls, uint64_t *launches, double *total_ms, d
         if (hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) return fail(ZPP_ERR_DEVICE, "event elapsed failed");
         ms += t;
         w += r.work;
+        b += r.bytes;
         ++n;
     }
     if (launches) *launches = n;
     if (total_ms) *total_ms = ms;
     if (work) *work = w;
+    if (bytes) *bytes = b;
     return ZPP_OK;
 }
 
