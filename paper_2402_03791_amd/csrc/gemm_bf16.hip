@@ -461,16 +461,23 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
 
     const int nk = (int)(K / kBK);
 
-    auto issue_loads = [&](int kt, int buf) {
+    // Loads of one tile are issued in two halves so that the memory pipeline is fed at a steady rate
+    // instead of in bursts (a burst of 16-byte-per-lane loads blocks the issuing waves, MFMAs included).
+    constexpr int LPS = A_I + B_I;
+    constexpr int G1 = LPS / 2, G2 = LPS - G1;
+    auto issue_loads = [&](int kt, int buf, int first, int count) {
         const int64_t ko = (int64_t)kt * kBK;
         bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;
         bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
 #pragma unroll
-        for (int j = 0; j < A_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 8 * kBK), 16, 0, 0);
+        for (int j = 0; j < LPS; ++j) {
+            if (j < first || j >= first + count) continue;
+            if (j < A_I)
+                __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j - A_I] + ko),
+                                                 (lds_void_t *)(bs + (j - A_I) * 8 * kBK), 16, 0, 0);
+        }
     };
 
     const int a_row0 = wm * WM + (lane & 31);
@@ -499,16 +506,17 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
     constexpr int MFMAS = MT * NT;         // MFMAs per sub-step
     constexpr int MPR = MFMAS / READS;     // MFMAs per LDS read in the interleave
 
-    unsigned long long dbg_vm = 0, dbg_bar = 0, dbg_start = 0;
-    if (epi.dbg) dbg_start = __builtin_amdgcn_s_memtime();
-    issue_loads(0, 0);
+    issue_loads(0, 0, 0, LPS);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    issue_loads(nk > 1 ? 1 : 0, 1);
+    issue_loads(nk > 1 ? 1 : 0, 1, 0, LPS);
     read_frags(0, 0, 0);
 
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
+        // second half of the loads of tile kt+1 (first half went out after the previous barrier)
+        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
+        if (kt > 0) issue_loads(nxt1, buf ^ 1, G1, G2);
         // sub-steps 0..2 of tile kt, each overlapping the operand reads of the next sub-step
 #pragma unroll
         for (int ks = 0; ks < 3; ++ks) {
@@ -518,43 +526,27 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
 #pragma unroll
         for (int r = 0; r < 3 * READS; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 LDS read
+            if (r < G2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global->LDS load
             __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);  // MPR MFMAs
         }
         // tile kt+1 has landed and every wave is done reading tile kt
-        unsigned long long t0 = 0, t1 = 0, t2 = 0;
-        if (epi.dbg) t0 = __builtin_amdgcn_s_memtime();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (epi.dbg) t1 = __builtin_amdgcn_s_memtime();
         __syncthreads();
-        if (epi.dbg) {
-            t2 = __builtin_amdgcn_s_memtime();
-            dbg_vm += t1 - t0;
-            dbg_bar += t2 - t1;
-        }
         const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
-        issue_loads(nxt2, buf);
+        issue_loads(nxt2, buf, 0, G1);
         read_frags(buf ^ 1, 0, 0);  // first operands of tile kt+1 (harmless garbage after the last tile)
         mfma_block(1);              // sub-step 3 of tile kt
 #pragma unroll
         for (int r = 0; r < READS; ++r) {
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, (A_I + B_I) / READS, 0);  // global->LDS loads
+            if (r < G1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
-    unsigned long long dbg_loop_end = 0;
-    if (epi.dbg) dbg_loop_end = __builtin_amdgcn_s_memtime();
 
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-    if (epi.dbg && lane == 0) {
-        unsigned long long *d = epi.dbg + ((size_t)blockIdx.x * NW + wave) * 4;
-        d[0] = dbg_loop_end - dbg_start;
-        d[1] = dbg_vm;
-        d[2] = dbg_bar;
-        d[3] = __builtin_amdgcn_s_memtime() - dbg_loop_end;
-    }
 }
 
 template <int BM, int BN, int WGM, int WGN>

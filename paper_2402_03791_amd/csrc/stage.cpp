@@ -21,6 +21,7 @@ hipError_t launch_attn_simple_bwd(int dt, const void *qkv, const void *attn, con
                                   const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq,
                                   int64_t nh, int64_t d, hipStream_t s);
 void gemm_bf16_force_variant(int v);
+void flat_set_tuning(int blocks_per_cu, int mode);
 }  // namespace zpp
 
 using namespace zpp;
@@ -760,7 +761,9 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     return ZPP_OK;
 }
 
-// development aid, not declared in the public headers
+// development aids, not declared in the public headers
+void zpp_dev_flat_tuning(int32_t blocks_per_cu, int32_t mode) { flat_set_tuning(blocks_per_cu, mode); }
+
 zpp_status zpp_dev_gemm_dbg(int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C, int32_t variant,
                             void *dbg, void *hip_stream)
 {

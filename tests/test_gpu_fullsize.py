@@ -1,0 +1,62 @@
+"""GPU parity at the benchmark's full kernel shapes.
+
+Every kernel launch configuration of a stage depends on (T, h, heads, f, arch) only, not on the
+number of blocks or micro-batches, so one block and one micro-batch at the full T/h/f of each
+bf16 configuration exercises exactly the launches bench.py times.  At these sizes the oracle needs
+tens of seconds per case, so each case is one block x one micro-batch, compared element by element
+(not sampled) on y, dx and every gradient tensor.  The flat Adam pass is compared over the whole
+805M-element shard of the 6.2B-shaped stage."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+import paper_2402_03791_amd as zpp
+from _harness import compare_units, make_inputs, run_gpu_unit, run_oracle_unit
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["cfg2_gpt_1p3b", "cfg3_gpt_6p2b", "cfg4_llama_13b", "cfg5_wide_gpt"])
+def test_one_block_at_full_shape(name):
+    sh = synth.CONFIGS[name].replace(n_blocks=1, unit_mbs=1, name=name + "_1blk")
+    print(f"full-shape block {sh.name}: T={sh.tokens} h={sh.hidden} f={sh.ffn}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.05)
+    xs, dys = make_inputs(sh, 1)
+    gpu = run_gpu_unit(sh, P0, xs, dys)
+    print("gpu done", flush=True)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f32")
+    print("oracle done", flush=True)
+    assert np.array_equal(gpu["W"], ref["W"])
+    worst = compare_units(sh, gpu, ref, layout, 2e-2)
+    print("worst rel err", max(worst.values()), max(worst, key=worst.get), flush=True)
+
+
+def test_adam_over_the_whole_6p2b_shard():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    n = oracle.param_count(sh)
+    print(f"flat Adam over {n} elements", flush=True)
+    p0 = synth.normal_f32(9, 1, n, 0.0, 0.02)
+    g = synth.normal_f32(9, 2, n, 0.0, 1e-3)
+    m0 = synth.normal_f32(9, 3, n, 0.0, 1e-4)
+    v0 = synth.normal_f32(9, 4, n, 0.0, 1e-4) ** 2
+    P, M, V, G = (torch.from_numpy(a).cuda() for a in (p0, m0, v0, g))
+    zpp.op_flat_adam(P, M, V, G, step=3, zero_grad=1, **synth.ADAM)
+    torch.cuda.synchronize()
+    o = oracle.OracleStage(sh, "f32")
+    o.P[:], o.M[:], o.V[:], o.G[:] = p0, m0, v0, g
+    o.adam(step=3, zero_grad=1, **{k: float(np.float32(v)) for k, v in synth.ADAM.items()})
+    for name, a, b in (("p", P, o.P), ("m", M, o.M), ("v", V, o.V)):
+        a = a.cpu().numpy()
+        err = np.abs(a - b) / np.maximum(np.abs(b), 1e-30)
+        assert err.max() <= 1e-6, (name, err.max())
+    assert torch.count_nonzero(G).item() == 0
+    # accumulate over the same shard: G += 0.5 * S
+    S = torch.from_numpy(g).cuda()
+    G.copy_(torch.from_numpy(p0))
+    zpp.op_flat_accumulate(G, S, 0.5)
+    ref = p0.astype(np.float64) + 0.5 * g.astype(np.float64)
+    assert np.abs(G.cpu().numpy() - ref).max() <= 1e-7 * np.abs(ref).max() + 1e-9
+    o.close()
