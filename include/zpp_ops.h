@@ -18,10 +18,17 @@ extern "C" {
  * transposed operands, of the input- and weight-gradient products of Section 2.3.
  * A, B: bf16, K-contiguous, leading dimensions lda, ldb (elements, multiples of 8); K % 64 == 0.
  * C: bf16, or float when out_f32 != 0; leading dimension ldc.  bias, resid: bf16 or NULL.
- * variant: -1 automatic, 0..3 force a tile shape (256x256/8 waves, 128x256, 128x128, 256x256/4 waves). */
+ * variant: -1 automatic, 0..16 force one of the kernel generations / tile shapes (development aid). */
 zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
                                int32_t out_f32, int32_t variant, void *hip_stream);
+
+/* The weight-gradient product of Section 2.3 without any transposition in memory: C[M,N] = A^T . B with
+ * A stored [K, M] (M contiguous, leading dimension lda >= M) and B stored [K, N] (leading dimension
+ * ldb >= N), i.e. dW[out,in] = dY[T,out]^T . X[T,in].  bf16 operands, fp32 accumulation; C is float when
+ * out_f32 != 0, else bf16.  K % 64 == 0; M, N, lda, ldb multiples of 8. */
+zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
 
 /* Causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each; T = b*seq, h = nh*d):
  * attn[T, h] = softmax(Q K^T / sqrt(d) + causal mask) V per (sample, head); lse[b, nh, seq] is the

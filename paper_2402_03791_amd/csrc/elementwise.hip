@@ -5,7 +5,54 @@
 namespace zpp {
 
 // ------------------------------------------------------------------ transpose
-// out[c, r] = in[r, c], 64x64 tiles staged in LDS; both sides touch memory row-contiguously.
+// out[c, r] = in[r, c], 64x64 tiles staged in LDS, 16-byte global loads and stores on both sides
+// (8 lanes cover one 128-byte row).  Optionally the same pass produces per-tile column sums of the
+// input (partial[tile_row][c] = sum over the tile's 64 rows), which the caller reduces over tile rows:
+// that is the bias gradient db = colsum(dY), for free while dY is being transposed for dW = dY^T X.
+// Requires R % 64 == 0, C % 64 == 0, ld_in % 8 == 0, ld_out % 8 == 0 (bf16).
+template <bool COLSUM>
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16 *__restrict__ in, int64_t ld_in,
+                                                             bf16 *__restrict__ out, int64_t ld_out,
+                                                             float *__restrict__ partial, int64_t C)
+{
+    constexpr int LD = 66;  // 33 dwords: the column reads of 8 row-chunks fall into 8 different banks
+    __shared__ bf16 tile[64 * LD];
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = t + i * 256;
+        const int row = q >> 3, ch = q & 7;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(in + (r0 + row) * ld_in + c0 + ch * 8);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(tile + row * LD + ch * 8);
+        dst[0] = v[0];
+        dst[1] = v[1];
+        dst[2] = v[2];
+        dst[3] = v[3];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = t + i * 256;
+        const int c = q >> 3, kc = q & 7;  // output row (input column) and chunk of 8 input rows
+        bf16x8 o;
+        float sum = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            o[j] = tile[(kc * 8 + j) * LD + c];
+            if (COLSUM) sum += (float)o[j];
+        }
+        *reinterpret_cast<bf16x8 *>(out + (c0 + c) * ld_out + r0 + kc * 8) = o;
+        if (COLSUM) {
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            sum += __shfl_xor(sum, 4, 64);
+            if (kc == 0) partial[(int64_t)blockIdx.y * C + c0 + c] = sum;
+        }
+    }
+}
+
+// generic element-wise fallback for other types and ragged sizes
 template <class T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ in, int64_t R, int64_t C,
                                                         int64_t ld_in, T *__restrict__ out, int64_t ld_out)
@@ -29,10 +76,40 @@ hipError_t launch_transpose(int dt, const void *in, int64_t R, int64_t C, int64_
 {
     if (R == 0 || C == 0) return hipSuccess;
     const dim3 grid((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64));
-    if (dt == DT_BF16)
-        transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16 *)in, R, C, ld_in, (bf16 *)out, ld_out);
-    else
+    if (dt == DT_BF16) {
+        if (R % 64 == 0 && C % 64 == 0 && ld_in % 8 == 0 && ld_out % 8 == 0)
+            transpose_bf16_kernel<false><<<grid, 256, 0, s>>>((const bf16 *)in, ld_in, (bf16 *)out, ld_out, nullptr, C);
+        else
+            transpose_kernel<bf16><<<grid, 256, 0, s>>>((const bf16 *)in, R, C, ld_in, (bf16 *)out, ld_out);
+    } else {
         transpose_kernel<float><<<grid, 256, 0, s>>>((const float *)in, R, C, ld_in, (float *)out, ld_out);
+    }
+    return hipGetLastError();
+}
+
+// Column sums of in[R, C] over all rows, written to colsum[C], fused with the transpose.
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float *__restrict__ partial, int64_t tiles,
+                                                            int64_t C, float *__restrict__ colsum)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.0f;
+    for (int64_t r = 0; r < tiles; ++r) s += partial[r * C + c];  // fixed order: run-to-run identical
+    colsum[c] = s;
+}
+
+uint64_t transpose_colsum_scratch_floats(int64_t R, int64_t C) { return (uint64_t)((R + 63) / 64) * C; }
+
+hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
+                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s)
+{
+    if (R == 0 || C == 0) return hipSuccess;
+    if (R % 64 || C % 64 || ld_in % 8 || ld_out % 8) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(C / 64), (unsigned)(R / 64));
+    transpose_bf16_kernel<true><<<grid, 256, 0, s>>>((const bf16 *)in, ld_in, (bf16 *)out, ld_out, partial, C);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    colsum_finish_kernel<<<(unsigned)((C + 255) / 256), 256, 0, s>>>(partial, R / 64, C, colsum);
     return hipGetLastError();
 }
 

@@ -400,8 +400,33 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_dl_kernel(
 // the barrier), and the instruction order inside each region is pinned with scheduling-group
 // barriers: one LDS read for every two MFMAs.  Meant for one wave per SIMD with a large
 // accumulator tile (lowest LDS traffic per flop), where nothing else hides LDS latency.
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
+// Operand layouts: AT = false: A is [M, K] with K contiguous (rows of the LDS tile are M indices, read
+// with plain 16-byte LDS loads).  AT = true: A is [K, M] with M contiguous (rows of the LDS tile are K
+// indices; the MFMA operand is gathered with the LDS transposing load, 4 consecutive K rows of one M
+// column per lane and load).  Same for B with N in place of M.  The K order inside an MFMA operand
+// is the same in both cases, so the layouts mix freely.
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+// element offset inside a [64][LD] tile stored K-major; 32-byte granules XOR-swizzled with the row
+template <int LD>
+__device__ __forceinline__ int tr_off(int row, int col)
+{
+    return row * LD + ((((col >> 4) ^ ((row & 3) << 1))) << 4) + (col & 15);
+}
+
+template <int LD>
+__device__ __forceinline__ bf16x8 tr_read8(const bf16 *tile, int k0, int col_base, int lane)
+{
+    const int i = lane & 15, e = i >> 2, q4 = i & 3;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tile + tr_off<LD>(k0 + e, col_base + 4 * q4)));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tile + tr_off<LD>(k0 + 4 + e, col_base + 4 * q4)));
+    typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AT, bool BT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_p_kernel(
     int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
     int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
 {
@@ -436,20 +461,40 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
     const bf16 *b_g[B_I];
 #pragma unroll
     for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t gm = m0 + row;
-        if (gm > M - 1) gm = M - 1;
-        a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
+        if constexpr (!AT) {
+            const int row = (wave * A_I + j) * 8 + lrow;
+            const int sw = (row & 7) ^ ((row >> 3) & 1);
+            int64_t gm = m0 + row;
+            if (gm > M - 1) gm = M - 1;
+            a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
+        } else {
+            const int byte = (wave * A_I + j) * 1024 + lane * 16;
+            const int r = byte / (BM * 2), pch = (byte % (BM * 2)) >> 4;
+            const int c = ((((pch >> 1) ^ ((r & 3) << 1))) << 1) | (pch & 1);
+            int64_t col = m0 + c * 8;
+            if (col + 8 > M) col = M - 8;
+            a_g[j] = A + (int64_t)r * lda + col;
+        }
     }
 #pragma unroll
     for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t gn = n0 + row;
-        if (gn > N - 1) gn = N - 1;
-        b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
+        if constexpr (!BT) {
+            const int row = (wave * B_I + j) * 8 + lrow;
+            const int sw = (row & 7) ^ ((row >> 3) & 1);
+            int64_t gn = n0 + row;
+            if (gn > N - 1) gn = N - 1;
+            b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
+        } else {
+            const int byte = (wave * B_I + j) * 1024 + lane * 16;
+            const int r = byte / (BN * 2), pch = (byte % (BN * 2)) >> 4;
+            const int c = ((((pch >> 1) ^ ((r & 3) << 1))) << 1) | (pch & 1);
+            int64_t col = n0 + c * 8;
+            if (col + 8 > N) col = N - 8;
+            b_g[j] = B + (int64_t)r * ldb + col;
+        }
     }
+    const int64_t a_kstep = AT ? (int64_t)kBK * lda : kBK;  // elements to advance per K-step
+    const int64_t b_kstep = BT ? (int64_t)kBK * ldb : kBK;
 
     f32x16 acc[MT][NT];
 #pragma unroll
@@ -466,16 +511,16 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
     constexpr int LPS = A_I + B_I;
     constexpr int G1 = LPS / 2, G2 = LPS - G1;
     auto issue_loads = [&](int kt, int buf, int first, int count) {
-        const int64_t ko = (int64_t)kt * kBK;
-        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;
+        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;  // 512 elements (1 KB) per instruction
         bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
 #pragma unroll
         for (int j = 0; j < LPS; ++j) {
             if (j < first || j >= first + count) continue;
             if (j < A_I)
-                __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + kt * a_kstep),
+                                                 (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
             else
-                __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j - A_I] + ko),
+                __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j - A_I] + kt * b_kstep),
                                                  (lds_void_t *)(bs + (j - A_I) * 8 * kBK), 16, 0, 0);
         }
     };
@@ -489,11 +534,19 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
         const bf16 *as = As + buf * BM * kBK;
         const bf16 *bs = Bs + buf * BN * kBK;
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-            af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, ks * 2 + khalf));
+        for (int i = 0; i < MT; ++i) {
+            if constexpr (!AT)
+                af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, ks * 2 + khalf));
+            else
+                af[slot][i] = tr_read8<BM>(as, ks * 16 + 8 * khalf, wm * WM + i * 32 + ((lane >> 4) & 1) * 16, lane);
+        }
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-            bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, ks * 2 + khalf));
+        for (int j = 0; j < NT; ++j) {
+            if constexpr (!BT)
+                bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, ks * 2 + khalf));
+            else
+                bfr[slot][j] = tr_read8<BN>(bs, ks * 16 + 8 * khalf, wn * WN + j * 32 + ((lane >> 4) & 1) * 16, lane);
+        }
     };
     auto mfma_block = [&](int slot) {
 #pragma unroll
@@ -502,9 +555,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
             for (int j = 0; j < NT; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
     };
-    constexpr int READS = MT + NT;         // LDS reads per sub-step
+    constexpr int READS = (AT ? 2 : 1) * MT + (BT ? 2 : 1) * NT;  // LDS reads per sub-step
     constexpr int MFMAS = MT * NT;         // MFMAs per sub-step
-    constexpr int MPR = MFMAS / READS;     // MFMAs per LDS read in the interleave
+    constexpr int MPR = MFMAS / READS > 0 ? MFMAS / READS : 1;  // MFMAs per LDS read in the interleave
 
     issue_loads(0, 0, 0, LPS);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -549,14 +602,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_p_kernel(
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, bool AT = false, bool BT = false>
 static hipError_t launch_variant_p(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
     constexpr int NTH = WGM * WGN * 64;
     constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
     static bool attr_set = false;
-    auto kern = gemm_bf16_nt_p_kernel<BM, BN, WGM, WGN>;
+    auto kern = gemm_bf16_p_kernel<BM, BN, WGM, WGN, AT, BT>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -787,6 +840,22 @@ static hipError_t launch_variant(int64_t M, int64_t N, int64_t K, const bf16 *A,
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
                                                                  tiles_n);
     return hipGetLastError();
+}
+
+// C[M,N] = A^T . B with A stored [K, M] and B stored [K, N] (the weight-gradient product dY^T . X)
+hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
+{
+    if (M == 0 || N == 0) return hipSuccess;
+    if (K <= 0 || (K % kBK) || (M % 8) || (N % 8) || M < 8 || N < 8 || (lda % 8) || (ldb % 8))
+        return hipErrorInvalidValue;
+    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
+              epi.act, epi.gelu_mode, epi.out_f32, (unsigned long long *)epi.dbg};
+    const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
+    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+    if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
+        return launch_variant_p<256, 256, 2, 4, true, true>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    return launch_variant_p<128, 128, 2, 2, true, true>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
 }
 
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)

@@ -62,6 +62,11 @@ hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, cons
 // out[c, r] = in[r, c]; in has row stride ld_in, out row stride ld_out (elements)
 hipError_t launch_transpose(int dt, const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
                             int64_t ld_out, hipStream_t s);
+// bf16 only: transpose plus colsum[c] = sum_r in[r, c] in the same pass (R, C multiples of 64);
+// partial: scratch of transpose_colsum_scratch_floats(R, C) floats.
+uint64_t transpose_colsum_scratch_floats(int64_t R, int64_t C);
+hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
+                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s);
 // table[p, i] = (cos, sin)(p * base^(-2i/d)), p < seq, i < d/2
 hipError_t launch_rope_table(float *table, int64_t seq, int64_t d, double base, hipStream_t s);
 // rotates the Q and K parts of qkv[T, 3h] in place; sign = +1 forward, -1 inverse
@@ -80,6 +85,10 @@ hipError_t launch_gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int6
 // bf16 MFMA GEMM, both operands K-contiguous: C[M,N] = A[M,K] . B[N,K]^T with fp32 accumulation.
 // Requires K % 64 == 0, lda/ldb % 8 == 0, 16-byte aligned bases.
 hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
+// Same with both operands stored K-major: C[M,N] = A^T . B, A is [K, M] (M contiguous), B is [K, N].
+// Requires K % 64 == 0, M, N multiples of 8, lda/ldb % 8 == 0.
+hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
 

@@ -197,6 +197,23 @@ def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     assert rel_err(to_np(Cf), ref2) <= 1e-5      # fp32 accumulation of exact bf16 products
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (128, 128, 128), (520, 304, 192), (8, 8, 64), (1024, 2048, 512),
+                                   (2304, 768, 256)])
+def test_gemm_bf16_tt_against_oracle(M, N, K):
+    """dW = dY^T . X straight from the token-major operands."""
+    print(f"gemm tt {M}x{N}x{K}", flush=True)
+    dy = synth.normal_f32(4, 80, K * M, bf16_exact=True).reshape(K, M)
+    x = synth.normal_f32(4, 81, K * N, bf16_exact=True).reshape(K, N)
+    ref, _ = oracle.Ops("f64").linear_bwd_weight(dy, x)
+    A, B = to_dev(dy, torch.bfloat16), to_dev(x, torch.bfloat16)
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    zpp.op_gemm_bf16_tt(A, B, C)
+    assert rel_err(to_np(C), ref) <= 1e-5
+    Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    zpp.op_gemm_bf16_tt(A, B, Cb)
+    assert rel_err(to_np(Cb), ref) <= 8e-3
+
+
 @pytest.mark.parametrize("dtype,b,s,nh,d", [(torch.float32, 2, 70, 3, 32), (torch.bfloat16, 1, 130, 2, 128),
                                             (torch.float32, 1, 1, 1, 64)])
 def test_generic_attention_against_oracle(dtype, b, s, nh, d):
