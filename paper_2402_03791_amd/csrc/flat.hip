@@ -12,8 +12,6 @@ namespace zpp {
 // before its first store, and uses non-temporal accesses (nothing is reused).  Measured on MI355X a
 // huge grid of such small chunks sustains 6.0-6.1 TB/s on the accumulate pass where a persistent
 // grid of 16 groups per CU reaches 4.7 TB/s (about what a device-to-device hipMemcpy gets).
-static int g_flat_vpt = 0;  // 0: defaults (accumulate 4, Adam 1 vectors per thread)
-void flat_set_tuning(int vpt, int) { g_flat_vpt = vpt; }
 
 template <class T> __device__ __forceinline__ T nt_load(const T *p) { return __builtin_nontemporal_load(p); }
 template <class T> __device__ __forceinline__ void nt_store(T v, T *p) { __builtin_nontemporal_store(v, p); }
@@ -144,11 +142,7 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ G, 
 hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
-    switch (g_flat_vpt) {
-    case 2: accumulate_kernel<2><<<flat_blocks(n / 4, 2), 256, 0, s>>>(G, S, n, scale); break;
-    case 8: accumulate_kernel<8><<<flat_blocks(n / 4, 8), 256, 0, s>>>(G, S, n, scale); break;
-    default: accumulate_kernel<4><<<flat_blocks(n / 4, 4), 256, 0, s>>>(G, S, n, scale); break;
-    }
+    accumulate_kernel<4><<<flat_blocks(n / 4, 4), 256, 0, s>>>(G, S, n, scale);
     return hipGetLastError();
 }
 
@@ -222,11 +216,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ P, float 
 hipError_t launch_adam(float *P, float *M, float *V, float *G, uint64_t n, const AdamArgs &a, hipStream_t s)
 {
     if (n == 0) return hipSuccess;
-    switch (g_flat_vpt) {
-    case 4: adam_kernel<4><<<flat_blocks(n / 4, 4), 256, 0, s>>>(P, M, V, G, n, a); break;
-    case 2: adam_kernel<2><<<flat_blocks(n / 4, 2), 256, 0, s>>>(P, M, V, G, n, a); break;
-    default: adam_kernel<1><<<flat_blocks(n / 4, 1), 256, 0, s>>>(P, M, V, G, n, a); break;
-    }
+    adam_kernel<1><<<flat_blocks(n / 4, 1), 256, 0, s>>>(P, M, V, G, n, a);
     return hipGetLastError();
 }
 

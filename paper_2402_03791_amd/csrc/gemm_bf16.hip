@@ -1,13 +1,21 @@
-// bf16 MFMA GEMM for gfx950: C[M,N] = A[M,K] . B[N,K]^T, both operands K-contiguous, fp32
-// accumulation in v_mfma_f32_32x32x16_bf16, fused epilogues (bias, residual, GeLU, GeLU', fp32 out).
+// bf16 MFMA GEMMs for gfx950: C[M,N] = A[M,K] . B[N,K]^T (both operands K-contiguous) and the K-major
+// variant C = A^T . B, fp32 accumulation in v_mfma_f32_32x32x16_bf16, fused epilogues (bias,
+// residual, GeLU, GeLU', fp32 or bf16 output).
 //
-// Structure: a work-group computes a BM x BN tile; K advances in steps of 64.  Each K-step's
-// operand tiles are fetched with 16-byte global loads into registers while the previous step is
-// being multiplied out of LDS, then written to the other LDS buffer (double buffering, one barrier
-// per step).  LDS rows are 128 bytes (64 bf16) with an XOR swizzle of the 16-byte chunk index so
-// that both the row-wise 16-byte writes and the MFMA-operand 16-byte reads (32 consecutive rows,
-// same chunk) are bank-conflict free.  Work-group ids are remapped so that each XCD (one L2 each,
-// ids are dealt round-robin over 8 XCDs) owns a compact group of neighbouring tiles.
+// Three kernel generations live here; the stage uses the third, the others stay selectable through
+// the operator-level entry point (and the second carries the K-major operand paths):
+//   1. register-staged: 16-byte global loads into registers while the previous K-step is multiplied
+//      out of LDS, then written to the other LDS buffer (double buffering, one barrier per step);
+//   2. pipelined: global -> LDS directly, K loop rotated across the barrier, instruction mix steered
+//      with scheduling-group barriers;
+//   3. hand-ordered: as 2, with the exact instruction order pinned and no vector address arithmetic
+//      in the loop.
+// Common to all: a work-group computes a BM x BN tile, K advances in steps of 64; LDS rows are 128
+// bytes (64 bf16) with an XOR swizzle of the 16-byte chunk index so that the row-wise 16-byte writes
+// and the MFMA-operand 16-byte reads (32 consecutive rows, same chunk) are bank-conflict free;
+// work-group ids are remapped so that each XCD (one L2 each, ids are dealt round-robin over 8 XCDs)
+// owns a compact group of neighbouring tiles; the epilogue transposes accumulators through LDS so
+// that every global access is 16 bytes per lane.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -21,7 +29,6 @@ struct EpiBf16 {
     const bf16 *bias, *resid, *aux;
     bf16 *out2;
     int act, gelu_mode, out_f32;
-    unsigned long long *dbg;  // optional [blocks][waves][4] cycle counters (development aid), else null
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -266,136 +273,14 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Second generation: operand tiles go from global memory straight into LDS (global_load_lds, 16
-// bytes per lane, no staging registers and no ds_write), and the MFMA operands of K sub-step ks+1
-// are fetched from LDS while sub-step ks is being multiplied.  Each load instruction of a wave
-// fills 8 consecutive tile rows (1 KB): lane i lands at byte 16*i, so lane i fetches the chunk the
-// swizzle assigns to that slot.
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void gbl_void_t;
 
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_dl_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
-{
-    constexpr int NW = WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;  // load instructions per wave per K-step
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);  // [2][BM*64]
-    bf16 *Bs = As + 2 * BM * kBK;                   // [2][BN*64]
-
-    int pid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    const int lrow = lane >> 3, lch = lane & 7;
-    const bf16 *a_g[A_I];
-    const bf16 *b_g[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t gm = m0 + row;
-        if (gm > M - 1) gm = M - 1;
-        a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
-    }
-#pragma unroll
-    for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t gn = n0 + row;
-        if (gn > N - 1) gn = N - 1;
-        b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
-    }
-
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    const int nk = (int)(K / kBK);
-
-    auto issue_loads = [&](int kt, int buf) {
-        const int64_t ko = (int64_t)kt * kBK;
-        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;
-        bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
-#pragma unroll
-        for (int j = 0; j < A_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 8 * kBK), 16, 0, 0);
-    };
-
-    const int a_row0 = wm * WM + (lane & 31);
-    const int b_row0 = wn * WN + (lane & 31);
-    const int khalf = lane >> 5;
-
-    auto compute = [&](int buf) {
-        const bf16 *as = As + buf * BM * kBK;
-        const bf16 *bs = Bs + buf * BN * kBK;
-        bf16x8 af[2][MT], bfr[2][NT];
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-            af[0][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, khalf));
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-            bfr[0][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, khalf));
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks < 3) {
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-                    af[nxt][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, (ks + 1) * 2 + khalf));
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, (ks + 1) * 2 + khalf));
-            }
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    issue_loads(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) issue_loads(kt + 1, (kt + 1) & 1);
-        compute(kt & 1);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    }
-
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
 // ---------------------------------------------------------------------------------------------
-// Third generation: same data movement as above, but the K loop is rotated so that the MFMAs of
+// Second generation ("pipelined"): operand tiles go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane, no staging registers and no ds_write; each load instruction
+// of a wave fills 1 KB of the tile: lane i lands at byte 16*i, so lane i fetches the chunk the swizzle
+// assigns to that slot), and the K loop is rotated so that the MFMAs of
 // the last K sub-step of a tile overlap the first LDS operand reads of the next tile (right after
 // the barrier), and the instruction order inside each region is pinned with scheduling-group
 // barriers: one LDS read for every two MFMAs.  Meant for one wave per SIMD with a large
@@ -623,44 +508,32 @@ static hipError_t launch_variant_p(int64_t M, int64_t N, int64_t K, const bf16 *
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fourth generation: a ring of four LDS stages of K = 32 each.  With two stages of K = 64 a tile
-// is requested only one K-step (about 2000 MFMA cycles) before it is needed, which is less than
-// the HBM/L2 round trip; with four half-size stages three are in flight (96 KB per CU) and a tile
-// has three steps (about 3000 cycles) to arrive, for the same LDS footprint.  One barrier per
-// stage; the MFMAs of each K sub-step overlap the LDS operand reads of the next one, across the
-// barrier as well.  LDS rows are 64 bytes (32 bf16); the 16-byte chunk index is XOR-swizzled with
-// bits 2..3 of the row so that 16 consecutive rows of one chunk column hit 16 different bank groups.
-constexpr int kRK = 32;      // K per ring stage
-constexpr int kRStages = 4;
-
-__device__ __forceinline__ int ring_off(int row, int chunk)
-{
-    // element offset of 16-byte chunk `chunk` (0..3) of tile row `row`
-    return row * kRK + ((chunk ^ ((row >> 2) & 3)) << 3);
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
+// Third generation ("hand-ordered"): same data movement as the pipelined kernel (two LDS buffers of
+// K = 64, operands global -> LDS directly, K loop rotated across the barrier), but
+//   * the instruction order of every phase is written out and pinned with scheduling barriers: the
+//     LDS reads of the next K sub-step are issued one per MFMA at the start of the current sub-step,
+//     so each has at least half a sub-step of MFMA time to return before it is needed;
+//   * the loop body is instantiated for both LDS buffers, so all LDS addresses are a per-lane base
+//     register plus an immediate, and the global addresses are a scalar base that advances per
+//     K-step plus a fixed per-lane 32-bit offset: no vector address arithmetic inside the loop.
 template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
     int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
     int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
 {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;  // load instructions (16 rows each) per wave per stage
-    constexpr int LPS = A_I + B_I;                         // loads per stage per wave
-    constexpr int STAGE_ELEMS = (BM + BN) * kRK;
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile/waves mismatch");
-    static_assert(2 * LPS <= 63, "vmcnt range");
+    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
+    constexpr int LPS = A_I + B_I;            // global->LDS loads per wave per K-step
+    constexpr int G1 = LPS / 2, G2 = LPS - G1;
+    constexpr int READS = MT + NT, MFMAS = MT * NT;
+    constexpr int A_BUF_BYTES = BM * kBK * 2, B_BUF_BYTES = BN * kBK * 2;
+    constexpr int B_REGION = 2 * A_BUF_BYTES;  // byte offset of the B buffers inside LDS
+    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
+    static_assert(3 * 4096 + A_BUF_BYTES < 65536 && 3 * 4096 + B_BUF_BYTES < 65536, "LDS immediates");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *ring = reinterpret_cast<bf16 *>(smem_raw);  // [4][A: BM*32 | B: BN*32]
 
     int pid = blockIdx.x;
     const int total = tiles_m * tiles_n;
@@ -679,23 +552,39 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // lane i of a load instruction lands at LDS byte 16*i: row i/4 of the 16-row group, slot i%4
-    const int lrow = lane >> 2, lslot = lane & 3;
-    const bf16 *a_g[A_I];
-    const bf16 *b_g[B_I];
+    // ---- global side: scalar tile base + per-lane byte offset (fits 32 bits: at most 256 rows)
+    const int lrow = lane >> 3, lch = lane & 7;
+    uint32_t a_voff[A_I], b_voff[B_I];
 #pragma unroll
     for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 16 + lrow;
-        int64_t gm = m0 + row;
-        if (gm > M - 1) gm = M - 1;
-        a_g[j] = A + gm * lda + ((lslot ^ ((row >> 2) & 3)) << 3);
+        const int row = (wave * A_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t r = row;
+        if (m0 + r > M - 1) r = M - 1 - m0;
+        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
     }
 #pragma unroll
     for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 16 + lrow;
-        int64_t gn = n0 + row;
-        if (gn > N - 1) gn = N - 1;
-        b_g[j] = B + gn * ldb + ((lslot ^ ((row >> 2) & 3)) << 3);
+        const int row = (wave * B_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t r = row;
+        if (n0 + r > N - 1) r = N - 1 - n0;
+        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
+    }
+    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
+    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
+
+    // ---- LDS side: per-lane byte addresses of the operand chunk for each K sub-step
+    const int khalf = lane >> 5;
+    unsigned char *a_rd[4], *b_rd[4];
+    {
+        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+        const int asw = (arow & 7) ^ ((arow >> 3) & 1), bsw = (brow & 7) ^ ((brow >> 3) & 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            a_rd[ks] = smem_raw + arow * 128 + (((ks * 2 + khalf) ^ asw) << 4);
+            b_rd[ks] = smem_raw + B_REGION + brow * 128 + (((ks * 2 + khalf) ^ bsw) << 4);
+        }
     }
 
     f32x16 acc[MT][NT];
@@ -706,110 +595,126 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    const int nk = (int)(K / kRK);
-
-    auto issue_loads = [&](int kt) {
-        const int st = kt < nk ? kt : nk - 1;  // past the end: reload the last stage into a free slot
-        const int64_t ko = (int64_t)st * kRK;
-        bf16 *as = ring + (kt & (kRStages - 1)) * STAGE_ELEMS + wave * A_I * 16 * kRK;
-        bf16 *bs = ring + (kt & (kRStages - 1)) * STAGE_ELEMS + BM * kRK + wave * B_I * 16 * kRK;
-#pragma unroll
-        for (int j = 0; j < A_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + ko), (lds_void_t *)(as + j * 16 * kRK), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_I; ++j)
-            __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j] + ko), (lds_void_t *)(bs + j * 16 * kRK), 16, 0, 0);
-    };
-
-    const int a_row0 = wm * WM + (lane & 31);
-    const int b_row0 = wn * WN + (lane & 31);
-    const int khalf = lane >> 5;
-
+    const int nk = (int)(K / kBK);
     bf16x8 af[2][MT], bfr[2][NT];
-    auto read_frags = [&](int kt, int ks, int slot) {
-        const bf16 *as = ring + (kt & (kRStages - 1)) * STAGE_ELEMS;
-        const bf16 *bs = as + BM * kRK;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-            af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + ring_off(a_row0 + i * 32, ks * 2 + khalf));
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-            bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + ring_off(b_row0 + j * 32, ks * 2 + khalf));
-    };
-    auto mfma_block = [&](int slot) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
-    };
-    constexpr int READS = MT + NT;
-    constexpr int MFMAS = MT * NT;
-    constexpr int MPR = MFMAS / READS > 0 ? MFMAS / READS : 1;
 
-    issue_loads(0);
-    issue_loads(1);
-    issue_loads(2);
-    wait_vmcnt<2 * LPS>();
-    __syncthreads();
-    read_frags(0, 0, 0);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        // after a barrier: slot (kt+3)%4 held stage kt-1, which every wave has finished reading
-        issue_loads(kt + 3);
-        read_frags(kt, 1, 1);
-        mfma_block(0);
-#pragma unroll
-        for (int r = 0; r < READS; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (r < LPS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+    // load n (0..LPS-1) of K-step kt into LDS buffer `buf`
+    // LDS byte addresses of this wave's first load slot in the A and B regions (scalar)
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
+    auto gll = [&](int n, int kt, int buf) {
+        // scalar base (advances with the K-step) + fixed per-lane 32-bit offset: no vector address
+        // arithmetic; M0 carries the LDS destination of the wave's 1 KB slot
+        const char *abase = a_tile + (int64_t)kt * (kBK * 2);
+        const char *bbase = b_tile + (int64_t)kt * (kBK * 2);
+        if (n < A_I) {
+            const uint32_t dst = a_slot + buf * A_BUF_BYTES + n * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "memory");
+        } else {
+            const int m = n - A_I;
+            const uint32_t dst = b_slot + buf * B_BUF_BYTES + m * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "memory");
         }
-        // stage kt+1 must have landed (only stages kt+2 and kt+3 may still be in flight)
-        wait_vmcnt<2 * LPS>();
+    };
+    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the
+    // LDS reads of sub-step RKS of buffer RBUF into the other fragment set, and with GCNT global loads
+    // (numbers GFIRST..) of K-step gkt into buffer GBUF.
+    auto phase = [&](auto cur_c, auto rbuf_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gbuf_c, int gkt) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        constexpr int RBUF = decltype(rbuf_c)::value, RKS = decltype(rks_c)::value;
+        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
+        constexpr int GBUF = decltype(gbuf_c)::value;
+        static_for<MFMAS>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            constexpr int i = t / NT, j = t % NT;
+            // reads are ordered A0, B0..B(NT-1), A1, A2, ... : the order in which the next phase needs them
+            if constexpr (t < READS) {
+                if constexpr (t == 0) {
+                    af[NXT][0] = *reinterpret_cast<const bf16x8 *>(a_rd[RKS] + RBUF * A_BUF_BYTES);
+                } else if constexpr (t <= NT) {
+                    bfr[NXT][t - 1] = *reinterpret_cast<const bf16x8 *>(b_rd[RKS] + RBUF * B_BUF_BYTES + (t - 1) * 4096);
+                } else {
+                    af[NXT][t - NT] = *reinterpret_cast<const bf16x8 *>(a_rd[RKS] + RBUF * A_BUF_BYTES + (t - NT) * 4096);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (GCNT > 0) {
+                // spread the global loads evenly over the MFMAs of the phase
+                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
+                if constexpr (after > before) {
+                    gll(GFIRST + before, gkt, GBUF);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using IG1 = std::integral_constant<int, G1>;
+    using IG2 = std::integral_constant<int, G2>;
+
+    // K-step kt out of buffer BUF.  On entry fragment set 0 holds sub-step 0 of tile kt, and the first
+    // half of tile kt+1's loads is in flight into the other buffer.
+    auto kstep = [&](auto buf_c, int kt) {
+        constexpr int BUF = decltype(buf_c)::value;
+        using IB = std::integral_constant<int, BUF>;
+        using IO = std::integral_constant<int, BUF ^ 1>;
+        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
+        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
+        phase(I0{}, IB{}, I1{}, IG1{}, IG2{}, IO{}, nxt1);  // MFMA sub-step 0, read sub-step 1, 2nd half of loads
+        phase(I1{}, IB{}, I2{}, I0{}, I0{}, IO{}, 0);
+        phase(I0{}, IB{}, I3{}, I0{}, I0{}, IO{}, 0);
+        // tile kt+1 has landed and every wave is done reading tile kt
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        read_frags(kt + 1, 0, 0);  // after the last stage this reads a stale slot; the values are unused
-        mfma_block(1);
+        phase(I1{}, IO{}, I0{}, I0{}, IG1{}, IB{}, nxt2);   // MFMA sub-step 3, read sub-step 0 of tile kt+1
+    };
+
 #pragma unroll
-        for (int r = 0; r < READS; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
-        }
+    for (int n = 0; n < LPS; ++n) gll(n, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    {
+        const int k1 = nk > 1 ? 1 : 0;
+#pragma unroll
+        for (int n = 0; n < G1; ++n) gll(n, k1, 1);
     }
-    wait_vmcnt<0>();
+    af[0][0] = *reinterpret_cast<const bf16x8 *>(a_rd[0]);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8 *>(b_rd[0] + j * 4096);
+#pragma unroll
+    for (int i = 1; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8 *>(a_rd[0] + i * 4096);
+
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        kstep(I0{}, kt);
+        kstep(I1{}, kt + 1);
+    }
+    if (kt < nk) kstep(I0{}, kt);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
 
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
 template <int BM, int BN, int WGM, int WGN>
-static hipError_t launch_variant_r(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+static hipError_t launch_variant_h(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)kRStages * (BM + BN) * kRK * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_nt_r_kernel<BM, BN, WGM, WGN>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, int WGM, int WGN>
-static hipError_t launch_variant_dl(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
     constexpr int NTH = WGM * WGN * 64;
     constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
     static bool attr_set = false;
-    auto kern = gemm_bf16_nt_dl_kernel<BM, BN, WGM, WGN>;
+    auto kern = gemm_bf16_nt_h_kernel<BM, BN, WGM, WGN>;
     if (!attr_set) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -850,7 +755,7 @@ hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (K <= 0 || (K % kBK) || (M % 8) || (N % 8) || M < 8 || N < 8 || (lda % 8) || (ldb % 8))
         return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, (unsigned long long *)epi.dbg};
+              epi.act, epi.gelu_mode, epi.out_f32};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
@@ -872,33 +777,25 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (M == 0 || N == 0) return hipSuccess;
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, (unsigned long long *)epi.dbg};
+              epi.act, epi.gelu_mode, epi.out_f32};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     int variant = g_forced_variant;
     if (variant < 0) {
-        // 256x256 tiles (8 waves) have the lowest LDS and L2 traffic per flop but need whole rounds of
-        // the 256 CUs; otherwise 128x128 tiles (up to 3 work-groups per CU) quantise better.
+        // 256x256 tiles (8 waves) whenever they give every CU a work-group: lowest LDS and L2 traffic
+        // per flop.  Otherwise (e.g. a T x h output of 128 big tiles) 128x128 tiles, 2 work-groups per CU.
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-        variant = (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024)) ? 11 : 12;
+        variant = t256 >= 256 ? 5 : 6;
     }
     switch (variant) {
     case 0: return launch_variant<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 1: return launch_variant<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 2: return launch_variant<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 3: return launch_variant<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 4: return launch_variant_dl<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 5: return launch_variant_dl<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 6: return launch_variant_dl<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 7: return launch_variant_dl<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 8: return launch_variant_dl<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 9: return launch_variant_p<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 10: return launch_variant_p<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 11: return launch_variant_p<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 12: return launch_variant_p<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 13: return launch_variant_r<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 14: return launch_variant_r<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 15: return launch_variant_r<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 16: return launch_variant_r<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 3: return launch_variant_p<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 4: return launch_variant_p<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 5: return launch_variant_h<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 6: return launch_variant_h<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 7: return launch_variant_h<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 8: return launch_variant_h<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }

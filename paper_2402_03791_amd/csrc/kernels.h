@@ -29,7 +29,6 @@ struct GemmEpi {
     int act = ACT_NONE;
     int gelu_mode = 0;
     int out_f32 = 0;              // 1: C is float regardless of the compute dtype (weight gradients)
-    void *dbg = nullptr;          // development aid: per-wave cycle counters (bf16 pipelined kernel only)
 };
 
 // ---- flat-buffer passes (HBM bound) ----

@@ -21,7 +21,6 @@ hipError_t launch_attn_simple_bwd(int dt, const void *qkv, const void *attn, con
                                   const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq,
                                   int64_t nh, int64_t d, hipStream_t s);
 void gemm_bf16_force_variant(int v);
-void flat_set_tuning(int blocks_per_cu, int mode);
 }  // namespace zpp
 
 using namespace zpp;
@@ -759,7 +758,7 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (K % 64 || lda % 8 || ldb % 8 || lda < K || ldb < K || ldc < N)
         return fail(ZPP_ERR_UNSUPPORTED, "need K %% 64 == 0, lda/ldb multiples of 8 and >= K, ldc >= N");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
-    if (variant < -1 || variant > 16) return fail(ZPP_ERR_ARG, "variant must be -1..16");
+    if (variant < -1 || variant > 8) return fail(ZPP_ERR_ARG, "variant must be -1..8");
     GemmEpi e;
     e.bias = bias;
     e.resid = resid;
@@ -769,20 +768,6 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     gemm_bf16_force_variant(-1);
     if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
     return ZPP_OK;
-}
-
-// development aids, not declared in the public headers
-void zpp_dev_flat_tuning(int32_t blocks_per_cu, int32_t mode) { flat_set_tuning(blocks_per_cu, mode); }
-
-zpp_status zpp_dev_gemm_dbg(int64_t M, int64_t N, int64_t K, const void *A, const void *B, void *C, int32_t variant,
-                            void *dbg, void *hip_stream)
-{
-    GemmEpi e;
-    e.dbg = dbg;
-    gemm_bf16_force_variant(variant);
-    hipError_t err = launch_gemm_bf16_nt(M, N, K, A, K, B, K, C, N, e, (hipStream_t)hip_stream);
-    gemm_bf16_force_variant(-1);
-    return err == hipSuccess ? ZPP_OK : ZPP_ERR_DEVICE;
 }
 
 zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,

@@ -178,7 +178,9 @@ def test_materialize_counters_and_idempotence():
 # ------------------------------------------------------------------ operators
 @pytest.mark.parametrize("M,N,K,variant", [
     (256, 256, 64, 0), (300, 520, 192, 0), (300, 520, 192, 1), (300, 520, 192, 2), (300, 520, 192, 3),
-    (64, 96, 128, -1), (1, 1, 64, 2), (777, 129, 256, -1), (2048, 512, 1024, -1),
+    (300, 520, 192, 4), (300, 520, 192, 5), (300, 520, 192, 6), (300, 520, 192, 7), (300, 520, 192, 8),
+    (64, 96, 128, -1), (1, 1, 64, 2), (1, 1, 64, 6), (777, 129, 256, -1), (2048, 512, 1024, -1), (512, 2048, 64, 5),
+    (1000, 1000, 320, 5), (1000, 1000, 320, 6),
 ])
 def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     print(f"gemm {M}x{N}x{K} variant {variant}", flush=True)
