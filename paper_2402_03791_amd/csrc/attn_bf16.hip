@@ -17,82 +17,102 @@
 namespace zpp {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kD = 128;        // head dim
 constexpr int kTile = 64;      // rows of a streamed tile
-constexpr int kTileElems = kTile * kD;
+constexpr int kTileBytes = kTile * kD * 2;  // 16 KB
 
-// LDS layouts of a [64][128] bf16 tile (256-byte rows).
-// "row" layout: read as MFMA operand with 8 consecutive columns per lane (16-byte chunks).
-__device__ __forceinline__ int off_row(int row, int chunk16) { return row * kD + ((chunk16 ^ (row & 15)) << 3); }
-// "tr" layout: read with the transposing load, 4 consecutive rows x 16 columns per 16 lanes.
-__device__ __forceinline__ int off_tr(int row, int col)
-{
-    const int gran = col >> 4;  // 32-byte granule
-    return row * kD + ((gran ^ ((row & 3) << 1)) << 4) + (col & 15);
-}
+// One LDS layout serves both ways a [64][128] bf16 tile (256-byte rows, 16 chunks of 16 bytes) is
+// read: chunk c of row r sits at chunk position c ^ g(r), g(r) = ((r & 3) << 2) | ((r >> 2) & 3).
+//  - row-wise MFMA operand (16 consecutive rows, same chunk): g takes 16 different values;
+//  - transposing load (4 consecutive rows x 4 consecutive chunks): bits 2..3 of the position follow
+//    the row, bits 0..1 the chunk, again 16 different positions.
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-// 8 operand values for one lane: rows k0a..k0a+3 and k0b..k0b+3 of column (col_base + lane%16),
-// out of a tile in "tr" layout.
-__device__ __forceinline__ bf16x8 read_tr8(const bf16 *tile, int k0a, int k0b, int col_base, int lane)
-{
-    const int i = lane & 15, e = i >> 2, q4 = i & 3;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + off_tr(k0a + e, col_base + 4 * q4)));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + off_tr(k0b + e, col_base + 4 * q4)));
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
-}
-
-struct TileLoader {
-    // 64 rows x 16 chunks of 16 bytes = 1024 chunks, 4 per thread
-    const bf16 *src[4];
-    int dst_row[4], dst_tr[4];
-    bf16x8 reg[4];
-    __device__ __forceinline__ void init(const bf16 *base, int64_t ld, int tid)
+// Global -> LDS copy of a tile, 4 load instructions per wave (4 rows of 256 bytes each): lane i of a
+// load lands at byte 16*i of the 1 KB slot, so it fetches the chunk the swizzle assigns to that place.
+struct TileCopy {
+    uint32_t voff[4];
+    __device__ __forceinline__ void init(int lane, int wave, int64_t ld_elems)
     {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int q = tid + i * 256;
-            const int row = q >> 4, ch = q & 15;
-            src[i] = base + (int64_t)row * ld + ch * 8;
-            dst_row[i] = off_row(row, ch);
-            dst_tr[i] = off_tr(row, ch * 8);
+        for (int j = 0; j < 4; ++j) {
+            const int row = wave * 16 + j * 4 + (lane >> 4);
+            const int c = (lane & 15) ^ swz(row);
+            voff[j] = (uint32_t)((row * ld_elems + c * 8) * 2);
         }
     }
-    __device__ __forceinline__ void load(int64_t row_off_elems)
+    // base: first byte of the tile's row 0 (uniform); lds_tile: LDS byte address of the tile (uniform)
+    __device__ __forceinline__ void issue(const char *base, uint32_t lds_tile, int wave) const
     {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) reg[i] = *reinterpret_cast<const bf16x8 *>(src[i] + row_off_elems);
-    }
-    __device__ __forceinline__ void store_row(bf16 *tile) const
-    {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8 *>(tile + dst_row[i]) = reg[i];
-    }
-    __device__ __forceinline__ void store_tr(bf16 *tile) const
-    {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8 *>(tile + dst_tr[i]) = reg[i];
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t dst = lds_tile + wave * 4096 + j * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(voff[j]), "s"(base)
+                         : "memory");
+        }
     }
 };
 
+// Per-lane LDS byte offsets (inside a tile) for the two read patterns.
+struct TileAddr {
+    uint32_t row[8];    // row-wise operand: rows lane%32 (+32 per MFMA tile), K sub-step st = 0..7
+    uint32_t tr[4][2];  // transposing load: column tile t = 0..3, first/second group of 4 rows
+    __device__ __forceinline__ void init(int lane)
+    {
+        const int r = lane & 31, gh = lane >> 5;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) row[st] = r * 256 + (((2 * st + gh) ^ swz(r)) << 4);
+        const int i = lane & 15, e = i >> 2, q4 = i & 3, half = (lane >> 4) & 1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                // row = k0 + e with k0 = (compile-time multiple of 16) + 4*gh + 8*hi
+                const int rr = 4 * gh + 8 * hi + e;
+                const int c = 4 * t + 2 * half + (q4 >> 1);
+                tr[t][hi] = (4 * gh + e) * 256 + ((c ^ swz(rr)) << 4) + (q4 & 1) * 8;
+            }
+    }
+};
+
+// MFMA operand rows (32*T + lane%32), K sub-step st, from a tile at LDS byte address `tile`
+__device__ __forceinline__ bf16x8 rd_row(const unsigned char *tile, const TileAddr &a, int T, int st)
+{
+    return *reinterpret_cast<const bf16x8 *>(tile + a.row[st] + T * 8192);
+}
+// MFMA operand gathered down the rows: column 32*t + lane%32 (as the operand's row index), K slots =
+// tile rows 16*st + 8*(lane/32) .. +7 in the order the accumulator layout of S^T / S produces them:
+// (4*gh + 0..3) then (8 + 4*gh + 0..3) inside each group of 16 rows.
+__device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAddr &a, int t, int st)
+{
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + a.tr[t][0] + st * 4096));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + a.tr[t][1] + st * 4096 + 2048));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// ------------------------------------------------------------------------------------ forward
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
-                                                            float *__restrict__ lse, int seq, int nh,
-                                                            float scale_log2e)
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem_raw);  // [2][64*128], "row" layout
-    bf16 *Vs = Ks + 2 * kTileElems;                 // [2][64*128], "tr" layout
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
 
+// ------------------------------------------------------------------------------------ forward
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
+                                                               float *__restrict__ lse, int seq, int nh,
+                                                               float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][K tile | V tile]
     const int qb = gridDim.x - 1 - blockIdx.x;  // heavy (late) query blocks first
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
     const int q0 = qb * 128, qw0 = q0 + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
@@ -103,10 +123,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16 *__restri
 #pragma unroll
         for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
     }
-
-    TileLoader lk, lv;
-    lk.init(qkv + row0 * ld + h + (int64_t)n * kD, ld, tid);
-    lv.init(qkv + row0 * ld + 2 * h + (int64_t)n * kD, ld, tid);
+    TileCopy cp;
+    cp.init(lane, wave, ld);
+    TileAddr ad;
+    ad.init(lane);
+    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
+    const char *vbase = kbase + h * 2;
+    const int64_t tile_stride = (int64_t)kTile * ld * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
 
     f32x16 oacc[4];
 #pragma unroll
@@ -116,32 +140,29 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16 *__restri
     float m_run = -INFINITY, l_run = 0.0f;
 
     const int n_tiles = (q0 + 128) / kTile;
-    lk.load(0);
-    lv.load(0);
-    lk.store_row(Ks);
-    lv.store_tr(Vs);
+    cp.issue(kbase, lds0, wave);
+    cp.issue(vbase, lds0 + kTileBytes, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int jt = 0; jt < n_tiles; ++jt) {
         const int buf = jt & 1;
         if (jt + 1 < n_tiles) {
-            lk.load((int64_t)(jt + 1) * kTile * ld);
-            lv.load((int64_t)(jt + 1) * kTile * ld);
+            cp.issue(kbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
+            cp.issue(vbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
         }
         const int kv0 = jt * kTile;
         if (kv0 <= qw0 + 31) {  // wave-uniform: this wave has unmasked entries in the tile
-            const bf16 *ks = Ks + buf * kTileElems;
-            const bf16 *vs = Vs + buf * kTileElems;
+            const unsigned char *ks = smem + buf * 2 * kTileBytes;
+            const unsigned char *vs = ks + kTileBytes;
             f32x16 sacc[2];
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) sacc[T][e] = 0.0f;
 #pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + off_row(32 * T + c, 2 * st + g));
-                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc[T], 0, 0, 0);
-                }
+                for (int st = 0; st < 8; ++st)
+                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc[T], 0, 0, 0);
             }
             // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c
             const bool need_mask = kv0 + kTile - 1 > qw0;
@@ -179,19 +200,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16 *__restri
                 for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
             // O^T[dv, q] += sum_kv V^T[dv, kv] P^T[kv, q]
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const int k0 = 32 * (st >> 1) + 16 * (st & 1) + 4 * g;
+            for (int st = 0; st < 4; ++st)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const bf16x8 vf = read_tr8(vs, k0, k0 + 8, 32 * t + ((lane >> 4) & 1) * 16, lane);
-                    oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st], oacc[t], 0, 0, 0);
-                }
-            }
+                for (int t = 0; t < 4; ++t)
+                    oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(vs, ad, t, st), pf[st], oacc[t], 0, 0, 0);
         }
-        if (jt + 1 < n_tiles) {
-            lk.store_row(Ks + (buf ^ 1) * kTileElems);
-            lv.store_tr(Vs + (buf ^ 1) * kTileElems);
-        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
 
@@ -214,23 +228,20 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16 *__restri
 // ------------------------------------------------------------------------------------ backward: dQ
 // Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
 // in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
-// taken from a second copy of the key tile through the transposing load.
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                               const bf16 *__restrict__ dattn,
-                                                               const float *__restrict__ lse,
-                                                               const float *__restrict__ delta,
-                                                               bf16 *__restrict__ dqkv, int seq, int nh, float scale,
-                                                               float scale_log2e)
+// gathered from the same key tile through the transposing load.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                  const bf16 *__restrict__ dattn,
+                                                                  const float *__restrict__ lse,
+                                                                  const float *__restrict__ delta,
+                                                                  bf16 *__restrict__ dqkv, int seq, int nh,
+                                                                  float scale, float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *Kr = reinterpret_cast<bf16 *>(smem_raw);  // [2][tile] row layout
-    bf16 *Kt = Kr + 2 * kTileElems;                 // [2][tile] tr layout
-    bf16 *Vr = Kt + 2 * kTileElems;                 // [2][tile] row layout
-
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][K tile | V tile]
     const int qb = gridDim.x - 1 - blockIdx.x;
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
     const int q0 = qb * 128, qw0 = q0 + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
@@ -249,9 +260,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16 *__res
     const float l2 = lse[stat] * 1.44269504088896340736f;
     const float dl = delta[stat];
 
-    TileLoader lk, lv;
-    lk.init(qkv + row0 * ld + h + (int64_t)n * kD, ld, tid);
-    lv.init(qkv + row0 * ld + 2 * h + (int64_t)n * kD, ld, tid);
+    TileCopy cp;
+    cp.init(lane, wave, ld);
+    TileAddr ad;
+    ad.init(lane);
+    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
+    const char *vbase = kbase + h * 2;
+    const int64_t tile_stride = (int64_t)kTile * ld * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
 
     f32x16 dqacc[4];
 #pragma unroll
@@ -260,66 +276,53 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16 *__res
         for (int e = 0; e < 16; ++e) dqacc[t][e] = 0.0f;
 
     const int n_tiles = (q0 + 128) / kTile;
-    lk.load(0);
-    lv.load(0);
-    lk.store_row(Kr);
-    lk.store_tr(Kt);
-    lv.store_row(Vr);
+    cp.issue(kbase, lds0, wave);
+    cp.issue(vbase, lds0 + kTileBytes, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int jt = 0; jt < n_tiles; ++jt) {
         const int buf = jt & 1;
         if (jt + 1 < n_tiles) {
-            lk.load((int64_t)(jt + 1) * kTile * ld);
-            lv.load((int64_t)(jt + 1) * kTile * ld);
+            cp.issue(kbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
+            cp.issue(vbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
         }
         const int kv0 = jt * kTile;
         if (kv0 <= qw0 + 31) {
-            const bf16 *kr = Kr + buf * kTileElems, *kt = Kt + buf * kTileElems, *vr = Vr + buf * kTileElems;
-            f32x16 sacc[2], dpacc[2];
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[T][e] = 0.0f;
-                    dpacc[T][e] = 0.0f;
-                }
-#pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kr + off_row(32 * T + c, 2 * st + g));
-                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc[T], 0, 0, 0);
-                    const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vr + off_row(32 * T + c, 2 * st + g));
-                    dpacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[st], dpacc[T], 0, 0, 0);
-                }
-            }
+            const unsigned char *ks = smem + buf * 2 * kTileBytes;
+            const unsigned char *vs = ks + kTileBytes;
             const bool need_mask = kv0 + kTile - 1 > qw0;
             bf16x8 dsf[4];
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+            for (int T = 0; T < 2; ++T) {
+                f32x16 sacc, dpacc;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    float p = fast_exp2(sacc[T][e] * scale_log2e - l2);
+                    sacc[e] = 0.0f;
+                    dpacc[e] = 0.0f;
+                }
+#pragma unroll
+                for (int st = 0; st < 8; ++st) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(vs, ad, T, st), dof[st], dpacc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float p = fast_exp2(sacc[e] * scale_log2e - l2);
                     if (need_mask) {
                         const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
                         if (kv > qw0 + c) p = 0.0f;
                     }
-                    dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[T][e] - dl));
-                }
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const int k0 = 32 * (st >> 1) + 16 * (st & 1) + 4 * g;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const bf16x8 ktf = read_tr8(kt, k0, k0 + 8, 32 * t + ((lane >> 4) & 1) * 16, lane);
-                    dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[st], dqacc[t], 0, 0, 0);
+                    dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[e] - dl));
                 }
             }
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ks, ad, t, st), dsf[st], dqacc[t], 0, 0, 0);
         }
-        if (jt + 1 < n_tiles) {
-            lk.store_row(Kr + (buf ^ 1) * kTileElems);
-            lk.store_tr(Kt + (buf ^ 1) * kTileElems);
-            lv.store_row(Vr + (buf ^ 1) * kTileElems);
-        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
     bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16 *__res
 // ------------------------------------------------------------------------------------ backward: dK, dV
 // Lane = key.  Per query tile: S = Q K^T and dP = dO V^T (operands Q, dO row-wise from LDS; K, V in
 // registers), P = exp2(S*c - lse[q]), dS = P o (dP - delta[q]); dV^T += dO^T P and dK^T += Q^T dS with
-// dO^T, Q^T taken from second copies of the tiles through the transposing load.
+// dO^T, Q^T gathered from the same tiles through the transposing load.
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
                                                                 const bf16 *__restrict__ dattn,
                                                                 const float *__restrict__ lse,
@@ -345,16 +348,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
                                                                 bf16 *__restrict__ dqkv, int seq, int nh, float scale,
                                                                 float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *Qr = reinterpret_cast<bf16 *>(smem_raw);  // [2][tile]
-    bf16 *Qt = Qr + 2 * kTileElems;
-    bf16 *Dr = Qt + 2 * kTileElems;
-    bf16 *Dt = Dr + 2 * kTileElems;
-
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][Q tile | dO tile]
     const int kb = blockIdx.x;  // early key blocks see the most queries and come first
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
     const int kv0 = kb * 128, kvw0 = kv0 + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
@@ -368,9 +367,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
             vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
         }
     }
-    TileLoader lq, ld_o;
-    lq.init(qkv + row0 * ld + (int64_t)n * kD, ld, tid);
-    ld_o.init(dattn + row0 * h + (int64_t)n * kD, h, tid);
+    TileCopy cq, cd;
+    cq.init(lane, wave, ld);
+    cd.init(lane, wave, h);
+    TileAddr ad;
+    ad.init(lane);
+    const char *qbase = reinterpret_cast<const char *>(qkv + row0 * ld + (int64_t)n * kD);
+    const char *dbase = reinterpret_cast<const char *>(dattn + row0 * h + (int64_t)n * kD);
+    const int64_t q_stride = (int64_t)kTile * ld * 2, d_stride = (int64_t)kTile * h * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
     const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
 
@@ -384,45 +389,37 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
         }
 
     const int it0 = kv0 / kTile, n_tiles = seq / kTile;
-    lq.load((int64_t)it0 * kTile * ld);
-    ld_o.load((int64_t)it0 * kTile * h);
-    lq.store_row(Qr);
-    lq.store_tr(Qt);
-    ld_o.store_row(Dr);
-    ld_o.store_tr(Dt);
+    cq.issue(qbase + it0 * q_stride, lds0, wave);
+    cd.issue(dbase + it0 * d_stride, lds0 + kTileBytes, wave);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int it = it0; it < n_tiles; ++it) {
         const int buf = (it - it0) & 1;
         if (it + 1 < n_tiles) {
-            lq.load((int64_t)(it + 1) * kTile * ld);
-            ld_o.load((int64_t)(it + 1) * kTile * h);
+            cq.issue(qbase + (it + 1) * q_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
+            cd.issue(dbase + (it + 1) * d_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
         }
         const int qt0 = it * kTile;
         if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
-            const bf16 *qr = Qr + buf * kTileElems, *qt = Qt + buf * kTileElems;
-            const bf16 *dr = Dr + buf * kTileElems, *dtp = Dt + buf * kTileElems;
-            f32x16 sacc[2], dpacc[2];
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[T][e] = 0.0f;
-                    dpacc[T][e] = 0.0f;
-                }
-#pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qr + off_row(32 * T + c, 2 * st + g));
-                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[st], sacc[T], 0, 0, 0);
-                    const bf16x8 df = *reinterpret_cast<const bf16x8 *>(dr + off_row(32 * T + c, 2 * st + g));
-                    dpacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(df, vf[st], dpacc[T], 0, 0, 0);
-                }
-            }
-            // sacc[T][e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
+            const unsigned char *qs = smem + buf * 2 * kTileBytes;
+            const unsigned char *ds = qs + kTileBytes;
             const bool need_mask = qt0 < kvw0 + 31;
             bf16x8 pf[4], dsf[4];
 #pragma unroll
-            for (int T = 0; T < 2; ++T)
+            for (int T = 0; T < 2; ++T) {
+                f32x16 sacc, dpacc;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    sacc[e] = 0.0f;
+                    dpacc[e] = 0.0f;
+                }
+#pragma unroll
+                for (int st = 0; st < 8; ++st) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(qs, ad, T, st), kf[st], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
+                }
+                // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     const int qrel = 32 * T + 8 * e4 + 4 * g;
@@ -431,31 +428,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int e = e4 * 4 + r;
-                        float p = fast_exp2(sacc[T][e] * scale_log2e - l4[r] * 1.44269504088896340736f);
+                        float p = fast_exp2(sacc[e] * scale_log2e - l4[r] * 1.44269504088896340736f);
                         if (need_mask && (kvw0 + c > qt0 + qrel + r)) p = 0.0f;
                         pf[2 * T + (e >> 3)][e & 7] = (bf16)p;
-                        dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[T][e] - d4[r]));
+                        dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[e] - d4[r]));
                     }
                 }
+            }
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const int k0 = 32 * (st >> 1) + 16 * (st & 1) + 4 * g;
+            for (int st = 0; st < 4; ++st)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const int col = 32 * t + ((lane >> 4) & 1) * 16;
-                    const bf16x8 dotf = read_tr8(dtp, k0, k0 + 8, col, lane);
-                    dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotf, pf[st], dvacc[t], 0, 0, 0);
-                    const bf16x8 qtf = read_tr8(qt, k0, k0 + 8, col, lane);
-                    dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf[st], dkacc[t], 0, 0, 0);
+                    dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ds, ad, t, st), pf[st], dvacc[t], 0, 0, 0);
+                    dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(qs, ad, t, st), dsf[st], dkacc[t], 0, 0, 0);
                 }
-            }
         }
-        if (it + 1 < n_tiles) {
-            lq.store_row(Qr + (buf ^ 1) * kTileElems);
-            lq.store_tr(Qt + (buf ^ 1) * kTileElems);
-            ld_o.store_row(Dr + (buf ^ 1) * kTileElems);
-            ld_o.store_tr(Dt + (buf ^ 1) * kTileElems);
-        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
     bf16 *okp = dqkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD;
@@ -509,7 +497,7 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    constexpr size_t lds = 4 * kTileElems * sizeof(bf16);  // 64 KB
+    constexpr size_t lds = 4 * kTileBytes;  // 64 KB: two buffers of (K tile, V tile)
     static bool attr_set = false;
     if (hipError_t e = set_lds(attn_fwd_mfma_kernel, lds, attr_set)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
@@ -524,8 +512,8 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
     static bool a1 = false, a2 = false;
-    constexpr size_t lds_dq = 6 * kTileElems * sizeof(bf16);   // 96 KB
-    constexpr size_t lds_dkv = 8 * kTileElems * sizeof(bf16);  // 128 KB
+    constexpr size_t lds_dq = 4 * kTileBytes;   // two buffers of (K tile, V tile)
+    constexpr size_t lds_dkv = 4 * kTileBytes;  // two buffers of (Q tile, dO tile)
     if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel, lds_dq, a1)) return e;
     if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel, lds_dkv, a2)) return e;
     const float scale = 1.0f / sqrtf((float)d);
