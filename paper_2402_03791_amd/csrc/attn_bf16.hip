@@ -8,8 +8,8 @@
 // transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one
 // value column.  The softmax never leaves registers; only O and the log-sum-exp are written.
 //
-// Backward: two kernels without atomics.  dQ: same structure as forward (lane = query), loops over
-// key tiles.  dK/dV: lane = key, loops over query tiles.  P is recomputed from the saved
+// Backward: three kernels without atomics.  dQ: same structure as forward (lane = query), loops over
+// key tiles.  dK and dV: lane = key, loop over query tiles.  P is recomputed from the saved
 // log-sum-exp; delta = rowsum(dO o O) is computed by a small kernel first.
 #include "device_utils.h"
 #include "kernels.h"
@@ -338,17 +338,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__
 }
 
 // ------------------------------------------------------------------------------------ backward: dK, dV
-// Lane = key.  Per query tile: S = Q K^T and dP = dO V^T (operands Q, dO row-wise from LDS; K, V in
-// registers), P = exp2(S*c - lse[q]), dS = P o (dP - delta[q]); dV^T += dO^T P and dK^T += Q^T dS with
-// dO^T, Q^T gathered from the same tiles through the transposing load.
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                const bf16 *__restrict__ dattn,
-                                                                const float *__restrict__ lse,
-                                                                const float *__restrict__ delta,
-                                                                bf16 *__restrict__ dqkv, int seq, int nh, float scale,
-                                                                float scale_log2e)
+// Lane = key.  Per query tile: S = Q K^T (operands Q row-wise from LDS, K in registers),
+// P = exp2(S*c - lse[q]).  Two instantiations, so that each fits two waves per SIMD:
+//   DK = false: dV^T += dO^T P, with dO^T gathered from the dO tile through the transposing load;
+//   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
+// Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy.
+template <bool DK>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                   const bf16 *__restrict__ dattn,
+                                                                   const float *__restrict__ lse,
+                                                                   const float *__restrict__ delta,
+                                                                   bf16 *__restrict__ dqkv, int seq, int nh,
+                                                                   float scale, float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][Q tile | dO tile]
+    // [2][Q tile | dO tile], then [2][lse of the tile's 64 queries | delta of the same].  The per-query
+    // statistics travel with the tiles (a 4-byte-per-lane global->LDS load each): fetching them with
+    // ordinary loads inside the loop would make every use wait, in order, behind the next tile's copies.
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int kb = blockIdx.x;  // early key blocks see the most queries and come first
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
@@ -358,13 +364,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
     const int kv0 = kb * 128, kvw0 = kv0 + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
 
-    bf16x8 kf[8], vf[8];
+    bf16x8 kf[8], vf[DK ? 8 : 1];
     {
         const bf16 *kp = qkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD + 8 * g;
 #pragma unroll
         for (int st = 0; st < 8; ++st) {
             kf[st] = *reinterpret_cast<const bf16x8 *>(kp + 16 * st);
-            vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
+            if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
         }
     }
     TileCopy cq, cd;
@@ -378,19 +384,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
     const uint32_t lds0 = lds_addr_of(smem);
     const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
+    const uint32_t stat0 = lds0 + 4 * kTileBytes;
+    const uint32_t lane4 = lane * 4;
+    auto issue_stats = [&](int it, int buf) {
+        if (wave == 0) {
+            const uint32_t dst = stat0 + buf * 512;
+            const float *src = lse_b + it * kTile;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
+        } else if (wave == 1 && DK) {
+            const uint32_t dst = stat0 + buf * 512 + 256;
+            const float *src = del_b + it * kTile;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
+        }
+    };
 
-    f32x16 dkacc[4], dvacc[4];
+    f32x16 acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            dkacc[t][e] = 0.0f;
-            dvacc[t][e] = 0.0f;
-        }
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
     const int it0 = kv0 / kTile, n_tiles = seq / kTile;
     cq.issue(qbase + it0 * q_stride, lds0, wave);
     cd.issue(dbase + it0 * d_stride, lds0 + kTileBytes, wave);
+    issue_stats(it0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -399,13 +416,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
         if (it + 1 < n_tiles) {
             cq.issue(qbase + (it + 1) * q_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
             cd.issue(dbase + (it + 1) * d_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
+            issue_stats(it + 1, buf ^ 1);
         }
         const int qt0 = it * kTile;
         if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
             const unsigned char *qs = smem + buf * 2 * kTileBytes;
             const unsigned char *ds = qs + kTileBytes;
+            const float *lse_s = reinterpret_cast<const float *>(smem + 4 * kTileBytes + buf * 512);
+            const float *del_s = lse_s + 64;
             const bool need_mask = qt0 < kvw0 + 31;
-            bf16x8 pf[4], dsf[4];
+            bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
                 f32x16 sacc, dpacc;
@@ -417,48 +437,46 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16 *__re
 #pragma unroll
                 for (int st = 0; st < 8; ++st) {
                     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(qs, ad, T, st), kf[st], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
+                    if constexpr (DK)
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
                 }
                 // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     const int qrel = 32 * T + 8 * e4 + 4 * g;
-                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_b + qt0 + qrel);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4 *>(del_b + qt0 + qrel);
+                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
+                    f32x4 d4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if constexpr (DK) d4 = *reinterpret_cast<const f32x4 *>(del_s + qrel);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int e = e4 * 4 + r;
                         float p = fast_exp2(sacc[e] * scale_log2e - l4[r] * 1.44269504088896340736f);
                         if (need_mask && (kvw0 + c > qt0 + qrel + r)) p = 0.0f;
-                        pf[2 * T + (e >> 3)][e & 7] = (bf16)p;
-                        dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[e] - d4[r]));
+                        frag[2 * T + (e >> 3)][e & 7] = DK ? (bf16)(p * (dpacc[e] - d4[r])) : (bf16)p;
                     }
                 }
             }
+            const unsigned char *src = DK ? qs : ds;  // dK^T += Q^T dS ; dV^T += dO^T P
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ds, ad, t, st), pf[st], dvacc[t], 0, 0, 0);
-                    dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(qs, ad, t, st), dsf[st], dkacc[t], 0, 0, 0);
-                }
+                for (int t = 0; t < 4; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(src, ad, t, st), frag[st], acc[t], 0, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-    bf16 *okp = dqkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD;
+    // K gradient goes to the K part of dqkv (scaled), V gradient to the V part
+    bf16 *out = dqkv + (row0 + kvw0 + c) * ld + (DK ? h : 2 * h) + (int64_t)n * kD;
+    const float oscale = DK ? scale : 1.0f;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 ok, ov;
+            bf16x4 o;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                ok[r] = (bf16)(dkacc[t][e4 * 4 + r] * scale);
-                ov[r] = (bf16)dvacc[t][e4 * 4 + r];
-            }
-            *reinterpret_cast<bf16x4 *>(okp + 32 * t + 8 * e4 + 4 * g) = ok;
-            *reinterpret_cast<bf16x4 *>(okp + h + 32 * t + 8 * e4 + 4 * g) = ov;
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(acc[t][e4 * 4 + r] * oscale);
+            *reinterpret_cast<bf16x4 *>(out + 32 * t + 8 * e4 + 4 * g) = o;
         }
 }
 
@@ -511,11 +529,12 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    static bool a1 = false, a2 = false;
+    static bool a1 = false, a2 = false, a3 = false;
     constexpr size_t lds_dq = 4 * kTileBytes;   // two buffers of (K tile, V tile)
-    constexpr size_t lds_dkv = 4 * kTileBytes;  // two buffers of (Q tile, dO tile)
+    constexpr size_t lds_dkv = 4 * kTileBytes + 1024;  // two buffers of (Q tile, dO tile) + their lse/delta
     if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel, lds_dkv, a2)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<true>, lds_dkv, a2)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false>, lds_dkv, a3)) return e;
     const float scale = 1.0f / sqrtf((float)d);
     const float scale_log2e = scale * 1.44269504088896340736f;
     const int64_t rows = b * seq;
@@ -524,8 +543,10 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     const dim3 grid((unsigned)(seq / 128), (unsigned)nh, (unsigned)b);
     attn_bwd_dq_mfma_kernel<<<grid, 256, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
                                                       (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<<<grid, 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                        (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<true><<<grid, 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
+                                                              (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<false><<<grid, 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
+                                                               (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
     return hipGetLastError();
 }
 
