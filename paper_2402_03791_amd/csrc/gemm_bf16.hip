@@ -96,6 +96,10 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         const int64_t n = n_wave + j * 32 + c32;
         bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
     }
+    // The loop over the passes is a real loop: unrolled, the element-wise tail (with its GeLU branches)
+    // would be replicated MT * PASSES times and the epilogue would run at the speed of instruction
+    // fetch.  The 32-row groups stay instantiated one by one, since accumulator registers can only be
+    // indexed with constants.
     static_for<MT>([&](auto ii) {
         constexpr int i = decltype(ii)::value;
         static_for<NT>([&](auto jj) {
@@ -107,7 +111,7 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         // the slice is private to this wave; LDS operations of a wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
+#pragma unroll 1
         for (int p = 0; p < PASSES; ++p) {
             const int row = p * ROWS_PER_PASS + lane / CH;
             const int c8 = lane % CH;
@@ -146,7 +150,11 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
                     }
                 }
             } else {
-                for (int k = 0; k < 8 && n + k < N; ++k) epi_store_one(v[k], o_idx + k, Cv, epi);
+                // ragged or unaligned edge: element by element (stage is re-read so that v[] is never
+                // indexed with a loop variable)
+#pragma unroll 1
+                for (int k = 0; k < 8; ++k)
+                    if (n + k < N) epi_store_one(stage[row * STRIDE + c8 * 8 + k], o_idx + k, Cv, epi);
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
