@@ -111,6 +111,27 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         // the slice is private to this wave; LDS operations of a wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (epi.out_f32 && vec_ok && !epi.resid && epi.act == ACT_NONE) {
+            // fp32 output (weight gradients): a lane owns 4 consecutive columns, so that one store
+            // instruction writes whole rows of the wave's slice (full 128-byte lines)
+            constexpr int CH4 = WN / 4, ROWS4 = 64 / CH4, PASSES4 = 32 / ROWS4;
+#pragma unroll 1
+            for (int p = 0; p < PASSES4; ++p) {
+                const int row = p * ROWS4 + lane / CH4;
+                const int c4 = lane % CH4;
+                const int64_t m = m_wave + i * 32 + row;
+                const int64_t n = n_wave + c4 * 4;
+                const f32x4 val = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c4 * 4);
+                if (m >= M || n >= N) continue;
+                float *cf = reinterpret_cast<float *>(Cv) + m * ldc + n;
+                if (n + 4 <= N) {
+                    // next read by the accumulate pass, long after: streamed past the caches
+                    __builtin_nontemporal_store(val, reinterpret_cast<f32x4 *>(cf));
+                } else {
+                    for (int k = 0; k < 4 && n + k < N; ++k) cf[k] = stage[row * STRIDE + c4 * 4 + k];
+                }
+            }
+        } else
 #pragma unroll 1
         for (int p = 0; p < PASSES; ++p) {
             const int row = p * ROWS_PER_PASS + lane / CH;
