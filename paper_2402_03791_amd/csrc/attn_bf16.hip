@@ -1,7 +1,12 @@
 // Fused causal attention for bf16, head dim 128, on gfx950 MFMA (v_mfma_f32_32x32x16_bf16).
 //
-// Forward: one work-group per (sample, head, block of 128 queries), four wavefronts of 32 queries
-// each.  Keys/values stream through LDS in tiles of 64 rows (double buffered).  Scores are computed
+// Forward: every wavefront owns a group of 32 queries; a work-group is either four consecutive groups
+// (128 queries) or, when the sequence is a multiple of 256, eight wavefronts: four consecutive groups
+// and their mirror images from the other end of the sequence.  Under the causal mask group i has
+// work proportional to i+1, and the two wavefronts that share a SIMD (w and w+4) hold groups i and
+// G-1-i, so every SIMD of every work-group gets the same amount of work and the whole grid finishes
+// together (plain 128-query work-groups range from 2 to 2s/128 tiles and the launch lasts as long as
+// the heaviest).  Keys/values stream through LDS in tiles of 64 rows (double buffered).  Scores are computed
 // transposed, S^T = K Q^T, so that a lane owns one query column and the softmax row reductions are
 // in-lane plus one exchange with the lane 32 away; the probabilities then feed the second product
 // O^T = V^T P^T straight from the accumulator registers.  The value tile is read with the LDS
@@ -31,15 +36,17 @@ constexpr int kTileBytes = kTile * kD * 2;  // 16 KB
 //    the row, bits 0..1 the chunk, again 16 different positions.
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-// Global -> LDS copy of a tile, 4 load instructions per wave (4 rows of 256 bytes each): lane i of a
-// load lands at byte 16*i of the 1 KB slot, so it fetches the chunk the swizzle assigns to that place.
+// Global -> LDS copy of a tile, 16 load instructions shared by the NW waves (4 rows of 256 bytes each):
+// lane i of a load lands at byte 16*i of the 1 KB slot, so it fetches the chunk the swizzle assigns to that place.
+template <int NW>
 struct TileCopy {
-    uint32_t voff[4];
+    static constexpr int NL = 16 / NW;  // loads per wave per tile
+    uint32_t voff[NL];
     __device__ __forceinline__ void init(int lane, int wave, int64_t ld_elems)
     {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row = wave * 16 + j * 4 + (lane >> 4);
+        for (int j = 0; j < NL; ++j) {
+            const int row = wave * (64 / NW) + j * 4 + (lane >> 4);
             const int c = (lane & 15) ^ swz(row);
             voff[j] = (uint32_t)((row * ld_elems + c * 8) * 2);
         }
@@ -48,8 +55,8 @@ struct TileCopy {
     __device__ __forceinline__ void issue(const char *base, uint32_t lds_tile, int wave) const
     {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t dst = lds_tile + wave * 4096 + j * 1024;
+        for (int j = 0; j < NL; ++j) {
+            const uint32_t dst = lds_tile + wave * (16384 / NW) + j * 1024;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(dst), "v"(voff[j]), "s"(base)
@@ -57,6 +64,16 @@ struct TileCopy {
         }
     }
 };
+
+// The 32-row group of the sequence that wave `wave` of work-group `blk` owns (n_groups = seq / 32).
+template <int NW>
+__device__ __forceinline__ int wave_group(int blk, int wave, int n_groups)
+{
+    if constexpr (NW == 4)
+        return blk * 4 + wave;
+    else
+        return wave < 4 ? blk * 4 + wave : n_groups - 1 - (blk * 4 + wave - 4);
+}
 
 // Per-lane LDS byte offsets (inside a tile) for the two read patterns.
 struct TileAddr {
@@ -95,6 +112,18 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+// LDS stages of a streamed operand pair: the copies of a pair are issued kStages-1 iterations before
+// it is used.  One iteration of lookahead does not cover the memory round trip (an iteration is
+// ~2000 cycles of MFMA + softmax work); the eight-wave kernels run one work-group per CU and can
+// afford four stages of 32 KB.
+template <int NW>
+constexpr int kStages = NW == 8 ? 4 : 2;
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
@@ -103,18 +132,21 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 }
 
 // ------------------------------------------------------------------------------------ forward
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
-                                                               float *__restrict__ lse, int seq, int nh,
-                                                               float scale_log2e)
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                    bf16 *__restrict__ attn,
+                                                                    float *__restrict__ lse, int seq, int nh,
+                                                                    float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][K tile | V tile]
-    const int qb = gridDim.x - 1 - blockIdx.x;  // heavy (late) query blocks first
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
+    // NW == 4: heavy (late) query blocks first; NW == 8: all work-groups are equally heavy
+    const int qb = NW == 4 ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
-    const int q0 = qb * 128, qw0 = q0 + 32 * wave;
+    const int qw0 = 32 * wave_group<NW>(qb, wave, seq / 32);
     const int64_t row0 = (int64_t)bi * seq;
 
     bf16x8 qf[8];
@@ -123,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
 #pragma unroll
         for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
     }
-    TileCopy cp;
+    TileCopy<NW> cp;
     cp.init(lane, wave, ld);
     TileAddr ad;
     ad.init(lane);
@@ -139,17 +171,26 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
         for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
-    const int n_tiles = (q0 + 128) / kTile;
-    cp.issue(kbase, lds0, wave);
-    cp.issue(vbase, lds0 + kTileBytes, wave);
+    // key tiles up to the last query of the work-group's latest group
+    const int n_tiles = NW == 4 ? (qb * 128 + 128) / kTile : (seq / 32 - 4 * qb) / 2;
+    constexpr int S = kStages<NW>;
+    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;  // copies per wave per (K, V) pair
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j)
+        if (j < n_tiles) {
+            cp.issue(kbase + j * tile_stride, lds0 + j * 2 * kTileBytes, wave);
+            cp.issue(vbase + j * tile_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
+        }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt & 1;
-        if (jt + 1 < n_tiles) {
-            cp.issue(kbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
-            cp.issue(vbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
+        const int buf = jt % S;
+        const bool more = jt + S - 1 < n_tiles;
+        if (more) {
+            const int nb = (jt + S - 1) % S;  // the stage read in the previous iteration
+            cp.issue(kbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes, wave);
+            cp.issue(vbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
         }
         const int kv0 = jt * kTile;
         if (kv0 <= qw0 + 31) {  // wave-uniform: this wave has unmasked entries in the tile
@@ -205,7 +246,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
                 for (int t = 0; t < 4; ++t)
                     oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(vs, ad, t, st), pf[st], oacc[t], 0, 0, 0);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // the next pair must have landed; the S-2 pairs after it may stay in flight (copies complete in order)
+        if (more)
+            wait_vmcnt<(S - 2) * PER_TILE>();
+        else
+            wait_vmcnt<0>();
         __syncthreads();
     }
 
@@ -229,21 +274,22 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(const bf16 *__res
 // Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
 // in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
 // gathered from the same key tile through the transposing load.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                  const bf16 *__restrict__ dattn,
-                                                                  const float *__restrict__ lse,
-                                                                  const float *__restrict__ delta,
-                                                                  bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                  float scale, float scale_log2e)
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                       const bf16 *__restrict__ dattn,
+                                                                       const float *__restrict__ lse,
+                                                                       const float *__restrict__ delta,
+                                                                       bf16 *__restrict__ dqkv, int seq, int nh,
+                                                                       float scale, float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][K tile | V tile]
-    const int qb = gridDim.x - 1 - blockIdx.x;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
+    const int qb = NW == 4 ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
-    const int q0 = qb * 128, qw0 = q0 + 32 * wave;
+    const int qw0 = 32 * wave_group<NW>(qb, wave, seq / 32);
     const int64_t row0 = (int64_t)bi * seq;
 
     bf16x8 qf[8], dof[8];
@@ -260,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__
     const float l2 = lse[stat] * 1.44269504088896340736f;
     const float dl = delta[stat];
 
-    TileCopy cp;
+    TileCopy<NW> cp;
     cp.init(lane, wave, ld);
     TileAddr ad;
     ad.init(lane);
@@ -275,17 +321,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__
 #pragma unroll
         for (int e = 0; e < 16; ++e) dqacc[t][e] = 0.0f;
 
-    const int n_tiles = (q0 + 128) / kTile;
-    cp.issue(kbase, lds0, wave);
-    cp.issue(vbase, lds0 + kTileBytes, wave);
+    const int n_tiles = NW == 4 ? (qb * 128 + 128) / kTile : (seq / 32 - 4 * qb) / 2;
+    constexpr int S = kStages<NW>;
+    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;  // copies per wave per (K, V) pair
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j)
+        if (j < n_tiles) {
+            cp.issue(kbase + j * tile_stride, lds0 + j * 2 * kTileBytes, wave);
+            cp.issue(vbase + j * tile_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
+        }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt & 1;
-        if (jt + 1 < n_tiles) {
-            cp.issue(kbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
-            cp.issue(vbase + (jt + 1) * tile_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
+        const int buf = jt % S;
+        const bool more = jt + S - 1 < n_tiles;
+        if (more) {
+            const int nb = (jt + S - 1) % S;  // the stage read in the previous iteration
+            cp.issue(kbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes, wave);
+            cp.issue(vbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
         }
         const int kv0 = jt * kTile;
         if (kv0 <= qw0 + 31) {
@@ -322,7 +376,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__
                 for (int t = 0; t < 4; ++t)
                     dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ks, ad, t, st), dsf[st], dqacc[t], 0, 0, 0);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (more)
+            wait_vmcnt<(S - 2) * PER_TILE>();
+        else
+            wait_vmcnt<0>();
         __syncthreads();
     }
     bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
@@ -343,25 +400,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__
 //   DK = false: dV^T += dO^T P, with dO^T gathered from the dO tile through the transposing load;
 //   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
 // Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy.
-template <bool DK>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
+template <bool DK, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
                                                                    const bf16 *__restrict__ dattn,
                                                                    const float *__restrict__ lse,
                                                                    const float *__restrict__ delta,
                                                                    bf16 *__restrict__ dqkv, int seq, int nh,
                                                                    float scale, float scale_log2e)
 {
-    // [2][Q tile | dO tile], then [2][lse of the tile's 64 queries | delta of the same].  The per-query
+    // [kStages][Q tile | dO tile], then [kStages][lse of the tile's 64 queries | delta of the same].  The per-query
     // statistics travel with the tiles (a 4-byte-per-lane global->LDS load each): fetching them with
     // ordinary loads inside the loop would make every use wait, in order, behind the next tile's copies.
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int kb = blockIdx.x;  // early key blocks see the most queries and come first
+    const int kb = blockIdx.x;  // NW == 4: early key blocks see the most queries and come first
     const int n = blockIdx.y, bi = blockIdx.z;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, c = lane & 31;
-    const int kv0 = kb * 128, kvw0 = kv0 + 32 * wave;
+    const int kvw0 = 32 * wave_group<NW>(kb, wave, seq / 32);
     const int64_t row0 = (int64_t)bi * seq;
 
     bf16x8 kf[8], vf[DK ? 8 : 1];
@@ -373,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *_
             if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
         }
     }
-    TileCopy cq, cd;
+    TileCopy<NW> cq, cd;
     cq.init(lane, wave, ld);
     cd.init(lane, wave, h);
     TileAddr ad;
@@ -384,7 +441,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *_
     const uint32_t lds0 = lds_addr_of(smem);
     const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
-    const uint32_t stat0 = lds0 + 4 * kTileBytes;
+    constexpr int S = kStages<NW>;
+    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;
+    const uint32_t stat0 = lds0 + S * 2 * kTileBytes;
     const uint32_t lane4 = lane * 4;
     auto issue_stats = [&](int it, int buf) {
         if (wave == 0) {
@@ -404,25 +463,32 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *_
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
-    const int it0 = kv0 / kTile, n_tiles = seq / kTile;
-    cq.issue(qbase + it0 * q_stride, lds0, wave);
-    cd.issue(dbase + it0 * d_stride, lds0 + kTileBytes, wave);
-    issue_stats(it0, 0);
+    // query tiles from the diagonal of the work-group's earliest group (4 * kb) to the end
+    const int it0 = 2 * kb, n_tiles = seq / kTile;
+#pragma unroll
+    for (int j = 0; j < S - 1; ++j)
+        if (it0 + j < n_tiles) {
+            cq.issue(qbase + (it0 + j) * q_stride, lds0 + j * 2 * kTileBytes, wave);
+            cd.issue(dbase + (it0 + j) * d_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
+            issue_stats(it0 + j, j);
+        }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int it = it0; it < n_tiles; ++it) {
-        const int buf = (it - it0) & 1;
-        if (it + 1 < n_tiles) {
-            cq.issue(qbase + (it + 1) * q_stride, lds0 + (buf ^ 1) * 2 * kTileBytes, wave);
-            cd.issue(dbase + (it + 1) * d_stride, lds0 + (buf ^ 1) * 2 * kTileBytes + kTileBytes, wave);
-            issue_stats(it + 1, buf ^ 1);
+        const int buf = (it - it0) % S;
+        const bool more = it + S - 1 < n_tiles;
+        if (more) {
+            const int nb = (it - it0 + S - 1) % S;
+            cq.issue(qbase + (it + S - 1) * q_stride, lds0 + nb * 2 * kTileBytes, wave);
+            cd.issue(dbase + (it + S - 1) * d_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
+            issue_stats(it + S - 1, nb);
         }
         const int qt0 = it * kTile;
         if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
             const unsigned char *qs = smem + buf * 2 * kTileBytes;
             const unsigned char *ds = qs + kTileBytes;
-            const float *lse_s = reinterpret_cast<const float *>(smem + 4 * kTileBytes + buf * 512);
+            const float *lse_s = reinterpret_cast<const float *>(smem + S * 2 * kTileBytes + buf * 512);
             const float *del_s = lse_s + 64;
             const bool need_mask = qt0 < kvw0 + 31;
             bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
@@ -463,7 +529,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *_
                 for (int t = 0; t < 4; ++t)
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(src, ad, t, st), frag[st], acc[t], 0, 0, 0);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // waves 0 and 1 carry one more copy per stage (the statistics)
+        if (!more)
+            wait_vmcnt<0>();
+        else if (wave == 0 || (DK && wave == 1))
+            wait_vmcnt<(S - 2) * (PER_TILE + 1)>();
+        else
+            wait_vmcnt<(S - 2) * PER_TILE>();
         __syncthreads();
     }
     // K gradient goes to the K part of dqkv (scaled), V gradient to the V part
@@ -515,12 +587,41 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    constexpr size_t lds = 4 * kTileBytes;  // 64 KB: two buffers of (K tile, V tile)
-    static bool attr_set = false;
-    if (hipError_t e = set_lds(attn_fwd_mfma_kernel, lds, attr_set)) return e;
+    constexpr size_t lds4 = kStages<4> * 2 * kTileBytes, lds8 = kStages<8> * 2 * kTileBytes;  // (K tile, V tile) stages
+    static bool a4 = false, a8 = false;
+    if (hipError_t e = set_lds(attn_fwd_mfma_kernel<4>, lds4, a4)) return e;
+    if (hipError_t e = set_lds(attn_fwd_mfma_kernel<8>, lds8, a8)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
-    const dim3 grid((unsigned)(seq / 128), (unsigned)nh, (unsigned)b);
-    attn_fwd_mfma_kernel<<<grid, 256, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, scale_log2e);
+    if (seq % 256 == 0) {
+        const dim3 grid((unsigned)(seq / 256), (unsigned)nh, (unsigned)b);
+        attn_fwd_mfma_kernel<8><<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
+                                                       scale_log2e);
+    } else {
+        const dim3 grid((unsigned)(seq / 128), (unsigned)nh, (unsigned)b);
+        attn_fwd_mfma_kernel<4><<<grid, 256, lds4, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
+                                                       scale_log2e);
+    }
+    return hipGetLastError();
+}
+
+template <int NW>
+static hipError_t launch_attn_bwd_nw(const void *qkv, const void *dattn, const float *lse, float *delta,
+                                     void *dqkv, int64_t b, int64_t seq, int64_t nh, float scale, hipStream_t s)
+{
+    static bool a1 = false, a2 = false, a3 = false;
+    constexpr size_t lds_dq = kStages<NW> * 2 * kTileBytes;                        // stages of (K tile, V tile)
+    constexpr size_t lds_dkv = kStages<NW> * 2 * kTileBytes + kStages<NW> * 512;  // (Q tile, dO tile) + lse/delta
+    if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel<NW>, lds_dq, a1)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<true, NW>, lds_dkv, a2)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false, NW>, lds_dkv, a3)) return e;
+    const float scale_log2e = scale * 1.44269504088896340736f;
+    const dim3 grid((unsigned)(seq / (32 * NW)), (unsigned)nh, (unsigned)b);
+    attn_bwd_dq_mfma_kernel<NW><<<grid, NW * 64, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
+                                                              (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<true, NW><<<grid, NW * 64, lds_dkv, s>>>(
+        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<false, NW><<<grid, NW * 64, lds_dkv, s>>>(
+        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
     return hipGetLastError();
 }
 
@@ -529,25 +630,12 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    static bool a1 = false, a2 = false, a3 = false;
-    constexpr size_t lds_dq = 4 * kTileBytes;   // two buffers of (K tile, V tile)
-    constexpr size_t lds_dkv = 4 * kTileBytes + 1024;  // two buffers of (Q tile, dO tile) + their lse/delta
-    if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<true>, lds_dkv, a2)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false>, lds_dkv, a3)) return e;
     const float scale = 1.0f / sqrtf((float)d);
-    const float scale_log2e = scale * 1.44269504088896340736f;
     const int64_t rows = b * seq;
     attn_delta_mfma_kernel<<<(unsigned)((rows * nh + 3) / 4), 256, 0, s>>>((const bf16 *)attn, (const bf16 *)dattn,
                                                                             delta, rows, (int)seq, (int)nh);
-    const dim3 grid((unsigned)(seq / 128), (unsigned)nh, (unsigned)b);
-    attn_bwd_dq_mfma_kernel<<<grid, 256, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                      (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<true><<<grid, 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                              (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<false><<<grid, 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                               (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    return hipGetLastError();
+    if (seq % 256 == 0) return launch_attn_bwd_nw<8>(qkv, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
+    return launch_attn_bwd_nw<4>(qkv, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
 }
 
 }  // namespace zpp
