@@ -19,6 +19,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace zpp {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -112,6 +114,26 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// Work-group -> (block of the sequence, head, sample) for a 1-D grid of nblk * nh * nb work-groups.
+// Work-groups are dealt round-robin over the 8 XCDs, each with a private L2: all work-groups of one
+// (sample, head) pair are given to the same XCD and to neighbouring dispatch slots, so that the head's
+// K/V (or Q/dO) rows are fetched into one L2 once and shared there, instead of into all eight.
+__device__ __forceinline__ void decode_block(int nblk, int nh, int nb, int &blk, int &n, int &bi)
+{
+    const int id = blockIdx.x, nv = nh * nb;
+    int v;
+    if ((nv & 7) == 0) {
+        const int j = id >> 3;
+        blk = j % nblk;
+        v = (j / nblk) * 8 + (id & 7);
+    } else {
+        blk = id % nblk;
+        v = id / nblk;
+    }
+    n = v % nh;
+    bi = v / nh;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -136,12 +158,13 @@ template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv,
                                                                     bf16 *__restrict__ attn,
                                                                     float *__restrict__ lse, int seq, int nh,
-                                                                    float scale_log2e)
+                                                                    int nb, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
+    int qb, n, bi;
+    decode_block(seq / (32 * NW), nh, nb, qb, n, bi);
     // NW == 4: heavy (late) query blocks first; NW == 8: all work-groups are equally heavy
-    const int qb = NW == 4 ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
-    const int n = blockIdx.y, bi = blockIdx.z;
+    if (NW == 4) qb = seq / 128 - 1 - qb;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -197,48 +220,55 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *_
             const unsigned char *ks = smem + buf * 2 * kTileBytes;
             const unsigned char *vs = ks + kTileBytes;
             f32x16 sacc[2];
+            const f32x16 zero16 = {};
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
+                sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, 0), qf[0], zero16, 0, 0, 0);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) sacc[T][e] = 0.0f;
-#pragma unroll
-                for (int st = 0; st < 8; ++st)
+                for (int st = 1; st < 8; ++st)
                     sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc[T], 0, 0, 0);
             }
-            // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c
-            const bool need_mask = kv0 + kTile - 1 > qw0;
-            float mloc = -INFINITY;
+            // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c.
+            // Only the tile on the diagonal needs the mask; the running maximum is kept on the raw scores
+            // (the scale is positive) and the scale is folded into the exponent: p = 2^(s*c - m*c).
+            if (kv0 + kTile - 1 > qw0) {
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (kv > qw0 + c) sacc[T][e] = -INFINITY;
+                    }
+            }
+            float mloc = sacc[0][0];
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float sv = sacc[T][e] * scale_log2e;
-                    if (need_mask) {
-                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) sv = -INFINITY;
-                    }
-                    sacc[T][e] = sv;
-                    mloc = fmaxf(mloc, sv);
-                }
+                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
             const float m_new = fmaxf(m_run, mloc);
-            const float alpha = fast_exp2(m_run - m_new);
+            const float mc = m_new * scale_log2e;
             float psum = 0.0f;
             bf16x8 pf[4];
 #pragma unroll
             for (int T = 0; T < 2; ++T)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const float p = fast_exp2(sacc[T][e] - m_new);
+                    const float p = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
                     psum += p;
                     pf[2 * T + (e >> 3)][e & 7] = (bf16)p;
                 }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
+            // the accumulators are rescaled only when some query of the wave saw a new maximum
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
+                l_run *= alpha;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+                m_run = m_new;
+            }
+            l_run += psum;
             // O^T[dv, q] += sum_kv V^T[dv, kv] P^T[kv, q]
 #pragma unroll
             for (int st = 0; st < 4; ++st)
@@ -267,7 +297,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *_
             *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
         }
     if (g == 0)
-        lse[((int64_t)bi * nh + n) * seq + qw0 + c] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+        lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
+            (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
 }
 
 // ------------------------------------------------------------------------------------ backward: dQ
@@ -280,11 +311,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
                                                                        const float *__restrict__ lse,
                                                                        const float *__restrict__ delta,
                                                                        bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                       float scale, float scale_log2e)
+                                                                       int nb, float scale, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
-    const int qb = NW == 4 ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
-    const int n = blockIdx.y, bi = blockIdx.z;
+    int qb, n, bi;
+    decode_block(seq / (32 * NW), nh, nb, qb, n, bi);
+    if (NW == 4) qb = seq / 128 - 1 - qb;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -345,8 +377,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
         if (kv0 <= qw0 + 31) {
             const unsigned char *ks = smem + buf * 2 * kTileBytes;
             const unsigned char *vs = ks + kTileBytes;
-            const bool need_mask = kv0 + kTile - 1 > qw0;
             bf16x8 dsf[4];
+            const bool diag = kv0 + kTile - 1 > qw0;  // wave-uniform: only the tile on the diagonal needs the mask
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
                 f32x16 sacc, dpacc;
@@ -360,13 +392,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
                     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc, 0, 0, 0);
                     dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(vs, ad, T, st), dof[st], dpacc, 0, 0, 0);
                 }
+                if (diag) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (kv > qw0 + c) sacc[e] = -INFINITY;  // p = 2^(-inf) = 0
+                    }
+                }
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    float p = fast_exp2(sacc[e] * scale_log2e - l2);
-                    if (need_mask) {
-                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) p = 0.0f;
-                    }
+                    const float p = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l2));
                     dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[e] - dl));
                 }
             }
@@ -406,14 +441,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
                                                                    const float *__restrict__ lse,
                                                                    const float *__restrict__ delta,
                                                                    bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                   float scale, float scale_log2e)
+                                                                   int nb, float scale, float scale_log2e)
 {
     // [kStages][Q tile | dO tile], then [kStages][lse of the tile's 64 queries | delta of the same].  The per-query
     // statistics travel with the tiles (a 4-byte-per-lane global->LDS load each): fetching them with
     // ordinary loads inside the loop would make every use wait, in order, behind the next tile's copies.
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int kb = blockIdx.x;  // NW == 4: early key blocks see the most queries and come first
-    const int n = blockIdx.y, bi = blockIdx.z;
+    int kb, n, bi;  // NW == 4: early key blocks see the most queries and come first
+    decode_block(seq / (32 * NW), nh, nb, kb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -490,8 +525,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
             const unsigned char *ds = qs + kTileBytes;
             const float *lse_s = reinterpret_cast<const float *>(smem + S * 2 * kTileBytes + buf * 512);
             const float *del_s = lse_s + 64;
-            const bool need_mask = qt0 < kvw0 + 31;
             bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
+            const bool diag = qt0 < kvw0 + 31;  // wave-uniform: only the tile on the diagonal needs the mask
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
                 f32x16 sacc, dpacc;
@@ -507,6 +542,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
                         dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
                 }
                 // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
+                if (diag) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (kvw0 + c > qt0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3)) sacc[e] = -INFINITY;
+                }
 #pragma unroll
                 for (int e4 = 0; e4 < 4; ++e4) {
                     const int qrel = 32 * T + 8 * e4 + 4 * g;
@@ -516,8 +556,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int e = e4 * 4 + r;
-                        float p = fast_exp2(sacc[e] * scale_log2e - l4[r] * 1.44269504088896340736f);
-                        if (need_mask && (kvw0 + c > qt0 + qrel + r)) p = 0.0f;
+                        const float p = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[r] * 1.44269504088896340736f));
                         frag[2 * T + (e >> 3)][e & 7] = DK ? (bf16)(p * (dpacc[e] - d4[r])) : (bf16)p;
                     }
                 }
@@ -593,13 +632,13 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
     if (hipError_t e = set_lds(attn_fwd_mfma_kernel<8>, lds8, a8)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
     if (seq % 256 == 0) {
-        const dim3 grid((unsigned)(seq / 256), (unsigned)nh, (unsigned)b);
+        const dim3 grid((unsigned)(seq / 256 * nh * b));
         attn_fwd_mfma_kernel<8><<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                       scale_log2e);
+                                                       (int)b, scale_log2e);
     } else {
-        const dim3 grid((unsigned)(seq / 128), (unsigned)nh, (unsigned)b);
+        const dim3 grid((unsigned)(seq / 128 * nh * b));
         attn_fwd_mfma_kernel<4><<<grid, 256, lds4, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                       scale_log2e);
+                                                       (int)b, scale_log2e);
     }
     return hipGetLastError();
 }
@@ -615,13 +654,16 @@ static hipError_t launch_attn_bwd_nw(const void *qkv, const void *dattn, const f
     if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<true, NW>, lds_dkv, a2)) return e;
     if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false, NW>, lds_dkv, a3)) return e;
     const float scale_log2e = scale * 1.44269504088896340736f;
-    const dim3 grid((unsigned)(seq / (32 * NW)), (unsigned)nh, (unsigned)b);
+    const dim3 grid((unsigned)(seq / (32 * NW) * nh * b));
     attn_bwd_dq_mfma_kernel<NW><<<grid, NW * 64, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                              (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<true, NW><<<grid, NW * 64, lds_dkv, s>>>(
-        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<false, NW><<<grid, NW * 64, lds_dkv, s>>>(
-        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, scale, scale_log2e);
+                                                              (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
+                                                              scale_log2e);
+    attn_bwd_dkv_mfma_kernel<true, NW><<<grid, NW * 64, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse,
+                                                                      delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
+                                                                      scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<false, NW><<<grid, NW * 64, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse,
+                                                                       delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
+                                                                       scale, scale_log2e);
     return hipGetLastError();
 }
 

@@ -736,6 +736,236 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fourth generation ("ring"): the hand-ordered kernel with K advancing in stages of 32 through a ring of
+// NS LDS stages instead of two buffers of 64.  The copies of a stage are issued NS-1 stages before it is
+// read, so with NS = 5 (all 160 KB of LDS) a tile has about three stages of MFMA time (~3000 cycles) to
+// arrive instead of about one and a half; two buffers of 64 do not cover a loaded HBM round trip and the
+// loop then waits at every K-step.  LDS rows are 64 bytes (4 chunks of 16), chunk c of row r sits at
+// chunk position c ^ ((r >> 2) & 3): 16 consecutive rows at one chunk hit all 64 banks exactly once.
+// Per stage and wave: 2 K sub-steps of MT*NT MFMAs, MT+NT operand reads each (issued one sub-step ahead,
+// one per MFMA), A_I + B_I copies, one barrier.
+template <int BM, int BN, int WGM, int WGN, int NS>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    constexpr int SK = 32;                     // K per stage
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;  // 1 KB copies (16 rows of 64 B) per wave per stage
+    constexpr int LPS = A_I + B_I;
+    constexpr int G1 = LPS / 2, G2 = LPS - G1;
+    constexpr int READS = MT + NT, MFMAS = MT * NT;
+    constexpr int A_ST = BM * SK * 2, B_ST = BN * SK * 2;  // bytes per stage
+    constexpr int B_REGION = NS * A_ST;
+    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile/waves mismatch");
+    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
+    static_assert(NS >= 3 && NS <= 5, "ring depth");
+    static_assert((size_t)NS * (A_ST + B_ST) >= (size_t)NW * 32 * (WN + 8) * 4, "epilogue staging must fit");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    int pid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (pid % per_group) % gsz;
+    const int tn = (pid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- global side: scalar tile base + per-lane byte offset; a copy covers 16 rows x 64 bytes
+    const int lrow = lane >> 2, lch = lane & 3;
+    uint32_t a_voff[A_I], b_voff[B_I];
+#pragma unroll
+    for (int j = 0; j < A_I; ++j) {
+        const int row = (wave * A_I + j) * 16 + lrow;
+        const int sw = (row >> 2) & 3;
+        int64_t r = row;
+        if (m0 + r > M - 1) r = M - 1 - m0;
+        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < B_I; ++j) {
+        const int row = (wave * B_I + j) * 16 + lrow;
+        const int sw = (row >> 2) & 3;
+        int64_t r = row;
+        if (n0 + r > N - 1) r = N - 1 - n0;
+        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
+    }
+    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
+    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
+
+    // ---- LDS side: per-lane byte addresses of the operand chunk for the two K sub-steps of a stage.
+    // Immediates reach 64 KB, so stages 0..3 hang off one base register and stage 4 off a second one.
+    const int khalf = lane >> 5;
+    unsigned char *a_rd[2][2], *b_rd[2][2];
+    {
+        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+        const int asw = (arow >> 2) & 3, bsw = (brow >> 2) & 3;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            a_rd[0][ks] = smem_raw + arow * 64 + (((ks * 2 + khalf) ^ asw) << 4);
+            b_rd[0][ks] = smem_raw + B_REGION + brow * 64 + (((ks * 2 + khalf) ^ bsw) << 4);
+            a_rd[1][ks] = a_rd[0][ks] + 3 * A_ST;
+            b_rd[1][ks] = b_rd[0][ks] + 3 * B_ST;
+        }
+    }
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nst = (int)(K / SK);
+    bf16x8 af[2][MT], bfr[2][NT];
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
+    // copy n (0..LPS-1) of K stage `stage` (clamped by the caller) into ring slot `slot`
+    auto gll = [&](int n, int stage, int slot) {
+        const char *abase = a_tile + (int64_t)stage * (SK * 2);
+        const char *bbase = b_tile + (int64_t)stage * (SK * 2);
+        if (n < A_I) {
+            const uint32_t dst = a_slot + slot * A_ST + n * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "memory");
+        } else {
+            const int m = n - A_I;
+            const uint32_t dst = b_slot + slot * B_ST + m * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "memory");
+        }
+    };
+    // operand reads of sub-step RKS of ring slot RSLOT
+    auto rd_a = [&](auto slot_c, auto ks_c, int i) {
+        constexpr int SL = decltype(slot_c)::value, KS = decltype(ks_c)::value;
+        if constexpr (SL < 3)
+            return *reinterpret_cast<const bf16x8 *>(a_rd[0][KS] + SL * A_ST + i * 2048);
+        else
+            return *reinterpret_cast<const bf16x8 *>(a_rd[1][KS] + (SL - 3) * A_ST + i * 2048);
+    };
+    auto rd_b = [&](auto slot_c, auto ks_c, int j) {
+        constexpr int SL = decltype(slot_c)::value, KS = decltype(ks_c)::value;
+        if constexpr (SL < 3)
+            return *reinterpret_cast<const bf16x8 *>(b_rd[0][KS] + SL * B_ST + j * 2048);
+        else
+            return *reinterpret_cast<const bf16x8 *>(b_rd[1][KS] + (SL - 3) * B_ST + j * 2048);
+    };
+    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the
+    // reads of sub-step RKS of slot RSLOT into the other set and with GCNT copies (numbers GFIRST..) of
+    // stage gstage into slot GSLOT.
+    auto phase = [&](auto cur_c, auto rslot_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gslot_c, int gstage) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
+        constexpr int GSLOT = decltype(gslot_c)::value;
+        static_for<MFMAS>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            constexpr int i = t / NT, j = t % NT;
+            if constexpr (t < READS) {
+                if constexpr (t == 0)
+                    af[NXT][0] = rd_a(rslot_c, rks_c, 0);
+                else if constexpr (t <= NT)
+                    bfr[NXT][t - 1] = rd_b(rslot_c, rks_c, t - 1);
+                else
+                    af[NXT][t - NT] = rd_a(rslot_c, rks_c, t - NT);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (GCNT > 0) {
+                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
+                if constexpr (after > before) {
+                    gll(GFIRST + before, gstage, GSLOT);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using IG1 = std::integral_constant<int, G1>;
+    using IG2 = std::integral_constant<int, G2>;
+
+    // Stage st out of ring slot SLOT.  On entry fragment set 0 holds sub-step 0 of the stage; stages up to
+    // st+NS-2 have been requested.
+    auto stage_step = [&](auto slot_c, int st) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        using IS = std::integral_constant<int, SLOT>;
+        using IN = std::integral_constant<int, (SLOT + 1) % NS>;          // next stage's slot
+        using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;     // slot freed by the previous stage
+        const int far = st + NS - 1 < nst ? st + NS - 1 : nst - 1;        // clamped: a surplus reload is never read
+        phase(I0{}, IS{}, I1{}, I0{}, IG1{}, IF{}, far);
+        // stage st+1 has landed (copies complete in order; NS-3 whole stages and the G1 copies just issued
+        // may stay in flight) and every wave has issued all its reads of stage st
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 3) * LPS + G1) : "memory");
+        __syncthreads();
+        phase(I1{}, IN{}, I0{}, IG1{}, IG2{}, IF{}, far);
+    };
+
+    // prologue: stages 0..NS-2
+    static_for<NS - 1>([&](auto ss) {
+        constexpr int S = decltype(ss)::value;
+        const int stg = S < nst ? S : nst - 1;
+#pragma unroll
+        for (int n = 0; n < LPS; ++n) gll(n, stg, S);
+    });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    af[0][0] = rd_a(I0{}, I0{}, 0);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) bfr[0][j] = rd_b(I0{}, I0{}, j);
+#pragma unroll
+    for (int i = 1; i < MT; ++i) af[0][i] = rd_a(I0{}, I0{}, i);
+
+    for (int st = 0; st < nst; st += NS)
+        static_for<NS>([&](auto ii) {
+            constexpr int I = decltype(ii)::value;
+            if (st + I < nst) stage_step(ii, st + I);
+        });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+static hipError_t launch_variant_r(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t lds = (size_t)NS * (BM + BN) * 32 * sizeof(bf16);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_r_kernel<BM, BN, WGM, WGN, NS>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
+                                                                 tiles_n);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int WGM, int WGN>
 static hipError_t launch_variant_h(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
@@ -825,6 +1055,9 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     case 6: return launch_variant_h<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 7: return launch_variant_h<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 8: return launch_variant_h<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 9: return launch_variant_r<256, 256, 2, 4, 5>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 10: return launch_variant_r<256, 256, 2, 4, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 11: return launch_variant_r<128, 128, 2, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -181,6 +181,8 @@ def test_materialize_counters_and_idempotence():
     (300, 520, 192, 4), (300, 520, 192, 5), (300, 520, 192, 6), (300, 520, 192, 7), (300, 520, 192, 8),
     (64, 96, 128, -1), (1, 1, 64, 2), (1, 1, 64, 6), (777, 129, 256, -1), (2048, 512, 1024, -1), (512, 2048, 64, 5),
     (1000, 1000, 320, 5), (1000, 1000, 320, 6),
+    (300, 520, 192, 9), (300, 520, 192, 10), (300, 520, 192, 11), (1000, 1000, 320, 9), (1000, 1000, 320, 11),
+    (512, 512, 64, 9), (256, 256, 1024, 9), (256, 256, 1024, 10), (1, 1, 64, 11),
 ])
 def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     print(f"gemm {M}x{N}x{K} variant {variant}", flush=True)
