@@ -1042,7 +1042,30 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (variant < 0) {
         // 256x256 tiles (8 waves) whenever they give every CU a work-group: lowest LDS and L2 traffic
         // per flop.  Otherwise (e.g. a T x h output of 128 big tiles) 128x128 tiles, 2 work-groups per CU.
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+        const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256, t256 = tm * tn;
+        // One CU holds one 256x256 work-group, so a grid runs in rounds of 256 tiles and e.g. 384 tiles
+        // (T x 3h at T = 2048) take as long as 512.  With only a few rounds, cut the columns into a part
+        // that is a whole number of rounds and a remainder that goes out with the small tiles.
+        if (t256 > 256 && t256 < 1024 && t256 % 256 != 0) {
+            int64_t cols = 0;  // tile columns of the first part
+            for (int64_t c = tn - 1; c >= 1; --c)
+                if ((tm * c) % 256 == 0) {
+                    cols = c;
+                    break;
+                }
+            if (cols > 0) {
+                const int64_t n1 = cols * 256;
+                GemmEpi e2 = epi;
+                const size_t osz = epi.out_f32 ? 4 : 2;
+                if (epi.bias) e2.bias = (const bf16 *)epi.bias + n1;
+                if (epi.resid) e2.resid = (const bf16 *)epi.resid + n1;
+                if (epi.aux) e2.aux = (const bf16 *)epi.aux + n1;
+                if (epi.out2) e2.out2 = (bf16 *)epi.out2 + n1;
+                hipError_t err = launch_gemm_bf16_nt(M, n1, K, A, lda, B, ldb, C, ldc, epi, s);
+                if (err != hipSuccess) return err;
+                return launch_gemm_bf16_nt(M, N - n1, K, A, lda, b + n1 * ldb, ldb, (char *)C + n1 * osz, ldc, e2, s);
+            }
+        }
         variant = t256 >= 256 ? 5 : 6;
     }
     switch (variant) {
