@@ -249,7 +249,7 @@ def test_generic_attention_against_oracle(dtype, b, s, nh, d):
     assert np.abs(lse.cpu().numpy().reshape(b, nh, s) - ref_lse).max() <= 1e-3
 
 
-@pytest.mark.parametrize("b,s,nh", [(1, 128, 1), (1, 256, 2), (2, 384, 3)])
+@pytest.mark.parametrize("b,s,nh", [(1, 128, 1), (1, 256, 2), (2, 384, 3), (1, 512, 8), (2, 768, 4), (1, 1024, 2)])
 def test_mfma_attention_against_oracle(b, s, nh):
     print(f"attention mfma b{b} s{s} nh{nh}", flush=True)
     d = 128
