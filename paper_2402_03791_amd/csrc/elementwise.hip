@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void colsum_finish_kernel(const float *__restr
 uint64_t transpose_colsum_scratch_floats(int64_t R, int64_t C) { return (uint64_t)((R + 63) / 64) * C; }
 
 hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
-                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s)
+                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s, FinishItem *defer)
 {
     if (R == 0 || C == 0) return hipSuccess;
     if (R % 64 || C % 64 || ld_in % 8 || ld_out % 8) return hipErrorInvalidValue;
@@ -109,8 +109,56 @@ hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t
     transpose_bf16_kernel<true><<<grid, 256, 0, s>>>((const bf16 *)in, ld_in, (bf16 *)out, ld_out, partial, C);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (defer) {
+        *defer = FinishItem{partial, nullptr, colsum, nullptr, (int32_t)(R / 64), C};
+        return hipSuccess;
+    }
     colsum_finish_kernel<<<(unsigned)((C + 255) / 256), 256, 0, s>>>(partial, R / 64, C, colsum);
     return hipGetLastError();
+}
+
+// Second level of up to kFinishMax column reductions in one launch; blocks [first[i], first[i+1]) work on
+// item i, one thread per column, partial rows added in ascending order (run-to-run identical).
+constexpr int kFinishMax = 32;
+struct FinishBatch {
+    FinishItem item[kFinishMax];
+    int32_t first[kFinishMax + 1];
+    int32_t n;
+};
+
+__global__ __launch_bounds__(256) void finish_columns_kernel(FinishBatch b)
+{
+    int i = 0;
+    while (i + 1 < b.n && (int)blockIdx.x >= b.first[i + 1]) ++i;
+    const FinishItem &it = b.item[i];
+    const int64_t c = (int64_t)((int)blockIdx.x - b.first[i]) * 256 + threadIdx.x;
+    if (c >= it.C) return;
+    float s0 = 0.0f, s1 = 0.0f;
+    for (int r = 0; r < it.rows; ++r) {
+        s0 += it.partial0[(int64_t)r * it.C + c];
+        if (it.partial1) s1 += it.partial1[(int64_t)r * it.C + c];
+    }
+    it.out0[c] = s0;
+    if (it.out1) it.out1[c] = s1;
+}
+
+hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s)
+{
+    for (int base = 0; base < n; base += kFinishMax) {
+        FinishBatch b;
+        b.n = n - base < kFinishMax ? n - base : kFinishMax;
+        int32_t blocks = 0;
+        for (int i = 0; i < b.n; ++i) {
+            b.item[i] = items[base + i];
+            b.first[i] = blocks;
+            blocks += (int32_t)((items[base + i].C + 255) / 256);
+        }
+        b.first[b.n] = blocks;
+        if (blocks == 0) continue;
+        finish_columns_kernel<<<(unsigned)blocks, 256, 0, s>>>(b);
+        if (hipError_t e = hipGetLastError()) return e;
+    }
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------ rotary embedding

@@ -52,10 +52,22 @@ hipError_t launch_norm_bwd(int dt, int kind, const void *dn, const void *x, cons
 //   COLRED_LAYERNORM: out0[c] = sum_t a[t,c]*(x[t,c]-mean[t])*rstd[t], out1[c] = sum_t a[t,c]
 //   COLRED_RMSNORM:   out0[c] = sum_t a[t,c]*x[t,c]*rstd[t]
 // partial: scratch of colreduce_scratch_floats(T, C) floats.
+// A column reduction in two levels: the first-level kernels above/below leave `rows` partial rows of C
+// floats each (two sets for COLRED_LAYERNORM, the second `rows * C` floats after the first); the second
+// level adds them up in a fixed order.  The second level of many reductions can be batched into one
+// launch (they are tiny and otherwise cost a launch each): pass `defer` to the first-level launchers,
+// collect the items, and call launch_finish_columns once.  Partials must stay untouched until then.
+struct FinishItem {
+    const float *partial0, *partial1;  // partial1 may be null
+    float *out0, *out1;
+    int32_t rows;
+    int64_t C;
+};
+hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s);
 uint64_t colreduce_scratch_floats(int64_t T, int64_t C);
 hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
                             const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
-                            float *partial, hipStream_t s);
+                            float *partial, hipStream_t s, FinishItem *defer = nullptr);
 
 // ---- elementwise ----
 // out[c, r] = in[r, c]; in has row stride ld_in, out row stride ld_out (elements)
@@ -65,7 +77,8 @@ hipError_t launch_transpose(int dt, const void *in, int64_t R, int64_t C, int64_
 // partial: scratch of transpose_colsum_scratch_floats(R, C) floats.
 uint64_t transpose_colsum_scratch_floats(int64_t R, int64_t C);
 hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t ld_in, void *out,
-                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s);
+                                   int64_t ld_out, float *colsum, float *partial, hipStream_t s,
+                                   FinishItem *defer = nullptr);
 // table[p, i] = (cos, sin)(p * base^(-2i/d)), p < seq, i < d/2
 hipError_t launch_rope_table(float *table, int64_t seq, int64_t d, double base, hipStream_t s);
 // rotates the Q and K parts of qkv[T, 3h] in place; sign = +1 forward, -1 inverse

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void colreduce_stage2(const float *__restrict_
 
 hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
                             const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
-                            float *partial, hipStream_t s)
+                            float *partial, hipStream_t s, FinishItem *defer)
 {
     if (T == 0 || C == 0) return hipSuccess;
     const int64_t rc = (T + kColRows - 1) / kColRows;
@@ -236,6 +236,11 @@ hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, cons
 #undef ZPP_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (defer) {
+        const bool two = mode == COLRED_LAYERNORM;
+        *defer = FinishItem{partial, two ? partial + rc * C : nullptr, out0, two ? out1 : nullptr, (int32_t)rc, C};
+        return hipSuccess;
+    }
     colreduce_stage2<<<(unsigned)((C + 255) / 256), 256, 0, s>>>(partial, rc, C, out0,
                                                                  mode == COLRED_LAYERNORM ? out1 : nullptr);
     return hipGetLastError();

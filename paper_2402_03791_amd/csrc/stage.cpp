@@ -122,6 +122,18 @@ struct zpp_stage {
     int pending_acc = -1;
     uint64_t n_materialize = 0, materialize_bytes = 0;
 
+    // Second levels of the column reductions (bias and gain gradients) of one stage_backward call: each
+    // first level writes its partial rows into its own slot of the "redpool" scratch and is listed here;
+    // one launch at the end of the call finishes them all.
+    std::vector<FinishItem> finish;
+    uint64_t red_floats = 0;  // floats per slot
+    float *red_slot() const { return (float *)(ws + tmp.at("redpool").off) + finish.size() * red_floats; }
+    FinishItem *defer()
+    {
+        finish.emplace_back();
+        return &finish.back();
+    }
+
     uint64_t off(int blk, const char *nm) const
     {
         return layout[index.at("blk" + std::to_string(blk) + "." + nm)].offset;
@@ -190,6 +202,8 @@ void build_layout(zpp_stage *s)
     s->Nmat = woff;
 }
 
+constexpr uint64_t kRedPerBlock = 6;  // four bias gradients and two norm-gain gradients per block at most
+
 void plan_workspace(zpp_stage *s)
 {
     uint64_t cur = 0;
@@ -250,8 +264,10 @@ void plan_workspace(zpp_stage *s)
         tmp("tA", widest * T, 2);
         tmp("tB", std::max<uint64_t>(h, f) * T, 2);
     }
-    tmp("colred", std::max(colreduce_scratch_floats((int64_t)T, (int64_t)widest),
-                           transpose_colsum_scratch_floats((int64_t)T, (int64_t)widest)), 4);
+    s->red_floats = std::max(colreduce_scratch_floats((int64_t)T, (int64_t)widest),
+                             transpose_colsum_scratch_floats((int64_t)T, (int64_t)widest));
+    tmp("redpool", s->red_floats * kRedPerBlock * s->L, 4);  // one slot per column reduction of a backward call
+    s->finish.reserve(kRedPerBlock * s->L);
     s->ws_bytes = cur;
 }
 
@@ -310,7 +326,10 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
         {
             ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
             if (bias)
-                e = launch_transpose_colsum(dy, s->T, out, out, tA, s->T, s->Sp(blk, bias), (float *)s->tp("colred"), st);
+            {
+                float *slot = s->red_slot();
+                e = launch_transpose_colsum(dy, s->T, out, out, tA, s->T, s->Sp(blk, bias), slot, st, s->defer());
+            }
             else
                 e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st);
             if (e != hipSuccess) return e;
@@ -328,9 +347,11 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
     }
     if (e != hipSuccess) return e;
     ProfScope prof2(ZPP_PROF_OTHER, 0.0, st);
-    if (bias)
+    if (bias) {
+        float *slot = s->red_slot();
         e = launch_colreduce(s->dt, COLRED_SUM, dy, nullptr, nullptr, nullptr, s->T, out, out, s->Sp(blk, bias),
-                             nullptr, (float *)s->tp("colred"), st);
+                             nullptr, slot, st, s->defer());
+    }
     return e;
 }
 
@@ -566,7 +587,7 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
     const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
     void *gbuf[2] = {s->tp("gA"), s->tp("gB")};
     void *dn = s->tp("dn"), *dx1 = s->tp("dx1"), *dattn = s->tp("dattn"), *dqkv = s->tp("dqkv"), *du = s->tp("du");
-    float *colred = (float *)s->tp("colred");
+    s->finish.clear();
     const void *dcur = dy;
     for (int blk = (int)s->L - 1; blk >= 0; --blk) {
         void *dout = blk == 0 ? dx : gbuf[blk & 1];
@@ -596,8 +617,11 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
         }
         const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
         ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h, st));
-        ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
-                                 s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, colred, st));
+        {
+            float *slot = s->red_slot();
+            ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
+                                       s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, slot, st, s->defer()));
+        }
         // ---- attention branch
         ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
         ZPP_TRY(linear_dx(s, dx1, blk, "attn.wo", h, h, dattn, GemmEpi(), st));
@@ -607,10 +631,16 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
         ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
         ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
         ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h, st));
-        ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
-                                 s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, colred, st));
+        {
+            float *slot = s->red_slot();
+            ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
+                                       s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, slot, st, s->defer()));
+        }
         dcur = dout;
     }
+    // second level of every column reduction of this call, in one launch
+    ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st));
+    s->finish.clear();
     s->mb_state[mb] = MB_BWD;
     s->pending_acc = mb;
     return ZPP_OK;
