@@ -2,6 +2,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <climits>
+
 namespace zpp {
 
 // ------------------------------------------------------------------ transpose
@@ -10,14 +12,14 @@ namespace zpp {
 // input (partial[tile_row][c] = sum over the tile's 64 rows), which the caller reduces over tile rows:
 // that is the bias gradient db = colsum(dY), for free while dY is being transposed for dW = dY^T X.
 // Requires R % 64 == 0, C % 64 == 0, ld_in % 8 == 0, ld_out % 8 == 0 (bf16).
+// One 64x64 tile: (cx, ry) = tile column / tile row of the input.
 template <bool COLSUM>
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16 *__restrict__ in, int64_t ld_in,
-                                                             bf16 *__restrict__ out, int64_t ld_out,
-                                                             float *__restrict__ partial, int64_t C)
+__device__ __forceinline__ void transpose_tile(const bf16 *__restrict__ in, int64_t ld_in, bf16 *__restrict__ out,
+                                               int64_t ld_out, float *__restrict__ partial, int64_t C, int cx, int ry,
+                                               bf16 *tile)
 {
     constexpr int LD = 66;  // 33 dwords: the column reads of 8 row-chunks fall into 8 different banks
-    __shared__ bf16 tile[64 * LD];
-    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    const int64_t r0 = (int64_t)ry * 64, c0 = (int64_t)cx * 64;
     const int t = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -47,8 +49,42 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16 *__restr
             sum += __shfl_xor(sum, 1, 64);
             sum += __shfl_xor(sum, 2, 64);
             sum += __shfl_xor(sum, 4, 64);
-            if (kc == 0) partial[(int64_t)blockIdx.y * C + c0 + c] = sum;
+            if (kc == 0) partial[(int64_t)ry * C + c0 + c] = sum;
         }
+    }
+}
+
+template <bool COLSUM>
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16 *__restrict__ in, int64_t ld_in,
+                                                             bf16 *__restrict__ out, int64_t ld_out,
+                                                             float *__restrict__ partial, int64_t C)
+{
+    __shared__ bf16 tile[64 * 66];
+    transpose_tile<COLSUM>(in, ld_in, out, ld_out, partial, C, blockIdx.x, blockIdx.y, tile);
+}
+
+// Two transposes in one launch (the two operands of a weight-gradient product): work-groups [0, n0) take
+// the tiles of the first matrix, which also yields column sums; the rest take the second.
+struct TransposeDesc {
+    const bf16 *in;
+    int64_t ld_in;
+    bf16 *out;
+    int64_t ld_out;
+    int32_t tiles_c;  // tile columns (C / 64)
+};
+__global__ __launch_bounds__(256) void transpose_pair_kernel(TransposeDesc a, float *__restrict__ partial_a,
+                                                             int64_t Ca, int32_t n0, TransposeDesc b)
+{
+    __shared__ bf16 tile[64 * 66];
+    const int id = blockIdx.x;
+    if (id < n0) {
+        if (partial_a)
+            transpose_tile<true>(a.in, a.ld_in, a.out, a.ld_out, partial_a, Ca, id % a.tiles_c, id / a.tiles_c, tile);
+        else
+            transpose_tile<false>(a.in, a.ld_in, a.out, a.ld_out, nullptr, Ca, id % a.tiles_c, id / a.tiles_c, tile);
+    } else {
+        const int j = id - n0;
+        transpose_tile<false>(b.in, b.ld_in, b.out, b.ld_out, nullptr, 0, j % b.tiles_c, j / b.tiles_c, tile);
     }
 }
 
@@ -114,6 +150,26 @@ hipError_t launch_transpose_colsum(const void *in, int64_t R, int64_t C, int64_t
         return hipSuccess;
     }
     colsum_finish_kernel<<<(unsigned)((C + 255) / 256), 256, 0, s>>>(partial, R / 64, C, colsum);
+    return hipGetLastError();
+}
+
+// a: [Ra, Ca] -> a_out[Ca, Ra] with column sums when colsum != null (partial, defer as in
+// launch_transpose_colsum; defer must be given then); b: [Rb, Cb] -> b_out[Cb, Rb].  bf16, all sizes
+// multiples of 64, leading dimensions multiples of 8.
+hipError_t launch_transpose_pair(const void *a, int64_t Ra, int64_t Ca, int64_t lda, void *a_out, int64_t lda_out,
+                                 float *colsum, float *partial, FinishItem *defer, const void *b, int64_t Rb,
+                                 int64_t Cb, int64_t ldb, void *b_out, int64_t ldb_out, hipStream_t s)
+{
+    if (Ra % 64 || Ca % 64 || Rb % 64 || Cb % 64 || lda % 8 || lda_out % 8 || ldb % 8 || ldb_out % 8 ||
+        (colsum && !defer))
+        return hipErrorInvalidValue;
+    const int64_t n0 = (Ra / 64) * (Ca / 64), n1 = (Rb / 64) * (Cb / 64);
+    if (n0 + n1 == 0) return hipSuccess;
+    if (n0 == 0 || n1 == 0 || n0 + n1 > INT32_MAX) return hipErrorInvalidValue;
+    const TransposeDesc da{(const bf16 *)a, lda, (bf16 *)a_out, lda_out, (int32_t)(Ca / 64)};
+    const TransposeDesc db{(const bf16 *)b, ldb, (bf16 *)b_out, ldb_out, (int32_t)(Cb / 64)};
+    transpose_pair_kernel<<<(unsigned)(n0 + n1), 256, 0, s>>>(da, colsum ? partial : nullptr, Ca, (int32_t)n0, db);
+    if (colsum) *defer = FinishItem{partial, nullptr, colsum, nullptr, (int32_t)(Ra / 64), Ca};
     return hipGetLastError();
 }
 

@@ -64,6 +64,12 @@ struct FinishItem {
     int64_t C;
 };
 hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s);
+// Two bf16 transposes in one launch: a[Ra, Ca] -> a_out[Ca, Ra] (with column sums of a when colsum is
+// given; then partial and defer as for launch_transpose_colsum, second level deferred), b likewise
+// without sums.  All sizes multiples of 64.
+hipError_t launch_transpose_pair(const void *a, int64_t Ra, int64_t Ca, int64_t lda, void *a_out, int64_t lda_out,
+                                 float *colsum, float *partial, FinishItem *defer, const void *b, int64_t Rb,
+                                 int64_t Cb, int64_t ldb, void *b_out, int64_t ldb_out, hipStream_t s);
 uint64_t colreduce_scratch_floats(int64_t T, int64_t C);
 hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
                             const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,

@@ -325,15 +325,22 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
         void *tA = s->tp("tA"), *tB = s->tp("tB");
         {
             ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
-            if (bias)
-            {
-                float *slot = s->red_slot();
-                e = launch_transpose_colsum(dy, s->T, out, out, tA, s->T, s->Sp(blk, bias), slot, st, s->defer());
+            if (s->T % 64 == 0 && in % 64 == 0 && out % 64 == 0) {  // both transposes in one launch
+                float *slot = bias ? s->red_slot() : nullptr;
+                e = launch_transpose_pair(dy, s->T, out, out, tA, s->T, bias ? s->Sp(blk, bias) : nullptr, slot,
+                                          bias ? s->defer() : nullptr, x, s->T, in, in, tB, s->T, st);
+                if (e != hipSuccess) return e;
+            } else {
+                // ragged sizes: element-wise transposes and a separate column reduction for the bias gradient
+                if ((e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st)) != hipSuccess) return e;
+                if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
+                if (bias) {
+                    float *slot = s->red_slot();
+                    e = launch_colreduce(DT_BF16, COLRED_SUM, dy, nullptr, nullptr, nullptr, s->T, out, out,
+                                         s->Sp(blk, bias), nullptr, slot, st, s->defer());
+                    if (e != hipSuccess) return e;
+                }
             }
-            else
-                e = launch_transpose(DT_BF16, dy, s->T, out, out, tA, s->T, st);
-            if (e != hipSuccess) return e;
-            if ((e = launch_transpose(DT_BF16, x, s->T, in, in, tB, s->T, st)) != hipSuccess) return e;
         }
         ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
                        2.0 * ((double)s->T * in + (double)s->T * out) + 4.0 * in * out);
