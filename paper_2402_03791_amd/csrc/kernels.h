@@ -71,6 +71,12 @@ hipError_t launch_transpose_pair(const void *a, int64_t Ra, int64_t Ca, int64_t 
                                  float *colsum, float *partial, FinishItem *defer, const void *b, int64_t Rb,
                                  int64_t Cb, int64_t ldb, void *b_out, int64_t ldb_out, hipStream_t s);
 uint64_t colreduce_scratch_floats(int64_t T, int64_t C);
+// launch_norm_bwd and the first level of the COLRED_LAYERNORM / COLRED_RMSNORM reduction of (dn, x) in one
+// launch; the second level is left in *defer.  partial: colreduce_scratch_floats(T, h) floats.
+hipError_t launch_norm_bwd_colreduce(int dt, int kind, const void *dn, const void *x, const float *mean,
+                                     const float *rstd, const void *gamma, const void *resid, void *dx, int64_t T,
+                                     int64_t h, float *dgamma, float *dbeta, float *partial, FinishItem *defer,
+                                     hipStream_t s);
 hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
                             const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
                             float *partial, hipStream_t s, FinishItem *defer = nullptr);

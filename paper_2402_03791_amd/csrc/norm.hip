@@ -4,6 +4,8 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <climits>
+
 namespace zpp {
 
 constexpr int kRowsPerBlock = 4;  // 4 waves of 64 lanes
@@ -85,15 +87,14 @@ hipError_t launch_norm_fwd(int dt, int kind, const void *x, const void *gamma, c
 // ghat = dn*gamma; LayerNorm: dx = (ghat - mean(ghat) - xhat*mean(ghat*xhat))*rstd
 //                  RMSNorm:   dx = (ghat - xhat*mean(ghat*xhat))*rstd          (+ resid)
 template <class T, int KIND>
-__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dn, const T *__restrict__ x,
-                                                       const float *__restrict__ mean,
-                                                       const float *__restrict__ rstd,
-                                                       const T *__restrict__ gamma, const T *__restrict__ resid,
-                                                       T *__restrict__ dx, int64_t rows, int64_t h)
+__device__ __forceinline__ void norm_bwd_rows(const T *__restrict__ dn, const T *__restrict__ x,
+                                              const float *__restrict__ mean, const float *__restrict__ rstd,
+                                              const T *__restrict__ gamma, const T *__restrict__ resid,
+                                              T *__restrict__ dx, int64_t rows, int64_t h, int64_t block)
 {
     constexpr int VN = Vec16<T>::N;
     const int lane = threadIdx.x & 63;
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int64_t row = block * kRowsPerBlock + (threadIdx.x >> 6);
     if (row >= rows) return;
     const int64_t nv = h / VN;
     const float mu = (KIND == NORM_LAYER) ? mean[row] : 0.0f;
@@ -135,6 +136,16 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dn,
     }
 }
 
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(const T *__restrict__ dn, const T *__restrict__ x,
+                                                       const float *__restrict__ mean,
+                                                       const float *__restrict__ rstd,
+                                                       const T *__restrict__ gamma, const T *__restrict__ resid,
+                                                       T *__restrict__ dx, int64_t rows, int64_t h)
+{
+    norm_bwd_rows<T, KIND>(dn, x, mean, rstd, gamma, resid, dx, rows, h, blockIdx.x);
+}
+
 hipError_t launch_norm_bwd(int dt, int kind, const void *dn, const void *x, const float *mean,
                            const float *rstd, const void *gamma, const void *resid, void *dx, int64_t T,
                            int64_t h, hipStream_t s)
@@ -165,16 +176,16 @@ uint64_t colreduce_scratch_floats(int64_t T, int64_t C)
 }
 
 template <class T, int MODE>
-__global__ __launch_bounds__(256) void colreduce_stage1(const T *__restrict__ a, const T *__restrict__ x,
-                                                        const float *__restrict__ mean,
-                                                        const float *__restrict__ rstd, int64_t rows, int64_t C,
-                                                        int64_t ld, float *__restrict__ partial)
+__device__ __forceinline__ void colreduce_tile(const T *__restrict__ a, const T *__restrict__ x,
+                                               const float *__restrict__ mean, const float *__restrict__ rstd,
+                                               int64_t rows, int64_t C, int64_t ld, float *__restrict__ partial,
+                                               int bx, int by, int rc)
 {
     __shared__ float red0[4][64];
     __shared__ float red1[4][64];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int64_t c = (int64_t)blockIdx.x * 64 + tx;
-    const int64_t r0 = (int64_t)blockIdx.y * kColRows;
+    const int64_t c = (int64_t)bx * 64 + tx;
+    const int64_t r0 = (int64_t)by * kColRows;
     const int64_t r1 = (r0 + kColRows < rows) ? r0 + kColRows : rows;
     float s0 = 0.0f, s1 = 0.0f;
     if (c < C) {
@@ -194,11 +205,67 @@ __global__ __launch_bounds__(256) void colreduce_stage1(const T *__restrict__ a,
     red1[ty][tx] = s1;
     __syncthreads();
     if (ty == 0 && c < C) {
-        const int64_t rc = gridDim.y;
-        partial[(int64_t)blockIdx.y * C + c] = (red0[0][tx] + red0[1][tx]) + (red0[2][tx] + red0[3][tx]);
+        partial[(int64_t)by * C + c] = (red0[0][tx] + red0[1][tx]) + (red0[2][tx] + red0[3][tx]);
         if (MODE == COLRED_LAYERNORM)
-            partial[(rc + blockIdx.y) * C + c] = (red1[0][tx] + red1[1][tx]) + (red1[2][tx] + red1[3][tx]);
+            partial[((int64_t)rc + by) * C + c] = (red1[0][tx] + red1[1][tx]) + (red1[2][tx] + red1[3][tx]);
     }
+}
+
+template <class T, int MODE>
+__global__ __launch_bounds__(256) void colreduce_stage1(const T *__restrict__ a, const T *__restrict__ x,
+                                                        const float *__restrict__ mean,
+                                                        const float *__restrict__ rstd, int64_t rows, int64_t C,
+                                                        int64_t ld, float *__restrict__ partial)
+{
+    colreduce_tile<T, MODE>(a, x, mean, rstd, rows, C, ld, partial, blockIdx.x, blockIdx.y, gridDim.y);
+}
+
+// Norm backward and the first level of its gain/offset gradient reduction in one launch: both read dn and
+// x and neither depends on the other.  Work-groups [0, nrow) take rows, the rest column tiles.
+template <class T, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_colreduce_kernel(const T *__restrict__ dn, const T *__restrict__ x,
+                                                                 const float *__restrict__ mean,
+                                                                 const float *__restrict__ rstd,
+                                                                 const T *__restrict__ gamma,
+                                                                 const T *__restrict__ resid, T *__restrict__ dx,
+                                                                 int64_t rows, int64_t h, int nrow, int tiles_c,
+                                                                 int rc, float *__restrict__ partial)
+{
+    const int id = blockIdx.x;
+    if (id < nrow) {
+        norm_bwd_rows<T, KIND>(dn, x, mean, rstd, gamma, resid, dx, rows, h, id);
+    } else {
+        const int j = id - nrow;
+        colreduce_tile<T, KIND == NORM_LAYER ? COLRED_LAYERNORM : COLRED_RMSNORM>(dn, x, mean, rstd, rows, h, h,
+                                                                                  partial, j % tiles_c, j / tiles_c, rc);
+    }
+}
+
+// dx = resid + d(norm)/dx, and the deferred item for d(gamma) (and d(beta) for LayerNorm)
+hipError_t launch_norm_bwd_colreduce(int dt, int kind, const void *dn, const void *x, const float *mean,
+                                     const float *rstd, const void *gamma, const void *resid, void *dx, int64_t T,
+                                     int64_t h, float *dgamma, float *dbeta, float *partial, FinishItem *defer,
+                                     hipStream_t s)
+{
+    if (T == 0 || h == 0) return hipSuccess;
+    if (!defer) return hipErrorInvalidValue;
+    const int64_t nrow = (T + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t rc = (T + kColRows - 1) / kColRows, tiles_c = (h + 63) / 64;
+    if (nrow + rc * tiles_c > INT32_MAX) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)(nrow + rc * tiles_c);
+#define ZPP_LAUNCH(TT, KK)                                                                                   \
+    norm_bwd_colreduce_kernel<TT, KK><<<grid, 256, 0, s>>>((const TT *)dn, (const TT *)x, mean, rstd,        \
+                                                           (const TT *)gamma, (const TT *)resid, (TT *)dx, T, h, \
+                                                           (int)nrow, (int)tiles_c, (int)rc, partial)
+    if (dt == DT_BF16) {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(bf16, NORM_LAYER); else ZPP_LAUNCH(bf16, NORM_RMS);
+    } else {
+        if (kind == NORM_LAYER) ZPP_LAUNCH(float, NORM_LAYER); else ZPP_LAUNCH(float, NORM_RMS);
+    }
+#undef ZPP_LAUNCH
+    const bool two = kind == NORM_LAYER;
+    *defer = FinishItem{partial, two ? partial + rc * h : nullptr, dgamma, two ? dbeta : nullptr, (int32_t)rc, h};
+    return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void colreduce_stage2(const float *__restrict__ partial, int64_t rc, int64_t C,

@@ -623,11 +623,11 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
             ZPP_TRY(linear_dx(s, du, blk, "mlp.wgate", h, f1, dn, GemmEpi(), st));
         }
         const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
-        ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h, st));
         {
             float *slot = s->red_slot();
-            ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, x1, mean2, rstd2, T, h, h,
-                                       s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, slot, st, s->defer()));
+            ZPP_OTHER(launch_norm_bwd_colreduce(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h,
+                                                s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, slot,
+                                                s->defer(), st));
         }
         // ---- attention branch
         ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
@@ -637,11 +637,11 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
             ZPP_OTHER(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
         ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
         ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
-        ZPP_OTHER(launch_norm_bwd(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h, st));
         {
             float *slot = s->red_slot();
-            ZPP_OTHER(launch_colreduce(s->dt, gpt ? COLRED_LAYERNORM : COLRED_RMSNORM, dn, xs, mean1, rstd1, T, h, h,
-                                       s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, slot, st, s->defer()));
+            ZPP_OTHER(launch_norm_bwd_colreduce(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h,
+                                                s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, slot,
+                                                s->defer(), st));
         }
         dcur = dout;
     }
