@@ -15,7 +15,7 @@
 //
 // Backward: three kernels without atomics.  dQ: same structure as forward (lane = query), loops over
 // key tiles.  dK and dV: lane = key, loop over query tiles.  P is recomputed from the saved
-// log-sum-exp; delta = rowsum(dO o O) is computed by a small kernel first.
+// log-sum-exp; delta = rowsum(dO o O) is computed by the dQ kernel and handed to the dK kernel.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -307,9 +307,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *_
 // gathered from the same key tile through the transposing load.
 template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                       const bf16 *__restrict__ attn,
                                                                        const bf16 *__restrict__ dattn,
                                                                        const float *__restrict__ lse,
-                                                                       const float *__restrict__ delta,
+                                                                       float *__restrict__ delta,
                                                                        bf16 *__restrict__ dqkv, int seq, int nh,
                                                                        int nb, float scale, float scale_log2e)
 {
@@ -336,7 +337,20 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
     }
     const int64_t stat = ((int64_t)bi * nh + n) * seq + qw0 + c;
     const float l2 = lse[stat] * 1.44269504088896340736f;
-    const float dl = delta[stat];
+    // delta[q] = sum_e dO[q,e] * O[q,e]: this lane holds half of its query's dO row; computed here (and
+    // stored for the dK kernel, which runs after this one) instead of by a kernel of its own
+    float dl = 0.0f;
+    {
+        const bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 of = *reinterpret_cast<const bf16x8 *>(op + 16 * st);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[st][k], (float)of[k], dl);
+        }
+        dl += __shfl_xor(dl, 32, 64);
+        if (g == 0) delta[stat] = dl;
+    }
 
     TileCopy<NW> cp;
     cp.init(lane, wave, ld);
@@ -591,24 +605,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
         }
 }
 
-// delta[b, nh, s] = sum_e dattn * attn, one wavefront per (row, head): each lane owns two columns
-__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(const bf16 *__restrict__ attn,
-                                                              const bf16 *__restrict__ dattn,
-                                                              float *__restrict__ delta, int64_t rows, int seq, int nh)
-{
-    const int lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (row, head)
-    if (item >= rows * nh) return;
-    const int64_t t = item / nh;
-    const int n = (int)(item % nh);
-    const int64_t base = t * ((int64_t)nh * kD) + (int64_t)n * kD + lane * 2;
-    const bf16x2 a = *reinterpret_cast<const bf16x2 *>(attn + base);
-    const bf16x2 d = *reinterpret_cast<const bf16x2 *>(dattn + base);
-    float acc = (float)a[0] * (float)d[0] + (float)a[1] * (float)d[1];
-    acc = wave_sum(acc);
-    if (lane == 0) delta[((t / seq) * nh + n) * seq + (t % seq)] = acc;
-}
-
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
 
 template <class K>
@@ -644,7 +640,7 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
 }
 
 template <int NW>
-static hipError_t launch_attn_bwd_nw(const void *qkv, const void *dattn, const float *lse, float *delta,
+static hipError_t launch_attn_bwd_nw(const void *qkv, const void *attn, const void *dattn, const float *lse, float *delta,
                                      void *dqkv, int64_t b, int64_t seq, int64_t nh, float scale, hipStream_t s)
 {
     static bool a1 = false, a2 = false, a3 = false;
@@ -655,9 +651,9 @@ static hipError_t launch_attn_bwd_nw(const void *qkv, const void *dattn, const f
     if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false, NW>, lds_dkv, a3)) return e;
     const float scale_log2e = scale * 1.44269504088896340736f;
     const dim3 grid((unsigned)(seq / (32 * NW) * nh * b));
-    attn_bwd_dq_mfma_kernel<NW><<<grid, NW * 64, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                              (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
-                                                              scale_log2e);
+    attn_bwd_dq_mfma_kernel<NW><<<grid, NW * 64, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn,
+                                                              (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq,
+                                                              (int)nh, (int)b, scale, scale_log2e);
     attn_bwd_dkv_mfma_kernel<true, NW><<<grid, NW * 64, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse,
                                                                       delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
                                                                       scale, scale_log2e);
@@ -673,11 +669,8 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
     const float scale = 1.0f / sqrtf((float)d);
-    const int64_t rows = b * seq;
-    attn_delta_mfma_kernel<<<(unsigned)((rows * nh + 3) / 4), 256, 0, s>>>((const bf16 *)attn, (const bf16 *)dattn,
-                                                                            delta, rows, (int)seq, (int)nh);
-    if (seq % 256 == 0) return launch_attn_bwd_nw<8>(qkv, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
-    return launch_attn_bwd_nw<4>(qkv, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
+    if (seq % 256 == 0) return launch_attn_bwd_nw<8>(qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
+    return launch_attn_bwd_nw<4>(qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
 }
 
 }  // namespace zpp
