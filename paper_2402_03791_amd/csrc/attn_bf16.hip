@@ -118,9 +118,9 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
 // Work-groups are dealt round-robin over the 8 XCDs, each with a private L2: all work-groups of one
 // (sample, head) pair are given to the same XCD and to neighbouring dispatch slots, so that the head's
 // K/V (or Q/dO) rows are fetched into one L2 once and shared there, instead of into all eight.
-__device__ __forceinline__ void decode_block(int nblk, int nh, int nb, int &blk, int &n, int &bi)
+__device__ __forceinline__ void decode_block(int id, int nblk, int nh, int nb, int &blk, int &n, int &bi)
 {
-    const int id = blockIdx.x, nv = nh * nb;
+    const int nv = nh * nb;
     int v;
     if ((nv & 7) == 0) {
         const int j = id >> 3;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *_
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
     int qb, n, bi;
-    decode_block(seq / (32 * NW), nh, nb, qb, n, bi);
+    decode_block(blockIdx.x, seq / (32 * NW), nh, nb, qb, n, bi);
     // NW == 4: heavy (late) query blocks first; NW == 8: all work-groups are equally heavy
     if (NW == 4) qb = seq / 128 - 1 - qb;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
     int qb, n, bi;
-    decode_block(seq / (32 * NW), nh, nb, qb, n, bi);
+    decode_block(blockIdx.x, seq / (32 * NW), nh, nb, qb, n, bi);
     if (NW == 4) qb = seq / 128 - 1 - qb;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -450,19 +450,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
 //   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
 // Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy.
 template <bool DK, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                   const bf16 *__restrict__ dattn,
-                                                                   const float *__restrict__ lse,
-                                                                   const float *__restrict__ delta,
-                                                                   bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                   int nb, float scale, float scale_log2e)
+__device__ __forceinline__ void attn_bwd_dkv_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
+                                                  const float *__restrict__ lse, const float *__restrict__ delta,
+                                                  bf16 *__restrict__ dqkv, int seq, int nh, int nb, float scale,
+                                                  float scale_log2e, int block_id)
 {
     // [kStages][Q tile | dO tile], then [kStages][lse of the tile's 64 queries | delta of the same].  The per-query
     // statistics travel with the tiles (a 4-byte-per-lane global->LDS load each): fetching them with
     // ordinary loads inside the loop would make every use wait, in order, behind the next tile's copies.
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int kb, n, bi;  // NW == 4: early key blocks see the most queries and come first
-    decode_block(seq / (32 * NW), nh, nb, kb, n, bi);
+    decode_block(block_id, seq / (32 * NW), nh, nb, kb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -605,6 +603,25 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
         }
 }
 
+// dK and dV in one grid: the first `total` work-groups compute dK (the longer ones: three products per
+// tile), the rest dV, so the dV work-groups fill the tail of the dK ones.  total % 8 == 0 keeps the
+// work-group -> XCD assignment of decode_block valid for the second half.
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
+                                                                       const bf16 *__restrict__ dattn,
+                                                                       const float *__restrict__ lse,
+                                                                       const float *__restrict__ delta,
+                                                                       bf16 *__restrict__ dqkv, int seq, int nh,
+                                                                       int nb, float scale, float scale_log2e,
+                                                                       int total)
+{
+    if ((int)blockIdx.x < total)
+        attn_bwd_dkv_body<true, NW>(qkv, dattn, lse, delta, dqkv, seq, nh, nb, scale, scale_log2e, blockIdx.x);
+    else
+        attn_bwd_dkv_body<false, NW>(qkv, dattn, lse, delta, dqkv, seq, nh, nb, scale, scale_log2e,
+                                     (int)blockIdx.x - total);
+}
+
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
 
 template <class K>
@@ -643,23 +660,19 @@ template <int NW>
 static hipError_t launch_attn_bwd_nw(const void *qkv, const void *attn, const void *dattn, const float *lse, float *delta,
                                      void *dqkv, int64_t b, int64_t seq, int64_t nh, float scale, hipStream_t s)
 {
-    static bool a1 = false, a2 = false, a3 = false;
+    static bool a1 = false, a2 = false;
     constexpr size_t lds_dq = kStages<NW> * 2 * kTileBytes;                        // stages of (K tile, V tile)
     constexpr size_t lds_dkv = kStages<NW> * 2 * kTileBytes + kStages<NW> * 512;  // (Q tile, dO tile) + lse/delta
     if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel<NW>, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<true, NW>, lds_dkv, a2)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<false, NW>, lds_dkv, a3)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<NW>, lds_dkv, a2)) return e;
     const float scale_log2e = scale * 1.44269504088896340736f;
-    const dim3 grid((unsigned)(seq / (32 * NW) * nh * b));
-    attn_bwd_dq_mfma_kernel<NW><<<grid, NW * 64, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn,
-                                                              (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq,
-                                                              (int)nh, (int)b, scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<true, NW><<<grid, NW * 64, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse,
-                                                                      delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
-                                                                      scale, scale_log2e);
-    attn_bwd_dkv_mfma_kernel<false, NW><<<grid, NW * 64, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse,
-                                                                       delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
-                                                                       scale, scale_log2e);
+    const int total = (int)(seq / (32 * NW) * nh * b);
+    attn_bwd_dq_mfma_kernel<NW><<<dim3((unsigned)total), NW * 64, lds_dq, s>>>(
+        (const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh,
+        (int)b, scale, scale_log2e);
+    attn_bwd_dkv_mfma_kernel<NW><<<dim3((unsigned)(2 * total)), NW * 64, lds_dkv, s>>>(
+        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
+        scale_log2e, total);
     return hipGetLastError();
 }
 
