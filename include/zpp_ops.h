@@ -18,9 +18,10 @@ extern "C" {
  * transposed operands, of the input- and weight-gradient products of Section 2.3.
  * A, B: bf16, K-contiguous, leading dimensions lda, ldb (elements, multiples of 8); K % 64 == 0.
  * C: bf16, or float when out_f32 != 0; leading dimension ldc.  bias, resid: bf16 or NULL.
- * variant: -1 automatic; 0..11 force a kernel generation and tile shape (0-2 register-staged 256x256/128x256/
+ * variant: -1 automatic; 0..15 force a kernel generation and tile shape (0-2 register-staged 256x256/128x256/
  * 128x128, 3-4 pipelined 256x256/128x128, 5-8 hand-ordered 256x256(8 waves)/128x128/256x256(4 waves)/128x256,
- * 9-11 LDS ring of K = 32 stages: 256x256 with 5 stages, 256x256 with 4, 128x128 with 4). */
+ * 9-11 LDS ring of K = 32 stages: 256x256 with 5 stages, 256x256 with 4, 128x128 with 4,
+ * 12-15 ring of K = 64 stages: 128x128 with 4 and 5 stages, 256x128 and 128x256 with 3). */
 zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
                                int32_t out_f32, int32_t variant, void *hip_stream);

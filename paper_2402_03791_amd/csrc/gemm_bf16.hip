@@ -966,6 +966,235 @@ static hipError_t launch_variant_r(int64_t M, int64_t N, int64_t K, const bf16 *
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Hand-ordered kernel with NS LDS stages of K = 64 (same 128-byte rows and swizzle as above) instead of
+// two: the copies of K-step kt+NS-1 are issued during K-step kt.  For the small tiles this is what
+// matters: a 128x128 work-group multiplies a K-step in ~500-1000 cycles, a loaded HBM round trip is
+// ~2000, so with one K-step of lookahead both work-groups of a CU spend most of the time waiting
+// (measured 43 % matrix-core busy at 2.2 GHz).  Four stages of 32 KB cover the round trip; the CU then
+// holds one work-group instead of two.
+template <int BM, int BN, int WGM, int WGN, int NS>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
+    constexpr int LPS = A_I + B_I;            // global->LDS copies per wave per K-step
+    constexpr int GQ = (LPS + 3) / 4;         // copies per phase (the last phases may get fewer)
+    constexpr int READS = MT + NT, MFMAS = MT * NT;
+    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
+    constexpr int B_REGION = NS * A_BUF;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
+    static_assert(NS >= 3 && NS <= 5, "ring depth");
+    static_assert(NS * A_BUF + 3 * 4096 < 2 * 65536 && NS * B_BUF + 3 * 4096 < 2 * 65536, "two base registers");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    int pid = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = pid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (pid % per_group) % gsz;
+    const int tn = (pid % per_group) / gsz;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    const int lrow = lane >> 3, lch = lane & 7;
+    uint32_t a_voff[A_I], b_voff[B_I];
+#pragma unroll
+    for (int j = 0; j < A_I; ++j) {
+        const int row = (wave * A_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t r = row;
+        if (m0 + r > M - 1) r = M - 1 - m0;
+        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < B_I; ++j) {
+        const int row = (wave * B_I + j) * 8 + lrow;
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+        int64_t r = row;
+        if (n0 + r > N - 1) r = N - 1 - n0;
+        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
+    }
+    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
+    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
+
+    // LDS read addresses: per K sub-step a base for byte offsets below 64 KB and one for those above
+    const int khalf = lane >> 5;
+    unsigned char *a_rd[2][4], *b_rd[2][4];
+    {
+        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+        const int asw = (arow & 7) ^ ((arow >> 3) & 1), bsw = (brow & 7) ^ ((brow >> 3) & 1);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            a_rd[0][ks] = smem_raw + arow * 128 + (((ks * 2 + khalf) ^ asw) << 4);
+            b_rd[0][ks] = smem_raw + B_REGION + brow * 128 + (((ks * 2 + khalf) ^ bsw) << 4);
+            a_rd[1][ks] = a_rd[0][ks] + 65536;
+            b_rd[1][ks] = b_rd[0][ks] + 65536;
+        }
+    }
+    auto rd_a = [&](auto slot_c, auto ks_c, auto i_c) {
+        constexpr int off = decltype(slot_c)::value * A_BUF + decltype(i_c)::value * 4096;
+        constexpr int KS = decltype(ks_c)::value;
+        if constexpr (off < 65536)
+            return *reinterpret_cast<const bf16x8 *>(a_rd[0][KS] + off);
+        else
+            return *reinterpret_cast<const bf16x8 *>(a_rd[1][KS] + (off - 65536));
+    };
+    auto rd_b = [&](auto slot_c, auto ks_c, auto j_c) {
+        constexpr int off = decltype(slot_c)::value * B_BUF + decltype(j_c)::value * 4096;
+        constexpr int KS = decltype(ks_c)::value;
+        if constexpr (off < 65536)
+            return *reinterpret_cast<const bf16x8 *>(b_rd[0][KS] + off);
+        else
+            return *reinterpret_cast<const bf16x8 *>(b_rd[1][KS] + (off - 65536));
+    };
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = (int)(K / kBK);
+    bf16x8 af[2][MT], bfr[2][NT];
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
+    auto gll = [&](int n, int kt, int slot) {
+        const char *abase = a_tile + (int64_t)kt * (kBK * 2);
+        const char *bbase = b_tile + (int64_t)kt * (kBK * 2);
+        if (n < A_I) {
+            const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "memory");
+        } else {
+            const int m = n - A_I;
+            const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "memory");
+        }
+    };
+    // One phase: the MFMAs of the sub-step in fragment set CUR, interleaved with the reads of sub-step RKS
+    // of slot RSLOT into the other set and with copies GFIRST .. GFIRST+GCNT-1 of K-step gkt into slot GSLOT.
+    auto phase = [&](auto cur_c, auto rslot_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gslot_c, int gkt) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
+        constexpr int GSLOT = decltype(gslot_c)::value;
+        static_for<MFMAS>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            constexpr int i = t / NT, j = t % NT;
+            if constexpr (t < READS) {
+                if constexpr (t == 0)
+                    af[NXT][0] = rd_a(rslot_c, rks_c, std::integral_constant<int, 0>{});
+                else if constexpr (t <= NT)
+                    bfr[NXT][t - 1] = rd_b(rslot_c, rks_c, std::integral_constant<int, t - 1>{});
+                else
+                    af[NXT][t - NT] = rd_a(rslot_c, rks_c, std::integral_constant<int, t - NT>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (GCNT > 0) {
+                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
+                if constexpr (after > before) {
+                    gll(GFIRST + before, gkt, GSLOT);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    constexpr int C0 = GQ < LPS ? GQ : LPS;                          // copies in phase 0
+    constexpr int C1 = (2 * GQ < LPS ? 2 * GQ : LPS) - C0;           // phase 1
+    constexpr int C2 = (3 * GQ < LPS ? 3 * GQ : LPS) - C0 - C1;      // phase 2
+    constexpr int C3 = LPS - C0 - C1 - C2;                           // phase 3 (after the barrier)
+
+    // K-step kt out of ring slot SLOT.  On entry fragment set 0 holds sub-step 0 of the tile and K-steps up
+    // to kt+NS-2 have been requested; this K-step requests kt+NS-1 into the slot the previous one left.
+    auto kstep = [&](auto slot_c, int kt) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        using IS = std::integral_constant<int, SLOT>;
+        using IN = std::integral_constant<int, (SLOT + 1) % NS>;
+        using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;
+        const int far = kt + NS - 1 < nk ? kt + NS - 1 : nk - 1;  // clamped: a surplus reload is never read
+        phase(I0{}, IS{}, I1{}, I0{}, std::integral_constant<int, C0>{}, IF{}, far);
+        phase(I1{}, IS{}, I2{}, std::integral_constant<int, C0>{}, std::integral_constant<int, C1>{}, IF{}, far);
+        phase(I0{}, IS{}, I3{}, std::integral_constant<int, C0 + C1>{}, std::integral_constant<int, C2>{}, IF{}, far);
+        // K-step kt+1 has landed: NS-3 whole K-steps and this K-step's first three batches may stay in flight
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 3) * LPS + C0 + C1 + C2) : "memory");
+        __syncthreads();
+        phase(I1{}, IN{}, I0{}, std::integral_constant<int, C0 + C1 + C2>{}, std::integral_constant<int, C3>{}, IF{}, far);
+    };
+
+    static_for<NS - 1>([&](auto ss) {
+        constexpr int S = decltype(ss)::value;
+        const int kt = S < nk ? S : nk - 1;
+#pragma unroll
+        for (int n = 0; n < LPS; ++n) gll(n, kt, S);
+    });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    af[0][0] = rd_a(I0{}, I0{}, I0{});
+    static_for<NT>([&](auto jj) { bfr[0][decltype(jj)::value] = rd_b(I0{}, I0{}, jj); });
+    static_for<MT - 1>([&](auto ii) {
+        constexpr int i = decltype(ii)::value + 1;
+        af[0][i] = rd_a(I0{}, I0{}, std::integral_constant<int, i>{});
+    });
+
+    for (int kt = 0; kt < nk; kt += NS)
+        static_for<NS>([&](auto ii) {
+            constexpr int I = decltype(ii)::value;
+            if (kt + I < nk) kstep(ii, kt + I);
+        });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+static hipError_t launch_variant_d(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    constexpr int NTH = WGM * WGN * 64;
+    constexpr size_t lds = (size_t)NS * (BM + BN) * kBK * sizeof(bf16);
+    static bool attr_set = false;
+    auto kern = gemm_bf16_nt_d_kernel<BM, BN, WGM, WGN, NS>;
+    if (!attr_set) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
+                                                                 tiles_n);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int WGM, int WGN>
 static hipError_t launch_variant_h(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
                                    int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
@@ -1040,33 +1269,21 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     int variant = g_forced_variant;
     if (variant < 0) {
-        // 256x256 tiles (8 waves) whenever they give every CU a work-group: lowest LDS and L2 traffic
-        // per flop.  Otherwise (e.g. a T x h output of 128 big tiles) 128x128 tiles, 2 work-groups per CU.
-        const int64_t tm = (M + 255) / 256, tn = (N + 255) / 256, t256 = tm * tn;
-        // One CU holds one 256x256 work-group, so a grid runs in rounds of 256 tiles and e.g. 384 tiles
-        // (T x 3h at T = 2048) take as long as 512.  With only a few rounds, cut the columns into a part
-        // that is a whole number of rounds and a remainder that goes out with the small tiles.
-        if (t256 > 256 && t256 < 1024 && t256 % 256 != 0) {
-            int64_t cols = 0;  // tile columns of the first part
-            for (int64_t c = tn - 1; c >= 1; --c)
-                if ((tm * c) % 256 == 0) {
-                    cols = c;
-                    break;
-                }
-            if (cols > 0) {
-                const int64_t n1 = cols * 256;
-                GemmEpi e2 = epi;
-                const size_t osz = epi.out_f32 ? 4 : 2;
-                if (epi.bias) e2.bias = (const bf16 *)epi.bias + n1;
-                if (epi.resid) e2.resid = (const bf16 *)epi.resid + n1;
-                if (epi.aux) e2.aux = (const bf16 *)epi.aux + n1;
-                if (epi.out2) e2.out2 = (bf16 *)epi.out2 + n1;
-                hipError_t err = launch_gemm_bf16_nt(M, n1, K, A, lda, B, ldb, C, ldc, epi, s);
-                if (err != hipSuccess) return err;
-                return launch_gemm_bf16_nt(M, N - n1, K, A, lda, b + n1 * ldb, ldb, (char *)C + n1 * osz, ldc, e2, s);
-            }
+        // 256x256 tiles, two LDS stages (variant 5): lowest LDS and L2 traffic per flop, but one work-group
+        // per CU, so a grid runs in rounds of 256 tiles; used when the rounds come out whole (or there are
+        // many).  Otherwise 256x128 / 128x256 tiles with three stages (variants 14, 15): twice as many tiles,
+        // and copies issued two K-steps ahead, which the shorter K-step of a smaller tile needs (a T x h
+        // output at T = 2048 is 128 big tiles; T x 3h is 384, a round and a half).  Small problems: 128x128.
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+        if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024)) {
+            variant = 5;
+        } else {
+            const int64_t ta = ((M + 255) / 256) * ((N + 127) / 128), tb = ((M + 127) / 128) * ((N + 255) / 256);
+            if (ta >= 192 || tb >= 192)
+                variant = tb >= 192 ? 15 : 14;
+            else
+                variant = 6;
         }
-        variant = t256 >= 256 ? 5 : 6;
     }
     switch (variant) {
     case 0: return launch_variant<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
@@ -1078,6 +1295,10 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     case 6: return launch_variant_h<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 7: return launch_variant_h<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 8: return launch_variant_h<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 12: return launch_variant_d<128, 128, 2, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 13: return launch_variant_d<128, 128, 2, 2, 5>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 14: return launch_variant_d<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case 15: return launch_variant_d<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 9: return launch_variant_r<256, 256, 2, 4, 5>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 10: return launch_variant_r<256, 256, 2, 4, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case 11: return launch_variant_r<128, 128, 2, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);

@@ -795,7 +795,7 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (K % 64 || lda % 8 || ldb % 8 || lda < K || ldb < K || ldc < N)
         return fail(ZPP_ERR_UNSUPPORTED, "need K %% 64 == 0, lda/ldb multiples of 8 and >= K, ldc >= N");
     if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
-    if (variant < -1 || variant > 11) return fail(ZPP_ERR_ARG, "variant must be -1..11");
+    if (variant < -1 || variant > 15) return fail(ZPP_ERR_ARG, "variant must be -1..15");
     GemmEpi e;
     e.bias = bias;
     e.resid = resid;

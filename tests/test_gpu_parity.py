@@ -183,6 +183,8 @@ def test_materialize_counters_and_idempotence():
     (1000, 1000, 320, 5), (1000, 1000, 320, 6),
     (300, 520, 192, 9), (300, 520, 192, 10), (300, 520, 192, 11), (1000, 1000, 320, 9), (1000, 1000, 320, 11),
     (512, 512, 64, 9), (256, 256, 1024, 9), (256, 256, 1024, 10), (1, 1, 64, 11),
+    (300, 520, 192, 12), (300, 520, 192, 13), (300, 520, 192, 14), (300, 520, 192, 15), (1000, 1000, 320, 12),
+    (128, 128, 64, 12), (128, 128, 1024, 13), (512, 256, 768, 14), (1, 1, 64, 15),
 ])
 def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     print(f"gemm {M}x{N}x{K} variant {variant}", flush=True)
