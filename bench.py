@@ -149,7 +149,7 @@ def main():
     bf16 = sh.compute_dtype == 1
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     roofline = {
-        "kernel": "gemm_bf16_nt_h_kernel" if bf16 else "gemm_f32_kernel",
+        "kernel": "gemm_bf16_nt_h_kernel, gemm_bf16_nt_d_kernel (all bf16 GEMMs of the step)" if bf16 else "gemm_f32_kernel",
         "bound": "mfma" if bf16 else "alu",
         "achieved": round(gemm_tflops, 2), "peak": peak, "unit": "TFLOP/s",
         "frac": round(gemm_tflops / peak, 4),
