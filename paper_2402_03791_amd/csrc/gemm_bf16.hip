@@ -991,6 +991,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
     static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
     static_assert(NS >= 3 && NS <= 5, "ring depth");
     static_assert(NS * A_BUF + 3 * 4096 < 2 * 65536 && NS * B_BUF + 3 * 4096 < 2 * 65536, "two base registers");
+    static_assert((NS - 2) * LPS < 64, "the wait count is a 6-bit immediate");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
