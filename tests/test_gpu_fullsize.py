@@ -60,3 +60,34 @@ def test_adam_over_the_whole_6p2b_shard():
     ref = p0.astype(np.float64) + 0.5 * g.astype(np.float64)
     assert np.abs(G.cpu().numpy() - ref).max() <= 1e-7 * np.abs(ref).max() + 1e-9
     o.close()
+
+
+@pytest.mark.parametrize("M,N,K,variant", [
+    (2048, 4096, 16384, -1),    # T x h output: the three-stage ring kernel, 256 K-steps
+    (2048, 12288, 4096, -1),    # T x 3h: a grid of one and a half rounds of 256x256 tiles
+    (2048, 16384, 4096, -1),    # two whole rounds of 256x256 tiles
+    (16384, 4096, 2048, -1),    # weight-gradient shape, fp32 output
+    (2048, 4096, 4096, 14), (2048, 4096, 4096, 13), (2048, 4096, 4096, 9),
+])
+def test_gemm_repeats_are_bit_identical_at_full_shape(M, N, K, variant):
+    """The ring kernels recycle LDS slots while copies are in flight; a slot reused too early would show as
+    run-to-run differences (the products themselves are checked against the oracle elsewhere).  Forty
+    launches at the benchmark's shapes, cold operands in between, must all give the same bits."""
+    print(f"gemm repeat {M}x{N}x{K} variant {variant}", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    A = torch.randn(M, K, device="cuda", generator=g).to(torch.bfloat16)
+    B = (torch.randn(N, K, device="cuda", generator=g) * 0.05).to(torch.bfloat16)
+    f32 = K == 2048
+    C0 = torch.empty(M, N, dtype=torch.float32 if f32 else torch.bfloat16, device="cuda")
+    C = torch.empty_like(C0)
+    spoil = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")  # flushes the caches between launches
+    zpp.op_gemm_bf16_nt(A, B, C0, variant=variant)
+    ref = (A[:64].float() @ B[:64].float().t()).cpu().numpy()
+    got = C0[:64, :64].float().cpu().numpy()
+    assert np.abs(got - ref).max() <= 2e-2 * np.abs(ref).max()
+    for i in range(40):
+        if i % 4 == 0:
+            spoil.fill_(i)
+        C.zero_()
+        zpp.op_gemm_bf16_nt(A, B, C, variant=variant)
+        assert torch.equal(C.view(torch.int32 if f32 else torch.int16), C0.view(torch.int32 if f32 else torch.int16)), i
