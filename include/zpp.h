@@ -120,6 +120,7 @@ zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float 
  *        -> stage_backward(mb) only after stage_forward(mb), once
  *        -> stage_accumulate_grads(mb) only after stage_backward(mb), once; because the staging
  *           buffer is reused, stage_backward of another micro-batch before that is ZPP_ERR_STATE
+ *           (stage_backward_accumulate(mb) stands for the pair backward + accumulate of one micro-batch)
  *        -> shard_adam_step only when no micro-batch is backward-done but not accumulated
  *        -> zpp_stage_end_unit, after which the next unit starts with forward (the working copy
  *           stays valid until P changes; after shard_adam_step without write-back a new
@@ -147,6 +148,16 @@ zpp_status stage_backward(zpp_stage *stage, int32_t micro_batch, const void *dy,
 /* Stand-in for the per-unit gradient reduce-scatter of Section 3.2: G <- G + scale * g_mb over the
  * whole flat shard. */
 zpp_status stage_accumulate_grads(zpp_stage *stage, int32_t micro_batch, float scale, void *hip_stream);
+
+/* stage_backward followed by stage_accumulate_grads of the same micro-batch, as one call that never
+ * materialises g_mb: every weight-gradient product adds scale * dW into its place in G from the
+ * GEMM epilogue, and the bias and gain gradients are added by the reduction that sums them
+ * (Section 2.3 for the products, Section 3.2 for the accumulation).  Each element of G receives the same
+ * single fused multiply-add G + scale * g as in the two-call sequence, so the results are bit-identical
+ * to it; the staging buffer is neither read nor written.  Arguments and errors as stage_backward;
+ * afterwards the micro-batch counts as accumulated. */
+zpp_status stage_backward_accumulate(zpp_stage *stage, int32_t micro_batch, const void *dy, void *dx,
+                                     float scale, void *hip_stream);
 
 /* The optimizer-step task (Section 3.1.1; Section 3.2.2 "update the parameters corresponding to the
  * partitioned optimizer states"): Adam on elements [offset, offset+count) of P, M, V using G.

@@ -18,6 +18,8 @@ extern "C" {
  * transposed operands, of the input- and weight-gradient products of Section 2.3.
  * A, B: bf16, K-contiguous, leading dimensions lda, ldb (elements, multiples of 8); K % 64 == 0.
  * C: bf16, or float when out_f32 != 0; leading dimension ldc.  bias, resid: bf16 or NULL.
+ * out_f32 == 2: C is float and receives C + result (the in-place gradient accumulation of
+ * stage_backward_accumulate, scale 1), so C must hold valid data on entry.
  * variant: -1 automatic; 0..15 force a kernel generation and tile shape (0-2 register-staged 256x256/128x256/
  * 128x128, 3-4 pipelined 256x256/128x128, 5-8 hand-ordered 256x256(8 waves)/128x128/256x256(4 waves)/128x256,
  * 9-11 LDS ring of K = 32 stages: 256x256 with 5 stages, 256x256 with 4, 128x128 with 4,

@@ -13,7 +13,7 @@ _lib = None
 EXPORTS = [
     "zpp_stage_create", "zpp_stage_destroy", "zpp_stage_param_count", "zpp_stage_workspace_bytes",
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
-    "stage_forward", "stage_backward", "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
+    "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
@@ -67,6 +67,7 @@ def load_library(path: str | None = None):
     L.stage_materialize_params.argtypes = [vp, vp]
     L.stage_forward.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward.argtypes = [vp, i32, vp, vp, vp]
+    L.stage_backward_accumulate.argtypes = [vp, i32, vp, vp, f32, vp]
     L.stage_accumulate_grads.argtypes = [vp, i32, f32, vp]
     L.shard_adam_step.argtypes = [vp, u64, u64, ctypes.POINTER(_Adam), vp]
     L.zpp_stage_end_unit.argtypes = [vp]
@@ -215,6 +216,14 @@ class Stage:
         _check(lib().stage_backward(self._h, mb, dy.data_ptr(), dx.data_ptr(), _stream_ptr(stream)))
         return dx
 
+    def backward_accumulate(self, mb: int, dy, dx=None, scale: float = 1.0, stream=None):
+        import torch
+        if dx is None:
+            dx = torch.empty_like(dy)
+        _check(lib().stage_backward_accumulate(self._h, mb, dy.data_ptr(), dx.data_ptr(), scale,
+                                               _stream_ptr(stream)))
+        return dx
+
     def accumulate_grads(self, mb: int, scale: float = 1.0, stream=None):
         _check(lib().stage_accumulate_grads(self._h, mb, scale, _stream_ptr(stream)))
 
@@ -264,14 +273,18 @@ def profile_read():
 
 
 # ---- operator-level entry points (include/zpp_ops.h) ----------------------------------------------
-def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, variant: int = -1, stream=None):
+def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, variant: int = -1, stream=None, accumulate: bool = False):
+    """C = A . B^T (+ bias) (+ resid); accumulate (float C only): C += A . B^T."""
     import torch
+    if accumulate and C.dtype != torch.float32:
+        raise ValueError("accumulate needs a float32 C")
     M, K = A.shape
     N = B.shape[0]
     _check(lib().zpp_op_gemm_bf16_nt(M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(),
                                      C.stride(0), None if bias is None else bias.data_ptr(),
                                      None if resid is None else resid.data_ptr(),
-                                     int(C.dtype == torch.float32), variant, _stream_ptr(stream)))
+                                     2 if accumulate else int(C.dtype == torch.float32), variant,
+                                     _stream_ptr(stream)))
     return C
 
 

@@ -50,6 +50,11 @@ template <class T> __device__ __forceinline__ void store16(T *p, const Vec16<T> 
     *reinterpret_cast<decltype(r.v) *>(p) = r.v;
 }
 
+// One gradient-accumulation step g + scale * v (Section 3.1), a single fused multiply-add.  Every kernel
+// that adds into the flat gradient buffer uses this form, so the separate accumulate pass and the
+// weight-gradient epilogues that accumulate in place give bit-identical sums.
+__device__ __forceinline__ float grad_accum(float g, float scale, float v) { return __builtin_fmaf(scale, v, g); }
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

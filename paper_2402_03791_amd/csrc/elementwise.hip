@@ -180,6 +180,8 @@ struct FinishBatch {
     FinishItem item[kFinishMax];
     int32_t first[kFinishMax + 1];
     int32_t n;
+    int32_t accumulate;  // out <- out + scale * sum
+    float scale;
 };
 
 __global__ __launch_bounds__(256) void finish_columns_kernel(FinishBatch b)
@@ -194,15 +196,17 @@ __global__ __launch_bounds__(256) void finish_columns_kernel(FinishBatch b)
         s0 += it.partial0[(int64_t)r * it.C + c];
         if (it.partial1) s1 += it.partial1[(int64_t)r * it.C + c];
     }
-    it.out0[c] = s0;
-    if (it.out1) it.out1[c] = s1;
+    it.out0[c] = b.accumulate ? grad_accum(it.out0[c], b.scale, s0) : s0;
+    if (it.out1) it.out1[c] = b.accumulate ? grad_accum(it.out1[c], b.scale, s1) : s1;
 }
 
-hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s)
+hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s, bool accumulate, float scale)
 {
     for (int base = 0; base < n; base += kFinishMax) {
         FinishBatch b;
         b.n = n - base < kFinishMax ? n - base : kFinishMax;
+        b.accumulate = accumulate;
+        b.scale = scale;
         int32_t blocks = 0;
         for (int i = 0; i < b.n; ++i) {
             b.item[i] = items[base + i];

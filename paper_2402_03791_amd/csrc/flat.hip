@@ -131,12 +131,12 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ G, 
         const uint64_t i = base + u * 256;
         if (i < nvec) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) g[u][k] = g[u][k] + scale * v[u][k];
+            for (int k = 0; k < 4; ++k) g[u][k] = grad_accum(g[u][k], scale, v[u][k]);
             nt_store(g[u], reinterpret_cast<f32x4 *>(G) + i);
         }
     }
     if (blockIdx.x == 0)
-        for (uint64_t j = nvec * 4 + threadIdx.x; j < n; j += 256) G[j] = G[j] + scale * S[j];
+        for (uint64_t j = nvec * 4 + threadIdx.x; j < n; j += 256) G[j] = grad_accum(G[j], scale, S[j]);
 }
 
 hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s)

@@ -28,7 +28,8 @@ constexpr int kBK = 64;
 struct EpiBf16 {
     const bf16 *bias, *resid, *aux;
     bf16 *out2;
-    int act, gelu_mode, out_f32;
+    int act, gelu_mode, out_f32;  // out_f32 2: C (fp32) <- C + accum_scale * result
+    float accum_scale;
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -58,7 +59,8 @@ __device__ __forceinline__ void epi_store_one(float v, int64_t o_idx, void *__re
     if (epi.resid) v += (float)epi.resid[o_idx];
     if (epi.act == ACT_DGELU_MUL) v *= gelu_bwd((float)epi.aux[o_idx], epi.gelu_mode);
     if (epi.out_f32) {
-        reinterpret_cast<float *>(Cv)[o_idx] = v;
+        float *c = reinterpret_cast<float *>(Cv) + o_idx;
+        *c = epi.out_f32 == 2 ? grad_accum(*c, epi.accum_scale, v) : v;
     } else {
         const bf16 o = (bf16)v;
         reinterpret_cast<bf16 *>(Cv)[o_idx] = o;
@@ -96,12 +98,42 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         const int64_t n = n_wave + j * 32 + c32;
         bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
     }
+    // fp32 output without an element-wise tail (weight gradients): a lane owns 4 consecutive columns,
+    // so that one store instruction writes whole rows of the wave's slice (full 128-byte lines).
+    constexpr int CH4 = WN / 4, ROWS4 = 64 / CH4, PASSES4 = 32 / ROWS4;
+    const bool f32_rows = epi.out_f32 && vec_ok && !epi.resid && epi.act == ACT_NONE;
+    const bool accum = f32_rows && epi.out_f32 == 2;
+    const int row4 = lane / CH4, c4 = lane % CH4;
+    const int64_t n4 = n_wave + c4 * 4;
+    // this lane's first element, the distance between passes, and how much of the tile is inside C
+    float *const cf0 = reinterpret_cast<float *>(Cv) + (m_wave + row4) * ldc + n4;
+    const int64_t pstep = ROWS4 * ldc;
+    const int64_t rl = M - m_wave - row4;
+    const int rows_left = rl > 4096 ? 4096 : (int)rl;  // rows i*32 + p*ROWS4 below this are inside
+    const bool col_full = n4 + 4 <= N, col_any = n4 < N;
+    // Accumulating in place (Section 3.1: G <- G + scale * dW): the old values of a 32-row group are
+    // fetched one group ahead, so their latency hides behind the previous group's transposition and
+    // stores; only the first group's fetch is exposed.
+    f32x4 old[2][PASSES4];
+    auto fetch_old = [&](auto ii, f32x4 (&dst)[PASSES4]) {
+        constexpr int i = decltype(ii)::value;
+#pragma unroll
+        for (int p = 0; p < PASSES4; ++p) {
+            dst[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (i * 32 + p * ROWS4 < rows_left && col_full)
+                dst[p] = __builtin_nontemporal_load(
+                    reinterpret_cast<const f32x4 *>(cf0 + (i * (32 / ROWS4) + p) * pstep));
+        }
+    };
+    if (accum) fetch_old(std::integral_constant<int, 0>{}, old[0]);
     // The loop over the passes is a real loop: unrolled, the element-wise tail (with its GeLU branches)
     // would be replicated MT * PASSES times and the epilogue would run at the speed of instruction
     // fetch.  The 32-row groups stay instantiated one by one, since accumulator registers can only be
     // indexed with constants.
     static_for<MT>([&](auto ii) {
         constexpr int i = decltype(ii)::value;
+        if constexpr (i + 1 < MT)
+            if (accum) fetch_old(std::integral_constant<int, i + 1>{}, old[(i + 1) & 1]);
         static_for<NT>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
 #pragma unroll
@@ -111,24 +143,35 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         // the slice is private to this wave; LDS operations of a wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (epi.out_f32 && vec_ok && !epi.resid && epi.act == ACT_NONE) {
-            // fp32 output (weight gradients): a lane owns 4 consecutive columns, so that one store
-            // instruction writes whole rows of the wave's slice (full 128-byte lines)
-            constexpr int CH4 = WN / 4, ROWS4 = 64 / CH4, PASSES4 = 32 / ROWS4;
+        if (accum) {
+#pragma unroll
+            for (int p = 0; p < PASSES4; ++p) {
+                const int row = p * ROWS4 + row4;
+                const f32x4 val = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c4 * 4);
+                if (i * 32 + p * ROWS4 >= rows_left || !col_any) continue;
+                float *cf = cf0 + (i * (32 / ROWS4) + p) * pstep;
+                if (col_full) {
+                    f32x4 g = old[i & 1][p];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) g[k] = grad_accum(g[k], epi.accum_scale, val[k]);
+                    __builtin_nontemporal_store(g, reinterpret_cast<f32x4 *>(cf));
+                } else {
+                    for (int k = 0; k < 4 && n4 + k < N; ++k)
+                        cf[k] = grad_accum(cf[k], epi.accum_scale, stage[row * STRIDE + c4 * 4 + k]);
+                }
+            }
+        } else if (f32_rows) {
 #pragma unroll 1
             for (int p = 0; p < PASSES4; ++p) {
-                const int row = p * ROWS4 + lane / CH4;
-                const int c4 = lane % CH4;
-                const int64_t m = m_wave + i * 32 + row;
-                const int64_t n = n_wave + c4 * 4;
+                const int row = p * ROWS4 + row4;
                 const f32x4 val = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c4 * 4);
-                if (m >= M || n >= N) continue;
-                float *cf = reinterpret_cast<float *>(Cv) + m * ldc + n;
-                if (n + 4 <= N) {
+                if (i * 32 + p * ROWS4 >= rows_left || !col_any) continue;
+                float *cf = cf0 + (i * (32 / ROWS4) + p) * pstep;
+                if (col_full) {
                     // next read by the accumulate pass, long after: streamed past the caches
                     __builtin_nontemporal_store(val, reinterpret_cast<f32x4 *>(cf));
                 } else {
-                    for (int k = 0; k < 4 && n + k < N; ++k) cf[k] = stage[row * STRIDE + c4 * 4 + k];
+                    for (int k = 0; k < 4 && n4 + k < N; ++k) cf[k] = stage[row * STRIDE + c4 * 4 + k];
                 }
             }
         } else
@@ -1244,7 +1287,7 @@ hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (K <= 0 || (K % kBK) || (M % 8) || (N % 8) || M < 8 || N < 8 || (lda % 8) || (ldb % 8))
         return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32};
+              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
     if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
@@ -1266,7 +1309,7 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (M == 0 || N == 0) return hipSuccess;
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32};
+              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     int variant = g_forced_variant;
     if (variant < 0) {

@@ -9,7 +9,8 @@ namespace zpp {
 struct EpiF32 {
     const float *bias, *resid, *aux;
     float *out2;
-    int act, gelu_mode;
+    int act, gelu_mode, accumulate;
+    float accum_scale;
 };
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(int64_t M, int64_t N, int64_t K,
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int64_t M, int64_t N, int
             if (epi.bias) v += epi.bias[n];
             if (epi.resid) v += epi.resid[m * ldc + n];
             if (epi.act == ACT_DGELU_MUL) v *= gelu_bwd(epi.aux[m * ldc + n], epi.gelu_mode);
-            C[m * ldc + n] = v;
+            C[m * ldc + n] = epi.accumulate ? grad_accum(C[m * ldc + n], epi.accum_scale, v) : v;
             if (epi.act == ACT_GELU_DUAL) epi.out2[m * ldc + n] = gelu_fwd(v, epi.gelu_mode);
         }
     }
@@ -76,7 +77,7 @@ hipError_t launch_gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int6
 {
     if (M == 0 || N == 0) return hipSuccess;
     EpiF32 e{(const float *)epi.bias, (const float *)epi.resid, (const float *)epi.aux, (float *)epi.out2,
-             epi.act, epi.gelu_mode};
+             epi.act, epi.gelu_mode, epi.out_f32 == 2, epi.accum_scale};
     const dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
     gemm_f32_kernel<<<grid, 256, 0, s>>>(M, N, K, A, sam, sak, B, sbn, sbk, C, ldc, e);
     return hipGetLastError();

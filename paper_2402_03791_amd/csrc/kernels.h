@@ -28,7 +28,9 @@ struct GemmEpi {
     const void *aux = nullptr;    // ACT_DGELU_MUL: pre-activation u[m,n]; out = acc * gelu'(u)
     int act = ACT_NONE;
     int gelu_mode = 0;
-    int out_f32 = 0;              // 1: C is float regardless of the compute dtype (weight gradients)
+    int out_f32 = 0;              // 1: C is float regardless of the compute dtype (weight gradients);
+                                  // 2: as 1, and C <- C + accum_scale * result (accumulation in place)
+    float accum_scale = 1.0f;
 };
 
 // ---- flat-buffer passes (HBM bound) ----
@@ -63,7 +65,9 @@ struct FinishItem {
     int32_t rows;
     int64_t C;
 };
-hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s);
+// accumulate: out <- out + scale * sum instead of out <- sum
+hipError_t launch_finish_columns(const FinishItem *items, int n, hipStream_t s, bool accumulate = false,
+                                 float scale = 1.0f);
 // Two bf16 transposes in one launch: a[Ra, Ca] -> a_out[Ca, Ra] (with column sums of a when colsum is
 // given; then partial and defer as for launch_transpose_colsum, second level deferred), b likewise
 // without sums.  All sizes multiples of 64.

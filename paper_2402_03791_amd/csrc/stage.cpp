@@ -143,7 +143,14 @@ struct zpp_stage {
     {
         return ws + rWt.off + wt.at("blk" + std::to_string(blk) + "." + nm).dst_off * 2;
     }
-    float *Sp(int blk, const char *nm) const { return (float *)(ws + rS.off) + off(blk, nm); }
+    // Where the gradient of a tensor goes during a backward call: its place in the staging buffer, or,
+    // when the call accumulates in place (stage_backward_accumulate), its place in G.
+    bool acc_in_place = false;
+    float acc_scale = 1.0f;
+    float *Sp(int blk, const char *nm) const
+    {
+        return (acc_in_place ? G : (float *)(ws + rS.off)) + off(blk, nm);
+    }
     void *stash(int mb, int blk, const char *nm) const
     {
         return ws + stash_base + ((uint64_t)mb * L + blk) * stash_block_bytes + stash_t.at(nm).off;
@@ -315,7 +322,8 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
                      int64_t in, int64_t out, hipStream_t st)
 {
     GemmEpi epi;
-    epi.out_f32 = 1;
+    epi.out_f32 = s->acc_in_place ? 2 : 1;
+    epi.accum_scale = s->acc_scale;
     hipError_t e;
     if (s->dt == DT_BF16) {
         // Both operands are stored token-major.  They are transposed into scratch first so that the GEMM
@@ -343,7 +351,7 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
             }
         }
         ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
-                       2.0 * ((double)s->T * in + (double)s->T * out) + 4.0 * in * out);
+                       2.0 * ((double)s->T * in + (double)s->T * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out);
         e = launch_gemm_bf16_nt(out, in, s->T, tA, s->T, tB, s->T, s->Sp(blk, w), in, epi, st);
         return e;
     } else {
@@ -576,7 +584,12 @@ zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void 
     return ZPP_OK;
 }
 
-zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, void *hip_stream)
+namespace {
+
+// The backward sequence of one micro-batch; with in_place the gradients are added into G (scaled) as they
+// are produced, otherwise they are written to the staging buffer.
+zpp_status backward_sequence(zpp_stage *s, int32_t mb, const void *dy, void *dx, bool in_place, float scale,
+                             void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
     if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
@@ -595,6 +608,8 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
     void *gbuf[2] = {s->tp("gA"), s->tp("gB")};
     void *dn = s->tp("dn"), *dx1 = s->tp("dx1"), *dattn = s->tp("dattn"), *dqkv = s->tp("dqkv"), *du = s->tp("du");
     s->finish.clear();
+    s->acc_in_place = in_place;
+    s->acc_scale = scale;
     const void *dcur = dy;
     for (int blk = (int)s->L - 1; blk >= 0; --blk) {
         void *dout = blk == 0 ? dx : gbuf[blk & 1];
@@ -646,11 +661,25 @@ zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, vo
         dcur = dout;
     }
     // second level of every column reduction of this call, in one launch
-    ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st));
+    ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st, in_place, scale));
     s->finish.clear();
-    s->mb_state[mb] = MB_BWD;
-    s->pending_acc = mb;
+    s->acc_in_place = false;
+    s->mb_state[mb] = in_place ? MB_ACC : MB_BWD;
+    s->pending_acc = in_place ? -1 : mb;
     return ZPP_OK;
+}
+
+}  // namespace
+
+zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, void *hip_stream)
+{
+    return backward_sequence(s, mb, dy, dx, false, 1.0f, hip_stream);
+}
+
+zpp_status stage_backward_accumulate(zpp_stage *s, int32_t mb, const void *dy, void *dx, float scale,
+                                     void *hip_stream)
+{
+    return backward_sequence(s, mb, dy, dx, true, scale, hip_stream);
 }
 
 zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *hip_stream)
@@ -799,7 +828,7 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     GemmEpi e;
     e.bias = bias;
     e.resid = resid;
-    e.out_f32 = out_f32;
+    e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
     gemm_bf16_force_variant(variant);
     hipError_t err = launch_gemm_bf16_nt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
     gemm_bf16_force_variant(-1);

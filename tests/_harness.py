@@ -50,7 +50,9 @@ def run_oracle_unit(shape, P0: np.ndarray, xs, dys, dtype="f64", keep_stage=Fals
     return out
 
 
-def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False):
+def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=False, scale=1.0):
+    """One scheduling unit on the GPU.  in_place: stage_backward_accumulate instead of the pair
+    stage_backward + stage_accumulate_grads (then there is no staging snapshot S0)."""
     import torch
     import paper_2402_03791_amd as zpp
     st = zpp.Stage(shape)
@@ -61,10 +63,13 @@ def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False):
     dxs = []
     S0 = None
     for m, dy in enumerate(dys):
+        if in_place:
+            dxs.append(st.backward_accumulate(m, to_dev(dy, st.act_dtype), scale=scale))
+            continue
         dxs.append(st.backward(m, to_dev(dy, st.act_dtype)))
         if m == 0:
             S0 = to_np(st.region("S"))
-        st.accumulate_grads(m, 1.0)
+        st.accumulate_grads(m, scale)
     torch.cuda.synchronize()
     out = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs], G=to_np(st.G), S0=S0,
                W=to_np(st.region("W")))

@@ -32,6 +32,14 @@ def test_one_block_at_full_shape(name):
     assert np.array_equal(gpu["W"], ref["W"])
     worst = compare_units(sh, gpu, ref, layout, 2e-2)
     print("worst rel err", max(worst.values()), max(worst, key=worst.get), flush=True)
+    # accumulation in place (the path bench.py times), two micro-batches so that the second one really adds:
+    # bit-identical to backward followed by the accumulate pass
+    sh2 = sh.replace(unit_mbs=2)
+    xs2, dys2 = make_inputs(sh2, 2)
+    two = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5)
+    one = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True)
+    assert np.array_equal(two["G"].view(np.uint32), one["G"].view(np.uint32))
+    assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], one["dxs"]))
 
 
 def test_adam_over_the_whole_6p2b_shard():

@@ -154,6 +154,63 @@ def test_small_stage_units(arch, dtype, kw):
     print("worst rel err", max(worst.values()), flush=True)
 
 
+@pytest.mark.parametrize("arch,dtype,kw,scale", [
+    (0, 0, {}, 1.0), (1, 0, dict(micro_batch=2, seq=96), 0.37), (0, 1, {}, 1.0), (1, 1, {}, 0.37),
+    (0, 1, dict(micro_batch=2, seq=160, ffn=768, n_heads=4, unit_mbs=3), 0.37),
+    (1, 1, dict(micro_batch=2, seq=96, ffn=320), 1.0),
+])
+def test_backward_accumulate_equals_backward_then_accumulate(arch, dtype, kw, scale):
+    """The in-place path adds the same fp32 gradient with the same single fused multiply-add per element
+    and micro-batch, so G and dx must be bit-identical to the two-call sequence."""
+    sh = small(arch, dtype, **kw)
+    print(f"in-place unit {sh.name} {kw} scale {scale}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    two = run_gpu_unit(sh, P0, xs, dys, scale=scale)
+    one = run_gpu_unit(sh, P0, xs, dys, scale=scale, in_place=True)
+    for a, b in zip(two["dxs"], one["dxs"]):
+        assert np.array_equal(a, b)
+    bad = [name for name, off, r, c in layout
+           if not np.array_equal(two["G"][off:off + r * c].view(np.uint32), one["G"][off:off + r * c].view(np.uint32))]
+    assert not bad, bad
+    # and against the oracle (scaled sum of the micro-batch gradients)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    tol = TOL_BF16 if dtype == 1 else TOL_FP32
+    for name, off, r, c in layout:
+        assert rel_err(one["G"][off:off + r * c], scale * ref["G"][off:off + r * c]) <= tol, name
+
+
+def test_backward_accumulate_state_machine():
+    sh = small(0, 1)
+    st = zpp.Stage(sh)
+    st.P.copy_(torch.from_numpy(synth.make_params(sh, oracle.param_layout(sh))))
+    st.G.zero_()
+    st.materialize_params()
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    x, dy = to_dev(xs[0], st.act_dtype), to_dev(dys[0], st.act_dtype)
+    with pytest.raises(zpp.ZppError) as e:   # no forward yet
+        st.backward_accumulate(0, dy)
+    assert e.value.status == -2
+    st.forward(0, x)
+    st.forward(1, x)
+    st.backward(1, dy)
+    with pytest.raises(zpp.ZppError) as e:   # staging buffer still holds micro-batch 1
+        st.backward_accumulate(0, dy)
+    assert e.value.status == -2
+    st.accumulate_grads(1)
+    st.backward_accumulate(0, dy)
+    with pytest.raises(zpp.ZppError) as e:   # already accumulated
+        st.accumulate_grads(0)
+    assert e.value.status == -2
+    with pytest.raises(zpp.ZppError) as e:
+        st.backward_accumulate(0, dy)
+    assert e.value.status == -2
+    st.adam_step(step=1, **synth.ADAM)       # nothing pending
+    torch.cuda.synchronize()
+    st.close()
+
+
 def test_materialize_counters_and_idempotence():
     sh = small(0, 1)
     layout = oracle.param_layout(sh)
@@ -201,6 +258,11 @@ def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     zpp.op_gemm_bf16_nt(A, B, Cf, variant=variant)
     ref2 = oracle.Ops("f64").linear_fwd(a, b)
     assert rel_err(to_np(Cf), ref2) <= 1e-5      # fp32 accumulation of exact bf16 products
+    # accumulation in place: every element receives exactly one rounded add of the same fp32 product
+    g0 = torch.from_numpy(synth.normal_f32(1, 54, M * N).reshape(M, N)).cuda()
+    G = g0.clone()
+    zpp.op_gemm_bf16_nt(A, B, G, variant=variant, accumulate=True)
+    assert torch.equal(G, g0 + Cf)
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (128, 128, 128), (520, 304, 192), (8, 8, 64), (1024, 2048, 512),
