@@ -168,8 +168,10 @@ def main():
         kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
         return float(kv["gemm_hbm_bytes_per_launch"]) if kv.get("workload") == sh.name else None
 
-    n_gemm, ms_gemm, fl_gemm, by_gemm = prof["gemm"]
-    gemm_tflops = rate("gemm", 1e12)
+    # the GEMM family = forward and input-gradient products ("gemm") + weight-gradient products ("gemm_dw")
+    fam = [prof["gemm"], prof["gemm_dw"]]
+    n_gemm, ms_gemm, fl_gemm, by_gemm = (sum(c[i] for c in fam) for i in range(4))
+    gemm_tflops = fl_gemm / (ms_gemm * 1e-3) / 1e12 if ms_gemm > 0 else 0.0
     bf16 = sh.compute_dtype == 1
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     roofline = {
@@ -181,10 +183,16 @@ def main():
         "flops_per_launch": fl_gemm / max(n_gemm, 1),
         "algorithmic_bytes": by_gemm / max(n_gemm, 1),
         "traffic": measured_traffic(),
+        # the same family by kind: the weight-gradient products carry the gradient accumulation in their
+        # epilogue when the step accumulates in place (one extra fp32 read of their output)
+        "by_kind": {k: {"launches": prof[c][0], "ms": round(prof[c][1], 3), "TFLOP/s": round(rate(c, 1e12), 1),
+                        "frac": round(rate(c, 1e12) / peak, 4)}
+                    for k, c in (("forward_and_input_gradient", "gemm"), ("weight_gradient", "gemm_dw"))},
     }
-    fb_ms = sum(prof[c][1] for c in ("gemm", "attn_fwd", "attn_bwd", "other"))
+    fb_ms = sum(prof[c][1] for c in ("gemm", "gemm_dw", "attn_fwd", "attn_bwd", "other"))
     phases = {c: {"launches": prof[c][0], "ms": round(prof[c][1], 3)} for c in prof}
-    phases["gemm"]["TFLOP/s"] = round(gemm_tflops, 1)
+    phases["gemm"]["TFLOP/s"] = round(rate("gemm", 1e12), 1)
+    phases["gemm_dw"]["TFLOP/s"] = round(rate("gemm_dw", 1e12), 1)
     phases["attn_fwd"]["TFLOP/s"] = round(rate("attn_fwd", 1e12), 1)
     phases["attn_bwd"]["TFLOP/s"] = round(rate("attn_bwd", 1e12), 1)
     for c in ("accumulate", "adam", "materialize"):

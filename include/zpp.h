@@ -191,10 +191,13 @@ zpp_status zpp_stage_region(const zpp_stage *stage, const char *name, int32_t mi
  * GEMM and attention with the causal convention 2*b*s^2*h forward and twice that backward; bytes
  * for the flat passes: 12 per element accumulate, 28 (+4 with zero_grad) Adam, read+write bytes
  * materialise; 0 for the rest), and for GEMMs also the minimum HBM bytes (each operand read once, the
- * result written once). */
+ * result written once; a product accumulated in place also reads its result once). */
 enum {
     ZPP_PROF_GEMM = 0, ZPP_PROF_ATTN_FWD = 1, ZPP_PROF_ATTN_BWD = 2, ZPP_PROF_ACCUMULATE = 3,
-    ZPP_PROF_ADAM = 4, ZPP_PROF_MATERIALIZE = 5, ZPP_PROF_OTHER = 6, ZPP_PROF_CLASSES = 7
+    ZPP_PROF_ADAM = 4, ZPP_PROF_MATERIALIZE = 5, ZPP_PROF_OTHER = 6,
+    ZPP_PROF_GEMM_DW = 7, /* the weight-gradient products dY^T.X (fp32 output, written or accumulated in place);
+                             ZPP_PROF_GEMM holds the forward and input-gradient products */
+    ZPP_PROF_CLASSES = 8
 };
 zpp_status zpp_profile_enable(int32_t on);
 void zpp_profile_reset(void);

@@ -251,7 +251,7 @@ class Stage:
         return raw.view(dt)
 
 
-PROF_CLASSES = ["gemm", "attn_fwd", "attn_bwd", "accumulate", "adam", "materialize", "other"]
+PROF_CLASSES = ["gemm", "attn_fwd", "attn_bwd", "accumulate", "adam", "materialize", "other", "gemm_dw"]
 
 
 def profile_enable(on: bool):

@@ -69,6 +69,49 @@ __device__ __forceinline__ void epi_store_one(float v, int64_t o_idx, void *__re
     }
 }
 
+// fp32 output without an element-wise tail (weight gradients): a lane owns 4 consecutive columns of a
+// row, so that one store instruction of a wave writes whole rows of its 32-row slice (full 128-byte
+// lines).  This is the lane geometry of that path, and the fetch of the old values of C when the product
+// is accumulated in place (Section 3.1: G <- G + scale * dW).
+template <int NT>
+struct F32Rows {
+    static constexpr int WN = NT * 32, CH4 = WN / 4, ROWS4 = 64 / CH4, PASSES4 = 32 / ROWS4;
+    float *cf0;      // this lane's element of the wave tile's first pass
+    int64_t pstep;   // elements between passes
+    int64_t n4;      // first of the lane's 4 columns
+    int rows_left;   // tile rows g*32 + p*ROWS4 below this are inside C
+    int row4, c4;
+    bool ok, accum, col_full, col_any;
+
+    __device__ __forceinline__ void init(void *Cv, int64_t ldc, const EpiBf16 &epi, int64_t M, int64_t N,
+                                         int64_t m_wave, int64_t n_wave, int lane)
+    {
+        ok = epi.out_f32 && (ldc % 8 == 0) && (reinterpret_cast<uintptr_t>(Cv) % 16 == 0) && !epi.resid &&
+             epi.act == ACT_NONE;
+        accum = ok && epi.out_f32 == 2;
+        row4 = lane / CH4;
+        c4 = lane % CH4;
+        n4 = n_wave + c4 * 4;
+        cf0 = reinterpret_cast<float *>(Cv) + (m_wave + row4) * ldc + n4;
+        pstep = ROWS4 * ldc;
+        const int64_t rl = M - m_wave - row4;
+        rows_left = rl > 4096 ? 4096 : (int)rl;
+        col_full = n4 + 4 <= N;
+        col_any = n4 < N;
+    }
+    // old values of 32-row group G (zeros where the tile leaves C or the path is not taken)
+    template <int G>
+    __device__ __forceinline__ void fetch(f32x4 *dst) const
+    {
+#pragma unroll
+        for (int p = 0; p < PASSES4; ++p) {
+            dst[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (accum && G * 32 + p * ROWS4 < rows_left && col_full)
+                dst[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(cf0 + (G * (32 / ROWS4) + p) * pstep));
+        }
+    }
+};
+
 // Epilogue shared by the GEMM kernels.  The accumulator layout of the 32x32 MFMA gives a lane one
 // column and scattered rows, which would make every global store a 2-byte-per-lane scatter.  So each
 // wave transposes its tile through its own slice of LDS, 32 rows at a time (fp32, bias already
@@ -98,34 +141,15 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         const int64_t n = n_wave + j * 32 + c32;
         bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
     }
-    // fp32 output without an element-wise tail (weight gradients): a lane owns 4 consecutive columns,
-    // so that one store instruction writes whole rows of the wave's slice (full 128-byte lines).
-    constexpr int CH4 = WN / 4, ROWS4 = 64 / CH4, PASSES4 = 32 / ROWS4;
-    const bool f32_rows = epi.out_f32 && vec_ok && !epi.resid && epi.act == ACT_NONE;
-    const bool accum = f32_rows && epi.out_f32 == 2;
-    const int row4 = lane / CH4, c4 = lane % CH4;
-    const int64_t n4 = n_wave + c4 * 4;
-    // this lane's first element, the distance between passes, and how much of the tile is inside C
-    float *const cf0 = reinterpret_cast<float *>(Cv) + (m_wave + row4) * ldc + n4;
-    const int64_t pstep = ROWS4 * ldc;
-    const int64_t rl = M - m_wave - row4;
-    const int rows_left = rl > 4096 ? 4096 : (int)rl;  // rows i*32 + p*ROWS4 below this are inside
-    const bool col_full = n4 + 4 <= N, col_any = n4 < N;
-    // Accumulating in place (Section 3.1: G <- G + scale * dW): the old values of a 32-row group are
-    // fetched one group ahead, so their latency hides behind the previous group's transposition and
-    // stores; only the first group's fetch is exposed.
+    F32Rows<NT> fr;
+    fr.init(Cv, ldc, epi, M, N, m_wave, n_wave, lane);
+    constexpr int ROWS4 = F32Rows<NT>::ROWS4, PASSES4 = F32Rows<NT>::PASSES4;
+    const bool f32_rows = fr.ok, accum = fr.accum;
+    const int row4 = fr.row4, c4 = fr.c4;
+    // Accumulating in place: the old values of a 32-row group are fetched one group ahead, so their
+    // latency hides behind the previous group's transposition and stores.
     f32x4 old[2][PASSES4];
-    auto fetch_old = [&](auto ii, f32x4 (&dst)[PASSES4]) {
-        constexpr int i = decltype(ii)::value;
-#pragma unroll
-        for (int p = 0; p < PASSES4; ++p) {
-            dst[p] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if (i * 32 + p * ROWS4 < rows_left && col_full)
-                dst[p] = __builtin_nontemporal_load(
-                    reinterpret_cast<const f32x4 *>(cf0 + (i * (32 / ROWS4) + p) * pstep));
-        }
-    };
-    if (accum) fetch_old(std::integral_constant<int, 0>{}, old[0]);
+    fr.template fetch<0>(old[0]);
     // The loop over the passes is a real loop: unrolled, the element-wise tail (with its GeLU branches)
     // would be replicated MT * PASSES times and the epilogue would run at the speed of instruction
     // fetch.  The 32-row groups stay instantiated one by one, since accumulator registers can only be
@@ -133,7 +157,7 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
     static_for<MT>([&](auto ii) {
         constexpr int i = decltype(ii)::value;
         if constexpr (i + 1 < MT)
-            if (accum) fetch_old(std::integral_constant<int, i + 1>{}, old[(i + 1) & 1]);
+            if (accum) fr.template fetch<i + 1>(old[(i + 1) & 1]);
         static_for<NT>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
 #pragma unroll
@@ -148,15 +172,15 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
             for (int p = 0; p < PASSES4; ++p) {
                 const int row = p * ROWS4 + row4;
                 const f32x4 val = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c4 * 4);
-                if (i * 32 + p * ROWS4 >= rows_left || !col_any) continue;
-                float *cf = cf0 + (i * (32 / ROWS4) + p) * pstep;
-                if (col_full) {
+                if (i * 32 + p * ROWS4 >= fr.rows_left || !fr.col_any) continue;
+                float *cf = fr.cf0 + (i * (32 / ROWS4) + p) * fr.pstep;
+                if (fr.col_full) {
                     f32x4 g = old[i & 1][p];
 #pragma unroll
                     for (int k = 0; k < 4; ++k) g[k] = grad_accum(g[k], epi.accum_scale, val[k]);
                     __builtin_nontemporal_store(g, reinterpret_cast<f32x4 *>(cf));
                 } else {
-                    for (int k = 0; k < 4 && n4 + k < N; ++k)
+                    for (int k = 0; k < 4 && fr.n4 + k < N; ++k)
                         cf[k] = grad_accum(cf[k], epi.accum_scale, stage[row * STRIDE + c4 * 4 + k]);
                 }
             }
@@ -165,13 +189,13 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
             for (int p = 0; p < PASSES4; ++p) {
                 const int row = p * ROWS4 + row4;
                 const f32x4 val = *reinterpret_cast<const f32x4 *>(stage + row * STRIDE + c4 * 4);
-                if (i * 32 + p * ROWS4 >= rows_left || !col_any) continue;
-                float *cf = cf0 + (i * (32 / ROWS4) + p) * pstep;
-                if (col_full) {
+                if (i * 32 + p * ROWS4 >= fr.rows_left || !fr.col_any) continue;
+                float *cf = fr.cf0 + (i * (32 / ROWS4) + p) * fr.pstep;
+                if (fr.col_full) {
                     // next read by the accumulate pass, long after: streamed past the caches
                     __builtin_nontemporal_store(val, reinterpret_cast<f32x4 *>(cf));
                 } else {
-                    for (int k = 0; k < 4 && n4 + k < N; ++k) cf[k] = stage[row * STRIDE + c4 * 4 + k];
+                    for (int k = 0; k < 4 && fr.n4 + k < N; ++k) cf[k] = stage[row * STRIDE + c4 * 4 + k];
                 }
             }
         } else

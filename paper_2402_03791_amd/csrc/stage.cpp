@@ -350,12 +350,12 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
                 }
             }
         }
-        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+        ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * s->T * in * out, st,
                        2.0 * ((double)s->T * in + (double)s->T * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out);
         e = launch_gemm_bf16_nt(out, in, s->T, tA, s->T, tB, s->T, s->Sp(blk, w), in, epi, st);
         return e;
     } else {
-        ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->T * in * out, st,
+        ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * s->T * in * out, st,
                        4.0 * ((double)s->T * in + (double)s->T * out + (double)in * out));
         e = launch_gemm_f32(out, in, s->T, (const float *)dy, 1, out, (const float *)x, 1, in, s->Sp(blk, w),
                             in, epi, st);
