@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--accumulate", choices=("in_place", "separate"), default="in_place",
                     help="in_place: stage_backward_accumulate (dW products add into G from their epilogues); "
                          "separate: stage_backward into the staging buffer, then stage_accumulate_grads")
+    ap.add_argument("--backward", choices=("fused", "split"), default="fused",
+                    help="fused: one backward call per micro-batch; split: the input-gradient tasks of all "
+                         "micro-batches of the unit first, then their weight-gradient tasks (same results bit for bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -83,7 +86,7 @@ def main():
     sh = synth.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    st = zpp.Stage(sh, device="cuda:0")
+    st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split")
     act = st.act_dtype
 
     # ---- synthetic inputs, resident in HBM before anything is timed
@@ -101,7 +104,14 @@ def main():
         st.materialize_params(stream)
         for m in range(sh.unit_mbs):
             st.forward(m, xs[m], y, stream)
-        for m in range(sh.unit_mbs):
+        if args.backward == "split":
+            for m in range(sh.unit_mbs):
+                st.backward_input(m, dys[m], dx, stream)
+            for m in range(sh.unit_mbs):
+                st.backward_weight(m, args.accumulate == "in_place", 1.0, stream)
+                if args.accumulate != "in_place":
+                    st.accumulate_grads(m, 1.0, stream)
+        for m in range(sh.unit_mbs if args.backward == "fused" else 0):
             if args.accumulate == "in_place":
                 st.backward_accumulate(m, dys[m], dx, 1.0, stream)
             else:
@@ -218,7 +228,7 @@ def main():
         "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
-                   "accumulate": args.accumulate},
+                   "accumulate": args.accumulate, "backward": args.backward},
         "model_flops_per_step": flops,
         "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),
         "fwd_bwd_TFLOPs": round(flops / (fb_ms * 1e-3) / 1e12, 2) if fb_ms > 0 else None,

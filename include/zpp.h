@@ -73,6 +73,9 @@ typedef struct {
     int32_t gelu_mode;     /* ZPP_GELU_TANH (default) or ZPP_GELU_ERF */
     float norm_eps;        /* epsilon inside the norm's square root */
     float rope_base;       /* rotary base (LLaMA only); angle = position * base^(-2i/d), adjacent pairs */
+    int32_t split_backward; /* 1: the workspace also holds, per (micro-batch, block), what the weight-gradient
+                              task needs from the input-gradient task (each linear layer's dY), so that
+                              stage_backward_input / stage_backward_weight may be used; 0: only the fused calls */
 } zpp_stage_config;
 
 typedef struct {
@@ -96,7 +99,8 @@ uint64_t zpp_stage_param_count(const zpp_stage *stage);
 /* Bytes of caller-owned device workspace the stage needs: the materialised working copy of the
  * stage (one gathered stage, the L*M_w/(P*V) term of the memory formula in Section 4.2), the
  * fp32 staging buffer for one micro-batch's weight gradients, the activation stash of one
- * scheduling unit (the min(B,U)*L*M_a/P term; linear in unit_mbs) and per-call temporaries. */
+ * scheduling unit (the min(B,U)*L*M_a/P term; linear in unit_mbs; with split_backward it also
+ * holds the output gradients kept between the two backward tasks) and per-call temporaries. */
 uint64_t zpp_stage_workspace_bytes(const zpp_stage *stage);
 
 /* Number of tensors in the flat layout, and the idx-th entry.  `name` points into the handle and
@@ -120,7 +124,9 @@ zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float 
  *        -> stage_backward(mb) only after stage_forward(mb), once
  *        -> stage_accumulate_grads(mb) only after stage_backward(mb), once; because the staging
  *           buffer is reused, stage_backward of another micro-batch before that is ZPP_ERR_STATE
- *           (stage_backward_accumulate(mb) stands for the pair backward + accumulate of one micro-batch)
+ *           (stage_backward_accumulate(mb) stands for the pair backward + accumulate of one micro-batch;
+ *           stage_backward_input(mb) then stage_backward_weight(mb) stand for stage_backward(mb) or,
+ *           with in_place, for stage_backward_accumulate(mb))
  *        -> shard_adam_step only when no micro-batch is backward-done but not accumulated
  *        -> zpp_stage_end_unit, after which the next unit starts with forward (the working copy
  *           stays valid until P changes; after shard_adam_step without write-back a new
@@ -158,6 +164,26 @@ zpp_status stage_accumulate_grads(zpp_stage *stage, int32_t micro_batch, float s
  * afterwards the micro-batch counts as accumulated. */
 zpp_status stage_backward_accumulate(zpp_stage *stage, int32_t micro_batch, const void *dy, void *dx,
                                      float scale, void *hip_stream);
+
+/* The backward of a micro-batch as the two separate tasks of Section 3.1.1 (the split of Section 2.3:
+ * "input gradient computation" dX = dY.W and "weight gradient computation" dW = dY^T.X), so that a
+ * scheduler can run the weight-gradient task later, e.g. where the pipeline would otherwise idle.
+ * Needs a stage created with split_backward = 1 (ZPP_ERR_STATE otherwise).
+ *   stage_backward_input(mb): after stage_forward(mb), once.  Computes dx exactly as stage_backward
+ *     and keeps each linear layer's dY (and the partial sums of the norm-gain reductions, which fall out of
+ *     the pass that computes dx) in the unit's stash; dy is copied, so the caller may reuse it at once.
+ *     Does not touch the staging buffer or G; input-gradient tasks of other micro-batches may follow
+ *     before this one's weight-gradient task.
+ *   stage_backward_weight(mb, in_place, scale): after stage_backward_input(mb), once.  Computes the
+ *     weight, bias and gain gradients of the micro-batch from the stash.  in_place == 0: into the
+ *     staging buffer, to be followed by stage_accumulate_grads(mb) like stage_backward (scale is
+ *     ignored); in_place != 0: added into G as scale * g_mb like stage_backward_accumulate.
+ * The two tasks launch the same kernels on the same operands as the fused calls: dx and the gradients
+ * are bit-identical to theirs.  shard_adam_step and zpp_stage_end_unit refuse to run while a
+ * micro-batch has its input gradient but not its weight gradient. */
+zpp_status stage_backward_input(zpp_stage *stage, int32_t micro_batch, const void *dy, void *dx, void *hip_stream);
+zpp_status stage_backward_weight(zpp_stage *stage, int32_t micro_batch, int32_t in_place, float scale,
+                                 void *hip_stream);
 
 /* The optimizer-step task (Section 3.1.1; Section 3.2.2 "update the parameters corresponding to the
  * partitioned optimizer states"): Adam on elements [offset, offset+count) of P, M, V using G.

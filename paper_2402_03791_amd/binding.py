@@ -13,7 +13,8 @@ _lib = None
 EXPORTS = [
     "zpp_stage_create", "zpp_stage_destroy", "zpp_stage_param_count", "zpp_stage_workspace_bytes",
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
-    "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
+    "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight",
+    "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
@@ -30,7 +31,7 @@ class ZppError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch",
                                               "unit_mbs", "compute_dtype", "gelu_mode")] + \
-               [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float)]
+               [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("split_backward", ctypes.c_int32)]
 
 
 class _Adam(ctypes.Structure):
@@ -68,6 +69,8 @@ def load_library(path: str | None = None):
     L.stage_forward.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward_accumulate.argtypes = [vp, i32, vp, vp, f32, vp]
+    L.stage_backward_input.argtypes = [vp, i32, vp, vp, vp]
+    L.stage_backward_weight.argtypes = [vp, i32, i32, f32, vp]
     L.stage_accumulate_grads.argtypes = [vp, i32, f32, vp]
     L.shard_adam_step.argtypes = [vp, u64, u64, ctypes.POINTER(_Adam), vp]
     L.zpp_stage_end_unit.argtypes = [vp]
@@ -116,16 +119,18 @@ class StageConfig:
     gelu_mode: int = 0
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
+    split_backward: int = 0
 
     @classmethod
-    def from_shape(cls, shape) -> "StageConfig":
+    def from_shape(cls, shape, split_backward: int = 0) -> "StageConfig":
         g = (lambda k: shape[k]) if isinstance(shape, dict) else (lambda k: getattr(shape, k))
         return cls(*(g(k) for k in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch", "unit_mbs",
-                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")))
+                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")), split_backward)
 
     def _c(self) -> _Config:
         return _Config(self.arch, self.n_blocks, self.hidden, self.n_heads, self.ffn, self.seq, self.micro_batch,
-                       self.unit_mbs, self.compute_dtype, self.gelu_mode, self.norm_eps, self.rope_base)
+                       self.unit_mbs, self.compute_dtype, self.gelu_mode, self.norm_eps, self.rope_base,
+                       self.split_backward)
 
 
 def _adam_struct(lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1, zero_grad=0) -> _Adam:
@@ -143,8 +148,8 @@ class Stage:
     """A stage handle.  With ``allocate=True`` it also owns torch tensors for P, G, M, V and the
     workspace and binds them; otherwise call :meth:`bind` with your own tensors."""
 
-    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True):
-        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg)
+    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: bool = False):
+        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward))
         self._h = ctypes.c_void_p()
         c = self.cfg._c()
         _check(lib().zpp_stage_create(ctypes.byref(c), ctypes.byref(self._h)))
@@ -223,6 +228,16 @@ class Stage:
         _check(lib().stage_backward_accumulate(self._h, mb, dy.data_ptr(), dx.data_ptr(), scale,
                                                _stream_ptr(stream)))
         return dx
+
+    def backward_input(self, mb: int, dy, dx=None, stream=None):
+        import torch
+        if dx is None:
+            dx = torch.empty_like(dy)
+        _check(lib().stage_backward_input(self._h, mb, dy.data_ptr(), dx.data_ptr(), _stream_ptr(stream)))
+        return dx
+
+    def backward_weight(self, mb: int, in_place: bool = False, scale: float = 1.0, stream=None):
+        _check(lib().stage_backward_weight(self._h, mb, int(in_place), scale, _stream_ptr(stream)))
 
     def accumulate_grads(self, mb: int, scale: float = 1.0, stream=None):
         _check(lib().stage_accumulate_grads(self._h, mb, scale, _stream_ptr(stream)))

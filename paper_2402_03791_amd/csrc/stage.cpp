@@ -52,7 +52,7 @@ struct Region {
     int esz = 0;
 };
 
-enum MbState { MB_IDLE = 0, MB_FWD = 1, MB_BWD = 2, MB_ACC = 3 };
+enum MbState { MB_IDLE = 0, MB_FWD = 1, MB_BWD = 2, MB_ACC = 3, MB_BIN = 4 /* input gradient done, weight gradient due */ };
 
 // ---- optional per-kernel-class timing with HIP events on the caller's stream -------------------
 struct ProfRec {
@@ -126,6 +126,9 @@ struct zpp_stage {
     // first level writes its partial rows into its own slot of the "redpool" scratch and is listed here;
     // one launch at the end of the call finishes them all.
     std::vector<FinishItem> finish;
+    // per micro-batch: the norm-gain reductions its input-gradient task started (two per block, top block
+    // first), finished by its weight-gradient task
+    std::vector<std::vector<FinishItem>> norm_items;
     uint64_t red_floats = 0;  // floats per slot
     float *red_slot() const { return (float *)(ws + tmp.at("redpool").off) + finish.size() * red_floats; }
     FinishItem *defer()
@@ -252,6 +255,16 @@ void plan_workspace(zpp_stage *s)
         sc("n2", T * h, e);
         sc("u", T * f1, e);
         sc("g", T * f, e);
+        if (s->c.split_backward) {
+            // what the weight-gradient task of a micro-batch needs from its input-gradient task: the dY of
+            // the four linear layers and the first-level partial sums of the two norm-gain reductions
+            sc("d_y", T * h, e);
+            sc("d_u", T * f1, e);
+            sc("d_x1", T * h, e);
+            sc("d_qkv", T * 3 * h, e);
+            sc("red_n2", colreduce_scratch_floats((int64_t)T, (int64_t)h), 4);
+            sc("red_n1", colreduce_scratch_floats((int64_t)T, (int64_t)h), 4);
+        }
         s->stash_block_bytes = rel;
         s->stash_base = cur;
         cur = align_up(cur + (uint64_t)s->U * s->L * rel);
@@ -453,6 +466,7 @@ zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out)
     build_layout(s);
     plan_workspace(s);
     s->mb_state.assign(s->U, MB_IDLE);
+    s->norm_items.assign(s->U, {});
     *out = s;
     return ZPP_OK;
 }
@@ -496,6 +510,7 @@ zpp_status zpp_stage_bind(zpp_stage *s, float *P, float *G, float *M, float *V, 
     s->rope_ready = false;
     s->pending_acc = -1;
     s->mb_state.assign(s->U, MB_IDLE);
+    s->norm_items.assign(s->U, {});
     return ZPP_OK;
 }
 
@@ -586,19 +601,35 @@ zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void 
 
 namespace {
 
-// The backward sequence of one micro-batch; with in_place the gradients are added into G (scaled) as they
-// are produced, otherwise they are written to the staging buffer.
-zpp_status backward_sequence(zpp_stage *s, int32_t mb, const void *dy, void *dx, bool in_place, float scale,
-                             void *hip_stream)
+// The backward sequence of one micro-batch, whole or one of its two tasks (Section 2.3, Section 3.1.1):
+//   BWD_INPUT  the input-gradient task: dX through every layer; with BWD_WEIGHT absent, each linear
+//              layer's dY and the partial sums of the norm-gain reductions are parked in the stash;
+//   BWD_WEIGHT the weight-gradient task: dW = dY^T . X, bias and gain gradients; with BWD_INPUT absent
+//              it reads what the input-gradient task parked.
+// With in_place the gradients are added into G (scaled) as they are produced, otherwise they are written
+// to the staging buffer.  Both orders of evaluation launch the same kernels on the same operands, so the
+// split tasks reproduce the fused call bit for bit.
+enum { BWD_INPUT = 1, BWD_WEIGHT = 2 };
+
+zpp_status backward_sequence(zpp_stage *s, int32_t mb, int tasks, const void *dy, void *dx, bool in_place,
+                             float scale, void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
     if (mb < 0 || mb >= s->U) return fail(ZPP_ERR_ARG, "micro_batch %d outside [0,%d)", mb, (int)s->U);
-    if (!dy || !dx) return fail(ZPP_ERR_ARG, "dy/dx is NULL");
-    if (!aligned(dy) || !aligned(dx)) return fail(ZPP_ERR_ALIGN, "dy and dx must be 256-byte aligned");
+    const bool do_in = tasks & BWD_INPUT, do_w = tasks & BWD_WEIGHT, split = !(do_in && do_w);
+    if (split && !s->c.split_backward)
+        return fail(ZPP_ERR_STATE, "the stage was created without split_backward (no stash room for dY)");
+    if (do_in) {
+        if (!dy || !dx) return fail(ZPP_ERR_ARG, "dy/dx is NULL");
+        if (!aligned(dy) || !aligned(dx)) return fail(ZPP_ERR_ALIGN, "dy and dx must be 256-byte aligned");
+    }
     if (!s->materialized) return fail(ZPP_ERR_STATE, "working copy is stale: call stage_materialize_params");
-    if (s->mb_state[mb] != MB_FWD)
-        return fail(ZPP_ERR_STATE, "stage_backward(%d) needs exactly one stage_forward(%d) before it", mb, mb);
-    if (s->pending_acc >= 0)
+    if (do_in && s->mb_state[mb] != MB_FWD)
+        return fail(ZPP_ERR_STATE, "backward of micro-batch %d needs exactly one stage_forward(%d) before it", mb, mb);
+    if (!do_in && s->mb_state[mb] != MB_BIN)
+        return fail(ZPP_ERR_STATE, "stage_backward_weight(%d) needs exactly one stage_backward_input(%d) before it",
+                    mb, mb);
+    if (do_w && !in_place && s->pending_acc >= 0)
         return fail(ZPP_ERR_STATE, "staging buffer still holds micro-batch %d: call stage_accumulate_grads first",
                     s->pending_acc);
     hipStream_t st = (hipStream_t)hip_stream;
@@ -606,66 +637,106 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, const void *dy, void *dx,
     const int kind = gpt ? NORM_LAYER : NORM_RMS;
     const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
     void *gbuf[2] = {s->tp("gA"), s->tp("gB")};
-    void *dn = s->tp("dn"), *dx1 = s->tp("dx1"), *dattn = s->tp("dattn"), *dqkv = s->tp("dqkv"), *du = s->tp("du");
+    void *dn = s->tp("dn"), *dattn = s->tp("dattn");
     s->finish.clear();
     s->acc_in_place = in_place;
     s->acc_scale = scale;
+    if (do_in && split) {
+        s->norm_items[mb].clear();
+        // the weight-gradient task of the top block needs the caller's dy after this call has returned
+        ZPP_OTHER(hipMemcpyAsync(s->stash(mb, (int)s->L - 1, "d_y"), dy, (size_t)(T * h) * s->esz,
+                                 hipMemcpyDeviceToDevice, st));
+    }
     const void *dcur = dy;
     for (int blk = (int)s->L - 1; blk >= 0; --blk) {
-        void *dout = blk == 0 ? dx : gbuf[blk & 1];
+        // gradient buffers: temporaries in the fused call, stash slots when the tasks are split
+        void *dout = blk == 0 ? dx : (split ? s->stash(mb, blk - 1, "d_y") : gbuf[blk & 1]);
+        void *dx1 = split ? s->stash(mb, blk, "d_x1") : s->tp("dx1");
+        void *dqkv = split ? s->stash(mb, blk, "d_qkv") : s->tp("dqkv");
+        void *du = split ? s->stash(mb, blk, "d_u") : s->tp("du");
+        if (split) dcur = s->stash(mb, blk, "d_y");
         const void *xs = s->stash(mb, blk, "x"), *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv");
         const void *attn = s->stash(mb, blk, "attn"), *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2");
         const void *u = s->stash(mb, blk, "u"), *g = s->stash(mb, blk, "g");
         const float *mean1 = (const float *)s->stash(mb, blk, "mean1"), *rstd1 = (const float *)s->stash(mb, blk, "rstd1");
         const float *mean2 = (const float *)s->stash(mb, blk, "mean2"), *rstd2 = (const float *)s->stash(mb, blk, "rstd2");
         const float *lse = (const float *)s->stash(mb, blk, "lse");
+        const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
+        // Norm backward: dx together with the first level of the gain-gradient reduction.  The fused call
+        // finishes the reduction at its end; a lone input-gradient task parks the partial sums instead.
+        auto norm_bwd = [&](const char *gname, const char *bname, const char *red, const void *x, const float *mean,
+                            const float *rstd, const void *resid, void *out) -> zpp_status {
+            float *slot = split ? (float *)s->stash(mb, blk, red) : s->red_slot();
+            FinishItem *item = s->defer();
+            ZPP_OTHER(launch_norm_bwd_colreduce(s->dt, kind, dn, x, mean, rstd, s->Wp(blk, gname), resid, out, T, h,
+                                                s->Sp(blk, gname), gpt ? s->Sp(blk, bname) : nullptr, slot, item, st));
+            if (split) {
+                s->norm_items[mb].push_back(*item);
+                s->finish.pop_back();
+            }
+            return ZPP_OK;
+        };
+        // a parked item of this block, with its destinations set for this call (staging buffer or G)
+        auto parked = [&](int which, const char *gname, const char *bname) {
+            FinishItem it = s->norm_items[mb][(size_t)((int)s->L - 1 - blk) * 2 + which];
+            it.out0 = s->Sp(blk, gname);
+            it.out1 = gpt ? s->Sp(blk, bname) : nullptr;
+            *s->defer() = it;
+        };
         // ---- MLP branch
         if (gpt) {
-            ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.w2", "mlp.b2", f, h, st));
-            GemmEpi e;
-            e.act = ACT_DGELU_MUL;
-            e.aux = u;
-            e.gelu_mode = s->c.gelu_mode;
-            ZPP_TRY(linear_dx(s, dcur, blk, "mlp.w2", f, h, du, e, st));
-            ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.w1", "mlp.b1", h, f, st));
-            ZPP_TRY(linear_dx(s, du, blk, "mlp.w1", h, f, dn, GemmEpi(), st));
+            if (do_w) ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.w2", "mlp.b2", f, h, st));
+            if (do_in) {
+                GemmEpi e;
+                e.act = ACT_DGELU_MUL;
+                e.aux = u;
+                e.gelu_mode = s->c.gelu_mode;
+                ZPP_TRY(linear_dx(s, dcur, blk, "mlp.w2", f, h, du, e, st));
+            }
+            if (do_w) ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.w1", "mlp.b1", h, f, st));
+            if (do_in) ZPP_TRY(linear_dx(s, du, blk, "mlp.w1", h, f, dn, GemmEpi(), st));
         } else {
-            void *dact = s->tp("dact");
-            ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.wdown", nullptr, f, h, st));
-            ZPP_TRY(linear_dx(s, dcur, blk, "mlp.wdown", f, h, dact, GemmEpi(), st));
-            ZPP_OTHER(launch_swiglu_bwd(s->dt, u, dact, du, T, f, st));
-            ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.wgate", nullptr, h, f1, st));
-            ZPP_TRY(linear_dx(s, du, blk, "mlp.wgate", h, f1, dn, GemmEpi(), st));
+            if (do_w) ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.wdown", nullptr, f, h, st));
+            if (do_in) {
+                void *dact = s->tp("dact");
+                ZPP_TRY(linear_dx(s, dcur, blk, "mlp.wdown", f, h, dact, GemmEpi(), st));
+                ZPP_OTHER(launch_swiglu_bwd(s->dt, u, dact, du, T, f, st));
+            }
+            if (do_w) ZPP_TRY(linear_dw(s, du, n2, blk, "mlp.wgate", nullptr, h, f1, st));
+            if (do_in) ZPP_TRY(linear_dx(s, du, blk, "mlp.wgate", h, f1, dn, GemmEpi(), st));
         }
-        const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
-        {
-            float *slot = s->red_slot();
-            ZPP_OTHER(launch_norm_bwd_colreduce(s->dt, kind, dn, x1, mean2, rstd2, s->Wp(blk, g2), dcur, dx1, T, h,
-                                                s->Sp(blk, g2), gpt ? s->Sp(blk, "ln2.beta") : nullptr, slot,
-                                                s->defer(), st));
+        if (do_in) {
+            if (zpp_status e = norm_bwd(g2, "ln2.beta", "red_n2", x1, mean2, rstd2, dcur, dx1)) return e;
+        } else {
+            parked(0, g2, "ln2.beta");
         }
         // ---- attention branch
-        ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
-        ZPP_TRY(linear_dx(s, dx1, blk, "attn.wo", h, h, dattn, GemmEpi(), st));
-        ZPP_TRY(attention_bwd(s, qkv, attn, dattn, lse, dqkv, st));
-        if (!gpt)
-            ZPP_OTHER(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
-        ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
-        ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
-        {
-            float *slot = s->red_slot();
-            ZPP_OTHER(launch_norm_bwd_colreduce(s->dt, kind, dn, xs, mean1, rstd1, s->Wp(blk, g1), dx1, dout, T, h,
-                                                s->Sp(blk, g1), gpt ? s->Sp(blk, "ln1.beta") : nullptr, slot,
-                                                s->defer(), st));
+        if (do_w) ZPP_TRY(linear_dw(s, dx1, attn, blk, "attn.wo", gpt ? "attn.bo" : nullptr, h, h, st));
+        if (do_in) {
+            ZPP_TRY(linear_dx(s, dx1, blk, "attn.wo", h, h, dattn, GemmEpi(), st));
+            ZPP_TRY(attention_bwd(s, qkv, attn, dattn, lse, dqkv, st));
+            if (!gpt)
+                ZPP_OTHER(launch_rope(s->dt, dqkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, -1, st));
+        }
+        if (do_w) ZPP_TRY(linear_dw(s, dqkv, n1, blk, "attn.wqkv", gpt ? "attn.bqkv" : nullptr, h, 3 * h, st));
+        if (do_in) {
+            ZPP_TRY(linear_dx(s, dqkv, blk, "attn.wqkv", h, 3 * h, dn, GemmEpi(), st));
+            if (zpp_status e = norm_bwd(g1, "ln1.beta", "red_n1", xs, mean1, rstd1, dx1, dout)) return e;
+        } else {
+            parked(1, g1, "ln1.beta");
         }
         dcur = dout;
     }
     // second level of every column reduction of this call, in one launch
-    ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st, in_place, scale));
+    if (do_w) ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st, in_place, scale));
     s->finish.clear();
     s->acc_in_place = false;
-    s->mb_state[mb] = in_place ? MB_ACC : MB_BWD;
-    s->pending_acc = in_place ? -1 : mb;
+    if (do_w) {
+        s->mb_state[mb] = in_place ? MB_ACC : MB_BWD;
+        if (!in_place) s->pending_acc = mb;  // in place leaves the staging buffer (and who holds it) alone
+    } else {
+        s->mb_state[mb] = MB_BIN;
+    }
     return ZPP_OK;
 }
 
@@ -673,13 +744,23 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, const void *dy, void *dx,
 
 zpp_status stage_backward(zpp_stage *s, int32_t mb, const void *dy, void *dx, void *hip_stream)
 {
-    return backward_sequence(s, mb, dy, dx, false, 1.0f, hip_stream);
+    return backward_sequence(s, mb, BWD_INPUT | BWD_WEIGHT, dy, dx, false, 1.0f, hip_stream);
 }
 
 zpp_status stage_backward_accumulate(zpp_stage *s, int32_t mb, const void *dy, void *dx, float scale,
                                      void *hip_stream)
 {
-    return backward_sequence(s, mb, dy, dx, true, scale, hip_stream);
+    return backward_sequence(s, mb, BWD_INPUT | BWD_WEIGHT, dy, dx, true, scale, hip_stream);
+}
+
+zpp_status stage_backward_input(zpp_stage *s, int32_t mb, const void *dy, void *dx, void *hip_stream)
+{
+    return backward_sequence(s, mb, BWD_INPUT, dy, dx, false, 1.0f, hip_stream);
+}
+
+zpp_status stage_backward_weight(zpp_stage *s, int32_t mb, int32_t in_place, float scale, void *hip_stream)
+{
+    return backward_sequence(s, mb, BWD_WEIGHT, nullptr, nullptr, in_place != 0, scale, hip_stream);
 }
 
 zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *hip_stream)
@@ -711,6 +792,9 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
         return fail(ZPP_ERR_ARG, "betas must lie in [0,1)");
     if (s->pending_acc >= 0)
         return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
+    for (int64_t m = 0; m < s->U; ++m)
+        if (s->mb_state[m] == MB_BIN)
+            return fail(ZPP_ERR_STATE, "micro-batch %d has its input gradient but not its weight gradient", (int)m);
     AdamArgs a;
     a.lr = hp->lr;
     a.beta1 = hp->beta1;
@@ -738,7 +822,11 @@ zpp_status zpp_stage_end_unit(zpp_stage *s)
     if (zpp_status e = check_stage(s, true)) return e;
     if (s->pending_acc >= 0)
         return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
+    for (int64_t m = 0; m < s->U; ++m)
+        if (s->mb_state[m] == MB_BIN)
+            return fail(ZPP_ERR_STATE, "micro-batch %d has its input gradient but not its weight gradient", (int)m);
     s->mb_state.assign(s->U, MB_IDLE);
+    s->norm_items.assign(s->U, {});
     return ZPP_OK;
 }
 

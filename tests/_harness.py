@@ -50,19 +50,35 @@ def run_oracle_unit(shape, P0: np.ndarray, xs, dys, dtype="f64", keep_stage=Fals
     return out
 
 
-def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=False, scale=1.0):
+def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=False, scale=1.0, split=None):
     """One scheduling unit on the GPU.  in_place: stage_backward_accumulate instead of the pair
-    stage_backward + stage_accumulate_grads (then there is no staging snapshot S0)."""
+    stage_backward + stage_accumulate_grads (then there is no staging snapshot S0).
+    split: None, or the order in which the weight-gradient tasks run after ALL input-gradient tasks
+    ("ascending", "descending"), or "interleaved" (each weight-gradient task right after its own
+    input-gradient task)."""
     import torch
     import paper_2402_03791_amd as zpp
-    st = zpp.Stage(shape)
+    st = zpp.Stage(shape, split_backward=split is not None)
     st.P.copy_(torch.from_numpy(P0))
     st.G.zero_()
     st.materialize_params()
     ys = [st.forward(m, to_dev(x, st.act_dtype)) for m, x in enumerate(xs)]
     dxs = []
     S0 = None
+    def weight_task(m):
+        nonlocal S0
+        st.backward_weight(m, in_place=in_place, scale=scale)
+        if not in_place:
+            if m == 0:
+                S0 = to_np(st.region("S"))
+            st.accumulate_grads(m, scale)
+
     for m, dy in enumerate(dys):
+        if split is not None:
+            dxs.append(st.backward_input(m, to_dev(dy, st.act_dtype)))
+            if split == "interleaved":
+                weight_task(m)
+            continue
         if in_place:
             dxs.append(st.backward_accumulate(m, to_dev(dy, st.act_dtype), scale=scale))
             continue
@@ -70,6 +86,10 @@ def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=Fals
         if m == 0:
             S0 = to_np(st.region("S"))
         st.accumulate_grads(m, scale)
+    if split in ("ascending", "descending"):
+        order = range(len(dys)) if split == "ascending" else reversed(range(len(dys)))
+        for m in order:
+            weight_task(m)
     torch.cuda.synchronize()
     out = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs], G=to_np(st.G), S0=S0,
                W=to_np(st.region("W")))

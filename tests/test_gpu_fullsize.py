@@ -40,6 +40,10 @@ def test_one_block_at_full_shape(name):
     one = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True)
     assert np.array_equal(two["G"].view(np.uint32), one["G"].view(np.uint32))
     assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], one["dxs"]))
+    # input-gradient tasks of both micro-batches first, weight-gradient tasks afterwards: same bits again
+    split = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, split="ascending")
+    assert np.array_equal(two["G"].view(np.uint32), split["G"].view(np.uint32))
+    assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], split["dxs"]))
 
 
 def test_adam_over_the_whole_6p2b_shard():

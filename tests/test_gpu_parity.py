@@ -181,6 +181,84 @@ def test_backward_accumulate_equals_backward_then_accumulate(arch, dtype, kw, sc
         assert rel_err(one["G"][off:off + r * c], scale * ref["G"][off:off + r * c]) <= tol, name
 
 
+@pytest.mark.parametrize("arch,dtype,kw", [
+    (0, 0, dict(unit_mbs=3)), (1, 0, dict(micro_batch=2, seq=96, unit_mbs=3)),
+    (0, 1, dict(unit_mbs=3)), (1, 1, dict(unit_mbs=3)),
+    (0, 1, dict(micro_batch=2, seq=160, ffn=768, n_heads=4, n_blocks=3, unit_mbs=3)),
+])
+def test_split_backward_tasks_equal_the_fused_call(arch, dtype, kw):
+    """Input-gradient and weight-gradient tasks (Section 2.3) run apart from each other - all input-gradient
+    tasks of the unit first, weight-gradient tasks later - must reproduce the fused backward bit for bit:
+    same kernels, same operands."""
+    sh = small(arch, dtype, **kw)
+    print(f"split unit {sh.name} {kw}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+
+    def same(a, b, what):
+        for x, y in zip(a["dxs"], b["dxs"]):
+            assert np.array_equal(x, y), what + " dx"
+        bad = [n for n, off, r, c in layout
+               if not np.array_equal(a["G"][off:off + r * c].view(np.uint32), b["G"][off:off + r * c].view(np.uint32))]
+        assert not bad, (what, bad)
+
+    fused = run_gpu_unit(sh, P0, xs, dys, scale=0.37)
+    # staging path: weight-gradient tasks in ascending order, each followed by the accumulate pass
+    asc = run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="ascending")
+    same(fused, asc, "ascending/staging")
+    assert np.array_equal(fused["S0"].view(np.uint32), asc["S0"].view(np.uint32))
+    # in-place path, deferred and interleaved
+    same(fused, run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="ascending", in_place=True), "ascending/in place")
+    same(fused, run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="interleaved", in_place=True), "interleaved")
+    # another order of the weight-gradient tasks changes G by summation order only
+    desc = run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="descending", in_place=True)
+    for x, y in zip(fused["dxs"], desc["dxs"]):
+        assert np.array_equal(x, y)
+    for n, off, r, c in layout:
+        assert rel_err(desc["G"][off:off + r * c], fused["G"][off:off + r * c]) <= 1e-5, n
+
+
+def test_split_backward_state_machine():
+    sh = small(0, 1)
+    st = zpp.Stage(sh, split_backward=True)
+    st.P.copy_(torch.from_numpy(synth.make_params(sh, oracle.param_layout(sh))))
+    st.G.zero_()
+    st.materialize_params()
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    x, dy = to_dev(xs[0], st.act_dtype), to_dev(dys[0], st.act_dtype)
+
+    def refused(fn):
+        with pytest.raises(zpp.ZppError) as e:
+            fn()
+        assert e.value.status == -2
+
+    refused(lambda: st.backward_input(0, dy))           # no forward yet
+    st.forward(0, x)
+    st.forward(1, x)
+    refused(lambda: st.backward_weight(0))              # no input-gradient task yet
+    st.backward_input(0, dy)
+    refused(lambda: st.backward_input(0, dy))           # twice
+    refused(lambda: st.backward(0, dy))                 # the fused call no longer applies
+    refused(lambda: st.adam_step(step=1, **synth.ADAM))  # a weight-gradient task is due
+    refused(lambda: st.end_unit())
+    st.backward_input(1, dy)                            # another input-gradient task may come first
+    st.backward_weight(1, in_place=False)
+    refused(lambda: st.backward_weight(0, in_place=False))  # staging buffer holds micro-batch 1
+    st.backward_weight(0, in_place=True, scale=1.0)     # in place does not need the staging buffer
+    refused(lambda: st.backward_weight(0, in_place=True))
+    st.accumulate_grads(1)
+    st.adam_step(step=1, **synth.ADAM)
+    st.end_unit()
+    torch.cuda.synchronize()
+    st.close()
+    plain = zpp.Stage(sh)
+    plain.materialize_params()
+    plain.forward(0, x)
+    refused(lambda: plain.backward_input(0, dy))        # created without split_backward
+    plain.close()
+
+
 def test_backward_accumulate_state_machine():
     sh = small(0, 1)
     st = zpp.Stage(sh)
@@ -195,11 +273,11 @@ def test_backward_accumulate_state_machine():
     st.forward(0, x)
     st.forward(1, x)
     st.backward(1, dy)
-    with pytest.raises(zpp.ZppError) as e:   # staging buffer still holds micro-batch 1
-        st.backward_accumulate(0, dy)
+    st.backward_accumulate(0, dy)            # does not use the staging buffer, which still holds micro-batch 1
+    with pytest.raises(zpp.ZppError) as e:   # ... and still waits for its accumulate pass
+        st.adam_step(step=1, **synth.ADAM)
     assert e.value.status == -2
     st.accumulate_grads(1)
-    st.backward_accumulate(0, dy)
     with pytest.raises(zpp.ZppError) as e:   # already accumulated
         st.accumulate_grads(0)
     assert e.value.status == -2

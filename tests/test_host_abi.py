@@ -98,6 +98,10 @@ def test_state_machine_and_argument_errors_without_launch():
         (lambda: L.stage_backward(st._h, 0, fake, fake, None), -2),
         (lambda: L.stage_accumulate_grads(st._h, 0, 1.0, None), -2),
         (lambda: L.stage_accumulate_grads(st._h, 99, 1.0, None), -1),
+        (lambda: L.stage_backward_accumulate(st._h, 0, fake, fake, 1.0, None), -2),
+        (lambda: L.stage_backward_accumulate(st._h, 0, fake, None, 1.0, None), -1),
+        (lambda: L.stage_backward_input(st._h, 0, fake, fake, None), -2),     # created without split_backward
+        (lambda: L.stage_backward_weight(st._h, 0, 0, 1.0, None), -2),
     ):
         with pytest.raises(zpp.ZppError) as e:
             binding._check(call())
@@ -113,6 +117,33 @@ def test_state_machine_and_argument_errors_without_launch():
     binding._check(L.shard_adam_step(st._h, 0, 0, ctypes.byref(a), None))
     st.end_unit()
     st.close()
+
+
+def test_split_backward_workspace_and_order_errors_without_launch():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    plain = zpp.Stage(sh, allocate=False)
+    split = zpp.Stage(sh, allocate=False, split_backward=True)
+    # room for each linear layer's dY ([T,h], [T,f], [T,h], [T,3h] in bf16) per (micro-batch, block)
+    T, h, f = sh.tokens, sh.hidden, sh.ffn
+    extra = split.workspace_bytes - plain.workspace_bytes
+    dy_bytes = 2 * T * (5 * h + f) * sh.n_blocks * sh.unit_mbs
+    assert dy_bytes <= extra <= dy_bytes * 1.05
+    L = zpp.lib()
+    fake = 0x10000
+    split.bind_raw(fake, fake, fake, fake, fake, split.workspace_bytes)
+    for call, status in (
+        (lambda: L.stage_backward_input(split._h, 0, fake, fake, None), -2),   # before materialise
+        (lambda: L.stage_backward_weight(split._h, 0, 1, 1.0, None), -2),
+        (lambda: L.stage_backward_input(split._h, -1, fake, fake, None), -1),
+        (lambda: L.stage_backward_weight(split._h, sh.unit_mbs, 1, 1.0, None), -1),
+        (lambda: L.stage_backward_input(split._h, 0, None, fake, None), -1),
+        (lambda: L.stage_backward_input(split._h, 0, fake, fake + 8, None), -3),
+    ):
+        with pytest.raises(zpp.ZppError) as e:
+            binding._check(call())
+        assert e.value.status == status, zpp.lib().zpp_last_error()
+    plain.close()
+    split.close()
 
 
 def test_missing_library_fails_loudly(tmp_path):
