@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--backward", choices=("fused", "split"), default="fused",
                     help="fused: one backward call per micro-batch; split: the input-gradient tasks of all "
                          "micro-batches of the unit first, then their weight-gradient tasks (same results bit for bit)")
+    ap.add_argument("--recompute", action="store_true",
+                    help="activation recomputation: keep only block inputs, run each block's forward again in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -86,7 +88,7 @@ def main():
     sh = synth.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split")
+    st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split", recompute=args.recompute)
     act = st.act_dtype
 
     # ---- synthetic inputs, resident in HBM before anything is timed
@@ -228,7 +230,8 @@ def main():
         "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
-                   "accumulate": args.accumulate, "backward": args.backward},
+                   "accumulate": args.accumulate, "backward": args.backward, "recompute": args.recompute,
+                   "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
         "model_flops_per_step": flops,
         "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),
         "fwd_bwd_TFLOPs": round(flops / (fb_ms * 1e-3) / 1e12, 2) if fb_ms > 0 else None,

@@ -76,6 +76,11 @@ typedef struct {
     int32_t split_backward; /* 1: the workspace also holds, per (micro-batch, block), what the weight-gradient
                               task needs from the input-gradient task (each linear layer's dY), so that
                               stage_backward_input / stage_backward_weight may be used; 0: only the fused calls */
+    int32_t recompute;      /* 1: activation recomputation (Section 3.3): stage_forward keeps only each block's
+                              input per micro-batch, and the backward calls run a block's forward again
+                              (without its last linear layer, whose output backward does not need) right
+                              before its backward; same kernels on the same inputs, so results are
+                              bit-identical to recompute = 0.  Excludes split_backward */
 } zpp_stage_config;
 
 typedef struct {

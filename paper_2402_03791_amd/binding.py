@@ -31,7 +31,8 @@ class ZppError(RuntimeError):
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch",
                                               "unit_mbs", "compute_dtype", "gelu_mode")] + \
-               [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("split_backward", ctypes.c_int32)]
+               [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("split_backward", ctypes.c_int32),
+                ("recompute", ctypes.c_int32)]
 
 
 class _Adam(ctypes.Structure):
@@ -120,17 +121,18 @@ class StageConfig:
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
     split_backward: int = 0
+    recompute: int = 0
 
     @classmethod
-    def from_shape(cls, shape, split_backward: int = 0) -> "StageConfig":
+    def from_shape(cls, shape, split_backward: int = 0, recompute: int = 0) -> "StageConfig":
         g = (lambda k: shape[k]) if isinstance(shape, dict) else (lambda k: getattr(shape, k))
         return cls(*(g(k) for k in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch", "unit_mbs",
-                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")), split_backward)
+                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")), split_backward, recompute)
 
     def _c(self) -> _Config:
         return _Config(self.arch, self.n_blocks, self.hidden, self.n_heads, self.ffn, self.seq, self.micro_batch,
                        self.unit_mbs, self.compute_dtype, self.gelu_mode, self.norm_eps, self.rope_base,
-                       self.split_backward)
+                       self.split_backward, self.recompute)
 
 
 def _adam_struct(lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1, zero_grad=0) -> _Adam:
@@ -148,8 +150,10 @@ class Stage:
     """A stage handle.  With ``allocate=True`` it also owns torch tensors for P, G, M, V and the
     workspace and binds them; otherwise call :meth:`bind` with your own tensors."""
 
-    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: bool = False):
-        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward))
+    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: bool = False,
+                 recompute: bool = False):
+        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward),
+                                                                                   int(recompute))
         self._h = ctypes.c_void_p()
         c = self.cfg._c()
         _check(lib().zpp_stage_create(ctypes.byref(c), ctypes.byref(self._h)))

@@ -110,6 +110,7 @@ struct zpp_stage {
     // workspace plan (byte offsets)
     Region rW, rWt, rS, rRope;
     uint64_t stash_base = 0, stash_block_bytes = 0;
+    uint64_t rc_base = 0;  // recompute mode: the one slot that holds a block's recomputed activations
     std::map<std::string, Region> stash_t;    // per (mb, block) tensors, offsets relative to the slot
     std::map<std::string, Region> tmp;        // shared temporaries
     uint64_t ws_bytes = 0;
@@ -154,10 +155,14 @@ struct zpp_stage {
     {
         return (acc_in_place ? G : (float *)(ws + rS.off)) + off(blk, nm);
     }
-    void *stash(int mb, int blk, const char *nm) const
+    // Address of a stashed tensor.  With activation recomputation only the block inputs "x" live per
+    // (micro-batch, block); everything else is in one slot, valid for the block that was run last.
+    uint64_t stash_off(int mb, int blk, const std::string &nm) const
     {
-        return ws + stash_base + ((uint64_t)mb * L + blk) * stash_block_bytes + stash_t.at(nm).off;
+        if (c.recompute && nm != "x") return rc_base + stash_t.at(nm).off;
+        return stash_base + ((uint64_t)mb * L + blk) * stash_block_bytes + (c.recompute ? 0 : stash_t.at(nm).off);
     }
+    void *stash(int mb, int blk, const char *nm) const { return ws + stash_off(mb, blk, nm); }
     void *tp(const char *nm) const { return ws + tmp.at(nm).off; }
 };
 
@@ -265,9 +270,18 @@ void plan_workspace(zpp_stage *s)
             sc("red_n2", colreduce_scratch_floats((int64_t)T, (int64_t)h), 4);
             sc("red_n1", colreduce_scratch_floats((int64_t)T, (int64_t)h), 4);
         }
-        s->stash_block_bytes = rel;
-        s->stash_base = cur;
-        cur = align_up(cur + (uint64_t)s->U * s->L * rel);
+        if (s->c.recompute) {
+            // only the block inputs are kept per (micro-batch, block); one more slot takes the rest
+            s->stash_block_bytes = align_up(T * h * e);
+            s->stash_base = cur;
+            cur = align_up(cur + (uint64_t)s->U * s->L * s->stash_block_bytes);
+            s->rc_base = cur;
+            cur = align_up(cur + rel);
+        } else {
+            s->stash_block_bytes = rel;
+            s->stash_base = cur;
+            cur = align_up(cur + (uint64_t)s->U * s->L * rel);
+        }
     }
     auto tmp = [&](const char *nm, uint64_t elems, int esz) { s->tmp[nm] = carve(elems, esz); };
     tmp("gA", T * h, e);
@@ -433,6 +447,9 @@ zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out)
         return fail(ZPP_ERR_ARG, "all sizes must be positive");
     if (c.hidden % c.n_heads) return fail(ZPP_ERR_ARG, "hidden (%d) not divisible by n_heads (%d)", c.hidden, c.n_heads);
     if (!(c.norm_eps > 0.0f)) return fail(ZPP_ERR_ARG, "norm_eps must be > 0");
+    if (c.recompute && c.split_backward)
+        return fail(ZPP_ERR_UNSUPPORTED, "recompute and split_backward exclude each other: the weight-gradient task "
+                                         "would need the recomputed activations again");
     const int64_t d = c.hidden / c.n_heads;
     if (c.arch == ZPP_ARCH_LLAMA && (d % 2)) return fail(ZPP_ERR_ARG, "rotary embedding needs an even head dim");
     if (c.arch == ZPP_ARCH_LLAMA && !(c.rope_base > 0.0f)) return fail(ZPP_ERR_ARG, "rope_base must be > 0");
@@ -538,6 +555,63 @@ zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
     return ZPP_OK;
 }
 
+namespace {
+
+// Forward of one block for micro-batch mb: x1 = xin + Attn(Norm1(xin)); out = x1 + MLP(Norm2(x1)), everything
+// backward needs written to the stash.  keep_x: also copy xin into the block's "x" slot (first block, whose
+// input is the caller's).  out == nullptr: the recomputation before the block's backward, which needs
+// the stashed tensors but not the block output, so the last linear layer is skipped.
+zpp_status forward_block(zpp_stage *s, int32_t mb, int blk, const void *xin, bool keep_x, void *out, hipStream_t st)
+{
+    const bool gpt = s->c.arch == ZPP_ARCH_GPT;
+    const int kind = gpt ? NORM_LAYER : NORM_RMS;
+    const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    void *xs = s->stash(mb, blk, "x");
+    float *mean1 = (float *)s->stash(mb, blk, "mean1"), *rstd1 = (float *)s->stash(mb, blk, "rstd1");
+    float *mean2 = (float *)s->stash(mb, blk, "mean2"), *rstd2 = (float *)s->stash(mb, blk, "rstd2");
+    void *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv"), *attn = s->stash(mb, blk, "attn");
+    void *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2"), *u = s->stash(mb, blk, "u");
+    void *g = s->stash(mb, blk, "g");
+    float *lse = (float *)s->stash(mb, blk, "lse");
+
+    ZPP_OTHER(launch_norm_fwd(s->dt, kind, xin, s->Wp(blk, gpt ? "ln1.gamma" : "norm1.gamma"),
+                            gpt ? s->Wp(blk, "ln1.beta") : nullptr, T, h, s->c.norm_eps, n1, mean1, rstd1,
+                            keep_x ? xs : nullptr, st));
+    GemmEpi e_qkv;
+    if (gpt) e_qkv.bias = s->Wp(blk, "attn.bqkv");
+    ZPP_TRY(linear_fwd(s, n1, blk, "attn.wqkv", h, 3 * h, qkv, e_qkv, st));
+    if (!gpt)
+        ZPP_OTHER(launch_rope(s->dt, qkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, +1, st));
+    ZPP_TRY(attention_fwd(s, qkv, attn, lse, st));
+    GemmEpi e_o;
+    if (gpt) e_o.bias = s->Wp(blk, "attn.bo");
+    e_o.resid = xs;
+    ZPP_TRY(linear_fwd(s, attn, blk, "attn.wo", h, h, x1, e_o, st));
+    ZPP_OTHER(launch_norm_fwd(s->dt, kind, x1, s->Wp(blk, gpt ? "ln2.gamma" : "norm2.gamma"),
+                            gpt ? s->Wp(blk, "ln2.beta") : nullptr, T, h, s->c.norm_eps, n2, mean2, rstd2,
+                            nullptr, st));
+    GemmEpi e_2;
+    e_2.resid = x1;
+    if (gpt) {
+        GemmEpi e_1;
+        e_1.bias = s->Wp(blk, "mlp.b1");
+        e_1.act = ACT_GELU_DUAL;
+        e_1.out2 = g;
+        e_1.gelu_mode = s->c.gelu_mode;
+        ZPP_TRY(linear_fwd(s, n2, blk, "mlp.w1", h, f, u, e_1, st));
+        e_2.bias = s->Wp(blk, "mlp.b2");
+        if (out) ZPP_TRY(linear_fwd(s, g, blk, "mlp.w2", f, h, out, e_2, st));
+    } else {
+        // wgate and wup are adjacent in the layout: one GEMM against the [2f, h] matrix gives [gate | up]
+        ZPP_TRY(linear_fwd(s, n2, blk, "mlp.wgate", h, f1, u, GemmEpi(), st));
+        ZPP_OTHER(launch_swiglu_fwd(s->dt, u, g, T, f, st));
+        if (out) ZPP_TRY(linear_fwd(s, g, blk, "mlp.wdown", f, h, out, e_2, st));
+    }
+    return ZPP_OK;
+}
+
+}  // namespace
+
 zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
@@ -547,53 +621,10 @@ zpp_status stage_forward(zpp_stage *s, int32_t mb, const void *x, void *y, void 
     if (!s->materialized) return fail(ZPP_ERR_STATE, "stage_forward before stage_materialize_params");
     if (s->mb_state[mb] != MB_IDLE) return fail(ZPP_ERR_STATE, "stage_forward(%d) called twice in this unit", mb);
     hipStream_t st = (hipStream_t)hip_stream;
-    const bool gpt = s->c.arch == ZPP_ARCH_GPT;
-    const int kind = gpt ? NORM_LAYER : NORM_RMS;
-    const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
     for (int blk = 0; blk < s->L; ++blk) {
-        void *xs = s->stash(mb, blk, "x");
-        const void *xin = blk == 0 ? x : xs;
+        const void *xin = blk == 0 ? x : s->stash(mb, blk, "x");
         void *out = blk == s->L - 1 ? y : s->stash(mb, blk + 1, "x");
-        float *mean1 = (float *)s->stash(mb, blk, "mean1"), *rstd1 = (float *)s->stash(mb, blk, "rstd1");
-        float *mean2 = (float *)s->stash(mb, blk, "mean2"), *rstd2 = (float *)s->stash(mb, blk, "rstd2");
-        void *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv"), *attn = s->stash(mb, blk, "attn");
-        void *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2"), *u = s->stash(mb, blk, "u");
-        void *g = s->stash(mb, blk, "g");
-        float *lse = (float *)s->stash(mb, blk, "lse");
-
-        ZPP_OTHER(launch_norm_fwd(s->dt, kind, xin, s->Wp(blk, gpt ? "ln1.gamma" : "norm1.gamma"),
-                                gpt ? s->Wp(blk, "ln1.beta") : nullptr, T, h, s->c.norm_eps, n1, mean1, rstd1,
-                                blk == 0 ? xs : nullptr, st));
-        GemmEpi e_qkv;
-        if (gpt) e_qkv.bias = s->Wp(blk, "attn.bqkv");
-        ZPP_TRY(linear_fwd(s, n1, blk, "attn.wqkv", h, 3 * h, qkv, e_qkv, st));
-        if (!gpt)
-            ZPP_OTHER(launch_rope(s->dt, qkv, (const float *)(s->ws + s->rRope.off), T, s->c.seq, s->nh, s->d, +1, st));
-        ZPP_TRY(attention_fwd(s, qkv, attn, lse, st));
-        GemmEpi e_o;
-        if (gpt) e_o.bias = s->Wp(blk, "attn.bo");
-        e_o.resid = xs;
-        ZPP_TRY(linear_fwd(s, attn, blk, "attn.wo", h, h, x1, e_o, st));
-        ZPP_OTHER(launch_norm_fwd(s->dt, kind, x1, s->Wp(blk, gpt ? "ln2.gamma" : "norm2.gamma"),
-                                gpt ? s->Wp(blk, "ln2.beta") : nullptr, T, h, s->c.norm_eps, n2, mean2, rstd2,
-                                nullptr, st));
-        GemmEpi e_2;
-        e_2.resid = x1;
-        if (gpt) {
-            GemmEpi e_1;
-            e_1.bias = s->Wp(blk, "mlp.b1");
-            e_1.act = ACT_GELU_DUAL;
-            e_1.out2 = g;
-            e_1.gelu_mode = s->c.gelu_mode;
-            ZPP_TRY(linear_fwd(s, n2, blk, "mlp.w1", h, f, u, e_1, st));
-            e_2.bias = s->Wp(blk, "mlp.b2");
-            ZPP_TRY(linear_fwd(s, g, blk, "mlp.w2", f, h, out, e_2, st));
-        } else {
-            // wgate and wup are adjacent in the layout: one GEMM against the [2f, h] matrix gives [gate | up]
-            ZPP_TRY(linear_fwd(s, n2, blk, "mlp.wgate", h, f1, u, GemmEpi(), st));
-            ZPP_OTHER(launch_swiglu_fwd(s->dt, u, g, T, f, st));
-            ZPP_TRY(linear_fwd(s, g, blk, "mlp.wdown", f, h, out, e_2, st));
-        }
+        if (zpp_status e = forward_block(s, mb, blk, xin, blk == 0, out, st)) return e;
     }
     s->mb_state[mb] = MB_FWD;
     return ZPP_OK;
@@ -655,6 +686,9 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int tasks, const void *dy
         void *dqkv = split ? s->stash(mb, blk, "d_qkv") : s->tp("dqkv");
         void *du = split ? s->stash(mb, blk, "d_u") : s->tp("du");
         if (split) dcur = s->stash(mb, blk, "d_y");
+        // activation recomputation (Section 3.3): only the block input was kept, run the block forward again
+        if (s->c.recompute)
+            if (zpp_status e = forward_block(s, mb, blk, s->stash(mb, blk, "x"), false, nullptr, st)) return e;
         const void *xs = s->stash(mb, blk, "x"), *n1 = s->stash(mb, blk, "n1"), *qkv = s->stash(mb, blk, "qkv");
         const void *attn = s->stash(mb, blk, "attn"), *x1 = s->stash(mb, blk, "x1"), *n2 = s->stash(mb, blk, "n2");
         const void *u = s->stash(mb, blk, "u"), *g = s->stash(mb, blk, "g");
@@ -850,7 +884,7 @@ zpp_status zpp_stage_region(const zpp_stage *s, const char *name, int32_t mb, in
     else if (s->stash_t.count(n)) {
         if (mb < 0 || mb >= s->U || blk < 0 || blk >= s->L) return fail(ZPP_ERR_ARG, "(mb, block) out of range");
         r = s->stash_t.at(n);
-        base = s->stash_base + ((uint64_t)mb * s->L + blk) * s->stash_block_bytes;
+        base = s->stash_off(mb, blk, n) - r.off;
     } else if (s->tmp.count(n)) r = s->tmp.at(n);
     else return fail(ZPP_ERR_ARG, "unknown region '%s'", name);
     *ptr = s->ws + base + r.off;

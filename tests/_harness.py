@@ -50,7 +50,8 @@ def run_oracle_unit(shape, P0: np.ndarray, xs, dys, dtype="f64", keep_stage=Fals
     return out
 
 
-def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=False, scale=1.0, split=None):
+def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=False, scale=1.0, split=None,
+                 recompute=False):
     """One scheduling unit on the GPU.  in_place: stage_backward_accumulate instead of the pair
     stage_backward + stage_accumulate_grads (then there is no staging snapshot S0).
     split: None, or the order in which the weight-gradient tasks run after ALL input-gradient tasks
@@ -58,7 +59,7 @@ def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=Fals
     input-gradient task)."""
     import torch
     import paper_2402_03791_amd as zpp
-    st = zpp.Stage(shape, split_backward=split is not None)
+    st = zpp.Stage(shape, split_backward=split is not None, recompute=recompute)
     st.P.copy_(torch.from_numpy(P0))
     st.G.zero_()
     st.materialize_params()

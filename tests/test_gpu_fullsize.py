@@ -44,6 +44,10 @@ def test_one_block_at_full_shape(name):
     split = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, split="ascending")
     assert np.array_equal(two["G"].view(np.uint32), split["G"].view(np.uint32))
     assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], split["dxs"]))
+    # activation recomputation: the block forward runs again inside the backward call
+    rc = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, recompute=True)
+    assert np.array_equal(two["G"].view(np.uint32), rc["G"].view(np.uint32))
+    assert all(np.array_equal(a, b) for a, b in zip(two["dxs"] + two["ys"], rc["dxs"] + rc["ys"]))
 
 
 def test_adam_over_the_whole_6p2b_shard():

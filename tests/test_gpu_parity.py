@@ -219,6 +219,33 @@ def test_split_backward_tasks_equal_the_fused_call(arch, dtype, kw):
         assert rel_err(desc["G"][off:off + r * c], fused["G"][off:off + r * c]) <= 1e-5, n
 
 
+@pytest.mark.parametrize("arch,dtype,kw", [
+    (0, 0, dict(unit_mbs=3)), (1, 0, dict(micro_batch=2, seq=96)), (0, 1, dict(unit_mbs=3)), (1, 1, {}),
+    (0, 1, dict(micro_batch=2, seq=160, ffn=768, n_heads=4, n_blocks=3)),
+    (1, 1, dict(micro_batch=2, seq=96, ffn=320, n_blocks=3)),
+])
+def test_activation_recomputation_reproduces_the_stashed_run(arch, dtype, kw):
+    """Section 3.3: with recomputation the backward runs each block's forward again from the block input
+    that was kept; same kernels, same inputs, so y, dx and G equal the stashed run bit for bit, and the
+    oracle bound holds as before."""
+    sh = small(arch, dtype, **kw)
+    print(f"recompute unit {sh.name} {kw}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    plain = run_gpu_unit(sh, P0, xs, dys)
+    for in_place in (False, True):
+        rc = run_gpu_unit(sh, P0, xs, dys, recompute=True, in_place=in_place)
+        for a, b in zip(plain["ys"] + plain["dxs"], rc["ys"] + rc["dxs"]):
+            assert np.array_equal(a, b)
+        assert np.array_equal(plain["G"].view(np.uint32), rc["G"].view(np.uint32))
+        if not in_place:
+            assert np.array_equal(plain["S0"].view(np.uint32), rc["S0"].view(np.uint32))
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    rc["S0"] = plain["S0"]
+    compare_units(sh, rc, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
+
+
 def test_split_backward_state_machine():
     sh = small(0, 1)
     st = zpp.Stage(sh, split_backward=True)

@@ -146,6 +146,25 @@ def test_split_backward_workspace_and_order_errors_without_launch():
     split.close()
 
 
+def test_recompute_shrinks_the_stash_to_block_inputs():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    plain = zpp.Stage(sh, allocate=False)
+    rc = zpp.Stage(sh, allocate=False, recompute=True)
+    T, h, f = sh.tokens, sh.hidden, sh.ffn
+    slots = sh.n_blocks * sh.unit_mbs
+    per_slot_plain = 2 * T * (8 * h + 2 * f)          # x, n1, qkv (3h), attn, x1, n2, u (f), g (f) in bf16
+    saved = plain.workspace_bytes - rc.workspace_bytes
+    # everything but x is kept once instead of once per (micro-batch, block)
+    expect = (slots - 1) * (per_slot_plain - 2 * T * h) - 2 * T * h
+    assert abs(saved - expect) <= 0.02 * expect
+    assert rc.N == plain.N
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.Stage(sh, allocate=False, recompute=True, split_backward=True)
+    assert e.value.status == -6
+    plain.close()
+    rc.close()
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         zpp.load_library(str(tmp_path / "libzpp.so"))
