@@ -71,6 +71,10 @@ def main():
     ap.add_argument("--backward", choices=("fused", "split"), default="fused",
                     help="fused: one backward call per micro-batch; split: the input-gradient tasks of all "
                          "micro-batches of the unit first, then their weight-gradient tasks (same results bit for bit)")
+    ap.add_argument("--stages", type=int, default=1,
+                    help="V > 1: the configuration's blocks as V stages on the device (zpp_device.h): breadth-first "
+                         "over the stages, one gathered stage live at a time, the next one's gather on a second stream")
+    ap.add_argument("--no-prefetch", action="store_true", help="with --stages: one working-copy slot, gathers in line")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: keep only block inputs, run each block's forward again in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -88,11 +92,22 @@ def main():
     sh = synth.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split", recompute=args.recompute)
+    V = args.stages
+    if V > 1:
+        if sh.n_blocks % V or args.backward != "fused" or args.accumulate != "in_place":
+            print("--stages needs a divisor of the block count and the default --backward/--accumulate", file=sys.stderr)
+            sys.exit(2)
+        full_layout = zpp.Stage(sh, allocate=False).layout()
+        st = zpp.Device(sh.replace(n_blocks=sh.n_blocks // V), V, prefetch=not args.no_prefetch,
+                        recompute=args.recompute)
+        st.N = st.N_total
+    else:
+        st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split", recompute=args.recompute)
+        full_layout = st.layout()
     act = st.act_dtype
 
     # ---- synthetic inputs, resident in HBM before anything is timed
-    P0 = synth.make_params(sh, st.layout())
+    P0 = synth.make_params(sh, full_layout)
     st.P.copy_(torch.from_numpy(P0))
     del P0
     xs = [torch.from_numpy(synth.make_x(sh, m)).to(dev, act) for m in range(sh.unit_mbs)]
@@ -102,7 +117,24 @@ def main():
     stream = torch.cuda.current_stream()
     adam = dict(synth.ADAM)
 
+    if V > 1:
+        # the stages are wired in a chain on this one GPU: y of stage v is x of stage v+1, dx of v is dy of v-1
+        U = sh.unit_mbs
+        side = torch.cuda.Stream()
+        mid = [[torch.empty_like(xs[0]) for _ in range(U)] for _ in range(V)]
+        gmid = [[torch.empty_like(xs[0]) for _ in range(U)] for _ in range(V)]
+        x_list = [(xs[m] if v == 0 else mid[v - 1][m]) for v in range(V) for m in range(U)]
+        y_list = [mid[v][m] for v in range(V) for m in range(U)]
+        dy_list = [(dys[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)]
+        dx_list = [gmid[v][m] for v in range(V) for m in range(U)]
+
     def step(t: int):
+        if V > 1:
+            st.forward_unit(x_list, y_list, stream, side)
+            st.backward_unit(dy_list, dx_list, 1.0, stream, side)
+            st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
+            st.end_unit()
+            return
         st.materialize_params(stream)
         for m in range(sh.unit_mbs):
             st.forward(m, xs[m], y, stream)
@@ -154,7 +186,7 @@ def main():
     # timed step does not contain it (in-place accumulation has no such launch)
     acc_standalone = None
     if args.accumulate == "in_place":
-        S = st.region("S")
+        S = st.region("S") if V == 1 else torch.empty_like(st.G)
         reps = 4
         a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         zpp.op_flat_accumulate(st.G, S, 1.0, stream=stream)
@@ -231,6 +263,7 @@ def main():
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
                    "accumulate": args.accumulate, "backward": args.backward, "recompute": args.recompute,
+                   "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
                    "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
         "model_flops_per_step": flops,
         "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),

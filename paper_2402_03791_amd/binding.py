@@ -19,6 +19,9 @@ EXPORTS = [
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
     "zpp_op_flat_accumulate", "zpp_op_flat_materialize",
+    "zpp_device_create", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
+    "zpp_device_workspace_bytes", "zpp_device_memory_terms", "zpp_device_stage", "zpp_device_bind",
+    "device_forward_unit", "device_backward_unit", "device_adam_step", "zpp_device_end_unit",
 ]
 
 
@@ -79,6 +82,22 @@ def load_library(path: str | None = None):
     L.zpp_stage_counters.restype = None
     L.zpp_stage_region.argtypes = [vp, ctypes.c_char_p, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(u64),
                                    ctypes.POINTER(i32)]
+    L.zpp_device_create.argtypes = [ctypes.POINTER(_Config), i32, i32, ctypes.POINTER(vp)]
+    L.zpp_device_destroy.argtypes = [vp]
+    L.zpp_device_destroy.restype = None
+    L.zpp_device_stage_count.argtypes = [vp]
+    L.zpp_device_param_count.argtypes = [vp]
+    L.zpp_device_param_count.restype = u64
+    L.zpp_device_workspace_bytes.argtypes = [vp]
+    L.zpp_device_workspace_bytes.restype = u64
+    L.zpp_device_memory_terms.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u64), ctypes.POINTER(u64)]
+    L.zpp_device_stage.argtypes = [vp, i32]
+    L.zpp_device_stage.restype = vp
+    L.zpp_device_bind.argtypes = [vp, vp, vp, vp, vp, vp, u64]
+    L.device_forward_unit.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp]
+    L.device_backward_unit.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), f32, vp, vp]
+    L.device_adam_step.argtypes = [vp, ctypes.POINTER(_Adam), vp]
+    L.zpp_device_end_unit.argtypes = [vp]
     L.zpp_profile_enable.argtypes = [i32]
     L.zpp_profile_reset.restype = None
     L.zpp_profile_read.argtypes = [i32, ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_double),
@@ -268,6 +287,75 @@ class Stage:
         else:
             dt = torch.bfloat16
         return raw.view(dt)
+
+
+class Device:
+    """V stages of one configuration on one device (include/zpp_device.h).  With ``allocate=True`` it owns
+    torch tensors for P, G, M, V (V * N elements, stage v at [v*N, (v+1)*N)) and the workspace."""
+
+    def __init__(self, cfg, n_stages: int, prefetch: bool = True, device: str | None = "cuda:0",
+                 allocate: bool = True, recompute: bool = False):
+        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, 0, int(recompute))
+        self._h = ctypes.c_void_p()
+        c = self.cfg._c()
+        _check(lib().zpp_device_create(ctypes.byref(c), n_stages, int(prefetch), ctypes.byref(self._h)))
+        self.n_stages = n_stages
+        self.U = self.cfg.unit_mbs
+        self.N_total = int(lib().zpp_device_param_count(self._h))
+        self.N = self.N_total // n_stages
+        self.workspace_bytes = int(lib().zpp_device_workspace_bytes(self._h))
+        self.P = self.G = self.M = self.V = self.workspace = None
+        if allocate:
+            import torch
+            self.act_dtype = torch.bfloat16 if self.cfg.compute_dtype == 1 else torch.float32
+            dev = torch.device(device)
+            self.P = torch.zeros(self.N_total, dtype=torch.float32, device=dev)
+            self.G = torch.zeros_like(self.P)
+            self.M = torch.zeros_like(self.P)
+            self.V = torch.zeros_like(self.P)
+            self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=dev)
+            _check(lib().zpp_device_bind(self._h, self.P.data_ptr(), self.G.data_ptr(), self.M.data_ptr(),
+                                         self.V.data_ptr(), self.workspace.data_ptr(), self.workspace_bytes))
+
+    def close(self):
+        if self._h:
+            lib().zpp_device_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def memory_terms(self):
+        a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib().zpp_device_memory_terms(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+        return {"working_copies": a.value, "scratch": b.value, "stash": c.value}
+
+    def bind_raw(self, P, G, M, V, workspace, workspace_bytes):
+        _check(lib().zpp_device_bind(self._h, P, G, M, V, workspace, workspace_bytes))
+
+    @staticmethod
+    def _ptrs(tensors):
+        arr = (ctypes.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        return arr
+
+    def forward_unit(self, xs, ys, stream=None, side_stream=None):
+        """xs, ys: lists of V*U tensors, entry v*U + m for stage v and micro-batch m."""
+        _check(lib().device_forward_unit(self._h, self._ptrs(xs), self._ptrs(ys), _stream_ptr(stream),
+                                         None if side_stream is None else ctypes.c_void_p(side_stream.cuda_stream)))
+
+    def backward_unit(self, dys, dxs, scale: float = 1.0, stream=None, side_stream=None):
+        _check(lib().device_backward_unit(self._h, self._ptrs(dys), self._ptrs(dxs), scale, _stream_ptr(stream),
+                                          None if side_stream is None else ctypes.c_void_p(side_stream.cuda_stream)))
+
+    def adam_step(self, stream=None, **hp):
+        a = _adam_struct(**hp)
+        _check(lib().device_adam_step(self._h, ctypes.byref(a), _stream_ptr(stream)))
+
+    def end_unit(self):
+        _check(lib().zpp_device_end_unit(self._h))
 
 
 PROF_CLASSES = ["gemm", "attn_fwd", "attn_bwd", "accumulate", "adam", "materialize", "other", "gemm_dw"]

@@ -5,6 +5,7 @@
 #include "../../include/zpp.h"
 #include "../../include/zpp_ops.h"
 #include "kernels.h"
+#include "stage_internal.h"
 
 #include <cmath>
 #include <cstdarg>
@@ -28,6 +29,18 @@ using namespace zpp;
 namespace {
 
 thread_local char g_err[512] = "";
+}
+
+zpp_status zpp::set_error(zpp_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+namespace {
 
 zpp_status fail(zpp_status st, const char *fmt, ...)
 {
@@ -219,9 +232,19 @@ void build_layout(zpp_stage *s)
 
 constexpr uint64_t kRedPerBlock = 6;  // four bias gradients and two norm-gain gradients per block at most
 
-void plan_workspace(zpp_stage *s)
+// The workspace has three parts, each planned from its own base offset so that several stages on one
+// device can share what only one of them uses at a time:
+//   working copy  W, its transposed copy, the rotary table        (one gathered stage, Section 4.2)
+//   scratch       the fp32 staging gradients and per-call temporaries
+//   stash         the activations of the unit's micro-batches     (private to a stage)
+// Returns the sizes of the three parts.
+struct PartSizes {
+    uint64_t wcopy, scratch, stash;
+};
+
+PartSizes plan_workspace(zpp_stage *s, uint64_t wcopy_off, uint64_t scratch_off, uint64_t stash_off)
 {
-    uint64_t cur = 0;
+    uint64_t cur = wcopy_off;
     auto carve = [&](uint64_t elems, int esz) {
         Region r;
         r.off = cur;
@@ -232,11 +255,15 @@ void plan_workspace(zpp_stage *s)
     };
     const int e = (int)s->esz;
     const uint64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    PartSizes sz;
+    // ---- working copy
     s->rW = carve(s->N, e);
     if (s->dt == DT_BF16) s->rWt = carve(s->Nmat, 2);
-    s->rS = carve(s->N, 4);
     if (s->c.arch == ZPP_ARCH_LLAMA) s->rRope = carve((uint64_t)s->c.seq * (s->d / 2) * 2, 4);
-    // activation stash: one slot per (micro-batch, block)
+    sz.wcopy = cur - wcopy_off;
+    // ---- activation stash: one slot per (micro-batch, block)
+    cur = stash_off;
+    s->stash_t.clear();
     {
         uint64_t rel = 0;
         auto sc = [&](const char *nm, uint64_t elems, int esz) {
@@ -283,6 +310,11 @@ void plan_workspace(zpp_stage *s)
             cur = align_up(cur + (uint64_t)s->U * s->L * rel);
         }
     }
+    sz.stash = cur - stash_off;
+    // ---- scratch
+    cur = scratch_off;
+    s->rS = carve(s->N, 4);
+    s->tmp.clear();
     auto tmp = [&](const char *nm, uint64_t elems, int esz) { s->tmp[nm] = carve(elems, esz); };
     tmp("gA", T * h, e);
     tmp("gB", T * h, e);
@@ -302,7 +334,8 @@ void plan_workspace(zpp_stage *s)
                              transpose_colsum_scratch_floats((int64_t)T, (int64_t)widest));
     tmp("redpool", s->red_floats * kRedPerBlock * s->L, 4);  // one slot per column reduction of a backward call
     s->finish.reserve(kRedPerBlock * s->L);
-    s->ws_bytes = cur;
+    sz.scratch = cur - scratch_off;
+    return sz;
 }
 
 #define ZPP_OTHER(expr)                                   \
@@ -481,7 +514,12 @@ zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out)
     s->dt = c.compute_dtype == ZPP_DTYPE_BF16 ? DT_BF16 : DT_F32;
     s->esz = dt_size(s->dt);
     build_layout(s);
-    plan_workspace(s);
+    {
+        // a stage on its own: the three parts one after the other
+        const PartSizes sz = plan_workspace(s, 0, 0, 0);
+        plan_workspace(s, 0, sz.wcopy, sz.wcopy + sz.scratch);
+        s->ws_bytes = sz.wcopy + sz.scratch + sz.stash;
+    }
     s->mb_state.assign(s->U, MB_IDLE);
     s->norm_items.assign(s->U, {});
     *out = s;
@@ -507,6 +545,25 @@ zpp_status zpp_stage_param_layout(const zpp_stage *s, int32_t idx, const char **
     return ZPP_OK;
 }
 
+namespace {
+
+void attach(zpp_stage *s, float *P, float *G, float *M, float *V, void *base)
+{
+    s->P = P;
+    s->G = G;
+    s->M = M;
+    s->V = V;
+    s->ws = (unsigned char *)base;
+    s->bound = true;
+    s->materialized = false;
+    s->rope_ready = false;
+    s->pending_acc = -1;
+    s->mb_state.assign(s->U, MB_IDLE);
+    s->norm_items.assign(s->U, {});
+}
+
+}  // namespace
+
 zpp_status zpp_stage_bind(zpp_stage *s, float *P, float *G, float *M, float *V, void *workspace,
                           uint64_t workspace_bytes)
 {
@@ -517,19 +574,38 @@ zpp_status zpp_stage_bind(zpp_stage *s, float *P, float *G, float *M, float *V, 
     if (workspace_bytes < s->ws_bytes)
         return fail(ZPP_ERR_WORKSPACE, "workspace has %llu bytes, %llu needed", (unsigned long long)workspace_bytes,
                     (unsigned long long)s->ws_bytes);
-    s->P = P;
-    s->G = G;
-    s->M = M;
-    s->V = V;
-    s->ws = (unsigned char *)workspace;
-    s->bound = true;
-    s->materialized = false;
-    s->rope_ready = false;
-    s->pending_acc = -1;
-    s->mb_state.assign(s->U, MB_IDLE);
-    s->norm_items.assign(s->U, {});
+    const PartSizes sz = plan_workspace(s, 0, 0, 0);
+    plan_workspace(s, 0, sz.wcopy, sz.wcopy + sz.scratch);
+    attach(s, P, G, M, V, workspace);
     return ZPP_OK;
 }
+
+extern "C++" {
+
+StageParts zpp::stage_parts(const zpp_stage *s)
+{
+    zpp_stage probe = *s;  // planning writes the region tables
+    const PartSizes sz = plan_workspace(&probe, 0, 0, 0);
+    return {sz.wcopy, sz.scratch, sz.stash};
+}
+
+zpp_status zpp::stage_bind_parts(zpp_stage *s, float *P, float *G, float *M, float *V, void *base,
+                                 uint64_t wcopy_off, uint64_t scratch_off, uint64_t stash_off)
+{
+    if (check_stage(s, false)) return ZPP_ERR_ARG;
+    if (!P || !G || !M || !V || !base) return fail(ZPP_ERR_ARG, "P, G, M, V and workspace must be non-NULL");
+    if (!aligned(P) || !aligned(G) || !aligned(M) || !aligned(V) || !aligned(base) || wcopy_off % kAlign ||
+        scratch_off % kAlign || stash_off % kAlign)
+        return fail(ZPP_ERR_ALIGN, "P, G, M, V, the workspace and its parts must be 256-byte aligned");
+    plan_workspace(s, wcopy_off, scratch_off, stash_off);
+    attach(s, P, G, M, V, base);
+    return ZPP_OK;
+}
+
+void zpp::stage_drop_working_copy(zpp_stage *s) { s->materialized = false; }
+bool zpp::stage_has_working_copy(const zpp_stage *s) { return s->materialized; }
+
+}  // extern "C++"
 
 zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
 {

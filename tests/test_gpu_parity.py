@@ -246,6 +246,68 @@ def test_activation_recomputation_reproduces_the_stashed_run(arch, dtype, kw):
     compare_units(sh, rc, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
 
 
+@pytest.mark.parametrize("arch,dtype,V,per,prefetch", [
+    (0, 1, 2, 2, True), (0, 1, 2, 2, False), (1, 1, 4, 1, True), (0, 0, 2, 1, True), (0, 1, 3, 1, True),
+    (1, 1, 3, 1, False),
+])
+def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, prefetch):
+    """V stages that take turns in one or two working-copy slots (the next one gathered on a second stream
+    while the current one computes) against a single stage holding all V * per blocks: two units with an
+    Adam step after each, everything bit-identical (same kernels, same operands, same order per tensor)."""
+    sh_all = small(arch, dtype, n_blocks=V * per, unit_mbs=3)
+    sh_one = sh_all.replace(n_blocks=per)
+    print(f"device {sh_all.name} V={V} per={per} prefetch={prefetch}", flush=True)
+    U = sh_all.unit_mbs
+    P0 = synth.make_params(sh_all, oracle.param_layout(sh_all), gain_jitter=0.1)
+    xs, dys = make_inputs(sh_all, U)
+
+    st = zpp.Stage(sh_all)
+    st.P.copy_(torch.from_numpy(P0))
+    st.G.zero_()
+    ref = []
+    for unit in range(2):
+        st.materialize_params()
+        ys = [st.forward(m, to_dev(xs[m], st.act_dtype)) for m in range(U)]
+        dxs = [st.backward_accumulate(m, to_dev(dys[m], st.act_dtype), scale=0.5) for m in range(U)]
+        g = st.G.clone()
+        st.adam_step(step=unit + 1, zero_grad=1, **synth.ADAM)
+        st.end_unit()
+        torch.cuda.synchronize()
+        ref.append((ys, dxs, g, st.P.clone()))
+    st.close()
+
+    dev = zpp.Device(sh_one, V, prefetch=prefetch)
+    assert dev.N_total == P0.size
+    dev.P.copy_(torch.from_numpy(P0))
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    act = dev.act_dtype
+    x_in = [to_dev(xs[m], act) for m in range(U)]
+    dy_in = [to_dev(dys[m], act) for m in range(U)]
+    # activations between the stages: y of stage v is x of stage v+1; dx of stage v is dy of stage v-1
+    mid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+    gmid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+    x_list = [(x_in[m] if v == 0 else mid[v - 1][m]) for v in range(V) for m in range(U)]
+    y_list = [mid[v][m] for v in range(V) for m in range(U)]
+    dy_list = [(dy_in[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)]
+    dx_list = [gmid[v][m] for v in range(V) for m in range(U)]
+    for unit in range(2):
+        dev.forward_unit(x_list, y_list, main, side)
+        dev.backward_unit(dy_list, dx_list, 0.5, main, side)
+        torch.cuda.synchronize()
+        ys, dxs, g, p = ref[unit]
+        for m in range(U):
+            assert torch.equal(mid[V - 1][m].view(torch.int16 if dtype else torch.int32),
+                               ys[m].view(torch.int16 if dtype else torch.int32)), ("y", unit, m)
+            assert torch.equal(gmid[0][m].view(torch.int16 if dtype else torch.int32),
+                               dxs[m].view(torch.int16 if dtype else torch.int32)), ("dx", unit, m)
+        assert torch.equal(dev.G.view(torch.int32), g.view(torch.int32)), ("G", unit)
+        dev.adam_step(step=unit + 1, zero_grad=1, **synth.ADAM)
+        dev.end_unit()
+        torch.cuda.synchronize()
+        assert torch.equal(dev.P.view(torch.int32), p.view(torch.int32)), ("P", unit)
+    dev.close()
+
+
 def test_split_backward_state_machine():
     sh = small(0, 1)
     st = zpp.Stage(sh, split_backward=True)

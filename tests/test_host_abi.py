@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def declared_functions():
     names = []
-    for hdr in ("zpp.h", "zpp_ops.h"):
+    for hdr in sorted(os.listdir(os.path.join(ROOT, "include"))):
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
@@ -163,6 +163,39 @@ def test_recompute_shrinks_the_stash_to_block_inputs():
     assert e.value.status == -6
     plain.close()
     rc.close()
+
+
+def test_device_memory_terms_follow_the_weight_memory_formula():
+    """Section 4.2: with V stages per device only one gathered stage is live (two with prefetch), so the
+    working-copy term shrinks by V while the activation term does not depend on V."""
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]                      # 4 blocks
+    whole = zpp.Device(sh, 1, prefetch=False, allocate=False)
+    halves = zpp.Device(sh.replace(n_blocks=2), 2, prefetch=False, allocate=False)
+    halves_pf = zpp.Device(sh.replace(n_blocks=2), 2, prefetch=True, allocate=False)
+    quarters = zpp.Device(sh.replace(n_blocks=1), 4, prefetch=True, allocate=False)
+    assert whole.N_total == halves.N_total == quarters.N_total == zpp.Stage(sh, allocate=False).N
+    w, h2, h2p, q = (d.memory_terms() for d in (whole, halves, halves_pf, quarters))
+    assert abs(h2["working_copies"] * 2 - w["working_copies"]) <= 4096
+    assert abs(h2p["working_copies"] - w["working_copies"]) <= 4096      # two slots of half a model
+    assert abs(q["working_copies"] * 2 - w["working_copies"]) <= 4096    # two slots of a quarter
+    for t in (h2, h2p, q):
+        assert abs(t["stash"] - w["stash"]) <= 1 << 16
+        assert t["scratch"] < w["scratch"]
+    assert sum(w.values()) == whole.workspace_bytes == zpp.Stage(sh, allocate=False).workspace_bytes
+    # errors before any launch
+    L = zpp.lib()
+    fake = 0x10000
+    with pytest.raises(zpp.ZppError) as e:
+        halves.bind_raw(fake, fake, fake, fake, fake, halves.workspace_bytes - 1)
+    assert e.value.status == -4
+    with pytest.raises(zpp.ZppError) as e:
+        binding._check(L.device_forward_unit(halves._h, None, None, None, None))
+    assert e.value.status == -2   # not bound
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.Device(sh, 0, allocate=False)
+    assert e.value.status == -1
+    for d in (whole, halves, halves_pf, quarters):
+        d.close()
 
 
 def test_missing_library_fails_loudly(tmp_path):
