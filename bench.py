@@ -75,6 +75,8 @@ def main():
                     help="V > 1: the configuration's blocks as V stages on the device (zpp_device.h): breadth-first "
                          "over the stages, one gathered stage live at a time, the next one's gather on a second stream")
     ap.add_argument("--no-prefetch", action="store_true", help="with --stages: one working-copy slot, gathers in line")
+    ap.add_argument("--adam", choices=("uniform", "decay_ranges"), default="uniform",
+                    help="decay_ranges: shard_adam_step_ranges with weight decay on matrices only")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: keep only block inputs, run each block's forward again in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -151,9 +153,13 @@ def main():
             else:
                 st.backward(m, dys[m], dx, stream)
                 st.accumulate_grads(m, 1.0, stream)
-        st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
+        if args.adam == "decay_ranges":
+            st.adam_step_ranges(ranges, step=t, zero_grad=1, stream=stream, **adam)
+        else:
+            st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
         st.end_unit()
 
+    ranges = st.decay_ranges(adam["lr"], adam["weight_decay"]) if args.adam == "decay_ranges" and V == 1 else None
     t = 0
     for _ in range(args.warmup):
         t += 1
@@ -263,7 +269,7 @@ def main():
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
                    "accumulate": args.accumulate, "backward": args.backward, "recompute": args.recompute,
-                   "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
+                   "adam": args.adam, "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
                    "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
         "model_flops_per_step": flops,
         "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),

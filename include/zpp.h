@@ -199,6 +199,26 @@ zpp_status stage_backward_weight(zpp_stage *stage, int32_t micro_batch, int32_t 
 zpp_status shard_adam_step(zpp_stage *stage, uint64_t offset, uint64_t count, const zpp_adam *hp,
                            void *hip_stream);
 
+/* The same update over several ranges of the shard in one launch, each range with its own learning
+ * rate and weight decay (the usual "no decay on norm gains, offsets and biases"; ZeRO-1-style
+ * sub-ranges of Section 3.2.2 are ranges too).  Everything else (betas, eps, step, grad_scale, the decay
+ * form, zero_grad) comes from *hp, whose lr and weight_decay are ignored.  Ranges: ascending, disjoint,
+ * offset and count multiples of 4 elements; elements outside every range are left untouched (G included).
+ * Errors as shard_adam_step; ZPP_ERR_ARG for overlapping or unordered ranges. */
+typedef struct {
+    uint64_t offset, count; /* elements */
+    float lr, weight_decay;
+} zpp_adam_range;
+zpp_status shard_adam_step_ranges(zpp_stage *stage, const zpp_adam_range *ranges, int32_t n_ranges,
+                                  const zpp_adam *hp, void *hip_stream);
+
+/* Fills `out` (capacity entries) with ranges that cover the whole shard in layout order: matrices with
+ * `weight_decay`, one-row tensors (gains, offsets, biases) with 0, all with `lr`; neighbours with equal
+ * settings are merged.  Returns the number of ranges the shard needs (call with out = NULL to size the
+ * array); host only. */
+int32_t zpp_stage_decay_ranges(const zpp_stage *stage, float lr, float weight_decay, zpp_adam_range *out,
+                               int32_t capacity);
+
 /* Releases the unit's activation stash slots ("memory allocated by each scheduling unit is released
  * before the next scheduling unit begins", Section 3.1.2) and resets the per-micro-batch states. */
 zpp_status zpp_stage_end_unit(zpp_stage *stage);

@@ -14,7 +14,8 @@ EXPORTS = [
     "zpp_stage_create", "zpp_stage_destroy", "zpp_stage_param_count", "zpp_stage_workspace_bytes",
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
     "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight",
-    "stage_accumulate_grads", "shard_adam_step", "zpp_stage_end_unit",
+    "stage_accumulate_grads", "shard_adam_step", "shard_adam_step_ranges", "zpp_stage_decay_ranges",
+    "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
@@ -36,6 +37,11 @@ class _Config(ctypes.Structure):
                                               "unit_mbs", "compute_dtype", "gelu_mode")] + \
                [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("split_backward", ctypes.c_int32),
                 ("recompute", ctypes.c_int32)]
+
+
+class _AdamRange(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_uint64), ("count", ctypes.c_uint64), ("lr", ctypes.c_float),
+                ("weight_decay", ctypes.c_float)]
 
 
 class _Adam(ctypes.Structure):
@@ -77,6 +83,8 @@ def load_library(path: str | None = None):
     L.stage_backward_weight.argtypes = [vp, i32, i32, f32, vp]
     L.stage_accumulate_grads.argtypes = [vp, i32, f32, vp]
     L.shard_adam_step.argtypes = [vp, u64, u64, ctypes.POINTER(_Adam), vp]
+    L.shard_adam_step_ranges.argtypes = [vp, ctypes.POINTER(_AdamRange), i32, ctypes.POINTER(_Adam), vp]
+    L.zpp_stage_decay_ranges.argtypes = [vp, f32, f32, ctypes.POINTER(_AdamRange), i32]
     L.zpp_stage_end_unit.argtypes = [vp]
     L.zpp_stage_counters.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u64)]
     L.zpp_stage_counters.restype = None
@@ -270,6 +278,20 @@ class Stage:
         if count is None:
             count = self.N - offset
         _check(lib().shard_adam_step(self._h, offset, count, ctypes.byref(a), _stream_ptr(stream)))
+
+    def decay_ranges(self, lr: float, weight_decay: float):
+        """(offset, count, lr, weight_decay) tuples covering the shard: decay on matrices only."""
+        n = lib().zpp_stage_decay_ranges(self._h, lr, weight_decay, None, 0)
+        arr = (_AdamRange * n)()
+        assert lib().zpp_stage_decay_ranges(self._h, lr, weight_decay, arr, n) == n
+        return [(r.offset, r.count, r.lr, r.weight_decay) for r in arr]
+
+    def adam_step_ranges(self, ranges, stream=None, **hp):
+        """ranges: iterable of (offset, count, lr, weight_decay); hp as adam_step (its lr / weight_decay unused)."""
+        ranges = list(ranges)
+        arr = (_AdamRange * max(len(ranges), 1))(*[_AdamRange(*r) for r in ranges])
+        a = _adam_struct(**hp)
+        _check(lib().shard_adam_step_ranges(self._h, arr, len(ranges), ctypes.byref(a), _stream_ptr(stream)))
 
     def end_unit(self):
         _check(lib().zpp_stage_end_unit(self._h))

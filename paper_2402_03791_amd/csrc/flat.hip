@@ -213,6 +213,56 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ P, float 
         }
 }
 
+// Several ranges in one launch: a block finds its range in the table (a scalar search over at most
+// kAdamRanges entries), takes that range's learning rate and weight decay, and then does exactly what a
+// block of adam_kernel<1> does on the range: 256 16-byte vectors per array.
+__global__ __launch_bounds__(256) void adam_ranges_kernel(float *__restrict__ P, float *__restrict__ M,
+                                                          float *__restrict__ V, float *__restrict__ G,
+                                                          AdamRanges r, AdamArgs a)
+{
+    int i = 0;
+    while (i + 1 < r.n && blockIdx.x >= r.first_block[i + 1]) ++i;
+    a.lr = r.lr[i];
+    a.wd = r.wd[i];
+    const uint64_t v = (uint64_t)(blockIdx.x - r.first_block[i]) * 256 + threadIdx.x;
+    if (v >= r.count[i] / 4) return;
+    const uint64_t e = r.offset[i] / 4 + v;
+    f32x4 p = nt_load(reinterpret_cast<const f32x4 *>(P) + e);
+    f32x4 m = nt_load(reinterpret_cast<const f32x4 *>(M) + e);
+    f32x4 vv = nt_load(reinterpret_cast<const f32x4 *>(V) + e);
+    f32x4 g = nt_load(reinterpret_cast<const f32x4 *>(G) + e);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float pp = p[k], mm = m[k], v2 = vv[k], gg = g[k];
+        adam_one(pp, mm, v2, gg, a);
+        p[k] = pp;
+        m[k] = mm;
+        vv[k] = v2;
+        g[k] = gg;
+    }
+    nt_store(p, reinterpret_cast<f32x4 *>(P) + e);
+    nt_store(m, reinterpret_cast<f32x4 *>(M) + e);
+    nt_store(vv, reinterpret_cast<f32x4 *>(V) + e);
+    if (a.zero_grad) nt_store(g, reinterpret_cast<f32x4 *>(G) + e);
+}
+
+hipError_t launch_adam_ranges(float *P, float *M, float *V, float *G, AdamRanges r, const AdamArgs &a, hipStream_t s)
+{
+    if (r.n <= 0) return hipSuccess;
+    if (r.n > kAdamRanges) return hipErrorInvalidValue;
+    uint64_t blocks = 0;
+    for (int i = 0; i < r.n; ++i) {
+        if (r.offset[i] % 4 || r.count[i] % 4) return hipErrorInvalidValue;
+        r.first_block[i] = (uint32_t)blocks;
+        blocks += (r.count[i] / 4 + 255) / 256;
+    }
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    r.first_block[r.n] = (uint32_t)blocks;
+    if (blocks == 0) return hipSuccess;
+    adam_ranges_kernel<<<(unsigned)blocks, 256, 0, s>>>(P, M, V, G, r, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_adam(float *P, float *M, float *V, float *G, uint64_t n, const AdamArgs &a, hipStream_t s)
 {
     if (n == 0) return hipSuccess;

@@ -20,6 +20,17 @@ struct AdamArgs {
     int decoupled, zero_grad;
 };
 
+// Up to kAdamRanges ranges of one flat shard updated by one launch, each with its own learning rate and
+// weight decay (everything else from AdamArgs).  offset/count in elements, multiples of 4.
+constexpr int kAdamRanges = 32;
+struct AdamRanges {
+    uint64_t offset[kAdamRanges], count[kAdamRanges];
+    float lr[kAdamRanges], wd[kAdamRanges];
+    uint32_t first_block[kAdamRanges + 1];  // blocks [first_block[i], first_block[i+1]) work on range i
+    int32_t n;
+};
+hipError_t launch_adam_ranges(float *P, float *M, float *V, float *G, AdamRanges r, const AdamArgs &a, hipStream_t s);
+
 // Epilogue of a GEMM: out = act(acc + bias[n] + resid[m,n]).
 struct GemmEpi {
     const void *bias = nullptr;   // [N], element type of the compute dtype, or null

@@ -7,6 +7,7 @@
 #include "kernels.h"
 #include "stage_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -888,6 +889,38 @@ zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *h
     return ZPP_OK;
 }
 
+namespace {
+
+// Host-side checks shared by the Adam entry points, and the kernel's argument block (lr and weight decay
+// from hp; the ranged entry point overrides them per range).
+zpp_status adam_args(zpp_stage *s, const zpp_adam *hp, AdamArgs *a)
+{
+    if (!hp) return fail(ZPP_ERR_ARG, "hyper-parameters are NULL");
+    if (hp->step < 1) return fail(ZPP_ERR_ARG, "step must be >= 1");
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f && hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+        return fail(ZPP_ERR_ARG, "betas must lie in [0,1)");
+    if (s->pending_acc >= 0)
+        return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
+    for (int64_t m = 0; m < s->U; ++m)
+        if (s->mb_state[m] == MB_BIN)
+            return fail(ZPP_ERR_STATE, "micro-batch %d has its input gradient but not its weight gradient", (int)m);
+    a->lr = hp->lr;
+    a->beta1 = hp->beta1;
+    a->beta2 = hp->beta2;
+    a->eps = hp->eps;
+    a->wd = hp->weight_decay;
+    a->grad_scale = hp->grad_scale;
+    a->omb1 = (float)(1.0 - (double)hp->beta1);
+    a->omb2 = (float)(1.0 - (double)hp->beta2);
+    a->c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
+    a->c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
+    a->decoupled = hp->decoupled_wd ? 1 : 0;
+    a->zero_grad = hp->zero_grad ? 1 : 0;
+    return ZPP_OK;
+}
+
+}  // namespace
+
 zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const zpp_adam *hp, void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
@@ -897,27 +930,8 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
                     (unsigned long long)count, (unsigned long long)s->N);
     if (offset % 4 || (count % 4 && offset + count != s->N))
         return fail(ZPP_ERR_ALIGN, "offset and count must be multiples of 4 elements");
-    if (hp->step < 1) return fail(ZPP_ERR_ARG, "step must be >= 1");
-    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f && hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
-        return fail(ZPP_ERR_ARG, "betas must lie in [0,1)");
-    if (s->pending_acc >= 0)
-        return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
-    for (int64_t m = 0; m < s->U; ++m)
-        if (s->mb_state[m] == MB_BIN)
-            return fail(ZPP_ERR_STATE, "micro-batch %d has its input gradient but not its weight gradient", (int)m);
     AdamArgs a;
-    a.lr = hp->lr;
-    a.beta1 = hp->beta1;
-    a.beta2 = hp->beta2;
-    a.eps = hp->eps;
-    a.wd = hp->weight_decay;
-    a.grad_scale = hp->grad_scale;
-    a.omb1 = (float)(1.0 - (double)hp->beta1);
-    a.omb2 = (float)(1.0 - (double)hp->beta2);
-    a.c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
-    a.c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
-    a.decoupled = hp->decoupled_wd ? 1 : 0;
-    a.zero_grad = hp->zero_grad ? 1 : 0;
+    if (zpp_status e = adam_args(s, hp, &a)) return e;
     {
         ProfScope prof(ZPP_PROF_ADAM, (a.zero_grad ? 32.0 : 28.0) * count, (hipStream_t)hip_stream);
         ZPP_TRY(launch_adam(s->P + offset, s->M + offset, s->V + offset, s->G + offset, count, a,
@@ -925,6 +939,61 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
     }
     if (count) s->materialized = false;
     return ZPP_OK;
+}
+
+zpp_status shard_adam_step_ranges(zpp_stage *s, const zpp_adam_range *ranges, int32_t n_ranges, const zpp_adam *hp,
+                                  void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (n_ranges < 0 || (n_ranges > 0 && !ranges)) return fail(ZPP_ERR_ARG, "ranges is NULL or n_ranges negative");
+    uint64_t end = 0, total = 0;
+    for (int32_t i = 0; i < n_ranges; ++i) {
+        const zpp_adam_range &r = ranges[i];
+        if (r.offset > s->N || r.count > s->N - r.offset)
+            return fail(ZPP_ERR_ARG, "range %d [%llu, +%llu) outside the shard of %llu elements", i,
+                        (unsigned long long)r.offset, (unsigned long long)r.count, (unsigned long long)s->N);
+        if (r.offset < end) return fail(ZPP_ERR_ARG, "range %d overlaps its predecessor or is out of order", i);
+        if (r.offset % 4 || r.count % 4) return fail(ZPP_ERR_ALIGN, "range %d: offset and count must be multiples of 4", i);
+        end = r.offset + r.count;
+        total += r.count;
+    }
+    AdamArgs a;
+    if (zpp_status e = adam_args(s, hp, &a)) return e;
+    ProfScope prof(ZPP_PROF_ADAM, (a.zero_grad ? 32.0 : 28.0) * total, (hipStream_t)hip_stream);
+    for (int32_t base = 0; base < n_ranges; base += kAdamRanges) {
+        AdamRanges tab{};
+        tab.n = std::min<int32_t>(kAdamRanges, n_ranges - base);
+        for (int32_t i = 0; i < tab.n; ++i) {
+            tab.offset[i] = ranges[base + i].offset;
+            tab.count[i] = ranges[base + i].count;
+            tab.lr[i] = ranges[base + i].lr;
+            tab.wd[i] = ranges[base + i].weight_decay;
+        }
+        ZPP_TRY(launch_adam_ranges(s->P, s->M, s->V, s->G, tab, a, (hipStream_t)hip_stream));
+    }
+    if (total) s->materialized = false;
+    return ZPP_OK;
+}
+
+int32_t zpp_stage_decay_ranges(const zpp_stage *s, float lr, float weight_decay, zpp_adam_range *out, int32_t capacity)
+{
+    if (!s) return 0;
+    int32_t n = 0;
+    float last_wd = 0.0f;
+    uint64_t last_end = 0;
+    for (const Tensor &t : s->layout) {
+        const float wd = t.rows > 1 ? weight_decay : 0.0f;  // matrices decay; gains, offsets and biases do not
+        const uint64_t cnt = t.rows * t.cols;
+        if (n > 0 && last_wd == wd && last_end == t.offset) {
+            if (out && n <= capacity) out[n - 1].count += cnt;
+        } else {
+            if (out && n < capacity) out[n] = zpp_adam_range{t.offset, cnt, lr, wd};
+            ++n;
+        }
+        last_wd = wd;
+        last_end = t.offset + cnt;
+    }
+    return n;
 }
 
 zpp_status zpp_stage_end_unit(zpp_stage *s)

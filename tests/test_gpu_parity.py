@@ -97,6 +97,56 @@ def test_flat_accumulate(n):
     assert n == 0 or np.abs(G.cpu().numpy() - ref).max() <= 1e-6 * max(1.0, np.abs(ref).max())
 
 
+@pytest.mark.parametrize("name", ["cfg1_tiny_gpt_fp32", "small_gpt_5_blocks"])
+def test_ranged_adam_matches_oracle_per_range(name):
+    """One launch over many ranges, each with its own lr and weight decay (none on gains, offsets and
+    biases), against the oracle's Adam called range by range; elements outside the ranges stay untouched."""
+    sh = synth.CONFIGS[name] if name in synth.CONFIGS else small(0, 1, n_blocks=5)
+    st = zpp.Stage(sh)
+    n = st.N
+    rng = np.random.default_rng(5)
+    p0 = rng.normal(0, 0.02, n).astype(np.float32)
+    g0 = rng.normal(0, 1e-3, n).astype(np.float32)
+    m0 = rng.normal(0, 1e-4, n).astype(np.float32)
+    v0 = rng.normal(0, 1e-4, n).astype(np.float32) ** 2
+    hp = f32hp()
+    ranges = st.decay_ranges(hp["lr"], 0.1)
+    assert len(ranges) > 32 or name.startswith("cfg1")      # the five-block case needs more than one launch
+    # leave a hole: drop one range, and give another its own learning rate
+    hole = ranges.pop(3)
+    ranges[1] = (ranges[1][0], ranges[1][1], 3e-4, ranges[1][3])
+    for t, a in ((st.P, p0), (st.M, m0), (st.V, v0), (st.G, g0)):
+        t.copy_(torch.from_numpy(a))
+    kw = {k: v for k, v in synth.ADAM.items()}
+    st.adam_step_ranges(ranges, step=3, zero_grad=1, **kw)
+    torch.cuda.synchronize()
+    o = oracle.OracleStage(sh, "f32")
+    o.P[:], o.M[:], o.V[:], o.G[:] = p0, m0, v0, g0
+    ohp = {k: v for k, v in hp.items() if k not in ("lr", "weight_decay")}
+    for off, cnt, lr, wd in ranges:
+        o.adam(off, cnt, step=3, zero_grad=1, lr=float(np.float32(lr)), weight_decay=float(np.float32(wd)), **ohp)
+    for nm, a, b in (("p", st.P, o.P), ("m", st.M, o.M), ("v", st.V, o.V)):
+        a = a.cpu().numpy()
+        assert (np.abs(a - b) / np.maximum(np.abs(b), 1e-30)).max() <= TOL_ADAM, nm
+    g = st.G.cpu().numpy()
+    h0, h1 = hole[0], hole[0] + hole[1]
+    assert np.array_equal(g[h0:h1], g0[h0:h1]) and np.count_nonzero(g[:h0]) == 0 and np.count_nonzero(g[h1:]) == 0
+    assert np.array_equal(st.P.cpu().numpy()[h0:h1], p0[h0:h1])
+    # with the same settings in every range the ranged launch equals the plain one bit for bit
+    for t, a in ((st.P, p0), (st.M, m0), (st.V, v0), (st.G, g0)):
+        t.copy_(torch.from_numpy(a))
+    st.adam_step_ranges([(r[0], r[1], synth.ADAM["lr"], synth.ADAM["weight_decay"]) for r in st.decay_ranges(0, 0)],
+                        step=2, **kw)
+    p_ranged = st.P.clone()
+    for t, a in ((st.P, p0), (st.M, m0), (st.V, v0), (st.G, g0)):
+        t.copy_(torch.from_numpy(a))
+    st.adam_step(step=2, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(p_ranged.view(torch.int32), st.P.view(torch.int32))
+    st.close()
+    o.close()
+
+
 # ------------------------------------------------------------------ whole unit, fp32 (configs[0])
 def test_cfg1_tiny_gpt_fp32_full_unit_and_adam():
     sh = synth.CONFIGS["cfg1_tiny_gpt_fp32"]

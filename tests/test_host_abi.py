@@ -198,6 +198,39 @@ def test_device_memory_terms_follow_the_weight_memory_formula():
         d.close()
 
 
+def test_decay_ranges_cover_the_shard_and_ranged_adam_checks_its_arguments():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    st = zpp.Stage(sh, allocate=False)
+    ranges = st.decay_ranges(1e-3, 0.1)
+    layout = st.layout()
+    # ascending, gap-free cover of [0, N)
+    assert ranges[0][0] == 0 and ranges[-1][0] + ranges[-1][1] == st.N
+    for a, b in zip(ranges, ranges[1:]):
+        assert a[0] + a[1] == b[0] and a[3] != b[3]
+    # every tensor lies inside one range with the decay its shape calls for
+    for name, off, r, c in layout:
+        hit = [x for x in ranges if x[0] <= off and off + r * c <= x[0] + x[1]]
+        assert len(hit) == 1, name
+        assert (hit[0][3] > 0) == (r > 1), name
+    L = zpp.lib()
+    fake = 0x10000
+    st.bind_raw(fake, fake, fake, fake, fake, st.workspace_bytes)
+    hp = binding._adam_struct(**synth.ADAM)
+
+    def status(rs, hp_=hp):
+        arr = (binding._AdamRange * max(len(rs), 1))(*[binding._AdamRange(*r) for r in rs])
+        return L.shard_adam_step_ranges(st._h, arr, len(rs), ctypes.byref(hp_) if hp_ else None, None)
+
+    assert status([(0, 8, 1e-3, 0.0), (4, 8, 1e-3, 0.0)]) == -1          # overlap
+    assert status([(16, 8, 1e-3, 0.0), (0, 8, 1e-3, 0.0)]) == -1         # out of order
+    assert status([(0, st.N + 4, 1e-3, 0.0)]) == -1
+    assert status([(2, 8, 1e-3, 0.0)]) == -3
+    assert status([(0, 6, 1e-3, 0.0)]) == -3
+    assert status([(0, 8, 1e-3, 0.0)], None) == -1
+    assert status([]) == 0                                               # nothing to do, nothing launched
+    st.close()
+
+
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(FileNotFoundError):
         zpp.load_library(str(tmp_path / "libzpp.so"))
