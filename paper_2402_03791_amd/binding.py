@@ -23,6 +23,8 @@ EXPORTS = [
     "zpp_device_create", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
     "zpp_device_workspace_bytes", "zpp_device_memory_terms", "zpp_device_stage", "zpp_device_bind",
     "device_forward_unit", "device_backward_unit", "device_adam_step", "zpp_device_end_unit",
+    "zpp_plan_tp_comm", "zpp_plan_zeropp_comm", "zpp_plan_zeropp_wins", "zpp_plan_bubbles", "zpp_plan_max_memory",
+    "zpp_plan_pp_method", "zpp_plan_choose",
 ]
 
 
@@ -42,6 +44,17 @@ class _Config(ctypes.Structure):
 class _AdamRange(ctypes.Structure):
     _fields_ = [("offset", ctypes.c_uint64), ("count", ctypes.c_uint64), ("lr", ctypes.c_float),
                 ("weight_decay", ctypes.c_float)]
+
+
+class PlanModel(ctypes.Structure):
+    """zpp_plan_model of include/zpp_plan.h (the paper's symbols)."""
+    _fields_ = [(n, ctypes.c_int64) for n in ("L", "h", "s", "b", "B", "P", "D")] + \
+               [("Mw", ctypes.c_double), ("Ma", ctypes.c_double)]
+
+
+class _PlanChoice(ctypes.Structure):
+    _fields_ = [("U", ctypes.c_int64), ("V", ctypes.c_int64), ("memory", ctypes.c_double),
+                ("comm", ctypes.c_double), ("bubbles", ctypes.c_double)]
 
 
 class _Adam(ctypes.Structure):
@@ -106,6 +119,18 @@ def load_library(path: str | None = None):
     L.device_backward_unit.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), f32, vp, vp]
     L.device_adam_step.argtypes = [vp, ctypes.POINTER(_Adam), vp]
     L.zpp_device_end_unit.argtypes = [vp]
+    pm, dbl = ctypes.POINTER(PlanModel), ctypes.c_double
+    L.zpp_plan_tp_comm.argtypes = [pm]
+    L.zpp_plan_tp_comm.restype = dbl
+    L.zpp_plan_zeropp_comm.argtypes = [pm, i64]
+    L.zpp_plan_zeropp_comm.restype = dbl
+    L.zpp_plan_zeropp_wins.argtypes = [pm, i64]
+    L.zpp_plan_bubbles.argtypes = [pm, i64]
+    L.zpp_plan_bubbles.restype = dbl
+    L.zpp_plan_max_memory.argtypes = [pm, i64, i64] + [ctypes.POINTER(dbl)] * 3
+    L.zpp_plan_max_memory.restype = dbl
+    L.zpp_plan_pp_method.argtypes = [pm, i32, i64] + [ctypes.POINTER(dbl)] * 3
+    L.zpp_plan_choose.argtypes = [pm, dbl, ctypes.POINTER(_PlanChoice)]
     L.zpp_profile_enable.argtypes = [i32]
     L.zpp_profile_reset.restype = None
     L.zpp_profile_read.argtypes = [i32, ctypes.POINTER(u64), ctypes.POINTER(ctypes.c_double),
@@ -378,6 +403,45 @@ class Device:
 
     def end_unit(self):
         _check(lib().zpp_device_end_unit(self._h))
+
+
+# ---- cost model and planner (include/zpp_plan.h) ---------------------------------------------------
+PP_METHODS = ["gpipe", "1f1b", "interleaved_1f1b", "zeropp", "zeropp_recompute"]
+
+
+def plan_tp_comm(m: PlanModel) -> float:
+    return lib().zpp_plan_tp_comm(ctypes.byref(m))
+
+
+def plan_zeropp_comm(m: PlanModel, U: int) -> float:
+    return lib().zpp_plan_zeropp_comm(ctypes.byref(m), U)
+
+
+def plan_zeropp_wins(m: PlanModel, U: int) -> bool:
+    return bool(lib().zpp_plan_zeropp_wins(ctypes.byref(m), U))
+
+
+def plan_bubbles(m: PlanModel, U: int) -> float:
+    return lib().zpp_plan_bubbles(ctypes.byref(m), U)
+
+
+def plan_max_memory(m: PlanModel, U: int, V: int) -> dict:
+    a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    tot = lib().zpp_plan_max_memory(ctypes.byref(m), U, V, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    return {"total": tot, "weights_partitioned": a.value, "weights_gathered": b.value, "activations": c.value}
+
+
+def plan_pp_method(m: PlanModel, method: str, V: int = 1) -> dict:
+    a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib().zpp_plan_pp_method(ctypes.byref(m), PP_METHODS.index(method), V, ctypes.byref(a), ctypes.byref(b),
+                                    ctypes.byref(c)))
+    return {"bubble_ratio": a.value, "weight_memory": b.value, "activation_memory": c.value}
+
+
+def plan_choose(m: PlanModel, memory_limit: float) -> dict:
+    c = _PlanChoice()
+    _check(lib().zpp_plan_choose(ctypes.byref(m), memory_limit, ctypes.byref(c)))
+    return {"U": c.U, "V": c.V, "memory": c.memory, "comm": c.comm, "bubbles": c.bubbles}
 
 
 PROF_CLASSES = ["gemm", "attn_fwd", "attn_bwd", "accumulate", "adam", "materialize", "other", "gemm_dw"]

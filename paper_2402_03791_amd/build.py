@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzpp.so")
 
-SOURCES = ["stage.cpp", "device.cpp", "flat.hip", "norm.hip", "elementwise.hip", "gemm_f32.hip", "gemm_bf16.hip",
+SOURCES = ["stage.cpp", "device.cpp", "plan.cpp", "flat.hip", "norm.hip", "elementwise.hip", "gemm_f32.hip", "gemm_bf16.hip",
            "attn_simple.hip", "attn_bf16.hip"]
 
 # -packed-fp32-ops is switched off on purpose (packed fp32 VALU forms are not trusted on the test machines);
