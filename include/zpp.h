@@ -1,8 +1,8 @@
 /*
  * zpp.h — C ABI of the ZeroPP stage hot path on one MI355X (gfx950).
  *
- * What one GPU does under the ZeroPP schedule (paper Section 3.1 "ZeRO-compatible pipeline
- * parallelism" and Section 3.2 "ZeRO-3 + PP + DP"): the micro-batches of a pipeline stage run
+ * What one GPU does under the ZeroPP schedule (the pipeline schedule of paper Section 3.1 and its
+ * combination with ZeRO-3 and data parallelism in Section 3.2): the micro-batches of a pipeline stage run
  * back to back inside a scheduling unit of U micro-batches, so that the stage's parameters are
  * gathered once per unit (not once per micro-batch), its gradients are reduced once per unit, and
  * the optimizer step runs on the local partition of the model state.  With one GPU the gather is
@@ -31,7 +31,7 @@
  *   LLaMA (arch 1): norm1.gamma[h] attn.wqkv[3h,h] attn.wo[h,h] norm2.gamma[h]
  *                   mlp.wgate[f,h] mlp.wup[f,h] mlp.wdown[h,f]
  * Rows of wqkv: all of Q (head n = rows n*d .. (n+1)*d-1), then K, then V.  A GPT block holds
- * 4h^2 + 2hf + 9h + f parameters, i.e. the "around 12 h^2" of Section 4.1 when f = 4h.
+ * 4h^2 + 2hf + 9h + f parameters, i.e. the roughly 12 h^2 per block that Section 4.1 counts with, when f = 4h.
  */
 #ifndef ZPP_H
 #define ZPP_H
@@ -61,7 +61,7 @@ enum { ZPP_GELU_TANH = 0, ZPP_GELU_ERF = 1 };
 typedef struct {
     int32_t arch;          /* ZPP_ARCH_GPT: pre-LN LayerNorm, biases, GeLU MLP.
                               ZPP_ARCH_LLAMA: RMSNorm, rotary embedding on Q and K, SwiGLU MLP, no biases */
-    int32_t n_blocks;      /* transformer blocks in the stage ("contiguous network layers", Section 2.1) */
+    int32_t n_blocks;      /* transformer blocks in the stage (a stage is a run of consecutive layers, Section 2.1) */
     int32_t hidden;        /* h */
     int32_t n_heads;       /* head dim d = h / n_heads */
     int32_t ffn;           /* f, MLP width */
@@ -171,7 +171,7 @@ zpp_status stage_backward_accumulate(zpp_stage *stage, int32_t micro_batch, cons
                                      float scale, void *hip_stream);
 
 /* The backward of a micro-batch as the two separate tasks of Section 3.1.1 (the split of Section 2.3:
- * "input gradient computation" dX = dY.W and "weight gradient computation" dW = dY^T.X), so that a
+ * the input-gradient computation dX = dY.W and the weight-gradient computation dW = dY^T.X), so that a
  * scheduler can run the weight-gradient task later, e.g. where the pipeline would otherwise idle.
  * Needs a stage created with split_backward = 1 (ZPP_ERR_STATE otherwise).
  *   stage_backward_input(mb): after stage_forward(mb), once.  Computes dx exactly as stage_backward
@@ -190,8 +190,8 @@ zpp_status stage_backward_input(zpp_stage *stage, int32_t micro_batch, const voi
 zpp_status stage_backward_weight(zpp_stage *stage, int32_t micro_batch, int32_t in_place, float scale,
                                  void *hip_stream);
 
-/* The optimizer-step task (Section 3.1.1; Section 3.2.2 "update the parameters corresponding to the
- * partitioned optimizer states"): Adam on elements [offset, offset+count) of P, M, V using G.
+/* The optimizer-step task (Section 3.1.1; Section 3.2.2: each rank updates the parameters whose optimizer
+ * states it holds): Adam on elements [offset, offset+count) of P, M, V using G.
  *   ghat = grad_scale*G (+ wd*p in L2 form); m <- b1 m + (1-b1) ghat; v <- b2 v + (1-b2) ghat^2;
  *   p <- p - lr*( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd*p_old [decoupled form] ).
  * offset and count must be multiples of 4 elements except that offset+count may equal N.
@@ -219,8 +219,8 @@ zpp_status shard_adam_step_ranges(zpp_stage *stage, const zpp_adam_range *ranges
 int32_t zpp_stage_decay_ranges(const zpp_stage *stage, float lr, float weight_decay, zpp_adam_range *out,
                                int32_t capacity);
 
-/* Releases the unit's activation stash slots ("memory allocated by each scheduling unit is released
- * before the next scheduling unit begins", Section 3.1.2) and resets the per-micro-batch states. */
+/* Releases the unit's activation stash slots (a unit gives its memory back before the next unit starts,
+ * Section 3.1.2) and resets the per-micro-batch states. */
 zpp_status zpp_stage_end_unit(zpp_stage *stage);
 
 /* ---- introspection (tests, benchmarks) ------------------------------------------------------- */

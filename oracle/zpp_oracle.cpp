@@ -12,8 +12,8 @@
 //
 // The schedule changes *when* things are communicated, never the numbers, so
 // the oracle is the plain definition of mini-batch training of a stack of
-// transformer blocks (Section 4.1 takes "the core transformer block" with
-// hidden size h and about 12h^2 parameters as its unit): forward, the chain
+// transformer blocks (Section 4.1 reasons about the standard transformer block of
+// hidden size h with about 12h^2 parameters): forward, the chain
 // rule, a sum over micro-batches, one Adam update.  For every linear layer the
 // backward is exactly Section 2.3: input gradient = activation gradient times
 // weights, weight gradient = activation gradient (transposed) times inputs.
