@@ -2,9 +2,12 @@
 """Benchmark of the ZeroPP stage hot path on one MI355X.
 
 A step is one pass of the whole hot path over one scheduling unit of synthetic input:
-stage_materialize_params, U x stage_forward, U x stage_backward_accumulate (or, with
---accumulate separate, U x (stage_backward + stage_accumulate_grads); same results bit for bit),
-shard_adam_step (with zero_grad), zpp_stage_end_unit.  Inputs are resident in HBM before the timed
+stage_materialize_params, U x stage_forward, U x stage_backward_input, then the weight-gradient tasks
+of the unit as one grouped task that adds into G (stage_backward_weight_group), shard_adam_step (with
+zero_grad), zpp_stage_end_unit.  Other orders of the same work: --group g (g micro-batches per
+weight-gradient task; 1 = one by one), --backward fused (U x stage_backward_accumulate), --accumulate
+separate (stage_backward + stage_accumulate_grads); the last three give identical bits, grouping
+changes the summation order inside G.  Inputs are resident in HBM before the timed
 region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3_gpt_6p2b] [--no-cpu-baseline]
@@ -68,15 +71,18 @@ def main():
     ap.add_argument("--accumulate", choices=("in_place", "separate"), default="in_place",
                     help="in_place: stage_backward_accumulate (dW products add into G from their epilogues); "
                          "separate: stage_backward into the staging buffer, then stage_accumulate_grads")
-    ap.add_argument("--backward", choices=("fused", "split"), default="fused",
-                    help="fused: one backward call per micro-batch; split: the input-gradient tasks of all "
-                         "micro-batches of the unit first, then their weight-gradient tasks (same results bit for bit)")
+    ap.add_argument("--backward", choices=("fused", "split"), default="split",
+                    help="split: the input-gradient tasks of all micro-batches of the unit first, then their "
+                         "weight-gradient tasks; fused: one backward call per micro-batch")
     ap.add_argument("--stages", type=int, default=1,
                     help="V > 1: the configuration's blocks as V stages on the device (zpp_device.h): breadth-first "
                          "over the stages, one gathered stage live at a time, the next one's gather on a second stream")
     ap.add_argument("--no-prefetch", action="store_true", help="with --stages: one working-copy slot, gathers in line")
     ap.add_argument("--adam", choices=("uniform", "decay_ranges"), default="uniform",
                     help="decay_ranges: shard_adam_step_ranges with weight decay on matrices only")
+    ap.add_argument("--group", type=int, default=0,
+                    help="with --backward split: weight-gradient tasks of this many micro-batches as one product "
+                         "(stage_backward_weight_group); 0 = the whole unit, 1 = one by one (bit-identical to fused)")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: keep only block inputs, run each block's forward again in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,16 +101,26 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     V = args.stages
+    if V > 1 or args.recompute:
+        args.backward = "fused"       # the device scheduler and recomputation use the fused backward call
+    if args.backward != "split" or sh.compute_dtype != 1:
+        args.group = 1
+    elif args.group == 0:
+        args.group = sh.unit_mbs
+    if args.group > 1 and args.accumulate != "in_place":
+        print("--group > 1 adds into G in place: not with --accumulate separate", file=sys.stderr)
+        sys.exit(2)
     if V > 1:
-        if sh.n_blocks % V or args.backward != "fused" or args.accumulate != "in_place":
-            print("--stages needs a divisor of the block count and the default --backward/--accumulate", file=sys.stderr)
+        if sh.n_blocks % V or args.accumulate != "in_place":
+            print("--stages needs a divisor of the block count and the default --accumulate", file=sys.stderr)
             sys.exit(2)
         full_layout = zpp.Stage(sh, allocate=False).layout()
         st = zpp.Device(sh.replace(n_blocks=sh.n_blocks // V), V, prefetch=not args.no_prefetch,
                         recompute=args.recompute)
         st.N = st.N_total
     else:
-        st = zpp.Stage(sh, device="cuda:0", split_backward=args.backward == "split", recompute=args.recompute)
+        st = zpp.Stage(sh, device="cuda:0", split_backward=args.group if args.backward == "split" else 0,
+                       recompute=args.recompute)
         full_layout = st.layout()
     act = st.act_dtype
 
@@ -143,7 +159,10 @@ def main():
         if args.backward == "split":
             for m in range(sh.unit_mbs):
                 st.backward_input(m, dys[m], dx, stream)
-            for m in range(sh.unit_mbs):
+            for m in range(0, sh.unit_mbs, args.group):
+                if args.group > 1:
+                    st.backward_weight_group(m, min(args.group, sh.unit_mbs - m), 1.0, stream)
+                    continue
                 st.backward_weight(m, args.accumulate == "in_place", 1.0, stream)
                 if args.accumulate != "in_place":
                     st.accumulate_grads(m, 1.0, stream)
@@ -268,7 +287,7 @@ def main():
         "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
-                   "accumulate": args.accumulate, "backward": args.backward, "recompute": args.recompute,
+                   "accumulate": args.accumulate, "backward": args.backward, "weight_task_group": args.group, "recompute": args.recompute,
                    "adam": args.adam, "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
                    "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
         "model_flops_per_step": flops,

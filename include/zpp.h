@@ -73,9 +73,11 @@ typedef struct {
     int32_t gelu_mode;     /* ZPP_GELU_TANH (default) or ZPP_GELU_ERF */
     float norm_eps;        /* epsilon inside the norm's square root */
     float rope_base;       /* rotary base (LLaMA only); angle = position * base^(-2i/d), adjacent pairs */
-    int32_t split_backward; /* 1: the workspace also holds, per (micro-batch, block), what the weight-gradient
+    int32_t split_backward; /* g >= 1: the workspace also holds, per (micro-batch, block), what the weight-gradient
                               task needs from the input-gradient task (each linear layer's dY), so that
-                              stage_backward_input / stage_backward_weight may be used; 0: only the fused calls */
+                              stage_backward_input / stage_backward_weight may be used, and temporaries for
+                              weight-gradient tasks of up to g micro-batches at once
+                              (stage_backward_weight_group); 0: only the fused calls.  At most unit_mbs */
     int32_t recompute;      /* 1: activation recomputation (Section 3.3): stage_forward keeps only each block's
                               input per micro-batch, and the backward calls run a block's forward again
                               (without its last linear layer, whose output backward does not need) right
@@ -189,6 +191,18 @@ zpp_status stage_backward_accumulate(zpp_stage *stage, int32_t micro_batch, cons
 zpp_status stage_backward_input(zpp_stage *stage, int32_t micro_batch, const void *dy, void *dx, void *hip_stream);
 zpp_status stage_backward_weight(zpp_stage *stage, int32_t micro_batch, int32_t in_place, float scale,
                                  void *hip_stream);
+
+/* The weight-gradient tasks of micro-batches [first, first + count) as one: since the gradient of the unit
+ * is the sum over its micro-batches (Section 3.2.1 reduces it once per unit), each weight-gradient product
+ * runs once over the concatenated tokens, dW += scale * [dY_first; ...]^T . [X_first; ...] with
+ * K = count * T, so G is read and written once per group instead of once per micro-batch and the
+ * product has a longer K loop.  Always in place (adds into G).  Needs every micro-batch of the group to
+ * have had its stage_backward_input, count <= split_backward of the configuration, the bf16 path and
+ * sizes in multiples of 64 (ZPP_ERR_UNSUPPORTED otherwise: use stage_backward_weight).  The sum over
+ * the group's micro-batches is formed inside the product's fp32 accumulation, so G differs from the
+ * one-by-one result by summation order only (not bit-identical). */
+zpp_status stage_backward_weight_group(zpp_stage *stage, int32_t first, int32_t count, float scale,
+                                       void *hip_stream);
 
 /* The optimizer-step task (Section 3.1.1; Section 3.2.2: each rank updates the parameters whose optimizer
  * states it holds): Adam on elements [offset, offset+count) of P, M, V using G.

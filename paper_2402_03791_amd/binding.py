@@ -13,7 +13,7 @@ _lib = None
 EXPORTS = [
     "zpp_stage_create", "zpp_stage_destroy", "zpp_stage_param_count", "zpp_stage_workspace_bytes",
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
-    "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight",
+    "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight", "stage_backward_weight_group",
     "stage_accumulate_grads", "shard_adam_step", "shard_adam_step_ranges", "zpp_stage_decay_ranges",
     "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
@@ -94,6 +94,7 @@ def load_library(path: str | None = None):
     L.stage_backward_accumulate.argtypes = [vp, i32, vp, vp, f32, vp]
     L.stage_backward_input.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward_weight.argtypes = [vp, i32, i32, f32, vp]
+    L.stage_backward_weight_group.argtypes = [vp, i32, i32, f32, vp]
     L.stage_accumulate_grads.argtypes = [vp, i32, f32, vp]
     L.shard_adam_step.argtypes = [vp, u64, u64, ctypes.POINTER(_Adam), vp]
     L.shard_adam_step_ranges.argtypes = [vp, ctypes.POINTER(_AdamRange), i32, ctypes.POINTER(_Adam), vp]
@@ -202,7 +203,7 @@ class Stage:
     """A stage handle.  With ``allocate=True`` it also owns torch tensors for P, G, M, V and the
     workspace and binds them; otherwise call :meth:`bind` with your own tensors."""
 
-    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: bool = False,
+    def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: int = 0,
                  recompute: bool = False):
         self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward),
                                                                                    int(recompute))
@@ -294,6 +295,9 @@ class Stage:
 
     def backward_weight(self, mb: int, in_place: bool = False, scale: float = 1.0, stream=None):
         _check(lib().stage_backward_weight(self._h, mb, int(in_place), scale, _stream_ptr(stream)))
+
+    def backward_weight_group(self, first: int, count: int, scale: float = 1.0, stream=None):
+        _check(lib().stage_backward_weight_group(self._h, first, count, scale, _stream_ptr(stream)))
 
     def accumulate_grads(self, mb: int, scale: float = 1.0, stream=None):
         _check(lib().stage_accumulate_grads(self._h, mb, scale, _stream_ptr(stream)))

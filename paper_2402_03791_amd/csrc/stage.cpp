@@ -327,13 +327,16 @@ PartSizes plan_workspace(zpp_stage *s, uint64_t wcopy_off, uint64_t scratch_off,
     if (s->c.arch == ZPP_ARCH_LLAMA) tmp("dact", T * f, e);
     tmp("delta", (uint64_t)s->c.micro_batch * s->nh * s->c.seq, 4);
     const uint64_t widest = std::max<uint64_t>(3 * h, f1);
+    // split_backward = g > 1: weight-gradient tasks of up to g micro-batches may run as one product over
+    // K = g * T, so the transposed operands and the reduction slots are sized for g micro-batches
+    const uint64_t gmax = std::max<uint64_t>(1, (uint64_t)s->c.split_backward);
     if (s->dt == DT_BF16) {
-        tmp("tA", widest * T, 2);
-        tmp("tB", std::max<uint64_t>(h, f) * T, 2);
+        tmp("tA", widest * T * gmax, 2);
+        tmp("tB", std::max<uint64_t>(h, f) * T * gmax, 2);
     }
     s->red_floats = std::max(colreduce_scratch_floats((int64_t)T, (int64_t)widest),
                              transpose_colsum_scratch_floats((int64_t)T, (int64_t)widest));
-    tmp("redpool", s->red_floats * kRedPerBlock * s->L, 4);  // one slot per column reduction of a backward call
+    tmp("redpool", s->red_floats * kRedPerBlock * s->L * gmax, 4);  // one slot per column reduction of a backward call
     s->finish.reserve(kRedPerBlock * s->L);
     sz.scratch = cur - scratch_off;
     return sz;
@@ -481,6 +484,8 @@ zpp_status zpp_stage_create(const zpp_stage_config *cfg, zpp_stage **out)
         return fail(ZPP_ERR_ARG, "all sizes must be positive");
     if (c.hidden % c.n_heads) return fail(ZPP_ERR_ARG, "hidden (%d) not divisible by n_heads (%d)", c.hidden, c.n_heads);
     if (!(c.norm_eps > 0.0f)) return fail(ZPP_ERR_ARG, "norm_eps must be > 0");
+    if (c.split_backward < 0 || c.split_backward > c.unit_mbs)
+        return fail(ZPP_ERR_ARG, "split_backward must lie in [0, unit_mbs]");
     if (c.recompute && c.split_backward)
         return fail(ZPP_ERR_UNSUPPORTED, "recompute and split_backward exclude each other: the weight-gradient task "
                                          "would need the recomputed activations again");
@@ -872,6 +877,81 @@ zpp_status stage_backward_input(zpp_stage *s, int32_t mb, const void *dy, void *
 zpp_status stage_backward_weight(zpp_stage *s, int32_t mb, int32_t in_place, float scale, void *hip_stream)
 {
     return backward_sequence(s, mb, BWD_WEIGHT, nullptr, nullptr, in_place != 0, scale, hip_stream);
+}
+
+zpp_status stage_backward_weight_group(zpp_stage *s, int32_t first, int32_t count, float scale, void *hip_stream)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    if (count < 1 || first < 0 || first > s->U - count)
+        return fail(ZPP_ERR_ARG, "micro-batches [%d, %d) outside [0,%d)", first, first + count, (int)s->U);
+    if (count > s->c.split_backward)
+        return fail(ZPP_ERR_STATE, "the stage was created with split_backward = %d: groups of at most that many",
+                    s->c.split_backward);
+    const int64_t T = s->T, h = s->h, f = s->f, f1 = s->f1;
+    if (s->dt != DT_BF16 || T % 64 || h % 64 || f % 64)
+        return fail(ZPP_ERR_UNSUPPORTED, "grouped weight-gradient tasks need the bf16 path and sizes in multiples of 64");
+    if (!s->materialized) return fail(ZPP_ERR_STATE, "working copy is stale: call stage_materialize_params");
+    for (int k = 0; k < count; ++k)
+        if (s->mb_state[first + k] != MB_BIN)
+            return fail(ZPP_ERR_STATE, "stage_backward_weight_group: micro-batch %d has no input-gradient task pending",
+                        first + k);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const bool gpt = s->c.arch == ZPP_ARCH_GPT;
+    s->acc_in_place = true;  // gradients go straight into G
+    s->acc_scale = scale;
+    GemmEpi epi;
+    epi.out_f32 = 2;
+    epi.accum_scale = scale;
+    uint16_t *tA = (uint16_t *)s->tp("tA"), *tB = (uint16_t *)s->tp("tB");  // bf16 elements
+    float *pool = (float *)s->tp("redpool");
+    uint64_t used = 0;
+    // The second levels of the column reductions (bias and gain gradients) of one micro-batch add into the
+    // same elements of G as those of the next, so each micro-batch gets its own finishing launch.
+    std::vector<std::vector<FinishItem>> fin((size_t)count);
+    struct Layer {
+        const char *dy, *x, *w, *bias;
+        int64_t in, out;
+    };
+    const Layer gpt_layers[4] = {{"d_y", "g", "mlp.w2", "mlp.b2", f, h}, {"d_u", "n2", "mlp.w1", "mlp.b1", h, f},
+                                 {"d_x1", "attn", "attn.wo", "attn.bo", h, h}, {"d_qkv", "n1", "attn.wqkv", "attn.bqkv", h, 3 * h}};
+    const Layer llama_layers[4] = {{"d_y", "g", "mlp.wdown", nullptr, f, h}, {"d_u", "n2", "mlp.wgate", nullptr, h, f1},
+                                   {"d_x1", "attn", "attn.wo", nullptr, h, h}, {"d_qkv", "n1", "attn.wqkv", nullptr, h, 3 * h}};
+    const Layer *layers = gpt ? gpt_layers : llama_layers;
+    const int64_t K = (int64_t)count * T;
+    for (int blk = (int)s->L - 1; blk >= 0; --blk) {
+        for (int l = 0; l < 4; ++l) {
+            const Layer &ly = layers[l];
+            {
+                // micro-batch k's operands become columns [k*T, (k+1)*T) of the K-contiguous operands
+                ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
+                for (int k = 0; k < count; ++k) {
+                    FinishItem item{};
+                    float *slot = ly.bias ? pool + (used++) * s->red_floats : nullptr;
+                    ZPP_TRY(launch_transpose_pair(s->stash(first + k, blk, ly.dy), T, ly.out, ly.out, tA + (int64_t)k * T, K,
+                                                  ly.bias ? s->Sp(blk, ly.bias) : nullptr, slot, ly.bias ? &item : nullptr,
+                                                  s->stash(first + k, blk, ly.x), T, ly.in, ly.in, tB + (int64_t)k * T, K,
+                                                  st));
+                    if (ly.bias) fin[(size_t)k].push_back(item);
+                }
+            }
+            ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * K * ly.in * ly.out, st,
+                           2.0 * ((double)K * ly.in + (double)K * ly.out) + 8.0 * ly.in * ly.out);
+            ZPP_TRY(launch_gemm_bf16_nt(ly.out, ly.in, K, tA, K, tB, K, s->Sp(blk, ly.w), ly.in, epi, st));
+        }
+        const char *g2 = gpt ? "ln2.gamma" : "norm2.gamma", *g1 = gpt ? "ln1.gamma" : "norm1.gamma";
+        for (int k = 0; k < count; ++k)
+            for (int which = 0; which < 2; ++which) {
+                FinishItem it = s->norm_items[first + k][(size_t)((int)s->L - 1 - blk) * 2 + which];
+                it.out0 = s->Sp(blk, which == 0 ? g2 : g1);
+                it.out1 = gpt ? s->Sp(blk, which == 0 ? "ln2.beta" : "ln1.beta") : nullptr;
+                fin[(size_t)k].push_back(it);
+            }
+    }
+    for (int k = 0; k < count; ++k)
+        ZPP_OTHER(launch_finish_columns(fin[(size_t)k].data(), (int)fin[(size_t)k].size(), st, true, scale));
+    s->acc_in_place = false;
+    for (int k = 0; k < count; ++k) s->mb_state[first + k] = MB_ACC;
+    return ZPP_OK;
 }
 
 zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *hip_stream)

@@ -56,10 +56,11 @@ def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=Fals
     stage_backward + stage_accumulate_grads (then there is no staging snapshot S0).
     split: None, or the order in which the weight-gradient tasks run after ALL input-gradient tasks
     ("ascending", "descending"), or "interleaved" (each weight-gradient task right after its own
-    input-gradient task)."""
+    input-gradient task), or ("group", g): afterwards, g micro-batches per grouped weight-gradient task."""
     import torch
     import paper_2402_03791_amd as zpp
-    st = zpp.Stage(shape, split_backward=split is not None, recompute=recompute)
+    group = split[1] if isinstance(split, tuple) else 0
+    st = zpp.Stage(shape, split_backward=max(group, int(split is not None)), recompute=recompute)
     st.P.copy_(torch.from_numpy(P0))
     st.G.zero_()
     st.materialize_params()
@@ -87,6 +88,9 @@ def run_gpu_unit(shape, P0: np.ndarray, xs, dys, keep_stage=False, in_place=Fals
         if m == 0:
             S0 = to_np(st.region("S"))
         st.accumulate_grads(m, scale)
+    if group:
+        for first in range(0, len(dys), group):
+            st.backward_weight_group(first, min(group, len(dys) - first), scale)
     if split in ("ascending", "descending"):
         order = range(len(dys)) if split == "ascending" else reversed(range(len(dys)))
         for m in order:

@@ -44,6 +44,12 @@ def test_one_block_at_full_shape(name):
     split = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, split="ascending")
     assert np.array_equal(two["G"].view(np.uint32), split["G"].view(np.uint32))
     assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], split["dxs"]))
+    # both weight-gradient tasks as one product over K = 2T (what bench.py times, with the whole unit)
+    grp = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, split=("group", 2))
+    assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], grp["dxs"]))
+    from _harness import rel_err
+    for n_, off, r, c in layout:
+        assert rel_err(grp["G"][off:off + r * c], two["G"][off:off + r * c]) <= 1e-5, n_
     # activation recomputation: the block forward runs again inside the backward call
     rc = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, recompute=True)
     assert np.array_equal(two["G"].view(np.uint32), rc["G"].view(np.uint32))

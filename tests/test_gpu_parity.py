@@ -358,6 +358,41 @@ def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, 
     dev.close()
 
 
+@pytest.mark.parametrize("arch,kw,g", [
+    (0, dict(unit_mbs=4), 2), (0, dict(unit_mbs=5, n_blocks=3), 3), (1, dict(unit_mbs=4), 4),
+    (0, dict(micro_batch=2, seq=128, ffn=768, n_heads=4, unit_mbs=3), 2),
+])
+def test_grouped_weight_gradient_tasks(arch, kw, g):
+    """Weight-gradient tasks of g micro-batches as one product over K = g*T: the sum over the group is formed
+    in the product's fp32 accumulator, so G matches the one-by-one result up to summation order, dx exactly."""
+    sh = small(arch, 1, **kw)
+    print(f"grouped W {sh.name} {kw} g={g}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    fused = run_gpu_unit(sh, P0, xs, dys, scale=0.37, in_place=True)
+    grouped = run_gpu_unit(sh, P0, xs, dys, scale=0.37, in_place=True, split=("group", g))
+    for x, y in zip(fused["dxs"], grouped["dxs"]):
+        assert np.array_equal(x, y)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    for n, off, r, c in layout:
+        assert rel_err(grouped["G"][off:off + r * c], fused["G"][off:off + r * c]) <= 1e-5, n
+        assert rel_err(grouped["G"][off:off + r * c], 0.37 * ref["G"][off:off + r * c]) <= TOL_BF16, n
+    # more micro-batches than the configuration allows, and a micro-batch without its input-gradient task
+    st = zpp.Stage(sh, split_backward=g)
+    st.materialize_params()
+    x, dy = to_dev(xs[0], st.act_dtype), to_dev(dys[0], st.act_dtype)
+    for m in range(sh.unit_mbs):
+        st.forward(m, x)
+    st.backward_input(0, dy)
+    for first, count, status in ((0, g + 1, -2 if g + 1 <= sh.unit_mbs else -1), (0, 2, -2), (sh.unit_mbs - 1, 2, -1)):
+        with pytest.raises(zpp.ZppError) as e:
+            st.backward_weight_group(first, count)
+        assert e.value.status == status, (first, count)
+    st.backward_weight_group(0, 1)
+    st.close()
+
+
 def test_split_backward_state_machine():
     sh = small(0, 1)
     st = zpp.Stage(sh, split_backward=True)
