@@ -101,8 +101,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     V = args.stages
-    if V > 1 or args.recompute:
-        args.backward = "fused"       # the device scheduler and recomputation use the fused backward call
+    if args.recompute:
+        args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
     if args.backward != "split" or sh.compute_dtype != 1:
         args.group = 1
     elif args.group == 0:
@@ -116,7 +116,7 @@ def main():
             sys.exit(2)
         full_layout = zpp.Stage(sh, allocate=False).layout()
         st = zpp.Device(sh.replace(n_blocks=sh.n_blocks // V), V, prefetch=not args.no_prefetch,
-                        recompute=args.recompute)
+                        recompute=args.recompute, split_backward=args.group if args.backward == "split" else 0)
         st.N = st.N_total
     else:
         st = zpp.Stage(sh, device="cuda:0", split_backward=args.group if args.backward == "split" else 0,

@@ -62,7 +62,9 @@ zpp_status device_forward_unit(zpp_device *dev, const void *const *x, void *cons
 
 /* Backward phase of the unit: for v = V-1 .. 0: gather stage v again unless its working copy is still in
  * a slot (the second gather of Section 3.2.1), then stage_backward_accumulate(scale) of its U
- * micro-batches.  dy, dx: as x, y. */
+ * micro-batches; or, when the configuration has split_backward = g > 0, the stage's U input-gradient
+ * tasks followed by its weight-gradient tasks in groups of g micro-batches (stage_backward_weight_group;
+ * one by one where grouping is not supported).  dy, dx: as x, y. */
 zpp_status device_backward_unit(zpp_device *dev, const void *const *dy, void *const *dx, float scale,
                                 void *stream, void *side_stream);
 

@@ -345,8 +345,9 @@ class Device:
     torch tensors for P, G, M, V (V * N elements, stage v at [v*N, (v+1)*N)) and the workspace."""
 
     def __init__(self, cfg, n_stages: int, prefetch: bool = True, device: str | None = "cuda:0",
-                 allocate: bool = True, recompute: bool = False):
-        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, 0, int(recompute))
+                 allocate: bool = True, recompute: bool = False, split_backward: int = 0):
+        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward),
+                                                                                   int(recompute))
         self._h = ctypes.c_void_p()
         c = self.cfg._c()
         _check(lib().zpp_device_create(ctypes.byref(c), n_stages, int(prefetch), ctypes.byref(self._h)))

@@ -11,6 +11,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <vector>
 
 using namespace zpp;
@@ -105,8 +106,9 @@ zpp_status ensure_events(zpp_device *d)
 
 // One phase of a unit: the stages in ascending or descending order, each with its U micro-batches back
 // to back.
-template <class PerMicroBatch>
-zpp_status run_phase(zpp_device *d, bool descending, hipStream_t main, hipStream_t side, PerMicroBatch &&body)
+template <class PerMicroBatch, class PerStage>
+zpp_status run_phase(zpp_device *d, bool descending, hipStream_t main, hipStream_t side, PerMicroBatch &&body,
+                     PerStage &&after_stage)
 {
     if (d->slots < 2) side = nullptr;
     if (zpp_status e = ensure_events(d)) return e;
@@ -121,6 +123,7 @@ zpp_status run_phase(zpp_device *d, bool descending, hipStream_t main, hipStream
         if (zpp_status e = acquire(d, v, main)) return e;
         for (int m = 0; m < d->U; ++m)
             if (zpp_status e = body(v, m)) return e;
+        if (zpp_status e = after_stage(v)) return e;
         if (zpp_status e = release(d, v, main)) return e;
         if (d->slots == 1 && i + 1 < d->V)
             if (zpp_status e = gather(d, next, main, side)) return e;
@@ -229,9 +232,12 @@ zpp_status device_forward_unit(zpp_device *d, const void *const *x, void *const 
 {
     if (zpp_status e = check(d, true)) return e;
     if (!x || !y) return set_error(ZPP_ERR_ARG, "x/y is NULL");
-    return run_phase(d, false, (hipStream_t)stream, (hipStream_t)side_stream, [&](int v, int m) {
-        return stage_forward(d->st[v], m, x[(size_t)v * d->U + m], y[(size_t)v * d->U + m], stream);
-    });
+    return run_phase(
+        d, false, (hipStream_t)stream, (hipStream_t)side_stream,
+        [&](int v, int m) {
+            return stage_forward(d->st[v], m, x[(size_t)v * d->U + m], y[(size_t)v * d->U + m], stream);
+        },
+        [](int) { return ZPP_OK; });
 }
 
 zpp_status device_backward_unit(zpp_device *d, const void *const *dy, void *const *dx, float scale, void *stream,
@@ -239,9 +245,32 @@ zpp_status device_backward_unit(zpp_device *d, const void *const *dy, void *cons
 {
     if (zpp_status e = check(d, true)) return e;
     if (!dy || !dx) return set_error(ZPP_ERR_ARG, "dy/dx is NULL");
-    return run_phase(d, true, (hipStream_t)stream, (hipStream_t)side_stream, [&](int v, int m) {
-        return stage_backward_accumulate(d->st[v], m, dy[(size_t)v * d->U + m], dx[(size_t)v * d->U + m], scale, stream);
-    });
+    // split_backward = g in the configuration: the stage's input-gradient tasks first, then its
+    // weight-gradient tasks in groups of g micro-batches (one by one where grouping is not supported)
+    const int g = d->cfg.split_backward;
+    return run_phase(
+        d, true, (hipStream_t)stream, (hipStream_t)side_stream,
+        [&](int v, int m) {
+            const void *dyp = dy[(size_t)v * d->U + m];
+            void *dxp = dx[(size_t)v * d->U + m];
+            return g > 0 ? stage_backward_input(d->st[v], m, dyp, dxp, stream)
+                         : stage_backward_accumulate(d->st[v], m, dyp, dxp, scale, stream);
+        },
+        [&](int v) -> zpp_status {
+            if (g <= 0) return ZPP_OK;
+            for (int first = 0; first < d->U; first += g) {
+                const int count = std::min(g, d->U - first);
+                zpp_status e = count > 1 ? stage_backward_weight_group(d->st[v], first, count, scale, stream)
+                                         : ZPP_ERR_UNSUPPORTED;
+                if (e == ZPP_ERR_UNSUPPORTED) {
+                    e = ZPP_OK;
+                    for (int m = first; m < first + count && e == ZPP_OK; ++m)
+                        e = stage_backward_weight(d->st[v], m, 1, scale, stream);
+                }
+                if (e) return e;
+            }
+            return ZPP_OK;
+        });
 }
 
 zpp_status device_adam_step(zpp_device *d, const zpp_adam *hp, void *stream)

@@ -296,11 +296,11 @@ def test_activation_recomputation_reproduces_the_stashed_run(arch, dtype, kw):
     compare_units(sh, rc, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
 
 
-@pytest.mark.parametrize("arch,dtype,V,per,prefetch", [
-    (0, 1, 2, 2, True), (0, 1, 2, 2, False), (1, 1, 4, 1, True), (0, 0, 2, 1, True), (0, 1, 3, 1, True),
-    (1, 1, 3, 1, False),
+@pytest.mark.parametrize("arch,dtype,V,per,prefetch,grp", [
+    (0, 1, 2, 2, True, 0), (0, 1, 2, 2, False, 0), (1, 1, 4, 1, True, 0), (0, 0, 2, 1, True, 0), (0, 1, 3, 1, True, 0),
+    (1, 1, 3, 1, False, 0), (0, 1, 2, 2, True, 2), (1, 1, 2, 1, True, 3), (0, 0, 2, 1, True, 2), (0, 1, 2, 1, False, 1),
 ])
-def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, prefetch):
+def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, prefetch, grp):
     """V stages that take turns in one or two working-copy slots (the next one gathered on a second stream
     while the current one computes) against a single stage holding all V * per blocks: two units with an
     Adam step after each, everything bit-identical (same kernels, same operands, same order per tensor)."""
@@ -311,14 +311,25 @@ def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, 
     P0 = synth.make_params(sh_all, oracle.param_layout(sh_all), gain_jitter=0.1)
     xs, dys = make_inputs(sh_all, U)
 
-    st = zpp.Stage(sh_all)
+    st = zpp.Stage(sh_all, split_backward=grp)
     st.P.copy_(torch.from_numpy(P0))
     st.G.zero_()
     ref = []
     for unit in range(2):
         st.materialize_params()
         ys = [st.forward(m, to_dev(xs[m], st.act_dtype)) for m in range(U)]
-        dxs = [st.backward_accumulate(m, to_dev(dys[m], st.act_dtype), scale=0.5) for m in range(U)]
+        if grp == 0:
+            dxs = [st.backward_accumulate(m, to_dev(dys[m], st.act_dtype), scale=0.5) for m in range(U)]
+        else:
+            # input-gradient tasks, then weight-gradient tasks in groups of grp (one by one in fp32)
+            dxs = [st.backward_input(m, to_dev(dys[m], st.act_dtype)) for m in range(U)]
+            for first in range(0, U, grp):
+                count = min(grp, U - first)
+                if count > 1 and dtype == 1:
+                    st.backward_weight_group(first, count, 0.5)
+                else:
+                    for m in range(first, first + count):
+                        st.backward_weight(m, in_place=True, scale=0.5)
         g = st.G.clone()
         st.adam_step(step=unit + 1, zero_grad=1, **synth.ADAM)
         st.end_unit()
@@ -326,7 +337,7 @@ def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, 
         ref.append((ys, dxs, g, st.P.clone()))
     st.close()
 
-    dev = zpp.Device(sh_one, V, prefetch=prefetch)
+    dev = zpp.Device(sh_one, V, prefetch=prefetch, split_backward=grp)
     assert dev.N_total == P0.size
     dev.P.copy_(torch.from_numpy(P0))
     main, side = torch.cuda.current_stream(), torch.cuda.Stream()
