@@ -100,6 +100,11 @@ def main():
     sh = synth.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    props = torch.cuda.get_device_properties(0)
+    # how the peaks used below come about: CUs x clock x 4096 bf16 flop per clock and CU (dense MFMA)
+    device_info = {"name": props.name, "compute_units": props.multi_processor_count,
+                   "peak_bf16_TFLOPs_used": PEAK_BF16_TFLOPS, "peak_hbm_GBps_used": PEAK_HBM_GBS,
+                   "peak_note": "vendor figures: 256 CUs x 2.4 GHz x 4096 bf16 flop/clk/CU = 2.52 PFLOP/s dense; HBM3E 8 TB/s"}
     V = args.stages
     if args.recompute:
         args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
@@ -294,6 +299,7 @@ def main():
         "frac_bf16_peak_whole_step": round(value / PEAK_BF16_TFLOPS, 4),
         "fwd_bwd_TFLOPs": round(flops / (fb_ms * 1e-3) / 1e12, 2) if fb_ms > 0 else None,
         "wall_s_timed": round(wall, 3),
+        "device": device_info,
         "roofline": roofline,
         "hbm_pass": hbm_pass,
         "phases": phases,
