@@ -304,6 +304,38 @@ def main():
         "hbm_pass": hbm_pass,
         "phases": phases,
     }
+    # The same unit through the five calls the interface is named after, one after the other per micro-batch
+    # (materialise, forward, backward into the staging buffer, accumulate pass, Adam), timed the same way,
+    # for comparison with the default order of the work above.
+    if V == 1 and not args.recompute and (args.backward, args.accumulate) != ("fused", "separate"):
+        st2 = zpp.Stage(sh, device="cuda:0")
+        st2.P.copy_(st.P)
+
+        def step5(tt: int):
+            st2.materialize_params(stream)
+            for m in range(sh.unit_mbs):
+                st2.forward(m, xs[m], y, stream)
+            for m in range(sh.unit_mbs):
+                st2.backward(m, dys[m], dx, stream)
+                st2.accumulate_grads(m, 1.0, stream)
+            st2.adam_step(step=tt, zero_grad=1, stream=stream, **adam)
+            st2.end_unit()
+
+        step5(1)
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record(stream)
+        for i in range(args.steps):
+            step5(2 + i)
+        f1.record(stream)
+        torch.cuda.synchronize()
+        ms5 = f0.elapsed_time(f1) / args.steps
+        out["five_call_order"] = {"calls": "stage_materialize_params, U x stage_forward, U x (stage_backward, "
+                                           "stage_accumulate_grads), shard_adam_step",
+                                  "ms_per_step": round(ms5, 3), "value": round(flops / (ms5 * 1e-3) / 1e12, 2),
+                                  "unit": "TFLOP/s"}
+        st2.close()
+        del st2
     if not args.no_cpu_baseline:
         st.close()
         del st, xs, dys
