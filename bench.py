@@ -178,9 +178,9 @@ def main():
                 st.backward(m, dys[m], dx, stream)
                 st.accumulate_grads(m, 1.0, stream)
         if args.adam == "decay_ranges":
-            st.adam_step_ranges(ranges, step=t, zero_grad=1, stream=stream, **adam)
+            st.adam_step_ranges(ranges, step=t, zero_grad=1, write_back=1, stream=stream, **adam)
         else:
-            st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
+            st.adam_step(step=t, zero_grad=1, write_back=1, stream=stream, **adam)
         st.end_unit()
 
     ranges = st.decay_ranges(adam["lr"], adam["weight_decay"]) if args.adam == "decay_ranges" and V == 1 else None

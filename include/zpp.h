@@ -91,6 +91,10 @@ typedef struct {
     int32_t step;          /* t >= 1, used for bias correction */
     int32_t decoupled_wd;  /* 1: p -= lr*wd*p_old (AdamW form).  0: ghat += wd*p (L2 form) */
     int32_t zero_grad;     /* 1: G is zeroed in the same pass */
+    int32_t write_back;    /* 1: the updated parameters are also written into the stage's working copy (the bf16
+                              round-to-nearest-even cast, or the float copy), so that the next
+                              stage_materialize_params need not read P again for it (when the call, or the
+                              ranges, covered the whole shard it only refreshes the transposed copy) */
 } zpp_adam;
 
 /* ---- handle, sizes, layout (host only; no device is touched) -------------------------------- */

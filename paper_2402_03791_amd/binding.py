@@ -59,7 +59,7 @@ class _PlanChoice(ctypes.Structure):
 
 class _Adam(ctypes.Structure):
     _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + \
-               [(n, ctypes.c_int32) for n in ("step", "decoupled_wd", "zero_grad")]
+               [(n, ctypes.c_int32) for n in ("step", "decoupled_wd", "zero_grad", "write_back")]
 
 
 def load_library(path: str | None = None):
@@ -188,8 +188,9 @@ class StageConfig:
                        self.split_backward, self.recompute)
 
 
-def _adam_struct(lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1, zero_grad=0) -> _Adam:
-    return _Adam(lr, beta1, beta2, eps, weight_decay, grad_scale, step, decoupled_wd, zero_grad)
+def _adam_struct(lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1, zero_grad=0,
+                 write_back=0) -> _Adam:
+    return _Adam(lr, beta1, beta2, eps, weight_decay, grad_scale, step, decoupled_wd, zero_grad, write_back)
 
 
 def _stream_ptr(stream):

@@ -165,6 +165,21 @@ __device__ __forceinline__ void adam_one(float &p, float &m, float &v, float &g,
     if (a.zero_grad) g = 0.0f;
 }
 
+// Optional write-back of updated parameters into the working copy (element i of the shard, 4 elements):
+// the cast the next materialise would do, done while the values are in registers.
+__device__ __forceinline__ void adam_write_back(const AdamArgs &a, uint64_t vec, const f32x4 &p)
+{
+    if (!a.wb) return;
+    if (a.wb_bf16) {
+        bf16x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (bf16)p[k];
+        reinterpret_cast<bf16x4 *>(a.wb)[vec] = o;
+    } else {
+        reinterpret_cast<f32x4 *>(a.wb)[vec] = p;
+    }
+}
+
 template <int VPT>
 __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ P, float *__restrict__ M,
                                                    float *__restrict__ V, float *__restrict__ G, uint64_t n,
@@ -200,6 +215,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ P, float 
             nt_store(m[u], reinterpret_cast<f32x4 *>(M) + i);
             nt_store(v[u], reinterpret_cast<f32x4 *>(V) + i);
             if (a.zero_grad) nt_store(g[u], reinterpret_cast<f32x4 *>(G) + i);
+            adam_write_back(a, i, p[u]);
         }
     }
     if (blockIdx.x == 0)
@@ -210,6 +226,10 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ P, float 
             M[j] = mm;
             V[j] = vv;
             if (a.zero_grad) G[j] = gg;
+            if (a.wb) {
+                if (a.wb_bf16) reinterpret_cast<bf16 *>(a.wb)[j] = (bf16)pp;
+                else reinterpret_cast<float *>(a.wb)[j] = pp;
+            }
         }
 }
 
@@ -244,6 +264,7 @@ __global__ __launch_bounds__(256) void adam_ranges_kernel(float *__restrict__ P,
     nt_store(m, reinterpret_cast<f32x4 *>(M) + e);
     nt_store(vv, reinterpret_cast<f32x4 *>(V) + e);
     if (a.zero_grad) nt_store(g, reinterpret_cast<f32x4 *>(G) + e);
+    adam_write_back(a, e, p);
 }
 
 hipError_t launch_adam_ranges(float *P, float *M, float *V, float *G, AdamRanges r, const AdamArgs &a, hipStream_t s)

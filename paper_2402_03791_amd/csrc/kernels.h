@@ -18,6 +18,8 @@ struct AdamArgs {
     float omb1, omb2;  // 1-beta1, 1-beta2, formed in double on the host and rounded once
     float c1, c2;      // bias corrections 1-beta1^t, 1-beta2^t
     int decoupled, zero_grad;
+    void *wb = nullptr;  // optional write-back: bf16 (wb_bf16) or float copy of the new parameters, same indexing as P
+    int wb_bf16 = 0;
 };
 
 // Up to kAdamRanges ranges of one flat shard updated by one launch, each with its own learning rate and

@@ -133,6 +133,8 @@ struct zpp_stage {
     float *P = nullptr, *G = nullptr, *M = nullptr, *V = nullptr;
     unsigned char *ws = nullptr;
     bool bound = false, materialized = false, rope_ready = false;
+    bool w_fresh = false;        // the plain working copy already holds cast(P) (an Adam step wrote it back)
+    bool shared_wcopy = false;   // the working-copy part is a slot shared with other stages (zpp_device)
     std::vector<int> mb_state;
     int pending_acc = -1;
     uint64_t n_materialize = 0, materialize_bytes = 0;
@@ -563,6 +565,7 @@ void attach(zpp_stage *s, float *P, float *G, float *M, float *V, void *base)
     s->bound = true;
     s->materialized = false;
     s->rope_ready = false;
+    s->w_fresh = false;
     s->pending_acc = -1;
     s->mb_state.assign(s->U, MB_IDLE);
     s->norm_items.assign(s->U, {});
@@ -583,6 +586,7 @@ zpp_status zpp_stage_bind(zpp_stage *s, float *P, float *G, float *M, float *V, 
     const PartSizes sz = plan_workspace(s, 0, 0, 0);
     plan_workspace(s, 0, sz.wcopy, sz.wcopy + sz.scratch);
     attach(s, P, G, M, V, workspace);
+    s->shared_wcopy = false;
     return ZPP_OK;
 }
 
@@ -605,6 +609,7 @@ zpp_status zpp::stage_bind_parts(zpp_stage *s, float *P, float *G, float *M, flo
         return fail(ZPP_ERR_ALIGN, "P, G, M, V, the workspace and its parts must be 256-byte aligned");
     plan_workspace(s, wcopy_off, scratch_off, stash_off);
     attach(s, P, G, M, V, base);
+    s->shared_wcopy = true;
     return ZPP_OK;
 }
 
@@ -617,10 +622,12 @@ zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
 {
     if (zpp_status e = check_stage(s, true)) return e;
     hipStream_t st = (hipStream_t)hip_stream;
-    uint64_t bytes = s->N * (4 + s->esz);
+    // an Adam step that wrote the new parameters back has already produced the plain copy
+    const bool plain = !s->w_fresh;
+    uint64_t bytes = plain ? s->N * (4 + s->esz) : 0;
     if (s->dt == DT_BF16) bytes += s->Nmat * 6;
     ProfScope prof(ZPP_PROF_MATERIALIZE, (double)bytes, st);
-    ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
+    if (plain) ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
     if (s->dt == DT_BF16) {
         for (auto &kv : s->wt) {
             const auto &w = kv.second;
@@ -996,6 +1003,14 @@ zpp_status adam_args(zpp_stage *s, const zpp_adam *hp, AdamArgs *a)
     a->c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
     a->decoupled = hp->decoupled_wd ? 1 : 0;
     a->zero_grad = hp->zero_grad ? 1 : 0;
+    a->wb = nullptr;
+    a->wb_bf16 = s->dt == DT_BF16;
+    if (hp->write_back) {
+        if (s->shared_wcopy)
+            return fail(ZPP_ERR_STATE, "write_back needs a working copy of the stage's own (stages of a zpp_device "
+                                       "share theirs)");
+        a->wb = s->ws + s->rW.off;
+    }
     return ZPP_OK;
 }
 
@@ -1012,12 +1027,19 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
         return fail(ZPP_ERR_ALIGN, "offset and count must be multiples of 4 elements");
     AdamArgs a;
     if (zpp_status e = adam_args(s, hp, &a)) return e;
+    if (a.wb) a.wb = (unsigned char *)a.wb + offset * s->esz;  // the kernel indexes from `offset`
     {
-        ProfScope prof(ZPP_PROF_ADAM, (a.zero_grad ? 32.0 : 28.0) * count, (hipStream_t)hip_stream);
+        ProfScope prof(ZPP_PROF_ADAM, ((a.zero_grad ? 32.0 : 28.0) + (a.wb ? (double)s->esz : 0.0)) * count,
+                       (hipStream_t)hip_stream);
         ZPP_TRY(launch_adam(s->P + offset, s->M + offset, s->V + offset, s->G + offset, count, a,
                             (hipStream_t)hip_stream));
     }
-    if (count) s->materialized = false;
+    if (count) {
+        s->materialized = false;
+        // the plain working copy is current only if this call rewrote all of it (or kept up an already
+        // current copy); a step without write-back leaves it behind P
+        s->w_fresh = a.wb && (s->w_fresh || (offset == 0 && count == s->N));
+    }
     return ZPP_OK;
 }
 
@@ -1039,7 +1061,8 @@ zpp_status shard_adam_step_ranges(zpp_stage *s, const zpp_adam_range *ranges, in
     }
     AdamArgs a;
     if (zpp_status e = adam_args(s, hp, &a)) return e;
-    ProfScope prof(ZPP_PROF_ADAM, (a.zero_grad ? 32.0 : 28.0) * total, (hipStream_t)hip_stream);
+    ProfScope prof(ZPP_PROF_ADAM, ((a.zero_grad ? 32.0 : 28.0) + (a.wb ? (double)s->esz : 0.0)) * total,
+                   (hipStream_t)hip_stream);
     for (int32_t base = 0; base < n_ranges; base += kAdamRanges) {
         AdamRanges tab{};
         tab.n = std::min<int32_t>(kAdamRanges, n_ranges - base);
@@ -1051,7 +1074,10 @@ zpp_status shard_adam_step_ranges(zpp_stage *s, const zpp_adam_range *ranges, in
         }
         ZPP_TRY(launch_adam_ranges(s->P, s->M, s->V, s->G, tab, a, (hipStream_t)hip_stream));
     }
-    if (total) s->materialized = false;
+    if (total) {
+        s->materialized = false;
+        s->w_fresh = a.wb && (s->w_fresh || total == s->N);  // disjoint ranges of N elements cover the shard
+    }
     return ZPP_OK;
 }
 

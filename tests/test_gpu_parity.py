@@ -147,6 +147,57 @@ def test_ranged_adam_matches_oracle_per_range(name):
     o.close()
 
 
+@pytest.mark.parametrize("arch,dtype,ranged", [(0, 1, False), (1, 1, True), (0, 0, False), (0, 0, True)])
+def test_adam_write_back_is_the_cast_materialise_would_do(arch, dtype, ranged):
+    sh = small(arch, dtype)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    st = zpp.Stage(sh)
+    st.P.copy_(torch.from_numpy(P0))
+    st.G.copy_(torch.from_numpy(synth.normal_f32(3, 70, st.N, std=1e-3)))
+    st.materialize_params()
+    calls0, bytes0 = st.counters()
+    if ranged:
+        st.adam_step_ranges(st.decay_ranges(synth.ADAM["lr"], 0.1), step=1, write_back=1, **synth.ADAM)
+    else:
+        st.adam_step(step=1, write_back=1, **synth.ADAM)
+    torch.cuda.synchronize()
+    # the plain working copy now equals the cast of the new P, bit for bit
+    expect = torch.empty(st.N, dtype=st.act_dtype, device="cuda")
+    zpp.op_flat_materialize(st.P, expect)
+    view = torch.int16 if dtype else torch.int32
+    assert torch.equal(st.region("W").view(view), expect.view(view))
+    # ... so the next materialise only refreshes the transposed copy (and reads less)
+    st.materialize_params()
+    calls1, bytes1 = st.counters()
+    assert calls1 == calls0 + 1 and bytes1 - bytes0 < bytes0
+    y = st.forward(0, to_dev(xs[0], st.act_dtype)).clone()
+    dx = st.backward_accumulate(0, to_dev(dys[0], st.act_dtype)).clone()
+    torch.cuda.synchronize()
+    ref = zpp.Stage(sh)
+    ref.P.copy_(st.P)
+    ref.G.zero_()
+    ref.materialize_params()
+    y2 = ref.forward(0, to_dev(xs[0], ref.act_dtype))
+    dx2 = ref.backward_accumulate(0, to_dev(dys[0], ref.act_dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(view), y2.view(view)) and torch.equal(dx.view(view), dx2.view(view))
+    # a step without write-back makes the copy stale again: the next materialise reads P in full
+    st.end_unit()
+    st.adam_step(step=2, **synth.ADAM)
+    st.materialize_params()
+    calls2, bytes2 = st.counters()
+    assert bytes2 - bytes1 == bytes0
+    st.close()
+    ref.close()
+    dev = zpp.Device(sh, 2)
+    with pytest.raises(zpp.ZppError) as e:      # the stages of a device share their working-copy slots
+        dev.adam_step(step=1, write_back=1, **synth.ADAM)
+    assert e.value.status == -2
+    dev.close()
+
+
 # ------------------------------------------------------------------ whole unit, fp32 (configs[0])
 def test_cfg1_tiny_gpt_fp32_full_unit_and_adam():
     sh = synth.CONFIGS["cfg1_tiny_gpt_fp32"]
