@@ -301,6 +301,187 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *_
             (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
 }
 
+// ------------------------------------------------------------------------------------ forward, split keys
+// Eight waves on 128 consecutive queries: waves w and w+4 (the two waves of a SIMD) own the same group of
+// 32 queries and split its key tiles between them, wave w the even tiles, wave w+4 the odd ones, each with
+// its own running maximum, row sum and output accumulator; at the end the second wave hands its three
+// through LDS to the first, which merges them (the usual rescale by 2^(m_i - m)).  Key tiles are streamed
+// in pairs, one barrier per pair, so in every interval both waves of a SIMD have a tile to work on and
+// the SIMD interleaves the matrix phase of one with the softmax phase of the other; with one wave per
+// query group the early (short) group of a SIMD leaves the late one running alone for most of the kernel.
+// Work-groups are as heavy as their position in the sequence; the heavy ones are dispatched first.
+__global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
+                                                                float *__restrict__ lse, int seq, int nh, int nb,
+                                                                float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
+    // Heaviest blocks of all heads first, then the next lighter ones: a CU takes its next work-group when it
+    // has finished one, so this order packs the unequal work-groups tightly.  A head keeps its XCD (ids are
+    // dealt round-robin over the 8 XCDs), so its K/V are fetched into one L2.
+    int qb, n, bi;
+    {
+        const int id = blockIdx.x, nv = nh * nb;
+        int blk, v;
+        if ((nv & 7) == 0) {
+            const int j = id >> 3, per = nv >> 3;
+            blk = j / per;
+            v = (j % per) * 8 + (id & 7);
+        } else {
+            blk = id / nv;
+            v = id % nv;
+        }
+        qb = seq / 128 - 1 - blk;
+        n = v % nh;
+        bi = v / nh;
+    }
+    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = wave >> 2, grp = wave & 3;
+    const int g = lane >> 5, c = lane & 31;
+    const int qw0 = 128 * qb + 32 * grp;
+    const int64_t row0 = (int64_t)bi * seq;
+
+    bf16x8 qf[8];
+    {
+        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
+    }
+    TileCopy<8> cp;
+    cp.init(lane, wave, ld);
+    TileAddr ad;
+    ad.init(lane);
+    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
+    const char *vbase = kbase + h * 2;
+    const int64_t tile_stride = (int64_t)kTile * ld * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    const int n_pairs = qb + 1;            // key tiles 2p, 2p+1 cover keys [128p, 128p + 128)
+    const int my_tiles = qw0 / kTile + 1;  // tiles with unmasked entries for this wave's queries
+    auto issue_pair = [&](int p) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint32_t dst = lds0 + ((p & 1) * 2 + t) * 2 * kTileBytes;
+            cp.issue(kbase + (2 * p + t) * tile_stride, dst, wave);
+            cp.issue(vbase + (2 * p + t) * tile_stride, dst + kTileBytes, wave);
+        }
+    };
+    issue_pair(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int p = 0; p < n_pairs; ++p) {
+        if (p + 1 < n_pairs) issue_pair(p + 1);  // into the buffer read in the previous interval
+        const int jt = 2 * p + half;
+        if (jt < my_tiles) {
+            const int kv0 = jt * kTile;
+            const unsigned char *ks = smem + ((p & 1) * 2 + half) * 2 * kTileBytes;
+            const unsigned char *vs = ks + kTileBytes;
+            f32x16 sacc[2];
+            const f32x16 zero16 = {};
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, 0), qf[0], zero16, 0, 0, 0);
+#pragma unroll
+                for (int st = 1; st < 8; ++st)
+                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc[T], 0, 0, 0);
+            }
+            // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c; mask on the diagonal only
+            if (kv0 + kTile - 1 > qw0) {
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (kv > qw0 + c) sacc[T][e] = -INFINITY;
+                    }
+            }
+            float mloc = sacc[0][0];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            const float m_new = fmaxf(m_run, mloc);
+            const float mc = m_new * scale_log2e;
+            float psum = 0.0f;
+            bf16x8 pf[4];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
+                    psum += pe;
+                    pf[2 * T + (e >> 3)][e & 7] = (bf16)pe;
+                }
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+                m_run = m_new;
+            }
+            l_run += psum;
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(vs, ad, t, st), pf[st], oacc[t], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    // merge the two halves of every query group: [64 accumulator values | m | l] x 64 lanes per group
+    float *mg = reinterpret_cast<float *>(smem) + grp * (66 * 64);
+    if (half == 1) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = oacc[t][e];
+        mg[64 * 64 + lane] = m_run;
+        mg[65 * 64 + lane] = l_run;
+    }
+    __syncthreads();
+    if (half == 1) return;
+    {
+        const float m_b = mg[64 * 64 + lane], l_b = mg[65 * 64 + lane];
+        const float m = fmaxf(m_run, m_b);  // this wave always had tile 0, so m is finite
+        const float a_a = fast_exp2((m_run - m) * scale_log2e), a_b = fast_exp2((m_b - m) * scale_log2e);
+        l_run = l_run * a_a + l_b * a_b;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[t][e] = oacc[t][e] * a_a + mg[(t * 16 + e) * 64 + lane] * a_b;
+        m_run = m;
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(oacc[t][e4 * 4 + r] * inv);
+            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
+        }
+    if (g == 0)
+        lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
+            (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+}
+
 // ------------------------------------------------------------------------------------ backward: dQ
 // Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
 // in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
@@ -634,6 +815,9 @@ static hipError_t set_lds(K kern, size_t lds, bool &done)
     return e;
 }
 
+static bool g_attn_fwd_split = true;
+void attn_set_fwd_split(bool on) { g_attn_fwd_split = on; }
+
 hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int64_t b, int64_t seq, int64_t nh,
                            int64_t d, hipStream_t s)
 {
@@ -644,7 +828,13 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
     if (hipError_t e = set_lds(attn_fwd_mfma_kernel<4>, lds4, a4)) return e;
     if (hipError_t e = set_lds(attn_fwd_mfma_kernel<8>, lds8, a8)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
-    if (seq % 256 == 0) {
+    if (seq % 256 == 0 && g_attn_fwd_split) {
+        static bool as = false;
+        if (hipError_t e = set_lds(attn_fwd_split_kernel, lds8, as)) return e;
+        const dim3 grid((unsigned)(seq / 128 * nh * b));
+        attn_fwd_split_kernel<<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b,
+                                                     scale_log2e);
+    } else if (seq % 256 == 0) {
         const dim3 grid((unsigned)(seq / 256 * nh * b));
         attn_fwd_mfma_kernel<8><<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
                                                        (int)b, scale_log2e);
