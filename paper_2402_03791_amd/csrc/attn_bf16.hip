@@ -134,6 +134,27 @@ __device__ __forceinline__ void decode_block(int id, int nblk, int nh, int nb, i
     bi = v / nh;
 }
 
+// Work-group -> (block, head, sample) for work-groups whose work grows with the block index: the heaviest
+// blocks of all heads come first, then the next lighter ones.  A CU takes its next work-group when it has
+// finished one, so this order packs the unequal work-groups tightly.  A head keeps its XCD (ids are dealt
+// round-robin over the 8 XCDs), so its K/V (or Q/dO) rows are fetched into one L2.
+__device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int &blk, int &n, int &bi)
+{
+    const int nv = nh * nb;
+    int k, v;
+    if ((nv & 7) == 0) {
+        const int j = id >> 3, per = nv >> 3;
+        k = j / per;
+        v = (j % per) * 8 + (id & 7);
+    } else {
+        k = id / nv;
+        v = id % nv;
+    }
+    blk = nblk - 1 - k;
+    n = v % nh;
+    bi = v / nh;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -315,25 +336,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
                                                                 float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
-    // Heaviest blocks of all heads first, then the next lighter ones: a CU takes its next work-group when it
-    // has finished one, so this order packs the unequal work-groups tightly.  A head keeps its XCD (ids are
-    // dealt round-robin over the 8 XCDs), so its K/V are fetched into one L2.
     int qb, n, bi;
-    {
-        const int id = blockIdx.x, nv = nh * nb;
-        int blk, v;
-        if ((nv & 7) == 0) {
-            const int j = id >> 3, per = nv >> 3;
-            blk = j / per;
-            v = (j % per) * 8 + (id & 7);
-        } else {
-            blk = id / nv;
-            v = id % nv;
-        }
-        qb = seq / 128 - 1 - blk;
-        n = v % nh;
-        bi = v / nh;
-    }
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -624,6 +628,152 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16
         }
 }
 
+// ------------------------------------------------------------------------------------ backward: dQ, split keys
+// As attn_bwd_dq_mfma_kernel, with the work laid out as in attn_fwd_split_kernel: 128 consecutive queries
+// per work-group, the two waves of a SIMD share a group of 32 queries and take the even / odd key tiles,
+// tiles streamed in pairs; the second wave's partial dQ goes through LDS to the first, which adds it.
+__global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *__restrict__ qkv,
+                                                                   const bf16 *__restrict__ attn,
+                                                                   const bf16 *__restrict__ dattn,
+                                                                   const float *__restrict__ lse,
+                                                                   float *__restrict__ delta, bf16 *__restrict__ dqkv,
+                                                                   int seq, int nh, int nb, float scale,
+                                                                   float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
+    int qb, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
+    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = wave >> 2, grp = wave & 3;
+    const int g = lane >> 5, c = lane & 31;
+    const int qw0 = 128 * qb + 32 * grp;
+    const int64_t row0 = (int64_t)bi * seq;
+
+    bf16x8 qf[8], dof[8];
+    {
+        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
+        const bf16 *dp = dattn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
+            dof[st] = *reinterpret_cast<const bf16x8 *>(dp + 16 * st);
+        }
+    }
+    const int64_t stat = ((int64_t)bi * nh + n) * seq + qw0 + c;
+    const float l2 = lse[stat] * 1.44269504088896340736f;
+    // delta[q] = sum_e dO[q,e] * O[q,e] (both waves of the pair need it; the first one stores it for the
+    // dK kernel, which runs after this one)
+    float dl = 0.0f;
+    {
+        const bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 of = *reinterpret_cast<const bf16x8 *>(op + 16 * st);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[st][k], (float)of[k], dl);
+        }
+        dl += __shfl_xor(dl, 32, 64);
+        if (g == 0 && half == 0) delta[stat] = dl;
+    }
+
+    TileCopy<8> cp;
+    cp.init(lane, wave, ld);
+    TileAddr ad;
+    ad.init(lane);
+    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
+    const char *vbase = kbase + h * 2;
+    const int64_t tile_stride = (int64_t)kTile * ld * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
+
+    f32x16 dqacc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dqacc[t][e] = 0.0f;
+
+    const int n_pairs = qb + 1;
+    const int my_tiles = qw0 / kTile + 1;
+    auto issue_pair = [&](int p) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint32_t dst = lds0 + ((p & 1) * 2 + t) * 2 * kTileBytes;
+            cp.issue(kbase + (2 * p + t) * tile_stride, dst, wave);
+            cp.issue(vbase + (2 * p + t) * tile_stride, dst + kTileBytes, wave);
+        }
+    };
+    issue_pair(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int p = 0; p < n_pairs; ++p) {
+        if (p + 1 < n_pairs) issue_pair(p + 1);
+        const int jt = 2 * p + half;
+        if (jt < my_tiles) {
+            const int kv0 = jt * kTile;
+            const unsigned char *ks = smem + ((p & 1) * 2 + half) * 2 * kTileBytes;
+            const unsigned char *vs = ks + kTileBytes;
+            bf16x8 dsf[4];
+            const bool diag = kv0 + kTile - 1 > qw0;
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                f32x16 sacc, dpacc;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    sacc[e] = 0.0f;
+                    dpacc[e] = 0.0f;
+                }
+#pragma unroll
+                for (int st = 0; st < 8; ++st) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc, 0, 0, 0);
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(vs, ad, T, st), dof[st], dpacc, 0, 0, 0);
+                }
+                if (diag) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (kv > qw0 + c) sacc[e] = -INFINITY;  // p = 2^(-inf) = 0
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l2));
+                    dsf[2 * T + (e >> 3)][e & 7] = (bf16)(pe * (dpacc[e] - dl));
+                }
+            }
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ks, ad, t, st), dsf[st], dqacc[t], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    float *mg = reinterpret_cast<float *>(smem) + grp * (64 * 64);
+    if (half == 1) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = dqacc[t][e];
+    }
+    __syncthreads();
+    if (half == 1) return;
+    bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                o[r] = (bf16)((dqacc[t][e4 * 4 + r] + mg[(t * 16 + e4 * 4 + r) * 64 + lane]) * scale);
+            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
+        }
+}
+
 // ------------------------------------------------------------------------------------ backward: dK, dV
 // Lane = key.  Per query tile: S = Q K^T (operands Q row-wise from LDS, K in registers),
 // P = exp2(S*c - lse[q]).  Two instantiations, so that each fits two waves per SIMD:
@@ -803,6 +953,176 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf1
                                      (int)blockIdx.x - total);
 }
 
+// dK / dV with the work laid out as in attn_fwd_split_kernel: 128 consecutive keys per work-group, the two
+// waves of a SIMD share a group of 32 keys and take the even / odd query tiles (streamed in pairs, from
+// the diagonal to the end of the sequence); the second wave's partial sum goes through LDS to the first.
+// Early key blocks see the most queries and are dispatched first; the dK and dV work-groups of a key
+// block follow each other.
+template <bool DK>
+__device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
+                                                        const float *__restrict__ lse, const float *__restrict__ delta,
+                                                        bf16 *__restrict__ dqkv, int seq, int nh, float scale,
+                                                        float scale_log2e, int kb, int n, int bi)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4][Q tile | dO tile], [4][lse | delta]
+    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = wave >> 2, grp = wave & 3;
+    const int g = lane >> 5, c = lane & 31;
+    const int kvw0 = 128 * kb + 32 * grp;
+    const int64_t row0 = (int64_t)bi * seq;
+
+    bf16x8 kf[8], vf[DK ? 8 : 1];
+    {
+        const bf16 *kp = qkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            kf[st] = *reinterpret_cast<const bf16x8 *>(kp + 16 * st);
+            if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
+        }
+    }
+    TileCopy<8> cq, cd;
+    cq.init(lane, wave, ld);
+    cd.init(lane, wave, h);
+    TileAddr ad;
+    ad.init(lane);
+    const char *qbase = reinterpret_cast<const char *>(qkv + row0 * ld + (int64_t)n * kD);
+    const char *dbase = reinterpret_cast<const char *>(dattn + row0 * h + (int64_t)n * kD);
+    const int64_t q_stride = (int64_t)kTile * ld * 2, d_stride = (int64_t)kTile * h * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
+    const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
+    const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
+    constexpr int S = 4;
+    const uint32_t stat0 = lds0 + S * 2 * kTileBytes;
+    const uint32_t lane4 = lane * 4;
+    const int it0 = 2 * kb, n_pairs = seq / 128 - kb;  // query tiles it0 + 2p, it0 + 2p + 1
+    auto issue_pair = [&](int p) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int it = it0 + 2 * p + t, buf = (p & 1) * 2 + t;
+            cq.issue(qbase + it * q_stride, lds0 + buf * 2 * kTileBytes, wave);
+            cd.issue(dbase + it * d_stride, lds0 + buf * 2 * kTileBytes + kTileBytes, wave);
+            // the per-query statistics travel with the tiles (a 4-byte-per-lane global->LDS load each)
+            if (wave == 0) {
+                const uint32_t dst = stat0 + buf * 512;
+                const float *src = lse_b + it * kTile;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
+            } else if (wave == 1 && DK) {
+                const uint32_t dst = stat0 + buf * 512 + 256;
+                const float *src = del_b + it * kTile;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
+            }
+        }
+    };
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+
+    issue_pair(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int p = 0; p < n_pairs; ++p) {
+        if (p + 1 < n_pairs) issue_pair(p + 1);
+        const int buf = (p & 1) * 2 + half;
+        const int qt0 = (it0 + 2 * p + half) * kTile;
+        if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
+            const unsigned char *qs = smem + buf * 2 * kTileBytes;
+            const unsigned char *ds = qs + kTileBytes;
+            const float *lse_s = reinterpret_cast<const float *>(smem + S * 2 * kTileBytes + buf * 512);
+            const float *del_s = lse_s + 64;
+            bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
+            const bool diag = qt0 < kvw0 + 31;
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+                f32x16 sacc, dpacc;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    sacc[e] = 0.0f;
+                    dpacc[e] = 0.0f;
+                }
+#pragma unroll
+                for (int st = 0; st < 8; ++st) {
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(qs, ad, T, st), kf[st], sacc, 0, 0, 0);
+                    if constexpr (DK)
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
+                }
+                // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
+                if (diag) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        if (kvw0 + c > qt0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3)) sacc[e] = -INFINITY;
+                }
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int qrel = 32 * T + 8 * e4 + 4 * g;
+                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
+                    f32x4 d4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if constexpr (DK) d4 = *reinterpret_cast<const f32x4 *>(del_s + qrel);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int e = e4 * 4 + r;
+                        const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[r] * 1.44269504088896340736f));
+                        frag[2 * T + (e >> 3)][e & 7] = DK ? (bf16)(pe * (dpacc[e] - d4[r])) : (bf16)pe;
+                    }
+                }
+            }
+            const unsigned char *src = DK ? qs : ds;  // dK^T += Q^T dS ; dV^T += dO^T P
+#pragma unroll
+            for (int st = 0; st < 4; ++st)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(src, ad, t, st), frag[st], acc[t], 0, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+
+    float *mg = reinterpret_cast<float *>(smem) + grp * (64 * 64);
+    if (half == 1) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = acc[t][e];
+    }
+    __syncthreads();
+    if (half == 1) return;
+    // K gradient goes to the K part of dqkv (scaled), V gradient to the V part
+    bf16 *out = dqkv + (row0 + kvw0 + c) * ld + (DK ? h : 2 * h) + (int64_t)n * kD;
+    const float oscale = DK ? scale : 1.0f;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                o[r] = (bf16)((acc[t][e4 * 4 + r] + mg[(t * 16 + e4 * 4 + r) * 64 + lane]) * oscale);
+            *reinterpret_cast<bf16x4 *>(out + 32 * t + 8 * e4 + 4 * g) = o;
+        }
+}
+
+__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_split_kernel(const bf16 *__restrict__ qkv,
+                                                                    const bf16 *__restrict__ dattn,
+                                                                    const float *__restrict__ lse,
+                                                                    const float *__restrict__ delta,
+                                                                    bf16 *__restrict__ dqkv, int seq, int nh, int nb,
+                                                                    float scale, float scale_log2e)
+{
+    // the two kinds of work-group of a (key block, head, sample) are told apart by doubling the sample count
+    int blk, n, v;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, 2 * nb, blk, n, v);
+    const int kb = seq / 128 - 1 - blk;  // heavy = early key blocks
+    if (v < nb)
+        attn_bwd_dkv_split_body<true>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v);
+    else
+        attn_bwd_dkv_split_body<false>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v - nb);
+}
+
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
 
 template <class K>
@@ -857,9 +1177,23 @@ static hipError_t launch_attn_bwd_nw(const void *qkv, const void *attn, const vo
     if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<NW>, lds_dkv, a2)) return e;
     const float scale_log2e = scale * 1.44269504088896340736f;
     const int total = (int)(seq / (32 * NW) * nh * b);
+    if (NW == 8 && g_attn_fwd_split) {
+        static bool a3 = false;
+        if (hipError_t e = set_lds(attn_bwd_dq_split_kernel, lds_dq, a3)) return e;
+        attn_bwd_dq_split_kernel<<<dim3((unsigned)(seq / 128 * nh * b)), 512, lds_dq, s>>>(
+            (const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh,
+            (int)b, scale, scale_log2e);
+    } else
     attn_bwd_dq_mfma_kernel<NW><<<dim3((unsigned)total), NW * 64, lds_dq, s>>>(
         (const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh,
         (int)b, scale, scale_log2e);
+    if (NW == 8 && g_attn_fwd_split) {
+        static bool a4 = false;
+        if (hipError_t e = set_lds(attn_bwd_dkv_split_kernel, lds_dkv, a4)) return e;
+        attn_bwd_dkv_split_kernel<<<dim3((unsigned)(2 * (seq / 128) * nh * b)), 512, lds_dkv, s>>>(
+            (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
+            scale_log2e);
+    } else
     attn_bwd_dkv_mfma_kernel<NW><<<dim3((unsigned)(2 * total)), NW * 64, lds_dkv, s>>>(
         (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
         scale_log2e, total);
