@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: keep only block inputs, run each block's forward again in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-five-call-order", action="store_true",
+                    help="skip the extra timing of the unit through the five named calls (keeps a profile to the default step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the path; this build has no multi-GPU leg "
@@ -307,7 +309,8 @@ def main():
     # The same unit through the five calls the interface is named after, one after the other per micro-batch
     # (materialise, forward, backward into the staging buffer, accumulate pass, Adam), timed the same way,
     # for comparison with the default order of the work above.
-    if V == 1 and not args.recompute and (args.backward, args.accumulate) != ("fused", "separate"):
+    if V == 1 and not args.recompute and not args.no_five_call_order and \
+            (args.backward, args.accumulate) != ("fused", "separate"):
         st2 = zpp.Stage(sh, device="cuda:0")
         st2.P.copy_(st.P)
 
