@@ -1,21 +1,20 @@
 // Fused causal attention for bf16, head dim 128, on gfx950 MFMA (v_mfma_f32_32x32x16_bf16).
 //
-// Forward: every wavefront owns a group of 32 queries; a work-group is either four consecutive groups
-// (128 queries) or, when the sequence is a multiple of 256, eight wavefronts: four consecutive groups
-// and their mirror images from the other end of the sequence.  Under the causal mask group i has
-// work proportional to i+1, and the two wavefronts that share a SIMD (w and w+4) hold groups i and
-// G-1-i, so every SIMD of every work-group gets the same amount of work and the whole grid finishes
-// together (plain 128-query work-groups range from 2 to 2s/128 tiles and the launch lasts as long as
-// the heaviest).  Keys/values stream through LDS in tiles of 64 rows (double buffered).  Scores are computed
-// transposed, S^T = K Q^T, so that a lane owns one query column and the softmax row reductions are
-// in-lane plus one exchange with the lane 32 away; the probabilities then feed the second product
-// O^T = V^T P^T straight from the accumulator registers.  The value tile is read with the LDS
-// transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one
+// Forward: a work-group is eight wavefronts on 128 consecutive queries, four groups of 32; the two
+// wavefronts that share a SIMD (w and w+4) own the same group and split its key tiles between them, each
+// with its own online softmax, merged at the end.  Under the causal mask a work-group's work grows with
+// its position in the sequence; the heavy ones are dispatched first, and because both wavefronts of a SIMD
+// always have a tile to work on the SIMD overlaps the matrix phase of one with the softmax phase of the
+// other.  Keys/values stream through LDS in tiles of 64 rows, two pairs of (K, V) tiles, one barrier per
+// pair.  Scores are computed transposed, S^T = K Q^T, so that a lane owns one query column and the softmax
+// row reductions are in-lane plus one exchange with the lane 32 away; the probabilities then feed the
+// second product O^T = V^T P^T straight from the accumulator registers.  The value tile is read with the
+// LDS transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one
 // value column.  The softmax never leaves registers; only O and the log-sum-exp are written.
 //
-// Backward: three kernels without atomics.  dQ: same structure as forward (lane = query), loops over
-// key tiles.  dK and dV: lane = key, loop over query tiles.  P is recomputed from the saved
-// log-sum-exp; delta = rowsum(dO o O) is computed by the dQ kernel and handed to the dK kernel.
+// Backward: two launches without atomics, laid out the same way.  dQ: lane = query, loops over key tiles.
+// dK and dV: lane = key, loop over query tiles.  P is recomputed from the saved log-sum-exp;
+// delta = rowsum(dO o O) is computed by the dQ kernel and handed to the dK kernel.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -38,8 +37,9 @@ constexpr int kTileBytes = kTile * kD * 2;  // 16 KB
 //    the row, bits 0..1 the chunk, again 16 different positions.
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-// Global -> LDS copy of a tile, 16 load instructions shared by the NW waves (4 rows of 256 bytes each):
-// lane i of a load lands at byte 16*i of the 1 KB slot, so it fetches the chunk the swizzle assigns to that place.
+// Global -> LDS copy of a tile, 16 load instructions shared by the NW waves of the work-group (4 rows of
+// 256 bytes each): lane i of a load lands at byte 16*i of the 1 KB slot, so it fetches the chunk the
+// swizzle assigns to that place.
 template <int NW>
 struct TileCopy {
     static constexpr int NL = 16 / NW;  // loads per wave per tile
@@ -66,16 +66,6 @@ struct TileCopy {
         }
     }
 };
-
-// The 32-row group of the sequence that wave `wave` of work-group `blk` owns (n_groups = seq / 32).
-template <int NW>
-__device__ __forceinline__ int wave_group(int blk, int wave, int n_groups)
-{
-    if constexpr (NW == 4)
-        return blk * 4 + wave;
-    else
-        return wave < 4 ? blk * 4 + wave : n_groups - 1 - (blk * 4 + wave - 4);
-}
 
 // Per-lane LDS byte offsets (inside a tile) for the two read patterns.
 struct TileAddr {
@@ -114,30 +104,12 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// Work-group -> (block of the sequence, head, sample) for a 1-D grid of nblk * nh * nb work-groups.
-// Work-groups are dealt round-robin over the 8 XCDs, each with a private L2: all work-groups of one
-// (sample, head) pair are given to the same XCD and to neighbouring dispatch slots, so that the head's
-// K/V (or Q/dO) rows are fetched into one L2 once and shared there, instead of into all eight.
-__device__ __forceinline__ void decode_block(int id, int nblk, int nh, int nb, int &blk, int &n, int &bi)
-{
-    const int nv = nh * nb;
-    int v;
-    if ((nv & 7) == 0) {
-        const int j = id >> 3;
-        blk = j % nblk;
-        v = (j / nblk) * 8 + (id & 7);
-    } else {
-        blk = id % nblk;
-        v = id / nblk;
-    }
-    n = v % nh;
-    bi = v / nh;
-}
-
-// Work-group -> (block, head, sample) for work-groups whose work grows with the block index: the heaviest
-// blocks of all heads come first, then the next lighter ones.  A CU takes its next work-group when it has
-// finished one, so this order packs the unequal work-groups tightly.  A head keeps its XCD (ids are dealt
-// round-robin over the 8 XCDs), so its K/V (or Q/dO) rows are fetched into one L2.
+// Work-group -> (block of the sequence, head, sample) for a 1-D grid of nblk * nh * nb work-groups whose
+// work grows with the block index: the heaviest blocks of all heads come first, then the next lighter
+// ones.  A CU takes its next work-group when it has finished one, so this order packs the unequal
+// work-groups tightly.  Work-groups are dealt round-robin over the 8 XCDs, each with a private L2: all
+// work-groups of one (sample, head) pair go to the same XCD, so the head's K/V (or Q/dO) rows are fetched
+// into one L2 once and shared there, instead of into all eight.
 __device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int &blk, int &n, int &bi)
 {
     const int nv = nh * nb;
@@ -155,17 +127,8 @@ __device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int
     bi = v / nh;
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-// LDS stages of a streamed operand pair: the copies of a pair are issued kStages-1 iterations before
-// it is used.  One iteration of lookahead does not cover the memory round trip (an iteration is
-// ~2000 cycles of MFMA + softmax work); the eight-wave kernels run one work-group per CU and can
-// afford four stages of 32 KB.
-template <int NW>
-constexpr int kStages = NW == 8 ? 4 : 2;
+// LDS holds two pairs of streamed tiles: a pair is copied in while the other is worked on.
+constexpr int kStages = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -175,154 +138,6 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 }
 
 // ------------------------------------------------------------------------------------ forward
-template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_fwd_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                    bf16 *__restrict__ attn,
-                                                                    float *__restrict__ lse, int seq, int nh,
-                                                                    int nb, float scale_log2e)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
-    int qb, n, bi;
-    decode_block(blockIdx.x, seq / (32 * NW), nh, nb, qb, n, bi);
-    // NW == 4: heavy (late) query blocks first; NW == 8: all work-groups are equally heavy
-    if (NW == 4) qb = seq / 128 - 1 - qb;
-    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = lane >> 5, c = lane & 31;
-    const int qw0 = 32 * wave_group<NW>(qb, wave, seq / 32);
-    const int64_t row0 = (int64_t)bi * seq;
-
-    bf16x8 qf[8];
-    {
-        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
-    }
-    TileCopy<NW> cp;
-    cp.init(lane, wave, ld);
-    TileAddr ad;
-    ad.init(lane);
-    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
-    const char *vbase = kbase + h * 2;
-    const int64_t tile_stride = (int64_t)kTile * ld * 2;
-    const uint32_t lds0 = lds_addr_of(smem);
-
-    f32x16 oacc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
-
-    // key tiles up to the last query of the work-group's latest group
-    const int n_tiles = NW == 4 ? (qb * 128 + 128) / kTile : (seq / 32 - 4 * qb) / 2;
-    constexpr int S = kStages<NW>;
-    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;  // copies per wave per (K, V) pair
-#pragma unroll
-    for (int j = 0; j < S - 1; ++j)
-        if (j < n_tiles) {
-            cp.issue(kbase + j * tile_stride, lds0 + j * 2 * kTileBytes, wave);
-            cp.issue(vbase + j * tile_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
-        }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt % S;
-        const bool more = jt + S - 1 < n_tiles;
-        if (more) {
-            const int nb = (jt + S - 1) % S;  // the stage read in the previous iteration
-            cp.issue(kbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes, wave);
-            cp.issue(vbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
-        }
-        const int kv0 = jt * kTile;
-        if (kv0 <= qw0 + 31) {  // wave-uniform: this wave has unmasked entries in the tile
-            const unsigned char *ks = smem + buf * 2 * kTileBytes;
-            const unsigned char *vs = ks + kTileBytes;
-            f32x16 sacc[2];
-            const f32x16 zero16 = {};
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, 0), qf[0], zero16, 0, 0, 0);
-#pragma unroll
-                for (int st = 1; st < 8; ++st)
-                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc[T], 0, 0, 0);
-            }
-            // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c.
-            // Only the tile on the diagonal needs the mask; the running maximum is kept on the raw scores
-            // (the scale is positive) and the scale is folded into the exponent: p = 2^(s*c - m*c).
-            if (kv0 + kTile - 1 > qw0) {
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) sacc[T][e] = -INFINITY;
-                    }
-            }
-            float mloc = sacc[0][0];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float m_new = fmaxf(m_run, mloc);
-            const float mc = m_new * scale_log2e;
-            float psum = 0.0f;
-            bf16x8 pf[4];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
-                    psum += p;
-                    pf[2 * T + (e >> 3)][e & 7] = (bf16)p;
-                }
-            // the accumulators are rescaled only when some query of the wave saw a new maximum
-            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
-                l_run *= alpha;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
-                m_run = m_new;
-            }
-            l_run += psum;
-            // O^T[dv, q] += sum_kv V^T[dv, kv] P^T[kv, q]
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(vs, ad, t, st), pf[st], oacc[t], 0, 0, 0);
-        }
-        // the next pair must have landed; the S-2 pairs after it may stay in flight (copies complete in order)
-        if (more)
-            wait_vmcnt<(S - 2) * PER_TILE>();
-        else
-            wait_vmcnt<0>();
-        __syncthreads();
-    }
-
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    const float inv = 1.0f / l_tot;
-    bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(oacc[t][e4 * 4 + r] * inv);
-            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
-        }
-    if (g == 0)
-        lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
-            (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
-}
-
-// ------------------------------------------------------------------------------------ forward, split keys
 // Eight waves on 128 consecutive queries: waves w and w+4 (the two waves of a SIMD) own the same group of
 // 32 queries and split its key tiles between them, wave w the even tiles, wave w+4 the odd ones, each with
 // its own running maximum, row sum and output accumulator; at the end the second wave hands its three
@@ -489,149 +304,10 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
 // ------------------------------------------------------------------------------------ backward: dQ
 // Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
 // in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
-// gathered from the same key tile through the transposing load.
-template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dq_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                       const bf16 *__restrict__ attn,
-                                                                       const bf16 *__restrict__ dattn,
-                                                                       const float *__restrict__ lse,
-                                                                       float *__restrict__ delta,
-                                                                       bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                       int nb, float scale, float scale_log2e)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [kStages][K tile | V tile]
-    int qb, n, bi;
-    decode_block(blockIdx.x, seq / (32 * NW), nh, nb, qb, n, bi);
-    if (NW == 4) qb = seq / 128 - 1 - qb;
-    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = lane >> 5, c = lane & 31;
-    const int qw0 = 32 * wave_group<NW>(qb, wave, seq / 32);
-    const int64_t row0 = (int64_t)bi * seq;
-
-    bf16x8 qf[8], dof[8];
-    {
-        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
-        const bf16 *dp = dattn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
-            dof[st] = *reinterpret_cast<const bf16x8 *>(dp + 16 * st);
-        }
-    }
-    const int64_t stat = ((int64_t)bi * nh + n) * seq + qw0 + c;
-    const float l2 = lse[stat] * 1.44269504088896340736f;
-    // delta[q] = sum_e dO[q,e] * O[q,e]: this lane holds half of its query's dO row; computed here (and
-    // stored for the dK kernel, which runs after this one) instead of by a kernel of its own
-    float dl = 0.0f;
-    {
-        const bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 of = *reinterpret_cast<const bf16x8 *>(op + 16 * st);
-#pragma unroll
-            for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[st][k], (float)of[k], dl);
-        }
-        dl += __shfl_xor(dl, 32, 64);
-        if (g == 0) delta[stat] = dl;
-    }
-
-    TileCopy<NW> cp;
-    cp.init(lane, wave, ld);
-    TileAddr ad;
-    ad.init(lane);
-    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
-    const char *vbase = kbase + h * 2;
-    const int64_t tile_stride = (int64_t)kTile * ld * 2;
-    const uint32_t lds0 = lds_addr_of(smem);
-
-    f32x16 dqacc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) dqacc[t][e] = 0.0f;
-
-    const int n_tiles = NW == 4 ? (qb * 128 + 128) / kTile : (seq / 32 - 4 * qb) / 2;
-    constexpr int S = kStages<NW>;
-    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;  // copies per wave per (K, V) pair
-#pragma unroll
-    for (int j = 0; j < S - 1; ++j)
-        if (j < n_tiles) {
-            cp.issue(kbase + j * tile_stride, lds0 + j * 2 * kTileBytes, wave);
-            cp.issue(vbase + j * tile_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
-        }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const int buf = jt % S;
-        const bool more = jt + S - 1 < n_tiles;
-        if (more) {
-            const int nb = (jt + S - 1) % S;  // the stage read in the previous iteration
-            cp.issue(kbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes, wave);
-            cp.issue(vbase + (jt + S - 1) * tile_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
-        }
-        const int kv0 = jt * kTile;
-        if (kv0 <= qw0 + 31) {
-            const unsigned char *ks = smem + buf * 2 * kTileBytes;
-            const unsigned char *vs = ks + kTileBytes;
-            bf16x8 dsf[4];
-            const bool diag = kv0 + kTile - 1 > qw0;  // wave-uniform: only the tile on the diagonal needs the mask
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                f32x16 sacc, dpacc;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[e] = 0.0f;
-                    dpacc[e] = 0.0f;
-                }
-#pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(vs, ad, T, st), dof[st], dpacc, 0, 0, 0);
-                }
-                if (diag) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) sacc[e] = -INFINITY;  // p = 2^(-inf) = 0
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l2));
-                    dsf[2 * T + (e >> 3)][e & 7] = (bf16)(p * (dpacc[e] - dl));
-                }
-            }
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ks, ad, t, st), dsf[st], dqacc[t], 0, 0, 0);
-        }
-        if (more)
-            wait_vmcnt<(S - 2) * PER_TILE>();
-        else
-            wait_vmcnt<0>();
-        __syncthreads();
-    }
-    bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(dqacc[t][e4 * 4 + r] * scale);
-            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
-        }
-}
-
-// ------------------------------------------------------------------------------------ backward: dQ, split keys
-// As attn_bwd_dq_mfma_kernel, with the work laid out as in attn_fwd_split_kernel: 128 consecutive queries
-// per work-group, the two waves of a SIMD share a group of 32 queries and take the even / odd key tiles,
-// tiles streamed in pairs; the second wave's partial dQ goes through LDS to the first, which adds it.
+// gathered from the same key tile through the transposing load.  Work laid out as in the forward kernel:
+// 128 consecutive queries per work-group, the two waves of a SIMD share a group of 32 queries and take
+// the even / odd key tiles, tiles streamed in pairs; the second wave's partial dQ goes through LDS to
+// the first, which adds it.
 __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *__restrict__ qkv,
                                                                    const bf16 *__restrict__ attn,
                                                                    const bf16 *__restrict__ dattn,
@@ -779,181 +455,8 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
 // P = exp2(S*c - lse[q]).  Two instantiations, so that each fits two waves per SIMD:
 //   DK = false: dV^T += dO^T P, with dO^T gathered from the dO tile through the transposing load;
 //   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
-// Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy.
-template <bool DK, int NW>
-__device__ __forceinline__ void attn_bwd_dkv_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
-                                                  const float *__restrict__ lse, const float *__restrict__ delta,
-                                                  bf16 *__restrict__ dqkv, int seq, int nh, int nb, float scale,
-                                                  float scale_log2e, int block_id)
-{
-    // [kStages][Q tile | dO tile], then [kStages][lse of the tile's 64 queries | delta of the same].  The per-query
-    // statistics travel with the tiles (a 4-byte-per-lane global->LDS load each): fetching them with
-    // ordinary loads inside the loop would make every use wait, in order, behind the next tile's copies.
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    int kb, n, bi;  // NW == 4: early key blocks see the most queries and come first
-    decode_block(block_id, seq / (32 * NW), nh, nb, kb, n, bi);
-    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int g = lane >> 5, c = lane & 31;
-    const int kvw0 = 32 * wave_group<NW>(kb, wave, seq / 32);
-    const int64_t row0 = (int64_t)bi * seq;
-
-    bf16x8 kf[8], vf[DK ? 8 : 1];
-    {
-        const bf16 *kp = qkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            kf[st] = *reinterpret_cast<const bf16x8 *>(kp + 16 * st);
-            if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
-        }
-    }
-    TileCopy<NW> cq, cd;
-    cq.init(lane, wave, ld);
-    cd.init(lane, wave, h);
-    TileAddr ad;
-    ad.init(lane);
-    const char *qbase = reinterpret_cast<const char *>(qkv + row0 * ld + (int64_t)n * kD);
-    const char *dbase = reinterpret_cast<const char *>(dattn + row0 * h + (int64_t)n * kD);
-    const int64_t q_stride = (int64_t)kTile * ld * 2, d_stride = (int64_t)kTile * h * 2;
-    const uint32_t lds0 = lds_addr_of(smem);
-    const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
-    const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
-    constexpr int S = kStages<NW>;
-    constexpr int PER_TILE = 2 * TileCopy<NW>::NL;
-    const uint32_t stat0 = lds0 + S * 2 * kTileBytes;
-    const uint32_t lane4 = lane * 4;
-    auto issue_stats = [&](int it, int buf) {
-        if (wave == 0) {
-            const uint32_t dst = stat0 + buf * 512;
-            const float *src = lse_b + it * kTile;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-        } else if (wave == 1 && DK) {
-            const uint32_t dst = stat0 + buf * 512 + 256;
-            const float *src = del_b + it * kTile;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-        }
-    };
-
-    f32x16 acc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
-
-    // query tiles from the diagonal of the work-group's earliest group (4 * kb) to the end
-    const int it0 = 2 * kb, n_tiles = seq / kTile;
-#pragma unroll
-    for (int j = 0; j < S - 1; ++j)
-        if (it0 + j < n_tiles) {
-            cq.issue(qbase + (it0 + j) * q_stride, lds0 + j * 2 * kTileBytes, wave);
-            cd.issue(dbase + (it0 + j) * d_stride, lds0 + j * 2 * kTileBytes + kTileBytes, wave);
-            issue_stats(it0 + j, j);
-        }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    for (int it = it0; it < n_tiles; ++it) {
-        const int buf = (it - it0) % S;
-        const bool more = it + S - 1 < n_tiles;
-        if (more) {
-            const int nb = (it - it0 + S - 1) % S;
-            cq.issue(qbase + (it + S - 1) * q_stride, lds0 + nb * 2 * kTileBytes, wave);
-            cd.issue(dbase + (it + S - 1) * d_stride, lds0 + nb * 2 * kTileBytes + kTileBytes, wave);
-            issue_stats(it + S - 1, nb);
-        }
-        const int qt0 = it * kTile;
-        if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
-            const unsigned char *qs = smem + buf * 2 * kTileBytes;
-            const unsigned char *ds = qs + kTileBytes;
-            const float *lse_s = reinterpret_cast<const float *>(smem + S * 2 * kTileBytes + buf * 512);
-            const float *del_s = lse_s + 64;
-            bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
-            const bool diag = qt0 < kvw0 + 31;  // wave-uniform: only the tile on the diagonal needs the mask
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                f32x16 sacc, dpacc;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[e] = 0.0f;
-                    dpacc[e] = 0.0f;
-                }
-#pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(qs, ad, T, st), kf[st], sacc, 0, 0, 0);
-                    if constexpr (DK)
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
-                }
-                // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
-                if (diag) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (kvw0 + c > qt0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3)) sacc[e] = -INFINITY;
-                }
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int qrel = 32 * T + 8 * e4 + 4 * g;
-                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
-                    f32x4 d4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if constexpr (DK) d4 = *reinterpret_cast<const f32x4 *>(del_s + qrel);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int e = e4 * 4 + r;
-                        const float p = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[r] * 1.44269504088896340736f));
-                        frag[2 * T + (e >> 3)][e & 7] = DK ? (bf16)(p * (dpacc[e] - d4[r])) : (bf16)p;
-                    }
-                }
-            }
-            const unsigned char *src = DK ? qs : ds;  // dK^T += Q^T dS ; dV^T += dO^T P
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(src, ad, t, st), frag[st], acc[t], 0, 0, 0);
-        }
-        // waves 0 and 1 carry one more copy per stage (the statistics)
-        if (!more)
-            wait_vmcnt<0>();
-        else if (wave == 0 || (DK && wave == 1))
-            wait_vmcnt<(S - 2) * (PER_TILE + 1)>();
-        else
-            wait_vmcnt<(S - 2) * PER_TILE>();
-        __syncthreads();
-    }
-    // K gradient goes to the K part of dqkv (scaled), V gradient to the V part
-    bf16 *out = dqkv + (row0 + kvw0 + c) * ld + (DK ? h : 2 * h) + (int64_t)n * kD;
-    const float oscale = DK ? scale : 1.0f;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(acc[t][e4 * 4 + r] * oscale);
-            *reinterpret_cast<bf16x4 *>(out + 32 * t + 8 * e4 + 4 * g) = o;
-        }
-}
-
-// dK and dV in one grid: the first `total` work-groups compute dK (the longer ones: three products per
-// tile), the rest dV, so the dV work-groups fill the tail of the dK ones.  total % 8 == 0 keeps the
-// work-group -> XCD assignment of decode_block valid for the second half.
-template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_bwd_dkv_mfma_kernel(const bf16 *__restrict__ qkv,
-                                                                       const bf16 *__restrict__ dattn,
-                                                                       const float *__restrict__ lse,
-                                                                       const float *__restrict__ delta,
-                                                                       bf16 *__restrict__ dqkv, int seq, int nh,
-                                                                       int nb, float scale, float scale_log2e,
-                                                                       int total)
-{
-    if ((int)blockIdx.x < total)
-        attn_bwd_dkv_body<true, NW>(qkv, dattn, lse, delta, dqkv, seq, nh, nb, scale, scale_log2e, blockIdx.x);
-    else
-        attn_bwd_dkv_body<false, NW>(qkv, dattn, lse, delta, dqkv, seq, nh, nb, scale, scale_log2e,
-                                     (int)blockIdx.x - total);
-}
-
-// dK / dV with the work laid out as in attn_fwd_split_kernel: 128 consecutive keys per work-group, the two
+// Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy (fused they need
+// 434 VGPRs).  Work laid out as in the forward kernel: 128 consecutive keys per work-group, the two
 // waves of a SIMD share a group of 32 keys and take the even / odd query tiles (streamed in pairs, from
 // the diagonal to the end of the sequence); the second wave's partial sum goes through LDS to the first.
 // Early key blocks see the most queries and are dispatched first; the dK and dV work-groups of a key
@@ -993,7 +496,7 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
     const uint32_t lds0 = lds_addr_of(smem);
     const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
-    constexpr int S = 4;
+    constexpr int S = kStages;
     const uint32_t stat0 = lds0 + S * 2 * kTileBytes;
     const uint32_t lane4 = lane * 4;
     const int it0 = 2 * kb, n_pairs = seq / 128 - kb;  // query tiles it0 + 2p, it0 + 2p + 1
@@ -1135,68 +638,17 @@ static hipError_t set_lds(K kern, size_t lds, bool &done)
     return e;
 }
 
-static bool g_attn_fwd_split = true;
-void attn_set_fwd_split(bool on) { g_attn_fwd_split = on; }
-
 hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int64_t b, int64_t seq, int64_t nh,
                            int64_t d, hipStream_t s)
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    constexpr size_t lds4 = kStages<4> * 2 * kTileBytes, lds8 = kStages<8> * 2 * kTileBytes;  // (K tile, V tile) stages
-    static bool a4 = false, a8 = false;
-    if (hipError_t e = set_lds(attn_fwd_mfma_kernel<4>, lds4, a4)) return e;
-    if (hipError_t e = set_lds(attn_fwd_mfma_kernel<8>, lds8, a8)) return e;
+    constexpr size_t lds = kStages * 2 * kTileBytes;  // (K tile, V tile) stages
+    static bool done = false;
+    if (hipError_t e = set_lds(attn_fwd_split_kernel, lds, done)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
-    if (seq % 256 == 0 && g_attn_fwd_split) {
-        static bool as = false;
-        if (hipError_t e = set_lds(attn_fwd_split_kernel, lds8, as)) return e;
-        const dim3 grid((unsigned)(seq / 128 * nh * b));
-        attn_fwd_split_kernel<<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b,
-                                                     scale_log2e);
-    } else if (seq % 256 == 0) {
-        const dim3 grid((unsigned)(seq / 256 * nh * b));
-        attn_fwd_mfma_kernel<8><<<grid, 512, lds8, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                       (int)b, scale_log2e);
-    } else {
-        const dim3 grid((unsigned)(seq / 128 * nh * b));
-        attn_fwd_mfma_kernel<4><<<grid, 256, lds4, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                       (int)b, scale_log2e);
-    }
-    return hipGetLastError();
-}
-
-template <int NW>
-static hipError_t launch_attn_bwd_nw(const void *qkv, const void *attn, const void *dattn, const float *lse, float *delta,
-                                     void *dqkv, int64_t b, int64_t seq, int64_t nh, float scale, hipStream_t s)
-{
-    static bool a1 = false, a2 = false;
-    constexpr size_t lds_dq = kStages<NW> * 2 * kTileBytes;                        // stages of (K tile, V tile)
-    constexpr size_t lds_dkv = kStages<NW> * 2 * kTileBytes + kStages<NW> * 512;  // (Q tile, dO tile) + lse/delta
-    if (hipError_t e = set_lds(attn_bwd_dq_mfma_kernel<NW>, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_mfma_kernel<NW>, lds_dkv, a2)) return e;
-    const float scale_log2e = scale * 1.44269504088896340736f;
-    const int total = (int)(seq / (32 * NW) * nh * b);
-    if (NW == 8 && g_attn_fwd_split) {
-        static bool a3 = false;
-        if (hipError_t e = set_lds(attn_bwd_dq_split_kernel, lds_dq, a3)) return e;
-        attn_bwd_dq_split_kernel<<<dim3((unsigned)(seq / 128 * nh * b)), 512, lds_dq, s>>>(
-            (const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh,
-            (int)b, scale, scale_log2e);
-    } else
-    attn_bwd_dq_mfma_kernel<NW><<<dim3((unsigned)total), NW * 64, lds_dq, s>>>(
-        (const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh,
-        (int)b, scale, scale_log2e);
-    if (NW == 8 && g_attn_fwd_split) {
-        static bool a4 = false;
-        if (hipError_t e = set_lds(attn_bwd_dkv_split_kernel, lds_dkv, a4)) return e;
-        attn_bwd_dkv_split_kernel<<<dim3((unsigned)(2 * (seq / 128) * nh * b)), 512, lds_dkv, s>>>(
-            (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
-            scale_log2e);
-    } else
-    attn_bwd_dkv_mfma_kernel<NW><<<dim3((unsigned)(2 * total)), NW * 64, lds_dkv, s>>>(
-        (const bf16 *)qkv, (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
-        scale_log2e, total);
+    attn_fwd_split_kernel<<<dim3((unsigned)(seq / 128 * nh * b)), 512, lds, s>>>(
+        (const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b, scale_log2e);
     return hipGetLastError();
 }
 
@@ -1206,8 +658,20 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
     const float scale = 1.0f / sqrtf((float)d);
-    if (seq % 256 == 0) return launch_attn_bwd_nw<8>(qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
-    return launch_attn_bwd_nw<4>(qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, scale, s);
+    const float scale_log2e = scale * 1.44269504088896340736f;
+    constexpr size_t lds_dq = kStages * 2 * kTileBytes;                    // stages of (K tile, V tile)
+    constexpr size_t lds_dkv = kStages * 2 * kTileBytes + kStages * 512;  // (Q tile, dO tile) + lse/delta
+    static bool a1 = false, a2 = false;
+    if (hipError_t e = set_lds(attn_bwd_dq_split_kernel, lds_dq, a1)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_split_kernel, lds_dkv, a2)) return e;
+    const unsigned blocks = (unsigned)(seq / 128 * nh * b);
+    attn_bwd_dq_split_kernel<<<dim3(blocks), 512, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn,
+                                                               (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq,
+                                                               (int)nh, (int)b, scale, scale_log2e);
+    attn_bwd_dkv_split_kernel<<<dim3(2 * blocks), 512, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
+                                                                     (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
+                                                                     scale_log2e);
+    return hipGetLastError();
 }
 
 }  // namespace zpp
