@@ -137,11 +137,12 @@ zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float 
  *           buffer is reused, stage_backward of another micro-batch before that is ZPP_ERR_STATE
  *           (stage_backward_accumulate(mb) stands for the pair backward + accumulate of one micro-batch;
  *           stage_backward_input(mb) then stage_backward_weight(mb) stand for stage_backward(mb) or,
- *           with in_place, for stage_backward_accumulate(mb))
+ *           with in_place, for stage_backward_accumulate(mb); stage_backward_weight_group covers several
+ *           micro-batches whose input-gradient tasks have run)
  *        -> shard_adam_step only when no micro-batch is backward-done but not accumulated
  *        -> zpp_stage_end_unit, after which the next unit starts with forward (the working copy
- *           stays valid until P changes; after shard_adam_step without write-back a new
- *           stage_materialize_params is required).
+ *           stays valid until P changes; after shard_adam_step a new stage_materialize_params is
+ *           required, which is cheaper when the step wrote the parameters back).
  */
 
 /* Stand-in for the per-unit parameter all-gather of Section 3.2: produces the working copy of the
