@@ -455,6 +455,33 @@ def test_grouped_weight_gradient_tasks(arch, kw, g):
     st.close()
 
 
+def test_device_with_recomputation_matches_device_without():
+    sh = small(1, 1, n_blocks=2, unit_mbs=3)
+    U, V = sh.unit_mbs, 2
+    P0 = synth.make_params(sh.replace(n_blocks=4), oracle.param_layout(sh.replace(n_blocks=4)), gain_jitter=0.1)
+    xs, dys = make_inputs(sh, U)
+    results = []
+    for rc in (False, True):
+        dev = zpp.Device(sh, V, prefetch=True, recompute=rc)
+        dev.P.copy_(torch.from_numpy(P0))
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        x_in = [to_dev(xs[m], dev.act_dtype) for m in range(U)]
+        dy_in = [to_dev(dys[m], dev.act_dtype) for m in range(U)]
+        mid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        gmid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        dev.forward_unit([(x_in[m] if v == 0 else mid[v - 1][m]) for v in range(V) for m in range(U)],
+                         [mid[v][m] for v in range(V) for m in range(U)], main, side)
+        dev.backward_unit([(dy_in[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)],
+                          [gmid[v][m] for v in range(V) for m in range(U)], 1.0, main, side)
+        torch.cuda.synchronize()
+        results.append((dev.G.clone(), [t.clone() for t in gmid[0]], dev.memory_terms()["stash"]))
+        dev.close()
+    assert torch.equal(results[0][0].view(torch.int32), results[1][0].view(torch.int32))
+    for a, b in zip(results[0][1], results[1][1]):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert results[1][2] < results[0][2] / 3      # the stashes shrink to the block inputs
+
+
 def test_split_backward_state_machine():
     sh = small(0, 1)
     st = zpp.Stage(sh, split_backward=True)
