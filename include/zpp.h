@@ -139,7 +139,8 @@ zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float 
  *           stage_backward_input(mb) then stage_backward_weight(mb) stand for stage_backward(mb) or,
  *           with in_place, for stage_backward_accumulate(mb); stage_backward_weight_group covers several
  *           micro-batches whose input-gradient tasks have run)
- *        -> shard_adam_step only when no micro-batch is backward-done but not accumulated
+ *        -> shard_adam_step only when no micro-batch is half-done (forward without backward, input
+ *           gradient without weight gradient, backward without accumulate)
  *        -> zpp_stage_end_unit, after which the next unit starts with forward (the working copy
  *           stays valid until P changes; after shard_adam_step a new stage_materialize_params is
  *           required, which is cheaper when the step wrote the parameters back).
@@ -148,8 +149,15 @@ zpp_status zpp_stage_bind(zpp_stage *stage, float *P, float *G, float *M, float 
 /* Stand-in for the per-unit parameter all-gather of Section 3.2: produces the working copy of the
  * whole stage from the flat fp32 master shard P (bf16 round-to-nearest-even cast, or a float
  * copy).  Idempotent; may be called again before the backward phase, mirroring the paper's second
- * gather, without changing results. */
+ * gather, without changing results.  After an Adam step with write_back the first gather takes the
+ * plain copy that step wrote instead of casting P again; a caller who writes P itself between such a
+ * step and the gather (a checkpoint load, a re-initialisation) must call zpp_stage_params_changed
+ * first.  Every other gather reads P. */
 zpp_status stage_materialize_params(zpp_stage *stage, void *hip_stream);
+
+/* Tells the stage that the caller has written P: the working copy is stale and the next
+ * stage_materialize_params casts all of it from P.  Host only.  Errors: ZPP_ERR_STATE before bind. */
+zpp_status zpp_stage_params_changed(zpp_stage *stage);
 
 /* One micro-batch through all blocks of the stage (the forward task of Section 3.1.1).  Per block:
  * x1 = x + Attn(Norm1(x)); y = x1 + MLP(Norm2(x1)), causal attention, no dropout.  x, y: [T, h]

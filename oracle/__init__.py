@@ -65,6 +65,12 @@ def _load():
     lib.oracle_set_num_threads.argtypes = [i32]
     lib.oracle_bf16_bits_rne.argtypes = [ctypes.c_float]
     lib.oracle_bf16_bits_rne.restype = ctypes.c_uint16
+    lib.oracle_flat_materialize_bits.argtypes = [vp, vp, i64]
+    lib.oracle_flat_materialize_bits.restype = None
+    lib.oracle_flat_accumulate_f32.argtypes = [vp, vp, i64, dbl]
+    lib.oracle_flat_accumulate_f32.restype = None
+    lib.oracle_flat_adam_f32.argtypes = [vp, vp, vp, vp, i64, dbl, dbl, dbl, dbl, dbl, dbl, i32, i32, i32]
+    lib.oracle_flat_adam_f32.restype = None
     for suf in ("f32", "f64"):
         def f(name):
             return getattr(lib, f"{name}_{suf}")
@@ -145,6 +151,35 @@ def param_layout(shape):
 
 def bf16_bits_rne(v: float) -> int:
     return int(_load().oracle_bf16_bits_rne(ctypes.c_float(v)))
+
+
+def _flat_arg(a: np.ndarray, dtype) -> np.ndarray:
+    assert a.dtype == dtype and a.flags.c_contiguous and a.ndim == 1
+    return a
+
+
+def flat_materialize_bits(P: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) of a float32 array, round to nearest even (the materialise pass)."""
+    P = _flat_arg(P, np.float32)
+    out = np.empty(P.size, np.uint16)
+    _load().oracle_flat_materialize_bits(P.ctypes.data, out.ctypes.data, P.size)
+    return out
+
+
+def flat_accumulate(G: np.ndarray, S: np.ndarray, scale: float) -> None:
+    """G <- G + scale * S in place over float32 arrays (the accumulate pass)."""
+    G, S = _flat_arg(G, np.float32), _flat_arg(S, np.float32)
+    assert G.size == S.size
+    _load().oracle_flat_accumulate_f32(G.ctypes.data, S.ctypes.data, G.size, float(scale))
+
+
+def flat_adam(P, M, V, G, *, lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1,
+              zero_grad=0) -> None:
+    """One Adam step in place over float32 arrays (the same routine OracleStage.adam runs on its shard)."""
+    P, M, V, G = (_flat_arg(a, np.float32) for a in (P, M, V, G))
+    assert P.size == M.size == V.size == G.size
+    _load().oracle_flat_adam_f32(P.ctypes.data, M.ctypes.data, V.ctypes.data, G.ctypes.data, P.size, lr, beta1,
+                                 beta2, eps, weight_decay, grad_scale, step, decoupled_wd, zero_grad)
 
 
 def _np_dtype(dtype: str):

@@ -774,6 +774,27 @@ void oracle_set_num_threads(int32_t n)
 
 uint16_t oracle_bf16_bits_rne(float v) { return bf16_bits_rne(v); }
 
+// The three flat passes over caller-owned arrays, for shards too large to hold in a Stage on the host
+// (a test walks the shard slice by slice).  Same element-wise definitions as Stage::materialize,
+// Stage::accumulate and adam_range.
+void oracle_flat_materialize_bits(const float *P, uint16_t *W, int64_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) W[i] = bf16_bits_rne(P[i]);
+}
+void oracle_flat_accumulate_f32(float *G, const float *S, int64_t n, double scale)
+{
+    const float sc = (float)scale;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) G[i] = G[i] + sc * S[i];
+}
+void oracle_flat_adam_f32(float *P, float *M, float *V, float *G, int64_t n, double lr, double b1, double b2,
+                          double eps, double wd, double grad_scale, int32_t step, int32_t decoupled,
+                          int32_t zero_grad)
+{
+    adam_range<float>(P, M, V, G, 0, n, lr, b1, b2, eps, wd, grad_scale, step, decoupled, zero_grad);
+}
+
 #define ORACLE_API(SUF, R)                                                                               \
     void *oracle_stage_create_##SUF(const oracle_cfg *c) { return new Stage<R>(*c); }                    \
     void oracle_stage_destroy_##SUF(void *h) { delete (Stage<R> *)h; }                                   \

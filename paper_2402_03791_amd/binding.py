@@ -13,6 +13,7 @@ _lib = None
 EXPORTS = [
     "zpp_stage_create", "zpp_stage_destroy", "zpp_stage_param_count", "zpp_stage_workspace_bytes",
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
+    "zpp_stage_params_changed",
     "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight", "stage_backward_weight_group",
     "stage_accumulate_grads", "shard_adam_step", "shard_adam_step_ranges", "zpp_stage_decay_ranges",
     "zpp_stage_end_unit",
@@ -89,6 +90,7 @@ def load_library(path: str | None = None):
                                          ctypes.POINTER(u64), ctypes.POINTER(u64)]
     L.zpp_stage_bind.argtypes = [vp, vp, vp, vp, vp, vp, u64]
     L.stage_materialize_params.argtypes = [vp, vp]
+    L.zpp_stage_params_changed.argtypes = [vp]
     L.stage_forward.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward_accumulate.argtypes = [vp, i32, vp, vp, f32, vp]
@@ -264,6 +266,9 @@ class Stage:
 
     def materialize_params(self, stream=None):
         _check(lib().stage_materialize_params(self._h, _stream_ptr(stream)))
+
+    def params_changed(self):
+        _check(lib().zpp_stage_params_changed(self._h))
 
     def forward(self, mb: int, x, y=None, stream=None):
         import torch

@@ -639,8 +639,19 @@ zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
         s->rope_ready = true;
     }
     s->materialized = true;
+    // a write-back is good for one gather: later ones cast from P again, so that parameters the caller
+    // has rewritten since (zpp_stage_params_changed covers the gather right after an Adam step) are seen
+    s->w_fresh = false;
     s->n_materialize++;
     s->materialize_bytes += bytes;
+    return ZPP_OK;
+}
+
+zpp_status zpp_stage_params_changed(zpp_stage *s)
+{
+    if (zpp_status e = check_stage(s, true)) return e;
+    s->w_fresh = false;
+    s->materialized = false;
     return ZPP_OK;
 }
 
@@ -988,9 +999,13 @@ zpp_status adam_args(zpp_stage *s, const zpp_adam *hp, AdamArgs *a)
         return fail(ZPP_ERR_ARG, "betas must lie in [0,1)");
     if (s->pending_acc >= 0)
         return fail(ZPP_ERR_STATE, "micro-batch %d is backward-done but not accumulated", s->pending_acc);
-    for (int64_t m = 0; m < s->U; ++m)
+    for (int64_t m = 0; m < s->U; ++m) {
         if (s->mb_state[m] == MB_BIN)
             return fail(ZPP_ERR_STATE, "micro-batch %d has its input gradient but not its weight gradient", (int)m);
+        // a stash computed with the old parameters must not meet a backward that runs with the new ones
+        if (s->mb_state[m] == MB_FWD)
+            return fail(ZPP_ERR_STATE, "micro-batch %d is forward-done but has no backward yet", (int)m);
+    }
     a->lr = hp->lr;
     a->beta1 = hp->beta1;
     a->beta2 = hp->beta2;

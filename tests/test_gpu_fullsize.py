@@ -1,11 +1,15 @@
-"""GPU parity at the benchmark's full kernel shapes.
+"""GPU parity at the benchmark's full shapes and depths.
 
-Every kernel launch configuration of a stage depends on (T, h, heads, f, arch) only, not on the
-number of blocks or micro-batches, so one block and one micro-batch at the full T/h/f of each
-bf16 configuration exercises exactly the launches bench.py times.  At these sizes the oracle needs
-tens of seconds per case, so each case is one block x one micro-batch, compared element by element
-(not sampled) on y, dx and every gradient tensor.  The flat Adam pass is compared over the whole
-805M-element shard of the 6.2B-shaped stage."""
+The stages are created exactly as bench.py creates them (all blocks, the configuration's U micro-batch
+slots, split backward tasks with the unit's weight-gradient tasks grouped), and a prefix of k
+micro-batches is run through them in the order bench.py times (forwards, input-gradient tasks, one
+grouped weight-gradient task) and through the five calls the interface is named after (forward,
+backward into the staging buffer, accumulate).  The oracle runs the same k micro-batches through the
+full-depth stage; y, dx and every gradient tensor are compared element by element (not sampled).  The
+micro-batches are placed in the first and in the last slots of the unit, so the deepest stash
+addresses of the workspace are used.  One block x one micro-batch cases cover the bit-identity of the
+different orders of the work at full T/h/f, and the flat passes run over the 6.2B-shaped stage's shard
+and over the wide stage's 1.61e9-element shard (6.4 GB per buffer, indices beyond 2^32 bytes)."""
 import numpy as np
 import pytest
 import torch
@@ -13,25 +17,109 @@ import torch
 import oracle
 import synth
 import paper_2402_03791_amd as zpp
-from _harness import compare_units, make_inputs, run_gpu_unit, run_oracle_unit
+from _harness import compare_units, make_inputs, rel_err, run_gpu_unit, run_oracle_unit, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["cfg2_gpt_1p3b", "cfg3_gpt_6p2b", "cfg4_llama_13b", "cfg5_wide_gpt"])
-def test_one_block_at_full_shape(name):
-    sh = synth.CONFIGS[name].replace(n_blocks=1, unit_mbs=1, name=name + "_1blk")
-    print(f"full-shape block {sh.name}: T={sh.tokens} h={sh.hidden} f={sh.ffn}", flush=True)
+def _say(capsys, *a):
+    """Progress lines that reach the terminal while the test runs (the oracle takes minutes here)."""
+    with capsys.disabled():
+        print("   ", *a, flush=True)
+
+
+def _compare(tag, layout, gpu, ref, tol=2e-2):
+    worst = {}
+    for m, (a, b) in enumerate(zip(gpu["ys"], ref["ys"])):
+        worst[f"y[{m}]"] = rel_err(a, b)
+    for m, (a, b) in enumerate(zip(gpu["dxs"], ref["dxs"])):
+        worst[f"dx[{m}]"] = rel_err(a, b)
+    for name, off, r, c in layout:
+        worst[f"G.{name}"] = rel_err(gpu["G"][off:off + r * c], ref["G"][off:off + r * c])
+    bad = {k: v for k, v in worst.items() if not (v <= tol)}
+    assert not bad, f"{tag}: tolerance {tol} exceeded: {bad}"
+    return max(worst.values()), max(worst, key=worst.get)
+
+
+def _prefix_through_stage(st, slots, xs, dys, order):
+    """Runs len(slots) micro-batches in the given slots of a bound stage; returns ys, dxs, G (host)."""
+    st.G.zero_()
+    st.materialize_params()
+    ys = [st.forward(m, to_dev(x, st.act_dtype)) for m, x in zip(slots, xs)]
+    if order == "grouped":       # what bench.py times: input-gradient tasks, then one grouped weight-gradient task
+        dxs = [st.backward_input(m, to_dev(dy, st.act_dtype)) for m, dy in zip(slots, dys)]
+        assert list(slots) == list(range(slots[0], slots[0] + len(slots)))
+        st.backward_weight_group(slots[0], len(slots), 1.0)
+    else:                        # the five named calls
+        dxs = []
+        for m, dy in zip(slots, dys):
+            dxs.append(st.backward(m, to_dev(dy, st.act_dtype)))
+            st.accumulate_grads(m, 1.0)
+    torch.cuda.synchronize()
+    out = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs], G=to_np(st.G))
+    st.end_unit()
+    return out
+
+
+@pytest.mark.parametrize("name,n_blocks,k", [
+    ("cfg3_gpt_6p2b", 4, 2),     # the benchmark's stage, whole depth
+    ("cfg2_gpt_1p3b", 4, 2),     # whole stage
+    ("cfg4_llama_13b", 2, 1),    # half the depth (the oracle needs ~50 s per block and micro-batch here)
+])
+def test_full_depth_prefix_of_the_unit(name, n_blocks, k, capsys):
+    full = synth.CONFIGS[name]
+    sh = full.replace(n_blocks=n_blocks, name=f"{name}_{n_blocks}blk")
+    U = sh.unit_mbs
     layout = oracle.param_layout(sh)
     P0 = synth.make_params(sh, layout, gain_jitter=0.05)
-    xs, dys = make_inputs(sh, 1)
-    gpu = run_gpu_unit(sh, P0, xs, dys)
-    print("gpu done", flush=True)
-    ref = run_oracle_unit(sh, P0, xs, dys, "f32")
-    print("oracle done", flush=True)
-    assert np.array_equal(gpu["W"], ref["W"])
-    worst = compare_units(sh, gpu, ref, layout, 2e-2)
-    print("worst rel err", max(worst.values()), max(worst, key=worst.get), flush=True)
+    xs, dys = make_inputs(sh, k)
+    _say(capsys, f"{sh.name}: {n_blocks} blocks, T={sh.tokens} h={sh.hidden} f={sh.ffn}, {k} of U={U} micro-batches")
+    runs = {}
+    st = zpp.Stage(sh, split_backward=U)                 # as bench.py: group = the whole unit
+    st.P.copy_(torch.from_numpy(P0))
+    _say(capsys, f"workspace {st.workspace_bytes / 2**30:.1f} GiB")
+    runs["grouped, first slots"] = _prefix_through_stage(st, list(range(k)), xs, dys, "grouped")
+    runs["grouped, last slots"] = _prefix_through_stage(st, list(range(U - k, U)), xs, dys, "grouped")
+    W = to_np(st.region("W"))
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    st = zpp.Stage(sh)
+    st.P.copy_(torch.from_numpy(P0))
+    runs["five calls, last slots"] = _prefix_through_stage(st, list(range(U - k, U)), xs, dys, "five")
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    _say(capsys, "gpu done; oracle ...")
+    ref = run_oracle_unit(sh.replace(unit_mbs=k), P0, xs, dys, "f32")
+    _say(capsys, "oracle done")
+    assert np.array_equal(W, ref["W"])
+    for tag, gpu in runs.items():
+        worst, where = _compare(f"{sh.name} {tag}", layout, gpu, ref)
+        _say(capsys, f"{tag}: worst rel err {worst:.2e} ({where})")
+    # the same micro-batches in other slots give the same bits
+    a, b = runs["grouped, first slots"], runs["grouped, last slots"]
+    assert all(np.array_equal(p, q) for p, q in zip(a["ys"] + a["dxs"], b["ys"] + b["dxs"]))
+    assert np.array_equal(a["G"].view(np.uint32), b["G"].view(np.uint32))
+
+
+@pytest.mark.parametrize("name", ["cfg2_gpt_1p3b", "cfg3_gpt_6p2b", "cfg4_llama_13b", "cfg5_wide_gpt"])
+def test_one_block_at_full_shape(name, capsys):
+    """One block x one micro-batch at full T/h/f: the orders of the work give the same bits.  The wide
+    stage, which has no full-depth case above, is also compared with the oracle here."""
+    sh = synth.CONFIGS[name].replace(n_blocks=1, unit_mbs=1, name=name + "_1blk")
+    _say(capsys, f"full-shape block {sh.name}: T={sh.tokens} h={sh.hidden} f={sh.ffn}")
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.05)
+    if name == "cfg5_wide_gpt":
+        xs, dys = make_inputs(sh, 1)
+        gpu = run_gpu_unit(sh, P0, xs, dys)
+        _say(capsys, "gpu done; oracle ...")
+        ref = run_oracle_unit(sh, P0, xs, dys, "f32")
+        assert np.array_equal(gpu["W"], ref["W"])
+        worst = compare_units(sh, gpu, ref, layout, 2e-2)
+        _say(capsys, f"worst rel err {max(worst.values()):.2e} ({max(worst, key=worst.get)})")
+        del gpu, ref
     # accumulation in place (the path bench.py times), two micro-batches so that the second one really adds:
     # bit-identical to backward followed by the accumulate pass
     sh2 = sh.replace(unit_mbs=2)
@@ -47,7 +135,6 @@ def test_one_block_at_full_shape(name):
     # both weight-gradient tasks as one product over K = 2T (what bench.py times, with the whole unit)
     grp = run_gpu_unit(sh2, P0, xs2, dys2, scale=0.5, in_place=True, split=("group", 2))
     assert all(np.array_equal(a, b) for a, b in zip(two["dxs"], grp["dxs"]))
-    from _harness import rel_err
     for n_, off, r, c in layout:
         assert rel_err(grp["G"][off:off + r * c], two["G"][off:off + r * c]) <= 1e-5, n_
     # activation recomputation: the block forward runs again inside the backward call
@@ -82,6 +169,49 @@ def test_adam_over_the_whole_6p2b_shard():
     ref = p0.astype(np.float64) + 0.5 * g.astype(np.float64)
     assert np.abs(G.cpu().numpy() - ref).max() <= 1e-7 * np.abs(ref).max() + 1e-9
     o.close()
+
+
+def test_flat_passes_beyond_4GiB_on_the_wide_stage_shard(capsys):
+    """Materialise, accumulate and Adam over the wide stage's 1,610,825,728-element shard: every flat
+    buffer is 6.44 GB, so element indices pass 2^32 bytes and 2^31 elements' worth of 16-byte vectors.
+    Compared with the oracle's flat passes over all elements, slice by slice on the host."""
+    sh = synth.CONFIGS["cfg5_wide_gpt"]
+    n = oracle.param_count(sh)
+    assert n == 1_610_825_728 and n * 4 > 2 ** 32
+    hp = {k: float(np.float32(v)) for k, v in synth.ADAM.items()}
+    _say(capsys, f"flat passes over {n} elements ({n * 4 / 1e9:.2f} GB per buffer)")
+    p0 = synth.normal_f32(19, 1, n, 0.0, 0.02)
+    g = synth.normal_f32(19, 2, n, 0.0, 1e-3)
+    m0 = synth.normal_f32(19, 3, n, 0.0, 1e-4)
+    v0 = synth.normal_f32(19, 4, n, 0.0, 1e-4)
+    np.square(v0, out=v0)
+    _say(capsys, "inputs generated")
+    P, M, V, G = (torch.from_numpy(a).cuda() for a in (p0, m0, v0, g))
+    W = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    A = P.clone()
+    zpp.op_flat_materialize(P, W)
+    zpp.op_flat_accumulate(A, G, 0.5)                  # A = P + 0.5 * G
+    zpp.op_flat_adam(P, M, V, G, step=3, zero_grad=1, **synth.ADAM)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(G).item() == 0
+    _say(capsys, "gpu done; oracle ...")
+    chunk = 1 << 27
+    worst = dict(p=0.0, m=0.0, v=0.0, acc=0.0)
+    for off in range(0, n, chunk):
+        sl = slice(off, min(n, off + chunk))
+        bits = oracle.flat_materialize_bits(p0[sl])
+        assert np.array_equal(bits, W[sl].view(torch.int16).cpu().numpy().view(np.uint16)), f"materialise, slice at {off}"
+        acc = p0[sl].copy()
+        oracle.flat_accumulate(acc, g[sl], 0.5)
+        bound = 6e-8 * (np.abs(p0[sl]) + 0.5 * np.abs(g[sl])) + 1e-30
+        worst["acc"] = max(worst["acc"], float((np.abs(A[sl].cpu().numpy() - acc) / bound).max()))
+        oracle.flat_adam(p0[sl], m0[sl], v0[sl], g[sl], step=3, zero_grad=1, **hp)
+        for key, dev_t, ref in (("p", P, p0), ("m", M, m0), ("v", V, v0)):
+            err = np.abs(dev_t[sl].cpu().numpy() - ref[sl]) / np.maximum(np.abs(ref[sl]), 1e-30)
+            worst[key] = max(worst[key], float(err.max()))
+    _say(capsys, f"worst element-wise errors: {worst}")
+    assert worst["acc"] <= 1.0, worst          # in units of half an ulp of the larger addend
+    assert max(worst["p"], worst["m"], worst["v"]) <= 1e-6, worst
 
 
 @pytest.mark.parametrize("M,N,K,variant", [

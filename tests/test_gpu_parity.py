@@ -189,6 +189,25 @@ def test_adam_write_back_is_the_cast_materialise_would_do(arch, dtype, ranged):
     st.materialize_params()
     calls2, bytes2 = st.counters()
     assert bytes2 - bytes1 == bytes0
+    # the caller rewrites P: (1) with no Adam step in between, the next gather casts from P by itself
+    # (a write-back is consumed by the first gather after it); (2) right after a write-back step the
+    # caller has to say so
+    def w_is_cast_of_p():
+        torch.cuda.synchronize()
+        zpp.op_flat_materialize(st.P, expect)
+        return torch.equal(st.region("W").view(view), expect.view(view))
+    st.adam_step(step=3, write_back=1, **synth.ADAM)
+    st.materialize_params()
+    st.P.mul_(1.5)
+    st.materialize_params()
+    assert w_is_cast_of_p()
+    st.adam_step(step=4, write_back=1, **synth.ADAM)
+    st.P.mul_(0.5)
+    st.params_changed()
+    with pytest.raises(zpp.ZppError):       # the working copy counts as stale until the next gather
+        st.forward(0, to_dev(xs[0], st.act_dtype))
+    st.materialize_params()
+    assert w_is_cast_of_p()
     st.close()
     ref.close()
     dev = zpp.Device(sh, 2)
@@ -308,6 +327,10 @@ def test_split_backward_tasks_equal_the_fused_call(arch, dtype, kw):
     # staging path: weight-gradient tasks in ascending order, each followed by the accumulate pass
     asc = run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="ascending")
     same(fused, asc, "ascending/staging")
+    # the split tasks against the oracle directly (unit scale, so that G is the plain sum)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    compare_units(sh, run_gpu_unit(sh, P0, xs, dys, split="descending"), ref, layout,
+                  TOL_BF16 if dtype == 1 else TOL_FP32)
     assert np.array_equal(fused["S0"].view(np.uint32), asc["S0"].view(np.uint32))
     # in-place path, deferred and interleaved
     same(fused, run_gpu_unit(sh, P0, xs, dys, scale=0.37, split="ascending", in_place=True), "ascending/in place")
@@ -402,10 +425,22 @@ def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, 
     y_list = [mid[v][m] for v in range(V) for m in range(U)]
     dy_list = [(dy_in[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)]
     dx_list = [gmid[v][m] for v in range(V) for m in range(U)]
+    layout = oracle.param_layout(sh_all)
+    ora = run_oracle_unit(sh_all, P0, xs, dys, "f64")   # the V stages are one stack of V * per blocks
+    tol = TOL_BF16 if dtype == 1 else TOL_FP32
     for unit in range(2):
         dev.forward_unit(x_list, y_list, main, side)
         dev.backward_unit(dy_list, dx_list, 0.5, main, side)
         torch.cuda.synchronize()
+        if unit == 0:
+            # the device against the oracle directly: outputs of the last stage, input gradients of the
+            # first, and the accumulated gradients of all stages (scale 0.5)
+            for m in range(U):
+                assert rel_err(to_np(mid[V - 1][m]), ora["ys"][m]) <= tol, ("y vs oracle", m)
+                assert rel_err(to_np(gmid[0][m]), ora["dxs"][m]) <= tol, ("dx vs oracle", m)
+            g_host = to_np(dev.G)
+            for name, off, r, c in layout:
+                assert rel_err(g_host[off:off + r * c], 0.5 * ora["G"][off:off + r * c]) <= tol, ("G vs oracle", name)
         ys, dxs, g, p = ref[unit]
         for m in range(U):
             assert torch.equal(mid[V - 1][m].view(torch.int16 if dtype else torch.int32),
@@ -535,6 +570,9 @@ def test_backward_accumulate_state_machine():
     assert e.value.status == -2
     st.forward(0, x)
     st.forward(1, x)
+    with pytest.raises(zpp.ZppError) as e:   # forward-done micro-batches would meet new weights in backward
+        st.adam_step(step=1, **synth.ADAM)
+    assert e.value.status == -2
     st.backward(1, dy)
     st.backward_accumulate(0, dy)            # does not use the staging buffer, which still holds micro-batch 1
     with pytest.raises(zpp.ZppError) as e:   # ... and still waits for its accumulate pass

@@ -359,6 +359,30 @@ def test_adam_multi_step_against_torch_adamw():
     assert np.abs(st32.P[:n] - ref).max() <= 1e-6 * np.abs(ref).max()
 
 
+def test_flat_array_passes_closed_forms():
+    """The flat passes over caller-owned arrays (used slice by slice on shards too large for a host Stage):
+    first Adam step in closed form, bf16 bits against torch's cast, accumulate against float64."""
+    rng = np.random.default_rng(11)
+    n = 10007
+    hp = synth.ADAM
+    p0 = rng.normal(0, 0.02, n).astype(np.float32)
+    g = rng.normal(0, 1e-3, n).astype(np.float32)
+    g[::5] = 0.0
+    P, M, V, G = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32), g.copy()
+    oracle.flat_adam(P, M, V, G, step=1, zero_grad=1, **hp)
+    p64, g64 = p0.astype(np.float64), g.astype(np.float64)
+    expect = p64 - hp["lr"] * (g64 / (np.abs(g64) + hp["eps"]) + hp["weight_decay"] * p64)
+    assert np.abs(P - expect).max() <= 3e-7 * np.abs(expect).max() + 1e-11
+    assert np.allclose(M, (1 - hp["beta1"]) * g64, rtol=2e-6, atol=0)
+    assert np.allclose(V, (1 - hp["beta2"]) * g64 * g64, rtol=2e-6, atol=1e-30)
+    assert not G.any()
+    bits = oracle.flat_materialize_bits(p0)
+    assert np.array_equal(bits, torch.from_numpy(p0).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    A, S = p0.copy(), g.copy()
+    oracle.flat_accumulate(A, S, 0.5)
+    assert np.abs(A - (p64 + 0.5 * g64)).max() <= 6e-8 * np.abs(p64).max()
+
+
 # --------------------------------------------------------------------------- materialise (bf16 RNE)
 def nearest_bf16_by_distance(v: np.float32) -> int:
     """Nearest 8-bit-significand value by exact distance (ties to even pattern)."""
