@@ -47,6 +47,20 @@ zpp_status zpp_op_attention_bwd(int32_t dtype, int32_t impl, const void *qkv, co
                                 const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh,
                                 int64_t d, void *hip_stream);
 
+/* For callers that cannot allocate device memory (HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): zpp_op_attention_bwd without the `delta` argument.  The b * nh * seq floats of
+ * scratch live in a 4 MiB array inside the library's device image (one copy per GPU the library runs on,
+ * held until the process ends), so the call allocates nothing, and neither does anything it calls.
+ * Limit: b * nh * seq <= zpp_op_attention_bwd_noalloc_max_rows() (2^20), ZPP_ERR_WORKSPACE beyond it.
+ * The device of `hip_stream` must be the current device.  Every byte of scratch the kernels read is
+ * written by the same call first, so nothing needs clearing between calls; but all calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or host threads) race
+ * and must be serialised by the caller.  Same kernels and same results as zpp_op_attention_bwd. */
+uint64_t zpp_op_attention_bwd_noalloc_max_rows(void);
+zpp_status zpp_op_attention_bwd_noalloc(int32_t dtype, int32_t impl, const void *qkv, const void *attn,
+                                        const void *dattn, const float *lse, void *dqkv, int64_t b, int64_t seq,
+                                        int64_t nh, int64_t d, void *hip_stream);
+
 /* The flat-buffer passes on raw arrays of n elements (16-byte aligned): the optimizer step, the
  * gradient accumulation G += scale*S, and the fp32 -> working-copy cast. */
 zpp_status zpp_op_flat_adam(float *P, float *M, float *V, float *G, uint64_t n, const zpp_adam *hp, void *hip_stream);

@@ -20,7 +20,8 @@ EXPORTS = [
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
     "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
-    "zpp_op_flat_accumulate", "zpp_op_flat_materialize",
+    "zpp_op_flat_accumulate", "zpp_op_flat_materialize", "zpp_op_attention_bwd_noalloc",
+    "zpp_op_attention_bwd_noalloc_max_rows",
     "zpp_device_create", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
     "zpp_device_workspace_bytes", "zpp_device_memory_terms", "zpp_device_stage", "zpp_device_bind",
     "device_forward_unit", "device_backward_unit", "device_adam_step", "zpp_device_end_unit",
@@ -144,6 +145,8 @@ def load_library(path: str | None = None):
     L.zpp_op_gemm_bf16_tt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
     L.zpp_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    L.zpp_op_attention_bwd_noalloc.argtypes = [i32, i32, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    L.zpp_op_attention_bwd_noalloc_max_rows.restype = u64
     L.zpp_op_flat_adam.argtypes = [vp, vp, vp, vp, u64, ctypes.POINTER(_Adam), vp]
     L.zpp_op_flat_accumulate.argtypes = [vp, vp, u64, f32, vp]
     L.zpp_op_flat_materialize.argtypes = [vp, vp, u64, i32, vp]
@@ -514,6 +517,14 @@ def op_attention_bwd(qkv, attn, dattn, lse, delta, dqkv, b, seq, nh, d, impl=0, 
     dt = 1 if qkv.dtype == torch.bfloat16 else 0
     _check(lib().zpp_op_attention_bwd(dt, impl, qkv.data_ptr(), attn.data_ptr(), dattn.data_ptr(), lse.data_ptr(),
                                       delta.data_ptr(), dqkv.data_ptr(), b, seq, nh, d, _stream_ptr(stream)))
+
+
+def op_attention_bwd_noalloc(qkv, attn, dattn, lse, dqkv, b, seq, nh, d, impl=0, stream=None):
+    """As op_attention_bwd, scratch inside the library (no allocation anywhere in the call)."""
+    import torch
+    dt = 1 if qkv.dtype == torch.bfloat16 else 0
+    _check(lib().zpp_op_attention_bwd_noalloc(dt, impl, qkv.data_ptr(), attn.data_ptr(), dattn.data_ptr(),
+                                              lse.data_ptr(), dqkv.data_ptr(), b, seq, nh, d, _stream_ptr(stream)))
 
 
 def op_flat_adam(P, M, V, G, stream=None, **hp):

@@ -12,7 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzpp.so")
 
 SOURCES = ["stage.cpp", "device.cpp", "plan.cpp", "flat.hip", "norm.hip", "elementwise.hip", "gemm_f32.hip", "gemm_bf16.hip",
-           "attn_simple.hip", "attn_bf16.hip"]
+           "attn_simple.hip", "attn_bf16.hip", "noalloc.hip"]
 
 # -packed-fp32-ops is switched off on purpose (packed fp32 VALU forms are not trusted on the test machines);
 # hipcc's host pass prints a harmless note that it does not know the feature.
