@@ -10,7 +10,12 @@ separate (stage_backward + stage_accumulate_grads); the last three give identica
 changes the summation order inside G.  Inputs are resident in HBM before the timed
 region.  Prints ONE JSON line.
 
+After the timed region the same process adds, outside `value`: one event-instrumented step (roofline, phases),
+the unit through the five named calls, the Adam / accumulate passes on the wide configuration's 6.4 GB shard,
+two steps of each other bf16 configuration, and the CPU oracle on a bounded sample.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3_gpt_6p2b] [--no-cpu-baseline]
+                  [--no-five-call-order] [--no-large-shard] [--no-other-workloads]
 """
 from __future__ import annotations
 
@@ -26,6 +31,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
+DEFAULT_MB_GROUP = 1        # micro-batches per forward / input-gradient call in the default order of the work
 
 
 def model_flops_per_unit(sh) -> float:
@@ -37,29 +43,172 @@ def model_flops_per_unit(sh) -> float:
     return 3.0 * (gemm + attn) * sh.n_blocks * sh.unit_mbs
 
 
-def cpu_baseline(sh, seconds_hint: float = 20.0):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
-    one block of the stage, one micro-batch, full T/h/f (forward, backward, accumulate)."""
+def kernel_sources_sha256() -> str:
+    """One hash over the library's kernel and launch-sequence sources, to tie counter summaries to the code."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2402_03791_amd", "csrc")
+    hsh = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            hsh.update(name.encode())
+            hsh.update(open(os.path.join(d, name), "rb").read())
+    return hsh.hexdigest()
+
+
+def hbm_large_shard(zpp, torch, synth, stream):
+    """The flat passes on the wide configuration's shard (1.61e9 elements, 6.44 GB per fp32 buffer: far beyond any
+    cache): Adam with zero_grad (32 B per element) and the accumulate pass (12 B per element), each timed with
+    events on the launching stream over several launches."""
+    n = zpp.Stage(synth.CONFIGS["cfg5_wide_gpt"], allocate=False).N
+    g = torch.Generator(device="cuda").manual_seed(5)
+    P = torch.randn(n, device="cuda", generator=g) * 0.02
+    G = torch.randn(n, device="cuda", generator=g) * 1e-3
+    S = torch.randn(n, device="cuda", generator=g) * 1e-3
+    M = torch.zeros(n, device="cuda")
+    V = torch.zeros(n, device="cuda")
+    hp = dict(synth.ADAM)
+    out = {"workload": "cfg5_wide_gpt flat shard", "elements": n, "GB_per_buffer": round(n * 4 / 1e9, 2)}
+    for name, reps, bytes_per, fn in (
+            ("adam", 3, 32.0, lambda i: zpp.op_flat_adam(P, M, V, G, step=i + 1, zero_grad=1, stream=stream, **hp)),
+            ("accumulate", 4, 12.0, lambda i: zpp.op_flat_accumulate(G, S, 1.0, stream=stream))):
+        fn(0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(reps):
+            fn(1 + i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        gbs = bytes_per * n / (ms * 1e-3) / 1e9
+        out[name] = {"ms": round(ms, 3), "GB/s": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+                     "bytes_per_element": bytes_per}
+    tot_b = 32.0 * n + 12.0 * n
+    tot_ms = out["adam"]["ms"] + out["accumulate"]["ms"]
+    out["combined_GBps"] = round(tot_b / (tot_ms * 1e-3) / 1e9, 1)
+    out["combined_frac"] = round(out["combined_GBps"] / PEAK_HBM_GBS, 4)
+    return out
+
+
+def time_default_step(zpp, torch, synth, sh, steps, warmup, stream):
+    """The default order of the work (materialise, U forwards, U input-gradient tasks, the unit's weight-gradient
+    tasks as one grouped task, Adam with zero_grad and write-back) on another workload; whole-step figures only."""
+    st = zpp.Stage(sh, device="cuda:0", split_backward=sh.unit_mbs)
+    P0 = synth.make_params(sh, st.layout())
+    st.P.copy_(torch.from_numpy(P0))
+    del P0
+    act = st.act_dtype
+    xs = [torch.from_numpy(synth.make_x(sh, m)).to("cuda:0", act) for m in range(sh.unit_mbs)]
+    dys = [torch.from_numpy(synth.make_dy(sh, m)).to("cuda:0", act) for m in range(sh.unit_mbs)]
+    y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
+
+    def step(t):
+        st.materialize_params(stream)
+        for m in range(sh.unit_mbs):
+            st.forward(m, xs[m], y, stream)
+        for m in range(sh.unit_mbs):
+            st.backward_input(m, dys[m], dx, stream)
+        st.backward_weight_group(0, sh.unit_mbs, 1.0, stream)
+        st.adam_step(step=t, zero_grad=1, write_back=1, stream=stream, **synth.ADAM)
+        st.end_unit()
+
+    for t in range(warmup):
+        step(t + 1)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for t in range(steps):
+        step(warmup + t + 1)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    fl = model_flops_per_unit(sh)
+    res = {"ms_per_step": round(ms, 3), "value": round(fl / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+           "frac_bf16_peak_whole_step": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "steps": steps,
+           "params": st.N, "workspace_GB": round(st.workspace_bytes / 1e9, 2)}
+    st.close()
+    return res
+
+
+def cpu_baseline(sh):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload.
+    Forward, backward and accumulate: one block of the stage at full T/h/f over k = 2 micro-batches,
+    timed separately and scaled by (blocks x U / k) - the work is exactly linear in blocks and
+    micro-batches.  Adam and materialise: timed in full over the stage's whole N-element shard with the
+    oracle's flat passes.  Plus the whole tiny fp32 configuration on one thread."""
     import numpy as np
     import oracle
     import synth
-    sample = sh.replace(n_blocks=1, unit_mbs=1)
+    k = min(2, sh.unit_mbs)
+    sample = sh.replace(n_blocks=1, unit_mbs=k)
     st = oracle.OracleStage(sample, "f32")
     synth.make_params(sample, st.layout(), out=st.P)
-    x, dy = synth.make_x(sample, 0), synth.make_dy(sample, 0)
-    t0 = time.perf_counter()
+    xs = [synth.make_x(sample, m) for m in range(k)]
+    dys = [synth.make_dy(sample, m) for m in range(k)]
     st.materialize()
-    st.forward(0, x)
-    st.backward(0, dy)
-    st.accumulate(0, 1.0)
-    dt = time.perf_counter() - t0
-    flops = model_flops_per_unit(sample)
-    threads = oracle.num_threads()
+    t = {"forward": 0.0, "backward": 0.0, "accumulate": 0.0}
+    for m in range(k):
+        t0 = time.perf_counter()
+        st.forward(m, xs[m])
+        t["forward"] += time.perf_counter() - t0
+    for m in range(k):
+        t0 = time.perf_counter()
+        st.backward(m, dys[m])
+        t1 = time.perf_counter()
+        st.accumulate(m, 1.0)
+        t["backward"] += t1 - t0
+        t["accumulate"] += time.perf_counter() - t1
     st.close()
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "seconds": round(dt, 3),
-            "sample": f"1 of {sh.n_blocks} blocks x 1 of {sh.unit_mbs} micro-batches at full T={sh.tokens}, "
-                      f"h={sh.hidden}, f={sh.ffn}: materialise + forward + backward + accumulate, fp32 oracle"}
+    del st, xs, dys
+    scale = sh.n_blocks * sh.unit_mbs / k
+    # the flat passes over the whole shard
+    N = oracle.param_count(sh)
+    hp = {kk: float(np.float32(v)) for kk, v in synth.ADAM.items()}
+    P = synth.normal_f32(1, 1, N, 0.0, 0.02)
+    G = synth.normal_f32(1, 2, N, 0.0, 1e-3)
+    M = np.zeros(N, np.float32)
+    V = np.zeros(N, np.float32)
+    M[:] = 0.0   # touch the pages before timing
+    V[:] = 0.0
+    t0 = time.perf_counter()
+    oracle.flat_adam(P, M, V, G, step=1, zero_grad=1, **hp)
+    t["adam_full"] = time.perf_counter() - t0
+    del M, V, G
+    if sh.compute_dtype == 1:
+        t0 = time.perf_counter()
+        oracle.flat_materialize_bits(P)
+        t["materialize_full"] = time.perf_counter() - t0
+    else:
+        t["materialize_full"] = 0.0
+    del P
+    unit_s = (t["forward"] + t["backward"] + t["accumulate"]) * scale + t["adam_full"] + t["materialize_full"]
+    threads = oracle.num_threads()
+    # the tiny fp32 configuration, whole unit, on one thread
+    tiny = synth.CONFIGS["cfg1_tiny_gpt_fp32"]
+    oracle.set_num_threads(1)
+    o1 = oracle.OracleStage(tiny, "f32")
+    synth.make_params(tiny, o1.layout(), out=o1.P)
+    t0 = time.perf_counter()
+    o1.materialize()
+    for m in range(tiny.unit_mbs):
+        o1.forward(m, synth.make_x(tiny, m))
+    for m in range(tiny.unit_mbs):
+        o1.backward(m, synth.make_dy(tiny, m))
+        o1.accumulate(m, 1.0)
+    o1.adam(step=1, **{kk: float(np.float32(v)) for kk, v in synth.ADAM.items()})
+    tiny_s = time.perf_counter() - t0
+    o1.close()
+    oracle.set_num_threads(threads)
+    return {"value": model_flops_per_unit(sh) / unit_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "affinity_cores": len(os.sched_getaffinity(0)), "omp_max_threads": threads,
+            "seconds_measured": round(sum(t.values()), 2),
+            "seconds_per_unit_extrapolated": round(unit_s, 1),
+            "seconds": {kk: round(v, 3) for kk, v in t.items()},
+            "cfg1_whole_unit_one_thread_s": round(tiny_s, 3),
+            "cfg1_one_thread_TFLOPs": round(model_flops_per_unit(tiny) / tiny_s / 1e12, 5),
+            "sample": f"fp32 oracle; forward + backward + accumulate of 1 of {sh.n_blocks} blocks x {k} of "
+                      f"{sh.unit_mbs} micro-batches at full T={sh.tokens}, h={sh.hidden}, f={sh.ffn}, scaled by "
+                      f"{scale:g} (extrapolated from {k} of {sh.unit_mbs}); Adam and materialise timed in full over "
+                      f"the {N}-element shard"}
 
 
 def main():
@@ -83,9 +232,17 @@ def main():
     ap.add_argument("--group", type=int, default=0,
                     help="with --backward split: weight-gradient tasks of this many micro-batches as one product "
                          "(stage_backward_weight_group); 0 = the whole unit, 1 = one by one (bit-identical to fused)")
-    ap.add_argument("--recompute", action="store_true",
-                    help="activation recomputation: keep only block inputs, run each block's forward again in backward")
+    ap.add_argument("--recompute", nargs="?", const="full", default="none", choices=("none", "full", "selective"),
+                    help="activation recomputation: full (keep only block inputs, run each block's forward again in "
+                         "backward) or selective (rebuild only the norm and activation outputs)")
+    ap.add_argument("--mb-group", type=int, default=DEFAULT_MB_GROUP,
+                    help="micro-batches per forward / input-gradient (or fused backward) call: stage_forward_group etc. "
+                         "run every linear layer once over this many micro-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-large-shard", action="store_true",
+                    help="skip the Adam / accumulate bandwidth leg on the wide configuration's 1.61e9-element shard")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short whole-step timings of the other bf16 configurations")
     ap.add_argument("--no-five-call-order", action="store_true",
                     help="skip the extra timing of the unit through the five named calls (keeps a profile to the default step)")
     args = ap.parse_args()
@@ -108,6 +265,7 @@ def main():
                    "peak_bf16_TFLOPs_used": PEAK_BF16_TFLOPS, "peak_hbm_GBps_used": PEAK_HBM_GBS,
                    "peak_note": "vendor figures: 256 CUs x 2.4 GHz x 4096 bf16 flop/clk/CU = 2.52 PFLOP/s dense; HBM3E 8 TB/s"}
     V = args.stages
+    args.recompute = {"none": 0, "full": 1, "selective": 2}[args.recompute]
     if args.recompute:
         args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
     if args.backward != "split" or sh.compute_dtype != 1:
@@ -127,7 +285,7 @@ def main():
         st.N = st.N_total
     else:
         st = zpp.Stage(sh, device="cuda:0", split_backward=args.group if args.backward == "split" else 0,
-                       recompute=args.recompute)
+                       recompute=args.recompute, group_mbs=args.mb_group)
         full_layout = st.layout()
     act = st.act_dtype
 
@@ -135,10 +293,24 @@ def main():
     P0 = synth.make_params(sh, full_layout)
     st.P.copy_(torch.from_numpy(P0))
     del P0
-    xs = [torch.from_numpy(synth.make_x(sh, m)).to(dev, act) for m in range(sh.unit_mbs)]
-    dys = [torch.from_numpy(synth.make_dy(sh, m)).to(dev, act) for m in range(sh.unit_mbs)]
-    y = torch.empty_like(xs[0])
-    dx = torch.empty_like(xs[0])
+    # the unit's micro-batches lie back to back, so that a group of them is one matrix
+    T = sh.tokens
+    X = torch.empty(sh.unit_mbs * T, sh.hidden, device=dev, dtype=act)
+    DY = torch.empty_like(X)
+    for m in range(sh.unit_mbs):
+        X[m * T:(m + 1) * T].copy_(torch.from_numpy(synth.make_x(sh, m)))
+        DY[m * T:(m + 1) * T].copy_(torch.from_numpy(synth.make_dy(sh, m)))
+    xs = [X[m * T:(m + 1) * T] for m in range(sh.unit_mbs)]
+    dys = [DY[m * T:(m + 1) * T] for m in range(sh.unit_mbs)]
+    mg = args.mb_group
+    if mg < 1 or mg > sh.unit_mbs or (mg > 1 and (V > 1 or args.accumulate != "in_place")) or \
+            (args.backward == "split" and args.group % mg):
+        print("--mb-group needs 1 <= g <= U, a single stage, the default --accumulate and a weight-task --group "
+              "that is a multiple of it", file=sys.stderr)
+        sys.exit(2)
+    Y = torch.empty(mg * T, sh.hidden, device=dev, dtype=act)
+    DX = torch.empty_like(Y)
+    y, dx = Y[:T], DX[:T]
     stream = torch.cuda.current_stream()
     adam = dict(synth.ADAM)
 
@@ -161,10 +333,20 @@ def main():
             st.end_unit()
             return
         st.materialize_params(stream)
-        for m in range(sh.unit_mbs):
+        if mg > 1:
+            for f in range(0, sh.unit_mbs, mg):
+                c = min(mg, sh.unit_mbs - f)
+                st.forward_group(f, c, X[f * T:(f + c) * T], Y[:c * T], stream)
+            for f in range(0, sh.unit_mbs, mg):
+                c = min(mg, sh.unit_mbs - f)
+                if args.backward == "split":
+                    st.backward_input_group(f, c, DY[f * T:(f + c) * T], DX[:c * T], stream)
+                else:
+                    st.backward_accumulate_group(f, c, DY[f * T:(f + c) * T], DX[:c * T], 1.0, stream)
+        for m in range(sh.unit_mbs if mg == 1 else 0):
             st.forward(m, xs[m], y, stream)
         if args.backward == "split":
-            for m in range(sh.unit_mbs):
+            for m in range(sh.unit_mbs if mg == 1 else 0):
                 st.backward_input(m, dys[m], dx, stream)
             for m in range(0, sh.unit_mbs, args.group):
                 if args.group > 1:
@@ -173,7 +355,7 @@ def main():
                 st.backward_weight(m, args.accumulate == "in_place", 1.0, stream)
                 if args.accumulate != "in_place":
                     st.accumulate_grads(m, 1.0, stream)
-        for m in range(sh.unit_mbs if args.backward == "fused" else 0):
+        for m in range(sh.unit_mbs if args.backward == "fused" and mg == 1 else 0):
             if args.accumulate == "in_place":
                 st.backward_accumulate(m, dys[m], dx, 1.0, stream)
             else:
@@ -235,35 +417,64 @@ def main():
         n, ms, work, _ = prof[cls]
         return (work / (ms * 1e-3) / scale) if ms > 0 else 0.0
 
-    def measured_traffic():
-        """HBM bytes per GEMM launch from the committed rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE,
-        scaled by what the counters read on the flat passes of known size), if they cover this workload."""
-        path = os.path.join(ROOT, "profiles", "cfg3_gemm_traffic.kv")
-        if not os.path.exists(path):
-            return None
+    def profile_kv():
+        """Figures taken from the committed rocprofv3 --pmc summaries (HBM bytes per GEMM launch from
+        FETCH_SIZE / WRITE_SIZE scaled by what the counters read on the flat passes of known size; matrix-core
+        busy cycles): counters cannot be read from inside this process, so they come from profiles/ and are
+        used only when they were taken on this workload, this default order of the work and these kernel
+        sources (hash of the csrc/ files recorded with them); otherwise the fields are null."""
+        path = os.path.join(ROOT, "profiles", f"{sh.name}_counters.kv")
+        if not os.path.exists(path) or not default_order:
+            return {}
         kv = dict(l.strip().split("=", 1) for l in open(path) if "=" in l and not l.startswith("#"))
-        return float(kv["gemm_hbm_bytes_per_launch"]) if kv.get("workload") == sh.name else None
+        if kv.get("workload") != sh.name or kv.get("kernel_sources_sha256") != kernel_sources_sha256():
+            return {}
+        return kv
 
-    # the GEMM family = forward and input-gradient products ("gemm") + weight-gradient products ("gemm_dw")
+    # The share the target is stated on: all matrix-core work of the step, i.e. the bf16 GEMM family (forward and
+    # input-gradient products "gemm" + weight-gradient products "gemm_dw") and the attention kernels.
     fam = [prof["gemm"], prof["gemm_dw"]]
     n_gemm, ms_gemm, fl_gemm, by_gemm = (sum(c[i] for c in fam) for i in range(4))
     gemm_tflops = fl_gemm / (ms_gemm * 1e-3) / 1e12 if ms_gemm > 0 else 0.0
+    mc = fam + [prof["attn_fwd"], prof["attn_bwd"]]
+    n_mc, ms_mc, fl_mc = (sum(c[i] for c in mc) for i in range(3))
+    mc_tflops = fl_mc / (ms_mc * 1e-3) / 1e12 if ms_mc > 0 else 0.0
     bf16 = sh.compute_dtype == 1
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    default_order = (V == 1 and args.backward == "split" and args.group == sh.unit_mbs and not args.recompute
+                     and mg == DEFAULT_MB_GROUP
+                     and args.accumulate == "in_place" and args.adam == "uniform")
+    kv = profile_kv()
+
+    def kind(c):
+        return {"launches": prof[c][0], "ms": round(prof[c][1], 3), "TFLOP/s": round(rate(c, 1e12), 1),
+                "frac": round(rate(c, 1e12) / peak, 4)}
+
     roofline = {
-        "kernel": "gemm_bf16_nt_h_kernel, gemm_bf16_nt_d_kernel (all bf16 GEMMs of the step)" if bf16 else "gemm_f32_kernel",
+        "kernel": ("bf16 GEMM family (gemm_bf16_nt_h_kernel, gemm_bf16_nt_d_kernel) + MFMA attention kernels: the "
+                   "GEMM/attention share of the step") if bf16 else "gemm_f32_kernel + generic attention kernels",
         "bound": "mfma" if bf16 else "alu",
-        "achieved": round(gemm_tflops, 2), "peak": peak, "unit": "TFLOP/s",
-        "frac": round(gemm_tflops / peak, 4),
-        "launches": n_gemm, "avg_launch_ms": round(ms_gemm / max(n_gemm, 1), 4),
-        "flops_per_launch": fl_gemm / max(n_gemm, 1),
-        "algorithmic_bytes": by_gemm / max(n_gemm, 1),
-        "traffic": measured_traffic(),
-        # the same family by kind: the weight-gradient products carry the gradient accumulation in their
-        # epilogue when the step accumulates in place (one extra fp32 read of their output)
-        "by_kind": {k: {"launches": prof[c][0], "ms": round(prof[c][1], 3), "TFLOP/s": round(rate(c, 1e12), 1),
-                        "frac": round(rate(c, 1e12) / peak, 4)}
-                    for k, c in (("forward_and_input_gradient", "gemm"), ("weight_gradient", "gemm_dw"))},
+        # algorithmic flops of all those launches of one step / their summed durations (HIP events on the
+        # launching stream around each launch)
+        "achieved": round(mc_tflops, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(mc_tflops / peak, 4),
+        "launches": n_mc, "avg_launch_ms": round(ms_mc / max(n_mc, 1), 4),
+        "flops_per_launch": fl_mc / max(n_mc, 1),
+        # HBM bytes per GEMM launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled) and matrix-core busy cycles, from
+        # profiles/<workload>_counters.kv when it matches this code and order of work, else null
+        "traffic": float(kv["gemm_hbm_bytes_per_launch"]) if "gemm_hbm_bytes_per_launch" in kv else None,
+        "traffic_source": kv.get("source"),
+        "mfma_busy": ({"gemm_and_attention_pct": float(kv["mfma_busy_pct"]), "gemm_pct": float(kv["mfma_busy_gemm_pct"]),
+                       "gemm_clock_GHz": float(kv["gemm_clock_ghz"]), "source": kv.get("mfma_source")}
+                      if "mfma_busy_pct" in kv else None),
+        # the GEMM family alone (the dominant kernels: about 80 % of the step), and by kind: the weight-gradient
+        # products carry the gradient accumulation in their epilogue when the step accumulates in place
+        "gemm_family": {"launches": n_gemm, "ms": round(ms_gemm, 3), "TFLOP/s": round(gemm_tflops, 1),
+                        "frac": round(gemm_tflops / peak, 4), "avg_launch_ms": round(ms_gemm / max(n_gemm, 1), 4),
+                        "flops_per_launch": fl_gemm / max(n_gemm, 1),
+                        "algorithmic_bytes_per_launch": by_gemm / max(n_gemm, 1)},
+        "by_kind": {"forward_and_input_gradient": kind("gemm"), "weight_gradient": kind("gemm_dw"),
+                    "attention_forward": kind("attn_fwd"), "attention_backward": kind("attn_bwd")},
     }
     fb_ms = sum(prof[c][1] for c in ("gemm", "gemm_dw", "attn_fwd", "attn_bwd", "other"))
     phases = {c: {"launches": prof[c][0], "ms": round(prof[c][1], 3)} for c in prof}
@@ -294,7 +505,8 @@ def main():
         "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
-                   "accumulate": args.accumulate, "backward": args.backward, "weight_task_group": args.group, "recompute": args.recompute,
+                   "accumulate": args.accumulate, "backward": args.backward, "weight_task_group": args.group, "micro_batch_group": mg,
+                   "recompute": ["none", "full", "selective"][args.recompute],
                    "adam": args.adam, "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
                    "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
         "model_flops_per_step": flops,
@@ -336,12 +548,23 @@ def main():
         out["five_call_order"] = {"calls": "stage_materialize_params, U x stage_forward, U x (stage_backward, "
                                            "stage_accumulate_grads), shard_adam_step",
                                   "ms_per_step": round(ms5, 3), "value": round(flops / (ms5 * 1e-3) / 1e12, 2),
-                                  "unit": "TFLOP/s"}
+                                  "unit": "TFLOP/s",
+                                  "frac_bf16_peak_whole_step": round(flops / (ms5 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
         st2.close()
         del st2
+    st.close()
+    del st, xs, dys, y, dx, X, DY, Y, DX
+    torch.cuda.empty_cache()
+    if not args.no_large_shard and bf16:
+        out["hbm_pass_large_shard"] = hbm_large_shard(zpp, torch, synth, stream)
+        torch.cuda.empty_cache()
+    if not args.no_other_workloads and default_order and args.config == "cfg3_gpt_6p2b":
+        # the other bf16 configurations through the same default order of the work, two steps each
+        out["other_workloads"] = {}
+        for name in ("cfg2_gpt_1p3b", "cfg4_llama_13b", "cfg5_wide_gpt"):
+            out["other_workloads"][name] = time_default_step(zpp, torch, synth, synth.CONFIGS[name], 2, 1, stream)
+            torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        st.close()
-        del st, xs, dys
         out["cpu_baseline"] = cpu_baseline(sh)
         out["gpu_over_cpu"] = round(value / out["cpu_baseline"]["value"], 1)
     print(json.dumps(out), flush=True)

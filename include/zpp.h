@@ -57,6 +57,7 @@ typedef enum {
 enum { ZPP_ARCH_GPT = 0, ZPP_ARCH_LLAMA = 1 };
 enum { ZPP_DTYPE_FP32 = 0, ZPP_DTYPE_BF16 = 1 };
 enum { ZPP_GELU_TANH = 0, ZPP_GELU_ERF = 1 };
+enum { ZPP_RECOMPUTE_NONE = 0, ZPP_RECOMPUTE_FULL = 1, ZPP_RECOMPUTE_SELECTIVE = 2 };
 
 typedef struct {
     int32_t arch;          /* ZPP_ARCH_GPT: pre-LN LayerNorm, biases, GeLU MLP.
@@ -78,11 +79,23 @@ typedef struct {
                               stage_backward_input / stage_backward_weight may be used, and temporaries for
                               weight-gradient tasks of up to g micro-batches at once
                               (stage_backward_weight_group); 0: only the fused calls.  At most unit_mbs */
-    int32_t recompute;      /* 1: activation recomputation (Section 3.3): stage_forward keeps only each block's
-                              input per micro-batch, and the backward calls run a block's forward again
-                              (without its last linear layer, whose output backward does not need) right
-                              before its backward; same kernels on the same inputs, so results are
-                              bit-identical to recompute = 0.  Excludes split_backward */
+    int32_t recompute;      /* Activation recomputation (Section 3.3), full or selective.
+                              ZPP_RECOMPUTE_FULL: stage_forward keeps only each block's input per micro-batch, and
+                              the backward calls run a block's forward again (without its last linear layer,
+                              whose output backward does not need) right before its backward.
+                              ZPP_RECOMPUTE_SELECTIVE: the products and the attention output are kept, and only
+                              what costs next to nothing to rebuild is dropped and rebuilt element-wise in
+                              backward: the outputs of the two norms and of the activation function (6h of the
+                              16h stored elements per token of a GPT block with f = 4h; the s x s attention
+                              probabilities, the usual first choice, are never stored by the fused attention
+                              kernels in any mode).
+                              Same kernels on the same inputs either way, so results are bit-identical to
+                              recompute = 0.  The fused backward calls rebuild once for both gradient tasks; with
+                              split_backward each of the two tasks rebuilds for itself (twice the extra work:
+                              the reason Section 3.3 recomputes only where the two tasks run back to back) */
+    int32_t group_mbs;      /* g >= 2: the stage_*_group calls may take up to g consecutive micro-batches as one
+                              matrix of g*T tokens (temporaries are sized for it); 0 or 1: one at a time.  A
+                              split_backward = g' > 1 allows groups of g' too.  At most unit_mbs */
 } zpp_stage_config;
 
 typedef struct {
@@ -210,12 +223,32 @@ zpp_status stage_backward_weight(zpp_stage *stage, int32_t micro_batch, int32_t 
  * runs once over the concatenated tokens, dW += scale * [dY_first; ...]^T . [X_first; ...] with
  * K = count * T, so G is read and written once per group instead of once per micro-batch and the
  * product has a longer K loop.  Always in place (adds into G).  Needs every micro-batch of the group to
- * have had its stage_backward_input, count <= split_backward of the configuration, the bf16 path and
- * sizes in multiples of 64 (ZPP_ERR_UNSUPPORTED otherwise: use stage_backward_weight).  The sum over
+ * have had its input-gradient task (the group must cover grouped input-gradient tasks whole) and
+ * count <= max(split_backward, group_mbs) of the configuration (ZPP_ERR_STATE otherwise).  The sum over
  * the group's micro-batches is formed inside the product's fp32 accumulation, so G differs from the
  * one-by-one result by summation order only (not bit-identical). */
 zpp_status stage_backward_weight_group(zpp_stage *stage, int32_t first, int32_t count, float scale,
                                        void *hip_stream);
+
+/* The micro-batches of a scheduling unit run back to back against one gathered copy of the stage's
+ * parameters (Section 3.1, Section 3.1.2); these calls take `count` consecutive micro-batches
+ * [first, first + count) of the unit as ONE task: every linear layer runs once over count * T tokens (a
+ * larger product that reads the weights once per group instead of once per micro-batch), norms and
+ * attention over count * micro_batch samples.  x, y, dy, dx: [count * T, h], micro-batch first + k in
+ * rows [k*T, (k+1)*T).  Row by row the arithmetic is that of the one-micro-batch calls: y and dx are
+ * bit-identical to theirs; weight, bias and gain gradients of the group are summed inside the products
+ * and reductions (same value, another summation order).  count <= max(group_mbs, split_backward) of the
+ * configuration (ZPP_ERR_STATE beyond); states and errors per micro-batch as for the one-micro-batch calls.
+ *   stage_forward_group              = stage_forward of each micro-batch of the group
+ *   stage_backward_input_group       = stage_backward_input of each; a later weight-gradient task
+ *                                      (stage_backward_weight or _group) must cover the group whole
+ *   stage_backward_accumulate_group  = stage_backward_accumulate of each (both tasks, added into G) */
+zpp_status stage_forward_group(zpp_stage *stage, int32_t first, int32_t count, const void *x, void *y,
+                               void *hip_stream);
+zpp_status stage_backward_input_group(zpp_stage *stage, int32_t first, int32_t count, const void *dy, void *dx,
+                                      void *hip_stream);
+zpp_status stage_backward_accumulate_group(zpp_stage *stage, int32_t first, int32_t count, const void *dy,
+                                           void *dx, float scale, void *hip_stream);
 
 /* The optimizer-step task (Section 3.1.1; Section 3.2.2: each rank updates the parameters whose optimizer
  * states it holds): Adam on elements [offset, offset+count) of P, M, V using G.

@@ -34,6 +34,14 @@ typedef struct zpp_device zpp_device; /* opaque; host-side metadata and HIP even
  * working-copy slots and gathers on the side stream.  Errors: as zpp_stage_create; ZPP_ERR_ARG for
  * n_stages < 1. */
 zpp_status zpp_device_create(const zpp_stage_config *cfg, int32_t n_stages, int32_t prefetch, zpp_device **out);
+/* The same with a recomputation mode per stage (recompute[v] = ZPP_RECOMPUTE_*, overriding cfg->recompute;
+ * NULL: cfg's for all).  Section 3.3 recomputes every stage mapped to a device except the last one: a stage
+ * whose input- and weight-gradient tasks run back to back needs one recomputation for both, the last
+ * stage's tasks are scheduled apart and it keeps its activations.  So a stage that recomputes runs the fused
+ * backward call per micro-batch whatever cfg->split_backward says, and only the other stages split their
+ * backward tasks; the stashes are sized stage by stage. */
+zpp_status zpp_device_create_per_stage(const zpp_stage_config *cfg, int32_t n_stages, int32_t prefetch,
+                                       const int32_t *recompute, zpp_device **out);
 void zpp_device_destroy(zpp_device *dev);
 
 int32_t zpp_device_stage_count(const zpp_device *dev);
@@ -62,9 +70,9 @@ zpp_status device_forward_unit(zpp_device *dev, const void *const *x, void *cons
 
 /* Backward phase of the unit: for v = V-1 .. 0: gather stage v again unless its working copy is still in
  * a slot (the second gather of Section 3.2.1), then stage_backward_accumulate(scale) of its U
- * micro-batches; or, when the configuration has split_backward = g > 0, the stage's U input-gradient
- * tasks followed by its weight-gradient tasks in groups of g micro-batches (stage_backward_weight_group;
- * one by one where grouping is not supported).  dy, dx: as x, y. */
+ * micro-batches; or, for a stage with split_backward = g > 0 that does not recompute, the stage's U
+ * input-gradient tasks followed by its weight-gradient tasks in groups of g micro-batches
+ * (stage_backward_weight_group).  dy, dx: as x, y. */
 zpp_status device_backward_unit(zpp_device *dev, const void *const *dy, void *const *dx, float scale,
                                 void *stream, void *side_stream);
 

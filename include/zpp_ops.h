@@ -20,20 +20,12 @@ extern "C" {
  * C: bf16, or float when out_f32 != 0; leading dimension ldc.  bias, resid: bf16 or NULL.
  * out_f32 == 2: C is float and receives C + result (the in-place gradient accumulation of
  * stage_backward_accumulate, scale 1), so C must hold valid data on entry.
- * variant: -1 automatic; 0..15 force a kernel generation and tile shape (0-2 register-staged 256x256/128x256/
- * 128x128, 3-4 pipelined 256x256/128x128, 5-8 hand-ordered 256x256(8 waves)/128x128/256x256(4 waves)/128x256,
- * 9-11 LDS ring of K = 32 stages: 256x256 with 5 stages, 256x256 with 4, 128x128 with 4,
- * 12-15 ring of K = 64 stages: 128x128 with 4 and 5 stages, 256x128 and 128x256 with 3). */
+ * tile: -1 chosen from the shape; 0 256x256 and 1 128x128 work-group tiles (two LDS stages), 2 256x128 and
+ * 3 128x256 (a ring of three LDS stages), 4 256x256 with four waves of 128x128: the kernels the stage calls
+ * select among. */
 zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
-                               int32_t out_f32, int32_t variant, void *hip_stream);
-
-/* The weight-gradient product of Section 2.3 without any transposition in memory: C[M,N] = A^T . B with
- * A stored [K, M] (M contiguous, leading dimension lda >= M) and B stored [K, N] (leading dimension
- * ldb >= N), i.e. dW[out,in] = dY[T,out]^T . X[T,in].  bf16 operands, fp32 accumulation; C is float when
- * out_f32 != 0, else bf16.  K % 64 == 0; M, N, lda, ldb multiples of 8. */
-zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
+                               int32_t out_f32, int32_t tile, void *hip_stream);
 
 /* Causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each; T = b*seq, h = nh*d):
  * attn[T, h] = softmax(Q K^T / sqrt(d) + causal mask) V per (sample, head); lse[b, nh, seq] is the

@@ -15,14 +15,15 @@ EXPORTS = [
     "zpp_stage_layout_size", "zpp_stage_param_layout", "zpp_stage_bind", "stage_materialize_params",
     "zpp_stage_params_changed",
     "stage_forward", "stage_backward", "stage_backward_accumulate", "stage_backward_input", "stage_backward_weight", "stage_backward_weight_group",
+    "stage_forward_group", "stage_backward_input_group", "stage_backward_accumulate_group",
     "stage_accumulate_grads", "shard_adam_step", "shard_adam_step_ranges", "zpp_stage_decay_ranges",
     "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
-    "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
+    "zpp_op_gemm_bf16_nt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
     "zpp_op_flat_accumulate", "zpp_op_flat_materialize", "zpp_op_attention_bwd_noalloc",
     "zpp_op_attention_bwd_noalloc_max_rows",
-    "zpp_device_create", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
+    "zpp_device_create", "zpp_device_create_per_stage", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
     "zpp_device_workspace_bytes", "zpp_device_memory_terms", "zpp_device_stage", "zpp_device_bind",
     "device_forward_unit", "device_backward_unit", "device_adam_step", "zpp_device_end_unit",
     "zpp_plan_tp_comm", "zpp_plan_zeropp_comm", "zpp_plan_zeropp_wins", "zpp_plan_bubbles", "zpp_plan_max_memory",
@@ -40,7 +41,7 @@ class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch",
                                               "unit_mbs", "compute_dtype", "gelu_mode")] + \
                [("norm_eps", ctypes.c_float), ("rope_base", ctypes.c_float), ("split_backward", ctypes.c_int32),
-                ("recompute", ctypes.c_int32)]
+                ("recompute", ctypes.c_int32), ("group_mbs", ctypes.c_int32)]
 
 
 class _AdamRange(ctypes.Structure):
@@ -98,6 +99,9 @@ def load_library(path: str | None = None):
     L.stage_backward_input.argtypes = [vp, i32, vp, vp, vp]
     L.stage_backward_weight.argtypes = [vp, i32, i32, f32, vp]
     L.stage_backward_weight_group.argtypes = [vp, i32, i32, f32, vp]
+    L.stage_forward_group.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.stage_backward_input_group.argtypes = [vp, i32, i32, vp, vp, vp]
+    L.stage_backward_accumulate_group.argtypes = [vp, i32, i32, vp, vp, f32, vp]
     L.stage_accumulate_grads.argtypes = [vp, i32, f32, vp]
     L.shard_adam_step.argtypes = [vp, u64, u64, ctypes.POINTER(_Adam), vp]
     L.shard_adam_step_ranges.argtypes = [vp, ctypes.POINTER(_AdamRange), i32, ctypes.POINTER(_Adam), vp]
@@ -108,6 +112,7 @@ def load_library(path: str | None = None):
     L.zpp_stage_region.argtypes = [vp, ctypes.c_char_p, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(u64),
                                    ctypes.POINTER(i32)]
     L.zpp_device_create.argtypes = [ctypes.POINTER(_Config), i32, i32, ctypes.POINTER(vp)]
+    L.zpp_device_create_per_stage.argtypes = [ctypes.POINTER(_Config), i32, i32, ctypes.POINTER(i32), ctypes.POINTER(vp)]
     L.zpp_device_destroy.argtypes = [vp]
     L.zpp_device_destroy.restype = None
     L.zpp_device_stage_count.argtypes = [vp]
@@ -142,7 +147,6 @@ def load_library(path: str | None = None):
     L.zpp_last_error.restype = ctypes.c_char_p
     L.zpp_version.restype = ctypes.c_char_p
     L.zpp_op_gemm_bf16_nt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i32, i32, vp]
-    L.zpp_op_gemm_bf16_tt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
     L.zpp_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd_noalloc.argtypes = [i32, i32, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
@@ -179,18 +183,20 @@ class StageConfig:
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
     split_backward: int = 0
-    recompute: int = 0
+    recompute: int = 0     # 0 none, 1 full, 2 selective
+    group_mbs: int = 0
 
     @classmethod
-    def from_shape(cls, shape, split_backward: int = 0, recompute: int = 0) -> "StageConfig":
+    def from_shape(cls, shape, split_backward: int = 0, recompute: int = 0, group_mbs: int = 0) -> "StageConfig":
         g = (lambda k: shape[k]) if isinstance(shape, dict) else (lambda k: getattr(shape, k))
         return cls(*(g(k) for k in ("arch", "n_blocks", "hidden", "n_heads", "ffn", "seq", "micro_batch", "unit_mbs",
-                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")), split_backward, recompute)
+                                    "compute_dtype", "gelu_mode", "norm_eps", "rope_base")), split_backward, recompute,
+                   group_mbs)
 
     def _c(self) -> _Config:
         return _Config(self.arch, self.n_blocks, self.hidden, self.n_heads, self.ffn, self.seq, self.micro_batch,
                        self.unit_mbs, self.compute_dtype, self.gelu_mode, self.norm_eps, self.rope_base,
-                       self.split_backward, self.recompute)
+                       self.split_backward, self.recompute, self.group_mbs)
 
 
 def _adam_struct(lr, beta1, beta2, eps, weight_decay, grad_scale=1.0, step=1, decoupled_wd=1, zero_grad=0,
@@ -210,9 +216,9 @@ class Stage:
     workspace and binds them; otherwise call :meth:`bind` with your own tensors."""
 
     def __init__(self, cfg, device: str | None = "cuda:0", allocate: bool = True, split_backward: int = 0,
-                 recompute: bool = False):
+                 recompute: int = 0, group_mbs: int = 0):
         self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward),
-                                                                                   int(recompute))
+                                                                                   int(recompute), int(group_mbs))
         self._h = ctypes.c_void_p()
         c = self.cfg._c()
         _check(lib().zpp_stage_create(ctypes.byref(c), ctypes.byref(self._h)))
@@ -308,6 +314,30 @@ class Stage:
     def backward_weight_group(self, first: int, count: int, scale: float = 1.0, stream=None):
         _check(lib().stage_backward_weight_group(self._h, first, count, scale, _stream_ptr(stream)))
 
+    def forward_group(self, first: int, count: int, x, y=None, stream=None):
+        """x, y: [count * T, h], micro-batch first + k in rows [k*T, (k+1)*T)."""
+        import torch
+        if y is None:
+            y = torch.empty_like(x)
+        _check(lib().stage_forward_group(self._h, first, count, x.data_ptr(), y.data_ptr(), _stream_ptr(stream)))
+        return y
+
+    def backward_input_group(self, first: int, count: int, dy, dx=None, stream=None):
+        import torch
+        if dx is None:
+            dx = torch.empty_like(dy)
+        _check(lib().stage_backward_input_group(self._h, first, count, dy.data_ptr(), dx.data_ptr(),
+                                                _stream_ptr(stream)))
+        return dx
+
+    def backward_accumulate_group(self, first: int, count: int, dy, dx=None, scale: float = 1.0, stream=None):
+        import torch
+        if dx is None:
+            dx = torch.empty_like(dy)
+        _check(lib().stage_backward_accumulate_group(self._h, first, count, dy.data_ptr(), dx.data_ptr(), scale,
+                                                     _stream_ptr(stream)))
+        return dx
+
     def accumulate_grads(self, mb: int, scale: float = 1.0, stream=None):
         _check(lib().stage_accumulate_grads(self._h, mb, scale, _stream_ptr(stream)))
 
@@ -354,12 +384,21 @@ class Device:
     torch tensors for P, G, M, V (V * N elements, stage v at [v*N, (v+1)*N)) and the workspace."""
 
     def __init__(self, cfg, n_stages: int, prefetch: bool = True, device: str | None = "cuda:0",
-                 allocate: bool = True, recompute: bool = False, split_backward: int = 0):
-        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(cfg, int(split_backward),
-                                                                                   int(recompute))
+                 allocate: bool = True, recompute=0, split_backward: int = 0):
+        """recompute: one mode for all stages (0 none, 1 full, 2 selective) or a list with one mode per stage."""
+        per_stage = list(recompute) if isinstance(recompute, (list, tuple)) else None
+        self.cfg = cfg if isinstance(cfg, StageConfig) else StageConfig.from_shape(
+            cfg, int(split_backward), 0 if per_stage is not None else int(recompute))
         self._h = ctypes.c_void_p()
         c = self.cfg._c()
-        _check(lib().zpp_device_create(ctypes.byref(c), n_stages, int(prefetch), ctypes.byref(self._h)))
+        if per_stage is not None:
+            if len(per_stage) != n_stages:
+                raise ValueError("one recomputation mode per stage")
+            modes = (ctypes.c_int32 * n_stages)(*[int(m) for m in per_stage])
+            _check(lib().zpp_device_create_per_stage(ctypes.byref(c), n_stages, int(prefetch), modes,
+                                                     ctypes.byref(self._h)))
+        else:
+            _check(lib().zpp_device_create(ctypes.byref(c), n_stages, int(prefetch), ctypes.byref(self._h)))
         self.n_stages = n_stages
         self.U = self.cfg.unit_mbs
         self.N_total = int(lib().zpp_device_param_count(self._h))
@@ -480,8 +519,11 @@ def profile_read():
 
 
 # ---- operator-level entry points (include/zpp_ops.h) ----------------------------------------------
-def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, variant: int = -1, stream=None, accumulate: bool = False):
-    """C = A . B^T (+ bias) (+ resid); accumulate (float C only): C += A . B^T."""
+GEMM_TILES = {"auto": -1, "256x256": 0, "128x128": 1, "256x128": 2, "128x256": 3, "256x256w4": 4}
+
+
+def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, tile="auto", stream=None, accumulate: bool = False):
+    """C = A . B^T (+ bias) (+ resid); accumulate (float C only): C += A . B^T.  tile: a key of GEMM_TILES."""
     import torch
     if accumulate and C.dtype != torch.float32:
         raise ValueError("accumulate needs a float32 C")
@@ -490,18 +532,8 @@ def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, variant: int = -1, stream=No
     _check(lib().zpp_op_gemm_bf16_nt(M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(),
                                      C.stride(0), None if bias is None else bias.data_ptr(),
                                      None if resid is None else resid.data_ptr(),
-                                     2 if accumulate else int(C.dtype == torch.float32), variant,
+                                     2 if accumulate else int(C.dtype == torch.float32), GEMM_TILES[tile],
                                      _stream_ptr(stream)))
-    return C
-
-
-def op_gemm_bf16_tt(A, B, C, stream=None):
-    """C[M,N] = A^T . B with A [K, M] and B [K, N]."""
-    import torch
-    K, M = A.shape
-    N = B.shape[1]
-    _check(lib().zpp_op_gemm_bf16_tt(M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(),
-                                     C.stride(0), int(C.dtype == torch.float32), _stream_ptr(stream)))
     return C
 
 

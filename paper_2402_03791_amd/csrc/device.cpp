@@ -23,7 +23,8 @@ struct zpp_device {
     uint64_t N = 0;
     StageParts parts{};
     uint64_t slot_off[2] = {0, 0}, scratch_off = 0, ws_bytes = 0;
-    std::vector<uint64_t> stash_off;
+    std::vector<uint64_t> stash_off, stash_bytes;
+    std::vector<int> split;  // per stage: its split_backward (0: the fused backward call per micro-batch)
     bool bound = false;
     // working-copy slots: which stage's parameters a slot holds, and the two events that order its reuse
     int owner[2] = {-1, -1};
@@ -135,7 +136,8 @@ zpp_status run_phase(zpp_device *d, bool descending, hipStream_t main, hipStream
 
 extern "C" {
 
-zpp_status zpp_device_create(const zpp_stage_config *cfg, int32_t n_stages, int32_t prefetch, zpp_device **out)
+zpp_status zpp_device_create_per_stage(const zpp_stage_config *cfg, int32_t n_stages, int32_t prefetch,
+                                       const int32_t *recompute, zpp_device **out)
 {
     if (!cfg || !out) return set_error(ZPP_ERR_ARG, "cfg/out is NULL");
     if (n_stages < 1 || n_stages > 4096) return set_error(ZPP_ERR_ARG, "n_stages must be in [1, 4096]");
@@ -145,16 +147,30 @@ zpp_status zpp_device_create(const zpp_stage_config *cfg, int32_t n_stages, int3
     d->V = n_stages;
     d->U = cfg->unit_mbs;
     d->slots = (prefetch && n_stages > 1) ? 2 : 1;
+    uint64_t scratch = 0;
     for (int v = 0; v < n_stages; ++v) {
+        zpp_stage_config c = *cfg;
+        if (recompute) c.recompute = recompute[v];
+        // a stage that recomputes runs its two gradient tasks back to back so that one recomputation
+        // serves both (Section 3.3); its stash needs no room for what the tasks hand to each other
+        if (c.recompute != ZPP_RECOMPUTE_NONE) {
+            c.group_mbs = std::max(c.group_mbs, c.split_backward);
+            c.split_backward = 0;
+        }
         zpp_stage *s = nullptr;
-        if (zpp_status e = zpp_stage_create(cfg, &s)) {
+        if (zpp_status e = zpp_stage_create(&c, &s)) {
             zpp_device_destroy(d);
             return e;
         }
         d->st.push_back(s);
+        d->split.push_back(c.split_backward);
+        const StageParts p = stage_parts(s);
+        if (v == 0) d->parts = p;
+        scratch = std::max(scratch, p.scratch);
+        d->stash_bytes.push_back(p.stash);
     }
     d->N = zpp_stage_param_count(d->st[0]);
-    d->parts = stage_parts(d->st[0]);
+    d->parts.scratch = scratch;
     uint64_t cur = 0;
     for (int i = 0; i < d->slots; ++i) {
         d->slot_off[i] = cur;
@@ -164,11 +180,16 @@ zpp_status zpp_device_create(const zpp_stage_config *cfg, int32_t n_stages, int3
     cur = align_up(cur + d->parts.scratch);
     for (int v = 0; v < n_stages; ++v) {
         d->stash_off.push_back(cur);
-        cur = align_up(cur + d->parts.stash);
+        cur = align_up(cur + d->stash_bytes[v]);
     }
     d->ws_bytes = cur;
     *out = d;
     return ZPP_OK;
+}
+
+zpp_status zpp_device_create(const zpp_stage_config *cfg, int32_t n_stages, int32_t prefetch, zpp_device **out)
+{
+    return zpp_device_create_per_stage(cfg, n_stages, prefetch, nullptr, out);
 }
 
 void zpp_device_destroy(zpp_device *d)
@@ -245,30 +266,22 @@ zpp_status device_backward_unit(zpp_device *d, const void *const *dy, void *cons
 {
     if (zpp_status e = check(d, true)) return e;
     if (!dy || !dx) return set_error(ZPP_ERR_ARG, "dy/dx is NULL");
-    // split_backward = g in the configuration: the stage's input-gradient tasks first, then its
-    // weight-gradient tasks in groups of g micro-batches (one by one where grouping is not supported)
-    const int g = d->cfg.split_backward;
+    // A stage with split_backward = g: its input-gradient tasks first, then its weight-gradient tasks in groups
+    // of g micro-batches; a stage without (and every stage that recomputes): the fused call per micro-batch.
     return run_phase(
         d, true, (hipStream_t)stream, (hipStream_t)side_stream,
         [&](int v, int m) {
             const void *dyp = dy[(size_t)v * d->U + m];
             void *dxp = dx[(size_t)v * d->U + m];
-            return g > 0 ? stage_backward_input(d->st[v], m, dyp, dxp, stream)
-                         : stage_backward_accumulate(d->st[v], m, dyp, dxp, scale, stream);
+            return d->split[v] > 0 ? stage_backward_input(d->st[v], m, dyp, dxp, stream)
+                                   : stage_backward_accumulate(d->st[v], m, dyp, dxp, scale, stream);
         },
         [&](int v) -> zpp_status {
+            const int g = d->split[v];
             if (g <= 0) return ZPP_OK;
-            for (int first = 0; first < d->U; first += g) {
-                const int count = std::min(g, d->U - first);
-                zpp_status e = count > 1 ? stage_backward_weight_group(d->st[v], first, count, scale, stream)
-                                         : ZPP_ERR_UNSUPPORTED;
-                if (e == ZPP_ERR_UNSUPPORTED) {
-                    e = ZPP_OK;
-                    for (int m = first; m < first + count && e == ZPP_OK; ++m)
-                        e = stage_backward_weight(d->st[v], m, 1, scale, stream);
-                }
-                if (e) return e;
-            }
+            for (int first = 0; first < d->U; first += g)
+                if (zpp_status e = stage_backward_weight_group(d->st[v], first, std::min(g, d->U - first), scale, stream))
+                    return e;
             return ZPP_OK;
         });
 }

@@ -320,6 +320,34 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const T *__restrict__ g
     store16(dgu + t * 2 * f + f + c, du);
 }
 
+// g = GeLU(u) element-wise on stored pre-activations: what the epilogue of the first MLP product computes
+// from the value it stores, for selective recomputation (n elements, a multiple of the 16-byte vector).
+template <class T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T *__restrict__ u, T *__restrict__ g, int64_t nv, int mode)
+{
+    constexpr int VN = Vec16<T>::N;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= nv) return;
+    const Vec16<T> x = load16(u + idx * VN);
+    Vec16<T> o;
+#pragma unroll
+    for (int k = 0; k < VN; ++k) o.set(k, gelu_fwd(x.get(k), mode));
+    store16(g + idx * VN, o);
+}
+
+hipError_t launch_gelu_fwd(int dt, const void *u, void *g, int64_t n, int gelu_mode, hipStream_t s)
+{
+    const int64_t nv = n / (dt == DT_BF16 ? 8 : 4);
+    if (nv == 0) return hipSuccess;
+    if (n % (dt == DT_BF16 ? 8 : 4)) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((nv + 255) / 256);
+    if (dt == DT_BF16)
+        gelu_fwd_kernel<bf16><<<grid, 256, 0, s>>>((const bf16 *)u, (bf16 *)g, nv, gelu_mode);
+    else
+        gelu_fwd_kernel<float><<<grid, 256, 0, s>>>((const float *)u, (float *)g, nv, gelu_mode);
+    return hipGetLastError();
+}
+
 hipError_t launch_swiglu_fwd(int dt, const void *gu, void *act, int64_t T, int64_t f, hipStream_t s)
 {
     const int64_t n = T * (f / (dt == DT_BF16 ? 8 : 4));

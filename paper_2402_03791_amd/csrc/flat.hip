@@ -1,7 +1,7 @@
 // Flat-buffer passes over the ZeRO-3-style shard: materialise (stand-in for the per-unit parameter
 // all-gather), gradient accumulation (stand-in for the per-unit reduce-scatter) and the fused Adam
 // step (the optimizer-step task).  All three are HBM-bandwidth bound: 16-byte accesses, 64-bit
-// indexing (the flat buffers exceed 4 GiB at the wide configuration), grid-stride loops.
+// indexing (the flat buffers exceed 4 GiB at the wide configuration), one contiguous chunk per work-group.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -83,10 +83,10 @@ hipError_t launch_materialize(const float *P, void *W, uint64_t n, int dt, hipSt
     return hipGetLastError();
 }
 
-// Wt[c, r] = bf16(P[r, c]).  64x64 tiles through LDS; reads and writes are both row-contiguous.
-__global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__restrict__ P,
-                                                             bf16 *__restrict__ Wt, uint64_t rows,
-                                                             uint64_t cols)
+// Wt[c, r] = bf16(P[r, c]), any shape: 64x64 tiles through LDS, element accesses (the ragged fallback).
+__global__ __launch_bounds__(256) void transpose_cast_ragged_kernel(const float *__restrict__ P,
+                                                                    bf16 *__restrict__ Wt, uint64_t rows,
+                                                                    uint64_t cols)
 {
     __shared__ float tile[64][65];
     const uint64_t r0 = (uint64_t)blockIdx.y * 64, c0 = (uint64_t)blockIdx.x * 64;
@@ -102,11 +102,55 @@ __global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__rest
     }
 }
 
+// The same for rows and cols in multiples of 64, at streaming speed: a work-group takes a 64x64 tile with
+// 16-byte loads (each thread two pairs of vertically adjacent 4-float pieces, all four loads in flight before
+// the first use), rounds to bf16, packs the two rows of a pair into one 32-bit word per column (the output is
+// contiguous along rows) and writes the words transposed into LDS - row stride 33 words, so the 64 lanes of a
+// wave hit 64 different banks - then reads eight consecutive rows of a column back and stores them with one
+// 16-byte non-temporal store per lane (a full 128-byte line per 8 lanes).
+__global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__restrict__ P, bf16 *__restrict__ Wt,
+                                                             uint64_t rows, uint64_t cols)
+{
+    constexpr int S = 33;                  // words per LDS row (32 row pairs + 1)
+    __shared__ uint32_t tile[64 * S];      // [column][row pair]
+    const uint64_t r0 = (uint64_t)blockIdx.y * 64, c0 = (uint64_t)blockIdx.x * 64;
+    const int t = threadIdx.x;
+    const int col4 = t & 15, pair0 = t >> 4;   // row pairs pair0 and pair0 + 16
+    f32x4 top[2], bot[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const float *src = P + (r0 + 2 * (pair0 + 16 * u)) * cols + c0 + 4 * col4;
+        top[u] = nt_load(reinterpret_cast<const f32x4 *>(src));
+        bot[u] = nt_load(reinterpret_cast<const f32x4 *>(src + cols));
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            bf16x2 w;
+            w[0] = (bf16)top[u][k];
+            w[1] = (bf16)bot[u][k];
+            tile[(4 * col4 + k) * S + pair0 + 16 * u] = __builtin_bit_cast(uint32_t, w);
+        }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int c = (t >> 3) + 32 * u, q = t & 7;   // rows 8q .. 8q+7 of output row c
+        u32x4 o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = tile[c * S + 4 * q + k];
+        nt_store(o, reinterpret_cast<u32x4 *>(Wt + (c0 + c) * rows + r0 + 8 * q));
+    }
+}
+
 hipError_t launch_transpose_cast(const float *P, void *Wt, uint64_t rows, uint64_t cols, hipStream_t s)
 {
     if (rows == 0 || cols == 0) return hipSuccess;
     dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
-    transpose_cast_kernel<<<grid, 256, 0, s>>>(P, (bf16 *)Wt, rows, cols);
+    if (rows % 64 == 0 && cols % 64 == 0 && (reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(Wt)) % 16 == 0)
+        transpose_cast_kernel<<<grid, 256, 0, s>>>(P, (bf16 *)Wt, rows, cols);
+    else
+        transpose_cast_ragged_kernel<<<grid, 256, 0, s>>>(P, (bf16 *)Wt, rows, cols);
     return hipGetLastError();
 }
 

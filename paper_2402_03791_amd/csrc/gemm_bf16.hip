@@ -1,16 +1,12 @@
-// bf16 MFMA GEMMs for gfx950: C[M,N] = A[M,K] . B[N,K]^T (both operands K-contiguous) and the K-major
-// variant C = A^T . B, fp32 accumulation in v_mfma_f32_32x32x16_bf16, fused epilogues (bias,
-// residual, GeLU, GeLU', fp32 or bf16 output).
+// bf16 MFMA GEMM for gfx950: C[M,N] = A[M,K] . B[N,K]^T (both operands K-contiguous), fp32 accumulation in
+// v_mfma_f32_32x32x16_bf16, fused epilogues (bias, residual, GeLU, GeLU', fp32 or bf16 output, in-place
+// accumulation of fp32 output).
 //
-// Three kernel generations live here; the stage uses the third, the others stay selectable through
-// the operator-level entry point (and the second carries the K-major operand paths):
-//   1. register-staged: 16-byte global loads into registers while the previous K-step is multiplied
-//      out of LDS, then written to the other LDS buffer (double buffering, one barrier per step);
-//   2. pipelined: global -> LDS directly, K loop rotated across the barrier, instruction mix steered
-//      with scheduling-group barriers;
-//   3. hand-ordered: as 2, with the exact instruction order pinned and no vector address arithmetic
-//      in the loop.
-// Common to all: a work-group computes a BM x BN tile, K advances in steps of 64; LDS rows are 128
+// Two kernels: a 256x256 / 128x128 tile kernel with two LDS stages and a 256x128 / 128x256 tile kernel with
+// a ring of three.  Both copy their operands global -> LDS directly, rotate the K loop across the barrier,
+// and have the order of every MFMA, LDS read and copy written out and pinned, with no vector address
+// arithmetic in the loop.
+// Common: a work-group computes a BM x BN tile, K advances in steps of 64; LDS rows are 128
 // bytes (64 bf16) with an XOR swizzle of the 16-byte chunk index so that the row-wise 16-byte writes
 // and the MFMA-operand 16-byte reads (32 consecutive rows, same chunk) are bank-conflict free;
 // work-group ids are remapped so that each XCD (one L2 each, ids are dealt round-robin over 8 XCDs)
@@ -19,6 +15,7 @@
 #include "device_utils.h"
 #include "kernels.h"
 
+#include <mutex>
 #include <utility>
 
 namespace zpp {
@@ -250,23 +247,12 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
     });
 }
 
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+// Which tile a work-group computes.  Work-group ids are dealt round-robin over the 8 XCDs (one L2 each):
+// ids are first regrouped so that an XCD gets a contiguous run of tile numbers, and tile numbers walk the grid
+// in bands of 8 tile rows, down a column of the band first, so that the tiles in flight on an XCD share their
+// A rows and B columns in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
 {
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_CH = BM * 8 / NTH, B_CH = BN * 8 / NTH;  // 16-byte chunks per thread per K-step
-    static_assert(BM * 8 % NTH == 0 && BN * 8 % NTH == 0, "tile/threads mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);  // [2][BM*64]
-    bf16 *Bs = As + 2 * BM * kBK;                   // [2][BN*64]
-
-    // ---- tile assignment: XCD-aware, grouped along M
-    int pid = blockIdx.x;
     const int total = tiles_m * tiles_n;
     if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
     constexpr int GROUP_M = 8;
@@ -274,338 +260,13 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     const int group = pid / per_group;
     const int first_m = group * GROUP_M;
     const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    // ---- global load plan
-    const bf16 *a_ptr[A_CH];
-    const bf16 *b_ptr[B_CH];
-    int a_lds[A_CH], b_lds[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        const int q = tid + i * NTH;
-        const int row = q >> 3, ch = q & 7;
-        int64_t gm = m0 + row;
-        if (gm > M - 1) gm = M - 1;
-        a_ptr[i] = A + gm * lda + ch * 8;
-        a_lds[i] = lds_off(row, ch);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int q = tid + i * NTH;
-        const int row = q >> 3, ch = q & 7;
-        int64_t gn = n0 + row;
-        if (gn > N - 1) gn = N - 1;
-        b_ptr[i] = B + gn * ldb + ch * 8;
-        b_lds[i] = lds_off(row, ch);
-    }
-
-    bf16x8 a_reg[A_CH], b_reg[B_CH];
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    const int nk = (int)(K / kBK);
-
-    auto load_global = [&](int kt) {
-        const int64_t ko = (int64_t)kt * kBK;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const bf16x8 *>(a_ptr[i] + ko);
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const bf16x8 *>(b_ptr[i] + ko);
-    };
-    auto store_lds = [&](int buf) {
-        bf16 *as = As + buf * BM * kBK;
-        bf16 *bs = Bs + buf * BN * kBK;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<bf16x8 *>(as + a_lds[i]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<bf16x8 *>(bs + b_lds[i]) = b_reg[i];
-    };
-
-    const int a_row0 = wm * WM + (lane & 31);
-    const int b_row0 = wn * WN + (lane & 31);
-    const int khalf = lane >> 5;
-
-    auto compute = [&](int buf) {
-        const bf16 *as = As + buf * BM * kBK;
-        const bf16 *bs = Bs + buf * BN * kBK;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 af[MT], bfr[NT];
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, ks * 2 + khalf));
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, ks * 2 + khalf));
-#pragma unroll
-            for (int i = 0; i < MT; ++i)
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) load_global(kt + 1);
-        compute(kt & 1);
-        if (kt + 1 < nk) store_lds((kt + 1) & 1);
-        __syncthreads();
-    }
-
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void gbl_void_t;
-
-// ---------------------------------------------------------------------------------------------
-// Second generation ("pipelined"): operand tiles go from global memory straight into LDS
-// (global_load_lds, 16 bytes per lane, no staging registers and no ds_write; each load instruction
-// of a wave fills 1 KB of the tile: lane i lands at byte 16*i, so lane i fetches the chunk the swizzle
-// assigns to that slot), and the K loop is rotated so that the MFMAs of
-// the last K sub-step of a tile overlap the first LDS operand reads of the next tile (right after
-// the barrier), and the instruction order inside each region is pinned with scheduling-group
-// barriers: one LDS read for every two MFMAs.  Meant for one wave per SIMD with a large
-// accumulator tile (lowest LDS traffic per flop), where nothing else hides LDS latency.
-// Operand layouts: AT = false: A is [M, K] with K contiguous (rows of the LDS tile are M indices, read
-// with plain 16-byte LDS loads).  AT = true: A is [K, M] with M contiguous (rows of the LDS tile are K
-// indices; the MFMA operand is gathered with the LDS transposing load, 4 consecutive K rows of one M
-// column per lane and load).  Same for B with N in place of M.  The K order inside an MFMA operand
-// is the same in both cases, so the layouts mix freely.
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
-
-// element offset inside a [64][LD] tile stored K-major; 32-byte granules XOR-swizzled with the row
-template <int LD>
-__device__ __forceinline__ int tr_off(int row, int col)
-{
-    return row * LD + ((((col >> 4) ^ ((row & 3) << 1))) << 4) + (col & 15);
-}
-
-template <int LD>
-__device__ __forceinline__ bf16x8 tr_read8(const bf16 *tile, int k0, int col_base, int lane)
-{
-    const int i = lane & 15, e = i >> 2, q4 = i & 3;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tile + tr_off<LD>(k0 + e, col_base + 4 * q4)));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(tile + tr_off<LD>(k0 + 4 + e, col_base + 4 * q4)));
-    typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-}
-
-template <int BM, int BN, int WGM, int WGN, bool AT, bool BT>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_p_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
-{
-    constexpr int NW = WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *As = reinterpret_cast<bf16 *>(smem_raw);
-    bf16 *Bs = As + 2 * BM * kBK;
-
-    int pid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    const int lrow = lane >> 3, lch = lane & 7;
-    const bf16 *a_g[A_I];
-    const bf16 *b_g[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        if constexpr (!AT) {
-            const int row = (wave * A_I + j) * 8 + lrow;
-            const int sw = (row & 7) ^ ((row >> 3) & 1);
-            int64_t gm = m0 + row;
-            if (gm > M - 1) gm = M - 1;
-            a_g[j] = A + gm * lda + ((lch ^ sw) << 3);
-        } else {
-            const int byte = (wave * A_I + j) * 1024 + lane * 16;
-            const int r = byte / (BM * 2), pch = (byte % (BM * 2)) >> 4;
-            const int c = ((((pch >> 1) ^ ((r & 3) << 1))) << 1) | (pch & 1);
-            int64_t col = m0 + c * 8;
-            if (col + 8 > M) col = M - 8;
-            a_g[j] = A + (int64_t)r * lda + col;
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < B_I; ++j) {
-        if constexpr (!BT) {
-            const int row = (wave * B_I + j) * 8 + lrow;
-            const int sw = (row & 7) ^ ((row >> 3) & 1);
-            int64_t gn = n0 + row;
-            if (gn > N - 1) gn = N - 1;
-            b_g[j] = B + gn * ldb + ((lch ^ sw) << 3);
-        } else {
-            const int byte = (wave * B_I + j) * 1024 + lane * 16;
-            const int r = byte / (BN * 2), pch = (byte % (BN * 2)) >> 4;
-            const int c = ((((pch >> 1) ^ ((r & 3) << 1))) << 1) | (pch & 1);
-            int64_t col = n0 + c * 8;
-            if (col + 8 > N) col = N - 8;
-            b_g[j] = B + (int64_t)r * ldb + col;
-        }
-    }
-    const int64_t a_kstep = AT ? (int64_t)kBK * lda : kBK;  // elements to advance per K-step
-    const int64_t b_kstep = BT ? (int64_t)kBK * ldb : kBK;
-
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    const int nk = (int)(K / kBK);
-
-    // Loads of one tile are issued in two halves so that the memory pipeline is fed at a steady rate
-    // instead of in bursts (a burst of 16-byte-per-lane loads blocks the issuing waves, MFMAs included).
-    constexpr int LPS = A_I + B_I;
-    constexpr int G1 = LPS / 2, G2 = LPS - G1;
-    auto issue_loads = [&](int kt, int buf, int first, int count) {
-        bf16 *as = As + buf * BM * kBK + wave * A_I * 8 * kBK;  // 512 elements (1 KB) per instruction
-        bf16 *bs = Bs + buf * BN * kBK + wave * B_I * 8 * kBK;
-#pragma unroll
-        for (int j = 0; j < LPS; ++j) {
-            if (j < first || j >= first + count) continue;
-            if (j < A_I)
-                __builtin_amdgcn_global_load_lds((gbl_void_t *)(a_g[j] + kt * a_kstep),
-                                                 (lds_void_t *)(as + j * 8 * kBK), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds((gbl_void_t *)(b_g[j - A_I] + kt * b_kstep),
-                                                 (lds_void_t *)(bs + (j - A_I) * 8 * kBK), 16, 0, 0);
-        }
-    };
-
-    const int a_row0 = wm * WM + (lane & 31);
-    const int b_row0 = wn * WN + (lane & 31);
-    const int khalf = lane >> 5;
-
-    bf16x8 af[2][MT], bfr[2][NT];
-    auto read_frags = [&](int buf, int ks, int slot) {
-        const bf16 *as = As + buf * BM * kBK;
-        const bf16 *bs = Bs + buf * BN * kBK;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-            if constexpr (!AT)
-                af[slot][i] = *reinterpret_cast<const bf16x8 *>(as + lds_off(a_row0 + i * 32, ks * 2 + khalf));
-            else
-                af[slot][i] = tr_read8<BM>(as, ks * 16 + 8 * khalf, wm * WM + i * 32 + ((lane >> 4) & 1) * 16, lane);
-        }
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            if constexpr (!BT)
-                bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(bs + lds_off(b_row0 + j * 32, ks * 2 + khalf));
-            else
-                bfr[slot][j] = tr_read8<BN>(bs, ks * 16 + 8 * khalf, wn * WN + j * 32 + ((lane >> 4) & 1) * 16, lane);
-        }
-    };
-    auto mfma_block = [&](int slot) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
-    };
-    constexpr int READS = (AT ? 2 : 1) * MT + (BT ? 2 : 1) * NT;  // LDS reads per sub-step
-    constexpr int MFMAS = MT * NT;         // MFMAs per sub-step
-    constexpr int MPR = MFMAS / READS > 0 ? MFMAS / READS : 1;  // MFMAs per LDS read in the interleave
-
-    issue_loads(0, 0, 0, LPS);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    issue_loads(nk > 1 ? 1 : 0, 1, 0, LPS);
-    read_frags(0, 0, 0);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        // second half of the loads of tile kt+1 (first half went out after the previous barrier)
-        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
-        if (kt > 0) issue_loads(nxt1, buf ^ 1, G1, G2);
-        // sub-steps 0..2 of tile kt, each overlapping the operand reads of the next sub-step
-#pragma unroll
-        for (int ks = 0; ks < 3; ++ks) {
-            read_frags(buf, ks + 1, (ks + 1) & 1);
-            mfma_block(ks & 1);
-        }
-#pragma unroll
-        for (int r = 0; r < 3 * READS; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // 1 LDS read
-            if (r < G2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // 1 global->LDS load
-            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);  // MPR MFMAs
-        }
-        // tile kt+1 has landed and every wave is done reading tile kt
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
-        issue_loads(nxt2, buf, 0, G1);
-        read_frags(buf ^ 1, 0, 0);  // first operands of tile kt+1 (harmless garbage after the last tile)
-        mfma_block(1);              // sub-step 3 of tile kt
-#pragma unroll
-        for (int r = 0; r < READS; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (r < G1) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
-        }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
-
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-template <int BM, int BN, int WGM, int WGN, bool AT = false, bool BT = false>
-static hipError_t launch_variant_p(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_p_kernel<BM, BN, WGM, WGN, AT, BT>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
+    tm = first_m + (pid % per_group) % gsz;
+    tn = (pid % per_group) / gsz;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Third generation ("hand-ordered"): same data movement as the pipelined kernel (two LDS buffers of
-// K = 64, operands global -> LDS directly, K loop rotated across the barrier), but
+// Two-stage kernel: two LDS buffers of K = 64, operands global -> LDS directly, K loop rotated across the
+// barrier, and
 //   * the instruction order of every phase is written out and pinned with scheduling barriers: the
 //     LDS reads of the next K sub-step are issued one per MFMA at the start of the current sub-step,
 //     so each has at least half a sub-step of MFMA time to return before it is needed;
@@ -631,16 +292,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
-    int pid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
     const int tid = threadIdx.x;
@@ -804,236 +457,6 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fourth generation ("ring"): the hand-ordered kernel with K advancing in stages of 32 through a ring of
-// NS LDS stages instead of two buffers of 64.  The copies of a stage are issued NS-1 stages before it is
-// read, so with NS = 5 (all 160 KB of LDS) a tile has about three stages of MFMA time (~3000 cycles) to
-// arrive instead of about one and a half; two buffers of 64 do not cover a loaded HBM round trip and the
-// loop then waits at every K-step.  LDS rows are 64 bytes (4 chunks of 16), chunk c of row r sits at
-// chunk position c ^ ((r >> 2) & 3): 16 consecutive rows at one chunk hit all 64 banks exactly once.
-// Per stage and wave: 2 K sub-steps of MT*NT MFMAs, MT+NT operand reads each (issued one sub-step ahead,
-// one per MFMA), A_I + B_I copies, one barrier.
-template <int BM, int BN, int WGM, int WGN, int NS>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_r_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
-{
-    constexpr int SK = 32;                     // K per stage
-    constexpr int NW = WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_I = BM / 16 / NW, B_I = BN / 16 / NW;  // 1 KB copies (16 rows of 64 B) per wave per stage
-    constexpr int LPS = A_I + B_I;
-    constexpr int G1 = LPS / 2, G2 = LPS - G1;
-    constexpr int READS = MT + NT, MFMAS = MT * NT;
-    constexpr int A_ST = BM * SK * 2, B_ST = BN * SK * 2;  // bytes per stage
-    constexpr int B_REGION = NS * A_ST;
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile/waves mismatch");
-    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
-    static_assert(NS >= 3 && NS <= 5, "ring depth");
-    static_assert((size_t)NS * (A_ST + B_ST) >= (size_t)NW * 32 * (WN + 8) * 4, "epilogue staging must fit");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-
-    int pid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    // ---- global side: scalar tile base + per-lane byte offset; a copy covers 16 rows x 64 bytes
-    const int lrow = lane >> 2, lch = lane & 3;
-    uint32_t a_voff[A_I], b_voff[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 16 + lrow;
-        const int sw = (row >> 2) & 3;
-        int64_t r = row;
-        if (m0 + r > M - 1) r = M - 1 - m0;
-        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
-    }
-#pragma unroll
-    for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 16 + lrow;
-        const int sw = (row >> 2) & 3;
-        int64_t r = row;
-        if (n0 + r > N - 1) r = N - 1 - n0;
-        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
-    }
-    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
-    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
-
-    // ---- LDS side: per-lane byte addresses of the operand chunk for the two K sub-steps of a stage.
-    // Immediates reach 64 KB, so stages 0..3 hang off one base register and stage 4 off a second one.
-    const int khalf = lane >> 5;
-    unsigned char *a_rd[2][2], *b_rd[2][2];
-    {
-        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
-        const int asw = (arow >> 2) & 3, bsw = (brow >> 2) & 3;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            a_rd[0][ks] = smem_raw + arow * 64 + (((ks * 2 + khalf) ^ asw) << 4);
-            b_rd[0][ks] = smem_raw + B_REGION + brow * 64 + (((ks * 2 + khalf) ^ bsw) << 4);
-            a_rd[1][ks] = a_rd[0][ks] + 3 * A_ST;
-            b_rd[1][ks] = b_rd[0][ks] + 3 * B_ST;
-        }
-    }
-
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    const int nst = (int)(K / SK);
-    bf16x8 af[2][MT], bfr[2][NT];
-
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
-    // copy n (0..LPS-1) of K stage `stage` (clamped by the caller) into ring slot `slot`
-    auto gll = [&](int n, int stage, int slot) {
-        const char *abase = a_tile + (int64_t)stage * (SK * 2);
-        const char *bbase = b_tile + (int64_t)stage * (SK * 2);
-        if (n < A_I) {
-            const uint32_t dst = a_slot + slot * A_ST + n * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
-                         : "memory");
-        } else {
-            const int m = n - A_I;
-            const uint32_t dst = b_slot + slot * B_ST + m * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
-                         : "memory");
-        }
-    };
-    // operand reads of sub-step RKS of ring slot RSLOT
-    auto rd_a = [&](auto slot_c, auto ks_c, int i) {
-        constexpr int SL = decltype(slot_c)::value, KS = decltype(ks_c)::value;
-        if constexpr (SL < 3)
-            return *reinterpret_cast<const bf16x8 *>(a_rd[0][KS] + SL * A_ST + i * 2048);
-        else
-            return *reinterpret_cast<const bf16x8 *>(a_rd[1][KS] + (SL - 3) * A_ST + i * 2048);
-    };
-    auto rd_b = [&](auto slot_c, auto ks_c, int j) {
-        constexpr int SL = decltype(slot_c)::value, KS = decltype(ks_c)::value;
-        if constexpr (SL < 3)
-            return *reinterpret_cast<const bf16x8 *>(b_rd[0][KS] + SL * B_ST + j * 2048);
-        else
-            return *reinterpret_cast<const bf16x8 *>(b_rd[1][KS] + (SL - 3) * B_ST + j * 2048);
-    };
-    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the
-    // reads of sub-step RKS of slot RSLOT into the other set and with GCNT copies (numbers GFIRST..) of
-    // stage gstage into slot GSLOT.
-    auto phase = [&](auto cur_c, auto rslot_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gslot_c, int gstage) {
-        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
-        constexpr int GSLOT = decltype(gslot_c)::value;
-        static_for<MFMAS>([&](auto tt) {
-            constexpr int t = decltype(tt)::value;
-            constexpr int i = t / NT, j = t % NT;
-            if constexpr (t < READS) {
-                if constexpr (t == 0)
-                    af[NXT][0] = rd_a(rslot_c, rks_c, 0);
-                else if constexpr (t <= NT)
-                    bfr[NXT][t - 1] = rd_b(rslot_c, rks_c, t - 1);
-                else
-                    af[NXT][t - NT] = rd_a(rslot_c, rks_c, t - NT);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (GCNT > 0) {
-                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
-                if constexpr (after > before) {
-                    gll(GFIRST + before, gstage, GSLOT);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        });
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using IG1 = std::integral_constant<int, G1>;
-    using IG2 = std::integral_constant<int, G2>;
-
-    // Stage st out of ring slot SLOT.  On entry fragment set 0 holds sub-step 0 of the stage; stages up to
-    // st+NS-2 have been requested.
-    auto stage_step = [&](auto slot_c, int st) {
-        constexpr int SLOT = decltype(slot_c)::value;
-        using IS = std::integral_constant<int, SLOT>;
-        using IN = std::integral_constant<int, (SLOT + 1) % NS>;          // next stage's slot
-        using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;     // slot freed by the previous stage
-        const int far = st + NS - 1 < nst ? st + NS - 1 : nst - 1;        // clamped: a surplus reload is never read
-        phase(I0{}, IS{}, I1{}, I0{}, IG1{}, IF{}, far);
-        // stage st+1 has landed (copies complete in order; NS-3 whole stages and the G1 copies just issued
-        // may stay in flight) and every wave has issued all its reads of stage st
-        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 3) * LPS + G1) : "memory");
-        __syncthreads();
-        phase(I1{}, IN{}, I0{}, IG1{}, IG2{}, IF{}, far);
-    };
-
-    // prologue: stages 0..NS-2
-    static_for<NS - 1>([&](auto ss) {
-        constexpr int S = decltype(ss)::value;
-        const int stg = S < nst ? S : nst - 1;
-#pragma unroll
-        for (int n = 0; n < LPS; ++n) gll(n, stg, S);
-    });
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    af[0][0] = rd_a(I0{}, I0{}, 0);
-#pragma unroll
-    for (int j = 0; j < NT; ++j) bfr[0][j] = rd_b(I0{}, I0{}, j);
-#pragma unroll
-    for (int i = 1; i < MT; ++i) af[0][i] = rd_a(I0{}, I0{}, i);
-
-    for (int st = 0; st < nst; st += NS)
-        static_for<NS>([&](auto ii) {
-            constexpr int I = decltype(ii)::value;
-            if (st + I < nst) stage_step(ii, st + I);
-        });
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
-
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-template <int BM, int BN, int WGM, int WGN, int NS>
-static hipError_t launch_variant_r(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)NS * (BM + BN) * 32 * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_nt_r_kernel<BM, BN, WGM, WGN, NS>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
 // Hand-ordered kernel with NS LDS stages of K = 64 (same 128-byte rows and swizzle as above) instead of
 // two: the copies of K-step kt+NS-1 are issued during K-step kt.  For the small tiles this is what
 // matters: a 128x128 work-group multiplies a K-step in ~500-1000 cycles, a loaded HBM round trip is
@@ -1062,16 +485,8 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
-    int pid = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int group = pid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    const int tm = first_m + (pid % per_group) % gsz;
-    const int tn = (pid % per_group) / gsz;
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
     const int tid = threadIdx.x;
@@ -1243,80 +658,43 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
+// One launch wrapper for both kernels: raises the kernel's dynamic LDS limit once per process (guarded, so
+// that host threads driving different stages may launch concurrently) and starts one work-group per tile.
+template <class Kernel>
+static hipError_t launch_tiles(Kernel kern, std::once_flag &once, hipError_t &attr_err, int BM, int BN, int threads,
+                               size_t lds, int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                               int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    kern<<<dim3((unsigned)(tiles_m * tiles_n)), threads, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+// two LDS stages
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t launch_two_stage(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
+                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    return launch_tiles(gemm_bf16_nt_h_kernel<BM, BN, WGM, WGN>, once, attr_err, BM, BN, WGM * WGN * 64,
+                        (size_t)2 * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
+}
+
+// a ring of NS LDS stages
 template <int BM, int BN, int WGM, int WGN, int NS>
-static hipError_t launch_variant_d(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+static hipError_t launch_ring(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
+                              void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)NS * (BM + BN) * kBK * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_nt_d_kernel<BM, BN, WGM, WGN, NS>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, int WGM, int WGN>
-static hipError_t launch_variant_h(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_nt_h_kernel<BM, BN, WGM, WGN>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, int WGM, int WGN>
-static hipError_t launch_variant(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                 int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    constexpr int NTH = WGM * WGN * 64;
-    constexpr size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
-    static bool attr_set = false;
-    auto kern = gemm_bf16_nt_kernel<BM, BN, WGM, WGN>;
-    if (!attr_set) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    kern<<<dim3((unsigned)(tiles_m * tiles_n)), NTH, lds, s>>>(M, N, K, A, lda, B, ldb, C, ldc, e, tiles_m,
-                                                                 tiles_n);
-    return hipGetLastError();
-}
-
-// C[M,N] = A^T . B with A stored [K, M] and B stored [K, N] (the weight-gradient product dY^T . X)
-hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
-{
-    if (M == 0 || N == 0) return hipSuccess;
-    if (K <= 0 || (K % kBK) || (M % 8) || (N % 8) || M < 8 || N < 8 || (lda % 8) || (ldb % 8))
-        return hipErrorInvalidValue;
-    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
-    const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
-    const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-    if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
-        return launch_variant_p<256, 256, 2, 4, true, true>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    return launch_variant_p<128, 128, 2, 2, true, true>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    return launch_tiles(gemm_bf16_nt_d_kernel<BM, BN, WGM, WGN, NS>, once, attr_err, BM, BN, WGM * WGN * 64,
+                        (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
 }
 
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)
@@ -1324,52 +702,37 @@ bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)
     return M > 0 && N > 0 && K > 0 && (K % kBK) == 0;
 }
 
-static int g_forced_variant = -1;
-void gemm_bf16_force_variant(int v) { g_forced_variant = v; }
-
 hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s, int tile)
 {
     if (M == 0 || N == 0) return hipSuccess;
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
               epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
-    int variant = g_forced_variant;
-    if (variant < 0) {
-        // 256x256 tiles, two LDS stages (variant 5): lowest LDS and L2 traffic per flop, but one work-group
-        // per CU, so a grid runs in rounds of 256 tiles; used when the rounds come out whole (or there are
-        // many).  Otherwise 256x128 / 128x256 tiles with three stages (variants 14, 15): twice as many tiles,
-        // and copies issued two K-steps ahead, which the shorter K-step of a smaller tile needs (a T x h
-        // output at T = 2048 is 128 big tiles; T x 3h is 384, a round and a half).  Small problems: 128x128.
+    if (tile == GEMM_TILE_AUTO) {
+        // 256x256 tiles, two LDS stages: lowest LDS and L2 traffic per flop, but one work-group per CU, so a
+        // grid runs in rounds of 256 tiles; used when the rounds come out whole (or there are many).
+        // Otherwise 256x128 / 128x256 tiles with three stages: twice as many tiles, and copies issued two
+        // K-steps ahead, which the shorter K-step of a smaller tile needs (a T x h output at T = 2048 is 128
+        // big tiles; T x 3h is 384, a round and a half).  Small problems: 128x128.
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
         if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024)) {
-            variant = 5;
+            tile = GEMM_TILE_256x256;
         } else {
             const int64_t ta = ((M + 255) / 256) * ((N + 127) / 128), tb = ((M + 127) / 128) * ((N + 255) / 256);
             if (ta >= 192 || tb >= 192)
-                variant = tb >= 192 ? 15 : 14;
+                tile = tb >= 192 ? GEMM_TILE_128x256 : GEMM_TILE_256x128;
             else
-                variant = 6;
+                tile = GEMM_TILE_128x128;
         }
     }
-    switch (variant) {
-    case 0: return launch_variant<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 1: return launch_variant<128, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 2: return launch_variant<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 3: return launch_variant_p<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 4: return launch_variant_p<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 5: return launch_variant_h<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 6: return launch_variant_h<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 7: return launch_variant_h<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 8: return launch_variant_h<128, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 12: return launch_variant_d<128, 128, 2, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 13: return launch_variant_d<128, 128, 2, 2, 5>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 14: return launch_variant_d<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 15: return launch_variant_d<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 9: return launch_variant_r<256, 256, 2, 4, 5>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 10: return launch_variant_r<256, 256, 2, 4, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case 11: return launch_variant_r<128, 128, 2, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    switch (tile) {
+    case GEMM_TILE_256x256: return launch_two_stage<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_128x128: return launch_two_stage<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_256x128: return launch_ring<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_128x256: return launch_ring<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_256x256_W4: return launch_two_stage<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }

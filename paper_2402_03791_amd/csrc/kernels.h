@@ -113,6 +113,8 @@ hipError_t launch_rope_table(float *table, int64_t seq, int64_t d, double base, 
 // rotates the Q and K parts of qkv[T, 3h] in place; sign = +1 forward, -1 inverse
 hipError_t launch_rope(int dt, void *qkv, const float *table, int64_t T, int64_t seq, int64_t nh, int64_t d,
                        int sign, hipStream_t s);
+// g[i] = GeLU(u[i]), n elements (a multiple of the 16-byte vector), as the epilogue of the first MLP product
+hipError_t launch_gelu_fwd(int dt, const void *u, void *g, int64_t n, int gelu_mode, hipStream_t s);
 // gu = [gate | up] of shape [T, 2f]; act[T, f] = silu(gate) * up
 hipError_t launch_swiglu_fwd(int dt, const void *gu, void *act, int64_t T, int64_t f, hipStream_t s);
 hipError_t launch_swiglu_bwd(int dt, const void *gu, const void *dact, void *dgu, int64_t T, int64_t f,
@@ -124,13 +126,14 @@ hipError_t launch_gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int6
                            const float *B, int64_t sbn, int64_t sbk, float *C, int64_t ldc,
                            const GemmEpi &epi, hipStream_t s);
 // bf16 MFMA GEMM, both operands K-contiguous: C[M,N] = A[M,K] . B[N,K]^T with fp32 accumulation.
-// Requires K % 64 == 0, lda/ldb % 8 == 0, 16-byte aligned bases.
+// Requires K % 64 == 0, lda/ldb % 8 == 0, 16-byte aligned bases.  tile: the work-group tile, chosen from
+// the shape when GEMM_TILE_AUTO (256x256 and 128x128: two LDS stages; 256x128 and 128x256: a ring of three;
+// 256x256 with four waves of 128x128 each: a third less LDS traffic per flop, a slower epilogue).
+enum { GEMM_TILE_AUTO = -1, GEMM_TILE_256x256 = 0, GEMM_TILE_128x128 = 1, GEMM_TILE_256x128 = 2, GEMM_TILE_128x256 = 3,
+       GEMM_TILE_256x256_W4 = 4, GEMM_TILE_LAST = 4 };
 hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
-// Same with both operands stored K-major: C[M,N] = A^T . B, A is [K, M] (M contiguous), B is [K, N].
-// Requires K % 64 == 0, M, N multiples of 8, lda/ldb % 8 == 0.
-hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
-                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s,
+                               int tile = GEMM_TILE_AUTO);
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
 
 // ---- causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each) ----

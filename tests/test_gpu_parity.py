@@ -11,7 +11,8 @@ import oracle
 import synth
 from synth import StageShape
 import paper_2402_03791_amd as zpp
-from _harness import (compare_units, make_inputs, rel_err, run_gpu_unit, run_oracle_unit, to_dev, to_np)
+from _harness import (compare_units, make_inputs, rel_err, run_gpu_unit, run_gpu_unit_grouped, run_oracle_unit, to_dev,
+                      to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -358,16 +359,26 @@ def test_activation_recomputation_reproduces_the_stashed_run(arch, dtype, kw):
     P0 = synth.make_params(sh, layout, gain_jitter=0.1)
     xs, dys = make_inputs(sh, sh.unit_mbs)
     plain = run_gpu_unit(sh, P0, xs, dys)
-    for in_place in (False, True):
-        rc = run_gpu_unit(sh, P0, xs, dys, recompute=True, in_place=in_place)
-        for a, b in zip(plain["ys"] + plain["dxs"], rc["ys"] + rc["dxs"]):
-            assert np.array_equal(a, b)
-        assert np.array_equal(plain["G"].view(np.uint32), rc["G"].view(np.uint32))
-        if not in_place:
-            assert np.array_equal(plain["S0"].view(np.uint32), rc["S0"].view(np.uint32))
+    for mode in (1, 2):                 # full, selective
+        for in_place in (False, True):
+            rc = run_gpu_unit(sh, P0, xs, dys, recompute=mode, in_place=in_place)
+            for a, b in zip(plain["ys"] + plain["dxs"], rc["ys"] + rc["dxs"]):
+                assert np.array_equal(a, b), (mode, in_place)
+            assert np.array_equal(plain["G"].view(np.uint32), rc["G"].view(np.uint32)), (mode, in_place)
+            if not in_place:
+                assert np.array_equal(plain["S0"].view(np.uint32), rc["S0"].view(np.uint32))
+        # the two backward tasks apart, each rebuilding for itself: weight-gradient tasks after all
+        # input-gradient tasks, so the shared slot has been through every block of every micro-batch in between
+        sp = run_gpu_unit(sh, P0, xs, dys, recompute=mode, in_place=True, split="descending")
+        for a, b in zip(plain["ys"] + plain["dxs"], sp["ys"] + sp["dxs"]):
+            assert np.array_equal(a, b), (mode, "split")
+        for n, off, r, c in layout:
+            assert rel_err(sp["G"][off:off + r * c], plain["G"][off:off + r * c]) <= 1e-5, (mode, n)
     ref = run_oracle_unit(sh, P0, xs, dys, "f64")
     rc["S0"] = plain["S0"]
     compare_units(sh, rc, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
+    sp["S0"] = None
+    compare_units(sh, sp, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
 
 
 @pytest.mark.parametrize("arch,dtype,V,per,prefetch,grp", [
@@ -398,12 +409,7 @@ def test_device_of_V_stages_equals_one_stage_of_all_blocks(arch, dtype, V, per, 
             # input-gradient tasks, then weight-gradient tasks in groups of grp (one by one in fp32)
             dxs = [st.backward_input(m, to_dev(dys[m], st.act_dtype)) for m in range(U)]
             for first in range(0, U, grp):
-                count = min(grp, U - first)
-                if count > 1 and dtype == 1:
-                    st.backward_weight_group(first, count, 0.5)
-                else:
-                    for m in range(first, first + count):
-                        st.backward_weight(m, in_place=True, scale=0.5)
+                st.backward_weight_group(first, min(grp, U - first), 0.5)
         g = st.G.clone()
         st.adam_step(step=unit + 1, zero_grad=1, **synth.ADAM)
         st.end_unit()
@@ -488,6 +494,87 @@ def test_grouped_weight_gradient_tasks(arch, kw, g):
         assert e.value.status == status, (first, count)
     st.backward_weight_group(0, 1)
     st.close()
+
+
+@pytest.mark.parametrize("arch,dtype,kw,g", [
+    (0, 1, dict(unit_mbs=4), 2), (1, 1, dict(unit_mbs=5, n_blocks=3), 3), (0, 0, dict(unit_mbs=4), 4),
+    (1, 0, dict(micro_batch=2, seq=96, unit_mbs=3), 2), (0, 1, dict(micro_batch=2, seq=128, ffn=768, n_heads=4, unit_mbs=4), 4),
+])
+def test_grouped_calls_equal_the_one_by_one_calls(arch, dtype, kw, g):
+    """g micro-batches per call as one [g*T, h] matrix (forward, input-gradient and fused backward tasks):
+    row by row the same arithmetic, so y and dx equal the one-micro-batch calls bit for bit; the gradients
+    of a group are summed inside the products, so G agrees up to summation order; and everything is held
+    to the oracle bound directly."""
+    sh = small(arch, dtype, **kw)
+    print(f"grouped calls {sh.name} {kw} g={g}", flush=True)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, sh.unit_mbs)
+    one = run_gpu_unit(sh, P0, xs, dys, in_place=True)
+    ref = run_oracle_unit(sh, P0, xs, dys, "f64")
+    tol = TOL_BF16 if dtype == 1 else TOL_FP32
+    runs = dict(split=run_gpu_unit_grouped(sh, P0, xs, dys, g, fused=False),
+                fused=run_gpu_unit_grouped(sh, P0, xs, dys, g, fused=True),
+                split_wide=run_gpu_unit_grouped(sh, P0, xs, dys, max(g // 2, 1), fused=False, weight_group=g),
+                fused_full_recompute=run_gpu_unit_grouped(sh, P0, xs, dys, g, fused=True, recompute=1),
+                split_selective=run_gpu_unit_grouped(sh, P0, xs, dys, g, fused=False, recompute=2))
+    for tag, grp in runs.items():
+        for a, b in zip(one["ys"] + one["dxs"], grp["ys"] + grp["dxs"]):
+            assert np.array_equal(a, b), tag
+        for n, off, r, c in layout:
+            assert rel_err(grp["G"][off:off + r * c], one["G"][off:off + r * c]) <= 2e-5, (tag, n)
+        compare_units(sh, grp, ref, layout, tol)
+    # a weight-gradient task must cover grouped input-gradient tasks whole
+    st = zpp.Stage(sh, split_backward=g, group_mbs=g)
+    st.materialize_params()
+    x = to_dev(np.concatenate(xs[:2], axis=0), st.act_dtype)
+    dy = to_dev(np.concatenate(dys[:2], axis=0), st.act_dtype)
+    st.forward_group(0, 2, x)
+    st.backward_input_group(0, 2, dy)
+    with pytest.raises(zpp.ZppError) as e:
+        st.backward_weight(0, in_place=True)
+    assert e.value.status == -2
+    st.backward_weight_group(0, 2)
+    st.close()
+
+
+def test_device_recomputes_every_stage_but_the_last():
+    """Section 3.3: the stages mapped to a device recompute (one rebuild serves their two back-to-back gradient
+    tasks) except the last one, whose tasks are scheduled apart and which keeps its activations.  Same kernels
+    on the same operands as a device that keeps everything: identical y and dx, G up to summation order, and
+    the oracle bound directly."""
+    sh = small(0, 1, n_blocks=1, unit_mbs=4)
+    U, V = sh.unit_mbs, 3
+    sh_all = sh.replace(n_blocks=V)
+    layout = oracle.param_layout(sh_all)
+    P0 = synth.make_params(sh_all, layout, gain_jitter=0.1)
+    xs, dys = make_inputs(sh, U)
+    ora = run_oracle_unit(sh_all, P0, xs, dys, "f64")
+    results = []
+    for modes in ([0, 0, 0], [1, 1, 0], [2, 1, 0]):
+        dev = zpp.Device(sh, V, prefetch=True, recompute=modes, split_backward=2)
+        dev.P.copy_(torch.from_numpy(P0))
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        x_in = [to_dev(xs[m], dev.act_dtype) for m in range(U)]
+        dy_in = [to_dev(dys[m], dev.act_dtype) for m in range(U)]
+        mid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        gmid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        dev.forward_unit([(x_in[m] if v == 0 else mid[v - 1][m]) for v in range(V) for m in range(U)],
+                         [mid[v][m] for v in range(V) for m in range(U)], main, side)
+        dev.backward_unit([(dy_in[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)],
+                          [gmid[v][m] for v in range(V) for m in range(U)], 1.0, main, side)
+        torch.cuda.synchronize()
+        results.append(dict(ys=[to_np(t) for t in mid[V - 1]], dxs=[to_np(t) for t in gmid[0]], G=to_np(dev.G),
+                            stash=dev.memory_terms()["stash"]))
+        dev.close()
+    for r in results:
+        compare_units(sh_all, r, ora, layout, TOL_BF16)
+    for r in results[1:]:
+        for a, b in zip(results[0]["ys"] + results[0]["dxs"], r["ys"] + r["dxs"]):
+            assert np.array_equal(a, b)
+        for n, off, rr, c in layout:
+            assert rel_err(r["G"][off:off + rr * c], results[0]["G"][off:off + rr * c]) <= 2e-5, n
+    assert results[1]["stash"] < 0.6 * results[0]["stash"]
 
 
 def test_device_with_recomputation_matches_device_without():
@@ -590,6 +677,31 @@ def test_backward_accumulate_state_machine():
     st.close()
 
 
+@pytest.mark.parametrize("arch,kw", [(0, {}), (1, dict(ffn=320)), (0, dict(hidden=512, n_heads=4, ffn=1024))])
+def test_transposed_working_copy_is_the_transposed_cast(arch, kw):
+    """The gather also writes every matrix transposed (the input-gradient products read it): bit for bit the
+    transposed round-to-nearest-even cast of P, the gate and up matrices of the LLaMA block as one [h, 2f]."""
+    sh = small(arch, 1, **kw)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.1)
+    st = zpp.Stage(sh)
+    st.P.copy_(torch.from_numpy(P0))
+    st.materialize_params()
+    torch.cuda.synchronize()
+    wt = st.region("Wt").view(torch.int16).cpu().numpy().view(np.uint16)
+    pos = 0
+    for name, off, r, c in layout:
+        if r <= 1 or name.endswith("mlp.wup"):
+            continue
+        if name.endswith("mlp.wgate"):
+            r *= 2
+        expect = oracle.flat_materialize_bits(P0[off:off + r * c]).reshape(r, c).T
+        assert np.array_equal(wt[pos:pos + r * c].reshape(c, r), expect), name
+        pos += r * c
+    assert pos == wt.size
+    st.close()
+
+
 def test_materialize_counters_and_idempotence():
     sh = small(0, 1)
     layout = oracle.param_layout(sh)
@@ -612,18 +724,14 @@ def test_materialize_counters_and_idempotence():
 
 
 # ------------------------------------------------------------------ operators
-@pytest.mark.parametrize("M,N,K,variant", [
-    (256, 256, 64, 0), (300, 520, 192, 0), (300, 520, 192, 1), (300, 520, 192, 2), (300, 520, 192, 3),
-    (300, 520, 192, 4), (300, 520, 192, 5), (300, 520, 192, 6), (300, 520, 192, 7), (300, 520, 192, 8),
-    (64, 96, 128, -1), (1, 1, 64, 2), (1, 1, 64, 6), (777, 129, 256, -1), (2048, 512, 1024, -1), (512, 2048, 64, 5),
-    (1000, 1000, 320, 5), (1000, 1000, 320, 6),
-    (300, 520, 192, 9), (300, 520, 192, 10), (300, 520, 192, 11), (1000, 1000, 320, 9), (1000, 1000, 320, 11),
-    (512, 512, 64, 9), (256, 256, 1024, 9), (256, 256, 1024, 10), (1, 1, 64, 11),
-    (300, 520, 192, 12), (300, 520, 192, 13), (300, 520, 192, 14), (300, 520, 192, 15), (1000, 1000, 320, 12),
-    (128, 128, 64, 12), (128, 128, 1024, 13), (512, 256, 768, 14), (1, 1, 64, 15),
+@pytest.mark.parametrize("M,N,K,tile", [
+    (256, 256, 64, "256x256"), (300, 520, 192, "256x256"), (300, 520, 192, "128x128"), (300, 520, 192, "256x128"),
+    (300, 520, 192, "128x256"), (64, 96, 128, "auto"), (1, 1, 64, "128x128"), (1, 1, 64, "128x256"),
+    (777, 129, 256, "auto"), (2048, 512, 1024, "auto"), (512, 2048, 64, "256x256"), (1000, 1000, 320, "256x256"),
+    (1000, 1000, 320, "128x128"), (1000, 1000, 320, "256x128"), (512, 256, 768, "256x128"), (256, 512, 1024, "128x256"),
 ])
-def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
-    print(f"gemm {M}x{N}x{K} variant {variant}", flush=True)
+def test_gemm_bf16_nt_against_oracle(M, N, K, tile):
+    print(f"gemm {M}x{N}x{K} tile {tile}", flush=True)
     a = synth.normal_f32(1, 50, M * K, bf16_exact=True).reshape(M, K)
     b = synth.normal_f32(1, 51, N * K, std=0.05, bf16_exact=True).reshape(N, K)
     bias = synth.normal_f32(1, 52, N, bf16_exact=True)
@@ -631,34 +739,17 @@ def test_gemm_bf16_nt_against_oracle(M, N, K, variant):
     ref = oracle.Ops("f64").linear_fwd(a, b, bias) + res
     A, B, Bi, R = (to_dev(t, torch.bfloat16) for t in (a, b, bias, res))
     C = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
-    zpp.op_gemm_bf16_nt(A, B, C, bias=Bi, resid=R, variant=variant)
+    zpp.op_gemm_bf16_nt(A, B, C, bias=Bi, resid=R, tile=tile)
     assert rel_err(to_np(C), ref) <= 8e-3  # bf16 output rounding only (2^-9 relative)
     Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
-    zpp.op_gemm_bf16_nt(A, B, Cf, variant=variant)
+    zpp.op_gemm_bf16_nt(A, B, Cf, tile=tile)
     ref2 = oracle.Ops("f64").linear_fwd(a, b)
     assert rel_err(to_np(Cf), ref2) <= 1e-5      # fp32 accumulation of exact bf16 products
     # accumulation in place: every element receives exactly one rounded add of the same fp32 product
     g0 = torch.from_numpy(synth.normal_f32(1, 54, M * N).reshape(M, N)).cuda()
     G = g0.clone()
-    zpp.op_gemm_bf16_nt(A, B, G, variant=variant, accumulate=True)
+    zpp.op_gemm_bf16_nt(A, B, G, tile=tile, accumulate=True)
     assert torch.equal(G, g0 + Cf)
-
-
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (128, 128, 128), (520, 304, 192), (8, 8, 64), (1024, 2048, 512),
-                                   (2304, 768, 256)])
-def test_gemm_bf16_tt_against_oracle(M, N, K):
-    """dW = dY^T . X straight from the token-major operands."""
-    print(f"gemm tt {M}x{N}x{K}", flush=True)
-    dy = synth.normal_f32(4, 80, K * M, bf16_exact=True).reshape(K, M)
-    x = synth.normal_f32(4, 81, K * N, bf16_exact=True).reshape(K, N)
-    ref, _ = oracle.Ops("f64").linear_bwd_weight(dy, x)
-    A, B = to_dev(dy, torch.bfloat16), to_dev(x, torch.bfloat16)
-    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
-    zpp.op_gemm_bf16_tt(A, B, C)
-    assert rel_err(to_np(C), ref) <= 1e-5
-    Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
-    zpp.op_gemm_bf16_tt(A, B, Cb)
-    assert rel_err(to_np(Cb), ref) <= 8e-3
 
 
 @pytest.mark.parametrize("dtype,b,s,nh,d", [(torch.float32, 2, 70, 3, 32), (torch.bfloat16, 1, 130, 2, 128),

@@ -158,11 +158,60 @@ def test_recompute_shrinks_the_stash_to_block_inputs():
     expect = (slots - 1) * (per_slot_plain - 2 * T * h) - 2 * T * h
     assert abs(saved - expect) <= 0.02 * expect
     assert rc.N == plain.N
+    # selective recomputation drops the outputs of the norms and of the activation function: 2h + f of the
+    # 8h + 2f stored elements per token and block
+    sel = zpp.Stage(sh, allocate=False, recompute=2)
+    saved = plain.workspace_bytes - sel.workspace_bytes
+    expect = (slots - 1) * 2 * T * (2 * h + f)
+    assert abs(saved - expect) <= 0.02 * expect
+    # with split backward tasks the stash also holds what the two tasks hand to each other, in every mode
+    for mode in (1, 2):
+        both = zpp.Stage(sh, allocate=False, recompute=mode, split_backward=1)
+        alone = rc if mode == 1 else sel
+        extra = both.workspace_bytes - alone.workspace_bytes
+        dy_bytes = 2 * T * (5 * h + f) * slots
+        assert dy_bytes <= extra <= dy_bytes * 1.05
+        both.close()
     with pytest.raises(zpp.ZppError) as e:
-        zpp.Stage(sh, allocate=False, recompute=True, split_backward=True)
-    assert e.value.status == -6
+        zpp.Stage(sh, allocate=False, recompute=3)
+    assert e.value.status == -1
     plain.close()
     rc.close()
+    sel.close()
+
+
+def test_grouped_calls_check_their_arguments_without_launch():
+    sh = synth.CONFIGS["cfg3_gpt_6p2b"]
+    one = zpp.Stage(sh, allocate=False)
+    grp = zpp.Stage(sh, allocate=False, group_mbs=4)
+    # temporaries for four micro-batches at once; the stash does not change
+    T, h, f = sh.tokens, sh.hidden, sh.ffn
+    assert grp.workspace_bytes > one.workspace_bytes + 3 * 2 * T * (8 * h + f)
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.Stage(sh, allocate=False, group_mbs=sh.unit_mbs + 1)
+    assert e.value.status == -1
+    L = zpp.lib()
+    fake = 0x10000
+    grp.bind_raw(fake, fake, fake, fake, fake, grp.workspace_bytes)
+    one.bind_raw(fake, fake, fake, fake, fake, one.workspace_bytes)
+    for call, status in (
+        (lambda: L.stage_forward_group(grp._h, 0, 0, fake, fake, None), -1),
+        (lambda: L.stage_forward_group(grp._h, -1, 2, fake, fake, None), -1),
+        (lambda: L.stage_forward_group(grp._h, sh.unit_mbs - 1, 2, fake, fake, None), -1),
+        (lambda: L.stage_forward_group(grp._h, 0, 5, fake, fake, None), -2),     # more than group_mbs
+        (lambda: L.stage_forward_group(one._h, 0, 2, fake, fake, None), -2),     # created for one at a time
+        (lambda: L.stage_forward_group(grp._h, 0, 4, None, fake, None), -1),
+        (lambda: L.stage_forward_group(grp._h, 0, 4, fake, fake + 16, None), -3),
+        (lambda: L.stage_forward_group(grp._h, 0, 4, fake, fake, None), -2),     # before materialise
+        (lambda: L.stage_backward_input_group(grp._h, 0, 2, fake, fake, None), -2),   # no split_backward
+        (lambda: L.stage_backward_accumulate_group(grp._h, 0, 2, fake, fake, 1.0, None), -2),  # before materialise
+        (lambda: L.stage_backward_accumulate_group(grp._h, 0, 2, fake, None, 1.0, None), -1),
+    ):
+        with pytest.raises(zpp.ZppError) as e:
+            binding._check(call())
+        assert e.value.status == status, zpp.lib().zpp_last_error()
+    one.close()
+    grp.close()
 
 
 def test_device_memory_terms_follow_the_weight_memory_formula():
