@@ -2,12 +2,13 @@
 """Benchmark of the ZeroPP stage hot path on one MI355X.
 
 A step is one pass of the whole hot path over one scheduling unit of synthetic input:
-stage_materialize_params, U x stage_forward, U x stage_backward_input, then the weight-gradient tasks
-of the unit as one grouped task that adds into G (stage_backward_weight_group), shard_adam_step (with
-zero_grad), zpp_stage_end_unit.  Other orders of the same work: --group g (g micro-batches per
-weight-gradient task; 1 = one by one), --backward fused (U x stage_backward_accumulate), --accumulate
-separate (stage_backward + stage_accumulate_grads); the last three give identical bits, grouping
-changes the summation order inside G.  Inputs are resident in HBM before the timed
+stage_materialize_params, the U forward tasks and then the U input-gradient tasks two micro-batches per call
+(stage_forward_group, stage_backward_input_group), the weight-gradient tasks of the unit as one grouped task
+that adds into G (stage_backward_weight_group), shard_adam_step (with zero_grad), zpp_stage_end_unit.  Other
+orders of the same work: --mb-group g (micro-batches per forward / input-gradient call; 1 = the
+one-micro-batch calls), --group g (g micro-batches per weight-gradient task; 1 = one by one), --backward fused
+(stage_backward_accumulate), --accumulate separate (stage_backward + stage_accumulate_grads); y and dx are the
+same bits in all of them, grouping changes the summation order inside G.  Inputs are resident in HBM before the timed
 region.  Prints ONE JSON line.
 
 After the timed region the same process adds, outside `value`: one event-instrumented step (roofline, phases),
@@ -31,7 +32,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
-DEFAULT_MB_GROUP = 1        # micro-batches per forward / input-gradient call in the default order of the work
+DEFAULT_MB_GROUP = 2        # micro-batches per forward / input-gradient call in the default order of the work
 
 
 def model_flops_per_unit(sh) -> float:
@@ -90,24 +91,32 @@ def hbm_large_shard(zpp, torch, synth, stream):
 
 
 def time_default_step(zpp, torch, synth, sh, steps, warmup, stream):
-    """The default order of the work (materialise, U forwards, U input-gradient tasks, the unit's weight-gradient
-    tasks as one grouped task, Adam with zero_grad and write-back) on another workload; whole-step figures only."""
-    st = zpp.Stage(sh, device="cuda:0", split_backward=sh.unit_mbs)
+    """The default order of the work (materialise, forward and input-gradient tasks in groups of DEFAULT_MB_GROUP
+    micro-batches, the unit's weight-gradient tasks as one grouped task, Adam with zero_grad and write-back) on
+    another workload; whole-step figures only."""
+    U, T, g = sh.unit_mbs, sh.tokens, DEFAULT_MB_GROUP
+    st = zpp.Stage(sh, device="cuda:0", split_backward=U, group_mbs=g)
     P0 = synth.make_params(sh, st.layout())
     st.P.copy_(torch.from_numpy(P0))
     del P0
     act = st.act_dtype
-    xs = [torch.from_numpy(synth.make_x(sh, m)).to("cuda:0", act) for m in range(sh.unit_mbs)]
-    dys = [torch.from_numpy(synth.make_dy(sh, m)).to("cuda:0", act) for m in range(sh.unit_mbs)]
-    y, dx = torch.empty_like(xs[0]), torch.empty_like(xs[0])
+    X = torch.empty(U * T, sh.hidden, device="cuda:0", dtype=act)
+    DY = torch.empty_like(X)
+    for m in range(U):
+        X[m * T:(m + 1) * T].copy_(torch.from_numpy(synth.make_x(sh, m)))
+        DY[m * T:(m + 1) * T].copy_(torch.from_numpy(synth.make_dy(sh, m)))
+    Y = torch.empty(g * T, sh.hidden, device="cuda:0", dtype=act)
+    DX = torch.empty_like(Y)
 
     def step(t):
         st.materialize_params(stream)
-        for m in range(sh.unit_mbs):
-            st.forward(m, xs[m], y, stream)
-        for m in range(sh.unit_mbs):
-            st.backward_input(m, dys[m], dx, stream)
-        st.backward_weight_group(0, sh.unit_mbs, 1.0, stream)
+        for f in range(0, U, g):
+            c = min(g, U - f)
+            st.forward_group(f, c, X[f * T:(f + c) * T], Y[:c * T], stream)
+        for f in range(0, U, g):
+            c = min(g, U - f)
+            st.backward_input_group(f, c, DY[f * T:(f + c) * T], DX[:c * T], stream)
+        st.backward_weight_group(0, U, 1.0, stream)
         st.adam_step(step=t, zero_grad=1, write_back=1, stream=stream, **synth.ADAM)
         st.end_unit()
 
@@ -268,6 +277,8 @@ def main():
     args.recompute = {"none": 0, "full": 1, "selective": 2}[args.recompute]
     if args.recompute:
         args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
+    if sh.compute_dtype != 1:
+        args.mb_group = 1             # the tiny fp32 configuration: one micro-batch at a time
     if args.backward != "split" or sh.compute_dtype != 1:
         args.group = 1
     elif args.group == 0:

@@ -21,8 +21,7 @@ extern "C" {
  * out_f32 == 2: C is float and receives C + result (the in-place gradient accumulation of
  * stage_backward_accumulate, scale 1), so C must hold valid data on entry.
  * tile: -1 chosen from the shape; 0 256x256 and 1 128x128 work-group tiles (two LDS stages), 2 256x128 and
- * 3 128x256 (a ring of three LDS stages), 4 256x256 with four waves of 128x128: the kernels the stage calls
- * select among. */
+ * 3 128x256 (a ring of three LDS stages): the kernels the stage calls select among. */
 zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
                                int32_t out_f32, int32_t tile, void *hip_stream);

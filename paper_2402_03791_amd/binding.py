@@ -519,7 +519,7 @@ def profile_read():
 
 
 # ---- operator-level entry points (include/zpp_ops.h) ----------------------------------------------
-GEMM_TILES = {"auto": -1, "256x256": 0, "128x128": 1, "256x128": 2, "128x256": 3, "256x256w4": 4}
+GEMM_TILES = {"auto": -1, "256x256": 0, "128x128": 1, "256x128": 2, "128x256": 3}
 
 
 def op_gemm_bf16_nt(A, B, C, bias=None, resid=None, tile="auto", stream=None, accumulate: bool = False):

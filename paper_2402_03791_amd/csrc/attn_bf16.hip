@@ -132,6 +132,17 @@ constexpr int kStages = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// The tile copies are issued from inline assembly, so the compiler's own bookkeeping of outstanding global loads
+// does not know about them.  If ordinary loads (the operands a wave keeps in registers) are still pending, by
+// that bookkeeping, when the main loop is entered, the compiler puts its waits for them at their first use
+// inside the loop, where on every later iteration they wait for the tile copies in flight instead and undo
+// the overlap of copying and computing.  Naming a register as the input of an (empty) assembly statement makes
+// the compiler wait for its load here, before the loop.
+__device__ __forceinline__ void loaded_before_here(const bf16x8 &v)
+{
+    asm volatile("" : : "v"(__builtin_bit_cast(u32x4, v)));
+}
+
 __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
@@ -194,6 +205,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
         }
     };
     issue_pair(0);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) loaded_before_here(qf[st]);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -204,15 +217,28 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
             const int kv0 = jt * kTile;
             const unsigned char *ks = smem + ((p & 1) * 2 + half) * 2 * kTileBytes;
             const unsigned char *vs = ks + kTileBytes;
-            f32x16 sacc[2];
-            const f32x16 zero16 = {};
+            f32x16 sacc[2] = {};
+            // The 16 K operands come from LDS through a ring of four registers, each requested four MFMAs ahead
+            // of its use and the order pinned (left to itself the compiler reads every operand into the same
+            // register right before its MFMA and the matrix pipe waits out a whole LDS round trip each time).
+            bf16x8 kr[4];
 #pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, 0), qf[0], zero16, 0, 0, 0);
+            for (int i = 0; i < 4; ++i) kr[i] = rd_row(ks, ad, 0, i);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int st = 1; st < 8; ++st)
-                    sacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc[T], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) {
+                sacc[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[i & 3], qf[i & 7], sacc[i >> 3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 4 < 16) {
+                    kr[i & 3] = rd_row(ks, ad, (i + 4) >> 3, (i + 4) & 7);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+            // the first V operands travel while the softmax is computed
+            bf16x8 vr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vr[i] = rd_tr(vs, ad, i & 3, i >> 2);
+            __builtin_amdgcn_sched_barrier(0);
             // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c; mask on the diagonal only
             if (kv0 + kTile - 1 > qw0) {
 #pragma unroll
@@ -251,11 +277,16 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
                 m_run = m_new;
             }
             l_run += psum;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(vs, ad, t, st), pf[st], oacc[t], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) {  // i = 4 * st + t
+                oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[i & 3], pf[i >> 2], oacc[i & 3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 4 < 16) {
+                    vr[i & 3] = rd_tr(vs, ad, (i + 4) & 3, (i + 4) >> 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -380,6 +411,11 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
         }
     };
     issue_pair(0);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+        loaded_before_here(qf[st]);
+        loaded_before_here(dof[st]);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -526,6 +562,11 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
     issue_pair(0);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+        loaded_before_here(kf[st]);
+        if constexpr (DK) loaded_before_here(vf[st]);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 

@@ -102,29 +102,29 @@ __global__ __launch_bounds__(256) void transpose_cast_ragged_kernel(const float 
     }
 }
 
-// The same for rows and cols in multiples of 64, at streaming speed: a work-group takes a 64x64 tile with
-// 16-byte loads (each thread two pairs of vertically adjacent 4-float pieces, all four loads in flight before
-// the first use), rounds to bf16, packs the two rows of a pair into one 32-bit word per column (the output is
-// contiguous along rows) and writes the words transposed into LDS - row stride 33 words, so the 64 lanes of a
-// wave hit 64 different banks - then reads eight consecutive rows of a column back and stores them with one
-// 16-byte non-temporal store per lane (a full 128-byte line per 8 lanes).
-__global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__restrict__ P, bf16 *__restrict__ Wt,
-                                                             uint64_t rows, uint64_t cols)
+// The same for rows in multiples of 128 and cols in multiples of 64, at streaming speed: a work-group takes a
+// tile of 128 rows x 64 columns with 16-byte loads (each thread four pairs of vertically adjacent 4-float
+// pieces, all eight loads in flight before the first use), rounds to bf16, packs the two rows of a pair into
+// one 32-bit word per column (the output is contiguous along rows) and writes the words transposed into LDS -
+// row stride 65 words, so the 64 lanes of a wave hit 64 different banks both ways - then reads eight
+// consecutive rows of a column back and stores them with one 16-byte non-temporal store per lane.  Both the
+// reads and the writes touch memory in 256-byte runs.
+__device__ __forceinline__ void transpose_cast_tile(const float *__restrict__ P, bf16 *__restrict__ Wt, uint64_t rows,
+                                                    uint64_t cols, uint64_t r0, uint64_t c0)
 {
-    constexpr int S = 33;                  // words per LDS row (32 row pairs + 1)
+    constexpr int S = 65;                  // words per LDS row (64 row pairs + 1)
     __shared__ uint32_t tile[64 * S];      // [column][row pair]
-    const uint64_t r0 = (uint64_t)blockIdx.y * 64, c0 = (uint64_t)blockIdx.x * 64;
     const int t = threadIdx.x;
-    const int col4 = t & 15, pair0 = t >> 4;   // row pairs pair0 and pair0 + 16
-    f32x4 top[2], bot[2];
+    const int col4 = t & 15, pair0 = t >> 4;   // row pairs pair0 + 16 u
+    f32x4 top[4], bot[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
         const float *src = P + (r0 + 2 * (pair0 + 16 * u)) * cols + c0 + 4 * col4;
         top[u] = nt_load(reinterpret_cast<const f32x4 *>(src));
         bot[u] = nt_load(reinterpret_cast<const f32x4 *>(src + cols));
     }
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             bf16x2 w;
@@ -134,8 +134,8 @@ __global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__rest
         }
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int c = (t >> 3) + 32 * u, q = t & 7;   // rows 8q .. 8q+7 of output row c
+    for (int u = 0; u < 4; ++u) {
+        const int c = (t >> 4) + 16 * u, q = t & 15;   // rows 8q .. 8q+7 of output row c
         u32x4 o;
 #pragma unroll
         for (int k = 0; k < 4; ++k) o[k] = tile[c * S + 4 * q + k];
@@ -143,14 +143,64 @@ __global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__rest
     }
 }
 
+__global__ __launch_bounds__(256) void transpose_cast_kernel(const float *__restrict__ P, bf16 *__restrict__ Wt,
+                                                             uint64_t rows, uint64_t cols)
+{
+    transpose_cast_tile(P, Wt, rows, cols, (uint64_t)blockIdx.y * 128, (uint64_t)blockIdx.x * 64);
+}
+
+// All matrices of a stage in one launch (one kernel tail instead of one per matrix): a work-group finds its
+// matrix in the table by a scalar search, then its tile inside the matrix, column tiles fastest.
+__global__ __launch_bounds__(256) void transpose_cast_many_kernel(const float *__restrict__ P, bf16 *__restrict__ Wt,
+                                                                  TransposeCastTable tab)
+{
+    int i = 0;
+    while (i + 1 < tab.n && blockIdx.x >= tab.first_block[i + 1]) ++i;
+    const uint32_t local = blockIdx.x - tab.first_block[i];
+    const uint32_t tiles_c = (uint32_t)(tab.cols[i] / 64), tiles_r = (uint32_t)(tab.rows[i] / 128);
+    uint32_t tr, tc;
+    if (tiles_c % 8 == 0 && tiles_r % 8 == 0) {
+        // Work-groups that run at the same time form 8 x 8 squares of tiles: their reads are 2 KB runs of P's rows
+        // and their writes 2 KB runs of Wt's rows, so both sides find several accesses per open DRAM page (in
+        // row-major tile order the writes of concurrent work-groups are isolated 256-byte pieces).
+        const uint32_t sq = local >> 6, in = local & 63;
+        tr = (sq / (tiles_c / 8)) * 8 + (in >> 3);
+        tc = (sq % (tiles_c / 8)) * 8 + (in & 7);
+    } else {
+        tr = local / tiles_c;
+        tc = local % tiles_c;
+    }
+    transpose_cast_tile(P + tab.src[i], Wt + tab.dst[i], tab.rows[i], tab.cols[i], (uint64_t)tr * 128, (uint64_t)tc * 64);
+}
+
+hipError_t launch_transpose_cast_many(const float *P, void *Wt, TransposeCastTable tab, hipStream_t s)
+{
+    if (tab.n <= 0) return hipSuccess;
+    if (tab.n > kTransposeCastMax || (reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(Wt)) % 16)
+        return hipErrorInvalidValue;
+    uint64_t blocks = 0;
+    for (int i = 0; i < tab.n; ++i) {
+        if (tab.rows[i] % 128 || tab.cols[i] % 64 || tab.src[i] % 4 || tab.dst[i] % 8) return hipErrorInvalidValue;
+        tab.first_block[i] = (uint32_t)blocks;
+        blocks += (tab.rows[i] / 128) * (tab.cols[i] / 64);
+    }
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+    tab.first_block[tab.n] = (uint32_t)blocks;
+    if (blocks == 0) return hipSuccess;
+    transpose_cast_many_kernel<<<(unsigned)blocks, 256, 0, s>>>(P, (bf16 *)Wt, tab);
+    return hipGetLastError();
+}
+
 hipError_t launch_transpose_cast(const float *P, void *Wt, uint64_t rows, uint64_t cols, hipStream_t s)
 {
     if (rows == 0 || cols == 0) return hipSuccess;
-    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
-    if (rows % 64 == 0 && cols % 64 == 0 && (reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(Wt)) % 16 == 0)
+    if (rows % 128 == 0 && cols % 64 == 0 && (reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(Wt)) % 16 == 0) {
+        dim3 grid((unsigned)(cols / 64), (unsigned)(rows / 128));
         transpose_cast_kernel<<<grid, 256, 0, s>>>(P, (bf16 *)Wt, rows, cols);
-    else
+    } else {
+        dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
         transpose_cast_ragged_kernel<<<grid, 256, 0, s>>>(P, (bf16 *)Wt, rows, cols);
+    }
     return hipGetLastError();
 }
 

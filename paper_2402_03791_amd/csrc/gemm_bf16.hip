@@ -732,7 +732,6 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     case GEMM_TILE_128x128: return launch_two_stage<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case GEMM_TILE_256x128: return launch_ring<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case GEMM_TILE_128x256: return launch_ring<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case GEMM_TILE_256x256_W4: return launch_two_stage<256, 256, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -50,6 +50,15 @@ struct GemmEpi {
 hipError_t launch_materialize(const float *P, void *W, uint64_t n, int dt, hipStream_t s);
 // Wt[c, r] = bf16(P[r, c]) for a [rows, cols] matrix
 hipError_t launch_transpose_cast(const float *P, void *Wt, uint64_t rows, uint64_t cols, hipStream_t s);
+// The same for up to kTransposeCastMax matrices in one launch: matrix i is P[src[i] ...] of [rows[i], cols[i]]
+// (rows a multiple of 128, cols of 64) and goes to Wt[dst[i] ...] (element offsets).
+constexpr int kTransposeCastMax = 24;
+struct TransposeCastTable {
+    uint64_t src[kTransposeCastMax], dst[kTransposeCastMax], rows[kTransposeCastMax], cols[kTransposeCastMax];
+    uint32_t first_block[kTransposeCastMax + 1];
+    int32_t n;
+};
+hipError_t launch_transpose_cast_many(const float *P, void *Wt, TransposeCastTable tab, hipStream_t s);
 hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s);
 hipError_t launch_adam(float *P, float *M, float *V, float *G, uint64_t n, const AdamArgs &a, hipStream_t s);
 
@@ -127,10 +136,9 @@ hipError_t launch_gemm_f32(int64_t M, int64_t N, int64_t K, const float *A, int6
                            const GemmEpi &epi, hipStream_t s);
 // bf16 MFMA GEMM, both operands K-contiguous: C[M,N] = A[M,K] . B[N,K]^T with fp32 accumulation.
 // Requires K % 64 == 0, lda/ldb % 8 == 0, 16-byte aligned bases.  tile: the work-group tile, chosen from
-// the shape when GEMM_TILE_AUTO (256x256 and 128x128: two LDS stages; 256x128 and 128x256: a ring of three;
-// 256x256 with four waves of 128x128 each: a third less LDS traffic per flop, a slower epilogue).
+// the shape when GEMM_TILE_AUTO (256x256 and 128x128: two LDS stages; 256x128 and 128x256: a ring of three).
 enum { GEMM_TILE_AUTO = -1, GEMM_TILE_256x256 = 0, GEMM_TILE_128x128 = 1, GEMM_TILE_256x128 = 2, GEMM_TILE_128x256 = 3,
-       GEMM_TILE_256x256_W4 = 4, GEMM_TILE_LAST = 4 };
+       GEMM_TILE_LAST = 3 };
 hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s,
                                int tile = GEMM_TILE_AUTO);

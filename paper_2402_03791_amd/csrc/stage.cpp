@@ -710,10 +710,27 @@ zpp_status stage_materialize_params(zpp_stage *s, void *hip_stream)
     ProfScope prof(ZPP_PROF_MATERIALIZE, (double)bytes, st);
     if (plain) ZPP_TRY(launch_materialize(s->P, s->ws + s->rW.off, s->N, s->dt, st));
     if (s->dt == DT_BF16) {
+        // the transposed copies: matrices of streaming-friendly shape batched into as few launches as the
+        // table allows, the others one by one
+        TransposeCastTable tab{};
+        auto flush = [&]() -> hipError_t {
+            const hipError_t e = launch_transpose_cast_many(s->P, s->ws + s->rWt.off, tab, st);
+            tab.n = 0;
+            return e;
+        };
         for (auto &kv : s->wt) {
             const auto &w = kv.second;
-            ZPP_TRY(launch_transpose_cast(s->P + w.src_off, s->ws + s->rWt.off + w.dst_off * 2, w.rows, w.cols, st));
+            if (w.rows % 128 == 0 && w.cols % 64 == 0 && w.src_off % 4 == 0 && w.dst_off % 8 == 0) {
+                tab.src[tab.n] = w.src_off;
+                tab.dst[tab.n] = w.dst_off;
+                tab.rows[tab.n] = w.rows;
+                tab.cols[tab.n] = w.cols;
+                if (++tab.n == kTransposeCastMax) ZPP_TRY(flush());
+            } else {
+                ZPP_TRY(launch_transpose_cast(s->P + w.src_off, s->ws + s->rWt.off + w.dst_off * 2, w.rows, w.cols, st));
+            }
         }
+        ZPP_TRY(flush());
     }
     if (s->c.arch == ZPP_ARCH_LLAMA && !s->rope_ready) {
         ZPP_TRY(launch_rope_table((float *)(s->ws + s->rRope.off), s->c.seq, s->d, (double)s->c.rope_base, st));
