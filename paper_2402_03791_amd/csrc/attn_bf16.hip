@@ -1,20 +1,23 @@
 // Fused causal attention for bf16, head dim 128, on gfx950 MFMA (v_mfma_f32_32x32x16_bf16).
 //
-// Forward: a work-group is eight wavefronts on 128 consecutive queries, four groups of 32; the two
-// wavefronts that share a SIMD (w and w+4) own the same group and split its key tiles between them, each
-// with its own online softmax, merged at the end.  Under the causal mask a work-group's work grows with
-// its position in the sequence; the heavy ones are dispatched first, and because both wavefronts of a SIMD
-// always have a tile to work on the SIMD overlaps the matrix phase of one with the softmax phase of the
-// other.  Keys/values stream through LDS in tiles of 64 rows, two pairs of (K, V) tiles, one barrier per
-// pair.  Scores are computed transposed, S^T = K Q^T, so that a lane owns one query column and the softmax
-// row reductions are in-lane plus one exchange with the lane 32 away; the probabilities then feed the
-// second product O^T = V^T P^T straight from the accumulator registers.  The value tile is read with the
-// LDS transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one
-// value column.  The softmax never leaves registers; only O and the log-sum-exp are written.
+// A wave owns 32 queries (forward, dQ) or 32 keys (dK, dV); a work-group covers 128 consecutive ones.  Under
+// the causal mask a work-group's work grows with its position in the sequence; the heavy ones are dispatched
+// first.  Keys/values (or queries/dO) stream through LDS in tiles of 64 rows, copied global -> LDS directly.
+// Scores are computed transposed, S^T = K Q^T, so that a lane owns one query column and the softmax row
+// reductions are in-lane plus one exchange with the lane 32 away; the probabilities then feed the second
+// product O^T = V^T P^T straight from the accumulator registers.  The value tile is read with the LDS
+// transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one value
+// column.  The softmax never leaves registers; only O and the log-sum-exp are written.
 //
-// Backward: two launches without atomics, laid out the same way.  dQ: lane = query, loops over key tiles.
-// dK and dV: lane = key, loop over query tiles.  P is recomputed from the saved log-sum-exp;
-// delta = rowsum(dO o O) is computed by the dQ kernel and handed to the dK kernel.
+// Two work-group shapes.  Four waves, each taking every tile of its 32 rows, two stages of one tile pair in
+// LDS (64 KB), two work-groups per CU: the default (all backward launches, forward launches of more than two
+// work-groups per CU).  Eight waves, the two waves of a SIMD (w and w+4) sharing a group of 32 queries and
+// splitting its key tiles even / odd, merged at the end, one work-group per CU: forward launches of at most
+// two work-groups per CU, where the shorter chain of intervals per work-group wins.
+//
+// Backward: two launches without atomics.  dQ: lane = query, loops over key tiles.  dK and dV: lane = key,
+// loop over query tiles.  P is recomputed from the saved log-sum-exp; delta = rowsum(dO o O) is computed by
+// the dQ kernel and handed to the dK kernel.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -332,30 +335,171 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
             (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
 }
 
-// ------------------------------------------------------------------------------------ backward: dQ
-// Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
-// in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
-// gathered from the same key tile through the transposing load.  Work laid out as in the forward kernel:
-// 128 consecutive queries per work-group, the two waves of a SIMD share a group of 32 queries and take
-// the even / odd key tiles, tiles streamed in pairs; the second wave's partial dQ goes through LDS to
-// the first, which adds it.
-__global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *__restrict__ qkv,
-                                                                   const bf16 *__restrict__ attn,
-                                                                   const bf16 *__restrict__ dattn,
-                                                                   const float *__restrict__ lse,
-                                                                   float *__restrict__ delta, bf16 *__restrict__ dqkv,
-                                                                   int seq, int nh, int nb, float scale,
-                                                                   float scale_log2e)
+// The same with four waves per work-group: every wave takes all key tiles of its 32 queries (no split, no merge),
+// tiles streamed one by one through two stages of 32 KB, so two work-groups fit a CU and run out of step with
+// each other.  Used when the grid has more than two work-groups per CU.
+__global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
+                                                             float *__restrict__ lse, int seq, int nh, int nb,
+                                                             float scale_log2e)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
     int qb, n, bi;
     decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = wave >> 2, grp = wave & 3;
     const int g = lane >> 5, c = lane & 31;
-    const int qw0 = 128 * qb + 32 * grp;
+    const int qw0 = 128 * qb + 32 * wave;
+    const int64_t row0 = (int64_t)bi * seq;
+
+    bf16x8 qf[8];
+    {
+        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
+    }
+    TileCopy<4> cp;
+    cp.init(lane, wave, ld);
+    TileAddr ad;
+    ad.init(lane);
+    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
+    const char *vbase = kbase + h * 2;
+    const int64_t tile_stride = (int64_t)kTile * ld * 2;
+    const uint32_t lds0 = lds_addr_of(smem);
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    const int n_tiles = 2 * (qb + 1);
+    const int my_tiles = qw0 / kTile + 1;
+    auto issue_tile = [&](int jt) {
+        const uint32_t dst = lds0 + (jt & 1) * 2 * kTileBytes;
+        cp.issue(kbase + jt * tile_stride, dst, wave);
+        cp.issue(vbase + jt * tile_stride, dst + kTileBytes, wave);
+    };
+    issue_tile(0);
+#pragma unroll
+    for (int st = 0; st < 8; ++st) loaded_before_here(qf[st]);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        if (jt + 1 < n_tiles) issue_tile(jt + 1);
+        if (jt < my_tiles) {
+            const int kv0 = jt * kTile;
+            const unsigned char *ks = smem + (jt & 1) * 2 * kTileBytes;
+            const unsigned char *vs = ks + kTileBytes;
+            f32x16 sacc[2] = {};
+            bf16x8 kr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) kr[i] = rd_row(ks, ad, 0, i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                sacc[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[i & 3], qf[i & 7], sacc[i >> 3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 4 < 16) {
+                    kr[i & 3] = rd_row(ks, ad, (i + 4) >> 3, (i + 4) & 7);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            bf16x8 vr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vr[i] = rd_tr(vs, ad, i & 3, i >> 2);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kv0 + kTile - 1 > qw0) {
+#pragma unroll
+                for (int T = 0; T < 2; ++T)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (kv > qw0 + c) sacc[T][e] = -INFINITY;
+                    }
+            }
+            float mloc = sacc[0][0];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            const float m_new = fmaxf(m_run, mloc);
+            const float mc = m_new * scale_log2e;
+            float psum = 0.0f;
+            bf16x8 pf[4];
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
+                    psum += pe;
+                    pf[2 * T + (e >> 3)][e & 7] = (bf16)pe;
+                }
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+                m_run = m_new;
+            }
+            l_run += psum;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[i & 3], pf[i >> 2], oacc[i & 3], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 4 < 16) {
+                    vr[i & 3] = rd_tr(vs, ad, (i + 4) & 3, (i + 4) >> 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(oacc[t][e4 * 4 + r] * inv);
+            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
+        }
+    if (g == 0)
+        lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
+            (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+}
+
+// ------------------------------------------------------------------------------------ backward: dQ
+// Lane = query.  Per key tile: S^T = K Q^T and dP^T = V dO^T (operands K, V row-wise from LDS; Q, dO
+// in registers), P^T = exp2(S^T*c - lse), dS^T = P^T o (dP^T - delta), dQ^T += K^T dS^T with K^T
+// gathered from the same key tile through the transposing load.  It also computes
+// delta[q] = sum_e dO[q,e] * O[q,e] for its queries and stores it for the dK kernel, which runs after it.
+// Four waves per work-group on 128 consecutive queries: every wave all key tiles of its 32 queries, tiles
+// streamed one by one through two stages, two work-groups per CU.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ attn,
+                                                                const bf16 *__restrict__ dattn,
+                                                                const float *__restrict__ lse, float *__restrict__ delta,
+                                                                bf16 *__restrict__ dqkv, int seq, int nh, int nb,
+                                                                float scale, float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
+    int qb, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
+    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, c = lane & 31;
+    const int qw0 = 128 * qb + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
 
     bf16x8 qf[8], dof[8];
@@ -370,8 +514,6 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
     }
     const int64_t stat = ((int64_t)bi * nh + n) * seq + qw0 + c;
     const float l2 = lse[stat] * 1.44269504088896340736f;
-    // delta[q] = sum_e dO[q,e] * O[q,e] (both waves of the pair need it; the first one stores it for the
-    // dK kernel, which runs after this one)
     float dl = 0.0f;
     {
         const bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD + 8 * g;
@@ -382,10 +524,9 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
             for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[st][k], (float)of[k], dl);
         }
         dl += __shfl_xor(dl, 32, 64);
-        if (g == 0 && half == 0) delta[stat] = dl;
+        if (g == 0) delta[stat] = dl;
     }
-
-    TileCopy<8> cp;
+    TileCopy<4> cp;
     cp.init(lane, wave, ld);
     TileAddr ad;
     ad.init(lane);
@@ -400,17 +541,14 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
 #pragma unroll
         for (int e = 0; e < 16; ++e) dqacc[t][e] = 0.0f;
 
-    const int n_pairs = qb + 1;
+    const int n_tiles = 2 * (qb + 1);
     const int my_tiles = qw0 / kTile + 1;
-    auto issue_pair = [&](int p) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const uint32_t dst = lds0 + ((p & 1) * 2 + t) * 2 * kTileBytes;
-            cp.issue(kbase + (2 * p + t) * tile_stride, dst, wave);
-            cp.issue(vbase + (2 * p + t) * tile_stride, dst + kTileBytes, wave);
-        }
+    auto issue_tile = [&](int jt) {
+        const uint32_t dst = lds0 + (jt & 1) * 2 * kTileBytes;
+        cp.issue(kbase + jt * tile_stride, dst, wave);
+        cp.issue(vbase + jt * tile_stride, dst + kTileBytes, wave);
     };
-    issue_pair(0);
+    issue_tile(0);
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
         loaded_before_here(qf[st]);
@@ -419,12 +557,11 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    for (int p = 0; p < n_pairs; ++p) {
-        if (p + 1 < n_pairs) issue_pair(p + 1);
-        const int jt = 2 * p + half;
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        if (jt + 1 < n_tiles) issue_tile(jt + 1);
         if (jt < my_tiles) {
             const int kv0 = jt * kTile;
-            const unsigned char *ks = smem + ((p & 1) * 2 + half) * 2 * kTileBytes;
+            const unsigned char *ks = smem + (jt & 1) * 2 * kTileBytes;
             const unsigned char *vs = ks + kTileBytes;
             bf16x8 dsf[4];
             const bool diag = kv0 + kTile - 1 > qw0;
@@ -445,7 +582,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) sacc[e] = -INFINITY;  // p = 2^(-inf) = 0
+                        if (kv > qw0 + c) sacc[e] = -INFINITY;
                     }
                 }
 #pragma unroll
@@ -463,16 +600,6 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-
-    float *mg = reinterpret_cast<float *>(smem) + grp * (64 * 64);
-    if (half == 1) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = dqacc[t][e];
-    }
-    __syncthreads();
-    if (half == 1) return;
     bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -480,8 +607,7 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
         for (int e4 = 0; e4 < 4; ++e4) {
             bf16x4 o;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                o[r] = (bf16)((dqacc[t][e4 * 4 + r] + mg[(t * 16 + e4 * 4 + r) * 64 + lane]) * scale);
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(dqacc[t][e4 * 4 + r] * scale);
             *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
         }
 }
@@ -492,24 +618,24 @@ __global__ __launch_bounds__(512, 2) void attn_bwd_dq_split_kernel(const bf16 *_
 //   DK = false: dV^T += dO^T P, with dO^T gathered from the dO tile through the transposing load;
 //   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
 // Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy (fused they need
-// 434 VGPRs).  Work laid out as in the forward kernel: 128 consecutive keys per work-group, the two
-// waves of a SIMD share a group of 32 keys and take the even / odd query tiles (streamed in pairs, from
-// the diagonal to the end of the sequence); the second wave's partial sum goes through LDS to the first.
+// 434 VGPRs).  The per-query log-sum-exp and delta travel through LDS with the tiles (as ordinary loads
+// inside the loop their in-order completion made every use wait behind the next tile's copies).
 // Early key blocks see the most queries and are dispatched first; the dK and dV work-groups of a key
 // block follow each other.
+// Four waves per work-group on 128 consecutive keys: every wave all query tiles of its 32 keys (from the
+// diagonal to the end of the sequence), streamed one by one through two stages, two work-groups per CU.
 template <bool DK>
-__device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
-                                                        const float *__restrict__ lse, const float *__restrict__ delta,
-                                                        bf16 *__restrict__ dqkv, int seq, int nh, float scale,
-                                                        float scale_log2e, int kb, int n, int bi)
+__device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
+                                                     const float *__restrict__ lse, const float *__restrict__ delta,
+                                                     bf16 *__restrict__ dqkv, int seq, int nh, float scale,
+                                                     float scale_log2e, int kb, int n, int bi)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4][Q tile | dO tile], [4][lse | delta]
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][Q tile | dO tile], [2][lse | delta]
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = wave >> 2, grp = wave & 3;
     const int g = lane >> 5, c = lane & 31;
-    const int kvw0 = 128 * kb + 32 * grp;
+    const int kvw0 = 128 * kb + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
 
     bf16x8 kf[8], vf[DK ? 8 : 1];
@@ -521,7 +647,7 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
             if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
         }
     }
-    TileCopy<8> cq, cd;
+    TileCopy<4> cq, cd;
     cq.init(lane, wave, ld);
     cd.init(lane, wave, h);
     TileAddr ad;
@@ -532,26 +658,21 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
     const uint32_t lds0 = lds_addr_of(smem);
     const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
-    constexpr int S = kStages;
-    const uint32_t stat0 = lds0 + S * 2 * kTileBytes;
+    const uint32_t stat0 = lds0 + 2 * 2 * kTileBytes;
     const uint32_t lane4 = lane * 4;
-    const int it0 = 2 * kb, n_pairs = seq / 128 - kb;  // query tiles it0 + 2p, it0 + 2p + 1
-    auto issue_pair = [&](int p) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int it = it0 + 2 * p + t, buf = (p & 1) * 2 + t;
-            cq.issue(qbase + it * q_stride, lds0 + buf * 2 * kTileBytes, wave);
-            cd.issue(dbase + it * d_stride, lds0 + buf * 2 * kTileBytes + kTileBytes, wave);
-            // the per-query statistics travel with the tiles (a 4-byte-per-lane global->LDS load each)
-            if (wave == 0) {
-                const uint32_t dst = stat0 + buf * 512;
-                const float *src = lse_b + it * kTile;
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-            } else if (wave == 1 && DK) {
-                const uint32_t dst = stat0 + buf * 512 + 256;
-                const float *src = del_b + it * kTile;
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-            }
+    const int it0 = 2 * kb, n_tiles = 2 * (seq / 128 - kb);  // query tiles it0 + j
+    auto issue_tile = [&](int j) {
+        const int it = it0 + j, buf = j & 1;
+        cq.issue(qbase + it * q_stride, lds0 + buf * 2 * kTileBytes, wave);
+        cd.issue(dbase + it * d_stride, lds0 + buf * 2 * kTileBytes + kTileBytes, wave);
+        if (wave == 0) {
+            const uint32_t dst = stat0 + buf * 512;
+            const float *src = lse_b + it * kTile;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
+        } else if (wave == 1 && DK) {
+            const uint32_t dst = stat0 + buf * 512 + 256;
+            const float *src = del_b + it * kTile;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
         }
     };
 
@@ -561,7 +682,7 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
 
-    issue_pair(0);
+    issue_tile(0);
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
         loaded_before_here(kf[st]);
@@ -570,16 +691,16 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    for (int p = 0; p < n_pairs; ++p) {
-        if (p + 1 < n_pairs) issue_pair(p + 1);
-        const int buf = (p & 1) * 2 + half;
-        const int qt0 = (it0 + 2 * p + half) * kTile;
-        if (qt0 + kTile - 1 >= kvw0) {  // wave-uniform: some query of the tile sees some key of this wave
+    for (int j = 0; j < n_tiles; ++j) {
+        if (j + 1 < n_tiles) issue_tile(j + 1);
+        const int buf = j & 1;
+        const int qt0 = (it0 + j) * kTile;
+        if (qt0 + kTile - 1 >= kvw0) {
             const unsigned char *qs = smem + buf * 2 * kTileBytes;
             const unsigned char *ds = qs + kTileBytes;
-            const float *lse_s = reinterpret_cast<const float *>(smem + S * 2 * kTileBytes + buf * 512);
+            const float *lse_s = reinterpret_cast<const float *>(smem + 2 * 2 * kTileBytes + buf * 512);
             const float *del_s = lse_s + 64;
-            bf16x8 frag[4];  // P (for dV) or dS (for dK) as MFMA operand
+            bf16x8 frag[4];
             const bool diag = qt0 < kvw0 + 31;
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
@@ -595,7 +716,6 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
                     if constexpr (DK)
                         dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
                 }
-                // sacc[e] of this lane: query qt0 + 32T + 8(e/4) + 4g + e%4, key kvw0 + c
                 if (diag) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
@@ -615,7 +735,7 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
                     }
                 }
             }
-            const unsigned char *src = DK ? qs : ds;  // dK^T += Q^T dS ; dV^T += dO^T P
+            const unsigned char *src = DK ? qs : ds;
 #pragma unroll
             for (int st = 0; st < 4; ++st)
 #pragma unroll
@@ -625,17 +745,6 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-
-    float *mg = reinterpret_cast<float *>(smem) + grp * (64 * 64);
-    if (half == 1) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = acc[t][e];
-    }
-    __syncthreads();
-    if (half == 1) return;
-    // K gradient goes to the K part of dqkv (scaled), V gradient to the V part
     bf16 *out = dqkv + (row0 + kvw0 + c) * ld + (DK ? h : 2 * h) + (int64_t)n * kD;
     const float oscale = DK ? scale : 1.0f;
 #pragma unroll
@@ -644,27 +753,23 @@ __device__ __forceinline__ void attn_bwd_dkv_split_body(const bf16 *__restrict__
         for (int e4 = 0; e4 < 4; ++e4) {
             bf16x4 o;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                o[r] = (bf16)((acc[t][e4 * 4 + r] + mg[(t * 16 + e4 * 4 + r) * 64 + lane]) * oscale);
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(acc[t][e4 * 4 + r] * oscale);
             *reinterpret_cast<bf16x4 *>(out + 32 * t + 8 * e4 + 4 * g) = o;
         }
 }
 
-__global__ __launch_bounds__(512, 2) void attn_bwd_dkv_split_kernel(const bf16 *__restrict__ qkv,
-                                                                    const bf16 *__restrict__ dattn,
-                                                                    const float *__restrict__ lse,
-                                                                    const float *__restrict__ delta,
-                                                                    bf16 *__restrict__ dqkv, int seq, int nh, int nb,
-                                                                    float scale, float scale_log2e)
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_w4_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
+                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
+                                                                 bf16 *__restrict__ dqkv, int seq, int nh, int nb, float scale,
+                                                                 float scale_log2e)
 {
-    // the two kinds of work-group of a (key block, head, sample) are told apart by doubling the sample count
     int blk, n, v;
     decode_heavy_first(blockIdx.x, seq / 128, nh, 2 * nb, blk, n, v);
-    const int kb = seq / 128 - 1 - blk;  // heavy = early key blocks
+    const int kb = seq / 128 - 1 - blk;
     if (v < nb)
-        attn_bwd_dkv_split_body<true>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v);
+        attn_bwd_dkv_w4_body<true>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v);
     else
-        attn_bwd_dkv_split_body<false>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v - nb);
+        attn_bwd_dkv_w4_body<false>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v - nb);
 }
 
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
@@ -684,12 +789,25 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
 {
     if (dt != DT_BF16 || !attn_mfma_supported(seq, d)) return hipErrorInvalidValue;
     if (b * seq == 0) return hipSuccess;
-    constexpr size_t lds = kStages * 2 * kTileBytes;  // (K tile, V tile) stages
-    static bool done = false;
-    if (hipError_t e = set_lds(attn_fwd_split_kernel, lds, done)) return e;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
-    attn_fwd_split_kernel<<<dim3((unsigned)(seq / 128 * nh * b)), 512, lds, s>>>(
-        (const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b, scale_log2e);
+    const unsigned blocks = (unsigned)(seq / 128 * nh * b);
+    // Up to two work-groups per CU's worth of work: the eight-wave kernel (a work-group's chain of intervals is
+    // half as long); beyond: the four-wave kernel, two work-groups per CU, where one's prologue and epilogue
+    // hide behind the other's tiles (measured at 32 heads x 2048: 54.0 against 57.0 us for 512 work-groups,
+    // 106.8 against 95.2 us for 1024).
+    if (blocks >= 768) {
+        constexpr size_t lds = 4 * kTileBytes;  // two stages of (K tile, V tile)
+        static bool done = false;
+        if (hipError_t e = set_lds(attn_fwd_w4_kernel, lds, done)) return e;
+        attn_fwd_w4_kernel<<<dim3(blocks), 256, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b,
+                                                          scale_log2e);
+    } else {
+        constexpr size_t lds = kStages * 2 * kTileBytes;  // two pairs of (K tile, V tile)
+        static bool done = false;
+        if (hipError_t e = set_lds(attn_fwd_split_kernel, lds, done)) return e;
+        attn_fwd_split_kernel<<<dim3(blocks), 512, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
+                                                             (int)b, scale_log2e);
+    }
     return hipGetLastError();
 }
 
@@ -700,18 +818,16 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (b * seq == 0) return hipSuccess;
     const float scale = 1.0f / sqrtf((float)d);
     const float scale_log2e = scale * 1.44269504088896340736f;
-    constexpr size_t lds_dq = kStages * 2 * kTileBytes;                    // stages of (K tile, V tile)
-    constexpr size_t lds_dkv = kStages * 2 * kTileBytes + kStages * 512;  // (Q tile, dO tile) + lse/delta
+    constexpr size_t lds_dq = 4 * kTileBytes;             // two stages of (K tile, V tile)
+    constexpr size_t lds_dkv = 4 * kTileBytes + 2 * 512;  // two stages of (Q tile, dO tile) + lse/delta
     static bool a1 = false, a2 = false;
-    if (hipError_t e = set_lds(attn_bwd_dq_split_kernel, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_split_kernel, lds_dkv, a2)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dq_w4_kernel, lds_dq, a1)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_w4_kernel, lds_dkv, a2)) return e;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
-    attn_bwd_dq_split_kernel<<<dim3(blocks), 512, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn,
-                                                               (const bf16 *)dattn, lse, delta, (bf16 *)dqkv, (int)seq,
-                                                               (int)nh, (int)b, scale, scale_log2e);
-    attn_bwd_dkv_split_kernel<<<dim3(2 * blocks), 512, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                                     (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale,
-                                                                     scale_log2e);
+    attn_bwd_dq_w4_kernel<<<dim3(blocks), 256, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse,
+                                                            delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale, scale_log2e);
+    attn_bwd_dkv_w4_kernel<<<dim3(2 * blocks), 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
+                                                                  (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale, scale_log2e);
     return hipGetLastError();
 }
 
