@@ -26,6 +26,15 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
                                int64_t ldb, void *C, int64_t ldc, const void *bias, const void *resid,
                                int32_t out_f32, int32_t tile, void *hip_stream);
 
+/* The weight-gradient product of Section 2.3 without any transposition in memory: C[M,N] = A^T . B with A stored
+ * [K, M] (M contiguous, leading dimension lda >= M) and B stored [K, N] (leading dimension ldb >= N), i.e.
+ * dW[out,in] = dY[T,out]^T . X[T,in] read from the token-major activations where they lie.  bf16 operands, fp32
+ * accumulation; C is bf16 (out_f32 == 0), float (1), or float and receives C + result (2).  M and N multiples
+ * of 256, K a multiple of 64, lda and ldb multiples of 8 (ZPP_ERR_UNSUPPORTED otherwise; the stage then
+ * transposes the operands and uses the product above). */
+zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
+
 /* Causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each; T = b*seq, h = nh*d):
  * attn[T, h] = softmax(Q K^T / sqrt(d) + causal mask) V per (sample, head); lse[b, nh, seq] is the
  * log-sum-exp of the scaled, masked scores.  dtype: ZPP_DTYPE_*; impl 0 = generic kernel,

@@ -658,6 +658,194 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
     epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
+// ---------------------------------------------------------------------------------------------
+// K-major kernel: C[M,N] = A^T . B with A stored [K, M] (M contiguous) and B stored [K, N] - the weight-gradient
+// product dW = dY^T . X read straight from the token-major activations, no transposed copies in memory.  Same
+// skeleton as the two-stage kernel (256x256 tile, 8 waves of 128x64, two LDS buffers of K = 64, copies global ->
+// LDS directly, K loop rotated across the barrier, pinned order); what differs is the way through LDS:
+//   * a tile is [64 k][256 m] with 512-byte rows; a copy instruction moves two k-rows (1 KB);
+//   * the MFMA operand (one m, eight consecutive k per lane) is gathered down the rows with the transposing
+//     load ds_read_b64_tr_b16, two per operand (four k each): within 16 lanes, lanes 4j+q point at row j,
+//     8-byte piece q, and lane i receives element i%4 of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4,
+//     i.e. column i of four consecutive rows;
+//   * the 16-byte chunk c of row k sits at chunk position c ^ (4 * (k % 4)): the four rows of a transposing
+//     load then fall into four different 64-byte bank groups, and the two k-halves of the wave take the two
+//     passes a 512-byte access needs anyway - no bank conflicts.
+// Needs M and N in multiples of 256 and K in multiples of 64 (the dispatcher falls back to transposed copies
+// and the NT kernel otherwise).
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+__device__ __forceinline__ bf16x8 rd_tr8(const unsigned char *p)
+{
+    // rows k .. k+3 at p, rows k+4 .. k+7 four rows (2048 bytes) further
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 2048));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A,
+                                                           int64_t lda, const bf16 *__restrict__ B, int64_t ldb,
+                                                           void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m,
+                                                           int tiles_n)
+{
+    constexpr int BM = 256, BN = 256, WGN = 4, NW = 8;
+    constexpr int WM = 128, WN = 64, MT = 4, NT = 2;
+    constexpr int A_I = 4, B_I = 4;            // copies (of two k-rows each) per wave per K-step and operand
+    constexpr int LPS = A_I + B_I;
+    constexpr int G1 = LPS / 2, G2 = LPS - G1;
+    constexpr int FRAGS = MT + NT, MFMAS = MT * NT;
+    constexpr int A_BUF_BYTES = BM * kBK * 2, B_BUF_BYTES = BN * kBK * 2;
+    constexpr int B_REGION = 2 * A_BUF_BYTES;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- global side: copy j of this wave moves rows 2*(4*wave + j), +1 of the K-step; lane i writes bytes
+    // [16 i, 16 i + 16) of the 1 KB slot, i.e. row i/32, chunk position i%32, which holds chunk (i%32) ^ swizzle
+    uint32_t a_voff[A_I], b_voff[B_I];
+#pragma unroll
+    for (int j = 0; j < A_I; ++j) {
+        const int row = 2 * (wave * A_I + j) + (lane >> 5);
+        const int chunk = (lane & 31) ^ (4 * (row & 3));
+        a_voff[j] = (uint32_t)(((int64_t)row * lda + chunk * 8) * 2);
+        b_voff[j] = (uint32_t)(((int64_t)row * ldb + chunk * 8) * 2);
+    }
+    const char *a_tile = reinterpret_cast<const char *>(A + m0);
+    const char *b_tile = reinterpret_cast<const char *>(B + n0);
+    const int64_t a_kstep = (int64_t)kBK * lda * 2, b_kstep = (int64_t)kBK * ldb * 2;
+
+    // ---- LDS side: per-lane byte address of the first transposing load of every operand block at K sub-step 0
+    unsigned char *a_rd[MT], *b_rd[NT];
+    {
+        const int khalf = lane >> 5, g = (lane >> 4) & 1, j = (lane & 15) >> 2, q = lane & 3;
+        const int low2 = 2 * g + (q >> 1);
+        const int rowoff = (8 * khalf + j) * 512 + (q & 1) * 8;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) a_rd[i] = smem_raw + rowoff + 16 * (low2 + 4 * ((4 * wm + i) ^ j));
+#pragma unroll
+        for (int i = 0; i < NT; ++i) b_rd[i] = smem_raw + B_REGION + rowoff + 16 * (low2 + 4 * ((2 * wn + i) ^ j));
+    }
+
+    f32x16 acc[MT][NT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int nk = (int)(K / kBK);
+    bf16x8 af[2][MT], bfr[2][NT];
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
+    auto gll = [&](int n, int kt, int buf) {
+        if (n < A_I) {
+            const char *abase = a_tile + (int64_t)kt * a_kstep;
+            const uint32_t dst = a_slot + buf * A_BUF_BYTES + n * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "memory");
+        } else {
+            const int m = n - A_I;
+            const char *bbase = b_tile + (int64_t)kt * b_kstep;
+            const uint32_t dst = b_slot + buf * B_BUF_BYTES + m * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "memory");
+        }
+    };
+    // operand block f (0 = A0, 1..NT = B, then A1..) of K sub-step ks of buffer buf
+    auto rd_frag = [&](auto f_c, auto nxt_c, int off) {
+        constexpr int f = decltype(f_c)::value, NXT = decltype(nxt_c)::value;
+        if constexpr (f == 0)
+            af[NXT][0] = rd_tr8(a_rd[0] + off);
+        else if constexpr (f <= NT)
+            bfr[NXT][f - 1] = rd_tr8(b_rd[f - 1] + off);
+        else
+            af[NXT][f - NT] = rd_tr8(a_rd[f - NT] + off);
+    };
+    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the LDS
+    // reads of sub-step RKS of buffer RBUF into the other fragment set (one operand block = two transposing
+    // loads per MFMA), and with GCNT copies (numbers GFIRST..) of K-step gkt into buffer GBUF.
+    auto phase = [&](auto cur_c, auto rbuf_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gbuf_c, int gkt) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        constexpr int RBUF = decltype(rbuf_c)::value, RKS = decltype(rks_c)::value;
+        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
+        constexpr int GBUF = decltype(gbuf_c)::value;
+        static_for<MFMAS>([&](auto tt) {
+            constexpr int t = decltype(tt)::value;
+            constexpr int i = t / NT, j = t % NT;
+            if constexpr (t < FRAGS) {
+                rd_frag(tt, std::integral_constant<int, NXT>{}, RBUF * A_BUF_BYTES + RKS * 8192);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (GCNT > 0) {
+                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
+                if constexpr (after > before) {
+                    gll(GFIRST + before, gkt, GBUF);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using IG1 = std::integral_constant<int, G1>;
+    using IG2 = std::integral_constant<int, G2>;
+
+    auto kstep = [&](auto buf_c, int kt) {
+        constexpr int BUF = decltype(buf_c)::value;
+        using IB = std::integral_constant<int, BUF>;
+        using IO = std::integral_constant<int, BUF ^ 1>;
+        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
+        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
+        phase(I0{}, IB{}, I1{}, IG1{}, IG2{}, IO{}, nxt1);
+        phase(I1{}, IB{}, I2{}, I0{}, I0{}, IO{}, 0);
+        phase(I0{}, IB{}, I3{}, I0{}, I0{}, IO{}, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        phase(I1{}, IO{}, I0{}, I0{}, IG1{}, IB{}, nxt2);
+    };
+
+#pragma unroll
+    for (int n = 0; n < LPS; ++n) gll(n, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    {
+        const int k1 = nk > 1 ? 1 : 0;
+#pragma unroll
+        for (int n = 0; n < G1; ++n) gll(n, k1, 1);
+    }
+    static_for<FRAGS>([&](auto ff) { rd_frag(ff, I0{}, 0); });
+
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        kstep(I0{}, kt);
+        kstep(I1{}, kt + 1);
+    }
+    if (kt < nk) kstep(I0{}, kt);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
 // One launch wrapper for both kernels: raises the kernel's dynamic LDS limit once per process (guarded, so
 // that host threads driving different stages may launch concurrently) and starts one work-group per tile.
 template <class Kernel>
@@ -695,6 +883,24 @@ static hipError_t launch_ring(int64_t M, int64_t N, int64_t K, const bf16 *A, in
     static hipError_t attr_err = hipSuccess;
     return launch_tiles(gemm_bf16_nt_d_kernel<BM, BN, WGM, WGN, NS>, once, attr_err, BM, BN, WGM * WGN * 64,
                         (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
+}
+
+bool gemm_bf16_tt_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb)
+{
+    return M > 0 && N > 0 && K > 0 && M % 256 == 0 && N % 256 == 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+           64 * lda * 2 < (int64_t)1 << 31 && 64 * ldb * 2 < (int64_t)1 << 31;
+}
+
+hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                               void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
+{
+    if (!gemm_bf16_tt_supported(M, N, K, lda, ldb)) return hipErrorInvalidValue;
+    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
+              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    return launch_tiles(gemm_bf16_tt_kernel, once, attr_err, 256, 256, 512, (size_t)2 * 512 * kBK * sizeof(bf16), M, N, K,
+                        (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
 }
 
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)

@@ -142,6 +142,12 @@ enum { GEMM_TILE_AUTO = -1, GEMM_TILE_256x256 = 0, GEMM_TILE_128x128 = 1, GEMM_T
 hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s,
                                int tile = GEMM_TILE_AUTO);
+// The same product with both operands stored K-major: C[M,N] = A^T . B, A is [K, M] (row stride lda, M contiguous),
+// B is [K, N] (row stride ldb): the weight-gradient product read from token-major activations in place.
+// Only for shapes gemm_bf16_tt_supported accepts (M, N multiples of 256, K of 64).
+bool gemm_bf16_tt_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb);
+hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
 
 // ---- causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each) ----

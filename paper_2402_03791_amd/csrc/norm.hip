@@ -282,12 +282,44 @@ __global__ __launch_bounds__(256) void colreduce_stage2(const float *__restrict_
     if (out1) out1[c] = s1;
 }
 
+// Column sums of a bf16 matrix with 16-byte loads (the bias gradient db = column sums of dY when the
+// weight-gradient product reads dY in place and no transposing pass is there to produce them on the way): a
+// work-group takes kColRows rows x 512 columns, a lane eight adjacent columns, the four waves every fourth row;
+// the four partial sums per column meet in LDS and one partial row goes out, for the same second level as the
+// other column reductions.  C must be a multiple of 512.
+__global__ __launch_bounds__(256) void colsum_wide_kernel(const bf16 *__restrict__ a, int64_t rows, int64_t C, int64_t ld,
+                                                          float *__restrict__ partial)
+{
+    __shared__ float red[4][512];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 512 + tx * 8;
+    const int64_t r0 = (int64_t)blockIdx.y * kColRows;
+    const int64_t r1 = (r0 + kColRows < rows) ? r0 + kColRows : rows;
+    float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t r = r0 + ty; r < r1; r += 4) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(a + r * ld + c);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] += (float)v[k];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) red[ty][tx * 8 + k] = acc[k];
+    __syncthreads();
+    for (int i = threadIdx.x; i < 512; i += 256)
+        partial[(int64_t)blockIdx.y * C + (int64_t)blockIdx.x * 512 + i] = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
+}
+
 hipError_t launch_colreduce(int dt, int mode, const void *a, const void *x, const float *mean,
                             const float *rstd, int64_t T, int64_t C, int64_t ld, float *out0, float *out1,
                             float *partial, hipStream_t s, FinishItem *defer)
 {
     if (T == 0 || C == 0) return hipSuccess;
     const int64_t rc = (T + kColRows - 1) / kColRows;
+    if (dt == DT_BF16 && mode == COLRED_SUM && defer && C % 512 == 0 && ld % 8 == 0 &&
+        reinterpret_cast<uintptr_t>(a) % 16 == 0) {
+        colsum_wide_kernel<<<dim3((unsigned)(C / 512), (unsigned)rc), 256, 0, s>>>((const bf16 *)a, T, C, ld, partial);
+        *defer = FinishItem{partial, nullptr, out0, nullptr, (int32_t)rc, C};
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)((C + 63) / 64), (unsigned)rc);
 #define ZPP_LAUNCH(TT, MM)                                                                                 \
     colreduce_stage1<TT, MM><<<grid, 256, 0, s>>>((const TT *)a, (const TT *)x, mean, rstd, T, C, ld, partial)

@@ -450,6 +450,19 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
         // sees K-contiguous operands (reading them K-major in place with transposing LDS loads takes twice
         // the LDS read instructions per MFMA and measured about 30 % slower).  The bias gradient comes out of
         // the same pass that transposes dY.
+        if (gemm_bf16_tt_supported(out, in, s->Tc, out, in)) {
+            // K-major product: dY and X are read where they lie; the bias gradient needs its own pass over dY
+            if (bias) {
+                ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
+                float *slot = s->red_slot();
+                e = launch_colreduce(DT_BF16, COLRED_SUM, dy, nullptr, nullptr, nullptr, s->Tc, out, out, s->Sp(blk, bias),
+                                     nullptr, slot, st, s->defer());
+                if (e != hipSuccess) return e;
+            }
+            ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * s->Tc * in * out, st,
+                           2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out);
+            return launch_gemm_bf16_tt(out, in, s->Tc, dy, out, x, in, s->Sp(blk, w), in, epi, st);
+        }
         void *tA = s->tp("tA"), *tB = s->tp("tB");
         {
             ProfScope prof(ZPP_PROF_OTHER, 0.0, st);
@@ -1358,6 +1371,21 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     e.resid = resid;
     e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
     hipError_t err = launch_gemm_bf16_nt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream, tile);
+    if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream)
+{
+    if (!A || !B || !C) return fail(ZPP_ERR_ARG, "A/B/C is NULL");
+    if (M <= 0 || N <= 0 || K <= 0 || lda < M || ldb < N || ldc < N) return fail(ZPP_ERR_ARG, "bad sizes");
+    if (!gemm_bf16_tt_supported(M, N, K, lda, ldb))
+        return fail(ZPP_ERR_UNSUPPORTED, "need M, N multiples of 256, K a multiple of 64, lda/ldb multiples of 8");
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
+    GemmEpi e;
+    e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
+    hipError_t err = launch_gemm_bf16_tt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
     if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
     return ZPP_OK;
 }

@@ -752,6 +752,34 @@ def test_gemm_bf16_nt_against_oracle(M, N, K, tile):
     assert torch.equal(G, g0 + Cf)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 512, 192), (768, 256, 1024), (1024, 2048, 512)])
+def test_gemm_bf16_tt_against_oracle(M, N, K):
+    """dW = dY^T . X straight from the token-major operands, with strided rows, written and accumulated."""
+    print(f"gemm tt {M}x{N}x{K}", flush=True)
+    dy = synth.normal_f32(4, 80, K * M, bf16_exact=True).reshape(K, M)
+    x = synth.normal_f32(4, 81, K * N, bf16_exact=True).reshape(K, N)
+    ref, _ = oracle.Ops("f64").linear_bwd_weight(dy, x)
+    # operands as column slices of wider matrices, so the leading dimensions differ from M and N
+    Aw = torch.zeros(K, M + 64, dtype=torch.bfloat16, device="cuda")
+    Bw = torch.zeros(K, N + 128, dtype=torch.bfloat16, device="cuda")
+    Aw[:, 64:] = to_dev(dy, torch.bfloat16)
+    Bw[:, :N] = to_dev(x, torch.bfloat16)
+    A, B = Aw[:, 64:], Bw[:, :N]
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    zpp.op_gemm_bf16_tt(A, B, C)
+    assert rel_err(to_np(C), ref) <= 1e-5
+    Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    zpp.op_gemm_bf16_tt(A, B, Cb)
+    assert rel_err(to_np(Cb), ref) <= 8e-3
+    g0 = torch.from_numpy(synth.normal_f32(1, 54, M * N).reshape(M, N)).cuda()
+    G = g0.clone()
+    zpp.op_gemm_bf16_tt(A, B, G, accumulate=True)
+    assert torch.equal(G, g0 + C)
+    with pytest.raises(zpp.ZppError) as e:      # shapes the K-major kernel does not take are refused, not mangled
+        zpp.op_gemm_bf16_tt(A[:, :128], B, C[:128])
+    assert e.value.status == -6
+
+
 @pytest.mark.parametrize("dtype,b,s,nh,d", [(torch.float32, 2, 70, 3, 32), (torch.bfloat16, 1, 130, 2, 128),
                                             (torch.float32, 1, 1, 1, 64)])
 def test_generic_attention_against_oracle(dtype, b, s, nh, d):
