@@ -109,35 +109,30 @@ struct F32Rows {
     }
 };
 
-// Epilogue shared by the GEMM kernels.  The accumulator layout of the 32x32 MFMA gives a lane one
-// column and scattered rows, which would make every global store a 2-byte-per-lane scatter.  So each
-// wave transposes its tile through its own slice of LDS, 32 rows at a time (fp32, bias already
-// added), and then every lane owns 8 consecutive columns of a row: residual / GeLU inputs are read
-// and results written with 16-byte accesses, a full 128-byte line per 8 lanes.
-// acc[i][j][e] of lane l is C[m_wave + i*32 + (e/4)*8 + (l/32)*4 + e%4, n_wave + j*32 + l%32].
+// Epilogue shared by the GEMM kernels.  The accumulator layouts of the MFMAs give a lane one column and
+// scattered rows, which would make every global store a 2-byte-per-lane scatter.  So each wave transposes
+// its tile through its own slice of LDS, 32 rows at a time (fp32, bias already added; `put(i, stage)` deposits
+// rows [32 i, 32 i + 32) of the wave tile, row stride epi_stride), and then every lane owns 8 consecutive
+// columns of a row: residual / GeLU inputs are read and results written with 16-byte accesses, a full
+// 128-byte line per 8 lanes.
 // Must be entered after a work-group barrier that ends all use of the operand tiles in LDS.
-template <int MT, int NT>
-__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int wave, int lane,
-                                         void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
-                                         int64_t N, int64_t m_wave, int64_t n_wave)
+constexpr int epi_stride(int NT) { return NT * 32 + 8; }  // floats; 4 rows apart = half the banks apart
+
+template <int MT, int NT, class Put>
+__device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, int wave, int lane,
+                                              void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
+                                              int64_t N, int64_t m_wave, int64_t n_wave)
 {
     constexpr int WN = NT * 32;
-    constexpr int STRIDE = WN + 8;          // floats; 4 rows apart = half the banks apart
+    constexpr int STRIDE = epi_stride(NT);
     constexpr int CH = WN / 8;              // 8-column chunks per row
     constexpr int ROWS_PER_PASS = 64 / CH;  // rows covered by the 64 lanes at once
     constexpr int PASSES = 32 / ROWS_PER_PASS;
     float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * STRIDE);
-    const int khalf = lane >> 5, c32 = lane & 31;
     const bool vec_ok = (ldc % 8 == 0) && (reinterpret_cast<uintptr_t>(Cv) % 16 == 0) &&
                         (!epi.resid || reinterpret_cast<uintptr_t>(epi.resid) % 16 == 0) &&
                         (!epi.aux || reinterpret_cast<uintptr_t>(epi.aux) % 16 == 0) &&
                         (!epi.out2 || reinterpret_cast<uintptr_t>(epi.out2) % 16 == 0);
-    float bias[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int64_t n = n_wave + j * 32 + c32;
-        bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
-    }
     F32Rows<NT> fr;
     fr.init(Cv, ldc, epi, M, N, m_wave, n_wave, lane);
     constexpr int ROWS4 = F32Rows<NT>::ROWS4, PASSES4 = F32Rows<NT>::PASSES4;
@@ -155,12 +150,7 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
         constexpr int i = decltype(ii)::value;
         if constexpr (i + 1 < MT)
             if (accum) fr.template fetch<i + 1>(old[(i + 1) & 1]);
-        static_for<NT>([&](auto jj) {
-            constexpr int j = decltype(jj)::value;
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                stage[((e >> 2) * 8 + khalf * 4 + (e & 3)) * STRIDE + j * 32 + c32] = acc[i][j][e] + bias[j];
-        });
+        put(ii, stage);
         // the slice is private to this wave; LDS operations of a wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -247,6 +237,66 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
     });
 }
 
+// v_mfma_f32_32x32x16_bf16 accumulators: acc[i][j][e] of lane l is
+// C[m_wave + i*32 + (e/4)*8 + (l/32)*4 + e%4, n_wave + j*32 + l%32].
+template <int MT, int NT>
+__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int wave, int lane,
+                                         void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
+                                         int64_t N, int64_t m_wave, int64_t n_wave)
+{
+    constexpr int STRIDE = epi_stride(NT);
+    const int khalf = lane >> 5, c32 = lane & 31;
+    float bias[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const int64_t n = n_wave + j * 32 + c32;
+        bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
+    }
+    epilogue_rows<MT, NT>(
+        [&](auto ii, float *stage) {
+            constexpr int i = decltype(ii)::value;
+            static_for<NT>([&](auto jj) {
+                constexpr int j = decltype(jj)::value;
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    stage[((e >> 2) * 8 + khalf * 4 + (e & 3)) * STRIDE + j * 32 + c32] = acc[i][j][e] + bias[j];
+            });
+        },
+        smem_raw, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
+}
+
+// v_mfma_f32_16x16x32_bf16 accumulators: acc[i][j][e] of lane l is
+// C[m_wave + i*16 + (l/16)*4 + e, n_wave + j*16 + l%16].
+template <int MA, int NB>
+__device__ __forceinline__ void epilogue16(f32x4 (&acc)[MA][NB], unsigned char *smem_raw, int wave, int lane,
+                                           void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
+                                           int64_t N, int64_t m_wave, int64_t n_wave)
+{
+    static_assert(MA % 2 == 0 && NB % 2 == 0, "whole 32x32 groups");
+    constexpr int STRIDE = epi_stride(NB / 2);
+    const int q16 = lane >> 4, c16 = lane & 15;
+    float bias[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int64_t n = n_wave + j * 16 + c16;
+        bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
+    }
+    epilogue_rows<MA / 2, NB / 2>(
+        [&](auto ii, float *stage) {
+            constexpr int i = decltype(ii)::value;
+            static_for<2>([&](auto hh) {
+                constexpr int h = decltype(hh)::value;
+                static_for<NB>([&](auto jj) {
+                    constexpr int j = decltype(jj)::value;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        stage[(h * 16 + q16 * 4 + e) * STRIDE + j * 16 + c16] = acc[2 * i + h][j][e] + bias[j];
+                });
+            });
+        },
+        smem_raw, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
+}
+
 // Which tile a work-group computes.  Work-group ids are dealt round-robin over the 8 XCDs (one L2 each):
 // ids are first regrouped so that an XCD gets a contiguous run of tile numbers, and tile numbers walk the grid
 // in bands of 8 tile rows, down a column of the band first, so that the tiles in flight on an XCD share their
@@ -265,30 +315,56 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tile
 }
 
 // ---------------------------------------------------------------------------------------------
-// Two-stage kernel: two LDS buffers of K = 64, operands global -> LDS directly, K loop rotated across the
-// barrier, and
-//   * the instruction order of every phase is written out and pinned with scheduling barriers: the
-//     LDS reads of the next K sub-step are issued one per MFMA at the start of the current sub-step,
-//     so each has at least half a sub-step of MFMA time to return before it is needed;
-//   * the loop body is instantiated for both LDS buffers, so all LDS addresses are a per-lane base
-//     register plus an immediate, and the global addresses are a scalar base that advances per
-//     K-step plus a fixed per-lane 32-bit offset: no vector address arithmetic inside the loop.
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
+// NT kernel.  A ring of NS LDS slots of K = 64 (NS = 2 for the 256x256 and 128x128 tiles, 3 for 256x128 and
+// 128x256), operands global -> LDS directly, the K loop rotated across its one barrier per K-step.  The matrix
+// instruction is v_mfma_f32_16x16x32_bf16: on this part the chip's power management sets the pace of a GEMM,
+// and the 16x16x32 form delivers the same flops per cycle for less power than 32x32x16 (a register-only loop
+// runs at 2.0 against 1.75 GHz), which shows as a higher clock under the same kernel.
+//   * A K-step is two sub-steps of 32 k.  A sub-step is MA groups; group G multiplies the 16-row block G of
+//     the wave's A rows with the NB 16-column blocks of its B rows.  A blocks live in a ring of MA registers
+//     and are read AHEAD = MA/2 groups before their group; the B blocks of the next sub-step (a second set of
+//     registers) are read in groups AHEAD and AHEAD+1 together with its first A blocks.
+//   * The LDS reads are written as asm and waited for by count (LDS reads return in order; at each group the
+//     count of younger reads is a constant of the schedule).  Left to the compiler every wait is for all
+//     outstanding reads, which exposes the full LDS latency twice per sub-step.
+//   * Lane l of a 16x16x32 operand block holds row l%16 and eight consecutive k.  Which eight is free as long as
+//     A and B agree: lanes l and l+32 are served by the LDS in the same pass, so they take neighbouring
+//     16-byte chunks (k-group (l/16 % 2) * 2 + l/32), which the row swizzle then spreads over all banks; with the
+//     natural order (l/16) every read is a two-way bank conflict.
+//   * Copies: tile kt+NS-1's second half is issued in the first groups of K-step kt, tile kt+NS's first half
+//     after the barrier of K-step kt into the slot that barrier freed; the wait before the barrier leaves
+//     (NS-2) K-steps of copies in flight.
+//   * The loop body is instantiated per slot, so all LDS addresses are a per-lane base register plus an
+//     immediate, and the global addresses are a scalar base that advances per K-step plus a fixed per-lane
+//     32-bit offset: no vector address arithmetic inside the loop.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
+{
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
     int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
 {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
+    constexpr int MA = WM / 16, NB = WN / 16, NBH = NB / 2;
+    constexpr int AHEAD = MA / 2;
     constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
-    constexpr int LPS = A_I + B_I;            // global->LDS loads per wave per K-step
-    constexpr int G1 = LPS / 2, G2 = LPS - G1;
-    constexpr int READS = MT + NT, MFMAS = MT * NT;
-    constexpr int A_BUF_BYTES = BM * kBK * 2, B_BUF_BYTES = BN * kBK * 2;
-    constexpr int B_REGION = 2 * A_BUF_BYTES;  // byte offset of the B buffers inside LDS
-    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
-    static_assert(3 * 4096 + A_BUF_BYTES < 65536 && 3 * 4096 + B_BUF_BYTES < 65536, "LDS immediates");
+    constexpr int LPS = A_I + B_I;            // global->LDS copies per wave per K-step
+    constexpr int H1 = LPS / 2, H2 = LPS - H1;  // issued after the barrier / in the first groups of the next K-step
+    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
+    constexpr int B_REGION = NS * A_BUF;      // byte offset of the B slots inside LDS
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
+    static_assert(MA >= 4 && MA % 2 == 0 && NB % 2 == 0, "wave tile");
+    static_assert(AHEAD + NB + 1 <= 15, "the LDS wait count is a 4-bit field");
+    static_assert((H1 + MA - AHEAD - 1) / (MA - AHEAD) <= NB && (H2 + AHEAD - 1) / AHEAD <= NB, "one copy per MFMA at most");
+    static_assert(NS >= 2 && NS <= 3 && (NS - 2) * LPS < 64, "ring depth");
+    static_assert(NS * A_BUF + MA * 2048 <= 2 * 65536 && NS * B_BUF + NB * 2048 <= 2 * 65536, "two base registers");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
@@ -323,240 +399,34 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_h_kernel(
     const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
     const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
 
-    // ---- LDS side: per-lane byte addresses of the operand chunk for each K sub-step
-    const int khalf = lane >> 5;
-    unsigned char *a_rd[4], *b_rd[4];
+    // ---- LDS side: per-lane byte address of the operand chunk for each sub-step, one base for offsets below
+    // 64 KB and one for those above
+    uint32_t a_ad[2][2], b_ad[2][2];
     {
-        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+        const int r16 = lane & 15, kq = ((lane >> 4) & 1) * 2 + (lane >> 5);
+        const int arow = wm * WM + r16, brow = wn * WN + r16;
         const int asw = (arow & 7) ^ ((arow >> 3) & 1), bsw = (brow & 7) ^ ((brow >> 3) & 1);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            a_rd[ks] = smem_raw + arow * 128 + (((ks * 2 + khalf) ^ asw) << 4);
-            b_rd[ks] = smem_raw + B_REGION + brow * 128 + (((ks * 2 + khalf) ^ bsw) << 4);
+        for (int s = 0; s < 2; ++s) {
+            a_ad[0][s] = lds0 + arow * 128 + (((s * 4 + kq) ^ asw) << 4);
+            b_ad[0][s] = lds0 + B_REGION + brow * 128 + (((s * 4 + kq) ^ bsw) << 4);
+            a_ad[1][s] = a_ad[0][s] + 65536;
+            b_ad[1][s] = b_ad[0][s] + 65536;
         }
     }
 
-    f32x16 acc[MT][NT];
+    f32x4 acc[MA][NB];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < MA; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int nk = (int)(K / kBK);
-    bf16x8 af[2][MT], bfr[2][NT];
+    bf16x8 af[MA], bfr[2][NB];
 
-    // load n (0..LPS-1) of K-step kt into LDS buffer `buf`
-    // LDS byte addresses of this wave's first load slot in the A and B regions (scalar)
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
-    auto gll = [&](int n, int kt, int buf) {
-        // scalar base (advances with the K-step) + fixed per-lane 32-bit offset: no vector address
-        // arithmetic; M0 carries the LDS destination of the wave's 1 KB slot
-        const char *abase = a_tile + (int64_t)kt * (kBK * 2);
-        const char *bbase = b_tile + (int64_t)kt * (kBK * 2);
-        if (n < A_I) {
-            const uint32_t dst = a_slot + buf * A_BUF_BYTES + n * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
-                         : "memory");
-        } else {
-            const int m = n - A_I;
-            const uint32_t dst = b_slot + buf * B_BUF_BYTES + m * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
-                         : "memory");
-        }
-    };
-    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the
-    // LDS reads of sub-step RKS of buffer RBUF into the other fragment set, and with GCNT global loads
-    // (numbers GFIRST..) of K-step gkt into buffer GBUF.
-    auto phase = [&](auto cur_c, auto rbuf_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gbuf_c, int gkt) {
-        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-        constexpr int RBUF = decltype(rbuf_c)::value, RKS = decltype(rks_c)::value;
-        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
-        constexpr int GBUF = decltype(gbuf_c)::value;
-        static_for<MFMAS>([&](auto tt) {
-            constexpr int t = decltype(tt)::value;
-            constexpr int i = t / NT, j = t % NT;
-            // reads are ordered A0, B0..B(NT-1), A1, A2, ... : the order in which the next phase needs them
-            if constexpr (t < READS) {
-                if constexpr (t == 0) {
-                    af[NXT][0] = *reinterpret_cast<const bf16x8 *>(a_rd[RKS] + RBUF * A_BUF_BYTES);
-                } else if constexpr (t <= NT) {
-                    bfr[NXT][t - 1] = *reinterpret_cast<const bf16x8 *>(b_rd[RKS] + RBUF * B_BUF_BYTES + (t - 1) * 4096);
-                } else {
-                    af[NXT][t - NT] = *reinterpret_cast<const bf16x8 *>(a_rd[RKS] + RBUF * A_BUF_BYTES + (t - NT) * 4096);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (GCNT > 0) {
-                // spread the global loads evenly over the MFMAs of the phase
-                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
-                if constexpr (after > before) {
-                    gll(GFIRST + before, gkt, GBUF);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        });
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    using I3 = std::integral_constant<int, 3>;
-    using IG1 = std::integral_constant<int, G1>;
-    using IG2 = std::integral_constant<int, G2>;
-
-    // K-step kt out of buffer BUF.  On entry fragment set 0 holds sub-step 0 of tile kt, and the first
-    // half of tile kt+1's loads is in flight into the other buffer.
-    auto kstep = [&](auto buf_c, int kt) {
-        constexpr int BUF = decltype(buf_c)::value;
-        using IB = std::integral_constant<int, BUF>;
-        using IO = std::integral_constant<int, BUF ^ 1>;
-        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
-        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
-        phase(I0{}, IB{}, I1{}, IG1{}, IG2{}, IO{}, nxt1);  // MFMA sub-step 0, read sub-step 1, 2nd half of loads
-        phase(I1{}, IB{}, I2{}, I0{}, I0{}, IO{}, 0);
-        phase(I0{}, IB{}, I3{}, I0{}, I0{}, IO{}, 0);
-        // tile kt+1 has landed and every wave is done reading tile kt
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        phase(I1{}, IO{}, I0{}, I0{}, IG1{}, IB{}, nxt2);   // MFMA sub-step 3, read sub-step 0 of tile kt+1
-    };
-
-#pragma unroll
-    for (int n = 0; n < LPS; ++n) gll(n, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    {
-        const int k1 = nk > 1 ? 1 : 0;
-#pragma unroll
-        for (int n = 0; n < G1; ++n) gll(n, k1, 1);
-    }
-    af[0][0] = *reinterpret_cast<const bf16x8 *>(a_rd[0]);
-#pragma unroll
-    for (int j = 0; j < NT; ++j) bfr[0][j] = *reinterpret_cast<const bf16x8 *>(b_rd[0] + j * 4096);
-#pragma unroll
-    for (int i = 1; i < MT; ++i) af[0][i] = *reinterpret_cast<const bf16x8 *>(a_rd[0] + i * 4096);
-
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        kstep(I0{}, kt);
-        kstep(I1{}, kt + 1);
-    }
-    if (kt < nk) kstep(I0{}, kt);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
-
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Hand-ordered kernel with NS LDS stages of K = 64 (same 128-byte rows and swizzle as above) instead of
-// two: the copies of K-step kt+NS-1 are issued during K-step kt.  For the small tiles this is what
-// matters: a 128x128 work-group multiplies a K-step in ~500-1000 cycles, a loaded HBM round trip is
-// ~2000, so with one K-step of lookahead both work-groups of a CU spend most of the time waiting
-// (measured 43 % matrix-core busy at 2.2 GHz).  Four stages of 32 KB cover the round trip; the CU then
-// holds one work-group instead of two.
-template <int BM, int BN, int WGM, int WGN, int NS>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
-{
-    constexpr int NW = WGM * WGN;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MT = WM / 32, NT = WN / 32;
-    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
-    constexpr int LPS = A_I + B_I;            // global->LDS copies per wave per K-step
-    constexpr int GQ = (LPS + 3) / 4;         // copies per phase (the last phases may get fewer)
-    constexpr int READS = MT + NT, MFMAS = MT * NT;
-    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
-    constexpr int B_REGION = NS * A_BUF;
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
-    static_assert(READS <= MFMAS, "interleave assumes at most one LDS read per MFMA");
-    static_assert(NS >= 3 && NS <= 5, "ring depth");
-    static_assert(NS * A_BUF + 3 * 4096 < 2 * 65536 && NS * B_BUF + 3 * 4096 < 2 * 65536, "two base registers");
-    static_assert((NS - 2) * LPS < 64, "the wait count is a 6-bit immediate");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-
-    int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    const int lrow = lane >> 3, lch = lane & 7;
-    uint32_t a_voff[A_I], b_voff[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t r = row;
-        if (m0 + r > M - 1) r = M - 1 - m0;
-        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
-    }
-#pragma unroll
-    for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t r = row;
-        if (n0 + r > N - 1) r = N - 1 - n0;
-        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
-    }
-    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
-    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
-
-    // LDS read addresses: per K sub-step a base for byte offsets below 64 KB and one for those above
-    const int khalf = lane >> 5;
-    unsigned char *a_rd[2][4], *b_rd[2][4];
-    {
-        const int arow = wm * WM + (lane & 31), brow = wn * WN + (lane & 31);
-        const int asw = (arow & 7) ^ ((arow >> 3) & 1), bsw = (brow & 7) ^ ((brow >> 3) & 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            a_rd[0][ks] = smem_raw + arow * 128 + (((ks * 2 + khalf) ^ asw) << 4);
-            b_rd[0][ks] = smem_raw + B_REGION + brow * 128 + (((ks * 2 + khalf) ^ bsw) << 4);
-            a_rd[1][ks] = a_rd[0][ks] + 65536;
-            b_rd[1][ks] = b_rd[0][ks] + 65536;
-        }
-    }
-    auto rd_a = [&](auto slot_c, auto ks_c, auto i_c) {
-        constexpr int off = decltype(slot_c)::value * A_BUF + decltype(i_c)::value * 4096;
-        constexpr int KS = decltype(ks_c)::value;
-        if constexpr (off < 65536)
-            return *reinterpret_cast<const bf16x8 *>(a_rd[0][KS] + off);
-        else
-            return *reinterpret_cast<const bf16x8 *>(a_rd[1][KS] + (off - 65536));
-    };
-    auto rd_b = [&](auto slot_c, auto ks_c, auto j_c) {
-        constexpr int off = decltype(slot_c)::value * B_BUF + decltype(j_c)::value * 4096;
-        constexpr int KS = decltype(ks_c)::value;
-        if constexpr (off < 65536)
-            return *reinterpret_cast<const bf16x8 *>(b_rd[0][KS] + off);
-        else
-            return *reinterpret_cast<const bf16x8 *>(b_rd[1][KS] + (off - 65536));
-    };
-
-    f32x16 acc[MT][NT];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    const int nk = (int)(K / kBK);
-    bf16x8 af[2][MT], bfr[2][NT];
-
+    // copy n (0..LPS-1) of K-step kt into ring slot `slot`: scalar base (advances with the K-step) + fixed
+    // per-lane 32-bit offset; M0 carries the LDS destination of the wave's 1 KB piece
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
     const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
     auto gll = [&](int n, int kt, int slot) {
@@ -577,59 +447,91 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
                          : "memory");
         }
     };
-    // One phase: the MFMAs of the sub-step in fragment set CUR, interleaved with the reads of sub-step RKS
-    // of slot RSLOT into the other set and with copies GFIRST .. GFIRST+GCNT-1 of K-step gkt into slot GSLOT.
-    auto phase = [&](auto cur_c, auto rslot_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gslot_c, int gkt) {
-        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
-        constexpr int GSLOT = decltype(gslot_c)::value;
-        static_for<MFMAS>([&](auto tt) {
-            constexpr int t = decltype(tt)::value;
-            constexpr int i = t / NT, j = t % NT;
-            if constexpr (t < READS) {
-                if constexpr (t == 0)
-                    af[NXT][0] = rd_a(rslot_c, rks_c, std::integral_constant<int, 0>{});
-                else if constexpr (t <= NT)
-                    bfr[NXT][t - 1] = rd_b(rslot_c, rks_c, std::integral_constant<int, t - 1>{});
-                else
-                    af[NXT][t - NT] = rd_a(rslot_c, rks_c, std::integral_constant<int, t - NT>{});
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+    auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
+        constexpr int i = decltype(i_c)::value, s = decltype(s_c)::value;
+        constexpr int off = decltype(slot_c)::value * A_BUF + i * 2048;
+        af[i] = lds_read16<off % 65536>(a_ad[off / 65536][s]);
+    };
+    auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
+        constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
+        constexpr int off = decltype(slot_c)::value * B_BUF + j * 2048;
+        bfr[s][j] = lds_read16<off % 65536>(b_ad[off / 65536][s]);
+    };
+    // One group: the NB MFMAs of A block G of sub-step S, preceded by the reads that keep the operands AHEAD
+    // groups in front - A block G+AHEAD of this sub-step, or, in the second half of the sub-step, the first
+    // A blocks and the B blocks of the next sub-step RS of slot RSLOT - and interleaved with copies
+    // CP0 .. CP0+CPN-1 of K-step gkt into slot GSLOT.
+    auto group = [&](auto s_c, auto g_c, auto slot_c, auto rs_c, auto rslot_c, auto cp0_c, auto cpn_c, auto gslot_c,
+                     int gkt) {
+        constexpr int S = decltype(s_c)::value, G = decltype(g_c)::value;
+        constexpr int CP0 = decltype(cp0_c)::value, CPN = decltype(cpn_c)::value, GSLOT = decltype(gslot_c)::value;
+        if constexpr (G < AHEAD) {
+            rd_a(std::integral_constant<int, G + AHEAD>{}, s_c, slot_c);
+        } else if constexpr (G == AHEAD) {
+            rd_a(std::integral_constant<int, 0>{}, rs_c, rslot_c);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (GCNT > 0) {
-                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
-                if constexpr (after > before) {
-                    gll(GFIRST + before, gkt, GSLOT);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+            static_for<NBH>([&](auto jj) {
+                rd_b(jj, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else if constexpr (G == AHEAD + 1) {
+            static_for<NBH>([&](auto jj) {
+                rd_b(std::integral_constant<int, NBH + decltype(jj)::value>{}, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            rd_a(std::integral_constant<int, 1>{}, rs_c, rslot_c);
+        } else {
+            rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
+        }
+        // Reads younger than the last one this group needs (A block G; for G = 0 also the B blocks).  In issue
+        // order a sub-step reads A[AHEAD..MA-1] one per group, then {A'0, B'[0..NBH-1]}, {B'[NBH..NB-1], A'1},
+        // A'2, ..., A'[AHEAD-1] of the next sub-step.
+        constexpr int YOUNGER = G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + NBH : AHEAD + NB);
+        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER));
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NB>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            acc[G][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[G], bfr[S][j], acc[G][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (j < CPN) {
+                gll(CP0 + j, gkt, GSLOT);
+                __builtin_amdgcn_sched_barrier(0);
             }
         });
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    using I3 = std::integral_constant<int, 3>;
-    constexpr int C0 = GQ < LPS ? GQ : LPS;                          // copies in phase 0
-    constexpr int C1 = (2 * GQ < LPS ? 2 * GQ : LPS) - C0;           // phase 1
-    constexpr int C2 = (3 * GQ < LPS ? 3 * GQ : LPS) - C0 - C1;      // phase 2
-    constexpr int C3 = LPS - C0 - C1 - C2;                           // phase 3 (after the barrier)
 
-    // K-step kt out of ring slot SLOT.  On entry fragment set 0 holds sub-step 0 of the tile and K-steps up
-    // to kt+NS-2 have been requested; this K-step requests kt+NS-1 into the slot the previous one left.
+    // K-step kt out of ring slot SLOT.  On entry A blocks 0..AHEAD-1 and the B blocks of sub-step 0 are in
+    // registers, tiles up to kt+NS-2 and the first half of tile kt+NS-1 have been requested.
     auto kstep = [&](auto slot_c, int kt) {
         constexpr int SLOT = decltype(slot_c)::value;
         using IS = std::integral_constant<int, SLOT>;
         using IN = std::integral_constant<int, (SLOT + 1) % NS>;
         using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;
-        const int far = kt + NS - 1 < nk ? kt + NS - 1 : nk - 1;  // clamped: a surplus reload is never read
-        phase(I0{}, IS{}, I1{}, I0{}, std::integral_constant<int, C0>{}, IF{}, far);
-        phase(I1{}, IS{}, I2{}, std::integral_constant<int, C0>{}, std::integral_constant<int, C1>{}, IF{}, far);
-        phase(I0{}, IS{}, I3{}, std::integral_constant<int, C0 + C1>{}, std::integral_constant<int, C2>{}, IF{}, far);
-        // K-step kt+1 has landed: NS-3 whole K-steps and this K-step's first three batches may stay in flight
-        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 3) * LPS + C0 + C1 + C2) : "memory");
-        __syncthreads();
-        phase(I1{}, IN{}, I0{}, std::integral_constant<int, C0 + C1 + C2>{}, std::integral_constant<int, C3>{}, IF{}, far);
+        const int far1 = kt + NS - 1 < nk ? kt + NS - 1 : nk - 1;  // clamped: a surplus reload is never read
+        const int far2 = kt + NS < nk ? kt + NS : nk - 1;
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            // the second half of tile kt+NS-1's copies, spread over the first AHEAD groups
+            constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
+            group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
+                  std::integral_constant<int, after - before>{}, IF{}, far1);
+        });
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            if constexpr (G == AHEAD) {
+                // every read of this slot has been issued; tile kt+1 must have landed, (NS-2) K-steps of
+                // copies may stay in flight
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((NS - 2) * LPS) : "memory");
+                __builtin_amdgcn_s_barrier();
+            }
+            // the first half of tile kt+NS's copies into the slot the barrier freed, spread over the groups after it
+            constexpr int R = MA - AHEAD, Q = G - AHEAD;
+            constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
+            group(I1{}, gg, IS{}, I0{}, IN{}, std::integral_constant<int, before>{},
+                  std::integral_constant<int, after - before>{}, IS{}, far2);
+        });
     };
 
     static_for<NS - 1>([&](auto ss) {
@@ -640,22 +542,24 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_d_kernel(
     });
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    af[0][0] = rd_a(I0{}, I0{}, I0{});
-    static_for<NT>([&](auto jj) { bfr[0][decltype(jj)::value] = rd_b(I0{}, I0{}, jj); });
-    static_for<MT - 1>([&](auto ii) {
-        constexpr int i = decltype(ii)::value + 1;
-        af[0][i] = rd_a(I0{}, I0{}, std::integral_constant<int, i>{});
-    });
+    {
+        const int kf = NS - 1 < nk ? NS - 1 : nk - 1;
+#pragma unroll
+        for (int n = 0; n < H1; ++n) gll(n, kf, NS - 1);
+    }
+    static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
+    static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     for (int kt = 0; kt < nk; kt += NS)
         static_for<NS>([&](auto ii) {
             constexpr int I = decltype(ii)::value;
             if (kt + I < nk) kstep(ii, kt + I);
         });
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
 
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -863,25 +767,14 @@ static hipError_t launch_tiles(Kernel kern, std::once_flag &once, hipError_t &at
     return hipGetLastError();
 }
 
-// two LDS stages
-template <int BM, int BN, int WGM, int WGN>
-static hipError_t launch_two_stage(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B,
-                                   int64_t ldb, void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    return launch_tiles(gemm_bf16_nt_h_kernel<BM, BN, WGM, WGN>, once, attr_err, BM, BN, WGM * WGN * 64,
-                        (size_t)2 * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
-}
-
-// a ring of NS LDS stages
+// the NT kernel with a ring of NS LDS slots
 template <int BM, int BN, int WGM, int WGN, int NS>
 static hipError_t launch_ring(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
                               void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    return launch_tiles(gemm_bf16_nt_d_kernel<BM, BN, WGM, WGN, NS>, once, attr_err, BM, BN, WGM * WGN * 64,
+    return launch_tiles(gemm_bf16_nt_kernel<BM, BN, WGM, WGN, NS>, once, attr_err, BM, BN, WGM * WGN * 64,
                         (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
 }
 
@@ -934,8 +827,8 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
         }
     }
     switch (tile) {
-    case GEMM_TILE_256x256: return launch_two_stage<256, 256, 2, 4>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case GEMM_TILE_128x128: return launch_two_stage<128, 128, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_256x256: return launch_ring<256, 256, 2, 4, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_128x128: return launch_ring<128, 128, 2, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case GEMM_TILE_256x128: return launch_ring<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     case GEMM_TILE_128x256: return launch_ring<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
