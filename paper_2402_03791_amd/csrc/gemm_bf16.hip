@@ -565,26 +565,27 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
 // ---------------------------------------------------------------------------------------------
 // K-major kernel: C[M,N] = A^T . B with A stored [K, M] (M contiguous) and B stored [K, N] - the weight-gradient
 // product dW = dY^T . X read straight from the token-major activations, no transposed copies in memory.  Same
-// skeleton as the two-stage kernel (256x256 tile, 8 waves of 128x64, two LDS buffers of K = 64, copies global ->
-// LDS directly, K loop rotated across the barrier, pinned order); what differs is the way through LDS:
+// skeleton and schedule as the NT kernel with two slots (256x256 tile, 8 waves of 128x64, 16x16x32 MFMAs, reads
+// waited for by count); what differs is the way through LDS:
 //   * a tile is [64 k][256 m] with 512-byte rows; a copy instruction moves two k-rows (1 KB);
-//   * the MFMA operand (one m, eight consecutive k per lane) is gathered down the rows with the transposing
-//     load ds_read_b64_tr_b16, two per operand (four k each): within 16 lanes, lanes 4j+q point at row j,
+//   * an MFMA operand block (one m, eight consecutive k per lane) is gathered down the rows with the transposing
+//     load ds_read_b64_tr_b16, two per block (four k each): within 16 lanes, lanes 4j+q point at row j,
 //     8-byte piece q, and lane i receives element i%4 of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4,
-//     i.e. column i of four consecutive rows;
-//   * the 16-byte chunk c of row k sits at chunk position c ^ (4 * (k % 4)): the four rows of a transposing
-//     load then fall into four different 64-byte bank groups, and the two k-halves of the wave take the two
-//     passes a 512-byte access needs anyway - no bank conflicts.
+//     i.e. column i of four consecutive rows.  The 16 lanes l/16 = g take k-group g;
+//   * the 16-byte chunk c of row k sits at chunk position c ^ (4 * (k % 4)) ^ (2 * (k / 8 % 2)): a 512-byte
+//     access is served in two passes (lanes 0-31, lanes 32-63), a pass holds two k-groups of four rows each, and
+//     the swizzle sends those eight 32-byte pieces to eight different bank groups - no bank conflicts.
 // Needs M and N in multiples of 256 and K in multiples of 64 (the dispatcher falls back to transposed copies
 // and the NT kernel otherwise).
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
-__device__ __forceinline__ bf16x8 rd_tr8(const unsigned char *p)
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t addr)
 {
-    // rows k .. k+3 at p, rows k+4 .. k+7 four rows (2048 bytes) further
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 2048));
+    // rows k .. k+3 at addr, rows k+4 .. k+7 four rows (2048 bytes) further
+    s16x4_t lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + 2048));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -593,14 +594,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
                                                            void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m,
                                                            int tiles_n)
 {
-    constexpr int BM = 256, BN = 256, WGN = 4, NW = 8;
-    constexpr int WM = 128, WN = 64, MT = 4, NT = 2;
+    constexpr int BM = 256, BN = 256, WGN = 4;
+    constexpr int WM = 128, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
     constexpr int A_I = 4, B_I = 4;            // copies (of two k-rows each) per wave per K-step and operand
-    constexpr int LPS = A_I + B_I;
-    constexpr int G1 = LPS / 2, G2 = LPS - G1;
-    constexpr int FRAGS = MT + NT, MFMAS = MT * NT;
-    constexpr int A_BUF_BYTES = BM * kBK * 2, B_BUF_BYTES = BN * kBK * 2;
-    constexpr int B_REGION = 2 * A_BUF_BYTES;
+    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;
+    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
+    constexpr int B_REGION = 2 * A_BUF;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
@@ -619,7 +618,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
 #pragma unroll
     for (int j = 0; j < A_I; ++j) {
         const int row = 2 * (wave * A_I + j) + (lane >> 5);
-        const int chunk = (lane & 31) ^ (4 * (row & 3));
+        const int chunk = (lane & 31) ^ (4 * (row & 3)) ^ (2 * ((row >> 3) & 1));
         a_voff[j] = (uint32_t)(((int64_t)row * lda + chunk * 8) * 2);
         b_voff[j] = (uint32_t)(((int64_t)row * ldb + chunk * 8) * 2);
     }
@@ -627,35 +626,35 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
     const char *b_tile = reinterpret_cast<const char *>(B + n0);
     const int64_t a_kstep = (int64_t)kBK * lda * 2, b_kstep = (int64_t)kBK * ldb * 2;
 
-    // ---- LDS side: per-lane byte address of the first transposing load of every operand block at K sub-step 0
-    unsigned char *a_rd[MT], *b_rd[NT];
+    // ---- LDS side: per-lane byte address of the first transposing load of every operand block at sub-step 0 of
+    // slot 0: row 8*g + j of the tile, the 32-byte piece of 16-column block b at piece position b ^ (2*j) ^ (g%2)
+    uint32_t a_ad[MA], b_ad[NB];
     {
-        const int khalf = lane >> 5, g = (lane >> 4) & 1, j = (lane & 15) >> 2, q = lane & 3;
-        const int low2 = 2 * g + (q >> 1);
-        const int rowoff = (8 * khalf + j) * 512 + (q & 1) * 8;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+        const int g = lane >> 4, j = (lane & 15) >> 2, q = lane & 3;
+        const int x = (2 * j) ^ (g & 1);
+        const uint32_t rowoff = (uint32_t)((8 * g + j) * 512 + 8 * q);
 #pragma unroll
-        for (int i = 0; i < MT; ++i) a_rd[i] = smem_raw + rowoff + 16 * (low2 + 4 * ((4 * wm + i) ^ j));
+        for (int i = 0; i < MA; ++i) a_ad[i] = lds0 + rowoff + 32 * ((MA * wm + i) ^ x);
 #pragma unroll
-        for (int i = 0; i < NT; ++i) b_rd[i] = smem_raw + B_REGION + rowoff + 16 * (low2 + 4 * ((2 * wn + i) ^ j));
+        for (int i = 0; i < NB; ++i) b_ad[i] = lds0 + B_REGION + rowoff + 32 * ((NB * wn + i) ^ x);
     }
 
-    f32x16 acc[MT][NT];
+    f32x4 acc[MA][NB];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < MA; ++i)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int nk = (int)(K / kBK);
-    bf16x8 af[2][MT], bfr[2][NT];
+    bf16x8 af[MA], bfr[2][NB];
 
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
     const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
-    auto gll = [&](int n, int kt, int buf) {
+    auto gll = [&](int n, int kt, int slot) {
         if (n < A_I) {
             const char *abase = a_tile + (int64_t)kt * a_kstep;
-            const uint32_t dst = a_slot + buf * A_BUF_BYTES + n * 1024;
+            const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(dst), "v"(a_voff[n]), "s"(abase)
@@ -663,68 +662,85 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
         } else {
             const int m = n - A_I;
             const char *bbase = b_tile + (int64_t)kt * b_kstep;
-            const uint32_t dst = b_slot + buf * B_BUF_BYTES + m * 1024;
+            const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(dst), "v"(b_voff[m]), "s"(bbase)
                          : "memory");
         }
     };
-    // operand block f (0 = A0, 1..NT = B, then A1..) of K sub-step ks of buffer buf
-    auto rd_frag = [&](auto f_c, auto nxt_c, int off) {
-        constexpr int f = decltype(f_c)::value, NXT = decltype(nxt_c)::value;
-        if constexpr (f == 0)
-            af[NXT][0] = rd_tr8(a_rd[0] + off);
-        else if constexpr (f <= NT)
-            bfr[NXT][f - 1] = rd_tr8(b_rd[f - 1] + off);
-        else
-            af[NXT][f - NT] = rd_tr8(a_rd[f - NT] + off);
+    // sub-step s is rows 32 s .. 32 s + 31 of the tile (16 KB)
+    auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
+        constexpr int i = decltype(i_c)::value;
+        af[i] = lds_read_tr8<decltype(slot_c)::value * A_BUF + decltype(s_c)::value * 16384>(a_ad[i]);
     };
-    // One phase: the MFMAs of the sub-step whose operands sit in fragment set CUR, interleaved with the LDS
-    // reads of sub-step RKS of buffer RBUF into the other fragment set (one operand block = two transposing
-    // loads per MFMA), and with GCNT copies (numbers GFIRST..) of K-step gkt into buffer GBUF.
-    auto phase = [&](auto cur_c, auto rbuf_c, auto rks_c, auto gfirst_c, auto gcnt_c, auto gbuf_c, int gkt) {
-        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-        constexpr int RBUF = decltype(rbuf_c)::value, RKS = decltype(rks_c)::value;
-        constexpr int GFIRST = decltype(gfirst_c)::value, GCNT = decltype(gcnt_c)::value;
-        constexpr int GBUF = decltype(gbuf_c)::value;
-        static_for<MFMAS>([&](auto tt) {
-            constexpr int t = decltype(tt)::value;
-            constexpr int i = t / NT, j = t % NT;
-            if constexpr (t < FRAGS) {
-                rd_frag(tt, std::integral_constant<int, NXT>{}, RBUF * A_BUF_BYTES + RKS * 8192);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[CUR][i], bfr[CUR][j], acc[i][j], 0, 0, 0);
+    auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
+        constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
+        bfr[s][j] = lds_read_tr8<decltype(slot_c)::value * B_BUF + s * 16384>(b_ad[j]);
+    };
+    // One group, as in the NT kernel; an operand block is two LDS instructions here, and the wait count is a
+    // 4-bit field: where twice the number of younger blocks exceeds it, the wait covers a few blocks more.
+    auto group = [&](auto s_c, auto g_c, auto slot_c, auto rs_c, auto rslot_c, auto cp0_c, auto cpn_c, auto gslot_c,
+                     int gkt) {
+        constexpr int S = decltype(s_c)::value, G = decltype(g_c)::value;
+        constexpr int CP0 = decltype(cp0_c)::value, CPN = decltype(cpn_c)::value, GSLOT = decltype(gslot_c)::value;
+        if constexpr (G < AHEAD) {
+            rd_a(std::integral_constant<int, G + AHEAD>{}, s_c, slot_c);
+        } else if constexpr (G == AHEAD) {
+            rd_a(std::integral_constant<int, 0>{}, rs_c, rslot_c);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (GCNT > 0) {
-                constexpr int before = (t * GCNT) / MFMAS, after = ((t + 1) * GCNT) / MFMAS;
-                if constexpr (after > before) {
-                    gll(GFIRST + before, gkt, GBUF);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+            static_for<NBH>([&](auto jj) {
+                rd_b(jj, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else if constexpr (G == AHEAD + 1) {
+            static_for<NBH>([&](auto jj) {
+                rd_b(std::integral_constant<int, NBH + decltype(jj)::value>{}, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            rd_a(std::integral_constant<int, 1>{}, rs_c, rslot_c);
+        } else {
+            rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
+        }
+        constexpr int YOUNGER = 2 * (G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + NBH : AHEAD + NB));
+        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER < 15 ? YOUNGER : 15));
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NB>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            acc[G][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[G], bfr[S][j], acc[G][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (j < CPN) {
+                gll(CP0 + j, gkt, GSLOT);
+                __builtin_amdgcn_sched_barrier(0);
             }
         });
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    using I3 = std::integral_constant<int, 3>;
-    using IG1 = std::integral_constant<int, G1>;
-    using IG2 = std::integral_constant<int, G2>;
 
-    auto kstep = [&](auto buf_c, int kt) {
-        constexpr int BUF = decltype(buf_c)::value;
-        using IB = std::integral_constant<int, BUF>;
-        using IO = std::integral_constant<int, BUF ^ 1>;
-        const int nxt1 = kt + 1 < nk ? kt + 1 : nk - 1;
-        const int nxt2 = kt + 2 < nk ? kt + 2 : nk - 1;  // clamped: the surplus reload is never read
-        phase(I0{}, IB{}, I1{}, IG1{}, IG2{}, IO{}, nxt1);
-        phase(I1{}, IB{}, I2{}, I0{}, I0{}, IO{}, 0);
-        phase(I0{}, IB{}, I3{}, I0{}, I0{}, IO{}, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        phase(I1{}, IO{}, I0{}, I0{}, IG1{}, IB{}, nxt2);
+    auto kstep = [&](auto slot_c, int kt) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        using IS = std::integral_constant<int, SLOT>;
+        using IO = std::integral_constant<int, SLOT ^ 1>;
+        const int far1 = kt + 1 < nk ? kt + 1 : nk - 1;  // clamped: a surplus reload is never read
+        const int far2 = kt + 2 < nk ? kt + 2 : nk - 1;
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
+            group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
+                  std::integral_constant<int, after - before>{}, IO{}, far1);
+        });
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            if constexpr (G == AHEAD) {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+            }
+            constexpr int R = MA - AHEAD, Q = G - AHEAD;
+            constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
+            group(I1{}, gg, IS{}, I0{}, IO{}, std::integral_constant<int, before>{},
+                  std::integral_constant<int, after - before>{}, IS{}, far2);
+        });
     };
 
 #pragma unroll
@@ -734,9 +750,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
     {
         const int k1 = nk > 1 ? 1 : 0;
 #pragma unroll
-        for (int n = 0; n < G1; ++n) gll(n, k1, 1);
+        for (int n = 0; n < H1; ++n) gll(n, k1, 1);
     }
-    static_for<FRAGS>([&](auto ff) { rd_frag(ff, I0{}, 0); });
+    static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
+    static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
@@ -744,10 +762,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
         kstep(I1{}, kt + 1);
     }
     if (kt < nk) kstep(I0{}, kt);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
 
-    epilogue<MT, NT>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
 // One launch wrapper for both kernels: raises the kernel's dynamic LDS limit once per process (guarded, so
