@@ -422,7 +422,27 @@ def main():
         torch.cuda.synchronize()
         acc_standalone = (reps, a0.elapsed_time(a1), reps * 12.0 * st.N)
 
+    # the gather as a pass of its own (the cast of the whole shard plus the transposed copies this shape needs):
+    # in the timed step an Adam step with write-back has already produced the working copy
+    mat_standalone = None
+    if V == 1:
+        reps = 4
+        c0, b0 = st.counters()
+        m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        st.params_changed()
+        st.materialize_params(stream)
+        m0.record(stream)
+        for _ in range(reps):
+            st.params_changed()
+            st.materialize_params(stream)
+        m1.record(stream)
+        torch.cuda.synchronize()
+        c1, b1 = st.counters()
+        mat_standalone = (reps, m0.elapsed_time(m1), (b1 - b0) * reps / (c1 - c0))
+
     def rate(cls, scale):
+        if cls == "materialize" and mat_standalone:
+            return mat_standalone[2] / (mat_standalone[1] * 1e-3) / scale
         if cls == "accumulate" and acc_standalone:
             return acc_standalone[2] / (acc_standalone[1] * 1e-3) / scale
         n, ms, work, _ = prof[cls]
@@ -501,6 +521,12 @@ def main():
         phases["accumulate"]["standalone"] = {"launches": acc_standalone[0], "ms": round(acc_standalone[1], 3),
                                               "note": "not part of the timed step: timed alone on the stage's G and "
                                                       "staging buffers"}
+    if mat_standalone:
+        phases["materialize"]["standalone"] = {"launches": mat_standalone[0], "ms": round(mat_standalone[1], 3),
+                                               "bytes_per_launch": int(mat_standalone[2] / mat_standalone[0]),
+                                               "note": "a gather that casts the whole shard from P, timed alone; in the "
+                                                       "timed step the Adam write-back leaves it nothing to do unless "
+                                                       "the shape needs transposed copies"}
     hbm_pass = {
         "adam_GBps": phases["adam"]["GB/s"], "accumulate_GBps": phases["accumulate"]["GB/s"],
         "combined_GBps": round((prof["adam"][2] + acc_bytes) / max((prof["adam"][1] + acc_ms) * 1e-3, 1e-12) / 1e9, 1),

@@ -107,7 +107,8 @@ typedef struct {
     int32_t write_back;    /* 1: the updated parameters are also written into the stage's working copy (the bf16
                               round-to-nearest-even cast, or the float copy), so that the next
                               stage_materialize_params need not read P again for it (when the call, or the
-                              ranges, covered the whole shard it only refreshes the transposed copy) */
+                              ranges, covered the whole shard it only refreshes the transposed copies that
+                              matrices of unusual shape need, see zpp_stage_workspace_bytes) */
 } zpp_adam;
 
 /* ---- handle, sizes, layout (host only; no device is touched) -------------------------------- */
@@ -121,7 +122,9 @@ void zpp_stage_destroy(zpp_stage *stage);
 uint64_t zpp_stage_param_count(const zpp_stage *stage);
 
 /* Bytes of caller-owned device workspace the stage needs: the materialised working copy of the
- * stage (one gathered stage, the L*M_w/(P*V) term of the memory formula in Section 4.2), the
+ * stage (one gathered stage, the L*M_w/(P*V) term of the memory formula in Section 4.2; in bf16 mode a
+ * matrix [out, in] whose `in` is not a multiple of 256 or whose `out` is not a multiple of 64 also gets a
+ * transposed copy there, which the input-gradient product of such a shape reads), the
  * fp32 staging buffer for one micro-batch's weight gradients, the activation stash of one
  * scheduling unit (the min(B,U)*L*M_a/P term; linear in unit_mbs; with split_backward it also
  * holds the output gradients kept between the two backward tasks) and per-call temporaries. */
@@ -289,7 +292,7 @@ zpp_status zpp_stage_end_unit(zpp_stage *stage);
 void zpp_stage_counters(const zpp_stage *stage, uint64_t *materialize_calls, uint64_t *materialize_bytes);
 
 /* Device address and size of a named region inside the bound workspace:
- *   "W" working copy, "S" staging gradients; stash tensors of (micro_batch, block) by name, e.g.
+ *   "W" working copy, "Wt" the transposed copies (may be empty), "S" staging gradients; stash tensors of (micro_batch, block) by name, e.g.
  *   "x", "n1", "qkv", "attn", "lse", "x1", "n2", "u", "g".  elem_bytes is 2 or 4.
  * Errors: ZPP_ERR_STATE before bind, ZPP_ERR_ARG for an unknown name or index. */
 zpp_status zpp_stage_region(const zpp_stage *stage, const char *name, int32_t micro_batch, int32_t block,

@@ -35,6 +35,14 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
 zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
 
+/* The input-gradient product of Section 2.3 read from the weights as they are stored: C[M,N] = A . B with A
+ * [M, K] (K contiguous, leading dimension lda >= K) and B [K, N] (N contiguous, leading dimension ldb >= N),
+ * i.e. dX[T,in] = dY[T,out] . W[out,in] without a transposed copy of W.  bf16 operands, fp32 accumulation; C
+ * as for the products above.  N a multiple of 256, K a multiple of 64, lda and ldb multiples of 8
+ * (ZPP_ERR_UNSUPPORTED otherwise; the stage then keeps a transposed copy of that matrix). */
+zpp_status zpp_op_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
+
 /* Causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each; T = b*seq, h = nh*d):
  * attn[T, h] = softmax(Q K^T / sqrt(d) + causal mask) V per (sample, head); lse[b, nh, seq] is the
  * log-sum-exp of the scaled, masked scores.  dtype: ZPP_DTYPE_*; impl 0 = generic kernel,

@@ -20,7 +20,7 @@ EXPORTS = [
     "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
-    "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
+    "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_gemm_bf16_nn", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
     "zpp_op_flat_accumulate", "zpp_op_flat_materialize", "zpp_op_attention_bwd_noalloc",
     "zpp_op_attention_bwd_noalloc_max_rows",
     "zpp_device_create", "zpp_device_create_per_stage", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
@@ -148,6 +148,7 @@ def load_library(path: str | None = None):
     L.zpp_version.restype = ctypes.c_char_p
     L.zpp_op_gemm_bf16_nt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i32, i32, vp]
     L.zpp_op_gemm_bf16_tt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
+    L.zpp_op_gemm_bf16_nn.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
     L.zpp_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd_noalloc.argtypes = [i32, i32, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
@@ -544,6 +545,17 @@ def op_gemm_bf16_tt(A, B, C, stream=None, accumulate: bool = False):
     K, M = A.shape
     N = B.shape[1]
     _check(lib().zpp_op_gemm_bf16_tt(M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(),
+                                     C.stride(0), 2 if accumulate else int(C.dtype == torch.float32),
+                                     _stream_ptr(stream)))
+    return C
+
+
+def op_gemm_bf16_nn(A, B, C, stream=None, accumulate: bool = False):
+    """C[M,N] = A . B with A [M, K] and B [K, N] (the input-gradient product on the weights as stored)."""
+    import torch
+    M, K = A.shape
+    N = B.shape[1]
+    _check(lib().zpp_op_gemm_bf16_nn(M, N, K, A.data_ptr(), A.stride(0), B.data_ptr(), B.stride(0), C.data_ptr(),
                                      C.stride(0), 2 if accumulate else int(C.dtype == torch.float32),
                                      _stream_ptr(stream)))
     return C

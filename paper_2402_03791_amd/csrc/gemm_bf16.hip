@@ -768,6 +768,218 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
     epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
+// ---------------------------------------------------------------------------------------------
+// NN kernel: C[M,N] = A[M,K] . B[K,N], A K-contiguous as in the NT kernel, B stored [K, N] (N contiguous) as in
+// the K-major kernel - the input-gradient product dX = dY . W read from the weights as they are stored
+// ([out, in] row-major, out = K), so that no transposed copy of the weights is needed.  A side: the NT kernel's
+// (128-byte rows, 16-byte reads); B side: the K-major kernel's (512-byte rows, transposing reads), with one
+// change: both sides must hold the same eight k in a lane, the A side's 16-byte reads want k-group
+// (l/16 % 2) * 2 + l/32 there, so the B tile's swizzle separates the k-groups of a pass (now 0 and 2, or 1 and
+// 3) by bit 4 of k instead of bit 3: chunk ^ (4 * (k % 4)) ^ (2 * (k / 16 % 2)).
+// Tiles BM x 256 with BM = 256 (two slots) or 128 (ring of three), 8 waves as 2 x 4.  N a multiple of 256, K of 64.
+template <int BM, int NS>
+__global__ __launch_bounds__(512) void gemm_bf16_nn_kernel(int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A,
+                                                           int64_t lda, const bf16 *__restrict__ B, int64_t ldb,
+                                                           void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m,
+                                                           int tiles_n)
+{
+    constexpr int BN = 256, WGN = 4, NW = 8;
+    constexpr int WM = BM / 2, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
+    constexpr int A_I = BM / 8 / NW, B_I = 4;  // copies per wave per K-step: 8 rows of A, 2 k-rows of B each
+    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;
+    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
+    constexpr int B_REGION = NS * A_BUF;
+    static_assert((NS - 1) * A_BUF + MA * 2048 <= 65536, "A offsets are immediates");
+    static_assert(AHEAD + 2 * NB <= 15, "the LDS wait count is a 4-bit field");
+    static_assert((H1 + MA - AHEAD - 1) / (MA - AHEAD) <= NB && (H2 + AHEAD - 1) / AHEAD <= NB, "one copy per MFMA at most");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- global side
+    uint32_t a_voff[A_I], b_voff[B_I];
+    {
+        const int lrow = lane >> 3, lch = lane & 7;
+#pragma unroll
+        for (int j = 0; j < A_I; ++j) {
+            const int row = (wave * A_I + j) * 8 + lrow;
+            const int sw = (row & 7) ^ ((row >> 3) & 1);
+            int64_t r = row;
+            if (m0 + r > M - 1) r = M - 1 - m0;
+            a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < B_I; ++j) {
+            const int row = 2 * (wave * B_I + j) + (lane >> 5);
+            const int chunk = (lane & 31) ^ (4 * (row & 3)) ^ (2 * ((row >> 4) & 1));
+            b_voff[j] = (uint32_t)(((int64_t)row * ldb + chunk * 8) * 2);
+        }
+    }
+    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
+    const char *b_tile = reinterpret_cast<const char *>(B + n0);
+    const int64_t b_kstep = (int64_t)kBK * ldb * 2;
+
+    // ---- LDS side: lane l holds k-group kq = (l/16 % 2) * 2 + l/32 of a sub-step on both sides
+    uint32_t a_ad[2], b_ad[2][NB];
+    {
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+        const int kq = ((lane >> 4) & 1) * 2 + (lane >> 5);
+        const int r16 = lane & 15;
+        const int arow = wm * WM + r16;
+        const int asw = (arow & 7) ^ ((arow >> 3) & 1);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) a_ad[s] = lds0 + arow * 128 + (((s * 4 + kq) ^ asw) << 4);
+        const int j = (lane & 15) >> 2, q = lane & 3;
+        const int x = (2 * j) ^ (kq >> 1);
+        const uint32_t rowoff = (uint32_t)((8 * kq + j) * 512 + 8 * q);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            b_ad[0][i] = lds0 + B_REGION + rowoff + 32 * ((NB * wn + i) ^ x);
+            b_ad[1][i] = b_ad[0][i] + 65536;
+        }
+    }
+
+    f32x4 acc[MA][NB];
+#pragma unroll
+    for (int i = 0; i < MA; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int nk = (int)(K / kBK);
+    bf16x8 af[MA], bfr[2][NB];
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
+    auto gll = [&](int n, int kt, int slot) {
+        if (n < A_I) {
+            const char *abase = a_tile + (int64_t)kt * (kBK * 2);
+            const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "memory");
+        } else {
+            const int m = n - A_I;
+            const char *bbase = b_tile + (int64_t)kt * b_kstep;
+            const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "memory");
+        }
+    };
+    auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
+        constexpr int i = decltype(i_c)::value, s = decltype(s_c)::value;
+        af[i] = lds_read16<decltype(slot_c)::value * A_BUF + i * 2048>(a_ad[s]);
+    };
+    auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
+        constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
+        constexpr int off = decltype(slot_c)::value * B_BUF + s * 16384;
+        bfr[s][j] = lds_read_tr8<off % 65536>(b_ad[off / 65536][j]);
+    };
+    // One group, as in the NT kernel; a B block is two LDS instructions.
+    auto group = [&](auto s_c, auto g_c, auto slot_c, auto rs_c, auto rslot_c, auto cp0_c, auto cpn_c, auto gslot_c,
+                     int gkt) {
+        constexpr int S = decltype(s_c)::value, G = decltype(g_c)::value;
+        constexpr int CP0 = decltype(cp0_c)::value, CPN = decltype(cpn_c)::value, GSLOT = decltype(gslot_c)::value;
+        if constexpr (G < AHEAD) {
+            rd_a(std::integral_constant<int, G + AHEAD>{}, s_c, slot_c);
+        } else if constexpr (G == AHEAD) {
+            rd_a(std::integral_constant<int, 0>{}, rs_c, rslot_c);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<NBH>([&](auto jj) {
+                rd_b(jj, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else if constexpr (G == AHEAD + 1) {
+            static_for<NBH>([&](auto jj) {
+                rd_b(std::integral_constant<int, NBH + decltype(jj)::value>{}, rs_c, rslot_c);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            rd_a(std::integral_constant<int, 1>{}, rs_c, rslot_c);
+        } else {
+            rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
+        }
+        // LDS instructions younger than the last one this group needs: the A blocks in between are one each,
+        // the B blocks two
+        constexpr int YOUNGER = G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + 2 * NBH : AHEAD + 2 * NB);
+        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER));
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NB>([&](auto jj) {
+            constexpr int j = decltype(jj)::value;
+            acc[G][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[G], bfr[S][j], acc[G][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (j < CPN) {
+                gll(CP0 + j, gkt, GSLOT);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+
+    auto kstep = [&](auto slot_c, int kt) {
+        constexpr int SLOT = decltype(slot_c)::value;
+        using IS = std::integral_constant<int, SLOT>;
+        using IN = std::integral_constant<int, (SLOT + 1) % NS>;
+        using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;
+        const int far1 = kt + NS - 1 < nk ? kt + NS - 1 : nk - 1;  // clamped: a surplus reload is never read
+        const int far2 = kt + NS < nk ? kt + NS : nk - 1;
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
+            group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
+                  std::integral_constant<int, after - before>{}, IF{}, far1);
+        });
+        static_for<MA>([&](auto gg) {
+            constexpr int G = decltype(gg)::value;
+            if constexpr (G == AHEAD) {
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((NS - 2) * LPS) : "memory");
+                __builtin_amdgcn_s_barrier();
+            }
+            constexpr int R = MA - AHEAD, Q = G - AHEAD;
+            constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
+            group(I1{}, gg, IS{}, I0{}, IN{}, std::integral_constant<int, before>{},
+                  std::integral_constant<int, after - before>{}, IS{}, far2);
+        });
+    };
+
+    static_for<NS - 1>([&](auto ss) {
+        constexpr int S = decltype(ss)::value;
+        const int kt = S < nk ? S : nk - 1;
+#pragma unroll
+        for (int n = 0; n < LPS; ++n) gll(n, kt, S);
+    });
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    {
+        const int kf = NS - 1 < nk ? NS - 1 : nk - 1;
+#pragma unroll
+        for (int n = 0; n < H1; ++n) gll(n, kf, NS - 1);
+    }
+    static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
+    static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+
+    for (int kt = 0; kt < nk; kt += NS)
+        static_for<NS>([&](auto ii) {
+            constexpr int I = decltype(ii)::value;
+            if (kt + I < nk) kstep(ii, kt + I);
+        });
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+}
+
 // One launch wrapper for both kernels: raises the kernel's dynamic LDS limit once per process (guarded, so
 // that host threads driving different stages may launch concurrently) and starts one work-group per tile.
 template <class Kernel>
@@ -812,6 +1024,35 @@ hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     static hipError_t attr_err = hipSuccess;
     return launch_tiles(gemm_bf16_tt_kernel, once, attr_err, 256, 256, 512, (size_t)2 * 512 * kBK * sizeof(bf16), M, N, K,
                         (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
+}
+
+bool gemm_bf16_nn_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb)
+{
+    return M > 0 && N > 0 && K > 0 && N % 256 == 0 && K % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+           64 * ldb * 2 < (int64_t)1 << 31 && 256 * lda * 2 < (int64_t)1 << 31;
+}
+
+template <int BM, int NS>
+static hipError_t launch_nn(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
+                            void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+{
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    return launch_tiles(gemm_bf16_nn_kernel<BM, NS>, once, attr_err, BM, 256, 512, (size_t)NS * (BM + 256) * kBK * sizeof(bf16),
+                        M, N, K, A, lda, B, ldb, C, ldc, e, s);
+}
+
+hipError_t launch_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                               void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
+{
+    if (!gemm_bf16_nn_supported(M, N, K, lda, ldb)) return hipErrorInvalidValue;
+    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
+              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
+    // 256x256 tiles when they come in whole rounds of one per CU (or in many), else 128x256 with the deeper ring
+    const int64_t t256 = ((M + 255) / 256) * (N / 256);
+    if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
+        return launch_nn<256, 2>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
+    return launch_nn<128, 3>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
 }
 
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)

@@ -148,6 +148,12 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
 bool gemm_bf16_tt_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb);
 hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
+// The same product with A K-contiguous ([M, K], row stride lda) and B stored [K, N] (row stride ldb): the
+// input-gradient product read from the weights as stored.  Only for shapes gemm_bf16_nn_supported accepts
+// (N a multiple of 256, K of 64).
+bool gemm_bf16_nn_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb);
+hipError_t launch_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
 
 // ---- causal attention over packed qkv[T, 3h] (Q | K | V, head-major inside each) ----

@@ -199,6 +199,7 @@ struct zpp_stage {
         return layout[index.at("blk" + std::to_string(blk) + "." + nm)].offset;
     }
     void *Wp(int blk, const char *nm) const { return ws + rW.off + off(blk, nm) * esz; }
+    bool has_wt(int blk, const char *nm) const { return wt.count("blk" + std::to_string(blk) + "." + nm) != 0; }
     void *Wtp(int blk, const char *nm) const
     {
         return ws + rWt.off + wt.at("blk" + std::to_string(blk) + "." + nm).dst_off * 2;
@@ -262,14 +263,18 @@ void build_layout(zpp_stage *s)
         }
     }
     s->N = off;
-    // Transposed working copy (bf16 mode): one [cols, rows] slot per matrix.  wgate and wup are
-    // adjacent and are used as one [2f, h] matrix, so they share one [h, 2f] slot.
+    // Transposed working copy (bf16 mode): one [cols, rows] slot for every matrix whose input-gradient product
+    // cannot read it as stored (the NN kernel takes W[out, in] in place when `in` is a multiple of 256 and `out`
+    // of 64; the stages that are timed keep no transposed copy at all).  wgate and wup are adjacent and are used
+    // as one [2f, h] matrix, so they share one [h, 2f] slot.
     uint64_t woff = 0;
     for (auto &t : s->layout) {
         if (t.rows <= 1) continue;
         const std::string leaf = t.name.substr(t.name.find('.') + 1);
         if (leaf == "mlp.wup") continue;
         const uint64_t rows = leaf == "mlp.wgate" ? 2 * t.rows : t.rows;
+        if (t.offset % 8 == 0 && gemm_bf16_nn_supported(1, (int64_t)t.cols, (int64_t)rows, (int64_t)rows, (int64_t)t.cols))
+            continue;
         s->wt[t.name] = {t.offset, rows, t.cols, woff};
         woff += rows * t.cols;
     }
@@ -280,7 +285,7 @@ constexpr uint64_t kRedPerBlock = 6;  // four bias gradients and two norm-gain g
 
 // The workspace has three parts, each planned from its own base offset so that several stages on one
 // device can share what only one of them uses at a time:
-//   working copy  W, its transposed copy, the rotary table        (one gathered stage, Section 4.2)
+//   working copy  W, transposed copies where needed, the rotary table   (one gathered stage, Section 4.2)
 //   scratch       the fp32 staging gradients and per-call temporaries
 //   stash         the activations of the unit's micro-batches     (private to a stage)
 // Returns the sizes of the three parts.
@@ -430,8 +435,12 @@ hipError_t linear_dx(zpp_stage *s, const void *dy, int blk, const char *w, int64
 {
     ProfScope prof(ZPP_PROF_GEMM, 2.0 * s->Tc * in * out, st,
                    (double)s->esz * ((double)s->Tc * in + (double)in * out + (double)s->Tc * out));
-    if (s->dt == DT_BF16)  // uses the transposed working copy W^T[in,out] so both operands are K-contiguous
+    if (s->dt == DT_BF16) {
+        // W[out, in] as stored is the K-major operand of the NN kernel; matrices of other shapes have a
+        // transposed copy W^T[in, out], with which both operands are K-contiguous
+        if (!s->has_wt(blk, w)) return launch_gemm_bf16_nn(s->Tc, in, out, dy, out, s->Wp(blk, w), in, dx, in, epi, st);
         return launch_gemm_bf16_nt(s->Tc, in, out, dy, out, s->Wtp(blk, w), out, dx, in, epi, st);
+    }
     return launch_gemm_f32(s->Tc, in, out, (const float *)dy, out, 1, (const float *)s->Wp(blk, w), 1, in,
                            (float *)dx, in, epi, st);
 }
@@ -446,10 +455,10 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
     epi.accum_scale = s->acc_scale;
     hipError_t e;
     if (s->dt == DT_BF16) {
-        // Both operands are stored token-major.  They are transposed into scratch first so that the GEMM
-        // sees K-contiguous operands (reading them K-major in place with transposing LDS loads takes twice
-        // the LDS read instructions per MFMA and measured about 30 % slower).  The bias gradient comes out of
-        // the same pass that transposes dY.
+        // Both operands are stored token-major.  The K-major kernel reads them in place (the bias gradient is
+        // then a column-sum pass over dY); for shapes it does not take they are transposed into scratch first
+        // so that the NT kernel sees K-contiguous operands, and the bias gradient comes out of the pass that
+        // transposes dY.
         if (gemm_bf16_tt_supported(out, in, s->Tc, out, in)) {
             // K-major product: dY and X are read where they lie; the bias gradient needs its own pass over dY
             if (bias) {
@@ -1386,6 +1395,21 @@ zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     GemmEpi e;
     e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
     hipError_t err = launch_gemm_bf16_tt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
+    if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                               int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream)
+{
+    if (!A || !B || !C) return fail(ZPP_ERR_ARG, "A/B/C is NULL");
+    if (M <= 0 || N <= 0 || K <= 0 || lda < K || ldb < N || ldc < N) return fail(ZPP_ERR_ARG, "bad sizes");
+    if (!gemm_bf16_nn_supported(M, N, K, lda, ldb))
+        return fail(ZPP_ERR_UNSUPPORTED, "need N a multiple of 256, K a multiple of 64, lda/ldb multiples of 8");
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment required");
+    GemmEpi e;
+    e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
+    hipError_t err = launch_gemm_bf16_nn(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
     if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
     return ZPP_OK;
 }

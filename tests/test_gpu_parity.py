@@ -677,10 +677,13 @@ def test_backward_accumulate_state_machine():
     st.close()
 
 
-@pytest.mark.parametrize("arch,kw", [(0, {}), (1, dict(ffn=320)), (0, dict(hidden=512, n_heads=4, ffn=1024))])
+@pytest.mark.parametrize("arch,kw", [(0, {}), (1, dict(ffn=320)), (0, dict(hidden=512, n_heads=4, ffn=1024)),
+                                     (0, dict(hidden=320, n_heads=4, ffn=640)), (1, dict(hidden=192, n_heads=2, ffn=448))])
 def test_transposed_working_copy_is_the_transposed_cast(arch, kw):
-    """The gather also writes every matrix transposed (the input-gradient products read it): bit for bit the
-    transposed round-to-nearest-even cast of P, the gate and up matrices of the LLaMA block as one [h, 2f]."""
+    """The gather also writes transposed every matrix whose input-gradient product cannot read it as stored
+    (in not a multiple of 256 or out not a multiple of 64): bit for bit the transposed round-to-nearest-even
+    cast of P, the gate and up matrices of the LLaMA block as one [h, 2f].  The other matrices have no
+    transposed copy (first and third case: none at all)."""
     sh = small(arch, 1, **kw)
     layout = oracle.param_layout(sh)
     P0 = synth.make_params(sh, layout, gain_jitter=0.1)
@@ -695,6 +698,8 @@ def test_transposed_working_copy_is_the_transposed_cast(arch, kw):
             continue
         if name.endswith("mlp.wgate"):
             r *= 2
+        if c % 256 == 0 and r % 64 == 0 and off % 8 == 0:
+            continue
         expect = oracle.flat_materialize_bits(P0[off:off + r * c]).reshape(r, c).T
         assert np.array_equal(wt[pos:pos + r * c].reshape(c, r), expect), name
         pos += r * c
@@ -777,6 +782,31 @@ def test_gemm_bf16_tt_against_oracle(M, N, K):
     assert torch.equal(G, g0 + C)
     with pytest.raises(zpp.ZppError) as e:      # shapes the K-major kernel does not take are refused, not mangled
         zpp.op_gemm_bf16_tt(A[:, :128], B, C[:128])
+    assert e.value.status == -6
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (200, 512, 192), (1000, 256, 1024), (2048, 1024, 512),
+                                   (4096, 4096, 256)])
+def test_gemm_bf16_nn_against_oracle(M, N, K):
+    """dX = dY . W from the weights as stored ([out, in] = [K, N]); ragged M, strided rows, both tile shapes."""
+    print(f"gemm nn {M}x{N}x{K}", flush=True)
+    dy = synth.normal_f32(5, 80, M * K, bf16_exact=True).reshape(M, K)
+    w = synth.normal_f32(5, 81, K * N, bf16_exact=True).reshape(K, N)
+    ref = oracle.Ops("f64").linear_bwd_input(dy, w)
+    Aw = torch.zeros(M, K + 64, dtype=torch.bfloat16, device="cuda")
+    Bw = torch.zeros(K, N + 128, dtype=torch.bfloat16, device="cuda")
+    Aw[:, 64:] = to_dev(dy, torch.bfloat16)
+    Bw[:, :N] = to_dev(w, torch.bfloat16)
+    A, B = Aw[:, 64:], Bw[:, :N]
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    zpp.op_gemm_bf16_nn(A, B, C)
+    assert rel_err(to_np(C), ref) <= 1e-5
+    Cb = torch.full((M + 3, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    zpp.op_gemm_bf16_nn(A, B, Cb[:M])
+    assert rel_err(to_np(Cb[:M]), ref) <= 8e-3
+    assert bool((Cb[M:] == 7.0).all())           # rows past M are not written
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.op_gemm_bf16_nn(A, B[:, :128], C[:, :128])
     assert e.value.status == -6
 
 
