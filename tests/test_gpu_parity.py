@@ -707,6 +707,27 @@ def test_transposed_working_copy_is_the_transposed_cast(arch, kw):
     st.close()
 
 
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_gelu_far_from_zero(dtype):
+    """Activations far out on both sides (MLP pre-activations of several tens): the tanh-form GeLU and its
+    derivative, evaluated through exp2 and a reciprocal on the device, saturate to 0 / u and 0 / 1 and stay
+    finite, in the forward epilogue, the backward epilogue and the element-wise rebuild."""
+    sh = small(0, dtype, n_blocks=1, unit_mbs=1)
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout)
+    for name, off, r, c in layout:
+        if name.endswith("mlp.w1"):
+            P0[off:off + r * c] *= 60.0                      # pre-activations u of a few tens
+    xs, dys = make_inputs(sh, 1)
+    ref = run_oracle_unit(sh, P0, xs, dys, dtype="f64", keep_stage=True)
+    u = np.array(ref["stage"].stash(0, 0, "u"))
+    ref["stage"].close()
+    assert np.abs(u).max() > 20.0 and u.min() < -20.0
+    got = run_gpu_unit(sh, P0, xs, dys)
+    assert all(np.isfinite(a).all() for k in ("ys", "dxs") for a in got[k]) and np.isfinite(got["G"]).all()
+    compare_units(sh, got, ref, layout, TOL_BF16 if dtype == 1 else TOL_FP32)
+
+
 def test_materialize_counters_and_idempotence():
     sh = small(0, 1)
     layout = oracle.param_layout(sh)
