@@ -356,7 +356,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     constexpr int AHEAD = MA / 2;
     constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
     constexpr int LPS = A_I + B_I;            // global->LDS copies per wave per K-step
-    constexpr int H1 = LPS / 2, H2 = LPS - H1;  // issued after the barrier / in the first groups of the next K-step
+    constexpr int H1 = LPS, H2 = LPS - H1;      // issued after the barrier / in the first groups of the next K-step
     constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
     constexpr int B_REGION = NS * A_BUF;      // byte offset of the B slots inside LDS
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
@@ -597,7 +597,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
     constexpr int BM = 256, BN = 256, WGN = 4;
     constexpr int WM = 128, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
     constexpr int A_I = 4, B_I = 4;            // copies (of two k-rows each) per wave per K-step and operand
-    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;
+    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;  // half after the barrier, half in the next K-step
     constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
     constexpr int B_REGION = 2 * A_BUF;
 
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_nn_kernel(int64_t M, int64_t N,
     constexpr int BN = 256, WGN = 4, NW = 8;
     constexpr int WM = BM / 2, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
     constexpr int A_I = BM / 8 / NW, B_I = 4;  // copies per wave per K-step: 8 rows of A, 2 k-rows of B each
-    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;
+    constexpr int LPS = A_I + B_I, H1 = LPS, H2 = LPS - H1;
     constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
     constexpr int B_REGION = NS * A_BUF;
     static_assert((NS - 1) * A_BUF + MA * 2048 <= 65536, "A offsets are immediates");
