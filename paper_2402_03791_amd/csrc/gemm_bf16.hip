@@ -534,19 +534,21 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
         });
     };
 
+    // every slot is free at the start: request the first NS-1 K-steps and the first part of the next one at
+    // once, then wait for the first only
     static_for<NS - 1>([&](auto ss) {
         constexpr int S = decltype(ss)::value;
         const int kt = S < nk ? S : nk - 1;
 #pragma unroll
         for (int n = 0; n < LPS; ++n) gll(n, kt, S);
     });
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
     {
         const int kf = NS - 1 < nk ? NS - 1 : nk - 1;
 #pragma unroll
         for (int n = 0; n < H1; ++n) gll(n, kf, NS - 1);
     }
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * LPS + H1) : "memory");
+    __syncthreads();
     static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
     static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -743,15 +745,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N,
         });
     };
 
+    // both slots are free at the start: request the first K-step and the first half of the second at once,
+    // then wait for the first only
 #pragma unroll
     for (int n = 0; n < LPS; ++n) gll(n, 0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
     {
         const int k1 = nk > 1 ? 1 : 0;
 #pragma unroll
         for (int n = 0; n < H1; ++n) gll(n, k1, 1);
     }
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(H1) : "memory");
+    __syncthreads();
     static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
     static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -952,19 +956,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_nn_kernel(int64_t M, int64_t N,
         });
     };
 
+    // every slot is free at the start: request the first NS-1 K-steps and the first part of the next one at
+    // once, then wait for the first only
     static_for<NS - 1>([&](auto ss) {
         constexpr int S = decltype(ss)::value;
         const int kt = S < nk ? S : nk - 1;
 #pragma unroll
         for (int n = 0; n < LPS; ++n) gll(n, kt, S);
     });
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
     {
         const int kf = NS - 1 < nk ? NS - 1 : nk - 1;
 #pragma unroll
         for (int n = 0; n < H1; ++n) gll(n, kf, NS - 1);
     }
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * LPS + H1) : "memory");
+    __syncthreads();
     static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
     static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
