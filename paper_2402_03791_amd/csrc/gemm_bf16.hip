@@ -331,9 +331,10 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tile
 //     A and B agree: lanes l and l+32 are served by the LDS in the same pass, so they take neighbouring
 //     16-byte chunks (k-group (l/16 % 2) * 2 + l/32), which the row swizzle then spreads over all banks; with the
 //     natural order (l/16) every read is a two-way bank conflict.
-//   * Copies: tile kt+NS-1's second half is issued in the first groups of K-step kt, tile kt+NS's first half
-//     after the barrier of K-step kt into the slot that barrier freed; the wait before the barrier leaves
-//     (NS-2) K-steps of copies in flight.
+//   * Copies: the copies of tile kt+NS are issued after the barrier of K-step kt, spread over the groups that
+//     follow it, into the slot that barrier freed (every copy then has a whole K-step before it is waited for;
+//     H2 > 0 would put the last H2 of them into the first groups of the next K-step instead, which the K-major
+//     kernel does); the wait before the barrier leaves (NS-2) K-steps of copies in flight.
 //   * The loop body is instantiated per slot, so all LDS addresses are a per-lane base register plus an
 //     immediate, and the global addresses are a scalar base that advances per K-step plus a fixed per-lane
 //     32-bit offset: no vector address arithmetic inside the loop.
