@@ -260,12 +260,51 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, const fl
     e[1] = from_f32<T>(a * sn + b * c);
 }
 
+// The same rotation, one 16-byte vector (VN/2 pairs of one head) per thread: the vector's cos/sin values are
+// VN consecutive floats of the table.  Needs d % VN == 0 (a vector never straddles two heads).
+template <class T>
+__global__ __launch_bounds__(256) void rope_vec_kernel(T *__restrict__ qkv, const float *__restrict__ table,
+                                                       int64_t rows, int64_t seq, int64_t h, int64_t d, float sign)
+{
+    constexpr int VN = Vec16<T>::N;
+    const int64_t nvrow = 2 * h / VN;  // vectors in the Q and K parts of one row
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * nvrow) return;
+    const int64_t t = idx / nvrow, col = (idx % nvrow) * VN;
+    const int64_t i0 = (col % d) / 2, p = t % seq;
+    const float *cs = table + (p * (d / 2) + i0) * 2;
+    T *e = qkv + t * 3 * h + col;
+    const Vec16<T> v = load16(e);
+    Vec16<T> o;
+#pragma unroll
+    for (int k = 0; k < VN; k += 4) {
+        const f32x4 w = *reinterpret_cast<const f32x4 *>(cs + k);  // cos, sin of two pairs
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const float c = w[2 * q], sn = sign * w[2 * q + 1];
+            const float a = v.get(k + 2 * q), b = v.get(k + 2 * q + 1);
+            o.set(k + 2 * q, a * c - b * sn);
+            o.set(k + 2 * q + 1, a * sn + b * c);
+        }
+    }
+    store16(e, o);
+}
+
 hipError_t launch_rope(int dt, void *qkv, const float *table, int64_t T, int64_t seq, int64_t nh, int64_t d,
                        int sign, hipStream_t s)
 {
     const int64_t h = nh * d;
     const int64_t n = T * h;
     if (n == 0) return hipSuccess;
+    const int vn = dt == DT_BF16 ? 8 : 4;
+    if (d % vn == 0 && reinterpret_cast<uintptr_t>(qkv) % 16 == 0 && (3 * h) % vn == 0) {
+        const unsigned grid = (unsigned)((2 * n / vn + 255) / 256);
+        if (dt == DT_BF16)
+            rope_vec_kernel<bf16><<<grid, 256, 0, s>>>((bf16 *)qkv, table, T, seq, h, d, (float)sign);
+        else
+            rope_vec_kernel<float><<<grid, 256, 0, s>>>((float *)qkv, table, T, seq, h, d, (float)sign);
+        return hipGetLastError();
+    }
     const unsigned grid = (unsigned)((n + 255) / 256);
     if (dt == DT_BF16)
         rope_kernel<bf16><<<grid, 256, 0, s>>>((bf16 *)qkv, table, T, seq, h, d, (float)sign);

@@ -1072,6 +1072,8 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
 {
     if (M == 0 || N == 0) return hipSuccess;
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
+    // per-lane byte offsets inside a tile (up to 255 rows) are 32-bit
+    if (256 * lda * 2 >= (int64_t)1 << 32 || 256 * ldb * 2 >= (int64_t)1 << 32) return hipErrorInvalidValue;
     EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
               epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;

@@ -260,6 +260,7 @@ def small(arch, dtype, **kw):
     (0, 0, {}), (1, 0, {}), (0, 0, dict(gelu_mode=1, micro_batch=2, seq=96)),
     (0, 1, {}), (1, 1, {}), (0, 1, dict(micro_batch=2, seq=160, ffn=768, n_heads=4)),
     (1, 1, dict(micro_batch=2, seq=96, ffn=320)),
+    (1, 0, dict(hidden=192, n_heads=16, ffn=320)), (1, 1, dict(hidden=192, n_heads=16, ffn=320)),  # head dim 12
 ])
 def test_small_stage_units(arch, dtype, kw):
     sh = small(arch, dtype, **kw)
