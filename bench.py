@@ -482,7 +482,7 @@ def main():
                 "frac": round(rate(c, 1e12) / peak, 4)}
 
     roofline = {
-        "kernel": ("bf16 GEMM family (gemm_bf16_nt_kernel, gemm_bf16_nn_kernel, gemm_bf16_tt_kernel) + MFMA "
+        "kernel": ("bf16 GEMM family (gemm_bf16_kernel: NT forward, NN input-gradient, K-major weight-gradient) + MFMA "
                    "attention kernels: the GEMM/attention share of the step") if bf16 else "gemm_f32_kernel + generic attention kernels",
         "bound": "mfma" if bf16 else "alu",
         # algorithmic flops of all those launches of one step / their summed durations (HIP events on the

@@ -1,21 +1,19 @@
-// bf16 MFMA GEMM for gfx950: C[M,N] = A[M,K] . B[N,K]^T (both operands K-contiguous), fp32 accumulation in
-// v_mfma_f32_32x32x16_bf16, fused epilogues (bias, residual, GeLU, GeLU', fp32 or bf16 output, in-place
-// accumulation of fp32 output).
+// bf16 MFMA GEMM for gfx950, fp32 accumulation in v_mfma_f32_16x16x32_bf16, fused epilogues (bias, residual,
+// GeLU, GeLU', fp32 or bf16 output, in-place accumulation of fp32 output).
 //
-// Two kernels: a 256x256 / 128x128 tile kernel with two LDS stages and a 256x128 / 128x256 tile kernel with
-// a ring of three.  Both copy their operands global -> LDS directly, rotate the K loop across the barrier,
-// and have the order of every MFMA, LDS read and copy written out and pinned, with no vector address
-// arithmetic in the loop.
-// Common: a work-group computes a BM x BN tile, K advances in steps of 64; LDS rows are 128
-// bytes (64 bf16) with an XOR swizzle of the 16-byte chunk index so that the row-wise 16-byte writes
-// and the MFMA-operand 16-byte reads (32 consecutive rows, same chunk) are bank-conflict free;
-// work-group ids are remapped so that each XCD (one L2 each, ids are dealt round-robin over 8 XCDs)
-// owns a compact group of neighbouring tiles; the epilogue transposes accumulators through LDS so
-// that every global access is 16 bytes per lane.
+// One kernel template serves the three products of a linear layer (Section 2.3): each operand is read either
+// with K contiguous or K-major, as it is stored, so nothing is transposed in memory.  A work-group computes a
+// BM x BN tile (256x256 with two LDS slots of K = 64, or 128x256 / 256x128 with a ring of three, or 128x128);
+// operands are copied global -> LDS directly, the K loop is rotated across its one barrier per K-step, and the
+// order of every MFMA, LDS read and copy is written out and pinned, with no vector address arithmetic in the
+// loop.  Work-group ids are remapped so that each XCD (one L2 each, ids are dealt round-robin over 8 XCDs)
+// owns a compact group of neighbouring tiles; the epilogue transposes accumulators through LDS so that every
+// global access is 16 bytes per lane.
 #include "device_utils.h"
 #include "kernels.h"
 
 #include <mutex>
+#include <type_traits>
 #include <utility>
 
 namespace zpp {
@@ -315,26 +313,30 @@ __device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tile
 }
 
 // ---------------------------------------------------------------------------------------------
-// NT kernel.  A ring of NS LDS slots of K = 64 (NS = 2 for the 256x256 and 128x128 tiles, 3 for 256x128 and
-// 128x256), operands global -> LDS directly, the K loop rotated across its one barrier per K-step.  The matrix
-// instruction is v_mfma_f32_16x16x32_bf16: on this part the chip's power management sets the pace of a GEMM,
-// and the 16x16x32 form delivers the same flops per cycle for less power than 32x32x16 (a register-only loop
-// runs at 2.0 against 1.75 GHz), which shows as a higher clock under the same kernel.
+// The kernel.  C[M,N] = sum_k A(m,k) B(n,k), each operand stored either with K contiguous ("row-major side": A
+// [M, K], B [N, K]) or K-major (A [K, M], B [K, N]):
+//   NT  (A row-major, B row-major)  forward  y = x . W^T
+//   NN  (A row-major, B K-major)    input gradient  dX = dY . W  read from W[out, in] as stored
+//   TN  (A K-major,  B K-major)     weight gradient dW = dY^T . X read from the token-major activations
+// A ring of NS LDS slots of K = 64, operands global -> LDS directly, the K loop rotated across its one barrier
+// per K-step.  The matrix instruction is v_mfma_f32_16x16x32_bf16: on this part the chip's power management
+// sets the pace of a GEMM, and the 16x16x32 form delivers the same flops per cycle for less power than 32x32x16
+// (a register-only loop runs at 2.0 against 1.75 GHz), which shows as a higher clock under the same kernel.
 //   * A K-step is two sub-steps of 32 k.  A sub-step is MA groups; group G multiplies the 16-row block G of
 //     the wave's A rows with the NB 16-column blocks of its B rows.  A blocks live in a ring of MA registers
 //     and are read AHEAD = MA/2 groups before their group; the B blocks of the next sub-step (a second set of
 //     registers) are read in groups AHEAD and AHEAD+1 together with its first A blocks.
 //   * The LDS reads are written as asm and waited for by count (LDS reads return in order; at each group the
-//     count of younger reads is a constant of the schedule).  Left to the compiler every wait is for all
-//     outstanding reads, which exposes the full LDS latency twice per sub-step.
+//     count of younger read instructions is a constant of the schedule; where it exceeds the 4-bit field the
+//     wait covers a few blocks more).  Left to the compiler every wait is for all outstanding reads, which
+//     exposes the full LDS latency twice per sub-step.
 //   * Lane l of a 16x16x32 operand block holds row l%16 and eight consecutive k.  Which eight is free as long as
-//     A and B agree: lanes l and l+32 are served by the LDS in the same pass, so they take neighbouring
-//     16-byte chunks (k-group (l/16 % 2) * 2 + l/32), which the row swizzle then spreads over all banks; with the
-//     natural order (l/16) every read is a two-way bank conflict.
+//     A and B agree; all sides use k-group (l/16 % 2) * 2 + l/32 (see the sides below for why).
 //   * Copies: the copies of tile kt+NS are issued after the barrier of K-step kt, spread over the groups that
-//     follow it, into the slot that barrier freed (every copy then has a whole K-step before it is waited for;
-//     H2 > 0 would put the last H2 of them into the first groups of the next K-step instead, which the K-major
-//     kernel does); the wait before the barrier leaves (NS-2) K-steps of copies in flight.
+//     follow it, into the slot that barrier freed, so every copy has a whole K-step before it is waited for
+//     (SPLIT: the second half of them in the first groups of the next K-step instead; better for the long-K
+//     weight-gradient products, worse for the others); the wait before the barrier leaves (NS-2) K-steps of
+//     copies in flight.
 //   * The loop body is instantiated per slot, so all LDS addresses are a per-lane base register plus an
 //     immediate, and the global addresses are a scalar base that advances per K-step plus a fixed per-lane
 //     32-bit offset: no vector address arithmetic inside the loop.
@@ -346,8 +348,119 @@ __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
     return r;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t addr)
+{
+    // rows k .. k+3 at addr, rows k+4 .. k+7 four rows (2048 bytes) further
+    s16x4_t lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + 2048));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// k-group of lane l within a 32-k sub-step, the same on every side
+__device__ __forceinline__ int k_group(int lane) { return ((lane >> 4) & 1) * 2 + (lane >> 5); }
+
+// An operand stored with K contiguous ([rows, K]): ROWS rows of it per tile, NW waves copy them.  In LDS a
+// slot is [ROWS][64 k] with 128-byte rows, the 16-byte chunk XORed with (row & 7) ^ (row >> 3 & 1) so that the
+// row-wise 16-byte writes of a copy (8 rows x 128 bytes) and the 16-byte reads of an MFMA block (16 rows, one
+// chunk per k-group) are free of bank conflicts.  A 16-byte LDS read serves lanes l and l+32 in the same pass:
+// with k-group l/16 they would meet in the same banks (a two-way conflict on every read), with k_group() they
+// take neighbouring chunks.  Rows past `limit` are clamped to the last valid row (their products are masked
+// in the epilogue).
+template <int ROWS, int NW>
+struct RowMajorSide {
+    static constexpr int COPIES = ROWS / 8 / NW;  // per wave per K-step, 8 rows each
+    static constexpr int BUF = ROWS * kBK * 2;    // bytes per slot
+    static constexpr int READ_INSTRS = 1;         // LDS instructions per operand block
+    uint32_t voff[COPIES];
+    const char *tile;    // first byte of the tile's first K-step
+    int64_t kstep;       // bytes from one K-step to the next
+    uint32_t ad[2][2];   // [offsets above 64 KB][sub-step]: LDS byte address of this lane's chunk in block 0, slot 0
+
+    __device__ __forceinline__ void init(const bf16 *P, int64_t ld, int64_t origin, int64_t limit, int wave, int lane,
+                                         int wave_row0, uint32_t lds_region)
+    {
+        const int lrow = lane >> 3, lch = lane & 7;
+#pragma unroll
+        for (int j = 0; j < COPIES; ++j) {
+            const int row = (wave * COPIES + j) * 8 + lrow;
+            const int sw = (row & 7) ^ ((row >> 3) & 1);
+            int64_t r = row;
+            if (origin + r > limit - 1) r = limit - 1 - origin;
+            voff[j] = (uint32_t)((r * ld + ((lch ^ sw) << 3)) * 2);
+        }
+        tile = reinterpret_cast<const char *>(P + origin * ld);
+        kstep = kBK * 2;
+        const int row = wave_row0 + (lane & 15), kq = k_group(lane);
+        const int sw = (row & 7) ^ ((row >> 3) & 1);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            ad[0][s] = lds_region + row * 128 + (((s * 4 + kq) ^ sw) << 4);
+            ad[1][s] = ad[0][s] + 65536;
+        }
+    }
+    template <int BLK, int S, int SLOT>
+    __device__ __forceinline__ bf16x8 read() const
+    {
+        constexpr int off = SLOT * BUF + BLK * 2048;
+        return lds_read16<off % 65536>(ad[off / 65536][S]);
+    }
+};
+
+// An operand stored K-major ([K, rows], rows contiguous), 256 rows of it per tile.  In LDS a slot is
+// [64 k][256 rows] with 512-byte rows; a copy moves two k-rows (1 KB).  An MFMA block (one row, eight
+// consecutive k per lane) is gathered down the k-rows with the transposing read ds_read_b64_tr_b16, two per
+// block (four k each): within 16 lanes, lanes 4j+q point at k-row j, 8-byte piece q, and lane i receives
+// element i%4 of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4, i.e. column i of four consecutive k-rows.
+// The 16-byte chunk c of k-row k sits at chunk position c ^ (4 * (k % 4)) ^ (2 * (k / 16 % 2)): an 8-byte-per-lane
+// access is served in two passes (lanes 0-31, lanes 32-63), a pass holds two k-groups (0 and 2, or 1 and 3) of
+// four k-rows each, and the swizzle sends those eight 32-byte pieces to eight different bank groups.
+template <int ROWS, int NW, int NBLK>
+struct KMajorSide {
+    static_assert(ROWS == 256, "512-byte k-rows");
+    static constexpr int COPIES = kBK / 2 / NW;   // per wave per K-step, two k-rows each
+    static constexpr int BUF = ROWS * kBK * 2;
+    static constexpr int READ_INSTRS = 2;
+    uint32_t voff[COPIES];
+    const char *tile;
+    int64_t kstep;
+    uint32_t ad[2][NBLK];  // [offsets above 64 KB][block]: first transposing read of the block at sub-step 0, slot 0
+
+    __device__ __forceinline__ void init(const bf16 *P, int64_t ld, int64_t origin, int64_t, int wave, int lane,
+                                         int wave_row0, uint32_t lds_region)
+    {
+        // lane i of a copy writes bytes [16 i, 16 i + 16) of the 1 KB piece: k-row i/32, chunk position i%32
+#pragma unroll
+        for (int j = 0; j < COPIES; ++j) {
+            const int row = 2 * (wave * COPIES + j) + (lane >> 5);
+            const int chunk = (lane & 31) ^ (4 * (row & 3)) ^ (2 * ((row >> 4) & 1));
+            voff[j] = (uint32_t)(((int64_t)row * ld + chunk * 8) * 2);
+        }
+        tile = reinterpret_cast<const char *>(P + origin);
+        kstep = (int64_t)kBK * ld * 2;
+        // k-row 8 kq + j of the sub-step, the 32-byte piece of 16-row block b at piece position b ^ (2 j) ^ (kq / 2)
+        const int kq = k_group(lane), j = (lane & 15) >> 2, q = lane & 3;
+        const int x = (2 * j) ^ (kq >> 1);
+        const uint32_t rowoff = (uint32_t)((8 * kq + j) * 512 + 8 * q);
+#pragma unroll
+        for (int i = 0; i < NBLK; ++i) {
+            ad[0][i] = lds_region + rowoff + 32 * ((wave_row0 / 16 + i) ^ x);
+            ad[1][i] = ad[0][i] + 65536;
+        }
+    }
+    template <int BLK, int S, int SLOT>
+    __device__ __forceinline__ bf16x8 read() const
+    {
+        constexpr int off = SLOT * BUF + S * 16384;  // sub-step s is k-rows 32 s .. 32 s + 31
+        return lds_read_tr8<off % 65536>(ad[off / 65536][BLK]);
+    }
+};
+
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
     int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
     int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
 {
@@ -355,14 +468,15 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MA = WM / 16, NB = WN / 16, NBH = NB / 2;
     constexpr int AHEAD = MA / 2;
-    constexpr int A_I = BM / 8 / NW, B_I = BN / 8 / NW;
-    constexpr int LPS = A_I + B_I;            // global->LDS copies per wave per K-step
-    constexpr int H1 = LPS, H2 = LPS - H1;      // issued after the barrier / in the first groups of the next K-step
-    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
-    constexpr int B_REGION = NS * A_BUF;      // byte offset of the B slots inside LDS
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/waves mismatch");
-    static_assert(MA >= 4 && MA % 2 == 0 && NB % 2 == 0, "wave tile");
-    static_assert(AHEAD + NB + 1 <= 15, "the LDS wait count is a 4-bit field");
+    using ASide = typename std::conditional<A_KMAJOR, KMajorSide<BM, NW, MA>, RowMajorSide<BM, NW>>::type;
+    using BSide = typename std::conditional<B_KMAJOR, KMajorSide<BN, NW, NB>, RowMajorSide<BN, NW>>::type;
+    constexpr int A_I = ASide::COPIES, B_I = BSide::COPIES;
+    constexpr int LPS = A_I + B_I;                       // global->LDS copies per wave per K-step
+    constexpr int H1 = SPLIT ? LPS / 2 : LPS, H2 = LPS - H1;  // after the barrier / in the first groups of the next K-step
+    constexpr int A_BUF = ASide::BUF, B_BUF = BSide::BUF;
+    constexpr int B_REGION = NS * A_BUF;                 // byte offset of the B slots inside LDS
+    constexpr int IA = ASide::READ_INSTRS, IB = BSide::READ_INSTRS;
+    static_assert(A_I >= 1 && B_I >= 1 && MA >= 4 && MA % 2 == 0 && NB % 2 == 0, "tile/waves mismatch");
     static_assert((H1 + MA - AHEAD - 1) / (MA - AHEAD) <= NB && (H2 + AHEAD - 1) / AHEAD <= NB, "one copy per MFMA at most");
     static_assert(NS >= 2 && NS <= 3 && (NS - 2) * LPS < 64, "ring depth");
     static_assert(NS * A_BUF + MA * 2048 <= 2 * 65536 && NS * B_BUF + NB * 2048 <= 2 * 65536, "two base registers");
@@ -378,44 +492,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- global side: scalar tile base + per-lane byte offset (fits 32 bits: at most 256 rows)
-    const int lrow = lane >> 3, lch = lane & 7;
-    uint32_t a_voff[A_I], b_voff[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        const int row = (wave * A_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t r = row;
-        if (m0 + r > M - 1) r = M - 1 - m0;
-        a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
-    }
-#pragma unroll
-    for (int j = 0; j < B_I; ++j) {
-        const int row = (wave * B_I + j) * 8 + lrow;
-        const int sw = (row & 7) ^ ((row >> 3) & 1);
-        int64_t r = row;
-        if (n0 + r > N - 1) r = N - 1 - n0;
-        b_voff[j] = (uint32_t)((r * ldb + ((lch ^ sw) << 3)) * 2);
-    }
-    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
-    const char *b_tile = reinterpret_cast<const char *>(B + n0 * ldb);
-
-    // ---- LDS side: per-lane byte address of the operand chunk for each sub-step, one base for offsets below
-    // 64 KB and one for those above
-    uint32_t a_ad[2][2], b_ad[2][2];
-    {
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-        const int r16 = lane & 15, kq = ((lane >> 4) & 1) * 2 + (lane >> 5);
-        const int arow = wm * WM + r16, brow = wn * WN + r16;
-        const int asw = (arow & 7) ^ ((arow >> 3) & 1), bsw = (brow & 7) ^ ((brow >> 3) & 1);
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            a_ad[0][s] = lds0 + arow * 128 + (((s * 4 + kq) ^ asw) << 4);
-            b_ad[0][s] = lds0 + B_REGION + brow * 128 + (((s * 4 + kq) ^ bsw) << 4);
-            a_ad[1][s] = a_ad[0][s] + 65536;
-            b_ad[1][s] = b_ad[0][s] + 65536;
-        }
-    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
+    ASide a;
+    BSide b;
+    a.init(A, lda, m0, M, wave, lane, wm * WM, lds_base);
+    b.init(B, ldb, n0, N, wave, lane, wn * WN, lds_base + B_REGION);
 
     f32x4 acc[MA][NB];
 #pragma unroll
@@ -428,35 +509,32 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
 
     // copy n (0..LPS-1) of K-step kt into ring slot `slot`: scalar base (advances with the K-step) + fixed
     // per-lane 32-bit offset; M0 carries the LDS destination of the wave's 1 KB piece
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
     const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
     auto gll = [&](int n, int kt, int slot) {
-        const char *abase = a_tile + (int64_t)kt * (kBK * 2);
-        const char *bbase = b_tile + (int64_t)kt * (kBK * 2);
         if (n < A_I) {
+            const char *abase = a.tile + (int64_t)kt * a.kstep;
             const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
+                         : "s"(dst), "v"(a.voff[n]), "s"(abase)
                          : "memory");
         } else {
             const int m = n - A_I;
+            const char *bbase = b.tile + (int64_t)kt * b.kstep;
             const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
-                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
+                         : "s"(dst), "v"(b.voff[m]), "s"(bbase)
                          : "memory");
         }
     };
     auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
-        constexpr int i = decltype(i_c)::value, s = decltype(s_c)::value;
-        constexpr int off = decltype(slot_c)::value * A_BUF + i * 2048;
-        af[i] = lds_read16<off % 65536>(a_ad[off / 65536][s]);
+        constexpr int i = decltype(i_c)::value;
+        af[i] = a.template read<i, decltype(s_c)::value, decltype(slot_c)::value>();
     };
     auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
         constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
-        constexpr int off = decltype(slot_c)::value * B_BUF + j * 2048;
-        bfr[s][j] = lds_read16<off % 65536>(b_ad[off / 65536][s]);
+        bfr[s][j] = b.template read<j, s, decltype(slot_c)::value>();
     };
     // One group: the NB MFMAs of A block G of sub-step S, preceded by the reads that keep the operands AHEAD
     // groups in front - A block G+AHEAD of this sub-step, or, in the second half of the sub-step, the first
@@ -484,11 +562,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
         } else {
             rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
         }
-        // Reads younger than the last one this group needs (A block G; for G = 0 also the B blocks).  In issue
-        // order a sub-step reads A[AHEAD..MA-1] one per group, then {A'0, B'[0..NBH-1]}, {B'[NBH..NB-1], A'1},
-        // A'2, ..., A'[AHEAD-1] of the next sub-step.
-        constexpr int YOUNGER = G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + NBH : AHEAD + NB);
-        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER));
+        // LDS instructions younger than the last one this group needs (A block G; for G = 0 also the B blocks).
+        // In issue order a sub-step reads A[AHEAD..MA-1] one per group, then {A'0, B'[0..NBH-1]},
+        // {B'[NBH..NB-1], A'1}, A'2, ..., A'[AHEAD-1] of the next sub-step.
+        constexpr int YOUNGER = AHEAD * IA + (G < AHEAD ? 0 : (G == AHEAD ? NBH * IB : NB * IB));
+        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER < 15 ? YOUNGER : 15));
         __builtin_amdgcn_sched_barrier(0);
         static_for<NB>([&](auto jj) {
             constexpr int j = decltype(jj)::value;
@@ -504,7 +582,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     using I1 = std::integral_constant<int, 1>;
 
     // K-step kt out of ring slot SLOT.  On entry A blocks 0..AHEAD-1 and the B blocks of sub-step 0 are in
-    // registers, tiles up to kt+NS-2 and the first half of tile kt+NS-1 have been requested.
+    // registers, tiles up to kt+NS-2 and the first H1 copies of tile kt+NS-1 have been requested.
     auto kstep = [&](auto slot_c, int kt) {
         constexpr int SLOT = decltype(slot_c)::value;
         using IS = std::integral_constant<int, SLOT>;
@@ -514,7 +592,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
         const int far2 = kt + NS < nk ? kt + NS : nk - 1;
         static_for<MA>([&](auto gg) {
             constexpr int G = decltype(gg)::value;
-            // the second half of tile kt+NS-1's copies, spread over the first AHEAD groups
+            // the last H2 copies of tile kt+NS-1, spread over the first AHEAD groups
             constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
             group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
                   std::integral_constant<int, after - before>{}, IF{}, far1);
@@ -527,7 +605,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((NS - 2) * LPS) : "memory");
                 __builtin_amdgcn_s_barrier();
             }
-            // the first half of tile kt+NS's copies into the slot the barrier freed, spread over the groups after it
+            // the first H1 copies of tile kt+NS into the slot the barrier freed, spread over the groups after it
             constexpr int R = MA - AHEAD, Q = G - AHEAD;
             constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
             group(I1{}, gg, IS{}, I0{}, IN{}, std::integral_constant<int, before>{},
@@ -565,429 +643,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_nt_kernel(
     epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
-// ---------------------------------------------------------------------------------------------
-// K-major kernel: C[M,N] = A^T . B with A stored [K, M] (M contiguous) and B stored [K, N] - the weight-gradient
-// product dW = dY^T . X read straight from the token-major activations, no transposed copies in memory.  Same
-// skeleton and schedule as the NT kernel with two slots (256x256 tile, 8 waves of 128x64, 16x16x32 MFMAs, reads
-// waited for by count); what differs is the way through LDS:
-//   * a tile is [64 k][256 m] with 512-byte rows; a copy instruction moves two k-rows (1 KB);
-//   * an MFMA operand block (one m, eight consecutive k per lane) is gathered down the rows with the transposing
-//     load ds_read_b64_tr_b16, two per block (four k each): within 16 lanes, lanes 4j+q point at row j,
-//     8-byte piece q, and lane i receives element i%4 of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4,
-//     i.e. column i of four consecutive rows.  The 16 lanes l/16 = g take k-group g;
-//   * the 16-byte chunk c of row k sits at chunk position c ^ (4 * (k % 4)) ^ (2 * (k / 8 % 2)): a 512-byte
-//     access is served in two passes (lanes 0-31, lanes 32-63), a pass holds two k-groups of four rows each, and
-//     the swizzle sends those eight 32-byte pieces to eight different bank groups - no bank conflicts.
-// Needs M and N in multiples of 256 and K in multiples of 64 (the dispatcher falls back to transposed copies
-// and the NT kernel otherwise).
-typedef __attribute__((ext_vector_type(4))) short s16x4_t;
-
-template <int OFF>
-__device__ __forceinline__ bf16x8 lds_read_tr8(uint32_t addr)
-{
-    // rows k .. k+3 at addr, rows k+4 .. k+7 four rows (2048 bytes) further
-    s16x4_t lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + 2048));
-    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-}
-
-__global__ __launch_bounds__(512) void gemm_bf16_tt_kernel(int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A,
-                                                           int64_t lda, const bf16 *__restrict__ B, int64_t ldb,
-                                                           void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m,
-                                                           int tiles_n)
-{
-    constexpr int BM = 256, BN = 256, WGN = 4;
-    constexpr int WM = 128, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
-    constexpr int A_I = 4, B_I = 4;            // copies (of two k-rows each) per wave per K-step and operand
-    constexpr int LPS = A_I + B_I, H1 = LPS / 2, H2 = LPS - H1;  // half after the barrier, half in the next K-step
-    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
-    constexpr int B_REGION = 2 * A_BUF;
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-
-    int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    // ---- global side: copy j of this wave moves rows 2*(4*wave + j), +1 of the K-step; lane i writes bytes
-    // [16 i, 16 i + 16) of the 1 KB slot, i.e. row i/32, chunk position i%32, which holds chunk (i%32) ^ swizzle
-    uint32_t a_voff[A_I], b_voff[B_I];
-#pragma unroll
-    for (int j = 0; j < A_I; ++j) {
-        const int row = 2 * (wave * A_I + j) + (lane >> 5);
-        const int chunk = (lane & 31) ^ (4 * (row & 3)) ^ (2 * ((row >> 3) & 1));
-        a_voff[j] = (uint32_t)(((int64_t)row * lda + chunk * 8) * 2);
-        b_voff[j] = (uint32_t)(((int64_t)row * ldb + chunk * 8) * 2);
-    }
-    const char *a_tile = reinterpret_cast<const char *>(A + m0);
-    const char *b_tile = reinterpret_cast<const char *>(B + n0);
-    const int64_t a_kstep = (int64_t)kBK * lda * 2, b_kstep = (int64_t)kBK * ldb * 2;
-
-    // ---- LDS side: per-lane byte address of the first transposing load of every operand block at sub-step 0 of
-    // slot 0: row 8*g + j of the tile, the 32-byte piece of 16-column block b at piece position b ^ (2*j) ^ (g%2)
-    uint32_t a_ad[MA], b_ad[NB];
-    {
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-        const int g = lane >> 4, j = (lane & 15) >> 2, q = lane & 3;
-        const int x = (2 * j) ^ (g & 1);
-        const uint32_t rowoff = (uint32_t)((8 * g + j) * 512 + 8 * q);
-#pragma unroll
-        for (int i = 0; i < MA; ++i) a_ad[i] = lds0 + rowoff + 32 * ((MA * wm + i) ^ x);
-#pragma unroll
-        for (int i = 0; i < NB; ++i) b_ad[i] = lds0 + B_REGION + rowoff + 32 * ((NB * wn + i) ^ x);
-    }
-
-    f32x4 acc[MA][NB];
-#pragma unroll
-    for (int i = 0; i < MA; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    const int nk = (int)(K / kBK);
-    bf16x8 af[MA], bfr[2][NB];
-
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
-    auto gll = [&](int n, int kt, int slot) {
-        if (n < A_I) {
-            const char *abase = a_tile + (int64_t)kt * a_kstep;
-            const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
-                         : "memory");
-        } else {
-            const int m = n - A_I;
-            const char *bbase = b_tile + (int64_t)kt * b_kstep;
-            const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
-                         : "memory");
-        }
-    };
-    // sub-step s is rows 32 s .. 32 s + 31 of the tile (16 KB)
-    auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
-        constexpr int i = decltype(i_c)::value;
-        af[i] = lds_read_tr8<decltype(slot_c)::value * A_BUF + decltype(s_c)::value * 16384>(a_ad[i]);
-    };
-    auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
-        constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
-        bfr[s][j] = lds_read_tr8<decltype(slot_c)::value * B_BUF + s * 16384>(b_ad[j]);
-    };
-    // One group, as in the NT kernel; an operand block is two LDS instructions here, and the wait count is a
-    // 4-bit field: where twice the number of younger blocks exceeds it, the wait covers a few blocks more.
-    auto group = [&](auto s_c, auto g_c, auto slot_c, auto rs_c, auto rslot_c, auto cp0_c, auto cpn_c, auto gslot_c,
-                     int gkt) {
-        constexpr int S = decltype(s_c)::value, G = decltype(g_c)::value;
-        constexpr int CP0 = decltype(cp0_c)::value, CPN = decltype(cpn_c)::value, GSLOT = decltype(gslot_c)::value;
-        if constexpr (G < AHEAD) {
-            rd_a(std::integral_constant<int, G + AHEAD>{}, s_c, slot_c);
-        } else if constexpr (G == AHEAD) {
-            rd_a(std::integral_constant<int, 0>{}, rs_c, rslot_c);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<NBH>([&](auto jj) {
-                rd_b(jj, rs_c, rslot_c);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        } else if constexpr (G == AHEAD + 1) {
-            static_for<NBH>([&](auto jj) {
-                rd_b(std::integral_constant<int, NBH + decltype(jj)::value>{}, rs_c, rslot_c);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            rd_a(std::integral_constant<int, 1>{}, rs_c, rslot_c);
-        } else {
-            rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
-        }
-        constexpr int YOUNGER = 2 * (G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + NBH : AHEAD + NB));
-        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER < 15 ? YOUNGER : 15));
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<NB>([&](auto jj) {
-            constexpr int j = decltype(jj)::value;
-            acc[G][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[G], bfr[S][j], acc[G][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (j < CPN) {
-                gll(CP0 + j, gkt, GSLOT);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-
-    auto kstep = [&](auto slot_c, int kt) {
-        constexpr int SLOT = decltype(slot_c)::value;
-        using IS = std::integral_constant<int, SLOT>;
-        using IO = std::integral_constant<int, SLOT ^ 1>;
-        const int far1 = kt + 1 < nk ? kt + 1 : nk - 1;  // clamped: a surplus reload is never read
-        const int far2 = kt + 2 < nk ? kt + 2 : nk - 1;
-        static_for<MA>([&](auto gg) {
-            constexpr int G = decltype(gg)::value;
-            constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
-            group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
-                  std::integral_constant<int, after - before>{}, IO{}, far1);
-        });
-        static_for<MA>([&](auto gg) {
-            constexpr int G = decltype(gg)::value;
-            if constexpr (G == AHEAD) {
-                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-            }
-            constexpr int R = MA - AHEAD, Q = G - AHEAD;
-            constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
-            group(I1{}, gg, IS{}, I0{}, IO{}, std::integral_constant<int, before>{},
-                  std::integral_constant<int, after - before>{}, IS{}, far2);
-        });
-    };
-
-    // both slots are free at the start: request the first K-step and the first half of the second at once,
-    // then wait for the first only
-#pragma unroll
-    for (int n = 0; n < LPS; ++n) gll(n, 0, 0);
-    {
-        const int k1 = nk > 1 ? 1 : 0;
-#pragma unroll
-        for (int n = 0; n < H1; ++n) gll(n, k1, 1);
-    }
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(H1) : "memory");
-    __syncthreads();
-    static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
-    static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        kstep(I0{}, kt);
-        kstep(I1{}, kt + 1);
-    }
-    if (kt < nk) kstep(I0{}, kt);
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-// ---------------------------------------------------------------------------------------------
-// NN kernel: C[M,N] = A[M,K] . B[K,N], A K-contiguous as in the NT kernel, B stored [K, N] (N contiguous) as in
-// the K-major kernel - the input-gradient product dX = dY . W read from the weights as they are stored
-// ([out, in] row-major, out = K), so that no transposed copy of the weights is needed.  A side: the NT kernel's
-// (128-byte rows, 16-byte reads); B side: the K-major kernel's (512-byte rows, transposing reads), with one
-// change: both sides must hold the same eight k in a lane, the A side's 16-byte reads want k-group
-// (l/16 % 2) * 2 + l/32 there, so the B tile's swizzle separates the k-groups of a pass (now 0 and 2, or 1 and
-// 3) by bit 4 of k instead of bit 3: chunk ^ (4 * (k % 4)) ^ (2 * (k / 16 % 2)).
-// Tiles BM x 256 with BM = 256 (two slots) or 128 (ring of three), 8 waves as 2 x 4.  N a multiple of 256, K of 64.
-template <int BM, int NS>
-__global__ __launch_bounds__(512) void gemm_bf16_nn_kernel(int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A,
-                                                           int64_t lda, const bf16 *__restrict__ B, int64_t ldb,
-                                                           void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m,
-                                                           int tiles_n)
-{
-    constexpr int BN = 256, WGN = 4, NW = 8;
-    constexpr int WM = BM / 2, WN = 64, MA = WM / 16, NB = WN / 16, NBH = NB / 2, AHEAD = MA / 2;
-    constexpr int A_I = BM / 8 / NW, B_I = 4;  // copies per wave per K-step: 8 rows of A, 2 k-rows of B each
-    constexpr int LPS = A_I + B_I, H1 = LPS, H2 = LPS - H1;
-    constexpr int A_BUF = BM * kBK * 2, B_BUF = BN * kBK * 2;
-    constexpr int B_REGION = NS * A_BUF;
-    static_assert((NS - 1) * A_BUF + MA * 2048 <= 65536, "A offsets are immediates");
-    static_assert(AHEAD + 2 * NB <= 15, "the LDS wait count is a 4-bit field");
-    static_assert((H1 + MA - AHEAD - 1) / (MA - AHEAD) <= NB && (H2 + AHEAD - 1) / AHEAD <= NB, "one copy per MFMA at most");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-
-    int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    // ---- global side
-    uint32_t a_voff[A_I], b_voff[B_I];
-    {
-        const int lrow = lane >> 3, lch = lane & 7;
-#pragma unroll
-        for (int j = 0; j < A_I; ++j) {
-            const int row = (wave * A_I + j) * 8 + lrow;
-            const int sw = (row & 7) ^ ((row >> 3) & 1);
-            int64_t r = row;
-            if (m0 + r > M - 1) r = M - 1 - m0;
-            a_voff[j] = (uint32_t)((r * lda + ((lch ^ sw) << 3)) * 2);
-        }
-#pragma unroll
-        for (int j = 0; j < B_I; ++j) {
-            const int row = 2 * (wave * B_I + j) + (lane >> 5);
-            const int chunk = (lane & 31) ^ (4 * (row & 3)) ^ (2 * ((row >> 4) & 1));
-            b_voff[j] = (uint32_t)(((int64_t)row * ldb + chunk * 8) * 2);
-        }
-    }
-    const char *a_tile = reinterpret_cast<const char *>(A + m0 * lda);
-    const char *b_tile = reinterpret_cast<const char *>(B + n0);
-    const int64_t b_kstep = (int64_t)kBK * ldb * 2;
-
-    // ---- LDS side: lane l holds k-group kq = (l/16 % 2) * 2 + l/32 of a sub-step on both sides
-    uint32_t a_ad[2], b_ad[2][NB];
-    {
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-        const int kq = ((lane >> 4) & 1) * 2 + (lane >> 5);
-        const int r16 = lane & 15;
-        const int arow = wm * WM + r16;
-        const int asw = (arow & 7) ^ ((arow >> 3) & 1);
-#pragma unroll
-        for (int s = 0; s < 2; ++s) a_ad[s] = lds0 + arow * 128 + (((s * 4 + kq) ^ asw) << 4);
-        const int j = (lane & 15) >> 2, q = lane & 3;
-        const int x = (2 * j) ^ (kq >> 1);
-        const uint32_t rowoff = (uint32_t)((8 * kq + j) * 512 + 8 * q);
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            b_ad[0][i] = lds0 + B_REGION + rowoff + 32 * ((NB * wn + i) ^ x);
-            b_ad[1][i] = b_ad[0][i] + 65536;
-        }
-    }
-
-    f32x4 acc[MA][NB];
-#pragma unroll
-    for (int i = 0; i < MA; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-    const int nk = (int)(K / kBK);
-    bf16x8 af[MA], bfr[2][NB];
-
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem_raw;
-    const uint32_t a_slot = lds_base + wave * A_I * 1024, b_slot = lds_base + B_REGION + wave * B_I * 1024;
-    auto gll = [&](int n, int kt, int slot) {
-        if (n < A_I) {
-            const char *abase = a_tile + (int64_t)kt * (kBK * 2);
-            const uint32_t dst = a_slot + slot * A_BUF + n * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(a_voff[n]), "s"(abase)
-                         : "memory");
-        } else {
-            const int m = n - A_I;
-            const char *bbase = b_tile + (int64_t)kt * b_kstep;
-            const uint32_t dst = b_slot + slot * B_BUF + m * 1024;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(dst), "v"(b_voff[m]), "s"(bbase)
-                         : "memory");
-        }
-    };
-    auto rd_a = [&](auto i_c, auto s_c, auto slot_c) {
-        constexpr int i = decltype(i_c)::value, s = decltype(s_c)::value;
-        af[i] = lds_read16<decltype(slot_c)::value * A_BUF + i * 2048>(a_ad[s]);
-    };
-    auto rd_b = [&](auto j_c, auto s_c, auto slot_c) {
-        constexpr int j = decltype(j_c)::value, s = decltype(s_c)::value;
-        constexpr int off = decltype(slot_c)::value * B_BUF + s * 16384;
-        bfr[s][j] = lds_read_tr8<off % 65536>(b_ad[off / 65536][j]);
-    };
-    // One group, as in the NT kernel; a B block is two LDS instructions.
-    auto group = [&](auto s_c, auto g_c, auto slot_c, auto rs_c, auto rslot_c, auto cp0_c, auto cpn_c, auto gslot_c,
-                     int gkt) {
-        constexpr int S = decltype(s_c)::value, G = decltype(g_c)::value;
-        constexpr int CP0 = decltype(cp0_c)::value, CPN = decltype(cpn_c)::value, GSLOT = decltype(gslot_c)::value;
-        if constexpr (G < AHEAD) {
-            rd_a(std::integral_constant<int, G + AHEAD>{}, s_c, slot_c);
-        } else if constexpr (G == AHEAD) {
-            rd_a(std::integral_constant<int, 0>{}, rs_c, rslot_c);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<NBH>([&](auto jj) {
-                rd_b(jj, rs_c, rslot_c);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-        } else if constexpr (G == AHEAD + 1) {
-            static_for<NBH>([&](auto jj) {
-                rd_b(std::integral_constant<int, NBH + decltype(jj)::value>{}, rs_c, rslot_c);
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            rd_a(std::integral_constant<int, 1>{}, rs_c, rslot_c);
-        } else {
-            rd_a(std::integral_constant<int, G - AHEAD>{}, rs_c, rslot_c);
-        }
-        // LDS instructions younger than the last one this group needs: the A blocks in between are one each,
-        // the B blocks two
-        constexpr int YOUNGER = G < AHEAD ? AHEAD : (G == AHEAD ? AHEAD + 2 * NBH : AHEAD + 2 * NB);
-        asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(YOUNGER));
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<NB>([&](auto jj) {
-            constexpr int j = decltype(jj)::value;
-            acc[G][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[G], bfr[S][j], acc[G][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (j < CPN) {
-                gll(CP0 + j, gkt, GSLOT);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        });
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-
-    auto kstep = [&](auto slot_c, int kt) {
-        constexpr int SLOT = decltype(slot_c)::value;
-        using IS = std::integral_constant<int, SLOT>;
-        using IN = std::integral_constant<int, (SLOT + 1) % NS>;
-        using IF = std::integral_constant<int, (SLOT + NS - 1) % NS>;
-        const int far1 = kt + NS - 1 < nk ? kt + NS - 1 : nk - 1;  // clamped: a surplus reload is never read
-        const int far2 = kt + NS < nk ? kt + NS : nk - 1;
-        static_for<MA>([&](auto gg) {
-            constexpr int G = decltype(gg)::value;
-            constexpr int before = G < AHEAD ? (G * H2) / AHEAD : H2, after = G < AHEAD ? ((G + 1) * H2) / AHEAD : H2;
-            group(I0{}, gg, IS{}, I1{}, IS{}, std::integral_constant<int, H1 + before>{},
-                  std::integral_constant<int, after - before>{}, IF{}, far1);
-        });
-        static_for<MA>([&](auto gg) {
-            constexpr int G = decltype(gg)::value;
-            if constexpr (G == AHEAD) {
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" : : "n"((NS - 2) * LPS) : "memory");
-                __builtin_amdgcn_s_barrier();
-            }
-            constexpr int R = MA - AHEAD, Q = G - AHEAD;
-            constexpr int before = G < AHEAD ? 0 : (Q * H1) / R, after = G < AHEAD ? 0 : ((Q + 1) * H1) / R;
-            group(I1{}, gg, IS{}, I0{}, IN{}, std::integral_constant<int, before>{},
-                  std::integral_constant<int, after - before>{}, IS{}, far2);
-        });
-    };
-
-    // every slot is free at the start: request the first NS-1 K-steps and the first part of the next one at
-    // once, then wait for the first only
-    static_for<NS - 1>([&](auto ss) {
-        constexpr int S = decltype(ss)::value;
-        const int kt = S < nk ? S : nk - 1;
-#pragma unroll
-        for (int n = 0; n < LPS; ++n) gll(n, kt, S);
-    });
-    {
-        const int kf = NS - 1 < nk ? NS - 1 : nk - 1;
-#pragma unroll
-        for (int n = 0; n < H1; ++n) gll(n, kf, NS - 1);
-    }
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * LPS + H1) : "memory");
-    __syncthreads();
-    static_for<AHEAD>([&](auto ii) { rd_a(ii, I0{}, I0{}); });
-    static_for<NB>([&](auto jj) { rd_b(jj, I0{}, I0{}); });
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-
-    for (int kt = 0; kt < nk; kt += NS)
-        static_for<NS>([&](auto ii) {
-            constexpr int I = decltype(ii)::value;
-            if (kt + I < nk) kstep(ii, kt + I);
-        });
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
-}
-
-// One launch wrapper for both kernels: raises the kernel's dynamic LDS limit once per process (guarded, so
+// One launch wrapper for every instantiation: raises the kernel's dynamic LDS limit once per process (guarded, so
 // that host threads driving different stages may launch concurrently) and starts one work-group per tile.
 template <class Kernel>
 static hipError_t launch_tiles(Kernel kern, std::once_flag &once, hipError_t &attr_err, int BM, int BN, int threads,
@@ -1004,15 +660,20 @@ static hipError_t launch_tiles(Kernel kern, std::once_flag &once, hipError_t &at
     return hipGetLastError();
 }
 
-// the NT kernel with a ring of NS LDS slots
-template <int BM, int BN, int WGM, int WGN, int NS>
-static hipError_t launch_ring(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
-                              void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT = false>
+static hipError_t launch_kernel(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
+                                void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    return launch_tiles(gemm_bf16_nt_kernel<BM, BN, WGM, WGN, NS>, once, attr_err, BM, BN, WGM * WGN * 64,
-                        (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
+    return launch_tiles(gemm_bf16_kernel<A_KMAJOR, B_KMAJOR, BM, BN, WGM, WGN, NS, SPLIT>, once, attr_err, BM, BN,
+                        WGM * WGN * 64, (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
+}
+
+static EpiBf16 bf16_epilogue(const GemmEpi &epi)
+{
+    return EpiBf16{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
+                   epi.act,                epi.gelu_mode,           epi.out_f32,           epi.accum_scale};
 }
 
 bool gemm_bf16_tt_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb)
@@ -1025,12 +686,8 @@ hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
                                void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
 {
     if (!gemm_bf16_tt_supported(M, N, K, lda, ldb)) return hipErrorInvalidValue;
-    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    return launch_tiles(gemm_bf16_tt_kernel, once, attr_err, 256, 256, 512, (size_t)2 * 512 * kBK * sizeof(bf16), M, N, K,
-                        (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
+    return launch_kernel<true, true, 256, 256, 2, 4, 2, true>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc,
+                                                              bf16_epilogue(epi), s);
 }
 
 bool gemm_bf16_nn_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb)
@@ -1039,27 +696,16 @@ bool gemm_bf16_nn_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_
            64 * ldb * 2 < (int64_t)1 << 31 && 256 * lda * 2 < (int64_t)1 << 31;
 }
 
-template <int BM, int NS>
-static hipError_t launch_nn(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
-                            void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
-{
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    return launch_tiles(gemm_bf16_nn_kernel<BM, NS>, once, attr_err, BM, 256, 512, (size_t)NS * (BM + 256) * kBK * sizeof(bf16),
-                        M, N, K, A, lda, B, ldb, C, ldc, e, s);
-}
-
 hipError_t launch_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb,
                                void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s)
 {
     if (!gemm_bf16_nn_supported(M, N, K, lda, ldb)) return hipErrorInvalidValue;
-    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
+    const EpiBf16 e = bf16_epilogue(epi);
     // 256x256 tiles when they come in whole rounds of one per CU (or in many), else 128x256 with the deeper ring
     const int64_t t256 = ((M + 255) / 256) * (N / 256);
     if (t256 >= 256 && (t256 % 256 == 0 || t256 >= 1024))
-        return launch_nn<256, 2>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
-    return launch_nn<128, 3>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
+        return launch_kernel<false, true, 256, 256, 2, 4, 2>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
+    return launch_kernel<false, true, 128, 256, 2, 4, 3>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc, e, s);
 }
 
 bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K)
@@ -1074,8 +720,7 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (!gemm_bf16_supported(M, N, K) || (lda % 8) || (ldb % 8)) return hipErrorInvalidValue;
     // per-lane byte offsets inside a tile (up to 255 rows) are 32-bit
     if (256 * lda * 2 >= (int64_t)1 << 32 || 256 * ldb * 2 >= (int64_t)1 << 32) return hipErrorInvalidValue;
-    EpiBf16 e{(const bf16 *)epi.bias, (const bf16 *)epi.resid, (const bf16 *)epi.aux, (bf16 *)epi.out2,
-              epi.act, epi.gelu_mode, epi.out_f32, epi.accum_scale};
+    const EpiBf16 e = bf16_epilogue(epi);
     const bf16 *a = (const bf16 *)A, *b = (const bf16 *)B;
     if (tile == GEMM_TILE_AUTO) {
         // 256x256 tiles, two LDS stages: lowest LDS and L2 traffic per flop, but one work-group per CU, so a
@@ -1095,10 +740,10 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
         }
     }
     switch (tile) {
-    case GEMM_TILE_256x256: return launch_ring<256, 256, 2, 4, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case GEMM_TILE_128x128: return launch_ring<128, 128, 2, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case GEMM_TILE_256x128: return launch_ring<256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
-    case GEMM_TILE_128x256: return launch_ring<128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_256x256: return launch_kernel<false, false, 256, 256, 2, 4, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_128x128: return launch_kernel<false, false, 128, 128, 2, 2, 2>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_256x128: return launch_kernel<false, false, 256, 128, 4, 2, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
+    case GEMM_TILE_128x256: return launch_kernel<false, false, 128, 256, 2, 4, 3>(M, N, K, a, lda, b, ldb, C, ldc, e, s);
     default: return hipErrorInvalidValue;
     }
 }
