@@ -50,14 +50,15 @@ zpp_status zpp_op_gemm_bf16_nn(int64_t M, int64_t N, int64_t K, const void *A, i
 zpp_status zpp_op_attention_fwd(int32_t dtype, int32_t impl, const void *qkv, void *attn, float *lse, int64_t b,
                                 int64_t seq, int64_t nh, int64_t d, void *hip_stream);
 
-/* Backward of the above: dqkv[T, 3h] = (dQ | dK | dV) from dattn[T, h]; delta[b, nh, seq] is scratch. */
+/* Backward of the above: dqkv[T, 3h] = (dQ | dK | dV) from dattn[T, h]; delta is scratch of 2 * b * nh * seq
+ * floats (per query the row sum of dattn o attn and the log-sum-exp in the units the exponentials use). */
 zpp_status zpp_op_attention_bwd(int32_t dtype, int32_t impl, const void *qkv, const void *attn, const void *dattn,
                                 const float *lse, float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh,
                                 int64_t d, void *hip_stream);
 
 /* For callers that cannot allocate device memory (HIP graph capture, tight serving loops, harnesses
- * that forbid hipMalloc): zpp_op_attention_bwd without the `delta` argument.  The b * nh * seq floats of
- * scratch live in a 4 MiB array inside the library's device image (one copy per GPU the library runs on,
+ * that forbid hipMalloc): zpp_op_attention_bwd without the `delta` argument.  The 2 * b * nh * seq floats of
+ * scratch live in an 8 MiB array inside the library's device image (one copy per GPU the library runs on,
  * held until the process ends), so the call allocates nothing, and neither does anything it calls.
  * Limit: b * nh * seq <= zpp_op_attention_bwd_noalloc_max_rows() (2^20), ZPP_ERR_WORKSPACE beyond it.
  * The device of `hip_stream` must be the current device.  Every byte of scratch the kernels read is

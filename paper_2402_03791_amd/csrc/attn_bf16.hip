@@ -108,30 +108,70 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
 }
 
 // Work-group -> (block of the sequence, head, sample) for a 1-D grid of nblk * nh * nb work-groups whose
-// work grows with the block index: the heaviest blocks of all heads come first, then the next lighter
-// ones.  A CU takes its next work-group when it has finished one, so this order packs the unequal
-// work-groups tightly.  Work-groups are dealt round-robin over the 8 XCDs, each with a private L2: all
-// work-groups of one (sample, head) pair go to the same XCD, so the head's K/V (or Q/dO) rows are fetched
-// into one L2 once and shared there, instead of into all eight.
-__device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int &blk, int &n, int &bi)
+// work grows with the block index.  The (sample, head) pairs are taken in chunks of about two residencies of
+// the chip (1024 work-groups); inside a chunk the heaviest blocks of all its pairs come first, then the next
+// lighter ones: a CU takes its next work-group when it has finished one, so this order packs the unequal
+// work-groups tightly, and the light tail of one chunk runs beside the heavy head of the next.  Work-groups are
+// dealt round-robin over the 8 XCDs, each with a private L2: all work-groups of one pair go to the same XCD, and
+// an XCD works on chunk / 8 pairs at a time, so a pair's K/V (or Q/dO) rows are still near when the pair's other
+// blocks want them, however many samples the launch has (one chunk over everything, the order used before, loses
+// a quarter of the forward kernel's speed at 16 samples of 32 heads, and chunks of one residency start the
+// last chunk's long work-groups too late).  bodies = 2 (the dK/dV launch): each pair appears twice in a row on
+// its XCD, once per body, and `chunk` counts those.  chunk = 0: the whole grid is one chunk.  The last chunk
+// may be shorter than the others.
+__device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int chunk, int bodies, int &blk,
+                                                   int &n, int &bi, int &body)
 {
-    const int nv = nh * nb;
+    const int nv = nh * nb * bodies;
     int k, v;
-    if ((nv & 7) == 0) {
-        const int j = id >> 3, per = nv >> 3;
-        k = j / per;
-        v = (j % per) * 8 + (id & 7);
+    if (chunk > 0) {
+        const int per = nblk * chunk, ch = id / per, r = id - ch * per;
+        const int cs = min(chunk, nv - ch * chunk);  // (pair, body) slots of this chunk
+        const int x = r & 7, j = r >> 3, ppx = cs >> 3;
+        k = j / ppx;
+        const int pi = j - k * ppx;
+        if (bodies == 2) {
+            // the chunk's slots on an XCD alternate between the two bodies of a pair
+            body = pi & 1;
+            v = ch * (chunk >> 1) + (pi >> 1) * 8 + x;
+        } else {
+            body = 0;
+            v = ch * chunk + pi * 8 + x;
+        }
     } else {
-        k = id / nv;
-        v = id % nv;
+        if ((nv & 7) == 0) {
+            const int j = id >> 3, per = nv >> 3;
+            k = j / per;
+            v = (j % per) * 8 + (id & 7);
+        } else {
+            k = id / nv;
+            v = id % nv;
+        }
+        const int np = nh * nb;
+        body = v >= np ? 1 : 0;
+        v -= body * np;
     }
     blk = nblk - 1 - k;
     n = v % nh;
     bi = v / nh;
 }
 
+// (pair, body) slots per chunk for a launch over nv (sample, head) pairs: about 1024 work-groups per chunk, a
+// multiple of 16; 0 (one chunk) when there is no more than a chunk of them or they cannot be dealt evenly to the
+// XCDs
+static int chunk_slots(int64_t nblk, int64_t nv, int bodies)
+{
+    int64_t c = (1024 / nblk) / 16 * 16;
+    if (c < 16) c = 16;
+    return (nv % 8 == 0 && nv * bodies > c) ? (int)c : 0;
+}
+
 // LDS holds two pairs of streamed tiles: a pair is copied in while the other is worked on.
 constexpr int kStages = 4;
+
+// depth of the register rings that carry LDS operands to the matrix instructions of the backward kernels
+// (what fits beside the accumulators at two waves per SIMD)
+constexpr int kRingDq = 4, kRingDkv = 3;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -151,6 +191,58 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char *)p;
 }
 
+// max over the two lanes that share a query column (lane and lane ^ 32), without a trip through LDS:
+// v_permlane32_swap exchanges the upper half of one register with the lower half of another.
+__device__ __forceinline__ float max_with_lane32(float v)
+{
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+__device__ __forceinline__ float sum_with_lane32(float v)
+{
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+// One step of the online softmax for a lane's 32 scores of a key tile (two accumulator blocks of S^T):
+// p = 2^(s*c - m*c) as bf16 operands for the second product, row sum added to l_run.  The running maximum
+// m_run only has to bound the scores to within what the arithmetic tolerates, so it is raised (and the output
+// accumulator rescaled) only when some query of the wave sees a score more than 2^8 above it in the exponent:
+// after the first tiles of a row that almost never happens, and the 64 multiplications of the accumulator and
+// their wait for the previous tile's matrix instructions fall away.  The final division by the row sum makes the
+// result independent of which m was used.
+__device__ __forceinline__ void online_softmax_step(const f32x16 (&sacc)[2], float &m_run, float &l_run, f32x16 (&oacc)[4],
+                                                    bf16x8 (&pf)[4], float scale_log2e, float lazy)
+{
+    float mloc = sacc[0][0];
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
+    mloc = max_with_lane32(mloc);
+    if (__builtin_amdgcn_ballot_w64(mloc > m_run + lazy) != 0) {
+        const float m_new = fmaxf(m_run, mloc);
+        const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
+        l_run *= alpha;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+        m_run = m_new;
+    }
+    const float mc = m_run * scale_log2e;
+    float psum = 0.0f;
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float pe = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
+            psum += pe;
+            pf[2 * T + (e >> 3)][e & 7] = (bf16)pe;
+        }
+    l_run += psum;
+}
+
 // ------------------------------------------------------------------------------------ forward
 // Eight waves on 128 consecutive queries: waves w and w+4 (the two waves of a SIMD) own the same group of
 // 32 queries and split its key tiles between them, wave w the even tiles, wave w+4 the odd ones, each with
@@ -162,11 +254,11 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void *p)
 // Work-groups are as heavy as their position in the sequence; the heavy ones are dispatched first.
 __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
                                                                 float *__restrict__ lse, int seq, int nh, int nb,
-                                                                float scale_log2e)
+                                                                int chunk, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
-    int qb, n, bi;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
+    int qb, n, bi, body;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -196,6 +288,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
+    const float lazy = 8.0f / scale_log2e;  // 2^8 in the exponent, in units of the raw scores
 
     const int n_pairs = qb + 1;            // key tiles 2p, 2p+1 cover keys [128p, 128p + 128)
     const int my_tiles = qw0 / kTile + 1;  // tiles with unmasked entries for this wave's queries
@@ -252,34 +345,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
                         if (kv > qw0 + c) sacc[T][e] = -INFINITY;
                     }
             }
-            float mloc = sacc[0][0];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float m_new = fmaxf(m_run, mloc);
-            const float mc = m_new * scale_log2e;
-            float psum = 0.0f;
             bf16x8 pf[4];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float pe = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
-                    psum += pe;
-                    pf[2 * T + (e >> 3)][e & 7] = (bf16)pe;
-                }
-            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
-                l_run *= alpha;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
-                m_run = m_new;
-            }
-            l_run += psum;
+            online_softmax_step(sacc, m_run, l_run, oacc, pf, scale_log2e, lazy);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {  // i = 4 * st + t
@@ -318,7 +385,7 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
             for (int e = 0; e < 16; ++e) oacc[t][e] = oacc[t][e] * a_a + mg[(t * 16 + e) * 64 + lane] * a_b;
         m_run = m;
     }
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = sum_with_lane32(l_run);
     const float inv = 1.0f / l_tot;
     bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
 #pragma unroll
@@ -340,11 +407,11 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
 // each other.  Used when the grid has more than two work-groups per CU.
 __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
                                                              float *__restrict__ lse, int seq, int nh, int nb,
-                                                             float scale_log2e)
+                                                             int chunk, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
-    int qb, n, bi;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
+    int qb, n, bi, body;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -373,6 +440,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restr
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
+    const float lazy = 8.0f / scale_log2e;  // 2^8 in the exponent, in units of the raw scores
 
     const int n_tiles = 2 * (qb + 1);
     const int my_tiles = qw0 / kTile + 1;
@@ -420,34 +488,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restr
                         if (kv > qw0 + c) sacc[T][e] = -INFINITY;
                     }
             }
-            float mloc = sacc[0][0];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) mloc = fmaxf(mloc, sacc[T][e]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float m_new = fmaxf(m_run, mloc);
-            const float mc = m_new * scale_log2e;
-            float psum = 0.0f;
             bf16x8 pf[4];
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float pe = fast_exp2(__builtin_fmaf(sacc[T][e], scale_log2e, -mc));
-                    psum += pe;
-                    pf[2 * T + (e >> 3)][e & 7] = (bf16)pe;
-                }
-            if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-                const float alpha = fast_exp2((m_run - m_new) * scale_log2e);
-                l_run *= alpha;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
-                m_run = m_new;
-            }
-            l_run += psum;
+            online_softmax_step(sacc, m_run, l_run, oacc, pf, scale_log2e, lazy);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -462,7 +504,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restr
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = sum_with_lane32(l_run);
     const float inv = 1.0f / l_tot;
     bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
 #pragma unroll
@@ -490,11 +532,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
                                                                 const bf16 *__restrict__ dattn,
                                                                 const float *__restrict__ lse, float *__restrict__ delta,
                                                                 bf16 *__restrict__ dqkv, int seq, int nh, int nb,
-                                                                float scale, float scale_log2e)
+                                                                int chunk, float scale, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
-    int qb, n, bi;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, qb, n, bi);
+    int qb, n, bi, body;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -523,8 +565,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
 #pragma unroll
             for (int k = 0; k < 8; ++k) dl = __builtin_fmaf((float)dof[st][k], (float)of[k], dl);
         }
-        dl += __shfl_xor(dl, 32, 64);
-        if (g == 0) delta[stat] = dl;
+        dl = sum_with_lane32(dl);
+        if (g == 0) {
+            delta[stat] = dl;
+            delta[(int64_t)nb * nh * seq + stat] = l2;  // the statistic in the units the exponentials use
+        }
     }
     TileCopy<4> cp;
     cp.init(lane, wave, ld);
@@ -563,8 +608,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
             const int kv0 = jt * kTile;
             const unsigned char *ks = smem + (jt & 1) * 2 * kTileBytes;
             const unsigned char *vs = ks + kTileBytes;
-            bf16x8 dsf[4];
             const bool diag = kv0 + kTile - 1 > qw0;
+            // Half a tile (32 keys) at a time: its 16 score and dP instructions, its element-wise part, then the
+            // 8 dQ instructions that consume its dS, so that only two operand registers of dS are live.  LDS
+            // operands go through small rings of registers, requested kRingDq steps ahead of their use, order pinned.
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
                 f32x16 sacc, dpacc;
@@ -573,11 +620,33 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
                     sacc[e] = 0.0f;
                     dpacc[e] = 0.0f;
                 }
+                bf16x8 kr[kRingDq], vr[kRingDq];
+#pragma unroll
+                for (int i = 0; i < kRingDq; ++i) {
+                    kr[i] = rd_row(ks, ad, T, i);
+                    vr[i] = rd_row(vs, ad, T, i);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int st = 0; st < 8; ++st) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ks, ad, T, st), qf[st], sacc, 0, 0, 0);
-                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(vs, ad, T, st), dof[st], dpacc, 0, 0, 0);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[st % kRingDq], qf[st], sacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (st + kRingDq < 8) {
+                        kr[st % kRingDq] = rd_row(ks, ad, T, st + kRingDq);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[st % kRingDq], dof[st], dpacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (st + kRingDq < 8) {
+                        vr[st % kRingDq] = rd_row(vs, ad, T, st + kRingDq);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
+                // the first K^T operands of the dQ product travel during the element-wise part
+                bf16x8 tr[kRingDq];
+#pragma unroll
+                for (int i = 0; i < kRingDq; ++i) tr[i] = rd_tr(ks, ad, i & 3, 2 * T + (i >> 2));
+                __builtin_amdgcn_sched_barrier(0);
                 if (diag) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
@@ -585,17 +654,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
                         if (kv > qw0 + c) sacc[e] = -INFINITY;
                     }
                 }
+                bf16x8 dsf[2];
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l2));
-                    dsf[2 * T + (e >> 3)][e & 7] = (bf16)(pe * (dpacc[e] - dl));
+                    dsf[e >> 3][e & 7] = (bf16)(pe * (dpacc[e] - dl));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {  // i = 4 * (step of 16 keys) + t
+                    dqacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr[i % kRingDq], dsf[i >> 2], dqacc[i & 3], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i + kRingDq < 8) {
+                        tr[i % kRingDq] = rd_tr(ks, ad, (i + kRingDq) & 3, 2 * T + ((i + kRingDq) >> 2));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(ks, ad, t, st), dsf[st], dqacc[t], 0, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -626,9 +701,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
 // diagonal to the end of the sequence), streamed one by one through two stages, two work-groups per CU.
 template <bool DK>
 __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
-                                                     const float *__restrict__ lse, const float *__restrict__ delta,
-                                                     bf16 *__restrict__ dqkv, int seq, int nh, float scale,
-                                                     float scale_log2e, int kb, int n, int bi)
+                                                     const float *__restrict__ delta, bf16 *__restrict__ dqkv, int seq,
+                                                     int nh, int nb, float scale, float scale_log2e, int kb, int n, int bi)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][Q tile | dO tile], [2][lse | delta]
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
@@ -656,8 +730,8 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
     const char *dbase = reinterpret_cast<const char *>(dattn + row0 * h + (int64_t)n * kD);
     const int64_t q_stride = (int64_t)kTile * ld * 2, d_stride = (int64_t)kTile * h * 2;
     const uint32_t lds0 = lds_addr_of(smem);
-    const float *lse_b = lse + ((int64_t)bi * nh + n) * seq;
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
+    const float *lse_b = del_b + (int64_t)nb * nh * seq;  // log-sum-exp times log2(e), written by the dQ kernel
     const uint32_t stat0 = lds0 + 2 * 2 * kTileBytes;
     const uint32_t lane4 = lane * 4;
     const int it0 = 2 * kb, n_tiles = 2 * (seq / 128 - kb);  // query tiles it0 + j
@@ -700,8 +774,9 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
             const unsigned char *ds = qs + kTileBytes;
             const float *lse_s = reinterpret_cast<const float *>(smem + 2 * 2 * kTileBytes + buf * 512);
             const float *del_s = lse_s + 64;
-            bf16x8 frag[4];
             const bool diag = qt0 < kvw0 + 31;
+            const unsigned char *src = DK ? qs : ds;
+            // half a tile (32 queries) at a time, LDS operands through rings of registers, as in the dQ kernel
 #pragma unroll
             for (int T = 0; T < 2; ++T) {
                 f32x16 sacc, dpacc;
@@ -710,37 +785,68 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
                     sacc[e] = 0.0f;
                     dpacc[e] = 0.0f;
                 }
+                bf16x8 qr[kRingDkv], dr[DK ? kRingDkv : 1];
+#pragma unroll
+                for (int i = 0; i < kRingDkv; ++i) {
+                    qr[i] = rd_row(qs, ad, T, i);
+                    if constexpr (DK) dr[i] = rd_row(ds, ad, T, i);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int st = 0; st < 8; ++st) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(qs, ad, T, st), kf[st], sacc, 0, 0, 0);
-                    if constexpr (DK)
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(ds, ad, T, st), vf[st], dpacc, 0, 0, 0);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[st % kRingDkv], kf[st], sacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (st + kRingDkv < 8) {
+                        qr[st % kRingDkv] = rd_row(qs, ad, T, st + kRingDkv);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if constexpr (DK) {
+                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dr[st % kRingDkv], vf[st], dpacc, 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (st + kRingDkv < 8) {
+                            dr[st % kRingDkv] = rd_row(ds, ad, T, st + kRingDkv);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
                 }
+                // the first operands of the second product and the per-query statistics travel during the
+                // element-wise part
+                bf16x8 tr[kRingDkv];
+#pragma unroll
+                for (int i = 0; i < kRingDkv; ++i) tr[i] = rd_tr(src, ad, i & 3, 2 * T + (i >> 2));
+                f32x4 l4[4], d4[DK ? 4 : 1];
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const int qrel = 32 * T + 8 * e4 + 4 * g;
+                    l4[e4] = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
+                    if constexpr (DK) d4[e4] = *reinterpret_cast<const f32x4 *>(del_s + qrel);
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 if (diag) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e)
                         if (kvw0 + c > qt0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3)) sacc[e] = -INFINITY;
                 }
+                bf16x8 frag[2];
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int qrel = 32 * T + 8 * e4 + 4 * g;
-                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
-                    f32x4 d4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if constexpr (DK) d4 = *reinterpret_cast<const f32x4 *>(del_s + qrel);
+                for (int e = 0; e < 16; ++e) {
+                    const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[e >> 2][e & 3]));
+                    if constexpr (DK)
+                        frag[e >> 3][e & 7] = (bf16)(pe * (dpacc[e] - d4[e >> 2][e & 3]));
+                    else
+                        frag[e >> 3][e & 7] = (bf16)pe;
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int e = e4 * 4 + r;
-                        const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[r] * 1.44269504088896340736f));
-                        frag[2 * T + (e >> 3)][e & 7] = DK ? (bf16)(pe * (dpacc[e] - d4[r])) : (bf16)pe;
+                for (int i = 0; i < 8; ++i) {  // i = 4 * (step of 16 queries) + t
+                    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr[i % kRingDkv], frag[i >> 2], acc[i & 3], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (i + kRingDkv < 8) {
+                        tr[i % kRingDkv] = rd_tr(src, ad, (i + kRingDkv) & 3, 2 * T + ((i + kRingDkv) >> 2));
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
-            const unsigned char *src = DK ? qs : ds;
-#pragma unroll
-            for (int st = 0; st < 4; ++st)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_tr(src, ad, t, st), frag[st], acc[t], 0, 0, 0);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -760,16 +866,16 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
 
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_w4_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
                                                                  const float *__restrict__ lse, const float *__restrict__ delta,
-                                                                 bf16 *__restrict__ dqkv, int seq, int nh, int nb, float scale,
-                                                                 float scale_log2e)
+                                                                 bf16 *__restrict__ dqkv, int seq, int nh, int nb, int chunk,
+                                                                 float scale, float scale_log2e)
 {
-    int blk, n, v;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, 2 * nb, blk, n, v);
+    int blk, n, bi, body;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 2, blk, n, bi, body);
     const int kb = seq / 128 - 1 - blk;
-    if (v < nb)
-        attn_bwd_dkv_w4_body<true>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v);
+    if (body == 0)
+        attn_bwd_dkv_w4_body<true>(qkv, dattn, delta, dqkv, seq, nh, nb, scale, scale_log2e, kb, n, bi);
     else
-        attn_bwd_dkv_w4_body<false>(qkv, dattn, lse, delta, dqkv, seq, nh, scale, scale_log2e, kb, n, v - nb);
+        attn_bwd_dkv_w4_body<false>(qkv, dattn, delta, dqkv, seq, nh, nb, scale, scale_log2e, kb, n, bi);
 }
 
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
@@ -791,6 +897,7 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
     if (b * seq == 0) return hipSuccess;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
+    const int chunk = chunk_slots(seq / 128, nh * b, 1);
     // Up to two work-groups per CU's worth of work: the eight-wave kernel (a work-group's chain of intervals is
     // half as long); beyond: the four-wave kernel, two work-groups per CU, where one's prologue and epilogue
     // hide behind the other's tiles (measured at 32 heads x 2048: 54.0 against 57.0 us for 512 work-groups,
@@ -800,13 +907,13 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
         static bool done = false;
         if (hipError_t e = set_lds(attn_fwd_w4_kernel, lds, done)) return e;
         attn_fwd_w4_kernel<<<dim3(blocks), 256, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b,
-                                                          scale_log2e);
+                                                          chunk, scale_log2e);
     } else {
         constexpr size_t lds = kStages * 2 * kTileBytes;  // two pairs of (K tile, V tile)
         static bool done = false;
         if (hipError_t e = set_lds(attn_fwd_split_kernel, lds, done)) return e;
         attn_fwd_split_kernel<<<dim3(blocks), 512, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                             (int)b, scale_log2e);
+                                                             (int)b, 0, scale_log2e);
     }
     return hipGetLastError();
 }
@@ -825,9 +932,11 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (hipError_t e = set_lds(attn_bwd_dkv_w4_kernel, lds_dkv, a2)) return e;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
     attn_bwd_dq_w4_kernel<<<dim3(blocks), 256, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse,
-                                                            delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale, scale_log2e);
+                                                            delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
+                                                            chunk_slots(seq / 128, nh * b, 1), scale, scale_log2e);
     attn_bwd_dkv_w4_kernel<<<dim3(2 * blocks), 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                                  (bf16 *)dqkv, (int)seq, (int)nh, (int)b, scale, scale_log2e);
+                                                                  (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
+                                                                  chunk_slots(seq / 128, nh * b, 2), scale, scale_log2e);
     return hipGetLastError();
 }
 

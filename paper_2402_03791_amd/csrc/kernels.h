@@ -160,7 +160,8 @@ bool gemm_bf16_supported(int64_t M, int64_t N, int64_t K);
 // attn[T, h] (heads merged), lse[b, nh, s] = log-sum-exp of the scaled masked scores.
 hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int64_t b, int64_t seq,
                            int64_t nh, int64_t d, hipStream_t s);
-// delta[b, nh, s] = sum_e dattn*attn is scratch; dqkv[T, 3h] receives dQ | dK | dV.
+// delta is scratch of 2 * b * nh * s floats (sum_e dattn*attn per query, then the log-sum-exp times log2(e));
+// dqkv[T, 3h] receives dQ | dK | dV.
 hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void *dattn, const float *lse,
                            float *delta, void *dqkv, int64_t b, int64_t seq, int64_t nh, int64_t d,
                            hipStream_t s);

@@ -1,6 +1,7 @@
 // An entry point for callers that may not allocate device memory (code under HIP graph capture, tight
 // serving loops, harnesses that forbid hipMalloc): the attention backward of zpp_op_attention_bwd with
-// its per-query scratch (delta = rowsum(dO o O), b * nh * seq floats) in a file-scope device array
+// its per-query scratch (delta = rowsum(dO o O) and a scaled log-sum-exp, 2 * b * nh * seq floats) in a file-scope
+// device array
 // instead of a caller-supplied buffer.  Same kernels as zpp_op_attention_bwd.
 #include "../../include/zpp_ops.h"
 #include "kernels.h"
@@ -16,8 +17,9 @@ hipError_t launch_attn_simple_bwd(int dt, const void *qkv, const void *attn, con
 
 namespace {
 
-// 4 MiB per device that runs this library, held until the process ends.
-constexpr uint64_t kScratchFloats = 1ull << 20;
+// 8 MiB per device that runs this library, held until the process ends.
+constexpr uint64_t kScratchRows = 1ull << 20;        // queries (b * nh * seq) a call may have
+constexpr uint64_t kScratchFloats = 2 * kScratchRows;  // two floats of scratch per query
 static __device__ __align__(256) float scratch[kScratchFloats];
 
 // In host code `scratch` is only a handle of the symbol, not a device address: each device has its own copy
@@ -48,7 +50,7 @@ zpp_status scratch_of_current_device(float **out)
 
 extern "C" {
 
-uint64_t zpp_op_attention_bwd_noalloc_max_rows(void) { return kScratchFloats; }
+uint64_t zpp_op_attention_bwd_noalloc_max_rows(void) { return kScratchRows; }
 
 zpp_status zpp_op_attention_bwd_noalloc(int32_t dtype, int32_t impl, const void *qkv, const void *attn,
                                         const void *dattn, const float *lse, void *dqkv, int64_t b, int64_t seq,
@@ -57,10 +59,10 @@ zpp_status zpp_op_attention_bwd_noalloc(int32_t dtype, int32_t impl, const void 
     using namespace zpp;
     if (!qkv || !attn || !dattn || !lse || !dqkv) return set_error(ZPP_ERR_ARG, "NULL pointer");
     if (b <= 0 || seq <= 0 || nh <= 0 || d <= 0 || b > 65535 || nh > 65535) return set_error(ZPP_ERR_ARG, "bad sizes");
-    if ((uint64_t)b * (uint64_t)nh > kScratchFloats || (uint64_t)b * (uint64_t)nh * (uint64_t)seq > kScratchFloats)
+    if ((uint64_t)b * (uint64_t)nh > kScratchRows || (uint64_t)b * (uint64_t)nh * (uint64_t)seq > kScratchRows)
         return set_error(ZPP_ERR_WORKSPACE, "b * nh * seq = %llu exceeds the static scratch of %llu rows: use "
                                             "zpp_op_attention_bwd with a buffer of your own",
-                         (unsigned long long)((uint64_t)b * nh * seq), (unsigned long long)kScratchFloats);
+                         (unsigned long long)((uint64_t)b * nh * seq), (unsigned long long)kScratchRows);
     float *delta = nullptr;
     if (zpp_status st = scratch_of_current_device(&delta)) return st;
     hipStream_t s = (hipStream_t)hip_stream;

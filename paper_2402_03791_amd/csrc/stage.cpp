@@ -387,7 +387,7 @@ PartSizes plan_workspace(zpp_stage *s, uint64_t wcopy_off, uint64_t scratch_off,
     tmp("dqkv", T * 3 * h * gmax, e);
     tmp("du", T * f1 * gmax, e);
     if (s->c.arch == ZPP_ARCH_LLAMA) tmp("dact", T * f * gmax, e);
-    tmp("delta", (uint64_t)s->c.micro_batch * s->nh * s->c.seq * gmax, 4);
+    tmp("delta", 2 * (uint64_t)s->c.micro_batch * s->nh * s->c.seq * gmax, 4);  // per query: delta and a scaled log-sum-exp
     const uint64_t widest = std::max<uint64_t>(3 * h, f1);
     if (s->dt == DT_BF16) {
         // K-contiguous copies of the operands of a weight-gradient product over K = gmax * T tokens
@@ -512,11 +512,11 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
     return e;
 }
 
-// The attention kernels of a grouped call are launched for at most two micro-batches at a time: their
-// work-group order (heaviest blocks of every sample and head first) walks all (sample, head) pairs between
-// two blocks of one pair, and with more pairs than two micro-batches bring the keys and values stay in
-// the L2s less well in between (forward at 32 heads x 2048: 47.6 us per micro-batch at two, 50.8 at four).
-constexpr int kAttnMicroBatches = 2;
+// The attention kernels of a grouped call take the whole group in one launch (up to this many micro-batches):
+// their work-group order walks the (sample, head) pairs in chunks, so locality in the L2s does not depend on
+// the size of the launch, and the ramp and tail of a launch are paid once per group (forward at 32 heads x
+// 2048: 51 us per micro-batch at two, 41 at eight; backward 168 and 154).
+constexpr int kAttnMicroBatches = 64;
 
 hipError_t attention_fwd(zpp_stage *s, const void *qkv, void *attn, float *lse, hipStream_t st)
 {
@@ -548,7 +548,7 @@ hipError_t attention_bwd(zpp_stage *s, const void *qkv, const void *attn, const 
         const void *q = (const unsigned char *)qkv + row * 3 * h, *o = (const unsigned char *)attn + row * h;
         const void *dO = (const unsigned char *)dattn + row * h;
         void *dq = (unsigned char *)dqkv + row * 3 * h;
-        float *delta = (float *)s->tp("delta") + stat;
+        float *delta = (float *)s->tp("delta") + 2 * stat;
         ProfScope prof(ZPP_PROF_ATTN_BWD, 4.0 * nb * (double)s->c.seq * s->c.seq * h, st);
         hipError_t e;
         if (s->dt == DT_BF16 && attn_mfma_supported(s->c.seq, s->d))

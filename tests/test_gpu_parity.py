@@ -848,7 +848,7 @@ def test_generic_attention_against_oracle(dtype, b, s, nh, d):
     QKV, DA = to_dev(qkv, dtype), to_dev(da, dtype)
     AT = torch.empty(T, h, dtype=dtype, device="cuda")
     lse = torch.empty(b * nh * s, dtype=torch.float32, device="cuda")
-    delta = torch.empty_like(lse)
+    delta = torch.empty(2 * lse.numel(), dtype=torch.float32, device="cuda")
     DQKV = torch.empty_like(QKV)
     zpp.op_attention_fwd(QKV, AT, lse, b, s, nh, d, impl=0)
     zpp.op_attention_bwd(QKV, AT, DA, lse, delta, DQKV, b, s, nh, d, impl=0)
@@ -879,7 +879,7 @@ def test_mfma_attention_against_oracle(b, s, nh):
     QKV, DA = to_dev(qkv, torch.bfloat16), to_dev(da, torch.bfloat16)
     AT = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
     lse = torch.empty(b * nh * s, dtype=torch.float32, device="cuda")
-    delta = torch.empty_like(lse)
+    delta = torch.empty(2 * lse.numel(), dtype=torch.float32, device="cuda")
     DQKV = torch.empty_like(QKV)
     zpp.op_attention_fwd(QKV, AT, lse, b, s, nh, d, impl=1)
     torch.cuda.synchronize()

@@ -40,7 +40,7 @@ def test_attention_backward_without_allocation_matches_the_caller_scratch_call(i
     for seed, (b, seq, nh, d) in enumerate((first, second)):
         print(f"no-alloc attention backward impl={impl} b={b} seq={seq} nh={nh} d={d}", flush=True)
         qkv, attn, dattn, lse = _case(b, seq, nh, d, impl, dtype, 40 + seed)
-        delta = torch.empty(b * nh * seq, device="cuda", dtype=torch.float32)
+        delta = torch.empty(2 * b * nh * seq, device="cuda", dtype=torch.float32)
         ref = torch.full((b * seq, 3 * nh * d), float("nan"), device="cuda", dtype=dtype)
         out = torch.full_like(ref, float("nan"))
         rc = L.zpp_op_attention_bwd(dt, impl, qkv.data_ptr(), attn.data_ptr(), dattn.data_ptr(), lse.data_ptr(),
