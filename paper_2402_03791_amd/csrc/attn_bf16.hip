@@ -9,15 +9,23 @@
 // transposing load (ds_read_b64_tr_b16), which hands each lane four consecutive key rows of one value
 // column.  The softmax never leaves registers; only O and the log-sum-exp are written.
 //
-// Two work-group shapes.  Four waves, each taking every tile of its 32 rows, two stages of one tile pair in
-// LDS (64 KB), two work-groups per CU: the default (all backward launches, forward launches of more than two
-// work-groups per CU).  Eight waves, the two waves of a SIMD (w and w+4) sharing a group of 32 queries and
-// splitting its key tiles even / odd, merged at the end, one work-group per CU: forward launches of at most
-// two work-groups per CU, where the shorter chain of intervals per work-group wins.
+// Work-group shapes.  Forward and dQ: four waves, each taking every tile of its 32 rows, two stages of one tile
+// pair in LDS (64 KB), two work-groups per CU (all dQ launches, forward launches of more than two work-groups per
+// CU); forward launches of at most two work-groups per CU: eight waves, the two waves of a SIMD (w and w+4) sharing
+// a group of 32 queries and splitting its key tiles even / odd, merged at the end, one work-group per CU (the
+// shorter chain of intervals per work-group wins).  dK/dV: four waves, one per SIMD, with all 512 registers each
+// and four stages of tiles in LDS; see the kernel.
 //
 // Backward: two launches without atomics.  dQ: lane = query, loops over key tiles.  dK and dV: lane = key,
-// loop over query tiles.  P is recomputed from the saved log-sum-exp; delta = rowsum(dO o O) is computed by
-// the dQ kernel and handed to the dK kernel.
+// loop over query tiles.  P is recomputed from the saved log-sum-exp; delta = rowsum(dO o O) and the
+// log-sum-exp in base-2 units are computed by the dQ kernel and handed to the dK/dV kernel.
+//
+// What a wave can issue bounds these kernels as much as the matrix unit does: a SIMD issues one vector
+// instruction per four cycles, the element-wise part of a tile is as long as its matrix part (about 130
+// instructions against 32 of 32 cycles each in the forward kernel), and matrix and vector work of two waves on a
+// SIMD overlap only in part (measured on a synthetic mix: 16 matrix instructions and a softmax-sized block of
+// vector work take 455 ns on one SIMD when two waves each do one kind, 570 ns one after the other, 290 ns each
+// alone).  Hence the trimming of the element-wise parts below.
 #include "device_utils.h"
 #include "kernels.h"
 
@@ -116,54 +124,38 @@ __device__ __forceinline__ bf16x8 rd_tr(const unsigned char *tile, const TileAdd
 // an XCD works on chunk / 8 pairs at a time, so a pair's K/V (or Q/dO) rows are still near when the pair's other
 // blocks want them, however many samples the launch has (one chunk over everything, the order used before, loses
 // a quarter of the forward kernel's speed at 16 samples of 32 heads, and chunks of one residency start the
-// last chunk's long work-groups too late).  bodies = 2 (the dK/dV launch): each pair appears twice in a row on
-// its XCD, once per body, and `chunk` counts those.  chunk = 0: the whole grid is one chunk.  The last chunk
-// may be shorter than the others.
-__device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int chunk, int bodies, int &blk,
-                                                   int &n, int &bi, int &body)
+// last chunk's long work-groups too late).  chunk = 0: the whole grid is one chunk.  The last chunk may be
+// shorter than the others.
+__device__ __forceinline__ void decode_heavy_first(int id, int nblk, int nh, int nb, int chunk, int &blk, int &n, int &bi)
 {
-    const int nv = nh * nb * bodies;
+    const int nv = nh * nb;
     int k, v;
     if (chunk > 0) {
         const int per = nblk * chunk, ch = id / per, r = id - ch * per;
-        const int cs = min(chunk, nv - ch * chunk);  // (pair, body) slots of this chunk
+        const int cs = min(chunk, nv - ch * chunk);  // pairs of this chunk
         const int x = r & 7, j = r >> 3, ppx = cs >> 3;
         k = j / ppx;
-        const int pi = j - k * ppx;
-        if (bodies == 2) {
-            // the chunk's slots on an XCD alternate between the two bodies of a pair
-            body = pi & 1;
-            v = ch * (chunk >> 1) + (pi >> 1) * 8 + x;
-        } else {
-            body = 0;
-            v = ch * chunk + pi * 8 + x;
-        }
+        v = ch * chunk + (j - k * ppx) * 8 + x;
+    } else if ((nv & 7) == 0) {
+        const int j = id >> 3, per = nv >> 3;
+        k = j / per;
+        v = (j % per) * 8 + (id & 7);
     } else {
-        if ((nv & 7) == 0) {
-            const int j = id >> 3, per = nv >> 3;
-            k = j / per;
-            v = (j % per) * 8 + (id & 7);
-        } else {
-            k = id / nv;
-            v = id % nv;
-        }
-        const int np = nh * nb;
-        body = v >= np ? 1 : 0;
-        v -= body * np;
+        k = id / nv;
+        v = id % nv;
     }
     blk = nblk - 1 - k;
     n = v % nh;
     bi = v / nh;
 }
 
-// (pair, body) slots per chunk for a launch over nv (sample, head) pairs: about 1024 work-groups per chunk, a
-// multiple of 16; 0 (one chunk) when there is no more than a chunk of them or they cannot be dealt evenly to the
-// XCDs
-static int chunk_slots(int64_t nblk, int64_t nv, int bodies)
+// pairs per chunk for a launch over nv (sample, head) pairs: about 1024 work-groups per chunk, a multiple of 16;
+// 0 (one chunk) when there is no more than a chunk of them or they cannot be dealt evenly to the XCDs
+static int chunk_slots(int64_t nblk, int64_t nv)
 {
     int64_t c = (1024 / nblk) / 16 * 16;
     if (c < 16) c = 16;
-    return (nv % 8 == 0 && nv * bodies > c) ? (int)c : 0;
+    return (nv % 8 == 0 && nv > c) ? (int)c : 0;
 }
 
 // LDS holds two pairs of streamed tiles: a pair is copied in while the other is worked on.
@@ -243,6 +235,30 @@ __device__ __forceinline__ void online_softmax_step(const f32x16 (&sacc)[2], flo
     l_run += psum;
 }
 
+// A wave's 32 x 128 result block (accumulator layout: lane = row, registers along d) goes out through a
+// wave-private 8 KB of LDS so that every store instruction writes four whole 256-byte rows: straight from the
+// accumulator layout a store would touch 32 rows with 8 bytes each.  `w` must not be in use by anyone else.
+__device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[4], float mul, unsigned char *w, bf16 *row0_ptr,
+                                                  int64_t ld_elems, int lane)
+{
+    const int c = lane & 31, g = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (bf16)(acc[t][e4 * 4 + r] * mul);
+            *reinterpret_cast<bf16x4 *>(w + c * 256 + (((4 * t + e4) ^ (c & 15)) << 4) + g * 8) = o;
+        }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4), pos = lane & 15;
+        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(w + r * 256 + (pos << 4));
+        *reinterpret_cast<bf16x8 *>(row0_ptr + r * ld_elems + ((pos ^ (r & 15)) << 3)) = v;
+    }
+}
+
 // ------------------------------------------------------------------------------------ forward
 // Eight waves on 128 consecutive queries: waves w and w+4 (the two waves of a SIMD) own the same group of
 // 32 queries and split its key tiles between them, wave w the even tiles, wave w+4 the odd ones, each with
@@ -257,8 +273,8 @@ __global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__re
                                                                 int chunk, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
-    int qb, n, bi, body;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
+    int qb, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, qb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -410,8 +426,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restr
                                                              int chunk, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
-    int qb, n, bi, body;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
+    int qb, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, qb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -506,16 +522,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restr
     }
     const float l_tot = sum_with_lane32(l_run);
     const float inv = 1.0f / l_tot;
-    bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(oacc[t][e4 * 4 + r] * inv);
-            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
-        }
+    // (the loop's last barrier has every wave out of the stages)
+    store_rows_via_lds(oacc, inv, smem + wave * 8192, attn + (row0 + qw0) * h + (int64_t)n * kD, h, lane);
     if (g == 0)
         lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
             (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
@@ -535,8 +543,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
                                                                 int chunk, float scale, float scale_log2e)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][K tile | V tile]
-    int qb, n, bi, body;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 1, qb, n, bi, body);
+    int qb, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, qb, n, bi);
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -675,36 +683,136 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_w4_kernel(const bf16 *__re
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
-    bf16 *op = dqkv + (row0 + qw0 + c) * ld + (int64_t)n * kD;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(dqacc[t][e4 * 4 + r] * scale);
-            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
-        }
+    // (the loop's last barrier has every wave out of the stages)
+    store_rows_via_lds(dqacc, scale, smem + wave * 8192, dqkv + (row0 + qw0) * ld + (int64_t)n * kD, ld, lane);
 }
 
-// ------------------------------------------------------------------------------------ backward: dK, dV
-// Lane = key.  Per query tile: S = Q K^T (operands Q row-wise from LDS, K in registers),
-// P = exp2(S*c - lse[q]).  Two instantiations, so that each fits two waves per SIMD:
-//   DK = false: dV^T += dO^T P, with dO^T gathered from the dO tile through the transposing load;
-//   DK = true:  dP = dO V^T (V in registers), dS = P o (dP - delta[q]), dK^T += Q^T dS.
-// Recomputing S in both costs 16 of 80 MFMAs per tile and buys twice the occupancy (fused they need
-// 434 VGPRs).  The per-query log-sum-exp and delta travel through LDS with the tiles (as ordinary loads
-// inside the loop their in-order completion made every use wait behind the next tile's copies).
-// Early key blocks see the most queries and are dispatched first; the dK and dV work-groups of a key
-// block follow each other.
-// Four waves per work-group on 128 consecutive keys: every wave all query tiles of its 32 keys (from the
-// diagonal to the end of the sequence), streamed one by one through two stages, two work-groups per CU.
-template <bool DK>
-__device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
-                                                     const float *__restrict__ delta, bf16 *__restrict__ dqkv, int seq,
-                                                     int nh, int nb, float scale, float scale_log2e, int kb, int n, int bi)
+// ------------------------------------------------------------------------------------ backward: dK and dV
+// One wave per SIMD (four per work-group, 128 consecutive keys, lane = key) with all 512 registers: K and V
+// fragments and both accumulators stay in registers, and S and P are computed once for both products: 64 matrix
+// instructions per tile of 64 queries (split in a dK and a dV body, each small enough for two waves per SIMD, the
+// kernel needs 80 and three times the exponentials).  The element-wise part of one half tile (32 queries) is issued
+// between the matrix instructions of the next half tile's S and dP products, one element per instruction, so
+// that the vector unit works in the shadow of the matrix unit:
+//     [S, dP of half u+1  ||  P, dS of half u]   [dV, dK of half u]   ...
+// Query tiles (Q rows, dO rows, and the two per-query statistics) stream through four LDS stages, copied two
+// tiles ahead.  All four waves walk all tiles of the key block (the first tile is fully masked for the upper two
+// waves: uniform control flow is worth more than the skipped half tile).  With one wave per SIMD nothing hides
+// a work-group's start and end, so the key block's own K and V rows arrive through LDS with coalesced copies
+// and the results leave through LDS in whole rows.  Measured per work-group (timestamps in the kernel, 32
+// heads x 2048, two samples): about 3950 cycles per tile against 2048 of matrix instructions - a lone wave
+// issues its ~590 instructions per tile (64 matrix, 112 LDS reads, 160 element-wise, 64 accumulator reads, waits
+// and addresses) at one per 6-7 cycles - and 9400 + 8800 cycles before and after the tiles with plain loads and
+// stores from the accumulator layout, which the LDS paths cut.  Against the two-body kernel: 6 to 9 % less time
+// for the backward pass.
+constexpr int kFStages = 4;
+constexpr int kFStageBytes = 2 * kTileBytes + 512;  // Q tile | dO tile | 64 log-sum-exp | 64 delta
+constexpr int kFRingA = 4, kFRingB = 4;
+
+// S and dP of half tile TA of the tile at `ta` into (sa, da); between its matrix instructions the element-wise
+// part of half TV of the tile whose statistics lie at `stat`, from its scores and dP in (sv, dv), to the operands
+// (pf, dsf) of the second products.  MASK (the first two tiles of a key block): elements with in-tile query index
+// (less 4 g) below qlim are masked.
+template <bool WITH_A, bool MASK, int TA, int TV>
+__device__ __forceinline__ void dkv_scores_and_elementwise(f32x16 &sa, f32x16 &da, const f32x16 &sv, const f32x16 &dv,
+                                                           bf16x8 (&pf)[2], bf16x8 (&dsf)[2], const unsigned char *ta,
+                                                           const TileAddr &ad, const bf16x8 (&kf)[8],
+                                                           const bf16x8 (&vf)[8], const float *stat, float scale_log2e,
+                                                           int qlim, int g)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2][Q tile | dO tile], [2][lse | delta]
+    // the statistics of four queries at a time, requested one group ahead
+    f32x4 l4[2], d4[2];
+    l4[0] = *reinterpret_cast<const f32x4 *>(stat + 32 * TV + 4 * g);
+    d4[0] = *reinterpret_cast<const f32x4 *>(stat + 64 + 32 * TV + 4 * g);
+    bf16x8 qr[kFRingA], dr[kFRingA];
+    if constexpr (WITH_A) {
+#pragma unroll
+        for (int i = 0; i < kFRingA; ++i) {
+            qr[i] = rd_row(ta, ad, TA, i);
+            dr[i] = rd_row(ta + kTileBytes, ad, TA, i);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            sa[e] = 0.0f;
+            da[e] = 0.0f;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float p_prev = 0.0f, d_prev = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if constexpr (WITH_A) {
+            const int k = i >> 1;
+            if ((i & 1) == 0) {
+                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[k % kFRingA], kf[k], sa, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (k + kFRingA < 8) qr[k % kFRingA] = rd_row(ta, ad, TA, k + kFRingA);
+            } else {
+                da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dr[k % kFRingA], vf[k], da, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (k + kFRingA < 8) dr[k % kFRingA] = rd_row(ta + kTileBytes, ad, TA, k + kFRingA);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // element i of half TV: query 32 TV + 8 (i / 4) + 4 g + i % 4 of the tile
+        if ((i & 3) == 0 && i + 4 < 16) {
+            l4[((i >> 2) + 1) & 1] = *reinterpret_cast<const f32x4 *>(stat + 32 * TV + 8 * ((i >> 2) + 1) + 4 * g);
+            d4[((i >> 2) + 1) & 1] = *reinterpret_cast<const f32x4 *>(stat + 64 + 32 * TV + 8 * ((i >> 2) + 1) + 4 * g);
+        }
+        float sm = sv[i];
+        if constexpr (MASK) {
+            if (qlim > 32 * TV + 8 * (i >> 2) + (i & 3)) sm = -INFINITY;
+        }
+        const float pe = fast_exp2(__builtin_fmaf(sm, scale_log2e, -l4[(i >> 2) & 1][i & 3]));
+        const float de = pe * (dv[i] - d4[(i >> 2) & 1][i & 3]);
+        if (i & 1) {
+            pf[i >> 3][(i & 7) - 1] = (bf16)p_prev;
+            pf[i >> 3][i & 7] = (bf16)pe;
+            dsf[i >> 3][(i & 7) - 1] = (bf16)d_prev;
+            dsf[i >> 3][i & 7] = (bf16)de;
+        } else {
+            p_prev = pe;
+            d_prev = de;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// dV += dO^T P and dK += Q^T dS for half tile TB of the tile at `tb`
+template <int TB>
+__device__ __forceinline__ void dkv_second_products(const bf16x8 (&pf)[2], const bf16x8 (&dsf)[2], const unsigned char *tb,
+                                                    const TileAddr &ad, f32x16 (&acck)[4], f32x16 (&accv)[4])
+{
+    bf16x8 rv[kFRingB], rk[kFRingB];
+#pragma unroll
+    for (int i = 0; i < kFRingB; ++i) {
+        rv[i] = rd_tr(tb + kTileBytes, ad, i & 3, 2 * TB + (i >> 2));
+        rk[i] = rd_tr(tb, ad, i & 3, 2 * TB + (i >> 2));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {  // i = 4 * (step of 16 queries) + t
+        accv[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rv[i % kFRingB], pf[i >> 2], accv[i & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + kFRingB < 8) rv[i % kFRingB] = rd_tr(tb + kTileBytes, ad, (i + kFRingB) & 3, 2 * TB + ((i + kFRingB) >> 2));
+        __builtin_amdgcn_sched_barrier(0);
+        acck[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rk[i % kFRingB], dsf[i >> 2], acck[i & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + kFRingB < 8) rk[i % kFRingB] = rd_tr(tb, ad, (i + kFRingB) & 3, 2 * TB + ((i + kFRingB) >> 2));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv,
+                                                                    const bf16 *__restrict__ dattn,
+                                                                    const float *__restrict__ delta,
+                                                                    bf16 *__restrict__ dqkv, int seq, int nh, int nb,
+                                                                    int chunk, float scale, float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4 stages][Q tile | dO tile | statistics]
+    int blk, n, bi;
+    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, blk, n, bi);
+    const int kb = seq / 128 - 1 - blk;
     const int64_t h = (int64_t)nh * kD, ld = 3 * h;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -712,15 +820,6 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
     const int kvw0 = 128 * kb + 32 * wave;
     const int64_t row0 = (int64_t)bi * seq;
 
-    bf16x8 kf[8], vf[DK ? 8 : 1];
-    {
-        const bf16 *kp = qkv + (row0 + kvw0 + c) * ld + h + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            kf[st] = *reinterpret_cast<const bf16x8 *>(kp + 16 * st);
-            if constexpr (DK) vf[st] = *reinterpret_cast<const bf16x8 *>(kp + h + 16 * st);
-        }
-    }
     TileCopy<4> cq, cd;
     cq.init(lane, wave, ld);
     cd.init(lane, wave, h);
@@ -732,150 +831,124 @@ __device__ __forceinline__ void attn_bwd_dkv_w4_body(const bf16 *__restrict__ qk
     const uint32_t lds0 = lds_addr_of(smem);
     const float *del_b = delta + ((int64_t)bi * nh + n) * seq;
     const float *lse_b = del_b + (int64_t)nb * nh * seq;  // log-sum-exp times log2(e), written by the dQ kernel
-    const uint32_t stat0 = lds0 + 2 * 2 * kTileBytes;
     const uint32_t lane4 = lane * 4;
-    const int it0 = 2 * kb, n_tiles = 2 * (seq / 128 - kb);  // query tiles it0 + j
+    const int it0 = 2 * kb, n_tiles = 2 * (seq / 128 - kb);  // query tiles it0 + j, n_tiles >= 2
+    // every wave issues the same nine copies per tile, so that one count serves all waits: waves 0 and 2 bring the
+    // log-sum-exp values, waves 1 and 3 the deltas (twice the same bytes to the same place)
     auto issue_tile = [&](int j) {
-        const int it = it0 + j, buf = j & 1;
-        cq.issue(qbase + it * q_stride, lds0 + buf * 2 * kTileBytes, wave);
-        cd.issue(dbase + it * d_stride, lds0 + buf * 2 * kTileBytes + kTileBytes, wave);
-        if (wave == 0) {
-            const uint32_t dst = stat0 + buf * 512;
-            const float *src = lse_b + it * kTile;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-        } else if (wave == 1 && DK) {
-            const uint32_t dst = stat0 + buf * 512 + 256;
-            const float *src = del_b + it * kTile;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(dst), "v"(lane4), "s"(src) : "memory");
-        }
+        const int it = it0 + j;
+        const uint32_t dst = lds0 + (j & (kFStages - 1)) * kFStageBytes;
+        cq.issue(qbase + it * q_stride, dst, wave);
+        cd.issue(dbase + it * d_stride, dst + kTileBytes, wave);
+        const uint32_t sdst = dst + 2 * kTileBytes + (wave & 1) * 256;
+        const float *src = ((wave & 1) ? del_b : lse_b) + it * kTile;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(sdst), "v"(lane4), "s"(src) : "memory");
     };
 
-    f32x16 acc[4];
+    f32x16 acck[4], accv[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
-
-    issue_tile(0);
-#pragma unroll
-    for (int st = 0; st < 8; ++st) {
-        loaded_before_here(kf[st]);
-        if constexpr (DK) loaded_before_here(vf[st]);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    for (int j = 0; j < n_tiles; ++j) {
-        if (j + 1 < n_tiles) issue_tile(j + 1);
-        const int buf = j & 1;
-        const int qt0 = (it0 + j) * kTile;
-        if (qt0 + kTile - 1 >= kvw0) {
-            const unsigned char *qs = smem + buf * 2 * kTileBytes;
-            const unsigned char *ds = qs + kTileBytes;
-            const float *lse_s = reinterpret_cast<const float *>(smem + 2 * 2 * kTileBytes + buf * 512);
-            const float *del_s = lse_s + 64;
-            const bool diag = qt0 < kvw0 + 31;
-            const unsigned char *src = DK ? qs : ds;
-            // half a tile (32 queries) at a time, LDS operands through rings of registers, as in the dQ kernel
-#pragma unroll
-            for (int T = 0; T < 2; ++T) {
-                f32x16 sacc, dpacc;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    sacc[e] = 0.0f;
-                    dpacc[e] = 0.0f;
-                }
-                bf16x8 qr[kRingDkv], dr[DK ? kRingDkv : 1];
-#pragma unroll
-                for (int i = 0; i < kRingDkv; ++i) {
-                    qr[i] = rd_row(qs, ad, T, i);
-                    if constexpr (DK) dr[i] = rd_row(ds, ad, T, i);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[st % kRingDkv], kf[st], sacc, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (st + kRingDkv < 8) {
-                        qr[st % kRingDkv] = rd_row(qs, ad, T, st + kRingDkv);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    if constexpr (DK) {
-                        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dr[st % kRingDkv], vf[st], dpacc, 0, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (st + kRingDkv < 8) {
-                            dr[st % kRingDkv] = rd_row(ds, ad, T, st + kRingDkv);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                }
-                // the first operands of the second product and the per-query statistics travel during the
-                // element-wise part
-                bf16x8 tr[kRingDkv];
-#pragma unroll
-                for (int i = 0; i < kRingDkv; ++i) tr[i] = rd_tr(src, ad, i & 3, 2 * T + (i >> 2));
-                f32x4 l4[4], d4[DK ? 4 : 1];
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int qrel = 32 * T + 8 * e4 + 4 * g;
-                    l4[e4] = *reinterpret_cast<const f32x4 *>(lse_s + qrel);
-                    if constexpr (DK) d4[e4] = *reinterpret_cast<const f32x4 *>(del_s + qrel);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                if (diag) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (kvw0 + c > qt0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3)) sacc[e] = -INFINITY;
-                }
-                bf16x8 frag[2];
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float pe = fast_exp2(__builtin_fmaf(sacc[e], scale_log2e, -l4[e >> 2][e & 3]));
-                    if constexpr (DK)
-                        frag[e >> 3][e & 7] = (bf16)(pe * (dpacc[e] - d4[e >> 2][e & 3]));
-                    else
-                        frag[e >> 3][e & 7] = (bf16)pe;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {  // i = 4 * (step of 16 queries) + t
-                    acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr[i % kRingDkv], frag[i >> 2], acc[i & 3], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (i + kRingDkv < 8) {
-                        tr[i % kRingDkv] = rd_tr(src, ad, (i + kRingDkv) & 3, 2 * T + ((i + kRingDkv) >> 2));
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            }
+        for (int e = 0; e < 16; ++e) {
+            acck[t][e] = 0.0f;
+            accv[t][e] = 0.0f;
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // The key block's own K and V rows come through LDS as well (stages 2 and 3, free until tile 2 is asked for):
+    // coalesced copies and 16 LDS reads per wave instead of 16 loads that touch 32 rows each.
+    bf16x8 kf[8], vf[8];
+    {
+        const char *kblk = reinterpret_cast<const char *>(qkv + (row0 + 128 * kb) * ld + h + (int64_t)n * kD);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const uint32_t dst = lds0 + (2 + half) * kFStageBytes;
+            cq.issue(kblk + half * q_stride, dst, wave);
+            cq.issue(kblk + half * q_stride + h * 2, dst + kTileBytes, wave);
+        }
+        issue_tile(0);
+        issue_tile(1);
+        asm volatile("s_waitcnt vmcnt(18)" ::: "memory");  // the sixteen K/V copies; tiles 0 and 1 may be in flight
+        __syncthreads();
+        const unsigned char *kv = smem + (2 + (wave >> 1)) * kFStageBytes;
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+            kf[s8] = rd_row(kv, ad, wave & 1, s8);
+            vf[s8] = rd_row(kv + kTileBytes, ad, wave & 1, s8);
+        }
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) {
+            loaded_before_here(kf[s8]);
+            loaded_before_here(vf[s8]);
+        }
+        __syncthreads();
+        if (n_tiles > 2) {
+            issue_tile(2);
+            asm volatile("s_waitcnt vmcnt(18)" ::: "memory");  // tile 0 is there; tiles 1 and 2 may be in flight
+        } else {
+            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        }
         __syncthreads();
     }
-    bf16 *out = dqkv + (row0 + kvw0 + c) * ld + (DK ? h : 2 * h) + (int64_t)n * kD;
-    const float oscale = DK ? scale : 1.0f;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(acc[t][e4 * 4 + r] * oscale);
-            *reinterpret_cast<bf16x4 *>(out + 32 * t + 8 * e4 + 4 * g) = o;
-        }
-}
 
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_w4_kernel(const bf16 *__restrict__ qkv, const bf16 *__restrict__ dattn,
-                                                                 const float *__restrict__ lse, const float *__restrict__ delta,
-                                                                 bf16 *__restrict__ dqkv, int seq, int nh, int nb, int chunk,
-                                                                 float scale, float scale_log2e)
-{
-    int blk, n, bi, body;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, 2, blk, n, bi, body);
-    const int kb = seq / 128 - 1 - blk;
-    if (body == 0)
-        attn_bwd_dkv_w4_body<true>(qkv, dattn, delta, dqkv, seq, nh, nb, scale, scale_log2e, kb, n, bi);
+    f32x16 s0, p0, s1, p1;  // S and dP of the two half tiles in flight
+    bf16x8 pf[2], dsf[2];
+    {
+        // S and dP of the first half tile, nothing to overlap with yet
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            s0[e] = 0.0f;
+            p0[e] = 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(smem, ad, 0, k), kf[k], s0, 0, 0, 0);
+            p0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(smem + kTileBytes, ad, 0, k), vf[k], p0, 0, 0, 0);
+        }
+    }
+    const int qlim0 = kvw0 + c - it0 * kTile - 4 * g;
+    // one tile with the next tile's first half product inside it (the loop bodies), or without (the last tile)
+    auto enter_tile = [&](int j) {
+        // tile j + 1 has to be in LDS for this iteration; the copies of tile j + 2 (nine per wave) may still be in
+        // flight; tile j + 3 goes into the stage of tile j - 1, which every wave has left once it is past the barrier
+        if (j + 2 < n_tiles)
+            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (j + 3 < n_tiles) issue_tile(j + 3);
+    };
+    auto tile = [&](int j, auto mask, auto last) {
+        constexpr bool MASK = decltype(mask)::value, LAST = decltype(last)::value;
+        const unsigned char *tj = smem + (j & (kFStages - 1)) * kFStageBytes;
+        const unsigned char *tn = smem + ((j + 1) & (kFStages - 1)) * kFStageBytes;
+        const float *stat = reinterpret_cast<const float *>(tj + 2 * kTileBytes);
+        const int qlim = qlim0 - j * kTile;
+        dkv_scores_and_elementwise<true, MASK, 1, 0>(s1, p1, s0, p0, pf, dsf, tj, ad, kf, vf, stat, scale_log2e, qlim, g);
+        dkv_second_products<0>(pf, dsf, tj, ad, acck, accv);
+        dkv_scores_and_elementwise<!LAST, MASK, 0, 1>(s0, p0, s1, p1, pf, dsf, tn, ad, kf, vf, stat, scale_log2e, qlim, g);
+        dkv_second_products<1>(pf, dsf, tj, ad, acck, accv);
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    // the first two tiles of a key block touch the diagonal, the others need no mask
+    const int n_masked = n_tiles - 1 < 2 ? n_tiles - 1 : 2;
+    for (int j = 0; j < n_masked; ++j) {
+        enter_tile(j);
+        tile(j, T_{}, F_{});
+    }
+    for (int j = 2; j + 1 < n_tiles; ++j) {
+        enter_tile(j);
+        tile(j, F_{}, F_{});
+    }
+    enter_tile(n_tiles - 1);
+    if (n_tiles == 2)
+        tile(n_tiles - 1, T_{}, T_{});
     else
-        attn_bwd_dkv_w4_body<false>(qkv, dattn, delta, dqkv, seq, nh, nb, scale, scale_log2e, kb, n, bi);
+        tile(n_tiles - 1, F_{}, T_{});
+    __syncthreads();  // every wave has left the stages
+    bf16 *outk = dqkv + (row0 + kvw0) * ld + h + (int64_t)n * kD;
+    store_rows_via_lds(acck, scale, smem + wave * 16384, outk, ld, lane);
+    store_rows_via_lds(accv, 1.0f, smem + wave * 16384 + 8192, outk + h, ld, lane);
 }
 
 bool attn_mfma_supported(int64_t seq, int64_t d) { return d == kD && seq % 128 == 0 && seq >= 128; }
@@ -897,7 +970,7 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
     if (b * seq == 0) return hipSuccess;
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
-    const int chunk = chunk_slots(seq / 128, nh * b, 1);
+    const int chunk = chunk_slots(seq / 128, nh * b);
     // Up to two work-groups per CU's worth of work: the eight-wave kernel (a work-group's chain of intervals is
     // half as long); beyond: the four-wave kernel, two work-groups per CU, where one's prologue and epilogue
     // hide behind the other's tiles (measured at 32 heads x 2048: 54.0 against 57.0 us for 512 work-groups,
@@ -925,18 +998,18 @@ hipError_t launch_attn_bwd(int dt, const void *qkv, const void *attn, const void
     if (b * seq == 0) return hipSuccess;
     const float scale = 1.0f / sqrtf((float)d);
     const float scale_log2e = scale * 1.44269504088896340736f;
-    constexpr size_t lds_dq = 4 * kTileBytes;             // two stages of (K tile, V tile)
-    constexpr size_t lds_dkv = 4 * kTileBytes + 2 * 512;  // two stages of (Q tile, dO tile) + lse/delta
+    constexpr size_t lds_dq = 4 * kTileBytes;            // two stages of (K tile, V tile)
+    constexpr size_t lds_dkv = kFStages * kFStageBytes;  // four stages of (Q tile, dO tile, statistics)
     static bool a1 = false, a2 = false;
     if (hipError_t e = set_lds(attn_bwd_dq_w4_kernel, lds_dq, a1)) return e;
-    if (hipError_t e = set_lds(attn_bwd_dkv_w4_kernel, lds_dkv, a2)) return e;
+    if (hipError_t e = set_lds(attn_bwd_dkv_kernel, lds_dkv, a2)) return e;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
+    const int chunk = chunk_slots(seq / 128, nh * b);
     attn_bwd_dq_w4_kernel<<<dim3(blocks), 256, lds_dq, s>>>((const bf16 *)qkv, (const bf16 *)attn, (const bf16 *)dattn, lse,
-                                                            delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
-                                                            chunk_slots(seq / 128, nh * b, 1), scale, scale_log2e);
-    attn_bwd_dkv_w4_kernel<<<dim3(2 * blocks), 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, lse, delta,
-                                                                  (bf16 *)dqkv, (int)seq, (int)nh, (int)b,
-                                                                  chunk_slots(seq / 128, nh * b, 2), scale, scale_log2e);
+                                                            delta, (bf16 *)dqkv, (int)seq, (int)nh, (int)b, chunk, scale,
+                                                            scale_log2e);
+    attn_bwd_dkv_kernel<<<dim3(blocks), 256, lds_dkv, s>>>((const bf16 *)qkv, (const bf16 *)dattn, delta, (bf16 *)dqkv,
+                                                           (int)seq, (int)nh, (int)b, chunk, scale, scale_log2e);
     return hipGetLastError();
 }
 
