@@ -713,6 +713,20 @@ constexpr int kFRingA = 4, kFRingB = 4;
 // part of half TV of the tile whose statistics lie at `stat`, from its scores and dP in (sv, dv), to the operands
 // (pf, dsf) of the second products.  MASK (the first two tiles of a key block): elements with in-tile query index
 // (less 4 g) below qlim are masked.
+// A matrix instruction whose accumulator is kept in ordinary vector registers.  In a kernel that may use more than
+// 256 registers the compiler gives every matrix instruction an accumulator in the second register file, and the
+// element-wise code then pays one copy instruction per value it reads; written out, the S and dP accumulators stay
+// where the vector unit reads them.  The compiler inserts no wait states around these, so results may only be
+// read a phase (sixteen matrix instructions) later, which is how the kernel below is arranged anyway.
+__device__ __forceinline__ void mfma_v_first(f32x16 &acc, const bf16x8 &a, const bf16x8 &b)
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v(f32x16 &acc, const bf16x8 &a, const bf16x8 &b)
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
 template <bool WITH_A, bool MASK, int TA, int TV>
 __device__ __forceinline__ void dkv_scores_and_elementwise(f32x16 &sa, f32x16 &da, const f32x16 &sv, const f32x16 &dv,
                                                            bf16x8 (&pf)[2], bf16x8 (&dsf)[2], const unsigned char *ta,
@@ -731,48 +745,51 @@ __device__ __forceinline__ void dkv_scores_and_elementwise(f32x16 &sa, f32x16 &d
             qr[i] = rd_row(ta, ad, TA, i);
             dr[i] = rd_row(ta + kTileBytes, ad, TA, i);
         }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            sa[e] = 0.0f;
-            da[e] = 0.0f;
-        }
     }
     __builtin_amdgcn_sched_barrier(0);
-    float p_prev = 0.0f, d_prev = 0.0f;
+    float x0 = 0.0f, x1 = 0.0f, e0 = 0.0f, t0 = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         if constexpr (WITH_A) {
             const int k = i >> 1;
             if ((i & 1) == 0) {
-                sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[k % kFRingA], kf[k], sa, 0, 0, 0);
+                if (k == 0) mfma_v_first(sa, qr[0], kf[0]);
+                else mfma_v(sa, qr[k % kFRingA], kf[k]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (k + kFRingA < 8) qr[k % kFRingA] = rd_row(ta, ad, TA, k + kFRingA);
             } else {
-                da = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dr[k % kFRingA], vf[k], da, 0, 0, 0);
+                if (k == 0) mfma_v_first(da, dr[0], vf[0]);
+                else mfma_v(da, dr[k % kFRingA], vf[k]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (k + kFRingA < 8) dr[k % kFRingA] = rd_row(ta + kTileBytes, ad, TA, k + kFRingA);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // element i of half TV: query 32 TV + 8 (i / 4) + 4 g + i % 4 of the tile
+        // elements i - 1 and i (a pair) of half TV: query 32 TV + 8 (e / 4) + 4 g + e % 4 of the tile.  The pair's
+        // work is spread over the two slots so that no instruction uses the result of the one before it.
         if ((i & 3) == 0 && i + 4 < 16) {
             l4[((i >> 2) + 1) & 1] = *reinterpret_cast<const f32x4 *>(stat + 32 * TV + 8 * ((i >> 2) + 1) + 4 * g);
             d4[((i >> 2) + 1) & 1] = *reinterpret_cast<const f32x4 *>(stat + 64 + 32 * TV + 8 * ((i >> 2) + 1) + 4 * g);
         }
-        float sm = sv[i];
-        if constexpr (MASK) {
-            if (qlim > 32 * TV + 8 * (i >> 2) + (i & 3)) sm = -INFINITY;
-        }
-        const float pe = fast_exp2(__builtin_fmaf(sm, scale_log2e, -l4[(i >> 2) & 1][i & 3]));
-        const float de = pe * (dv[i] - d4[(i >> 2) & 1][i & 3]);
-        if (i & 1) {
-            pf[i >> 3][(i & 7) - 1] = (bf16)p_prev;
-            pf[i >> 3][i & 7] = (bf16)pe;
-            dsf[i >> 3][(i & 7) - 1] = (bf16)d_prev;
-            dsf[i >> 3][i & 7] = (bf16)de;
+        if ((i & 1) == 0) {
+            float sm0 = sv[i], sm1 = sv[i + 1];
+            if constexpr (MASK) {
+                if (qlim > 32 * TV + 8 * (i >> 2) + (i & 3)) sm0 = -INFINITY;
+                if (qlim > 32 * TV + 8 * (i >> 2) + (i & 3) + 1) sm1 = -INFINITY;
+            }
+            x0 = __builtin_fmaf(sm0, scale_log2e, -l4[(i >> 2) & 1][i & 3]);
+            x1 = __builtin_fmaf(sm1, scale_log2e, -l4[(i >> 2) & 1][(i & 3) + 1]);
+            t0 = dv[i] - d4[(i >> 2) & 1][i & 3];
+            e0 = fast_exp2(x0);
         } else {
-            p_prev = pe;
-            d_prev = de;
+            const float e1 = fast_exp2(x1);
+            const float t1 = dv[i] - d4[(i >> 2) & 1][i & 3];
+            const float m0 = e0 * t0;
+            pf[i >> 3][(i & 7) - 1] = (bf16)e0;
+            pf[i >> 3][i & 7] = (bf16)e1;
+            const float m1 = e1 * t1;
+            dsf[i >> 3][(i & 7) - 1] = (bf16)m0;
+            dsf[i >> 3][i & 7] = (bf16)m1;
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -895,14 +912,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     {
         // S and dP of the first half tile, nothing to overlap with yet
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            s0[e] = 0.0f;
-            p0[e] = 0.0f;
-        }
-#pragma unroll
         for (int k = 0; k < 8; ++k) {
-            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(smem, ad, 0, k), kf[k], s0, 0, 0, 0);
-            p0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rd_row(smem + kTileBytes, ad, 0, k), vf[k], p0, 0, 0, 0);
+            const bf16x8 qa = rd_row(smem, ad, 0, k), da = rd_row(smem + kTileBytes, ad, 0, k);
+            if (k == 0) {
+                mfma_v_first(s0, qa, kf[0]);
+                mfma_v_first(p0, da, vf[0]);
+            } else {
+                mfma_v(s0, qa, kf[k]);
+                mfma_v(p0, da, vf[k]);
+            }
         }
     }
     const int qlim0 = kvw0 + c - it0 * kTile - 4 * g;
