@@ -117,7 +117,7 @@ struct F32Rows {
 constexpr int epi_stride(int NT) { return NT * 32 + 8; }  // floats; 4 rows apart = half the banks apart
 
 template <int MT, int NT, class Put>
-__device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, int wave, int lane,
+__device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, int n_waves, int wave, int lane,
                                               void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
                                               int64_t N, int64_t m_wave, int64_t n_wave)
 {
@@ -131,6 +131,31 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
                         (!epi.resid || reinterpret_cast<uintptr_t>(epi.resid) % 16 == 0) &&
                         (!epi.aux || reinterpret_cast<uintptr_t>(epi.aux) % 16 == 0) &&
                         (!epi.out2 || reinterpret_cast<uintptr_t>(epi.out2) % 16 == 0);
+    // The bf16 side input of the element-wise tail (the residual, or the pre-activation of the GeLU derivative)
+    // is fetched one 32-row group ahead with direct-to-LDS copies, pass p of a group by the p-th copy, so that each
+    // lane later reads back from LDS exactly the 16 bytes it asked for: the loop over the passes stays a loop (no
+    // registers indexed by it), and the memory latency is met once per tile instead of once per pass (sixteen
+    // times per wave tile, the bulk of what these epilogues cost before).  Two 32-row buffers per wave after the
+    // staging slices.
+    const bf16 *side = epi.act == ACT_DGELU_MUL ? epi.aux : epi.resid;
+    const bool side_dma = side && vec_ok && !epi.out_f32 && !(epi.act == ACT_DGELU_MUL && epi.resid) &&
+                          m_wave + MT * 32 <= M && n_wave + WN <= N && 32 * ldc * 2 < ((int64_t)1 << 31);
+    unsigned char *side_buf = smem_raw + n_waves * (32 * STRIDE * 4) + wave * (2 * 32 * WN * 2);
+    const uint32_t side_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)side_buf;
+    const uint32_t side_voff = (uint32_t)(((lane / CH) * ldc + (lane % CH) * 8) * 2);
+    const char *side_base = reinterpret_cast<const char *>(side + m_wave * ldc + n_wave);
+    auto side_issue = [&](int grp) {
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const uint32_t dst = side_lds + (grp & 1) * (32 * WN * 2) + p * 1024;
+            const char *src = side_base + (int64_t)(grp * 32 + p * ROWS_PER_PASS) * ldc * 2;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(dst), "v"(side_voff), "s"(src)
+                         : "memory");
+        }
+    };
+    if (side_dma) side_issue(0);
     F32Rows<NT> fr;
     fr.init(Cv, ldc, epi, M, N, m_wave, n_wave, lane);
     constexpr int ROWS4 = F32Rows<NT>::ROWS4, PASSES4 = F32Rows<NT>::PASSES4;
@@ -152,6 +177,12 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
         // the slice is private to this wave; LDS operations of a wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (side_dma) {
+            // this group's side input has landed (and the stores of the group before are out); the next group's
+            // goes into the other buffer while this one is worked on
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if constexpr (i + 1 < MT) side_issue(i + 1);
+        }
         if (accum) {
 #pragma unroll
             for (int p = 0; p < PASSES4; ++p) {
@@ -196,13 +227,15 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
             if (m >= M || n >= N) continue;
             const int64_t o_idx = m * ldc + n;
             if (vec_ok && n + 8 <= N) {
+                bf16x8 sv;
+                if (side_dma) sv = *reinterpret_cast<const bf16x8 *>(side_buf + (i & 1) * (32 * WN * 2) + p * 1024 + lane * 16);
                 if (epi.resid) {
-                    const bf16x8 r = *reinterpret_cast<const bf16x8 *>(epi.resid + o_idx);
+                    const bf16x8 r = (side_dma && epi.act != ACT_DGELU_MUL) ? sv : *reinterpret_cast<const bf16x8 *>(epi.resid + o_idx);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) v[k] += (float)r[k];
                 }
                 if (epi.act == ACT_DGELU_MUL) {
-                    const bf16x8 u = *reinterpret_cast<const bf16x8 *>(epi.aux + o_idx);
+                    const bf16x8 u = side_dma ? sv : *reinterpret_cast<const bf16x8 *>(epi.aux + o_idx);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) v[k] *= gelu_bwd((float)u[k], epi.gelu_mode);
                 }
@@ -238,7 +271,7 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
 // v_mfma_f32_32x32x16_bf16 accumulators: acc[i][j][e] of lane l is
 // C[m_wave + i*32 + (e/4)*8 + (l/32)*4 + e%4, n_wave + j*32 + l%32].
 template <int MT, int NT>
-__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int wave, int lane,
+__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int n_waves, int wave, int lane,
                                          void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
                                          int64_t N, int64_t m_wave, int64_t n_wave)
 {
@@ -260,13 +293,13 @@ __device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *s
                     stage[((e >> 2) * 8 + khalf * 4 + (e & 3)) * STRIDE + j * 32 + c32] = acc[i][j][e] + bias[j];
             });
         },
-        smem_raw, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
+        smem_raw, n_waves, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
 }
 
 // v_mfma_f32_16x16x32_bf16 accumulators: acc[i][j][e] of lane l is
 // C[m_wave + i*16 + (l/16)*4 + e, n_wave + j*16 + l%16].
 template <int MA, int NB>
-__device__ __forceinline__ void epilogue16(f32x4 (&acc)[MA][NB], unsigned char *smem_raw, int wave, int lane,
+__device__ __forceinline__ void epilogue16(f32x4 (&acc)[MA][NB], unsigned char *smem_raw, int n_waves, int wave, int lane,
                                            void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
                                            int64_t N, int64_t m_wave, int64_t n_wave)
 {
@@ -292,7 +325,7 @@ __device__ __forceinline__ void epilogue16(f32x4 (&acc)[MA][NB], unsigned char *
                 });
             });
         },
-        smem_raw, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
+        smem_raw, n_waves, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
 }
 
 // Which tile a work-group computes.  Work-group ids are dealt round-robin over the 8 XCDs (one L2 each):
@@ -640,7 +673,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();  // nobody reads operand tiles any more: LDS becomes the epilogue's staging area
 
-    epilogue16<MA, NB>(acc, smem_raw, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
+    epilogue16<MA, NB>(acc, smem_raw, WGM * WGN, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
 // One launch wrapper for every instantiation: raises the kernel's dynamic LDS limit once per process (guarded, so
@@ -666,8 +699,13 @@ static hipError_t launch_kernel(int64_t M, int64_t N, int64_t K, const bf16 *A, 
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
+    // LDS: the operand ring, or what the epilogue lays over it: per wave a 32-row staging slice of the wave tile in
+    // fp32 and two 32-row buffers of a bf16 side input
+    constexpr int WN = BN / WGN;
+    constexpr size_t ring = (size_t)NS * (BM + BN) * kBK * sizeof(bf16);
+    constexpr size_t epi = (size_t)WGM * WGN * (32 * epi_stride(WN / 32) * 4 + 2 * 32 * WN * 2);
     return launch_tiles(gemm_bf16_kernel<A_KMAJOR, B_KMAJOR, BM, BN, WGM, WGN, NS, SPLIT>, once, attr_err, BM, BN,
-                        WGM * WGN * 64, (size_t)NS * (BM + BN) * kBK * sizeof(bf16), M, N, K, A, lda, B, ldb, C, ldc, e, s);
+                        WGM * WGN * 64, ring > epi ? ring : epi, M, N, K, A, lda, B, ldb, C, ldc, e, s);
 }
 
 static EpiBf16 bf16_epilogue(const GemmEpi &epi)
