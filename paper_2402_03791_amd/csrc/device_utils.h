@@ -104,5 +104,19 @@ __device__ __forceinline__ float gelu_bwd(float u, int mode)
     const float zp = __builtin_fmaf(c2 * 3.0f * 0.044715f, u * u, c2);
     return g.s * __builtin_fmaf(u * g.one_minus_s, zp, 1.0f);
 }
+// Both at once, from one logistic function: the same operations as gelu_fwd and gelu_bwd, so the same bits.
+__device__ __forceinline__ void gelu_both(float u, int mode, float &val, float &der)
+{
+    if (mode == 1) {
+        val = gelu_fwd(u, 1);
+        der = gelu_bwd(u, 1);
+        return;
+    }
+    const float c2 = 2.0f * 0.79788456080286535588f;
+    const GeluLogistic g(u);
+    const float zp = __builtin_fmaf(c2 * 3.0f * 0.044715f, u * u, c2);
+    val = u * g.s;
+    der = g.s * __builtin_fmaf(u * g.one_minus_s, zp, 1.0f);
+}
 
 }  // namespace zpp

@@ -52,15 +52,24 @@ __device__ __forceinline__ void static_for(F &&f)
 __device__ __forceinline__ void epi_store_one(float v, int64_t o_idx, void *__restrict__ Cv, const EpiBf16 &epi)
 {
     if (epi.resid) v += (float)epi.resid[o_idx];
-    if (epi.act == ACT_DGELU_MUL) v *= gelu_bwd((float)epi.aux[o_idx], epi.gelu_mode);
+    if (epi.act == ACT_DGELU_MUL) v *= (float)(bf16)gelu_bwd((float)epi.aux[o_idx], epi.gelu_mode);
+    if (epi.act == ACT_MUL_AUX) v *= (float)epi.aux[o_idx];
     if (epi.out_f32) {
         float *c = reinterpret_cast<float *>(Cv) + o_idx;
         *c = epi.out_f32 == 2 ? grad_accum(*c, epi.accum_scale, v) : v;
     } else {
         const bf16 o = (bf16)v;
-        reinterpret_cast<bf16 *>(Cv)[o_idx] = o;
-        // the activation is applied to the value that was stored (and that backward re-reads)
-        if (epi.act == ACT_GELU_DUAL) epi.out2[o_idx] = (bf16)gelu_fwd((float)o, epi.gelu_mode);
+        // the activation (and its derivative) is applied to the rounded pre-activation, the value that is stored
+        // and re-read where it is kept
+        if (epi.act == ACT_GELU_GRAD_DUAL) {
+            float val, der;
+            gelu_both((float)o, epi.gelu_mode, val, der);
+            reinterpret_cast<bf16 *>(Cv)[o_idx] = (bf16)der;
+            epi.out2[o_idx] = (bf16)val;
+        } else {
+            reinterpret_cast<bf16 *>(Cv)[o_idx] = o;
+            if (epi.act == ACT_GELU_DUAL) epi.out2[o_idx] = (bf16)gelu_fwd((float)o, epi.gelu_mode);
+        }
     }
 }
 
@@ -82,7 +91,7 @@ struct F32Rows {
                                          int64_t m_wave, int64_t n_wave, int lane)
     {
         ok = epi.out_f32 && (ldc % 8 == 0) && (reinterpret_cast<uintptr_t>(Cv) % 16 == 0) && !epi.resid &&
-             epi.act == ACT_NONE;
+             epi.act == ACT_NONE;  // (the activation modes are for bf16 outputs)
         accum = ok && epi.out_f32 == 2;
         row4 = lane / CH4;
         c4 = lane % CH4;
@@ -137,8 +146,9 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
     // registers indexed by it), and the memory latency is met once per tile instead of once per pass (sixteen
     // times per wave tile, the bulk of what these epilogues cost before).  Two 32-row buffers per wave after the
     // staging slices.
-    const bf16 *side = epi.act == ACT_DGELU_MUL ? epi.aux : epi.resid;
-    const bool side_dma = side && vec_ok && !epi.out_f32 && !(epi.act == ACT_DGELU_MUL && epi.resid) &&
+    const bool mul_side = epi.act == ACT_DGELU_MUL || epi.act == ACT_MUL_AUX;
+    const bf16 *side = mul_side ? epi.aux : epi.resid;
+    const bool side_dma = side && vec_ok && !epi.out_f32 && !(mul_side && epi.resid) &&
                           m_wave + MT * 32 <= M && n_wave + WN <= N && 32 * ldc * 2 < ((int64_t)1 << 31);
     unsigned char *side_buf = smem_raw + n_waves * (32 * STRIDE * 4) + wave * (2 * 32 * WN * 2);
     const uint32_t side_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)side_buf;
@@ -230,14 +240,19 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
                 bf16x8 sv;
                 if (side_dma) sv = *reinterpret_cast<const bf16x8 *>(side_buf + (i & 1) * (32 * WN * 2) + p * 1024 + lane * 16);
                 if (epi.resid) {
-                    const bf16x8 r = (side_dma && epi.act != ACT_DGELU_MUL) ? sv : *reinterpret_cast<const bf16x8 *>(epi.resid + o_idx);
+                    const bf16x8 r = (side_dma && !mul_side) ? sv : *reinterpret_cast<const bf16x8 *>(epi.resid + o_idx);
 #pragma unroll
                     for (int k = 0; k < 8; ++k) v[k] += (float)r[k];
                 }
-                if (epi.act == ACT_DGELU_MUL) {
+                if (mul_side) {
                     const bf16x8 u = side_dma ? sv : *reinterpret_cast<const bf16x8 *>(epi.aux + o_idx);
+                    if (epi.act == ACT_MUL_AUX) {
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) v[k] *= gelu_bwd((float)u[k], epi.gelu_mode);
+                        for (int k = 0; k < 8; ++k) v[k] *= (float)u[k];
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) v[k] *= (float)(bf16)gelu_bwd((float)u[k], epi.gelu_mode);
+                    }
                 }
                 if (epi.out_f32) {
                     float *cf = reinterpret_cast<float *>(Cv) + o_idx;
@@ -247,12 +262,25 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
                     bf16x8 o;
 #pragma unroll
                     for (int k = 0; k < 8; ++k) o[k] = (bf16)v[k];
-                    *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16 *>(Cv) + o_idx) = o;
-                    if (epi.act == ACT_GELU_DUAL) {
-                        bf16x8 g;
+                    if (epi.act == ACT_GELU_GRAD_DUAL) {
+                        bf16x8 g, d;
 #pragma unroll
-                        for (int k = 0; k < 8; ++k) g[k] = (bf16)gelu_fwd((float)o[k], epi.gelu_mode);
+                        for (int k = 0; k < 8; ++k) {
+                            float val, der;
+                            gelu_both((float)o[k], epi.gelu_mode, val, der);
+                            g[k] = (bf16)val;
+                            d[k] = (bf16)der;
+                        }
+                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16 *>(Cv) + o_idx) = d;
                         *reinterpret_cast<bf16x8 *>(epi.out2 + o_idx) = g;
+                    } else {
+                        *reinterpret_cast<bf16x8 *>(reinterpret_cast<bf16 *>(Cv) + o_idx) = o;
+                        if (epi.act == ACT_GELU_DUAL) {
+                            bf16x8 g;
+#pragma unroll
+                            for (int k = 0; k < 8; ++k) g[k] = (bf16)gelu_fwd((float)o[k], epi.gelu_mode);
+                            *reinterpret_cast<bf16x8 *>(epi.out2 + o_idx) = g;
+                        }
                     }
                 }
             } else {

@@ -9,7 +9,13 @@ namespace zpp {
 enum { DT_F32 = 0, DT_BF16 = 1 };
 enum { NORM_LAYER = 0, NORM_RMS = 1 };
 enum { COLRED_SUM = 0, COLRED_LAYERNORM = 1, COLRED_RMSNORM = 2 };
-enum { ACT_NONE = 0, ACT_GELU_DUAL = 1, ACT_DGELU_MUL = 2 };
+// ACT_GELU_DUAL: C receives the pre-activation u, out2 gelu(u).  ACT_DGELU_MUL: out = acc * gelu'(aux), aux = u.
+// ACT_GELU_GRAD_DUAL (bf16 products): C receives gelu'(u) and out2 gelu(u), u being the pre-activation rounded to
+// bf16 (it is not stored); ACT_MUL_AUX: out = acc * aux.  The pair moves the derivative's arithmetic from the
+// backward epilogue, where it would be evaluated alone, into the forward one, where it shares the logistic function
+// with the activation.  In bf16 ACT_DGELU_MUL multiplies by the derivative rounded to bf16, so that both pairs
+// give the same bits.
+enum { ACT_NONE = 0, ACT_GELU_DUAL = 1, ACT_DGELU_MUL = 2, ACT_GELU_GRAD_DUAL = 3, ACT_MUL_AUX = 4 };
 
 inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
@@ -37,8 +43,8 @@ hipError_t launch_adam_ranges(float *P, float *M, float *V, float *G, AdamRanges
 struct GemmEpi {
     const void *bias = nullptr;   // [N], element type of the compute dtype, or null
     const void *resid = nullptr;  // [M, ldc], element type of the compute dtype, or null
-    void *out2 = nullptr;         // ACT_GELU_DUAL: receives gelu(out) while C receives out
-    const void *aux = nullptr;    // ACT_DGELU_MUL: pre-activation u[m,n]; out = acc * gelu'(u)
+    void *out2 = nullptr;         // ACT_GELU_DUAL, ACT_GELU_GRAD_DUAL: receives gelu(u)
+    const void *aux = nullptr;    // ACT_DGELU_MUL: pre-activation u[m,n]; ACT_MUL_AUX: the factor itself
     int act = ACT_NONE;
     int gelu_mode = 0;
     int out_f32 = 0;              // 1: C is float regardless of the compute dtype (weight gradients);

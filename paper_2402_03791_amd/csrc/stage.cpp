@@ -184,6 +184,9 @@ struct zpp_stage {
         Tc = (int64_t)count * T;
         bc = (int64_t)count * c.micro_batch;
     }
+    // whether the first MLP product stores its pre-activation (fp32 stages; selective recomputation) or the
+    // activation's derivative in its place
+    bool keeps_preactivation() const { return dt != DT_BF16 || c.recompute == ZPP_RECOMPUTE_SELECTIVE; }
     float *red_slot() const
     {
         return (float *)(ws + tmp.at("redpool").off) + finish.size() * red_floats * (uint64_t)cur_count;
@@ -839,7 +842,9 @@ zpp_status forward_block(zpp_stage *s, int32_t mb, int blk, const void *xin, boo
     if (gpt) {
         GemmEpi e_1;
         e_1.bias = s->Wp(blk, "mlp.b1");
-        e_1.act = ACT_GELU_DUAL;
+        // bf16: the slot "u" of the stash receives gelu'(u) instead of u, which nothing but the derivative needs -
+        // unless selective recomputation is to rebuild the activation's output from u
+        e_1.act = s->keeps_preactivation() ? ACT_GELU_DUAL : ACT_GELU_GRAD_DUAL;
         e_1.out2 = g;
         e_1.gelu_mode = s->c.gelu_mode;
         ZPP_TRY(linear_fwd(s, n2, blk, "mlp.w1", h, f, u, e_1, st));
@@ -1029,7 +1034,7 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int32_t count, int tasks,
             if (do_w) ZPP_TRY(linear_dw(s, dcur, g, blk, "mlp.w2", "mlp.b2", f, h, st));
             if (do_in) {
                 GemmEpi e;
-                e.act = ACT_DGELU_MUL;
+                e.act = s->keeps_preactivation() ? ACT_DGELU_MUL : ACT_MUL_AUX;
                 e.aux = u;
                 e.gelu_mode = s->c.gelu_mode;
                 ZPP_TRY(linear_dx(s, dcur, blk, "mlp.w2", f, h, du, e, st));
