@@ -5,6 +5,7 @@
 #include "kernels.h"
 
 #include <climits>
+#include <type_traits>
 
 namespace zpp {
 
@@ -220,8 +221,52 @@ __global__ __launch_bounds__(256) void colreduce_stage1(const T *__restrict__ a,
     colreduce_tile<T, MODE>(a, x, mean, rstd, rows, C, ld, partial, blockIdx.x, blockIdx.y, gridDim.y);
 }
 
+// The first level of the gain/offset reduction of a norm for bf16 matrices whose width is a multiple of 512, with
+// 16-byte loads: a work-group takes kColRows rows x 512 columns, a lane eight adjacent columns, the four waves every
+// fourth row; the four partial sums per column meet in LDS and one partial row (two for LayerNorm) goes out, in the
+// layout of colreduce_tile.  (With one 2-byte element per lane the column part of the launch below cost more
+// than its row part.)
+template <int KIND>
+__device__ __forceinline__ void norm_colreduce_wide_tile(const bf16 *__restrict__ dn, const bf16 *__restrict__ x,
+                                                         const float *__restrict__ mean, const float *__restrict__ rstd,
+                                                         int64_t rows, int64_t C, float *__restrict__ partial, int bx,
+                                                         int by, int rc)
+{
+    __shared__ float red[2][4][512];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t c = (int64_t)bx * 512 + tx * 8;
+    const int64_t r0 = (int64_t)by * kColRows;
+    const int64_t r1 = (r0 + kColRows < rows) ? r0 + kColRows : rows;
+    float s0[8], s1[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s0[k] = s1[k] = 0.0f;
+    for (int64_t r = r0 + ty; r < r1; r += 4) {
+        const bf16x8 d = *reinterpret_cast<const bf16x8 *>(dn + r * C + c);
+        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(x + r * C + c);
+        const float mu = KIND == NORM_LAYER ? mean[r] : 0.0f, rs = rstd[r];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float dk = (float)d[k];
+            s0[k] += dk * (((float)v[k] - mu) * rs);
+            s1[k] += dk;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        red[0][ty][tx * 8 + k] = s0[k];
+        if (KIND == NORM_LAYER) red[1][ty][tx * 8 + k] = s1[k];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 512; i += 256) {
+        const int64_t at = (int64_t)by * C + (int64_t)bx * 512 + i;
+        partial[at] = (red[0][0][i] + red[0][1][i]) + (red[0][2][i] + red[0][3][i]);
+        if (KIND == NORM_LAYER) partial[(int64_t)rc * C + at] = (red[1][0][i] + red[1][1][i]) + (red[1][2][i] + red[1][3][i]);
+    }
+}
+
 // Norm backward and the first level of its gain/offset gradient reduction in one launch: both read dn and
-// x and neither depends on the other.  Work-groups [0, nrow) take rows, the rest column tiles.
+// x and neither depends on the other.  Work-groups [0, nrow) take rows, the rest column tiles (tiles_c of them per
+// group of kColRows rows; wide: 512 columns each, through the 16-byte path).
 template <class T, int KIND>
 __global__ __launch_bounds__(256) void norm_bwd_colreduce_kernel(const T *__restrict__ dn, const T *__restrict__ x,
                                                                  const float *__restrict__ mean,
@@ -229,11 +274,18 @@ __global__ __launch_bounds__(256) void norm_bwd_colreduce_kernel(const T *__rest
                                                                  const T *__restrict__ gamma,
                                                                  const T *__restrict__ resid, T *__restrict__ dx,
                                                                  int64_t rows, int64_t h, int nrow, int tiles_c,
-                                                                 int rc, float *__restrict__ partial)
+                                                                 int rc, float *__restrict__ partial, bool wide)
 {
     const int id = blockIdx.x;
     if (id < nrow) {
         norm_bwd_rows<T, KIND>(dn, x, mean, rstd, gamma, resid, dx, rows, h, id);
+    } else if constexpr (std::is_same<T, bf16>::value) {
+        const int j = id - nrow;
+        if (wide)
+            norm_colreduce_wide_tile<KIND>(dn, x, mean, rstd, rows, h, partial, j % tiles_c, j / tiles_c, rc);
+        else
+            colreduce_tile<T, KIND == NORM_LAYER ? COLRED_LAYERNORM : COLRED_RMSNORM>(dn, x, mean, rstd, rows, h, h,
+                                                                                      partial, j % tiles_c, j / tiles_c, rc);
     } else {
         const int j = id - nrow;
         colreduce_tile<T, KIND == NORM_LAYER ? COLRED_LAYERNORM : COLRED_RMSNORM>(dn, x, mean, rstd, rows, h, h,
@@ -250,13 +302,15 @@ hipError_t launch_norm_bwd_colreduce(int dt, int kind, const void *dn, const voi
     if (T == 0 || h == 0) return hipSuccess;
     if (!defer) return hipErrorInvalidValue;
     const int64_t nrow = (T + kRowsPerBlock - 1) / kRowsPerBlock;
-    const int64_t rc = (T + kColRows - 1) / kColRows, tiles_c = (h + 63) / 64;
+    const bool wide = dt == DT_BF16 && h % 512 == 0 && reinterpret_cast<uintptr_t>(dn) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(x) % 16 == 0;
+    const int64_t rc = (T + kColRows - 1) / kColRows, tiles_c = wide ? h / 512 : (h + 63) / 64;
     if (nrow + rc * tiles_c > INT32_MAX) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)(nrow + rc * tiles_c);
 #define ZPP_LAUNCH(TT, KK)                                                                                   \
     norm_bwd_colreduce_kernel<TT, KK><<<grid, 256, 0, s>>>((const TT *)dn, (const TT *)x, mean, rstd,        \
                                                            (const TT *)gamma, (const TT *)resid, (TT *)dx, T, h, \
-                                                           (int)nrow, (int)tiles_c, (int)rc, partial)
+                                                           (int)nrow, (int)tiles_c, (int)rc, partial, wide)
     if (dt == DT_BF16) {
         if (kind == NORM_LAYER) ZPP_LAUNCH(bf16, NORM_LAYER); else ZPP_LAUNCH(bf16, NORM_RMS);
     } else {
