@@ -293,7 +293,9 @@ void zpp_stage_counters(const zpp_stage *stage, uint64_t *materialize_calls, uin
 
 /* Device address and size of a named region inside the bound workspace:
  *   "W" working copy, "Wt" the transposed copies (may be empty), "S" staging gradients; stash tensors of (micro_batch, block) by name, e.g.
- *   "x", "n1", "qkv", "attn", "lse", "x1", "n2", "u", "g".  elem_bytes is 2 or 4.
+ *   "x", "n1", "qkv", "attn", "lse", "x1", "n2", "u", "g".  elem_bytes is 2 or 4.  ("u", the slot of the first MLP
+ *   product: its pre-activation in fp32 stages and with selective recomputation, else the derivative of the
+ *   activation at it, which is all the backward pass needs of it.)
  * Errors: ZPP_ERR_STATE before bind, ZPP_ERR_ARG for an unknown name or index. */
 zpp_status zpp_stage_region(const zpp_stage *stage, const char *name, int32_t micro_batch, int32_t block,
                             void **ptr, uint64_t *elems, int32_t *elem_bytes);
