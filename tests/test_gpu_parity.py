@@ -893,3 +893,37 @@ def test_mfma_attention_against_oracle(b, s, nh):
     got = to_np(DQKV)
     for i, r in enumerate((dq, dk, dv)):
         assert rel_err(got[:, i * h:(i + 1) * h], merge(r)) <= 1.5e-2, i
+
+@pytest.mark.parametrize("b,bs,s,nh", [(6, 2, 2048, 32), (6, 2, 2048, 24), (10, 2, 1024, 48)])
+def test_mfma_attention_one_launch_of_many_pairs_equals_smaller_launches(b, bs, s, nh):
+    """Launches with more (sample, head) pairs than a chunk walk their work-groups chunk by chunk (whole chunks, or a
+    shorter last one); which work-group computes what must not change any bit: the whole batch in one launch against
+    launches of `bs` samples, which have no more pairs than a chunk (the plain heavy-first order that the oracle
+    tests above cover) and enough work-groups to run the same forward kernel."""
+    print(f"attention mfma chunked b{b} s{s} nh{nh}", flush=True)
+    d = 128
+    h, T = nh * d, b * s
+    assert b % bs == 0 and (s // 128) * nh * bs >= 768 and nh * bs <= max(16, (1024 // (s // 128)) // 16 * 16) < nh * b
+    g = torch.Generator(device="cuda").manual_seed(11)
+    QKV = torch.randn(T, 3 * h, device="cuda", generator=g).to(torch.bfloat16)
+    DA = (0.1 * torch.randn(T, h, device="cuda", generator=g)).to(torch.bfloat16)
+
+    def run(q, da, nb):
+        at = torch.empty(nb * s, h, dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty(nb * nh * s, dtype=torch.float32, device="cuda")
+        delta = torch.empty(2 * lse.numel(), dtype=torch.float32, device="cuda")
+        dq = torch.full_like(q, float("nan"))
+        zpp.op_attention_fwd(q, at, lse, nb, s, nh, d, impl=1)
+        zpp.op_attention_bwd(q, at, da, lse, delta, dq, nb, s, nh, d, impl=1)
+        return at, lse, dq
+
+    at, lse, dq = run(QKV, DA, b)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dq.float()).all())
+    for i in range(0, b, bs):
+        rows = slice(i * s, (i + bs) * s)
+        a1, l1, d1 = run(QKV[rows].contiguous(), DA[rows].contiguous(), bs)
+        torch.cuda.synchronize()
+        assert torch.equal(at[rows].view(torch.int16), a1.view(torch.int16)), i
+        assert torch.equal(lse[i * nh * s:(i + bs) * nh * s], l1), i
+        assert torch.equal(dq[rows].view(torch.int16), d1.view(torch.int16)), i
