@@ -922,6 +922,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
                 mfma_v(p0, da, vf[k]);
             }
         }
+        // these results are read sooner than a phase later (after the first barrier below): spell out the wait
+        // states the compiler would put between a matrix instruction and a reader of its result
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     }
     const int qlim0 = kvw0 + c - it0 * kTile - 4 * g;
     // one tile with the next tile's first half product inside it (the loop bodies), or without (the last tile)

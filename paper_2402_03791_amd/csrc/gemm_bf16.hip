@@ -296,34 +296,6 @@ __device__ __forceinline__ void epilogue_rows(Put put, unsigned char *smem_raw, 
     });
 }
 
-// v_mfma_f32_32x32x16_bf16 accumulators: acc[i][j][e] of lane l is
-// C[m_wave + i*32 + (e/4)*8 + (l/32)*4 + e%4, n_wave + j*32 + l%32].
-template <int MT, int NT>
-__device__ __forceinline__ void epilogue(f32x16 (&acc)[MT][NT], unsigned char *smem_raw, int n_waves, int wave, int lane,
-                                         void *__restrict__ Cv, int64_t ldc, const EpiBf16 &epi, int64_t M,
-                                         int64_t N, int64_t m_wave, int64_t n_wave)
-{
-    constexpr int STRIDE = epi_stride(NT);
-    const int khalf = lane >> 5, c32 = lane & 31;
-    float bias[NT];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const int64_t n = n_wave + j * 32 + c32;
-        bias[j] = (epi.bias && n < N) ? (float)epi.bias[n] : 0.0f;
-    }
-    epilogue_rows<MT, NT>(
-        [&](auto ii, float *stage) {
-            constexpr int i = decltype(ii)::value;
-            static_for<NT>([&](auto jj) {
-                constexpr int j = decltype(jj)::value;
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    stage[((e >> 2) * 8 + khalf * 4 + (e & 3)) * STRIDE + j * 32 + c32] = acc[i][j][e] + bias[j];
-            });
-        },
-        smem_raw, n_waves, wave, lane, Cv, ldc, epi, M, N, m_wave, n_wave);
-}
-
 // v_mfma_f32_16x16x32_bf16 accumulators: acc[i][j][e] of lane l is
 // C[m_wave + i*16 + (l/16)*4 + e, n_wave + j*16 + l%16].
 template <int MA, int NB>
