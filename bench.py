@@ -32,7 +32,26 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, vendor figure
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, vendor figure
-DEFAULT_MB_GROUP = 2        # micro-batches per forward / input-gradient call in the default order of the work
+
+
+def default_mb_group(sh) -> int:
+    """Micro-batches per forward / input-gradient call in the default order of the work: the fewest (two, four or
+    eight, a divisor of U) for which every product of a block over the group's rows is a grid the library runs
+    with its 256 x 256 tile, i.e. a whole number of rounds of one tile per CU (256 CUs) or at least four rounds;
+    two if none does.  The group is one matrix of g * T rows, so g only decides how the tile grids come out:
+    T x h at T = 4096, h = 5120 is 2.5 rounds at g = 2 and 5 at g = 4."""
+    if sh.compute_dtype != 1:
+        return 1                  # the tiny fp32 configuration: one micro-batch at a time
+    widths = (3 * sh.hidden, sh.hidden, sh.ffn * (2 if sh.arch == 1 else 1))
+
+    def whole_rounds(rows):
+        tiles = [((rows + 255) // 256) * ((n + 255) // 256) for n in widths]
+        return all(t >= 256 and (t % 256 == 0 or t >= 1024) for t in tiles)
+
+    for g in (2, 4, 8):
+        if sh.unit_mbs % g == 0 and whole_rounds(g * sh.tokens):
+            return g
+    return 2 if sh.unit_mbs % 2 == 0 else 1
 
 
 def model_flops_per_unit(sh) -> float:
@@ -91,10 +110,10 @@ def hbm_large_shard(zpp, torch, synth, stream):
 
 
 def time_default_step(zpp, torch, synth, sh, steps, warmup, stream):
-    """The default order of the work (materialise, forward and input-gradient tasks in groups of DEFAULT_MB_GROUP
+    """The default order of the work (materialise, forward and input-gradient tasks in groups of default_mb_group()
     micro-batches, the unit's weight-gradient tasks as one grouped task, Adam with zero_grad and write-back) on
     another workload; whole-step figures only."""
-    U, T, g = sh.unit_mbs, sh.tokens, DEFAULT_MB_GROUP
+    U, T, g = sh.unit_mbs, sh.tokens, default_mb_group(sh)
     st = zpp.Stage(sh, device="cuda:0", split_backward=U, group_mbs=g)
     P0 = synth.make_params(sh, st.layout())
     st.P.copy_(torch.from_numpy(P0))
@@ -244,9 +263,10 @@ def main():
     ap.add_argument("--recompute", nargs="?", const="full", default="none", choices=("none", "full", "selective"),
                     help="activation recomputation: full (keep only block inputs, run each block's forward again in "
                          "backward) or selective (rebuild only the norm and activation outputs)")
-    ap.add_argument("--mb-group", type=int, default=DEFAULT_MB_GROUP,
+    ap.add_argument("--mb-group", type=int, default=0,
                     help="micro-batches per forward / input-gradient (or fused backward) call: stage_forward_group etc. "
-                         "run every linear layer once over this many micro-batches")
+                         "run every linear layer once over this many micro-batches; 0 = the fewest that give whole "
+                         "rounds of 256 x 256 tiles (default_mb_group), one where the other options need one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large-shard", action="store_true",
                     help="skip the Adam / accumulate bandwidth leg on the wide configuration's 1.61e9-element shard")
@@ -277,12 +297,17 @@ def main():
     args.recompute = {"none": 0, "full": 1, "selective": 2}[args.recompute]
     if args.recompute:
         args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
+    auto_mb_group = args.mb_group == 0
+    if auto_mb_group:
+        args.mb_group = default_mb_group(sh) if V == 1 and args.accumulate == "in_place" else 1
     if sh.compute_dtype != 1:
         args.mb_group = 1             # the tiny fp32 configuration: one micro-batch at a time
     if args.backward != "split" or sh.compute_dtype != 1:
         args.group = 1
     elif args.group == 0:
         args.group = sh.unit_mbs
+    if auto_mb_group and args.backward == "split" and args.group % args.mb_group:
+        args.mb_group = 1
     if args.group > 1 and args.accumulate != "in_place":
         print("--group > 1 adds into G in place: not with --accumulate separate", file=sys.stderr)
         sys.exit(2)
@@ -473,7 +498,7 @@ def main():
     bf16 = sh.compute_dtype == 1
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     default_order = (V == 1 and args.backward == "split" and args.group == sh.unit_mbs and not args.recompute
-                     and mg == DEFAULT_MB_GROUP
+                     and mg == default_mb_group(sh)
                      and args.accumulate == "in_place" and args.adam == "uniform")
     kv = profile_kv()
 

@@ -35,6 +35,16 @@ zpp_status zpp_op_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
 zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, int32_t out_f32, void *hip_stream);
 
+/* n (1..8) such products with the same K and the same kind of C as one launch: the weight-gradient products of
+ * a block (Section 2.3) taken together, as the stage issues them, so that the grid is all their tiles back to
+ * back and a product whose tiles do not fill the last round of one tile per CU shares that round with the next
+ * product.  M, N, A, lda, B, ldb, C, ldc are host arrays of n entries (device pointers inside A, B, C); the
+ * outputs must not overlap.  Each product's requirements and errors are those of zpp_op_gemm_bf16_tt, and every
+ * C element gets the bits that call gives it. */
+zpp_status zpp_op_gemm_bf16_tt_group(int32_t n, const int64_t *M, const int64_t *N, int64_t K, const void *const *A,
+                                     const int64_t *lda, const void *const *B, const int64_t *ldb, void *const *C,
+                                     const int64_t *ldc, int32_t out_f32, void *hip_stream);
+
 /* The input-gradient product of Section 2.3 read from the weights as they are stored: C[M,N] = A . B with A
  * [M, K] (K contiguous, leading dimension lda >= K) and B [K, N] (N contiguous, leading dimension ldb >= N),
  * i.e. dX[T,in] = dY[T,out] . W[out,in] without a transposed copy of W.  bf16 operands, fp32 accumulation; C

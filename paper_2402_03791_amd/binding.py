@@ -20,7 +20,7 @@ EXPORTS = [
     "zpp_stage_end_unit",
     "zpp_stage_counters", "zpp_stage_region", "zpp_last_error", "zpp_version",
     "zpp_profile_enable", "zpp_profile_reset", "zpp_profile_read",
-    "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_gemm_bf16_nn", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
+    "zpp_op_gemm_bf16_nt", "zpp_op_gemm_bf16_tt", "zpp_op_gemm_bf16_tt_group", "zpp_op_gemm_bf16_nn", "zpp_op_attention_fwd", "zpp_op_attention_bwd", "zpp_op_flat_adam",
     "zpp_op_flat_accumulate", "zpp_op_flat_materialize", "zpp_op_attention_bwd_noalloc",
     "zpp_op_attention_bwd_noalloc_max_rows",
     "zpp_device_create", "zpp_device_create_per_stage", "zpp_device_destroy", "zpp_device_stage_count", "zpp_device_param_count",
@@ -149,6 +149,7 @@ def load_library(path: str | None = None):
     L.zpp_op_gemm_bf16_nt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp, vp, i32, i32, vp]
     L.zpp_op_gemm_bf16_tt.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
     L.zpp_op_gemm_bf16_nn.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, i32, vp]
+    L.zpp_op_gemm_bf16_tt_group.argtypes = [i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, i32, vp]
     L.zpp_op_attention_fwd.argtypes = [i32, i32, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
     L.zpp_op_attention_bwd_noalloc.argtypes = [i32, i32, vp, vp, vp, vp, vp, i64, i64, i64, i64, vp]
@@ -548,6 +549,22 @@ def op_gemm_bf16_tt(A, B, C, stream=None, accumulate: bool = False):
                                      C.stride(0), 2 if accumulate else int(C.dtype == torch.float32),
                                      _stream_ptr(stream)))
     return C
+
+
+def op_gemm_bf16_tt_group(As, Bs, Cs, stream=None, accumulate: bool = False):
+    """op_gemm_bf16_tt for several (A, B, C) with the same K and the same kind of C, as one launch."""
+    import torch
+    n = len(As)
+    K = As[0].shape[0]
+    if any(a.shape[0] != K or b.shape[0] != K for a, b in zip(As, Bs)) or any(c.dtype != Cs[0].dtype for c in Cs):
+        raise ValueError("the products of a group share K and the output type")
+    i64, ptr = ctypes.c_int64 * n, ctypes.c_void_p * n
+    _check(lib().zpp_op_gemm_bf16_tt_group(
+        n, i64(*[a.shape[1] for a in As]), i64(*[b.shape[1] for b in Bs]), K, ptr(*[a.data_ptr() for a in As]),
+        i64(*[a.stride(0) for a in As]), ptr(*[b.data_ptr() for b in Bs]), i64(*[b.stride(0) for b in Bs]),
+        ptr(*[c.data_ptr() for c in Cs]), i64(*[c.stride(0) for c in Cs]),
+        2 if accumulate else int(Cs[0].dtype == torch.float32), _stream_ptr(stream)))
+    return Cs
 
 
 def op_gemm_bf16_nn(A, B, C, stream=None, accumulate: bool = False):

@@ -493,9 +493,9 @@ struct KMajorSide {
 };
 
 template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT>
-__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
-    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
-    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+__device__ __forceinline__ void gemm_bf16_tile(int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda,
+                                               const bf16 *__restrict__ B, int64_t ldb, void *__restrict__ Cv,
+                                               int64_t ldc, const EpiBf16 &epi, int tiles_m, int tiles_n, int pid)
 {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -517,7 +517,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
     int tm, tn;
-    tile_of_workgroup(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    tile_of_workgroup(pid, tiles_m, tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
     const int tid = threadIdx.x;
@@ -676,6 +676,44 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
     epilogue16<MA, NB>(acc, smem_raw, WGM * WGN, wave, lane, Cv, ldc, epi, M, N, m0 + wm * WM, n0 + wn * WN);
 }
 
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(
+    int64_t M, int64_t N, int64_t K, const bf16 *__restrict__ A, int64_t lda, const bf16 *__restrict__ B,
+    int64_t ldb, void *__restrict__ Cv, int64_t ldc, EpiBf16 epi, int tiles_m, int tiles_n)
+{
+    gemm_bf16_tile<A_KMAJOR, B_KMAJOR, BM, BN, WGM, WGN, NS, SPLIT>(M, N, K, A, lda, B, ldb, Cv, ldc, epi, tiles_m,
+                                                                    tiles_n, (int)blockIdx.x);
+}
+
+// Several products with the same K and the same epilogue as one grid: the tiles of product p are the work-groups
+// first[p] .. first[p+1]-1.  Every tile takes the same time, so CUs go from one product's last tiles straight to
+// the next one's first, and the launch takes ceil(all tiles / 256) rounds of one tile per CU where one launch per
+// product takes the sum of each product's rounded-up rounds (the four weight-gradient products of a block at
+// hidden 5120, ffn 13824: 19 rounds instead of 21; at hidden 2048, ffn 8192: 3 instead of 4).
+struct GemmGroupBf16 {
+    int n;
+    int first[kGemmGroupMax + 1];
+    struct Problem {
+        int64_t M, N;
+        const bf16 *A, *B;
+        void *C;
+        int64_t lda, ldb, ldc;
+        int tiles_m, tiles_n;
+    } p[kGemmGroupMax];
+};
+
+template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_group_kernel(GemmGroupBf16 g, int64_t K, EpiBf16 epi)
+{
+    const int id = (int)blockIdx.x;
+    int p = 0;
+    for (int i = 1; i < g.n; ++i)
+        if (id >= g.first[i]) p = i;
+    const GemmGroupBf16::Problem &q = g.p[p];
+    gemm_bf16_tile<A_KMAJOR, B_KMAJOR, BM, BN, WGM, WGN, NS, SPLIT>(q.M, q.N, K, q.A, q.lda, q.B, q.ldb, q.C, q.ldc, epi,
+                                                                    q.tiles_m, q.tiles_n, id - g.first[p]);
+}
+
 // One launch wrapper for every instantiation: raises the kernel's dynamic LDS limit once per process (guarded, so
 // that host threads driving different stages may launch concurrently) and starts one work-group per tile.
 template <class Kernel>
@@ -693,19 +731,25 @@ static hipError_t launch_tiles(Kernel kern, std::once_flag &once, hipError_t &at
     return hipGetLastError();
 }
 
+// LDS of a work-group: the operand ring, or what the epilogue lays over it: per wave a 32-row staging slice of the
+// wave tile in fp32 and two 32-row buffers of a bf16 side input
+template <int BM, int BN, int WGM, int WGN, int NS>
+static constexpr size_t gemm_lds_bytes()
+{
+    constexpr int WN = BN / WGN;
+    constexpr size_t ring = (size_t)NS * (BM + BN) * kBK * sizeof(bf16);
+    constexpr size_t epi = (size_t)WGM * WGN * (32 * epi_stride(WN / 32) * 4 + 2 * 32 * WN * 2);
+    return ring > epi ? ring : epi;
+}
+
 template <bool A_KMAJOR, bool B_KMAJOR, int BM, int BN, int WGM, int WGN, int NS, bool SPLIT = false>
 static hipError_t launch_kernel(int64_t M, int64_t N, int64_t K, const bf16 *A, int64_t lda, const bf16 *B, int64_t ldb,
                                 void *C, int64_t ldc, const EpiBf16 &e, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    // LDS: the operand ring, or what the epilogue lays over it: per wave a 32-row staging slice of the wave tile in
-    // fp32 and two 32-row buffers of a bf16 side input
-    constexpr int WN = BN / WGN;
-    constexpr size_t ring = (size_t)NS * (BM + BN) * kBK * sizeof(bf16);
-    constexpr size_t epi = (size_t)WGM * WGN * (32 * epi_stride(WN / 32) * 4 + 2 * 32 * WN * 2);
     return launch_tiles(gemm_bf16_kernel<A_KMAJOR, B_KMAJOR, BM, BN, WGM, WGN, NS, SPLIT>, once, attr_err, BM, BN,
-                        WGM * WGN * 64, ring > epi ? ring : epi, M, N, K, A, lda, B, ldb, C, ldc, e, s);
+                        WGM * WGN * 64, gemm_lds_bytes<BM, BN, WGM, WGN, NS>(), M, N, K, A, lda, B, ldb, C, ldc, e, s);
 }
 
 static EpiBf16 bf16_epilogue(const GemmEpi &epi)
@@ -726,6 +770,36 @@ hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     if (!gemm_bf16_tt_supported(M, N, K, lda, ldb)) return hipErrorInvalidValue;
     return launch_kernel<true, true, 256, 256, 2, 4, 2, true>(M, N, K, (const bf16 *)A, lda, (const bf16 *)B, ldb, C, ldc,
                                                               bf16_epilogue(epi), s);
+}
+
+hipError_t launch_gemm_bf16_tt_group(const GemmProblem *problems, int n, int64_t K, const GemmEpi &epi, hipStream_t s)
+{
+    if (n < 1 || n > kGemmGroupMax || epi.bias || epi.resid || epi.aux || epi.out2 || epi.act != ACT_NONE)
+        return hipErrorInvalidValue;
+    GemmGroupBf16 g;
+    g.n = n;
+    int64_t tiles = 0;
+    for (int i = 0; i < n; ++i) {
+        const GemmProblem &q = problems[i];
+        if (!gemm_bf16_tt_supported(q.M, q.N, K, q.lda, q.ldb)) return hipErrorInvalidValue;
+        g.first[i] = (int)tiles;
+        g.p[i] = {q.M, q.N, (const bf16 *)q.A, (const bf16 *)q.B, q.C, q.lda, q.ldb, q.ldc, (int)(q.M / 256), (int)(q.N / 256)};
+        tiles += (q.M / 256) * (q.N / 256);
+        if (tiles >= (int64_t)1 << 31) return hipErrorInvalidValue;
+    }
+    for (int i = n; i <= kGemmGroupMax; ++i) g.first[i] = (int)tiles;
+    for (int i = n; i < kGemmGroupMax; ++i) g.p[i] = g.p[0];
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    auto kern = gemm_bf16_group_kernel<true, true, 256, 256, 2, 4, 2, true>;
+    constexpr size_t lds = gemm_lds_bytes<256, 256, 2, 4, 2>();
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    kern<<<dim3((unsigned)tiles), 512, lds, s>>>(g, K, bf16_epilogue(epi));
+    return hipGetLastError();
 }
 
 bool gemm_bf16_nn_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb)

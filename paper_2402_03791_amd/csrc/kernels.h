@@ -154,6 +154,20 @@ hipError_t launch_gemm_bf16_nt(int64_t M, int64_t N, int64_t K, const void *A, i
 bool gemm_bf16_tt_supported(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb);
 hipError_t launch_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
                                int64_t ldb, void *C, int64_t ldc, const GemmEpi &epi, hipStream_t s);
+// Up to kGemmGroupMax K-major products with the same K and the same plain fp32 epilogue (write, or add into C
+// in place) as one launch; each must be a shape gemm_bf16_tt_supported accepts.  Every C element is computed
+// exactly as launch_gemm_bf16_tt computes it.
+constexpr int kGemmGroupMax = 8;
+struct GemmProblem {
+    int64_t M, N;
+    const void *A;
+    int64_t lda;
+    const void *B;
+    int64_t ldb;
+    void *C;
+    int64_t ldc;
+};
+hipError_t launch_gemm_bf16_tt_group(const GemmProblem *problems, int n, int64_t K, const GemmEpi &epi, hipStream_t s);
 // The same product with A K-contiguous ([M, K], row stride lda) and B stored [K, N] (row stride ldb): the
 // input-gradient product read from the weights as stored.  Only for shapes gemm_bf16_nn_supported accepts
 // (N a multiple of 256, K of 64).

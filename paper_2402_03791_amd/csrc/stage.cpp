@@ -211,6 +211,9 @@ struct zpp_stage {
     // when the call accumulates in place (stage_backward_accumulate), its place in G.
     bool acc_in_place = false;
     float acc_scale = 1.0f;
+    // weight-gradient products of the block in hand that wait for one launch together (K-major kernel only)
+    std::vector<GemmProblem> dw_batch;
+    double dw_batch_flops = 0.0, dw_batch_bytes = 0.0;
     float *Sp(int blk, const char *nm) const
     {
         return (acc_in_place ? G : (float *)(ws + rS.off)) + off(blk, nm);
@@ -450,6 +453,30 @@ hipError_t linear_dx(zpp_stage *s, const void *dy, int blk, const char *w, int64
 
 // Weight gradient (Section 2.3): dW[out,in] = dy[T,out]^T . x[T,in]  (fp32, into the staging buffer),
 // and optionally db[out] = column sums of dy.
+// The K-major weight-gradient products collected since the last flush, as one launch.  Their operands (the
+// block's stash slots and gradient buffers) must still hold what they held when linear_dw saw them: the callers
+// flush before they leave a block.
+hipError_t flush_dw_batch(zpp_stage *s, hipStream_t st)
+{
+    if (s->dw_batch.empty()) return hipSuccess;
+    GemmEpi epi;
+    epi.out_f32 = s->acc_in_place ? 2 : 1;
+    epi.accum_scale = s->acc_scale;
+    hipError_t e;
+    {
+        ProfScope prof(ZPP_PROF_GEMM_DW, s->dw_batch_flops, st, s->dw_batch_bytes);
+        if (s->dw_batch.size() == 1) {
+            const GemmProblem &q = s->dw_batch[0];
+            e = launch_gemm_bf16_tt(q.M, q.N, s->Tc, q.A, q.lda, q.B, q.ldb, q.C, q.ldc, epi, st);
+        } else {
+            e = launch_gemm_bf16_tt_group(s->dw_batch.data(), (int)s->dw_batch.size(), s->Tc, epi, st);
+        }
+    }
+    s->dw_batch.clear();
+    s->dw_batch_flops = s->dw_batch_bytes = 0.0;
+    return e;
+}
+
 hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const char *w, const char *bias,
                      int64_t in, int64_t out, hipStream_t st)
 {
@@ -471,9 +498,12 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
                                      nullptr, slot, st, s->defer());
                 if (e != hipSuccess) return e;
             }
-            ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * s->Tc * in * out, st,
-                           2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out);
-            return launch_gemm_bf16_tt(out, in, s->Tc, dy, out, x, in, s->Sp(blk, w), in, epi, st);
+            // the product itself waits for the other products of its block: they go out as one grid
+            s->dw_batch.push_back({out, in, dy, out, x, in, s->Sp(blk, w), in});
+            s->dw_batch_flops += 2.0 * s->Tc * in * out;
+            s->dw_batch_bytes += 2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out;
+            if ((int)s->dw_batch.size() == kGemmGroupMax) return flush_dw_batch(s, st);
+            return hipSuccess;
         }
         void *tA = s->tp("tA"), *tB = s->tp("tB");
         {
@@ -969,6 +999,8 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int32_t count, int tasks,
     s->finish.clear();
     s->acc_in_place = in_place;
     s->acc_scale = scale;
+    s->dw_batch.clear();  // (left over only if an earlier call failed half-way)
+    s->dw_batch_flops = s->dw_batch_bytes = 0.0;
     zpp_stage::InputTask *rec = nullptr;
     if (do_in && split) {
         s->input_tasks.push_back({mb, count, {}});
@@ -1071,6 +1103,7 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int32_t count, int tasks,
         } else {
             parked(1, g1, "ln1.beta");
         }
+        if (do_w) ZPP_TRY(flush_dw_batch(s, st));
         dcur = dout;
     }
     // second level of every column reduction of this call, in one launch
@@ -1400,6 +1433,31 @@ zpp_status zpp_op_gemm_bf16_tt(int64_t M, int64_t N, int64_t K, const void *A, i
     GemmEpi e;
     e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
     hipError_t err = launch_gemm_bf16_tt(M, N, K, A, lda, B, ldb, C, ldc, e, (hipStream_t)hip_stream);
+    if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
+    return ZPP_OK;
+}
+
+zpp_status zpp_op_gemm_bf16_tt_group(int32_t n, const int64_t *M, const int64_t *N, int64_t K, const void *const *A,
+                                     const int64_t *lda, const void *const *B, const int64_t *ldb, void *const *C,
+                                     const int64_t *ldc, int32_t out_f32, void *hip_stream)
+{
+    if (n < 1 || n > kGemmGroupMax) return fail(ZPP_ERR_ARG, "a group holds 1..%d products", kGemmGroupMax);
+    if (!M || !N || !A || !lda || !B || !ldb || !C || !ldc) return fail(ZPP_ERR_ARG, "an argument array is NULL");
+    GemmProblem q[kGemmGroupMax];
+    for (int i = 0; i < n; ++i) {
+        if (!A[i] || !B[i] || !C[i]) return fail(ZPP_ERR_ARG, "A/B/C of product %d is NULL", i);
+        if (M[i] <= 0 || N[i] <= 0 || K <= 0 || lda[i] < M[i] || ldb[i] < N[i] || ldc[i] < N[i])
+            return fail(ZPP_ERR_ARG, "bad sizes in product %d", i);
+        if (!gemm_bf16_tt_supported(M[i], N[i], K, lda[i], ldb[i]))
+            return fail(ZPP_ERR_UNSUPPORTED, "product %d: need M, N multiples of 256, K a multiple of 64, lda/ldb "
+                                             "multiples of 8", i);
+        if (((uintptr_t)A[i] | (uintptr_t)B[i] | (uintptr_t)C[i]) % 16)
+            return fail(ZPP_ERR_ALIGN, "16-byte alignment required (product %d)", i);
+        q[i] = {M[i], N[i], A[i], lda[i], B[i], ldb[i], C[i], ldc[i]};
+    }
+    GemmEpi e;
+    e.out_f32 = out_f32 == 2 ? 2 : (out_f32 != 0);
+    hipError_t err = launch_gemm_bf16_tt_group(q, n, K, e, (hipStream_t)hip_stream);
     if (err != hipSuccess) return fail(ZPP_ERR_DEVICE, "gemm launch: %s", hipGetErrorString(err));
     return ZPP_OK;
 }

@@ -807,6 +807,45 @@ def test_gemm_bf16_tt_against_oracle(M, N, K):
     assert e.value.status == -6
 
 
+@pytest.mark.parametrize("shapes,K", [(((256, 256),), 128),
+                                      (((768, 256), (256, 256), (1024, 256), (256, 1024)), 512),
+                                      # 75 + 25 + 270 + 135 tiles: one product ends and the next begins inside a
+                                      # round of one tile per CU, three times; no product's tile count is a multiple of 8
+                                      (((3840, 1280), (1280, 1280), (6912, 2560), (1280, 6912)), 192),
+                                      (((512, 256),) * 8, 64)])
+def test_gemm_bf16_tt_group_equals_the_single_products(shapes, K):
+    """Several K-major products as one grid: the first against the oracle, all of them bit for bit against one
+    launch per product (written, accumulated, bf16 output), operands with their own leading dimensions."""
+    print(f"gemm tt group {shapes} K={K}", flush=True)
+    As, Bs = [], []
+    for i, (M, N) in enumerate(shapes):
+        Aw = torch.zeros(K, M + 8 * (i + 1), dtype=torch.bfloat16, device="cuda")
+        Bw = torch.zeros(K, N + 64, dtype=torch.bfloat16, device="cuda")
+        Aw[:, :M] = to_dev(synth.normal_f32(6, 90 + i, K * M, bf16_exact=True).reshape(K, M), torch.bfloat16)
+        Bw[:, 64:] = to_dev(synth.normal_f32(6, 190 + i, K * N, bf16_exact=True).reshape(K, N), torch.bfloat16)
+        As.append(Aw[:, :M])
+        Bs.append(Bw[:, 64:])
+    for dtype in (torch.float32, torch.bfloat16):
+        Cs = [torch.full((M, N), 7.0, dtype=dtype, device="cuda") for M, N in shapes]
+        zpp.op_gemm_bf16_tt_group(As, Bs, Cs)
+        for A, B, C in zip(As, Bs, Cs):
+            assert torch.equal(C, zpp.op_gemm_bf16_tt(A, B, torch.empty_like(C)))
+    M0, N0 = shapes[0]
+    ref, _ = oracle.Ops("f64").linear_bwd_weight(to_np(As[0]), to_np(Bs[0]))
+    assert rel_err(to_np(Cs[0]), ref) <= 8e-3
+    G0 = [torch.from_numpy(synth.normal_f32(6, 290 + i, M * N).reshape(M, N)).cuda() for i, (M, N) in enumerate(shapes)]
+    G = [g.clone() for g in G0]
+    zpp.op_gemm_bf16_tt_group(As, Bs, G, accumulate=True)
+    for A, B, g, g0 in zip(As, Bs, G, G0):
+        assert torch.equal(g, zpp.op_gemm_bf16_tt(A, B, g0.clone(), accumulate=True))
+    with pytest.raises(zpp.ZppError) as e:      # a product the K-major kernel does not take refuses the whole group
+        zpp.op_gemm_bf16_tt_group(As[:1] + [As[0][:, :128]], Bs[:1] + Bs[:1], [G[0], G[0][:128]])
+    assert e.value.status == -6
+    with pytest.raises(zpp.ZppError) as e:
+        zpp.op_gemm_bf16_tt_group(As[:1] * 9, Bs[:1] * 9, G[:1] * 9)
+    assert e.value.status == -1
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (200, 512, 192), (1000, 256, 1024), (2048, 1024, 512),
                                    (4096, 4096, 256)])
 def test_gemm_bf16_nn_against_oracle(M, N, K):
