@@ -10,11 +10,9 @@
 // column.  The softmax never leaves registers; only O and the log-sum-exp are written.
 //
 // Work-group shapes.  Forward and dQ: four waves, each taking every tile of its 32 rows, two stages of one tile
-// pair in LDS (64 KB), two work-groups per CU (all dQ launches, forward launches of more than two work-groups per
-// CU); forward launches of at most two work-groups per CU: eight waves, the two waves of a SIMD (w and w+4) sharing
-// a group of 32 queries and splitting its key tiles even / odd, merged at the end, one work-group per CU (the
-// shorter chain of intervals per work-group wins).  dK/dV: four waves, one per SIMD, with all 512 registers each
-// and four stages of tiles in LDS; see the kernel.
+// pair in LDS (64 KB), two work-groups per CU.  dK/dV: four waves, one per SIMD, with all 512 registers each
+// and four stages of tiles in LDS; see the kernel.  Every kernel serves every launch size: what a launch computes
+// for a sample does not depend on how many samples it holds.
 //
 // Backward: two launches without atomics.  dQ: lane = query, loops over key tiles.  dK and dV: lane = key,
 // loop over query tiles.  P is recomputed from the saved log-sum-exp; delta = rowsum(dO o O) and the
@@ -158,12 +156,9 @@ static int chunk_slots(int64_t nblk, int64_t nv)
     return (nv % 8 == 0 && nv > c) ? (int)c : 0;
 }
 
-// LDS holds two pairs of streamed tiles: a pair is copied in while the other is worked on.
-constexpr int kStages = 4;
-
 // depth of the register rings that carry LDS operands to the matrix instructions of the backward kernels
 // (what fits beside the accumulators at two waves per SIMD)
-constexpr int kRingDq = 4, kRingDkv = 3;
+constexpr int kRingDq = 4;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -260,167 +255,13 @@ __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[4], float
 }
 
 // ------------------------------------------------------------------------------------ forward
-// Eight waves on 128 consecutive queries: waves w and w+4 (the two waves of a SIMD) own the same group of
-// 32 queries and split its key tiles between them, wave w the even tiles, wave w+4 the odd ones, each with
-// its own running maximum, row sum and output accumulator; at the end the second wave hands its three
-// through LDS to the first, which merges them (the usual rescale by 2^(m_i - m)).  Key tiles are streamed
-// in pairs, one barrier per pair, so in every interval both waves of a SIMD have a tile to work on and
-// the SIMD interleaves the matrix phase of one with the softmax phase of the other; with one wave per
-// query group the early (short) group of a SIMD leaves the late one running alone for most of the kernel.
-// Work-groups are as heavy as their position in the sequence; the heavy ones are dispatched first.
-__global__ __launch_bounds__(512, 2) void attn_fwd_split_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
-                                                                float *__restrict__ lse, int seq, int nh, int nb,
-                                                                int chunk, float scale_log2e)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 pairs][2 tiles][K tile | V tile]
-    int qb, n, bi;
-    decode_heavy_first(blockIdx.x, seq / 128, nh, nb, chunk, qb, n, bi);
-    const int64_t h = (int64_t)nh * kD, ld = 3 * h;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = wave >> 2, grp = wave & 3;
-    const int g = lane >> 5, c = lane & 31;
-    const int qw0 = 128 * qb + 32 * grp;
-    const int64_t row0 = (int64_t)bi * seq;
-
-    bf16x8 qf[8];
-    {
-        const bf16 *qp = qkv + (row0 + qw0 + c) * ld + (int64_t)n * kD + 8 * g;
-#pragma unroll
-        for (int st = 0; st < 8; ++st) qf[st] = *reinterpret_cast<const bf16x8 *>(qp + 16 * st);
-    }
-    TileCopy<8> cp;
-    cp.init(lane, wave, ld);
-    TileAddr ad;
-    ad.init(lane);
-    const char *kbase = reinterpret_cast<const char *>(qkv + row0 * ld + h + (int64_t)n * kD);
-    const char *vbase = kbase + h * 2;
-    const int64_t tile_stride = (int64_t)kTile * ld * 2;
-    const uint32_t lds0 = lds_addr_of(smem);
-
-    f32x16 oacc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[t][e] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
-    const float lazy = 8.0f / scale_log2e;  // 2^8 in the exponent, in units of the raw scores
-
-    const int n_pairs = qb + 1;            // key tiles 2p, 2p+1 cover keys [128p, 128p + 128)
-    const int my_tiles = qw0 / kTile + 1;  // tiles with unmasked entries for this wave's queries
-    auto issue_pair = [&](int p) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const uint32_t dst = lds0 + ((p & 1) * 2 + t) * 2 * kTileBytes;
-            cp.issue(kbase + (2 * p + t) * tile_stride, dst, wave);
-            cp.issue(vbase + (2 * p + t) * tile_stride, dst + kTileBytes, wave);
-        }
-    };
-    issue_pair(0);
-#pragma unroll
-    for (int st = 0; st < 8; ++st) loaded_before_here(qf[st]);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-
-    for (int p = 0; p < n_pairs; ++p) {
-        if (p + 1 < n_pairs) issue_pair(p + 1);  // into the buffer read in the previous interval
-        const int jt = 2 * p + half;
-        if (jt < my_tiles) {
-            const int kv0 = jt * kTile;
-            const unsigned char *ks = smem + ((p & 1) * 2 + half) * 2 * kTileBytes;
-            const unsigned char *vs = ks + kTileBytes;
-            f32x16 sacc[2] = {};
-            // The 16 K operands come from LDS through a ring of four registers, each requested four MFMAs ahead
-            // of its use and the order pinned (left to itself the compiler reads every operand into the same
-            // register right before its MFMA and the matrix pipe waits out a whole LDS round trip each time).
-            bf16x8 kr[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) kr[i] = rd_row(ks, ad, 0, i);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                sacc[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[i & 3], qf[i & 7], sacc[i >> 3], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i + 4 < 16) {
-                    kr[i & 3] = rd_row(ks, ad, (i + 4) >> 3, (i + 4) & 7);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            // the first V operands travel while the softmax is computed
-            bf16x8 vr[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) vr[i] = rd_tr(vs, ad, i & 3, i >> 2);
-            __builtin_amdgcn_sched_barrier(0);
-            // sacc[T][e] of this lane: key kv0 + 32T + 8(e/4) + 4g + e%4, query qw0 + c; mask on the diagonal only
-            if (kv0 + kTile - 1 > qw0) {
-#pragma unroll
-                for (int T = 0; T < 2; ++T)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int kv = kv0 + 32 * T + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (kv > qw0 + c) sacc[T][e] = -INFINITY;
-                    }
-            }
-            bf16x8 pf[4];
-            online_softmax_step(sacc, m_run, l_run, oacc, pf, scale_log2e, lazy);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {  // i = 4 * st + t
-                oacc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[i & 3], pf[i >> 2], oacc[i & 3], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i + 4 < 16) {
-                    vr[i & 3] = rd_tr(vs, ad, (i + 4) & 3, (i + 4) >> 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    }
-
-    // merge the two halves of every query group: [64 accumulator values | m | l] x 64 lanes per group
-    float *mg = reinterpret_cast<float *>(smem) + grp * (66 * 64);
-    if (half == 1) {
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mg[(t * 16 + e) * 64 + lane] = oacc[t][e];
-        mg[64 * 64 + lane] = m_run;
-        mg[65 * 64 + lane] = l_run;
-    }
-    __syncthreads();
-    if (half == 1) return;
-    {
-        const float m_b = mg[64 * 64 + lane], l_b = mg[65 * 64 + lane];
-        const float m = fmaxf(m_run, m_b);  // this wave always had tile 0, so m is finite
-        const float a_a = fast_exp2((m_run - m) * scale_log2e), a_b = fast_exp2((m_b - m) * scale_log2e);
-        l_run = l_run * a_a + l_b * a_b;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[t][e] = oacc[t][e] * a_a + mg[(t * 16 + e) * 64 + lane] * a_b;
-        m_run = m;
-    }
-    const float l_tot = sum_with_lane32(l_run);
-    const float inv = 1.0f / l_tot;
-    bf16 *op = attn + (row0 + qw0 + c) * h + (int64_t)n * kD;
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-            bf16x4 o;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = (bf16)(oacc[t][e4 * 4 + r] * inv);
-            *reinterpret_cast<bf16x4 *>(op + 32 * t + 8 * e4 + 4 * g) = o;
-        }
-    if (g == 0)
-        lse[((int64_t)bi * nh + n) * seq + qw0 + c] =
-            (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
-}
-
-// The same with four waves per work-group: every wave takes all key tiles of its 32 queries (no split, no merge),
-// tiles streamed one by one through two stages of 32 KB, so two work-groups fit a CU and run out of step with
-// each other.  Used when the grid has more than two work-groups per CU.
+// Four waves on 128 consecutive queries: every wave takes all key tiles of its 32 queries, tiles streamed one by
+// one through two stages of 32 KB, so two work-groups fit a CU and run out of step with each other (one's matrix
+// phase against the other's softmax phase, one's prologue and epilogue behind the other's tiles).  Work-groups are
+// as heavy as their position in the sequence; the heavy ones are dispatched first.  One kernel for every launch
+// size, so that a sample's result does not depend on how many samples the launch holds (an eight-wave form whose
+// two waves per SIMD split a query group's key tiles and merged at the end was 5 % faster on launches of at most
+// two work-groups per CU, 54 against 57 us at 32 heads x 2048, and gave other bits).
 __global__ __launch_bounds__(256, 2) void attn_fwd_w4_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ attn,
                                                              float *__restrict__ lse, int seq, int nh, int nb,
                                                              int chunk, float scale_log2e)
@@ -992,23 +833,11 @@ hipError_t launch_attn_fwd(int dt, const void *qkv, void *attn, float *lse, int6
     const float scale_log2e = (1.0f / sqrtf((float)d)) * 1.44269504088896340736f;
     const unsigned blocks = (unsigned)(seq / 128 * nh * b);
     const int chunk = chunk_slots(seq / 128, nh * b);
-    // Up to two work-groups per CU's worth of work: the eight-wave kernel (a work-group's chain of intervals is
-    // half as long); beyond: the four-wave kernel, two work-groups per CU, where one's prologue and epilogue
-    // hide behind the other's tiles (measured at 32 heads x 2048: 54.0 against 57.0 us for 512 work-groups,
-    // 106.8 against 95.2 us for 1024).
-    if (blocks >= 768) {
-        constexpr size_t lds = 4 * kTileBytes;  // two stages of (K tile, V tile)
-        static bool done = false;
-        if (hipError_t e = set_lds(attn_fwd_w4_kernel, lds, done)) return e;
-        attn_fwd_w4_kernel<<<dim3(blocks), 256, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b,
-                                                          chunk, scale_log2e);
-    } else {
-        constexpr size_t lds = kStages * 2 * kTileBytes;  // two pairs of (K tile, V tile)
-        static bool done = false;
-        if (hipError_t e = set_lds(attn_fwd_split_kernel, lds, done)) return e;
-        attn_fwd_split_kernel<<<dim3(blocks), 512, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh,
-                                                             (int)b, 0, scale_log2e);
-    }
+    constexpr size_t lds = 4 * kTileBytes;  // two stages of (K tile, V tile)
+    static bool done = false;
+    if (hipError_t e = set_lds(attn_fwd_w4_kernel, lds, done)) return e;
+    attn_fwd_w4_kernel<<<dim3(blocks), 256, lds, s>>>((const bf16 *)qkv, (bf16 *)attn, lse, (int)seq, (int)nh, (int)b, chunk,
+                                                      scale_log2e);
     return hipGetLastError();
 }
 

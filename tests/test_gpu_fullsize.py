@@ -46,8 +46,21 @@ def _prefix_through_stage(st, slots, xs, dys, order, handoff=False):
     request, what the blocks handed to each other (block inputs going up, output gradients coming down)."""
     st.G.zero_()
     st.materialize_params()
+    if order == "calls of a group":  # what bench.py times: the forward and the input-gradient tasks of a group of
+        g, f = len(slots), slots[0]  # micro-batches as one call each, then one grouped weight-gradient task
+        assert list(slots) == list(range(f, f + g))
+        stack = lambda arrs: to_dev(np.concatenate(arrs, axis=0), st.act_dtype)
+        y = st.forward_group(f, g, stack(xs))
+        ys = list(y.view(g, -1, y.shape[-1]))
+        dx = st.backward_input_group(f, g, stack(dys))
+        dxs = list(dx.view(g, -1, dx.shape[-1]))
+        st.backward_weight_group(f, g, 1.0)
+        torch.cuda.synchronize()
+        out = dict(ys=[to_np(y) for y in ys], dxs=[to_np(d) for d in dxs], G=to_np(st.G))
+        st.end_unit()
+        return out
     ys = [st.forward(m, to_dev(x, st.act_dtype)) for m, x in zip(slots, xs)]
-    if order == "grouped":       # what bench.py times: input-gradient tasks, then one grouped weight-gradient task
+    if order == "grouped":       # input-gradient tasks one by one, then one grouped weight-gradient task
         dxs = [st.backward_input(m, to_dev(dy, st.act_dtype)) for m, dy in zip(slots, dys)]
         assert list(slots) == list(range(slots[0], slots[0] + len(slots)))
         st.backward_weight_group(slots[0], len(slots), 1.0)
@@ -112,9 +125,11 @@ def test_full_depth_prefix_of_the_unit(name, n_blocks, k, end_to_end_G, capsys):
     xs, dys = make_inputs(sh, k)
     _say(capsys, f"{sh.name}: {n_blocks} blocks, T={sh.tokens} h={sh.hidden} f={sh.ffn}, {k} of U={U} micro-batches")
     runs = {}
-    st = zpp.Stage(sh, split_backward=U)                 # as bench.py: group = the whole unit
+    st = zpp.Stage(sh, split_backward=U, group_mbs=max(k, 2))   # as bench.py: weight-gradient group = the whole unit
     st.P.copy_(torch.from_numpy(P0))
     _say(capsys, f"workspace {st.workspace_bytes / 2**30:.1f} GiB")
+    if k > 1:
+        runs["calls of a group, last slots"] = _prefix_through_stage(st, list(range(U - k, U)), xs, dys, "calls of a group")
     runs["grouped, first slots"] = _prefix_through_stage(st, list(range(k)), xs, dys, "grouped")
     runs["grouped, last slots"] = _prefix_through_stage(st, list(range(U - k, U)), xs, dys, "grouped",
                                                         handoff=not end_to_end_G)
@@ -133,6 +148,12 @@ def test_full_depth_prefix_of_the_unit(name, n_blocks, k, end_to_end_G, capsys):
     a, b = runs["grouped, first slots"], runs["grouped, last slots"]
     assert all(np.array_equal(p, q) for p, q in zip(a["ys"] + a["dxs"], b["ys"] + b["dxs"]))
     assert np.array_equal(a["G"].view(np.uint32), b["G"].view(np.uint32))
+    # the calls of a group do row by row what the one-micro-batch calls do (G: summation order of the column sums)
+    if k > 1:
+        c = runs["calls of a group, last slots"]
+        assert all(np.array_equal(p, q) for p, q in zip(b["ys"] + b["dxs"], c["ys"] + c["dxs"]))
+        for n_, off, r, cc in layout:
+            assert rel_err(c["G"][off:off + r * cc], b["G"][off:off + r * cc]) <= 1e-5, n_
     # and the five named calls differ from the grouped order by the summation order inside G only
     c = runs["five calls, last slots"]
     assert all(np.array_equal(p, q) for p, q in zip(b["ys"] + b["dxs"], c["ys"] + c["dxs"]))
@@ -147,6 +168,29 @@ def test_full_depth_prefix_of_the_unit(name, n_blocks, k, end_to_end_G, capsys):
     for tag, gpu in runs.items():
         worst, where = _compare(f"{sh.name} {tag}", layout, gpu, ref)
         _say(capsys, f"{tag}: worst rel err {worst:.2e} ({where})")
+
+
+def test_calls_of_four_micro_batches_at_the_llama_shape_equal_the_single_calls(capsys):
+    """bench.py runs the LLaMA-shaped stage four micro-batches per forward / input-gradient call (whole rounds of
+    256 x 256 tiles at T = 4096, h = 5120).  One block at full shape: y and dx of the group's calls equal the
+    one-micro-batch calls bit for bit and G up to the summation order of the column sums; the one-micro-batch
+    calls are the ones held to the oracle above."""
+    full = synth.CONFIGS["cfg4_llama_13b"]
+    sh = full.replace(n_blocks=1, name="cfg4_llama_13b_1blk")
+    g = 4
+    layout = oracle.param_layout(sh)
+    P0 = synth.make_params(sh, layout, gain_jitter=0.05)
+    xs, dys = make_inputs(sh, g)
+    st = zpp.Stage(sh, split_backward=sh.unit_mbs, group_mbs=g)
+    st.P.copy_(torch.from_numpy(P0))
+    a = _prefix_through_stage(st, list(range(g)), xs, dys, "grouped")
+    b = _prefix_through_stage(st, list(range(sh.unit_mbs - g, sh.unit_mbs)), xs, dys, "calls of a group")
+    st.close()
+    assert all(np.array_equal(p, q) for p, q in zip(a["ys"] + a["dxs"], b["ys"] + b["dxs"]))
+    worst = max(rel_err(b["G"][off:off + r * c], a["G"][off:off + r * c]) for _, off, r, c in layout)
+    _say(capsys, f"{sh.name}: calls of {g} micro-batches against single calls: y, dx equal, G worst rel diff {worst:.1e}")
+    assert worst <= 1e-5
+    assert all(np.isfinite(y).all() and np.abs(y).max() > 0 for y in b["ys"] + b["dxs"])
 
 
 @pytest.mark.parametrize("name", ["cfg2_gpt_1p3b", "cfg3_gpt_6p2b", "cfg4_llama_13b", "cfg5_wide_gpt"])

@@ -933,16 +933,18 @@ def test_mfma_attention_against_oracle(b, s, nh):
     for i, r in enumerate((dq, dk, dv)):
         assert rel_err(got[:, i * h:(i + 1) * h], merge(r)) <= 1.5e-2, i
 
-@pytest.mark.parametrize("b,bs,s,nh", [(6, 2, 2048, 32), (6, 2, 2048, 24), (10, 2, 1024, 48)])
+@pytest.mark.parametrize("b,bs,s,nh", [(6, 2, 2048, 32), (6, 1, 2048, 32), (6, 2, 2048, 24), (10, 2, 1024, 48),
+                                       (10, 1, 1024, 48)])
 def test_mfma_attention_one_launch_of_many_pairs_equals_smaller_launches(b, bs, s, nh):
-    """Launches with more (sample, head) pairs than a chunk walk their work-groups chunk by chunk (whole chunks, or a
-    shorter last one); which work-group computes what must not change any bit: the whole batch in one launch against
-    launches of `bs` samples, which have no more pairs than a chunk (the plain heavy-first order that the oracle
-    tests above cover) and enough work-groups to run the same forward kernel."""
-    print(f"attention mfma chunked b{b} s{s} nh{nh}", flush=True)
+    """What a launch computes for a sample does not depend on how many samples it holds.  Launches with more
+    (sample, head) pairs than a chunk walk their work-groups chunk by chunk (whole chunks, or a shorter last one);
+    which work-group computes what must not change any bit: the whole batch in one launch against launches of `bs`
+    samples, which have no more pairs than a chunk (the plain heavy-first order that the oracle tests above
+    cover)."""
+    print(f"attention mfma chunked b{b} bs{bs} s{s} nh{nh}", flush=True)
     d = 128
     h, T = nh * d, b * s
-    assert b % bs == 0 and (s // 128) * nh * bs >= 768 and nh * bs <= max(16, (1024 // (s // 128)) // 16 * 16) < nh * b
+    assert b % bs == 0 and nh * bs <= max(16, (1024 // (s // 128)) // 16 * 16) < nh * b
     g = torch.Generator(device="cuda").manual_seed(11)
     QKV = torch.randn(T, 3 * h, device="cuda", generator=g).to(torch.bfloat16)
     DA = (0.1 * torch.randn(T, h, device="cuda", generator=g)).to(torch.bfloat16)
