@@ -11,8 +11,36 @@ namespace zpp {
 
 constexpr int kRowsPerBlock = 4;  // 4 waves of 64 lanes
 
+// A lane's share of a row is the 16-byte vectors lane, lane + 64, ...  Rows of up to 64 * RV vectors (RV = 4, 8 or
+// 16: up to 8192 bf16 or 4096 fp32 elements) are read once and kept in registers; longer rows (RV = 0) are read
+// again in every pass.  Either way a lane visits its vectors in ascending order, so the sums are the same bits.
+// (Forward only: 20.6 -> 15.8 us per launch of 4096 rows x 4096.  The backward row part with its two operands
+// per row held the same way needs 185 registers, and the column part of the same launch then runs at two waves
+// per SIMD: 41.5 -> 53 us.)
+constexpr int kRowVecsMax = 16;
+static int row_vecs(int64_t nv)
+{
+    for (int rv = 4; rv <= kRowVecsMax; rv *= 2)
+        if (nv <= 64 * rv) return rv;
+    return 0;
+}
+
+template <int RV, class F>
+__device__ __forceinline__ void for_each_vec(int lane, int64_t nv, F f)
+{
+    if constexpr (RV > 0) {
+#pragma unroll
+        for (int i = 0; i < RV; ++i) {
+            const int64_t c = lane + 64 * i;
+            if (c < nv) f(i, c);
+        }
+    } else {
+        for (int64_t c = lane; c < nv; c += 64) f(0, c);
+    }
+}
+
 // ------------------------------------------------------------------ forward
-template <class T, int KIND>
+template <class T, int KIND, int RV>
 __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, const T *__restrict__ gamma,
                                                        const T *__restrict__ beta, int64_t rows, int64_t h,
                                                        float eps, T *__restrict__ n, float *__restrict__ mean,
@@ -24,33 +52,39 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
     if (row >= rows) return;
     const T *xr = x + row * h;
     const int64_t nv = h / VN;
+    Vec16<T> buf[RV > 0 ? RV : 1];
+    if constexpr (RV > 0) for_each_vec<RV>(lane, nv, [&](int i, int64_t c) { buf[i] = load16(xr + c * VN); });
+    auto xv = [&](int i, int64_t c) -> Vec16<T> {
+        if constexpr (RV > 0) return buf[i];
+        else return load16(xr + c * VN);
+    };
     float mu = 0.0f;
     if (KIND == NORM_LAYER) {
         float s = 0.0f;
-        for (int64_t c = lane; c < nv; c += 64) {
-            const Vec16<T> v = load16(xr + c * VN);
+        for_each_vec<RV>(lane, nv, [&](int i, int64_t c) {
+            const Vec16<T> v = xv(i, c);
 #pragma unroll
             for (int k = 0; k < VN; ++k) s += v.get(k);
-        }
+        });
         mu = wave_sum(s) / (float)h;
     }
     float q = 0.0f;
-    for (int64_t c = lane; c < nv; c += 64) {
-        const Vec16<T> v = load16(xr + c * VN);
+    for_each_vec<RV>(lane, nv, [&](int i, int64_t c) {
+        const Vec16<T> v = xv(i, c);
 #pragma unroll
         for (int k = 0; k < VN; ++k) {
             const float dlt = v.get(k) - mu;
             q += dlt * dlt;
         }
-    }
+    });
     const float var = wave_sum(q) / (float)h;
     const float rs = 1.0f / sqrtf(var + eps);
     if (lane == 0) {
         if (mean) mean[row] = mu;
         rstd[row] = rs;
     }
-    for (int64_t c = lane; c < nv; c += 64) {
-        const Vec16<T> v = load16(xr + c * VN);
+    for_each_vec<RV>(lane, nv, [&](int i, int64_t c) {
+        const Vec16<T> v = xv(i, c);
         const Vec16<T> g = load16(gamma + c * VN);
         Vec16<T> o;
         if (KIND == NORM_LAYER) {
@@ -63,7 +97,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(const T *__restrict__ x, 
         }
         store16(n + row * h + c * VN, o);
         if (xcopy) store16(xcopy + row * h + c * VN, v);
-    }
+    });
 }
 
 hipError_t launch_norm_fwd(int dt, int kind, const void *x, const void *gamma, const void *beta, int64_t T,
@@ -72,15 +106,24 @@ hipError_t launch_norm_fwd(int dt, int kind, const void *x, const void *gamma, c
 {
     if (T == 0) return hipSuccess;
     const dim3 grid((unsigned)((T + kRowsPerBlock - 1) / kRowsPerBlock));
-#define ZPP_LAUNCH(TT, KK)                                                                               \
-    norm_fwd_kernel<TT, KK><<<grid, 256, 0, s>>>((const TT *)x, (const TT *)gamma, (const TT *)beta, T, h, \
-                                                 eps, (TT *)n, mean, rstd, (TT *)xcopy)
+    const int rv = row_vecs(h / (dt == DT_BF16 ? 8 : 4));
+#define ZPP_LAUNCH2(TT, KK, RR)                                                                              \
+    norm_fwd_kernel<TT, KK, RR><<<grid, 256, 0, s>>>((const TT *)x, (const TT *)gamma, (const TT *)beta, T, h, \
+                                                     eps, (TT *)n, mean, rstd, (TT *)xcopy)
+#define ZPP_LAUNCH(TT, KK)                          \
+    do {                                            \
+        if (rv == 4) ZPP_LAUNCH2(TT, KK, 4);        \
+        else if (rv == 8) ZPP_LAUNCH2(TT, KK, 8);   \
+        else if (rv == 16) ZPP_LAUNCH2(TT, KK, 16); \
+        else ZPP_LAUNCH2(TT, KK, 0);                \
+    } while (0)
     if (dt == DT_BF16) {
         if (kind == NORM_LAYER) ZPP_LAUNCH(bf16, NORM_LAYER); else ZPP_LAUNCH(bf16, NORM_RMS);
     } else {
         if (kind == NORM_LAYER) ZPP_LAUNCH(float, NORM_LAYER); else ZPP_LAUNCH(float, NORM_RMS);
     }
 #undef ZPP_LAUNCH
+#undef ZPP_LAUNCH2
     return hipGetLastError();
 }
 
