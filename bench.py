@@ -2,8 +2,8 @@
 """Benchmark of the ZeroPP stage hot path on one MI355X.
 
 A step is one pass of the whole hot path over one scheduling unit of synthetic input:
-stage_materialize_params, the U forward tasks and then the U input-gradient tasks two micro-batches per call
-(stage_forward_group, stage_backward_input_group), the weight-gradient tasks of the unit as one grouped task
+stage_materialize_params, the U forward tasks and then the U input-gradient tasks a few micro-batches per call
+(stage_forward_group, stage_backward_input_group; two, or default_mb_group() of them), the weight-gradient tasks of the unit as one grouped task
 that adds into G (stage_backward_weight_group), shard_adam_step (with zero_grad), zpp_stage_end_unit.  Other
 orders of the same work: --mb-group g (micro-batches per forward / input-gradient call; 1 = the
 one-micro-batch calls), --group g (g micro-batches per weight-gradient task; 1 = one by one), --backward fused
