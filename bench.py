@@ -4,7 +4,8 @@
 A step is one pass of the whole hot path over one scheduling unit of synthetic input:
 stage_materialize_params, the U forward tasks and then the U input-gradient tasks a few micro-batches per call
 (stage_forward_group, stage_backward_input_group; two, or default_mb_group() of them), the weight-gradient tasks of the unit as one grouped task
-that adds into G (stage_backward_weight_group), shard_adam_step (with zero_grad), zpp_stage_end_unit.  Other
+that adds into G (stage_backward_weight_group), shard_adam_step (with zero_grad; --zero-grad release: G is
+released instead and the next unit's first addition into it writes), zpp_stage_end_unit.  Other
 orders of the same work: --mb-group g (micro-batches per forward / input-gradient call; 1 = the
 one-micro-batch calls), --group g (g micro-batches per weight-gradient task; 1 = one by one), --backward fused
 (stage_backward_accumulate), --accumulate separate (stage_backward + stage_accumulate_grads); y and dx are the
@@ -267,6 +268,10 @@ def main():
                     help="micro-batches per forward / input-gradient (or fused backward) call: stage_forward_group etc. "
                          "run every linear layer once over this many micro-batches; 0 = the fewest that give whole "
                          "rounds of 256 x 256 tiles (default_mb_group), one where the other options need one")
+    ap.add_argument("--zero-grad", choices=("zero", "release"), default="zero",
+                    help="what the Adam step does with G: zero it in the same pass (the pass the HBM figure of the "
+                         "metric is stated on), or release it (zpp_adam.zero_grad = 2: the next unit's first addition "
+                         "into G writes instead; 4 + 4 bytes per parameter less per step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large-shard", action="store_true",
                     help="skip the Adam / accumulate bandwidth leg on the wide configuration's 1.61e9-element shard")
@@ -294,6 +299,7 @@ def main():
                    "peak_bf16_TFLOPs_used": PEAK_BF16_TFLOPS, "peak_hbm_GBps_used": PEAK_HBM_GBS,
                    "peak_note": "vendor figures: 256 CUs x 2.4 GHz x 4096 bf16 flop/clk/CU = 2.52 PFLOP/s dense; HBM3E 8 TB/s"}
     V = args.stages
+    zg = 2 if args.zero_grad == "release" else 1
     args.recompute = {"none": 0, "full": 1, "selective": 2}[args.recompute]
     if args.recompute:
         args.backward = "fused"       # recomputation serves both gradient tasks of a block from one re-run
@@ -365,7 +371,7 @@ def main():
         if V > 1:
             st.forward_unit(x_list, y_list, stream, side)
             st.backward_unit(dy_list, dx_list, 1.0, stream, side)
-            st.adam_step(step=t, zero_grad=1, stream=stream, **adam)
+            st.adam_step(step=t, zero_grad=zg, stream=stream, **adam)
             st.end_unit()
             return
         st.materialize_params(stream)
@@ -398,9 +404,9 @@ def main():
                 st.backward(m, dys[m], dx, stream)
                 st.accumulate_grads(m, 1.0, stream)
         if args.adam == "decay_ranges":
-            st.adam_step_ranges(ranges, step=t, zero_grad=1, write_back=1, stream=stream, **adam)
+            st.adam_step_ranges(ranges, step=t, zero_grad=zg, write_back=1, stream=stream, **adam)
         else:
-            st.adam_step(step=t, zero_grad=1, write_back=1, stream=stream, **adam)
+            st.adam_step(step=t, zero_grad=zg, write_back=1, stream=stream, **adam)
         st.end_unit()
 
     ranges = st.decay_ranges(adam["lr"], adam["weight_decay"]) if args.adam == "decay_ranges" and V == 1 else None
@@ -499,7 +505,7 @@ def main():
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
     default_order = (V == 1 and args.backward == "split" and args.group == sh.unit_mbs and not args.recompute
                      and mg == default_mb_group(sh)
-                     and args.accumulate == "in_place" and args.adam == "uniform")
+                     and args.accumulate == "in_place" and args.adam == "uniform" and args.zero_grad == "zero")
     kv = profile_kv()
 
     def kind(c):
@@ -567,7 +573,7 @@ def main():
         "config": {"workload": sh.name, "arch": "gpt" if sh.arch == 0 else "llama", "n_blocks": sh.n_blocks,
                    "hidden": sh.hidden, "n_heads": sh.n_heads, "ffn": sh.ffn, "seq": sh.seq,
                    "micro_batch": sh.micro_batch, "unit_mbs": sh.unit_mbs, "params": st.N,
-                   "accumulate": args.accumulate, "backward": args.backward, "weight_task_group": args.group, "micro_batch_group": mg,
+                   "accumulate": args.accumulate, "backward": args.backward, "weight_task_group": args.group, "micro_batch_group": mg, "zero_grad": args.zero_grad,
                    "recompute": ["none", "full", "selective"][args.recompute],
                    "adam": args.adam, "stages_on_device": V, "prefetch": V > 1 and not args.no_prefetch,
                    "workspace_GB": round(st.workspace_bytes / 1e9, 2)},
@@ -595,7 +601,7 @@ def main():
             for m in range(sh.unit_mbs):
                 st2.backward(m, dys[m], dx, stream)
                 st2.accumulate_grads(m, 1.0, stream)
-            st2.adam_step(step=tt, zero_grad=1, stream=stream, **adam)
+            st2.adam_step(step=tt, zero_grad=zg, stream=stream, **adam)
             st2.end_unit()
 
         step5(1)

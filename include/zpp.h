@@ -103,7 +103,13 @@ typedef struct {
     float grad_scale;      /* ghat = grad_scale * G */
     int32_t step;          /* t >= 1, used for bias correction */
     int32_t decoupled_wd;  /* 1: p -= lr*wd*p_old (AdamW form).  0: ghat += wd*p (L2 form) */
-    int32_t zero_grad;     /* 1: G is zeroed in the same pass */
+    int32_t zero_grad;     /* 1: G is zeroed in the same pass.  2 (a step over the whole shard only): G is released
+                              instead - it counts as zero, its memory keeps the old gradients, and the first call
+                              that adds into G afterwards (stage_accumulate_grads, or a gradient task that
+                              accumulates in place) writes instead of adding: the same values as adding onto zeros
+                              (an exact zero may differ in sign) without the 4 bytes per element of the zeroing and
+                              the 4 of reading the zeros back.  Until then the contents of G mean nothing;
+                              zpp_stage_bind forgets the release. */
     int32_t write_back;    /* 1: the updated parameters are also written into the stage's working copy (the bf16
                               round-to-nearest-even cast, or the float copy), so that the next
                               stage_materialize_params need not read P again for it (when the call, or the

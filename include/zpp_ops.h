@@ -80,8 +80,9 @@ zpp_status zpp_op_attention_bwd_noalloc(int32_t dtype, int32_t impl, const void 
                                         const void *dattn, const float *lse, void *dqkv, int64_t b, int64_t seq,
                                         int64_t nh, int64_t d, void *hip_stream);
 
-/* The flat-buffer passes on raw arrays of n elements (16-byte aligned): the optimizer step, the
- * gradient accumulation G += scale*S, and the fp32 -> working-copy cast. */
+/* The flat-buffer passes on raw arrays of n elements (16-byte aligned): the optimizer step (zero_grad 0 or 1: there
+ * is no stage here that could hold a released G), the gradient accumulation G += scale*S, and the fp32 ->
+ * working-copy cast. */
 zpp_status zpp_op_flat_adam(float *P, float *M, float *V, float *G, uint64_t n, const zpp_adam *hp, void *hip_stream);
 zpp_status zpp_op_flat_accumulate(float *G, const float *S, uint64_t n, float scale, void *hip_stream);
 zpp_status zpp_op_flat_materialize(const float *P, void *W, uint64_t n, int32_t dtype, void *hip_stream);

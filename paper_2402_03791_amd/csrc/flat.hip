@@ -205,7 +205,9 @@ hipError_t launch_transpose_cast(const float *P, void *Wt, uint64_t rows, uint64
 }
 
 // ---------------------------------------------------------------- accumulate
-template <int VPT>
+// FIRST: G counts as zero and is not read (the first accumulation after an Adam step that released G instead of
+// zeroing it): G <- 0 + scale * S, the bits that adding onto zeros gives, for 8 instead of 12 bytes per element.
+template <int VPT, bool FIRST>
 __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ G, const float *__restrict__ S,
                                                          uint64_t n, float scale)
 {
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ G, 
     for (int u = 0; u < VPT; ++u) {
         const uint64_t i = base + u * 256;
         if (i < nvec) {
-            g[u] = nt_load(reinterpret_cast<const f32x4 *>(G) + i);
+            g[u] = FIRST ? f32x4{0.0f, 0.0f, 0.0f, 0.0f} : nt_load(reinterpret_cast<const f32x4 *>(G) + i);
             v[u] = nt_load(reinterpret_cast<const f32x4 *>(S) + i);
         }
     }
@@ -230,13 +232,32 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float *__restrict__ G, 
         }
     }
     if (blockIdx.x == 0)
-        for (uint64_t j = nvec * 4 + threadIdx.x; j < n; j += 256) G[j] = grad_accum(G[j], scale, S[j]);
+        for (uint64_t j = nvec * 4 + threadIdx.x; j < n; j += 256) G[j] = grad_accum(FIRST ? 0.0f : G[j], scale, S[j]);
 }
 
-hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s)
+hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s, bool first)
 {
     if (n == 0) return hipSuccess;
-    accumulate_kernel<4><<<flat_blocks(n / 4, 4), 256, 0, s>>>(G, S, n, scale);
+    if (first)
+        accumulate_kernel<4, true><<<flat_blocks(n / 4, 4), 256, 0, s>>>(G, S, n, scale);
+    else
+        accumulate_kernel<4, false><<<flat_blocks(n / 4, 4), 256, 0, s>>>(G, S, n, scale);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ G, uint64_t n)
+{
+    const uint64_t nvec = n / 4;
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < nvec) nt_store(f32x4{0.0f, 0.0f, 0.0f, 0.0f}, reinterpret_cast<f32x4 *>(G) + i);
+    if (blockIdx.x == 0)
+        for (uint64_t j = nvec * 4 + threadIdx.x; j < n; j += 256) G[j] = 0.0f;
+}
+
+hipError_t launch_fill_zero(float *G, uint64_t n, hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    fill_zero_kernel<<<flat_blocks(n / 4, 1), 256, 0, s>>>(G, n);
     return hipGetLastError();
 }
 

@@ -65,7 +65,9 @@ struct TransposeCastTable {
     int32_t n;
 };
 hipError_t launch_transpose_cast_many(const float *P, void *Wt, TransposeCastTable tab, hipStream_t s);
-hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s);
+// first: G counts as zero and is not read (G <- 0 + scale * S)
+hipError_t launch_accumulate(float *G, const float *S, uint64_t n, float scale, hipStream_t s, bool first = false);
+hipError_t launch_fill_zero(float *G, uint64_t n, hipStream_t s);
 hipError_t launch_adam(float *P, float *M, float *V, float *G, uint64_t n, const AdamArgs &a, hipStream_t s);
 
 // ---- norms ----

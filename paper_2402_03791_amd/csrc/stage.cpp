@@ -211,6 +211,11 @@ struct zpp_stage {
     // when the call accumulates in place (stage_backward_accumulate), its place in G.
     bool acc_in_place = false;
     float acc_scale = 1.0f;
+    // An Adam step with zero_grad = 2 releases G instead of zeroing it: G counts as zero although its memory still
+    // holds the old gradients, and the first task that adds into G afterwards writes instead (acc_write: the
+    // weight-gradient products store their result, the column reductions store their sums - with scale 1 the bits
+    // that adding onto zeros gives).
+    bool g_released = false, acc_write = false;
     // weight-gradient products of the block in hand that wait for one launch together (K-major kernel only)
     std::vector<GemmProblem> dw_batch;
     double dw_batch_flops = 0.0, dw_batch_bytes = 0.0;
@@ -460,7 +465,7 @@ hipError_t flush_dw_batch(zpp_stage *s, hipStream_t st)
 {
     if (s->dw_batch.empty()) return hipSuccess;
     GemmEpi epi;
-    epi.out_f32 = s->acc_in_place ? 2 : 1;
+    epi.out_f32 = s->acc_in_place && !s->acc_write ? 2 : 1;
     epi.accum_scale = s->acc_scale;
     hipError_t e;
     {
@@ -481,7 +486,7 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
                      int64_t in, int64_t out, hipStream_t st)
 {
     GemmEpi epi;
-    epi.out_f32 = s->acc_in_place ? 2 : 1;
+    epi.out_f32 = s->acc_in_place && !s->acc_write ? 2 : 1;
     epi.accum_scale = s->acc_scale;
     hipError_t e;
     if (s->dt == DT_BF16) {
@@ -501,7 +506,7 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
             // the product itself waits for the other products of its block: they go out as one grid
             s->dw_batch.push_back({out, in, dy, out, x, in, s->Sp(blk, w), in});
             s->dw_batch_flops += 2.0 * s->Tc * in * out;
-            s->dw_batch_bytes += 2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out;
+            s->dw_batch_bytes += 2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place && !s->acc_write ? 8.0 : 4.0) * in * out;
             if ((int)s->dw_batch.size() == kGemmGroupMax) return flush_dw_batch(s, st);
             return hipSuccess;
         }
@@ -526,7 +531,7 @@ hipError_t linear_dw(zpp_stage *s, const void *dy, const void *x, int blk, const
             }
         }
         ProfScope prof(ZPP_PROF_GEMM_DW, 2.0 * s->Tc * in * out, st,
-                       2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place ? 8.0 : 4.0) * in * out);
+                       2.0 * ((double)s->Tc * in + (double)s->Tc * out) + (s->acc_in_place && !s->acc_write ? 8.0 : 4.0) * in * out);
         e = launch_gemm_bf16_nt(out, in, s->Tc, tA, s->Tc, tB, s->Tc, s->Sp(blk, w), in, epi, st);
         return e;
     } else {
@@ -702,6 +707,7 @@ void attach(zpp_stage *s, float *P, float *G, float *M, float *V, void *base)
     s->materialized = false;
     s->rope_ready = false;
     s->w_fresh = false;
+    s->g_released = false;
     s->pending_acc = -1;
     s->mb_state.assign(s->U, MB_IDLE);
     s->input_tasks.clear();
@@ -999,6 +1005,16 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int32_t count, int tasks,
     s->finish.clear();
     s->acc_in_place = in_place;
     s->acc_scale = scale;
+    s->acc_write = false;
+    if (do_w && in_place && s->g_released) {
+        // first addition into a released G: write instead of add; a scale other than 1 takes the plain way
+        // (zero G, then add)
+        if (scale == 1.0f)
+            s->acc_write = true;
+        else
+            ZPP_OTHER(launch_fill_zero(s->G, s->N, st));
+        s->g_released = false;
+    }
     s->dw_batch.clear();  // (left over only if an earlier call failed half-way)
     s->dw_batch_flops = s->dw_batch_bytes = 0.0;
     zpp_stage::InputTask *rec = nullptr;
@@ -1108,12 +1124,13 @@ zpp_status backward_sequence(zpp_stage *s, int32_t mb, int32_t count, int tasks,
     }
     // second level of every column reduction of this call, in one launch
     if (do_w) {
-        ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st, in_place, scale));
+        ZPP_OTHER(launch_finish_columns(s->finish.data(), (int)s->finish.size(), st, in_place && !s->acc_write, scale));
         for (auto &items : more_finish)
             ZPP_OTHER(launch_finish_columns(items.data(), (int)items.size(), st, in_place, scale));
     }
     s->finish.clear();
     s->acc_in_place = false;
+    s->acc_write = false;
     if (!do_in)  // the parked records are used up (erase from the back so the indices stay valid)
         for (size_t i = parked_tasks.size(); i-- > 0;) s->input_tasks.erase(s->input_tasks.begin() + (long)parked_tasks[i]);
     for (int m = mb; m < mb + count; ++m) {
@@ -1173,8 +1190,10 @@ zpp_status stage_accumulate_grads(zpp_stage *s, int32_t mb, float scale, void *h
     if (s->mb_state[mb] != MB_BWD || s->pending_acc != mb)
         return fail(ZPP_ERR_STATE, "stage_accumulate_grads(%d) needs stage_backward(%d) right before it", mb, mb);
     {
-        ProfScope prof(ZPP_PROF_ACCUMULATE, 12.0 * s->N, (hipStream_t)hip_stream);
-        ZPP_TRY(launch_accumulate(s->G, (const float *)(s->ws + s->rS.off), s->N, scale, (hipStream_t)hip_stream));
+        ProfScope prof(ZPP_PROF_ACCUMULATE, (s->g_released ? 8.0 : 12.0) * s->N, (hipStream_t)hip_stream);
+        ZPP_TRY(launch_accumulate(s->G, (const float *)(s->ws + s->rS.off), s->N, scale, (hipStream_t)hip_stream,
+                                  s->g_released));
+        s->g_released = false;
     }
     s->mb_state[mb] = MB_ACC;
     s->pending_acc = -1;
@@ -1211,7 +1230,8 @@ zpp_status adam_args(zpp_stage *s, const zpp_adam *hp, AdamArgs *a)
     a->c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)hp->step));
     a->c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)hp->step));
     a->decoupled = hp->decoupled_wd ? 1 : 0;
-    a->zero_grad = hp->zero_grad ? 1 : 0;
+    if (hp->zero_grad < 0 || hp->zero_grad > 2) return fail(ZPP_ERR_ARG, "zero_grad must be 0, 1 or 2");
+    a->zero_grad = hp->zero_grad == 1 ? 1 : 0;
     a->wb = nullptr;
     a->wb_bf16 = s->dt == DT_BF16;
     if (hp->write_back) {
@@ -1234,6 +1254,8 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
                     (unsigned long long)count, (unsigned long long)s->N);
     if (offset % 4 || (count % 4 && offset + count != s->N))
         return fail(ZPP_ERR_ALIGN, "offset and count must be multiples of 4 elements");
+    if (hp->zero_grad == 2 && (offset != 0 || count != s->N))
+        return fail(ZPP_ERR_ARG, "zero_grad = 2 releases the whole of G: it needs the step over the whole shard");
     AdamArgs a;
     if (zpp_status e = adam_args(s, hp, &a)) return e;
     if (a.wb) a.wb = (unsigned char *)a.wb + offset * s->esz;  // the kernel indexes from `offset`
@@ -1249,6 +1271,7 @@ zpp_status shard_adam_step(zpp_stage *s, uint64_t offset, uint64_t count, const 
         // current copy); a step without write-back leaves it behind P
         s->w_fresh = a.wb && (s->w_fresh || (offset == 0 && count == s->N));
     }
+    if (hp->zero_grad == 2) s->g_released = true;
     return ZPP_OK;
 }
 
@@ -1268,6 +1291,8 @@ zpp_status shard_adam_step_ranges(zpp_stage *s, const zpp_adam_range *ranges, in
         end = r.offset + r.count;
         total += r.count;
     }
+    if (hp && hp->zero_grad == 2 && total != s->N)
+        return fail(ZPP_ERR_ARG, "zero_grad = 2 releases the whole of G: the ranges must cover the whole shard");
     AdamArgs a;
     if (zpp_status e = adam_args(s, hp, &a)) return e;
     ProfScope prof(ZPP_PROF_ADAM, ((a.zero_grad ? 32.0 : 28.0) + (a.wb ? (double)s->esz : 0.0)) * total,
@@ -1287,6 +1312,7 @@ zpp_status shard_adam_step_ranges(zpp_stage *s, const zpp_adam_range *ranges, in
         s->materialized = false;
         s->w_fresh = a.wb && (s->w_fresh || total == s->N);  // disjoint ranges of N elements cover the shard
     }
+    if (hp->zero_grad == 2) s->g_released = true;
     return ZPP_OK;
 }
 
@@ -1518,6 +1544,7 @@ zpp_status zpp_op_flat_adam(float *P, float *M, float *V, float *G, uint64_t n, 
     if (!P || !M || !V || !G || !hp) return fail(ZPP_ERR_ARG, "NULL pointer");
     if (((uintptr_t)P | (uintptr_t)M | (uintptr_t)V | (uintptr_t)G) % 16) return fail(ZPP_ERR_ALIGN, "16-byte alignment");
     if (hp->step < 1) return fail(ZPP_ERR_ARG, "step must be >= 1");
+    if (hp->zero_grad != 0 && hp->zero_grad != 1) return fail(ZPP_ERR_ARG, "zero_grad must be 0 or 1 here (no stage to hold a released G)");
     AdamArgs a;
     a.lr = hp->lr; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps; a.wd = hp->weight_decay;
     a.grad_scale = hp->grad_scale;

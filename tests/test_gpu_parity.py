@@ -539,6 +539,74 @@ def test_grouped_calls_equal_the_one_by_one_calls(arch, dtype, kw, g):
     st.close()
 
 
+@pytest.mark.parametrize("arch,dtype", [(0, 1), (1, 1), (0, 0)])
+@pytest.mark.parametrize("order,scale", [("group", 1.0), ("group", 0.5), ("fused", 1.0), ("five", 1.0), ("five", 0.25)])
+def test_released_gradient_buffer_gives_what_zeroing_gives(arch, dtype, order, scale):
+    """Adam with zero_grad = 2 leaves the old gradients in G and the stage treats G as zero: the first call that
+    adds into G afterwards writes instead.  Two units in a row, the Adam step between them zeroing G or releasing
+    it: the second unit's G and the parameters after a second step are equal (as values: an exact zero may differ
+    in sign), in every order of the work and with a scale other than 1."""
+    sh = small(arch, dtype, unit_mbs=4)
+    print(f"released G {sh.name} {order} scale {scale}", flush=True)
+    U = sh.unit_mbs
+    layout = oracle.param_layout(sh)
+    P0 = torch.from_numpy(synth.make_params(sh, layout, gain_jitter=0.1))
+    xs, dys = make_inputs(sh, U)
+
+    def unit(st):
+        st.materialize_params()
+        xd = [to_dev(x, st.act_dtype) for x in xs]
+        dyd = [to_dev(d, st.act_dtype) for d in dys]
+        if order == "group":
+            for f in range(0, U, 2):
+                st.forward_group(f, 2, torch.cat(xd[f:f + 2]))
+            for f in range(0, U, 2):
+                st.backward_input_group(f, 2, torch.cat(dyd[f:f + 2]))
+            st.backward_weight_group(0, 2, scale)
+            st.backward_weight_group(2, 2, scale)
+        else:
+            for m in range(U):
+                st.forward(m, xd[m])
+            for m in range(U):
+                if order == "fused":
+                    st.backward_accumulate(m, dyd[m], scale=scale)
+                else:
+                    st.backward(m, dyd[m])
+                    st.accumulate_grads(m, scale)
+        st.end_unit()
+
+    res = {}
+    for zg in (1, 2):
+        st = zpp.Stage(sh, split_backward=2 if order == "group" else 0, group_mbs=2)
+        st.P.copy_(P0)
+        st.G.zero_()
+        unit(st)
+        g1 = st.G.clone()
+        st.adam_step(step=1, zero_grad=zg, write_back=1, **synth.ADAM)
+        if zg == 1:
+            assert float(st.G.abs().max()) == 0.0
+        else:
+            assert torch.equal(st.G, g1)          # nothing was written: the release is bookkeeping
+        unit(st)
+        g2 = st.G.clone()
+        st.adam_step(step=2, zero_grad=zg, write_back=1, **synth.ADAM)
+        torch.cuda.synchronize()
+        res[zg] = (g2, st.P.clone(), st.M.clone(), st.V.clone())
+        st.close()
+    for a, b in zip(res[1], res[2]):
+        assert bool(torch.isfinite(a).all()) and float(a.abs().max()) > 0
+        assert torch.equal(a, b)
+    # a release needs the whole shard, and only a stage can hold it
+    st = zpp.Stage(sh)
+    with pytest.raises(zpp.ZppError) as e:
+        st.adam_step(offset=0, count=st.N - 4, step=1, zero_grad=2, **synth.ADAM)
+    assert e.value.status == -1
+    with pytest.raises(zpp.ZppError) as e:
+        st.adam_step(step=1, zero_grad=3, **synth.ADAM)
+    assert e.value.status == -1
+    st.close()
+
+
 def test_device_recomputes_every_stage_but_the_last():
     """Section 3.3: the stages mapped to a device recompute (one rebuild serves their two back-to-back gradient
     tasks) except the last one, whose tasks are scheduled apart and which keeps its activations.  Same kernels

@@ -108,7 +108,11 @@ def test_state_machine_and_argument_errors_without_launch():
         assert e.value.status == status, zpp.lib().zpp_last_error()
     a = binding._adam_struct(**synth.ADAM)
     for off, cnt, hp, status in ((0, st.N + 4, a, -1), (2, 8, a, -3), (0, 6, a, -3),
-                                 (0, 8, binding._adam_struct(step=0, **synth.ADAM), -1), (0, 8, None, -1)):
+                                 (0, 8, binding._adam_struct(step=0, **synth.ADAM), -1), (0, 8, None, -1),
+                                 # releasing G (zero_grad = 2) needs the step over the whole shard
+                                 (0, 8, binding._adam_struct(zero_grad=2, **synth.ADAM), -1),
+                                 (4, st.N - 4, binding._adam_struct(zero_grad=2, **synth.ADAM), -1),
+                                 (0, 8, binding._adam_struct(zero_grad=3, **synth.ADAM), -1)):
         with pytest.raises(zpp.ZppError) as e:
             binding._check(L.shard_adam_step(st._h, off, cnt, ctypes.byref(hp) if hp else None, None))
         assert e.value.status == status
@@ -276,6 +280,7 @@ def test_decay_ranges_cover_the_shard_and_ranged_adam_checks_its_arguments():
     assert status([(2, 8, 1e-3, 0.0)]) == -3
     assert status([(0, 6, 1e-3, 0.0)]) == -3
     assert status([(0, 8, 1e-3, 0.0)], None) == -1
+    assert status([(0, 8, 1e-3, 0.0)], binding._adam_struct(zero_grad=2, **synth.ADAM)) == -1   # a release covers the shard
     assert status([]) == 0                                               # nothing to do, nothing launched
     st.close()
 
