@@ -607,6 +607,49 @@ def test_released_gradient_buffer_gives_what_zeroing_gives(arch, dtype, order, s
     st.close()
 
 
+@pytest.mark.parametrize("grp", [0, 2])
+def test_device_with_released_gradient_buffers(grp):
+    """Every stage of a device holds its own release: two units through V = 2 stages with the Adam step between
+    them zeroing or releasing G give the same gradients and parameters (scale 1: the in-place tasks of the
+    second unit write)."""
+    sh = small(0, 1, n_blocks=1, unit_mbs=4)
+    U, V = sh.unit_mbs, 2
+    sh_all = sh.replace(n_blocks=V)
+    print(f"device released G grp={grp}", flush=True)
+    P0 = torch.from_numpy(synth.make_params(sh_all, oracle.param_layout(sh_all), gain_jitter=0.1))
+    xs, dys = make_inputs(sh, U)
+    res = {}
+    for zg in (1, 2):
+        dev = zpp.Device(sh, V, prefetch=True, split_backward=grp)
+        dev.P.copy_(P0)
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        x_in = [to_dev(xs[m], dev.act_dtype) for m in range(U)]
+        dy_in = [to_dev(dys[m], dev.act_dtype) for m in range(U)]
+        mid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        gmid = [[torch.empty_like(x_in[0]) for _ in range(U)] for _ in range(V)]
+        x_list = [(x_in[m] if v == 0 else mid[v - 1][m]) for v in range(V) for m in range(U)]
+        y_list = [mid[v][m] for v in range(V) for m in range(U)]
+        dy_list = [(dy_in[m] if v == V - 1 else gmid[v + 1][m]) for v in range(V) for m in range(U)]
+        dx_list = [gmid[v][m] for v in range(V) for m in range(U)]
+        out = []
+        for unit in range(2):
+            dev.forward_unit(x_list, y_list, main, side)
+            dev.backward_unit(dy_list, dx_list, 1.0, main, side)
+            torch.cuda.synchronize()
+            out.append(dev.G.clone())
+            dev.adam_step(step=unit + 1, zero_grad=zg, **synth.ADAM)
+            dev.end_unit()
+            torch.cuda.synchronize()
+            out.append(dev.P.clone())
+            if unit == 0 and zg == 2:
+                assert torch.equal(dev.G, out[0])      # released, not written
+        res[zg] = out
+        dev.close()
+    for a, b in zip(res[1], res[2]):
+        assert bool(torch.isfinite(a).all()) and float(a.abs().max()) > 0
+        assert torch.equal(a, b)
+
+
 def test_device_recomputes_every_stage_but_the_last():
     """Section 3.3: the stages mapped to a device recompute (one rebuild serves their two back-to-back gradient
     tasks) except the last one, whose tasks are scheduled apart and which keeps its activations.  Same kernels
